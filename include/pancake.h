@@ -1,0 +1,183 @@
+/*
+ * libpancake -- C ABI of the MI355X (gfx950) IVF search / insert hot path.
+ *
+ * What is computed (paper sections, restated):
+ *   Section 2.2   An IVF index partitions vectors into clusters ("lists").  A query
+ *                 ranks the clusters by the distance between their centroids and
+ *                 itself (coarse search), keeps the best `nprobe`, and searches those
+ *                 clusters vector by vector (fine search), returning the best `k`.
+ *   Section 3.1 / Section 6.1 ("IVF-Static")
+ *                 A new vector is appended to the cluster of its nearest centroid;
+ *                 centroids never move, nothing else is maintained.
+ *   Section 4.4   Vectors inserted after the build sit in a per-cluster buffer that is
+ *                 searched together with the cluster and the partial results merged;
+ *                 here the buffer is a chain of device-resident delta pages of the list.
+ *   Section 3.2 / Section 5
+ *                 One independent index per agent ("memory scope"); operations arrive
+ *                 in batches and must not block the caller: every call only enqueues
+ *                 work on the caller's HIP stream.
+ *
+ * Conventions
+ *   - Every pointer is marked HOST or DEVICE.  Device buffers belong to the caller
+ *     (including arenas); the library owns only the host-side handle and one
+ *     grow-only device workspace per handle that it allocates itself.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work
+ *     is enqueued on it; outputs are valid once the caller has synchronised the stream.
+ *     Calls on one handle must come from one thread and one stream at a time; an
+ *     insert enqueued before a search on the same stream is seen by that search.
+ *     pk_index_build, pk_index_stats and pk_list_lengths synchronise the stream.
+ *   - One metric per index serves coarse ranking, build/insert assignment and fine
+ *     search.  PK_METRIC_L2 returns the SQUARED Euclidean distance.
+ *   - Result rows are sorted best first (inner product descending, L2 ascending); equal
+ *     values are ordered by ascending id; rows with fewer than k candidates are padded
+ *     with id -1 and -inf (IP) / +inf (L2).  Centroid ties go to the lower list number.
+ *   - Inputs must be finite.  Rows are float32, row-major, densely packed.
+ *   - Every function returns PK_OK (0) or a negative pk_status; nothing aborts, throws
+ *     or prints.  Argument checks happen on the host before anything is launched.
+ */
+#ifndef PANCAKE_H
+#define PANCAKE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pk_index pk_index; /* opaque per-agent handle (host object) */
+
+typedef enum { PK_METRIC_IP = 0, PK_METRIC_L2 = 1 } pk_metric;
+typedef enum { PK_F32 = 0, PK_F16 = 1 } pk_dtype; /* storage type of list vectors */
+
+typedef enum {
+    PK_OK = 0,
+    PK_ERR_INVALID_ARG = -1,  /* null pointer, size or parameter out of range         */
+    PK_ERR_BAD_HANDLE = -2,   /* not a live pk_index                                   */
+    PK_ERR_DIM_MISMATCH = -3, /* handles of one multi-agent call differ in d / metric  */
+    PK_ERR_NOMEM = -4,        /* arena (or host / workspace memory) exhausted          */
+    PK_ERR_HIP = -5,          /* a HIP runtime call failed                             */
+    PK_ERR_UNSUPPORTED = -6   /* valid request outside the limits below                */
+} pk_status;
+
+/* Limits (compile-time). */
+#define PK_MAX_K 1024        /* k per search                                          */
+#define PK_MAX_NPROBE 1024   /* nprobe per search (also <= nlist)                     */
+#define PK_MAX_HANDLES 128   /* handles per pk_search_multi call                      */
+#define PK_MAX_ARENAS 8      /* arenas per index                                      */
+#define PK_MAX_DIM 1536      /* vector dimension                                      */
+
+typedef struct {
+    int32_t d;               /* vector dimension, >= 1                                 */
+    int32_t nlist;           /* number of clusters / inverted lists, >= 1              */
+    int32_t metric;          /* pk_metric                                              */
+    int32_t storage;         /* pk_dtype: fp16 storage rounds to nearest even once     */
+    int32_t page_vecs;       /* vectors per page: multiple of 32 in [32, 1024]; 0 = 128 */
+    int32_t max_delta_pages; /* pages a list may grow by after the build; 0 = 1024     */
+} pk_config;
+
+typedef struct {
+    int64_t n_total;         /* vectors in the index (build + inserts)                 */
+    int64_t n_inserted;      /* vectors added by pk_insert                             */
+    int64_t pages_total;     /* pages available in all arenas                          */
+    int64_t pages_used;      /* pages handed to lists                                  */
+    int64_t arena_bytes;     /* sum of arena sizes                                     */
+    int64_t workspace_bytes; /* current size of the library-owned search workspace     */
+    int64_t max_list_len;    /* longest list                                           */
+    int32_t device_error;    /* sticky device-side flag: 0 ok, 1 out of pages, 2 list full, 4 work list overflow */
+    int32_t n_arenas;
+} pk_stats;
+
+/*
+ * Bytes of arena needed to build an index over n vectors and then insert
+ * n_insert_reserve more in the worst case (every list opening pages of its own).
+ * Returns 0 for an invalid config.
+ */
+size_t pk_arena_bytes(const pk_config *cfg, int64_t n, int64_t n_insert_reserve);
+
+/*
+ * Section 2.2 (index) + Section 3.1 (assignment rule).  Creates an index over
+ * `n` vectors: each goes to the list of its best centroid under cfg->metric (ties to the
+ * lower list number) and is stored list-major in pages carved from `arena`.
+ *   centroids  DEVICE [nlist, d] float32, copied into the arena
+ *   vectors    DEVICE [n, d] float32 (may be NULL when n == 0); not referenced after return
+ *   ids        DEVICE [n] int64, or NULL for 0 .. n-1
+ *   arena      DEVICE, 256-byte aligned, arena_bytes long; owned by the caller, must stay
+ *              allocated until pk_index_free
+ *   out        HOST, receives the handle
+ * Synchronises `stream` before returning.  PK_ERR_NOMEM if the arena is too small
+ * (pk_arena_bytes gives a sufficient size).
+ */
+int pk_index_build(const pk_config *cfg, const float *centroids, const float *vectors, const int64_t *ids,
+                   int64_t n, void *arena, size_t arena_bytes, void *stream, pk_index **out);
+
+/* Adds page space after PK_ERR_NOMEM.  arena: DEVICE, 256-byte aligned, caller-owned. */
+int pk_index_add_arena(pk_index *index, void *arena, size_t arena_bytes, void *stream);
+
+/*
+ * Section 3.1 / Section 6.1 "IVF-Static" insert + Section 4.4 insertion buffer.
+ * Each of the m vectors is assigned to its best centroid (same rule as the build) and
+ * appended to the tail page of that list, opening a delta page when the tail is full.
+ *   vectors         DEVICE [m, d] float32
+ *   ids             DEVICE [m] int64, or NULL to continue the running counter
+ *                   (n_total before the call, +1 per vector)
+ *   assigned_lists  DEVICE [m] int32, optional (NULL): receives the chosen lists
+ * Asynchronous.  PK_ERR_NOMEM if the arenas may not hold m more vectors (nothing is
+ * enqueued then).
+ */
+int pk_insert(pk_index *index, const float *vectors, const int64_t *ids, int64_t m, int32_t *assigned_lists,
+              void *stream);
+
+/* As pk_insert, with the lists given by the caller (DEVICE [m] int32, each in [0, nlist)). */
+int pk_insert_assigned(pk_index *index, const float *vectors, const int64_t *ids, int64_t m,
+                       const int32_t *lists, void *stream);
+
+/*
+ * Section 2.2 coarse + fine search for a batch of queries of one index.
+ *   queries   DEVICE [nq, d] float32
+ *   k         1 .. PK_MAX_K;  nprobe 1 .. min(nlist, PK_MAX_NPROBE)
+ *   out_ids   DEVICE [nq, k] int64;  out_dist DEVICE [nq, k] float32
+ * Asynchronous.
+ */
+int pk_search(pk_index *index, const float *queries, int64_t nq, int32_t k, int32_t nprobe, int64_t *out_ids,
+              float *out_dist, void *stream);
+
+/*
+ * Section 3.2 (independent per-agent indexes) + Section 5 (batched operations): queries
+ * addressed to many handles are served by one launch sequence.  Segment a = query rows
+ * [q_offsets[a], q_offsets[a+1]) is searched in handles[a]; results equal per-handle
+ * pk_search calls bit for bit.
+ *   handles    HOST [n_handles]; all share d, metric and storage; each at most once
+ *   q_offsets  HOST [n_handles + 1], non-decreasing, q_offsets[0] == 0
+ *   queries    DEVICE [q_offsets[n_handles], d];  outputs as in pk_search
+ */
+int pk_search_multi(pk_index *const *handles, int32_t n_handles, const int64_t *q_offsets, const float *queries,
+                    int32_t k, int32_t nprobe, int64_t *out_ids, float *out_dist, void *stream);
+
+/* Stage seams (tests isolate coarse and fine search with them). */
+
+/* Coarse search only: out_probes DEVICE [nq, nprobe] int32, best list first. */
+int pk_coarse(pk_index *index, const float *queries, int64_t nq, int32_t nprobe, int32_t *out_probes,
+              void *stream);
+
+/* Fine search over caller-given probe lists: probes DEVICE [nq, nprobe] int32, each row
+ * without repeats, every entry in [0, nlist). */
+int pk_scan_probes(pk_index *index, const float *queries, int64_t nq, int32_t k, int32_t nprobe,
+                   const int32_t *probes, int64_t *out_ids, float *out_dist, void *stream);
+
+/* Counters of the index; synchronises `stream`.  out: HOST. */
+int pk_index_stats(pk_index *index, pk_stats *out, void *stream);
+
+/* Current length of every list; synchronises `stream`.  out_len: HOST [nlist] int64. */
+int pk_list_lengths(pk_index *index, int64_t *out_len, void *stream);
+
+/* Frees the host object and the library-owned workspace (not the arenas).  The caller
+ * must have synchronised every stream that still uses the index. */
+int pk_index_free(pk_index *index);
+
+const char *pk_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PANCAKE_H */

@@ -1,0 +1,248 @@
+"""ctypes binding of libpancake.so: the C-ABI entry points under their own names.
+
+Argument marshalling only.  Every step of search / insert / build runs in the HIP
+kernels behind the C ABI; PyTorch is used for device memory (tensors own the
+buffers, including arenas) and for the current HIP stream.  There is no CPU
+fallback: if the library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libpancake.so")
+
+PK_METRIC_IP, PK_METRIC_L2 = 0, 1
+PK_F32, PK_F16 = 0, 1
+PK_OK = 0
+PK_ERR_INVALID_ARG, PK_ERR_BAD_HANDLE, PK_ERR_DIM_MISMATCH, PK_ERR_NOMEM, PK_ERR_HIP, PK_ERR_UNSUPPORTED = (
+    -1, -2, -3, -4, -5, -6)
+
+EXPORTS = ["pk_arena_bytes", "pk_index_build", "pk_index_add_arena", "pk_insert", "pk_insert_assigned", "pk_search",
+           "pk_search_multi", "pk_coarse", "pk_scan_probes", "pk_index_stats", "pk_list_lengths", "pk_index_free",
+           "pk_strerror"]
+
+
+class pk_config(C.Structure):
+    _fields_ = [("d", C.c_int32), ("nlist", C.c_int32), ("metric", C.c_int32), ("storage", C.c_int32),
+                ("page_vecs", C.c_int32), ("max_delta_pages", C.c_int32)]
+
+
+class pk_stats(C.Structure):
+    _fields_ = [("n_total", C.c_int64), ("n_inserted", C.c_int64), ("pages_total", C.c_int64),
+                ("pages_used", C.c_int64), ("arena_bytes", C.c_int64), ("workspace_bytes", C.c_int64),
+                ("max_list_len", C.c_int64), ("device_error", C.c_int32), ("n_arenas", C.c_int32)]
+
+
+class PancakeError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {strerror(status)} ({status})")
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it has not been built (python -m paper_2602_21477_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is missing: build it with `python -m paper_2602_21477_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+        L.pk_arena_bytes.restype = C.c_size_t
+        L.pk_arena_bytes.argtypes = [C.POINTER(pk_config), i64, i64]
+        L.pk_index_build.argtypes = [C.POINTER(pk_config), vp, vp, vp, i64, vp, C.c_size_t, vp, C.POINTER(vp)]
+        L.pk_index_add_arena.argtypes = [vp, vp, C.c_size_t, vp]
+        L.pk_insert.argtypes = [vp, vp, vp, i64, vp, vp]
+        L.pk_insert_assigned.argtypes = [vp, vp, vp, i64, vp, vp]
+        L.pk_search.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
+        L.pk_search_multi.argtypes = [C.POINTER(vp), i32, C.POINTER(i64), vp, i32, i32, vp, vp, vp]
+        L.pk_coarse.argtypes = [vp, vp, i64, i32, vp, vp]
+        L.pk_scan_probes.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp, vp]
+        L.pk_index_stats.argtypes = [vp, C.POINTER(pk_stats), vp]
+        L.pk_list_lengths.argtypes = [vp, vp, vp]
+        L.pk_index_free.argtypes = [vp]
+        L.pk_strerror.restype = C.c_char_p
+        L.pk_strerror.argtypes = [C.c_int]
+        for name in EXPORTS:
+            if name not in ("pk_arena_bytes", "pk_strerror"):
+                getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return lib().pk_strerror(int(status)).decode()
+
+
+def _check(status: int, what: str):
+    if status != PK_OK:
+        raise PancakeError(status, what)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t, dtype, what):
+    if t is None:
+        return None
+    if not (t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise ValueError(f"{what}: need a contiguous {dtype} CUDA tensor")
+    return t.data_ptr()
+
+
+def pk_arena_bytes(cfg: pk_config, n: int, n_insert_reserve: int) -> int:
+    return int(lib().pk_arena_bytes(C.byref(cfg), int(n), int(n_insert_reserve)))
+
+
+def pk_index_build(cfg: pk_config, centroids, vectors, ids, arena) -> int:
+    """Returns the handle (an integer).  `arena` is a uint8 CUDA tensor the caller keeps alive."""
+    n = 0 if vectors is None else vectors.shape[0]
+    h = C.c_void_p()
+    rc = lib().pk_index_build(C.byref(cfg), _dev(centroids, torch.float32, "centroids"),
+                              _dev(vectors, torch.float32, "vectors"), _dev(ids, torch.int64, "ids"), n,
+                              _dev(arena, torch.uint8, "arena"), arena.numel(), _stream(), C.byref(h))
+    _check(rc, "pk_index_build")
+    return h.value
+
+
+def pk_index_add_arena(handle: int, arena):
+    _check(lib().pk_index_add_arena(handle, _dev(arena, torch.uint8, "arena"), arena.numel(), _stream()),
+           "pk_index_add_arena")
+
+
+def pk_insert(handle: int, vectors, ids=None, assigned_lists=None):
+    _check(lib().pk_insert(handle, _dev(vectors, torch.float32, "vectors"), _dev(ids, torch.int64, "ids"),
+                           vectors.shape[0], _dev(assigned_lists, torch.int32, "assigned_lists"), _stream()),
+           "pk_insert")
+
+
+def pk_insert_assigned(handle: int, vectors, ids, lists):
+    _check(lib().pk_insert_assigned(handle, _dev(vectors, torch.float32, "vectors"), _dev(ids, torch.int64, "ids"),
+                                    vectors.shape[0], _dev(lists, torch.int32, "lists"), _stream()),
+           "pk_insert_assigned")
+
+
+def pk_search(handle: int, queries, k: int, nprobe: int, out_ids, out_dist):
+    _check(lib().pk_search(handle, _dev(queries, torch.float32, "queries"), queries.shape[0], k, nprobe,
+                           _dev(out_ids, torch.int64, "out_ids"), _dev(out_dist, torch.float32, "out_dist"),
+                           _stream()), "pk_search")
+
+
+def pk_search_multi(handles, q_offsets, queries, k: int, nprobe: int, out_ids, out_dist):
+    n = len(handles)
+    hs = (C.c_void_p * n)(*handles)
+    offs = (C.c_int64 * (n + 1))(*[int(o) for o in q_offsets])
+    _check(lib().pk_search_multi(hs, n, offs, _dev(queries, torch.float32, "queries"), k, nprobe,
+                                 _dev(out_ids, torch.int64, "out_ids"), _dev(out_dist, torch.float32, "out_dist"),
+                                 _stream()), "pk_search_multi")
+
+
+def pk_coarse(handle: int, queries, nprobe: int, out_probes):
+    _check(lib().pk_coarse(handle, _dev(queries, torch.float32, "queries"), queries.shape[0], nprobe,
+                           _dev(out_probes, torch.int32, "out_probes"), _stream()), "pk_coarse")
+
+
+def pk_scan_probes(handle: int, queries, k: int, probes, out_ids, out_dist):
+    _check(lib().pk_scan_probes(handle, _dev(queries, torch.float32, "queries"), queries.shape[0], k,
+                                probes.shape[1], _dev(probes, torch.int32, "probes"),
+                                _dev(out_ids, torch.int64, "out_ids"), _dev(out_dist, torch.float32, "out_dist"),
+                                _stream()), "pk_scan_probes")
+
+
+def pk_index_stats(handle: int) -> pk_stats:
+    st = pk_stats()
+    _check(lib().pk_index_stats(handle, C.byref(st), _stream()), "pk_index_stats")
+    return st
+
+
+def pk_list_lengths(handle: int, nlist: int):
+    import numpy as np
+    out = np.empty(nlist, dtype=np.int64)
+    _check(lib().pk_list_lengths(handle, out.ctypes.data_as(C.c_void_p), _stream()), "pk_list_lengths")
+    return out
+
+
+def pk_index_free(handle: int):
+    _check(lib().pk_index_free(handle), "pk_index_free")
+
+
+class Index:
+    """Convenience owner of one handle and its arena tensors (no arithmetic here)."""
+
+    def __init__(self, centroids, vectors, metric=PK_METRIC_IP, storage=PK_F32, ids=None, page_vecs=0,
+                 max_delta_pages=0, insert_reserve=0, arena_bytes=None):
+        nlist, d = centroids.shape
+        self.cfg = pk_config(d, nlist, metric, storage, page_vecs, max_delta_pages)
+        n = 0 if vectors is None else vectors.shape[0]
+        if arena_bytes is None:
+            arena_bytes = pk_arena_bytes(self.cfg, n, insert_reserve)
+            if arena_bytes == 0:
+                raise PancakeError(PK_ERR_INVALID_ARG, "pk_arena_bytes")
+        self.device = centroids.device
+        self.arenas = [torch.empty(arena_bytes, dtype=torch.uint8, device=self.device)]
+        self.nlist, self.d = nlist, d
+        self.handle = pk_index_build(self.cfg, centroids, vectors, ids, self.arenas[0])
+
+    def add_arena(self, nbytes: int):
+        t = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        pk_index_add_arena(self.handle, t)
+        self.arenas.append(t)
+
+    def insert(self, vectors, ids=None, want_lists=False):
+        out = torch.empty(vectors.shape[0], dtype=torch.int32, device=self.device) if want_lists else None
+        pk_insert(self.handle, vectors, ids, out)
+        return out
+
+    def insert_assigned(self, vectors, lists, ids=None):
+        pk_insert_assigned(self.handle, vectors, ids, lists)
+
+    def search(self, queries, k, nprobe):
+        ids = torch.empty((queries.shape[0], k), dtype=torch.int64, device=self.device)
+        dist = torch.empty((queries.shape[0], k), dtype=torch.float32, device=self.device)
+        pk_search(self.handle, queries, k, nprobe, ids, dist)
+        return ids, dist
+
+    def coarse(self, queries, nprobe):
+        out = torch.empty((queries.shape[0], nprobe), dtype=torch.int32, device=self.device)
+        pk_coarse(self.handle, queries, nprobe, out)
+        return out
+
+    def scan_probes(self, queries, k, probes):
+        ids = torch.empty((queries.shape[0], k), dtype=torch.int64, device=self.device)
+        dist = torch.empty((queries.shape[0], k), dtype=torch.float32, device=self.device)
+        pk_scan_probes(self.handle, queries, k, probes, ids, dist)
+        return ids, dist
+
+    def stats(self):
+        return pk_index_stats(self.handle)
+
+    def list_lengths(self):
+        return pk_list_lengths(self.handle, self.nlist)
+
+    def close(self):
+        if self.handle:
+            torch.cuda.synchronize(self.device)
+            pk_index_free(self.handle)
+            self.handle = None
+            self.arenas = []
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def search_multi(indexes, q_offsets, queries, k, nprobe):
+    dev = queries.device
+    ids = torch.empty((queries.shape[0], k), dtype=torch.int64, device=dev)
+    dist = torch.empty((queries.shape[0], k), dtype=torch.float32, device=dev)
+    pk_search_multi([ix.handle for ix in indexes], q_offsets, queries, k, nprobe, ids, dist)
+    return ids, dist

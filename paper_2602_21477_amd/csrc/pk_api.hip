@@ -1,0 +1,870 @@
+// C ABI of libpancake: handle management, arena layout, host-side bounds and the launch
+// sequences of build, insert and search.  See include/pancake.h for the contract.
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "pk_internal.h"
+
+using namespace pk;
+
+namespace {
+
+constexpr uint64_t kMagic = 0x70616e63616b6531ull;
+constexpr uint64_t kCandLimit = 1ull << 30; // candidate values per launch sequence (4 GiB of fp32)
+constexpr int kBuildChunk = 16384;          // vectors assigned per coarse pass during the build
+
+#define PK_HIP(expr)                                   \
+    do {                                               \
+        if ((expr) != hipSuccess) return PK_ERR_HIP;   \
+    } while (0)
+#define PK_TRY(expr)                                   \
+    do {                                               \
+        const int rc_ = (expr);                        \
+        if (rc_ != PK_OK) return rc_;                  \
+    } while (0)
+
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+} // namespace
+
+struct pk_index {
+    uint64_t magic;
+    pk_config cfg;
+    int dpad32, rb32, row_bytes, nlist_pad, P, max_dp;
+    size_t page_stride;     // bytes of one page over the three regions
+    DevIndex host;          // host copy of the device descriptor
+    DevIndex *dev;          // device copy, inside the first arena
+    uint32_t pages_total;
+    size_t arena_bytes;
+    std::vector<uint64_t> top_len; // [j] = total length of the j longest build-time lists
+    int64_t n_total, n_inserted;
+    // page accounting: last page counter read back, and how many vectors were inserted by then
+    uint32_t pages_known;
+    int64_t inserted_at_known;
+    uint32_t *pin_pages;
+    hipEvent_t ev;
+    bool ev_pending;
+    int64_t ev_inserted;
+    // library-owned workspace
+    char *ws;
+    size_t ws_bytes;
+    int lds_limit, num_cu;
+};
+
+namespace {
+
+bool live(const pk_index *ix) { return ix && ix->magic == kMagic; }
+
+struct Carver {
+    char *base;
+    size_t off;
+    template <typename T> T *take(size_t count)
+    {
+        off = round_up(off, 256);
+        T *p = base ? reinterpret_cast<T *>(base + off) : nullptr;
+        off += count * sizeof(T);
+        return p;
+    }
+};
+
+int ensure_ws(pk_index *ix, size_t bytes, hipStream_t s)
+{
+    if (bytes <= ix->ws_bytes) return PK_OK;
+    // grow: earlier work on this handle's stream may still use the old buffer
+    PK_HIP(hipStreamSynchronize(s));
+    if (ix->ws) PK_HIP(hipFree(ix->ws));
+    ix->ws = nullptr;
+    ix->ws_bytes = 0;
+    const size_t want = round_up(bytes + bytes / 8, 1 << 20);
+    void *p = nullptr;
+    if (hipMalloc(&p, want) != hipSuccess) {
+        (void)hipGetLastError();
+        return PK_ERR_NOMEM;
+    }
+    ix->ws = static_cast<char *>(p);
+    ix->ws_bytes = want;
+    return PK_OK;
+}
+
+uint32_t pages_used_ub(const pk_index *ix)
+{
+    const uint64_t ub = (uint64_t)ix->pages_known + (uint64_t)(ix->n_inserted - ix->inserted_at_known);
+    return (uint32_t)std::min<uint64_t>(ub, ix->pages_total);
+}
+
+// upper bound of one query's candidate range (padded segments) for `nprobe` lists
+uint64_t wq_ub(const pk_index *ix, int nprobe)
+{
+    const int np = std::min(nprobe, ix->cfg.nlist);
+    return round_up(ix->top_len[np] + (uint64_t)ix->n_inserted + 15ull * np, 16);
+}
+
+// Everything one launch sequence needs, carved out of the owner's workspace.
+struct Plan {
+    int64_t nq;
+    int nprobe, k, nh;
+    int mq_c, mq_f, grid_c, grid_f, cchunks, nchunks, K, nlist_max;
+    uint32_t stride, cand_cap, tile_cap, ctiles;
+    bool need_coarse, need_fine, f16;
+    // buffers
+    char *qs32, *qs;
+    float *qn32, *qn, *S, *cand;
+    uint32_t *cand_off, *cand_cnt, *cslot_q, *cslot_o, *lcnt, *lstart, *lfill, *ltile, *pair_off, *qtot, *qoff, *slot_q,
+        *slot_o, *scalars;
+    uint16_t *qagent;
+    Tile *ctile_buf, *tiles;
+    unsigned long long *cpartial, *partial;
+    int32_t *probes;
+    size_t bytes;
+};
+
+void carve(Plan &p, char *base, const pk_index *own)
+{
+    Carver c{base, 0};
+    const size_t nq = (size_t)p.nq;
+    p.qs32 = c.take<char>(nq * own->rb32);
+    p.qn32 = c.take<float>(nq);
+    if (p.f16) {
+        p.qs = c.take<char>(nq * own->row_bytes);
+        p.qn = c.take<float>(nq);
+    } else {
+        p.qs = p.qs32;
+        p.qn = p.qn32;
+    }
+    p.qagent = c.take<uint16_t>(nq);
+    p.scalars = c.take<uint32_t>(16);
+    p.probes = c.take<int32_t>(nq * p.nprobe);
+    p.cand_off = c.take<uint32_t>(nq);
+    p.cand_cnt = c.take<uint32_t>(nq);
+    p.cslot_q = c.take<uint32_t>(nq);
+    p.cslot_o = c.take<uint32_t>(nq);
+    if (p.need_coarse) {
+        p.S = c.take<float>(nq * p.stride + 16);
+        p.ctile_buf = c.take<Tile>(p.ctiles + 1);
+        p.cpartial = c.take<unsigned long long>(nq * p.cchunks * p.nprobe);
+    }
+    if (p.need_fine) {
+        const size_t nl = (size_t)p.nh * p.nlist_max;
+        p.lcnt = c.take<uint32_t>(nl);
+        p.lstart = c.take<uint32_t>(nl);
+        p.lfill = c.take<uint32_t>(nl);
+        p.ltile = c.take<uint32_t>(nl);
+        p.pair_off = c.take<uint32_t>(nq * (p.nprobe + 1));
+        p.qtot = c.take<uint32_t>(nq);
+        p.qoff = c.take<uint32_t>(nq);
+        p.slot_q = c.take<uint32_t>(nq * p.nprobe);
+        p.slot_o = c.take<uint32_t>(nq * p.nprobe);
+        p.tiles = c.take<Tile>((size_t)p.tile_cap + 1);
+        p.cand = c.take<float>((size_t)p.cand_cap + 16);
+        p.partial = c.take<unsigned long long>(nq * p.nchunks * p.K);
+    }
+    p.bytes = round_up(c.off, 256);
+}
+
+int grid_for(const pk_index *ix, int row_bytes, int mq, int waves)
+{
+    if (waves == 1) return ix->num_cu * 8;
+    const int lds = scan_lds_bytes(row_bytes, mq);
+    int per_cu = (160 * 1024) / lds;
+    per_cu = std::max(1, std::min(per_cu, 4));
+    return ix->num_cu * per_cu;
+}
+
+// Fills the plan for handles hs[0..nh) with query segments qlo (relative to this batch).
+int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t nq, int k, int nprobe,
+              bool need_coarse, bool need_fine)
+{
+    const pk_index *own = hs[0];
+    std::memset(&p, 0, sizeof(p));
+    p.nq = nq;
+    p.nprobe = nprobe;
+    p.k = k;
+    p.nh = nh;
+    p.need_coarse = need_coarse;
+    p.need_fine = need_fine;
+    p.f16 = own->cfg.storage == PK_F16;
+    p.mq_c = scan_max_mq(own->rb32, PK_F32, own->lds_limit);
+    p.mq_f = scan_max_mq(own->row_bytes, own->cfg.storage, own->lds_limit);
+    if (p.mq_c < 16 || p.mq_f < 16) return PK_ERR_UNSUPPORTED;
+    p.grid_c = grid_for(own, own->rb32, p.mq_c, 1);
+    p.grid_f = grid_for(own, own->row_bytes, p.mq_f, 4);
+    p.K = k + 1;
+    uint64_t cand = 0, tiles = 0, ctiles = 0, wmax = 0;
+    int nlist_hi = 0, pad_hi = 0;
+    for (int a = 0; a < nh; ++a) {
+        const pk_index *ix = hs[a];
+        const uint64_t nqa = qlo[a + 1] - qlo[a];
+        nlist_hi = std::max(nlist_hi, ix->cfg.nlist);
+        pad_hi = std::max(pad_hi, ix->nlist_pad);
+        ctiles += (nqa + p.mq_c - 1) / p.mq_c * (uint64_t)(ix->nlist_pad / kCoarsePage);
+        if (nqa == 0) continue;
+        const uint64_t w = wq_ub(ix, nprobe);
+        wmax = std::max(wmax, w);
+        cand += nqa * w;
+        const uint64_t pp = w / ix->P + nprobe;
+        tiles += std::min<uint64_t>(pages_used_ub(ix), nqa * pp) + nqa * pp / p.mq_f + 1;
+    }
+    if (cand > 0xfffffff0ull || tiles > 0xfffffff0ull || ctiles > 0xfffffff0ull) return PK_ERR_UNSUPPORTED;
+    p.nlist_max = nlist_hi;
+    p.stride = (uint32_t)pad_hi;
+    p.ctiles = (uint32_t)ctiles;
+    p.cchunks = (nlist_hi + kSelChunk - 1) / kSelChunk;
+    p.cand_cap = (uint32_t)cand;
+    p.tile_cap = (uint32_t)tiles;
+    p.nchunks = (int)std::max<uint64_t>(1, (wmax + kSelChunk - 1) / kSelChunk);
+    carve(p, nullptr, own);
+    return PK_OK;
+}
+
+void fill_multi(MultiArgs &m, pk_index *const *hs, int nh, const uint32_t *qlo, int mq_c)
+{
+    std::memset(&m, 0, sizeof(m));
+    m.n = nh;
+    uint32_t ct = 0;
+    for (int a = 0; a < nh; ++a) {
+        m.ix[a] = hs[a]->dev;
+        m.qlo[a] = qlo[a];
+        m.ctile[a] = ct;
+        const uint32_t nqa = qlo[a + 1] - qlo[a];
+        ct += (nqa + mq_c - 1) / mq_c * (uint32_t)(hs[a]->nlist_pad / kCoarsePage);
+    }
+    m.qlo[nh] = qlo[nh];
+    m.ctile[nh] = ct;
+}
+
+// Coarse search of one batch: probes[nq][nprobe] in the plan's workspace.
+int run_coarse(const Plan &p, const MultiArgs &m, const pk_index *own, const float *q, hipStream_t s)
+{
+    PK_HIP(launch_prep_queries(q, p.nq, own->cfg.d, PK_F32, own->rb32, p.qs32, p.qn32, s));
+    CoarseArgs ca{};
+    ca.mq = p.mq_c;
+    ca.scan_grid = p.grid_c;
+    ca.stride = p.stride;
+    ca.slot_query = p.cslot_q;
+    ca.slot_out = p.cslot_o;
+    ca.cand_off = p.cand_off;
+    ca.cand_cnt = p.cand_cnt;
+    ca.qagent = p.qagent;
+    ca.tiles = p.ctile_buf;
+    ca.scalars = p.scalars;
+    PK_HIP(launch_coarse_tiles(ca, m, s));
+    ScanArgs sa{};
+    sa.tiles = p.ctile_buf;
+    sa.ntiles = p.scalars + 0;
+    sa.tile_ctr = p.scalars + 1;
+    sa.batch = p.scalars + 2;
+    sa.qs = p.qs32;
+    sa.qnorm = p.qn32;
+    sa.slot_query = p.cslot_q;
+    sa.slot_out = p.cslot_o;
+    sa.out = p.S;
+    sa.row_bytes = own->rb32;
+    sa.metric = own->cfg.metric;
+    sa.storage = PK_F32;
+    sa.mq = p.mq_c;
+    PK_HIP(launch_scan(sa, 1, p.grid_c, s));
+    SelectArgs se{};
+    se.vals = p.S;
+    se.qoff = p.cand_off;
+    se.qcnt = p.cand_cnt;
+    se.metric = own->cfg.metric;
+    se.K = p.nprobe;
+    se.nchunks = p.cchunks;
+    se.partial = p.cpartial;
+    PK_HIP(launch_select_partial(se, p.nq, s));
+    PK_HIP(launch_select_probes(p.cpartial, p.cchunks, p.nprobe, p.nprobe, p.nq, p.probes, s));
+    return PK_OK;
+}
+
+// Fine search of one batch over p.probes.
+int run_fine(const Plan &p, const MultiArgs &m, const pk_index *own, const float *q, int64_t *out_ids, float *out_dist,
+             hipStream_t s)
+{
+    if (p.f16) PK_HIP(launch_prep_queries(q, p.nq, own->cfg.d, PK_F16, own->row_bytes, p.qs, p.qn, s));
+    WorklistArgs w{};
+    w.probes = p.probes;
+    w.qagent = p.qagent;
+    w.nq = p.nq;
+    w.nprobe = p.nprobe;
+    w.n_handles = p.nh;
+    w.nlist_max = p.nlist_max;
+    w.mq = p.mq_f;
+    w.scan_grid = p.grid_f;
+    w.lcnt = p.lcnt;
+    w.lstart = p.lstart;
+    w.lfill = p.lfill;
+    w.ltile = p.ltile;
+    w.pair_off = p.pair_off;
+    w.qtot = p.qtot;
+    w.qoff = p.qoff;
+    w.slot_query = p.slot_q;
+    w.slot_out = p.slot_o;
+    w.tiles = p.tiles;
+    w.tile_cap = p.tile_cap;
+    w.cand_cap = p.cand_cap;
+    w.scalars = p.scalars + 4;
+    PK_HIP(launch_worklist(w, m, s));
+    ScanArgs sa{};
+    sa.tiles = p.tiles;
+    sa.ntiles = p.scalars + 4;
+    sa.tile_ctr = p.scalars + 5;
+    sa.batch = p.scalars + 6;
+    sa.qs = p.qs;
+    sa.qnorm = p.qn;
+    sa.slot_query = p.slot_q;
+    sa.slot_out = p.slot_o;
+    sa.out = p.cand;
+    sa.row_bytes = own->row_bytes;
+    sa.metric = own->cfg.metric;
+    sa.storage = own->cfg.storage;
+    sa.mq = p.mq_f;
+    PK_HIP(launch_scan(sa, 4, p.grid_f, s));
+    SelectArgs se{};
+    se.vals = p.cand;
+    se.qoff = p.qoff;
+    se.qcnt = p.qtot;
+    se.metric = own->cfg.metric;
+    se.K = p.K;
+    se.nchunks = p.nchunks;
+    se.partial = p.partial;
+    PK_HIP(launch_select_partial(se, p.nq, s));
+    FinalArgs f{};
+    f.partial = p.partial;
+    f.nchunks = p.nchunks;
+    f.K = p.K;
+    f.k = p.k;
+    f.nprobe = p.nprobe;
+    f.metric = own->cfg.metric;
+    f.vals = p.cand;
+    f.qoff = p.qoff;
+    f.qcnt = p.qtot;
+    f.pair_off = p.pair_off;
+    f.probes = p.probes;
+    f.qagent = p.qagent;
+    f.out_ids = out_ids;
+    f.out_dist = out_dist;
+    PK_HIP(launch_select_final(f, m, p.nq, s));
+    return PK_OK;
+}
+
+// qagent for runs that skip the coarse stage (forced probes): one handle only
+int set_single_agent(const Plan &p, hipStream_t s)
+{
+    // uint16 zeros, written as uint32 words (the buffer is 256-byte aligned and padded)
+    PK_HIP(launch_fill_u32(reinterpret_cast<uint32_t *>(p.qagent), 0u, ((size_t)p.nq + 1) / 2, s));
+    return PK_OK;
+}
+
+enum Mode { kFull, kCoarseOnly, kForced };
+
+int search_impl(pk_index *const *hs, int nh, const int64_t *q_offsets, const float *queries, int k, int nprobe,
+                Mode mode, const int32_t *forced, int32_t *out_probes, int64_t *out_ids, float *out_dist, hipStream_t s)
+{
+    pk_index *own = hs[0];
+    const int64_t nq_all = q_offsets[nh];
+    const int d = own->cfg.d;
+    uint64_t wmax = 1;
+    for (int a = 0; a < nh; ++a) wmax = std::max(wmax, wq_ub(hs[a], nprobe));
+    const int64_t step = std::max<int64_t>(1, std::min<int64_t>(32768, (int64_t)(kCandLimit / wmax)));
+    std::vector<uint32_t> qlo(nh + 1);
+    for (int64_t q0 = 0; q0 < nq_all; q0 += step) {
+        const int64_t nq = std::min(step, nq_all - q0);
+        for (int a = 0; a <= nh; ++a)
+            qlo[a] = (uint32_t)std::min<int64_t>(std::max<int64_t>(q_offsets[a] - q0, 0), nq);
+        Plan p;
+        PK_TRY(make_plan(p, hs, nh, qlo.data(), nq, k, nprobe, mode != kForced, mode != kCoarseOnly));
+        PK_TRY(ensure_ws(own, p.bytes, s));
+        carve(p, own->ws, own);
+        MultiArgs m;
+        fill_multi(m, hs, nh, qlo.data(), p.mq_c);
+        const float *q = queries + (size_t)q0 * d;
+        if (mode == kForced) {
+            PK_TRY(set_single_agent(p, s));
+            PK_HIP(launch_copy_i32(forced + (size_t)q0 * nprobe, p.probes, nq * nprobe, s));
+            if (!p.f16) PK_HIP(launch_prep_queries(q, nq, d, PK_F32, own->rb32, p.qs32, p.qn32, s));
+        } else {
+            PK_TRY(run_coarse(p, m, own, q, s));
+        }
+        if (mode == kCoarseOnly) {
+            PK_HIP(launch_copy_i32(p.probes, out_probes + (size_t)q0 * nprobe, nq * nprobe, s));
+        } else {
+            PK_TRY(run_fine(p, m, own, q, out_ids + (size_t)q0 * k, out_dist + (size_t)q0 * k, s));
+        }
+    }
+    return PK_OK;
+}
+
+int check_search_args(const pk_index *ix, const void *q, int64_t nq, int k, int nprobe)
+{
+    if (!live(ix)) return PK_ERR_BAD_HANDLE;
+    if (nq < 0 || (nq > 0 && !q)) return PK_ERR_INVALID_ARG;
+    if (k < 1 || k > PK_MAX_K) return PK_ERR_INVALID_ARG;
+    if (nprobe < 1 || nprobe > ix->cfg.nlist || nprobe > PK_MAX_NPROBE) return PK_ERR_INVALID_ARG;
+    return PK_OK;
+}
+
+bool valid_config(const pk_config *c)
+{
+    if (!c) return false;
+    if (c->d < 1 || c->d > PK_MAX_DIM || c->nlist < 1) return false;
+    if (c->metric != PK_METRIC_IP && c->metric != PK_METRIC_L2) return false;
+    if (c->storage != PK_F32 && c->storage != PK_F16) return false;
+    if (c->page_vecs != 0 && (c->page_vecs < 32 || c->page_vecs > 1024 || c->page_vecs % 32 != 0)) return false;
+    if (c->max_delta_pages < 0) return false;
+    return true;
+}
+
+struct Dims {
+    int dpad32, rb32, row_bytes, nlist_pad, P, max_dp;
+    size_t header, page_stride;
+};
+
+Dims dims_of(const pk_config *c)
+{
+    Dims x;
+    x.rb32 = (int)round_up((size_t)c->d * 4, kIterBytes);
+    x.dpad32 = x.rb32 / 4;
+    x.row_bytes = c->storage == PK_F16 ? (int)round_up((size_t)c->d * 2, kIterBytes) : x.rb32;
+    x.nlist_pad = (int)round_up(c->nlist, kCoarsePage);
+    x.P = c->page_vecs ? c->page_vecs : 128;
+    x.max_dp = c->max_delta_pages ? c->max_delta_pages : 1024;
+    Carver h{nullptr, 0};
+    h.take<float>((size_t)x.nlist_pad * x.dpad32);
+    h.take<float>(x.nlist_pad);
+    h.take<uint32_t>(c->nlist);
+    h.take<uint32_t>(c->nlist);
+    h.take<uint32_t>(c->nlist);
+    h.take<uint32_t>((size_t)c->nlist * x.max_dp);
+    h.take<uint32_t>(16);
+    h.take<DevIndex>(1);
+    x.header = round_up(h.off, 4096);
+    x.page_stride = (size_t)x.P * x.row_bytes + (size_t)x.P * 12;
+    return x;
+}
+
+// pages that fit into `bytes`, leaving room to align the three regions
+uint32_t pages_in(size_t bytes, const Dims &x)
+{
+    if (bytes < 1024) return 0;
+    const size_t n = (bytes - 1024) / x.page_stride;
+    return (uint32_t)std::min<size_t>(n, 0x7fffffffu);
+}
+
+void place_arena(Arena &a, char *base, uint32_t first_page, uint32_t npages, const Dims &x)
+{
+    a.first_page = first_page;
+    a.npages = npages;
+    Carver c{base, 0};
+    a.vec = c.take<char>((size_t)npages * x.P * x.row_bytes);
+    a.norm = c.take<float>((size_t)npages * x.P);
+    a.ids = c.take<int64_t>((size_t)npages * x.P);
+}
+
+int snapshot_pages(pk_index *ix, hipStream_t s)
+{
+    if (ix->ev_pending) {
+        const hipError_t e = hipEventQuery(ix->ev);
+        if (e == hipSuccess) {
+            ix->pages_known = *ix->pin_pages;
+            ix->inserted_at_known = ix->ev_inserted;
+            ix->ev_pending = false;
+        } else if (e != hipErrorNotReady) {
+            return PK_ERR_HIP;
+        } else {
+            (void)hipGetLastError();
+        }
+    }
+    if (!ix->ev_pending) {
+        PK_HIP(hipMemcpyAsync(ix->pin_pages, ix->host.ctr, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+        PK_HIP(hipEventRecord(ix->ev, s));
+        ix->ev_pending = true;
+        ix->ev_inserted = ix->n_inserted;
+    }
+    return PK_OK;
+}
+
+// exact page count (waits for the pending read-back)
+int settle_pages(pk_index *ix)
+{
+    if (ix->ev_pending) {
+        PK_HIP(hipEventSynchronize(ix->ev));
+        ix->pages_known = *ix->pin_pages;
+        ix->inserted_at_known = ix->ev_inserted;
+        ix->ev_pending = false;
+    }
+    return PK_OK;
+}
+
+void destroy(pk_index *ix)
+{
+    if (!ix) return;
+    if (ix->ws) (void)hipFree(ix->ws);
+    if (ix->pin_pages) (void)hipHostFree(ix->pin_pages);
+    if (ix->ev) (void)hipEventDestroy(ix->ev);
+    ix->magic = 0;
+    delete ix;
+}
+
+int insert_impl(pk_index *ix, const float *x, const int64_t *ids, int64_t m, const int32_t *forced,
+                int32_t *assigned_out, hipStream_t s)
+{
+    if (!live(ix)) return PK_ERR_BAD_HANDLE;
+    if (m < 0 || (m > 0 && !x)) return PK_ERR_INVALID_ARG;
+    if (m == 0) return PK_OK;
+    // host-side capacity check: every vector may open at most one page
+    if ((uint64_t)pages_used_ub(ix) + (uint64_t)m > ix->pages_total ||
+        (uint64_t)ix->pages_known + (uint64_t)(ix->n_inserted - ix->inserted_at_known) + (uint64_t)m > ix->pages_total) {
+        PK_TRY(settle_pages(ix));
+        if ((uint64_t)ix->pages_known + (uint64_t)(ix->n_inserted - ix->inserted_at_known) + (uint64_t)m >
+            ix->pages_total)
+            return PK_ERR_NOMEM;
+    }
+    pk_index *hs[1] = {ix};
+    for (int64_t i0 = 0; i0 < m; i0 += 1024) {
+        const int mc = (int)std::min<int64_t>(1024, m - i0);
+        const uint32_t qlo[2] = {0, (uint32_t)mc};
+        Plan p;
+        PK_TRY(make_plan(p, hs, 1, qlo, mc, 1, 1, forced == nullptr, false));
+        const size_t extra = round_up(p.bytes, 256);
+        PK_TRY(ensure_ws(ix, extra + 4096 * 2, s));
+        carve(p, ix->ws, ix);
+        uint32_t *slots = reinterpret_cast<uint32_t *>(ix->ws + extra);
+        const float *xc = x + (size_t)i0 * ix->cfg.d;
+        const int32_t *assign;
+        if (forced) {
+            assign = forced + i0;
+        } else {
+            MultiArgs mm;
+            fill_multi(mm, hs, 1, qlo, p.mq_c);
+            PK_TRY(run_coarse(p, mm, ix, xc, s));
+            assign = p.probes;
+        }
+        PK_HIP(launch_reserve(ix->dev, assign, mc, slots, assigned_out ? assigned_out + i0 : nullptr, s));
+        PK_HIP(launch_append(ix->dev, xc, ids ? ids + i0 : nullptr, assign, slots, mc, ix->n_total, s));
+        ix->n_total += mc;
+        ix->n_inserted += mc;
+    }
+    return snapshot_pages(ix, s);
+}
+
+} // namespace
+
+// ------------------------------------------------------------------- C ABI
+
+extern "C" {
+
+size_t pk_arena_bytes(const pk_config *cfg, int64_t n, int64_t n_insert_reserve)
+{
+    if (!valid_config(cfg) || n < 0 || n_insert_reserve < 0) return 0;
+    const Dims x = dims_of(cfg);
+    const uint64_t pages = (uint64_t)(n + x.P - 1) / x.P + (uint64_t)std::min<int64_t>(n, cfg->nlist) +
+                           (uint64_t)(n_insert_reserve + x.P - 1) / x.P +
+                           (uint64_t)std::min<int64_t>(n_insert_reserve, cfg->nlist) + 1;
+    return x.header + pages * x.page_stride + 4096;
+}
+
+int pk_index_build(const pk_config *cfg, const float *centroids, const float *vectors, const int64_t *ids, int64_t n,
+                   void *arena, size_t arena_bytes, void *stream, pk_index **out)
+{
+    if (!out) return PK_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!cfg || !centroids || !arena || n < 0 || (n > 0 && !vectors)) return PK_ERR_INVALID_ARG;
+    if (cfg->d > PK_MAX_DIM) return PK_ERR_UNSUPPORTED;
+    if (!valid_config(cfg)) return PK_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(arena) % 256 != 0) return PK_ERR_INVALID_ARG;
+    if (n > 0x7fffffff00ll) return PK_ERR_UNSUPPORTED;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const Dims x = dims_of(cfg);
+    if (arena_bytes < x.header + 1024 + x.page_stride) return PK_ERR_NOMEM;
+
+    pk_index *ix = new (std::nothrow) pk_index();
+    if (!ix) return PK_ERR_NOMEM;
+    ix->magic = kMagic;
+    ix->cfg = *cfg;
+    ix->dpad32 = x.dpad32;
+    ix->rb32 = x.rb32;
+    ix->row_bytes = x.row_bytes;
+    ix->nlist_pad = x.nlist_pad;
+    ix->P = x.P;
+    ix->max_dp = x.max_dp;
+    ix->cfg.page_vecs = x.P;
+    ix->cfg.max_delta_pages = x.max_dp;
+    ix->page_stride = x.page_stride;
+    ix->arena_bytes = arena_bytes;
+    ix->top_len.assign((size_t)cfg->nlist + 1, 0);
+    int rc = PK_OK;
+    auto fail = [&](int code) {
+        (void)hipStreamSynchronize(s);
+        destroy(ix);
+        return code;
+    };
+
+    int dev = 0, lds = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+        return fail(PK_ERR_HIP);
+    ix->lds_limit = lds;
+    ix->num_cu = cus > 0 ? cus : 256;
+    if (scan_max_mq(x.rb32, PK_F32, lds) < 16 || scan_max_mq(x.row_bytes, cfg->storage, lds) < 16)
+        return fail(PK_ERR_UNSUPPORTED);
+    if (hipHostMalloc(reinterpret_cast<void **>(&ix->pin_pages), 64, hipHostMallocDefault) != hipSuccess)
+        return fail(PK_ERR_HIP);
+    if (hipEventCreateWithFlags(&ix->ev, hipEventDisableTiming) != hipSuccess) return fail(PK_ERR_HIP);
+
+    // header of the first arena
+    char *base = static_cast<char *>(arena);
+    Carver h{base, 0};
+    DevIndex &D = ix->host;
+    std::memset(&D, 0, sizeof(D));
+    float *cent = h.take<float>((size_t)x.nlist_pad * x.dpad32);
+    float *cnorm = h.take<float>(x.nlist_pad);
+    D.cent = cent;
+    D.cnorm = cnorm;
+    D.list_len = h.take<uint32_t>(cfg->nlist);
+    D.main_base = h.take<uint32_t>(cfg->nlist);
+    D.main_pages = h.take<uint32_t>(cfg->nlist);
+    D.dtab = h.take<uint32_t>((size_t)cfg->nlist * x.max_dp);
+    D.ctr = h.take<uint32_t>(16);
+    ix->dev = h.take<DevIndex>(1);
+    D.nlist = cfg->nlist;
+    D.nlist_pad = x.nlist_pad;
+    D.d = cfg->d;
+    D.dpad32 = x.dpad32;
+    D.P = x.P;
+    D.max_dp = x.max_dp;
+    D.metric = cfg->metric;
+    D.storage = cfg->storage;
+    D.row_bytes = x.row_bytes;
+    D.n_arenas = 1;
+    ix->pages_total = pages_in(arena_bytes - x.header, x);
+    place_arena(D.arenas[0], base + x.header, 0, ix->pages_total, x);
+
+    if (hipMemcpyAsync(ix->dev, &D, sizeof(D), hipMemcpyHostToDevice, s) != hipSuccess) return fail(PK_ERR_HIP);
+    if (launch_fill_u32(D.list_len, 0u, cfg->nlist, s) != hipSuccess ||
+        launch_fill_u32(D.main_base, 0u, cfg->nlist, s) != hipSuccess ||
+        launch_fill_u32(D.main_pages, 0u, cfg->nlist, s) != hipSuccess ||
+        launch_fill_u32(D.dtab, 0xffffffffu, (size_t)cfg->nlist * x.max_dp, s) != hipSuccess ||
+        launch_fill_u32(D.ctr, 0u, 16, s) != hipSuccess ||
+        launch_fill_u32(D.ctr + 2, ix->pages_total, 1, s) != hipSuccess ||
+        launch_store_centroids(centroids, cfg->nlist, cfg->d, x.dpad32, x.nlist_pad, cfg->metric, cent, cnorm, s) !=
+            hipSuccess)
+        return fail(PK_ERR_HIP);
+
+    std::vector<uint32_t> cnt((size_t)cfg->nlist, 0);
+    if (n > 0) {
+        int32_t *d_assign = nullptr;
+        uint32_t *d_cnt = nullptr;
+        if (hipMalloc(reinterpret_cast<void **>(&d_assign), (size_t)n * sizeof(int32_t)) != hipSuccess)
+            return fail(PK_ERR_NOMEM);
+        if (hipMalloc(reinterpret_cast<void **>(&d_cnt), (size_t)cfg->nlist * 2 * sizeof(uint32_t)) != hipSuccess) {
+            (void)hipFree(d_assign);
+            return fail(PK_ERR_NOMEM);
+        }
+        auto fail2 = [&](int code) {
+            (void)hipStreamSynchronize(s);
+            (void)hipFree(d_assign);
+            (void)hipFree(d_cnt);
+            destroy(ix);
+            return code;
+        };
+        // assignment: a top-1 coarse search per chunk (Section 3.1 rule = rank-1 probe)
+        pk_index *hs[1] = {ix};
+        for (int64_t i0 = 0; i0 < n && rc == PK_OK; i0 += kBuildChunk) {
+            const int64_t mc = std::min<int64_t>(kBuildChunk, n - i0);
+            const uint32_t qlo[2] = {0, (uint32_t)mc};
+            Plan p;
+            rc = make_plan(p, hs, 1, qlo, mc, 1, 1, true, false);
+            if (rc == PK_OK) rc = ensure_ws(ix, p.bytes, s);
+            if (rc != PK_OK) break;
+            carve(p, ix->ws, ix);
+            MultiArgs mm;
+            fill_multi(mm, hs, 1, qlo, p.mq_c);
+            rc = run_coarse(p, mm, ix, vectors + (size_t)i0 * cfg->d, s);
+            if (rc == PK_OK && launch_copy_i32(p.probes, d_assign + i0, mc, s) != hipSuccess) rc = PK_ERR_HIP;
+        }
+        if (rc != PK_OK) return fail2(rc);
+        if (launch_fill_u32(d_cnt, 0u, (size_t)cfg->nlist * 2, s) != hipSuccess ||
+            launch_hist(d_assign, n, d_cnt, s) != hipSuccess ||
+            hipMemcpyAsync(cnt.data(), d_cnt, (size_t)cfg->nlist * sizeof(uint32_t), hipMemcpyDeviceToHost, s) !=
+                hipSuccess ||
+            hipStreamSynchronize(s) != hipSuccess)
+            return fail2(PK_ERR_HIP);
+        std::vector<uint32_t> mbase((size_t)cfg->nlist), mpages((size_t)cfg->nlist);
+        uint64_t used = 0;
+        for (int l = 0; l < cfg->nlist; ++l) {
+            mbase[l] = (uint32_t)used;
+            mpages[l] = (cnt[l] + x.P - 1) / x.P;
+            used += mpages[l];
+        }
+        if (used > ix->pages_total) return fail2(PK_ERR_NOMEM);
+        const uint32_t used32 = (uint32_t)used;
+        if (hipMemcpyAsync(D.main_base, mbase.data(), mbase.size() * 4, hipMemcpyHostToDevice, s) != hipSuccess ||
+            hipMemcpyAsync(D.main_pages, mpages.data(), mpages.size() * 4, hipMemcpyHostToDevice, s) != hipSuccess ||
+            hipMemcpyAsync(D.list_len, cnt.data(), cnt.size() * 4, hipMemcpyHostToDevice, s) != hipSuccess ||
+            hipMemcpyAsync(D.ctr, &used32, 4, hipMemcpyHostToDevice, s) != hipSuccess ||
+            launch_scatter_build(ix->dev, vectors, ids, d_assign, n, 0, d_cnt + cfg->nlist, s) != hipSuccess ||
+            hipStreamSynchronize(s) != hipSuccess)
+            return fail2(PK_ERR_HIP);
+        (void)hipFree(d_assign);
+        (void)hipFree(d_cnt);
+        ix->pages_known = used32;
+    }
+    if (hipStreamSynchronize(s) != hipSuccess) return fail(PK_ERR_HIP);
+    ix->n_total = n;
+    ix->n_inserted = 0;
+    ix->inserted_at_known = 0;
+    std::vector<uint32_t> sorted(cnt);
+    std::sort(sorted.begin(), sorted.end(), [](uint32_t a, uint32_t b) { return a > b; });
+    for (int j = 0; j < cfg->nlist; ++j) ix->top_len[j + 1] = ix->top_len[j] + sorted[j];
+    *out = ix;
+    return PK_OK;
+}
+
+int pk_index_add_arena(pk_index *ix, void *arena, size_t arena_bytes, void *stream)
+{
+    if (!live(ix)) return PK_ERR_BAD_HANDLE;
+    if (!arena || reinterpret_cast<uintptr_t>(arena) % 256 != 0) return PK_ERR_INVALID_ARG;
+    if (ix->host.n_arenas >= PK_MAX_ARENAS) return PK_ERR_UNSUPPORTED;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const Dims x = dims_of(&ix->cfg);
+    const uint32_t np = pages_in(arena_bytes, x);
+    if (np == 0 || (uint64_t)ix->pages_total + np > 0x7fffffffu) return PK_ERR_INVALID_ARG;
+    DevIndex &D = ix->host;
+    place_arena(D.arenas[D.n_arenas], static_cast<char *>(arena), ix->pages_total, np, x);
+    D.n_arenas += 1;
+    ix->pages_total += np;
+    ix->arena_bytes += arena_bytes;
+    PK_HIP(hipMemcpyAsync(ix->dev, &D, sizeof(D), hipMemcpyHostToDevice, s));
+    PK_HIP(launch_fill_u32(D.ctr + 2, ix->pages_total, 1, s));
+    return PK_OK;
+}
+
+int pk_insert(pk_index *ix, const float *vectors, const int64_t *ids, int64_t m, int32_t *assigned_lists, void *stream)
+{
+    return insert_impl(ix, vectors, ids, m, nullptr, assigned_lists, static_cast<hipStream_t>(stream));
+}
+
+int pk_insert_assigned(pk_index *ix, const float *vectors, const int64_t *ids, int64_t m, const int32_t *lists,
+                       void *stream)
+{
+    if (m > 0 && !lists) return PK_ERR_INVALID_ARG;
+    return insert_impl(ix, vectors, ids, m, lists, nullptr, static_cast<hipStream_t>(stream));
+}
+
+int pk_search(pk_index *ix, const float *queries, int64_t nq, int32_t k, int32_t nprobe, int64_t *out_ids,
+              float *out_dist, void *stream)
+{
+    PK_TRY(check_search_args(ix, queries, nq, k, nprobe));
+    if (nq > 0 && (!out_ids || !out_dist)) return PK_ERR_INVALID_ARG;
+    if (nq == 0) return PK_OK;
+    pk_index *hs[1] = {ix};
+    const int64_t offs[2] = {0, nq};
+    return search_impl(hs, 1, offs, queries, k, nprobe, kFull, nullptr, nullptr, out_ids, out_dist,
+                       static_cast<hipStream_t>(stream));
+}
+
+int pk_search_multi(pk_index *const *handles, int32_t n_handles, const int64_t *q_offsets, const float *queries,
+                    int32_t k, int32_t nprobe, int64_t *out_ids, float *out_dist, void *stream)
+{
+    if (!handles || !q_offsets || n_handles < 1 || n_handles > PK_MAX_HANDLES) return PK_ERR_INVALID_ARG;
+    if (q_offsets[0] != 0) return PK_ERR_INVALID_ARG;
+    for (int a = 0; a < n_handles; ++a) {
+        if (!live(handles[a])) return PK_ERR_BAD_HANDLE;
+        if (q_offsets[a + 1] < q_offsets[a]) return PK_ERR_INVALID_ARG;
+        for (int b = 0; b < a; ++b)
+            if (handles[b] == handles[a]) return PK_ERR_INVALID_ARG;
+        const pk_config &c0 = handles[0]->cfg, &c = handles[a]->cfg;
+        if (c.d != c0.d || c.metric != c0.metric || c.storage != c0.storage) return PK_ERR_DIM_MISMATCH;
+        PK_TRY(check_search_args(handles[a], queries, q_offsets[n_handles], k, nprobe));
+    }
+    const int64_t nq = q_offsets[n_handles];
+    if (nq > 0 && (!out_ids || !out_dist || !queries)) return PK_ERR_INVALID_ARG;
+    if (nq == 0) return PK_OK;
+    return search_impl(handles, n_handles, q_offsets, queries, k, nprobe, kFull, nullptr, nullptr, out_ids, out_dist,
+                       static_cast<hipStream_t>(stream));
+}
+
+int pk_coarse(pk_index *ix, const float *queries, int64_t nq, int32_t nprobe, int32_t *out_probes, void *stream)
+{
+    PK_TRY(check_search_args(ix, queries, nq, 1, nprobe));
+    if (nq > 0 && !out_probes) return PK_ERR_INVALID_ARG;
+    if (nq == 0) return PK_OK;
+    pk_index *hs[1] = {ix};
+    const int64_t offs[2] = {0, nq};
+    return search_impl(hs, 1, offs, queries, 1, nprobe, kCoarseOnly, nullptr, out_probes, nullptr, nullptr,
+                       static_cast<hipStream_t>(stream));
+}
+
+int pk_scan_probes(pk_index *ix, const float *queries, int64_t nq, int32_t k, int32_t nprobe, const int32_t *probes,
+                   int64_t *out_ids, float *out_dist, void *stream)
+{
+    PK_TRY(check_search_args(ix, queries, nq, k, nprobe));
+    if (nq > 0 && (!probes || !out_ids || !out_dist)) return PK_ERR_INVALID_ARG;
+    if (nq == 0) return PK_OK;
+    pk_index *hs[1] = {ix};
+    const int64_t offs[2] = {0, nq};
+    return search_impl(hs, 1, offs, queries, k, nprobe, kForced, probes, nullptr, out_ids, out_dist,
+                       static_cast<hipStream_t>(stream));
+}
+
+int pk_index_stats(pk_index *ix, pk_stats *out, void *stream)
+{
+    if (!live(ix)) return PK_ERR_BAD_HANDLE;
+    if (!out) return PK_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint32_t ctr[4] = {0, 0, 0, 0};
+    std::vector<uint32_t> len((size_t)ix->cfg.nlist);
+    PK_HIP(hipMemcpyAsync(ctr, ix->host.ctr, sizeof(ctr), hipMemcpyDeviceToHost, s));
+    PK_HIP(hipMemcpyAsync(len.data(), ix->host.list_len, len.size() * 4, hipMemcpyDeviceToHost, s));
+    PK_HIP(hipStreamSynchronize(s));
+    PK_TRY(settle_pages(ix));
+    std::memset(out, 0, sizeof(*out));
+    out->n_total = ix->n_total;
+    out->n_inserted = ix->n_inserted;
+    out->pages_total = ix->pages_total;
+    out->pages_used = ctr[0];
+    out->arena_bytes = (int64_t)ix->arena_bytes;
+    out->workspace_bytes = (int64_t)ix->ws_bytes;
+    out->max_list_len = len.empty() ? 0 : *std::max_element(len.begin(), len.end());
+    out->device_error = (int32_t)ctr[1];
+    out->n_arenas = ix->host.n_arenas;
+    return PK_OK;
+}
+
+int pk_list_lengths(pk_index *ix, int64_t *out_len, void *stream)
+{
+    if (!live(ix)) return PK_ERR_BAD_HANDLE;
+    if (!out_len) return PK_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    std::vector<uint32_t> len((size_t)ix->cfg.nlist);
+    PK_HIP(hipMemcpyAsync(len.data(), ix->host.list_len, len.size() * 4, hipMemcpyDeviceToHost, s));
+    PK_HIP(hipStreamSynchronize(s));
+    for (size_t i = 0; i < len.size(); ++i) out_len[i] = len[i];
+    return PK_OK;
+}
+
+int pk_index_free(pk_index *ix)
+{
+    if (!live(ix)) return PK_ERR_BAD_HANDLE;
+    destroy(ix);
+    return PK_OK;
+}
+
+const char *pk_strerror(int status)
+{
+    switch (status) {
+    case PK_OK: return "ok";
+    case PK_ERR_INVALID_ARG: return "invalid argument";
+    case PK_ERR_BAD_HANDLE: return "bad index handle";
+    case PK_ERR_DIM_MISMATCH: return "handles differ in dimension, metric or storage";
+    case PK_ERR_NOMEM: return "out of arena, workspace or host memory";
+    case PK_ERR_HIP: return "HIP runtime error";
+    case PK_ERR_UNSUPPORTED: return "request outside the supported limits";
+    default: return "unknown status";
+    }
+}
+
+} // extern "C"

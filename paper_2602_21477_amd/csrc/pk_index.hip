@@ -1,0 +1,218 @@
+// Index construction and the insert path (device side).
+//
+// Section 3.1 / Section 6.1 "IVF-Static": a vector is appended to the list of its nearest
+// centroid and nothing else changes.  Section 4.4 keeps new vectors of a GPU-resident
+// cluster in a CPU-side buffer because a device list cannot grow in place; here a list
+// is a chain of fixed-size pages, so growing it means taking the next free page of the
+// arena: no reallocation, no copy of old data, no host involvement.
+#include "pk_internal.h"
+
+namespace pk {
+
+// centroid table in scan layout: [nlist_pad][dpad32] fp32, zero padded, plus squared norms
+__global__ __launch_bounds__(256) void store_centroids_kernel(const float *c, int nlist, int d, int dpad32, int metric,
+                                                              float *cent, float *cnorm)
+{
+    __shared__ float s_part[4];
+    const int row = blockIdx.x;
+    float acc = 0.f;
+    for (int i = threadIdx.x; i < dpad32; i += blockDim.x) {
+        const float v = (row < nlist && i < d) ? c[(size_t)row * d + i] : 0.f;
+        cent[(size_t)row * dpad32 + i] = v;
+        acc += v * v;
+    }
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+    if ((threadIdx.x & 63) == 0) s_part[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) cnorm[row] = metric == PK_METRIC_L2 ? s_part[0] + s_part[1] + s_part[2] + s_part[3] : 0.f;
+}
+
+hipError_t launch_store_centroids(const float *c, int nlist, int d, int dpad32, int nlist_pad, int metric, float *cent,
+                                  float *cnorm, hipStream_t s)
+{
+    hipLaunchKernelGGL(store_centroids_kernel, dim3(nlist_pad), dim3(256), 0, s, c, nlist, d, dpad32, metric, cent,
+                       cnorm);
+    return hipGetLastError();
+}
+
+__global__ void hist_kernel(const int32_t *assign, int64_t n, uint32_t *cnt)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+        atomicAdd(&cnt[assign[i]], 1u);
+}
+
+hipError_t launch_hist(const int32_t *assign, int64_t n, uint32_t *cnt, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    const int grid = (int)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
+    hipLaunchKernelGGL(hist_kernel, dim3(grid), dim3(256), 0, s, assign, n, cnt);
+    return hipGetLastError();
+}
+
+// one wave writes one vector into slot `slot` of list `l`: convert (fp16: round to nearest
+// even), zero pad the row, squared norm of the stored values, id
+__device__ void write_row(const DevIndex &ix, uint32_t l, uint32_t slot, const float *src, int64_t id)
+{
+    const uint32_t P = (uint32_t)ix.P;
+    const uint32_t lp = slot / P;
+    const uint32_t pg = phys_page(ix, l, lp);
+    const Arena &ar = arena_of(ix, pg);
+    const size_t local = (size_t)(pg - ar.first_page) * P + (slot - lp * P);
+    char *dst = ar.vec + local * (size_t)ix.row_bytes;
+    const int lane = threadIdx.x & 63;
+    const int n_el = ix.storage == PK_F16 ? ix.row_bytes / 2 : ix.row_bytes / 4;
+    float acc = 0.f;
+    for (int i = lane; i < n_el; i += 64) {
+        float v = i < ix.d ? src[i] : 0.f;
+        if (ix.storage == PK_F16) {
+            const _Float16 h = (_Float16)v;
+            reinterpret_cast<_Float16 *>(dst)[i] = h;
+            v = (float)h;
+        } else {
+            reinterpret_cast<float *>(dst)[i] = v;
+        }
+        acc += v * v;
+    }
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+    if (lane == 0) {
+        ar.norm[local] = acc;
+        ar.ids[local] = id;
+    }
+}
+
+// build: every vector takes the next slot of its list's build-time extent
+__global__ __launch_bounds__(256) void scatter_build_kernel(const DevIndex *ixp, const float *x, const int64_t *ids,
+                                                            const int32_t *assign, int64_t n, int64_t id0, uint32_t *fill)
+{
+    const DevIndex &ix = *ixp;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int64_t i = (int64_t)blockIdx.x * 4 + wave; i < n; i += (int64_t)gridDim.x * 4) {
+        const uint32_t l = (uint32_t)assign[i];
+        uint32_t slot = 0;
+        if (lane == 0) slot = atomicAdd(&fill[l], 1u);
+        slot = __shfl(slot, 0);
+        write_row(ix, l, slot, x + (size_t)i * ix.d, ids ? ids[i] : id0 + i);
+    }
+}
+
+hipError_t launch_scatter_build(const DevIndex *ix, const float *x, const int64_t *ids, const int32_t *assign, int64_t n,
+                                int64_t id0, uint32_t *fill, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    const int64_t want = (n + 3) / 4;
+    const int grid = (int)(want < 65536 ? want : 65536);
+    hipLaunchKernelGGL(scatter_build_kernel, dim3(grid), dim3(256), 0, s, ix, x, ids, assign, n, id0, fill);
+    return hipGetLastError();
+}
+
+// Insert, step 2: slot reservation for a batch of at most 1024 vectors by one workgroup.
+// Vector i takes slot list_len[l] + (number of earlier batch members of the same list), so
+// the order inside a list is the arrival order.  A vector whose slot starts a page beyond
+// the build-time extent opens a delta page.  If the arena or a list's delta table cannot
+// take the whole batch, nothing is changed, every slot is 0xffffffff and the sticky error
+// flag is set.
+__global__ __launch_bounds__(1024) void reserve_kernel(const DevIndex *ixp, const int32_t *assign, int m, uint32_t *slots,
+                                                       int32_t *assigned_out)
+{
+    __shared__ int32_t s_l[1024];
+    __shared__ uint32_t s_need, s_bad, s_page0;
+    const DevIndex &ix = *ixp;
+    const int i = threadIdx.x;
+    if (i == 0) {
+        s_need = 0;
+        s_bad = 0;
+    }
+    int32_t l = -1;
+    if (i < m) {
+        l = assign[i];
+        if (l < 0 || l >= ix.nlist) l = -1;
+    }
+    s_l[i] = l;
+    __syncthreads();
+    uint32_t rank = 0, cnt = 0;
+    if (l >= 0) {
+        for (int j = 0; j < m; ++j) {
+            const bool same = s_l[j] == l;
+            cnt += same ? 1u : 0u;
+            rank += (same && j < i) ? 1u : 0u;
+        }
+    }
+    uint32_t slot = 0xffffffffu, di = 0;
+    bool opens = false;
+    if (l >= 0) {
+        slot = ix.list_len[l] + rank;
+        const uint32_t lp = slot / (uint32_t)ix.P;
+        if (slot % (uint32_t)ix.P == 0 && lp >= ix.main_pages[l]) {
+            opens = true;
+            di = lp - ix.main_pages[l];
+            if (di >= (uint32_t)ix.max_dp) atomicOr(&s_bad, (uint32_t)kErrListFull);
+        }
+    } else if (i < m) {
+        atomicOr(&s_bad, (uint32_t)kErrListFull);
+    }
+    uint32_t my_page = 0;
+    if (opens) my_page = atomicAdd(&s_need, 1u);
+    __syncthreads();
+    if (i == 0) {
+        const uint32_t p0 = ix.ctr[0];
+        s_page0 = p0;
+        if (p0 + s_need > ix.ctr[2]) s_bad |= (uint32_t)kErrPages;
+        if (s_bad) atomicOr(&ix.ctr[1], s_bad);
+        else ix.ctr[0] = p0 + s_need;
+    }
+    __syncthreads();
+    const bool ok = s_bad == 0;
+    if (ok && opens) ix.dtab[(size_t)l * ix.max_dp + di] = s_page0 + my_page;
+    if (ok && l >= 0 && rank == cnt - 1) ix.list_len[l] = slot + 1;
+    if (i < m) {
+        slots[i] = ok ? slot : 0xffffffffu;
+        if (assigned_out) assigned_out[i] = l;
+    }
+}
+
+hipError_t launch_reserve(const DevIndex *ix, const int32_t *assign, int m, uint32_t *slots, int32_t *assigned_out,
+                          hipStream_t s)
+{
+    if (m <= 0) return hipSuccess;
+    if (m > 1024) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(reserve_kernel, dim3(1), dim3(1024), 0, s, ix, assign, m, slots, assigned_out);
+    return hipGetLastError();
+}
+
+// Insert, step 3: write the vectors into their reserved slots
+__global__ __launch_bounds__(256) void append_kernel(const DevIndex *ixp, const float *x, const int64_t *ids,
+                                                     const int32_t *assign, const uint32_t *slots, int m, int64_t id0)
+{
+    const DevIndex &ix = *ixp;
+    const int wave = threadIdx.x >> 6;
+    const int i = blockIdx.x * 4 + wave;
+    if (i >= m) return;
+    const uint32_t slot = slots[i];
+    if (slot == 0xffffffffu) return;
+    write_row(ix, (uint32_t)assign[i], slot, x + (size_t)i * ix.d, ids ? ids[i] : id0 + i);
+}
+
+hipError_t launch_append(const DevIndex *ix, const float *x, const int64_t *ids, const int32_t *assign,
+                         const uint32_t *slots, int m, int64_t id0, hipStream_t s)
+{
+    if (m <= 0) return hipSuccess;
+    hipLaunchKernelGGL(append_kernel, dim3((m + 3) / 4), dim3(256), 0, s, ix, x, ids, assign, slots, m, id0);
+    return hipGetLastError();
+}
+
+// probes[:, 0] of a top-1 coarse search -> assignment array (stride nprobe = 1 is the identity;
+// kept as a kernel so the copy stays on the stream)
+__global__ void copy_i32_kernel(const int32_t *src, int32_t *dst, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = src[i];
+}
+
+hipError_t launch_copy_i32(const int32_t *src, int32_t *dst, int64_t n, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(copy_i32_kernel, dim3((uint32_t)((n + 255) / 256)), dim3(256), 0, s, src, dst, n);
+    return hipGetLastError();
+}
+
+} // namespace pk

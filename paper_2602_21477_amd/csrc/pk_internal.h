@@ -1,0 +1,171 @@
+// Internal declarations shared by the translation units of libpancake (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "pancake.h"
+
+namespace pk {
+
+// ------------------------------------------------------------------ constants
+constexpr int kWave = 64;
+constexpr int kScanThreads = 256;     // 4 waves per workgroup in the scan kernel
+constexpr int kRowBlock = 32;         // rows one wave scores per pass (two 16-wide MFMA tiles)
+constexpr int kIterBytes = 256;       // bytes of one row consumed per inner iteration
+constexpr int kQPadBytes = 16;        // LDS row padding of the query tile (bank spread)
+constexpr int kCoarsePage = 32;       // rows per coarse tile (one wave per workgroup there)
+constexpr int kSelThreads = 256;
+constexpr int kSelVec = 4;            // candidates per thread per round
+constexpr int kSelCap = 4096;         // LDS key buffer of the select kernels (K + one round <= cap)
+constexpr int kSelChunk = 32768;      // candidates per (query, chunk) workgroup
+constexpr unsigned long long kMaxKey = ~0ull;
+
+constexpr int kErrPages = 1, kErrListFull = 2, kErrWorklist = 4;
+
+// One arena = npages pages: vectors | norms | ids, each indexed by the local page number.
+struct Arena {
+    uint32_t first_page, npages;
+    char *vec;       // [npages][P][row_bytes]
+    float *norm;     // [npages][P]
+    int64_t *ids;    // [npages][P]
+};
+
+// Device-resident description of one index (lives at the start of its first arena).
+struct DevIndex {
+    const float *cent;   // [nlist_pad][dpad32] fp32 centroid table, zero padded
+    const float *cnorm;  // [nlist_pad] squared norms (L2 only, else zeros)
+    uint32_t *list_len;  // [nlist] vectors per list
+    uint32_t *main_base; // [nlist] first page of the build-time extent
+    uint32_t *main_pages;// [nlist] pages in that extent
+    uint32_t *dtab;      // [nlist][max_dp] delta page numbers
+    uint32_t *ctr;       // [0] next free page, [1] sticky error flags, [2] pages total
+    int32_t nlist, nlist_pad, d, dpad32, P, max_dp, metric, storage;
+    int32_t row_bytes;   // padded bytes of one stored row
+    int32_t n_arenas;
+    Arena arenas[PK_MAX_ARENAS];
+};
+
+__device__ __forceinline__ const Arena &arena_of(const DevIndex &ix, uint32_t page)
+{
+    int a = 0;
+    while (a + 1 < ix.n_arenas && page >= ix.arenas[a].first_page + ix.arenas[a].npages) ++a;
+    return ix.arenas[a];
+}
+
+// physical page of logical page `lp` of list `l`
+__device__ __forceinline__ uint32_t phys_page(const DevIndex &ix, uint32_t l, uint32_t lp)
+{
+    uint32_t mp = ix.main_pages[l];
+    return lp < mp ? ix.main_base[l] + lp : ix.dtab[(size_t)l * ix.max_dp + (lp - mp)];
+}
+
+// One unit of scan work: one page of rows against one group of query slots.
+struct Tile {
+    const char *x;    // first row of the page
+    const float *xn;  // squared norms of the rows (L2), else unused
+    uint32_t row0;    // position of the page's first row in the list
+    uint32_t qbeg;    // first slot of the group in slot_query / slot_out
+    uint16_t nrows;   // rows to score (<= rows per page)
+    uint16_t qcnt;    // slots in the group (<= MQ)
+    uint32_t pad;
+};
+static_assert(sizeof(Tile) == 32, "Tile is 32 bytes");
+
+// Handles of one call, passed to kernels by value (fits the 4 KiB kernel-argument space).
+struct MultiArgs {
+    const DevIndex *ix[PK_MAX_HANDLES];
+    uint32_t qlo[PK_MAX_HANDLES + 1];   // handle a owns query rows [qlo[a], qlo[a+1])
+    uint32_t ctile[PK_MAX_HANDLES + 1]; // first coarse tile of handle a; [n] = total
+    int32_t n;
+};
+
+// --------------------------------------------------------------- launch APIs
+// (each enqueues on `s` and returns the HIP status of the launch)
+
+hipError_t launch_fill_u32(uint32_t *p, uint32_t v, size_t n, hipStream_t s);
+hipError_t launch_copy_i32(const int32_t *src, int32_t *dst, int64_t n, hipStream_t s);
+
+// queries -> storage type, zero padded rows, squared norms of the converted values
+hipError_t launch_prep_queries(const float *q, int64_t nq, int d, int storage, int row_bytes, void *qs,
+                               float *qnorm, hipStream_t s);
+
+struct ScanArgs {
+    const Tile *tiles;
+    const uint32_t *ntiles;      // device scalar
+    uint32_t *tile_ctr;          // device scalar, zero before the launch
+    const uint32_t *batch;       // device scalar: tiles taken per grab (>= 1)
+    const char *qs;              // prepared queries [nq][row_bytes]
+    const float *qnorm;          // [nq]
+    const uint32_t *slot_query;  // slot -> query row
+    const uint32_t *slot_out;    // slot -> first output element of the (query, list) pair
+    float *out;                  // values
+    int row_bytes, metric, storage, mq;
+};
+hipError_t launch_scan(const ScanArgs &a, int waves_per_wg, int grid, hipStream_t s);
+int scan_lds_bytes(int row_bytes, int mq);
+int scan_max_mq(int row_bytes, int storage, int lds_limit);
+
+struct SelectArgs {
+    const float *vals;            // candidate values
+    const uint32_t *qoff;         // [nq] first candidate of each query
+    const uint32_t *qcnt;         // [nq] candidates of each query
+    int metric, K, nchunks;
+    unsigned long long *partial;  // [nq][nchunks][K]
+};
+hipError_t launch_select_partial(const SelectArgs &a, int64_t nq, hipStream_t s);
+hipError_t launch_select_probes(const unsigned long long *partial, int nchunks, int K, int nprobe, int64_t nq,
+                                int32_t *probes, hipStream_t s);
+
+struct FinalArgs {
+    const unsigned long long *partial; // [nq][nchunks][K]
+    int nchunks, K, k, nprobe, metric;
+    const float *vals;
+    const uint32_t *qoff, *qcnt;      // candidate ranges
+    const uint32_t *pair_off;         // [nq][nprobe+1] start of each probe's segment inside the range
+    const int32_t *probes;            // [nq][nprobe]
+    const uint16_t *qagent;           // [nq] handle number
+    int64_t *out_ids;
+    float *out_dist;
+};
+hipError_t launch_select_final(const FinalArgs &a, const MultiArgs &m, int64_t nq, hipStream_t s);
+
+struct CoarseArgs {
+    int mq, scan_grid;
+    uint32_t stride;              // elements between the score rows of consecutive queries
+    uint32_t *slot_query, *slot_out;
+    uint32_t *cand_off, *cand_cnt; // [nq] score row of each query and its length (nlist of its handle)
+    uint16_t *qagent;             // [nq] out: handle number of each query
+    Tile *tiles;
+    uint32_t *scalars;            // [0] ntiles [1] tile counter [2] grab size
+};
+hipError_t launch_coarse_tiles(const CoarseArgs &a, const MultiArgs &m, hipStream_t s);
+
+struct WorklistArgs {
+    const int32_t *probes;     // [nq][nprobe]; entries outside [0, nlist) are ignored
+    const uint16_t *qagent;    // [nq]
+    int64_t nq;
+    int nprobe, n_handles, nlist_max, mq, scan_grid;
+    uint32_t *lcnt, *lstart, *lfill, *ltile; // [n_handles * nlist_max]
+    uint32_t *pair_off;        // [nq][nprobe+1]
+    uint32_t *qtot, *qoff;     // [nq]
+    uint32_t *slot_query, *slot_out; // [nq * nprobe]
+    Tile *tiles;
+    uint32_t tile_cap, cand_cap;
+    uint32_t *scalars;         // [0] ntiles [1] tile counter [2] grab size [3] total candidates
+};
+hipError_t launch_worklist(const WorklistArgs &a, const MultiArgs &m, hipStream_t s);
+
+// build / insert
+hipError_t launch_hist(const int32_t *assign, int64_t n, uint32_t *cnt, hipStream_t s);
+hipError_t launch_scatter_build(const DevIndex *ix, const float *x, const int64_t *ids, const int32_t *assign,
+                                int64_t n, int64_t id0, uint32_t *fill, hipStream_t s);
+hipError_t launch_store_centroids(const float *c, int nlist, int d, int dpad32, int nlist_pad, int metric,
+                                  float *cent, float *cnorm, hipStream_t s);
+hipError_t launch_reserve(const DevIndex *ix, const int32_t *assign, int m, uint32_t *slots, int32_t *assigned_out,
+                          hipStream_t s);
+hipError_t launch_append(const DevIndex *ix, const float *x, const int64_t *ids, const int32_t *assign,
+                         const uint32_t *slots, int m, int64_t id0, hipStream_t s);
+
+} // namespace pk

@@ -1,0 +1,225 @@
+// List scan (fine search) and centroid scoring (coarse search) for gfx950.
+//
+// Section 2.2 of the paper: the coarse step scores a query against every centroid, the
+// fine step against every vector of the probed clusters.  Both are "rows streamed from
+// HBM once, scored against a small group of queries", so one kernel serves both: a tile
+// is one page of rows (list page or a slice of the centroid table) plus a group of up to
+// MQ query slots.  Inserted vectors (Section 4.4's buffer) live in ordinary pages of the
+// list and are scored by the same tiles.
+//
+// Mapping to CDNA4.  The rows are the streaming operand and go HBM -> registers directly
+// in MFMA operand layout; the query group is staged once in LDS and re-read per pass.
+// With A = queries (M = 16 slots) and B = rows (N = 16 rows) the 16x16 accumulator puts
+// rows along lanes, so each store instruction writes 64 contiguous bytes per 16 lanes.
+// The contraction index may be permuted freely as long as A and B use the same
+// permutation, which lets every lane fetch 16 contiguous bytes per load (4 lanes cover a
+// 64-byte segment of one row, 16 rows per instruction) and feed them straight into
+// v_mfma_f32_16x16x32_f16 (fp16 storage) or four v_mfma_f32_16x16x4_f32 (fp32 storage),
+// always with fp32 accumulation.
+#include "pk_internal.h"
+
+namespace pk {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <int STORAGE>
+__device__ __forceinline__ void mfma_step(f32x4 &acc, const u32x4 &qa, const u32x4 &xb)
+{
+    if constexpr (STORAGE == PK_F16) {
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, qa), __builtin_bit_cast(half8, xb),
+                                                     acc, 0, 0, 0);
+    } else {
+        f32x4 qf = __builtin_bit_cast(f32x4, qa), xf = __builtin_bit_cast(f32x4, xb);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(qf[0], xf[0], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(qf[1], xf[1], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(qf[2], xf[2], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(qf[3], xf[3], acc, 0, 0, 0);
+    }
+}
+
+// MT = query tiles of 16 slots held in LDS (MQ = 16*MT); WAVES = waves per workgroup.
+template <int STORAGE, int MT, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void scan_kernel(ScanArgs a)
+{
+    extern __shared__ __align__(16) char smem[];
+    constexpr int MQ = MT * 16;
+    const int row_bytes = a.row_bytes;
+    const int qstride = row_bytes + kQPadBytes;
+    char *qtile = smem;
+    uint32_t *s_out = reinterpret_cast<uint32_t *>(smem + (size_t)MQ * qstride);
+    float *s_qn = reinterpret_cast<float *>(s_out + MQ);
+    uint32_t *s_misc = reinterpret_cast<uint32_t *>(s_qn + MQ);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int ln = lane & 15, lg = lane >> 4;
+    const uint32_t ntiles = *a.ntiles;
+    const uint32_t grab = *a.batch;
+    const int nit = row_bytes / kIterBytes;
+    const int chunks_per_row = row_bytes / 16;
+    const float worst = a.metric == PK_METRIC_IP ? -INFINITY : INFINITY;
+    uint32_t cur_qbeg = 0xffffffffu, cur_qcnt = 0;
+
+    for (;;) {
+        __syncthreads();
+        if (tid == 0) s_misc[0] = atomicAdd(a.tile_ctr, grab);
+        __syncthreads();
+        const uint32_t t0 = s_misc[0];
+        if (t0 >= ntiles) break; // every wave of every workgroup reaches this once the counter passes ntiles
+        const uint32_t t1 = min(t0 + grab, ntiles);
+        for (uint32_t t = t0; t < t1; ++t) {
+            const Tile *tp = a.tiles + t;
+            const char *tx = tp->x;
+            const float *txn = tp->xn;
+            const uint32_t row0 = tp->row0;
+            const uint32_t qbeg = __builtin_amdgcn_readfirstlane(tp->qbeg);
+            const uint32_t qcnt = __builtin_amdgcn_readfirstlane((uint32_t)tp->qcnt);
+            const int nrows = __builtin_amdgcn_readfirstlane((int)tp->nrows);
+            if (qbeg != cur_qbeg || qcnt != cur_qcnt) {
+                __syncthreads(); // everyone is done with the previous query group
+                const int mrows = (int)((qcnt + 15u) & ~15u);
+                for (int idx = tid; idx < mrows * chunks_per_row; idx += WAVES * 64) {
+                    const int m = idx / chunks_per_row, c = idx - m * chunks_per_row;
+                    u32x4 v = {0u, 0u, 0u, 0u};
+                    if ((uint32_t)m < qcnt)
+                        v = *reinterpret_cast<const u32x4 *>(a.qs + (size_t)a.slot_query[qbeg + m] * row_bytes +
+                                                             (size_t)c * 16);
+                    *reinterpret_cast<u32x4 *>(qtile + (size_t)m * qstride + (size_t)c * 16) = v;
+                }
+                if (tid < MQ) {
+                    const bool on = (uint32_t)tid < qcnt;
+                    s_out[tid] = on ? a.slot_out[qbeg + tid] : 0u;
+                    s_qn[tid] = on ? a.qnorm[a.slot_query[qbeg + tid]] : 0.f;
+                }
+                __syncthreads();
+                cur_qbeg = qbeg;
+                cur_qcnt = qcnt;
+            }
+            const int mt_used = (int)((qcnt + 15u) >> 4);
+            const int nrows_pad = (nrows + 15) & ~15;
+
+            for (int rb = wave; rb * kRowBlock < nrows; rb += WAVES) {
+                const int row_a = rb * kRowBlock + ln;
+                const char *p0 = tx + (size_t)row_a * row_bytes + lg * 16;
+                const char *p1 = p0 + (size_t)16 * row_bytes;
+                f32x4 acc[MT][2];
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    acc[mt][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    acc[mt][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+                u32x4 xa[2][4], xb[2][4]; // two register buffers of one iteration each
+                const char *qbase = qtile + (size_t)ln * qstride + lg * 16;
+
+#define PK_LOAD(buf, it)                                                                          \
+    _Pragma("unroll") for (int s = 0; s < 4; ++s)                                                 \
+    {                                                                                             \
+        buf[0][s] = *reinterpret_cast<const u32x4 *>(p0 + (size_t)(it) * kIterBytes + s * 64);    \
+        buf[1][s] = *reinterpret_cast<const u32x4 *>(p1 + (size_t)(it) * kIterBytes + s * 64);    \
+    }
+#define PK_COMPUTE(buf, it)                                                                       \
+    _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                             \
+    {                                                                                             \
+        if (mt < mt_used) {                                                                       \
+            const char *qrow = qbase + (size_t)mt * 16 * qstride + (size_t)(it) * kIterBytes;     \
+            _Pragma("unroll") for (int s = 0; s < 4; ++s)                                         \
+            {                                                                                     \
+                const u32x4 qa = *reinterpret_cast<const u32x4 *>(qrow + s * 64);                 \
+                mfma_step<STORAGE>(acc[mt][0], qa, buf[0][s]);                                    \
+                mfma_step<STORAGE>(acc[mt][1], qa, buf[1][s]);                                    \
+            }                                                                                     \
+        }                                                                                         \
+    }
+                PK_LOAD(xa, 0)
+                for (int it = 0; it < nit; it += 2) {
+                    if (it + 1 < nit) { PK_LOAD(xb, it + 1) }
+                    PK_COMPUTE(xa, it)
+                    if (it + 2 < nit) { PK_LOAD(xa, it + 2) }
+                    if (it + 1 < nit) { PK_COMPUTE(xb, it + 1) }
+                }
+#undef PK_LOAD
+#undef PK_COMPUTE
+
+                // epilogue: lane holds row (rb*32 + nt*16 + ln) for slots mt*16 + lg*4 + i
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt) {
+                    const int row = rb * kRowBlock + nt * 16 + ln;
+                    if (row < nrows_pad) {
+                        const bool live = row < nrows;
+                        float xn = 0.f;
+                        if (a.metric == PK_METRIC_L2 && live) xn = txn[row];
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                const int m = mt * 16 + lg * 4 + i;
+                                if ((uint32_t)m < qcnt) {
+                                    float v = acc[mt][nt][i];
+                                    if (a.metric == PK_METRIC_L2) v = fmaxf(xn - 2.f * v + s_qn[m], 0.f);
+                                    if (!live) v = worst;
+                                    a.out[(size_t)s_out[m] + row0 + row] = v;
+                                }
+                            }
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+int scan_lds_bytes(int row_bytes, int mq)
+{
+    return mq * (row_bytes + kQPadBytes) + mq * 8 + 16;
+}
+
+// Largest query group (16, 32 or 64 slots) whose LDS tile fits.  fp32 storage is held to
+// 32 slots: beyond that the fp32 MFMA rate, not HBM, would bound the scan.  Returns 0 when
+// even 16 slots do not fit.
+int scan_max_mq(int row_bytes, int storage, int lds_limit)
+{
+    const int budget = lds_limit < 100 * 1024 ? lds_limit : 100 * 1024;
+    const int cap = storage == PK_F16 ? 64 : 32;
+    int best = 0;
+    for (int mq = 16; mq <= cap; mq *= 2)
+        if (scan_lds_bytes(row_bytes, mq) <= budget) best = mq;
+    return best;
+}
+
+template <int STORAGE, int MT, int WAVES>
+static hipError_t launch_one(const ScanArgs &a, int grid, hipStream_t s)
+{
+    const int lds = scan_lds_bytes(a.row_bytes, MT * 16);
+    static int attr_bytes = 0; // per instantiation: dynamic LDS size the kernel is cleared for
+    if (lds > attr_bytes) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_kernel<STORAGE, MT, WAVES>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        attr_bytes = lds;
+    }
+    hipLaunchKernelGGL((scan_kernel<STORAGE, MT, WAVES>), dim3(grid), dim3(WAVES * 64), lds, s, a);
+    return hipGetLastError();
+}
+
+template <int STORAGE, int WAVES>
+static hipError_t launch_mt(const ScanArgs &a, int grid, hipStream_t s)
+{
+    switch (a.mq) {
+    case 16: return launch_one<STORAGE, 1, WAVES>(a, grid, s);
+    case 32: return launch_one<STORAGE, 2, WAVES>(a, grid, s);
+    case 64: return launch_one<STORAGE, 4, WAVES>(a, grid, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_scan(const ScanArgs &a, int waves_per_wg, int grid, hipStream_t s)
+{
+    if (a.row_bytes <= 0 || a.row_bytes % kIterBytes != 0) return hipErrorInvalidValue;
+    if (a.storage == PK_F16) {
+        return waves_per_wg == 1 ? launch_mt<PK_F16, 1>(a, grid, s) : launch_mt<PK_F16, 4>(a, grid, s);
+    }
+    return waves_per_wg == 1 ? launch_mt<PK_F32, 1>(a, grid, s) : launch_mt<PK_F32, 4>(a, grid, s);
+}
+
+} // namespace pk

@@ -1,0 +1,285 @@
+// Top-k selection for gfx950: best `nprobe` centroids per query (Section 2.2 coarse
+// search, "only the top-nprobe clusters are selected") and best `k` vectors per query
+// over the scored candidates of all probed lists, i.e. the merge of the per-list partial
+// results (Section 4.4: partial results are merged into the final result).
+//
+// A candidate is one 64-bit key: the value mapped to an unsigned integer whose ascending
+// order is best-first (high word) and the candidate's position inside the query's
+// candidate range (low word).  Keys are unique, so "smaller key" is a strict total order
+// and the selection is deterministic.  A workgroup streams candidates, keeps those that
+// beat the current K-th key in an LDS buffer, and re-sorts the buffer (bitonic network)
+// only when it runs full, so almost all candidates cost one compare.
+#include "pk_internal.h"
+
+namespace pk {
+
+typedef unsigned long long u64;
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint32_t order_bits(float v, int metric)
+{
+    const uint32_t b = __float_as_uint(v);
+    const uint32_t asc = b ^ ((b >> 31) ? 0xffffffffu : 0x80000000u);
+    return metric == PK_METRIC_L2 ? asc : ~asc;
+}
+
+__device__ __forceinline__ float value_of(uint32_t ob, int metric)
+{
+    const uint32_t asc = metric == PK_METRIC_L2 ? ob : ~ob;
+    const uint32_t b = (asc & 0x80000000u) ? (asc ^ 0x80000000u) : ~asc;
+    return __uint_as_float(b);
+}
+
+__device__ __forceinline__ uint32_t next_pow2(uint32_t n)
+{
+    uint32_t p = 2;
+    while (p < n) p <<= 1;
+    return p;
+}
+
+// ascending bitonic sort of keys[0, np2), np2 a power of two; all threads of the block call it
+__device__ void bitonic_sort(u64 *keys, uint32_t np2)
+{
+    for (uint32_t size = 2; size <= np2; size <<= 1) {
+        for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
+            for (uint32_t i = threadIdx.x; i < (np2 >> 1); i += blockDim.x) {
+                const uint32_t lo = 2 * i - (i & (stride - 1));
+                const uint32_t hi = lo + stride;
+                const bool up = (lo & size) == 0;
+                const u64 x = keys[lo], y = keys[hi];
+                if ((x > y) == up) {
+                    keys[lo] = y;
+                    keys[hi] = x;
+                }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// Streaming selector state.  keys: LDS [kSelCap]; cnt: LDS counter.
+struct Selector {
+    u64 *keys;
+    uint32_t *cnt;
+    int K;
+    u64 thr;
+
+    __device__ void init(u64 *k, uint32_t *c, int kk)
+    {
+        keys = k;
+        cnt = c;
+        K = kk;
+        thr = kMaxKey;
+        if (threadIdx.x == 0) *cnt = 0;
+        __syncthreads();
+    }
+    // sort what is buffered, keep the best K, tighten the threshold (block-wide)
+    __device__ void flush()
+    {
+        __syncthreads();
+        const uint32_t n = *cnt;
+        const uint32_t np2 = next_pow2(n);
+        for (uint32_t i = n + threadIdx.x; i < np2; i += blockDim.x) keys[i] = kMaxKey;
+        __syncthreads();
+        bitonic_sort(keys, np2);
+        const uint32_t kept = n < (uint32_t)K ? n : (uint32_t)K;
+        thr = kept == (uint32_t)K ? keys[K - 1] : kMaxKey;
+        __syncthreads();
+        if (threadIdx.x == 0) *cnt = kept;
+        __syncthreads();
+    }
+    // make room for one round of at most `room` pushes (block-wide)
+    __device__ void reserve(uint32_t room)
+    {
+        __syncthreads();
+        const uint32_t n = *cnt; // read by everyone before anyone pushes again
+        __syncthreads();
+        const uint32_t limit = (uint32_t)K + room <= 2048u ? 2048u : (uint32_t)kSelCap;
+        if (n + room > limit) flush();
+    }
+    __device__ __forceinline__ void push(u64 key)
+    {
+        if (key < thr) keys[atomicAdd(cnt, 1u)] = key;
+    }
+};
+
+__global__ __launch_bounds__(kSelThreads) void select_partial_kernel(SelectArgs a)
+{
+    __shared__ u64 keys[kSelCap];
+    __shared__ uint32_t s_cnt;
+    const uint32_t q = blockIdx.y, c = blockIdx.x;
+    const uint32_t base = a.qoff[q];
+    const uint32_t total = a.qcnt[q];
+    const uint32_t beg = c * (uint32_t)kSelChunk;
+    const uint32_t end = min(beg + (uint32_t)kSelChunk, total);
+    u64 *out = a.partial + ((size_t)q * a.nchunks + c) * a.K;
+
+    Selector sel;
+    sel.init(keys, &s_cnt, a.K);
+    const float *v = a.vals + base;
+    constexpr uint32_t kRound = kSelThreads * kSelVec;
+    for (uint32_t r = beg; r < end; r += kRound) {
+        sel.reserve(kRound);
+        const uint32_t p = r + threadIdx.x * kSelVec;
+        if (p < end) {
+            const f32x4 x = *reinterpret_cast<const f32x4 *>(v + p);
+#pragma unroll
+            for (int j = 0; j < kSelVec; ++j)
+                if (p + j < end) sel.push(((u64)order_bits(x[j], a.metric) << 32) | (p + j));
+        }
+    }
+    sel.flush();
+    const uint32_t n = s_cnt;
+    for (uint32_t i = threadIdx.x; i < (uint32_t)a.K; i += blockDim.x) out[i] = i < n ? keys[i] : kMaxKey;
+}
+
+// merge `nchunks` sorted partial lists of one query; leaves the best K sorted in keys[], returns count
+__device__ uint32_t merge_partials(Selector &sel, const u64 *part, int nchunks, int K)
+{
+    const uint32_t total = (uint32_t)nchunks * (uint32_t)K;
+    for (uint32_t r = 0; r < total; r += kSelThreads) {
+        sel.reserve(kSelThreads);
+        const uint32_t p = r + threadIdx.x;
+        if (p < total) {
+            const u64 key = part[p];
+            if (key != kMaxKey) sel.push(key);
+        }
+    }
+    sel.flush();
+    return *sel.cnt;
+}
+
+__global__ __launch_bounds__(kSelThreads) void select_probes_kernel(const u64 *partial, int nchunks, int K, int nprobe,
+                                                                    int32_t *probes)
+{
+    __shared__ u64 keys[kSelCap];
+    __shared__ uint32_t s_cnt;
+    const uint32_t q = blockIdx.x;
+    Selector sel;
+    sel.init(keys, &s_cnt, K);
+    merge_partials(sel, partial + (size_t)q * nchunks * K, nchunks, K);
+    for (int r = threadIdx.x; r < nprobe; r += blockDim.x) probes[(size_t)q * nprobe + r] = (int32_t)(uint32_t)keys[r];
+}
+
+// position inside the query's candidate range -> id stored in the list page
+__device__ int64_t resolve_id(const FinalArgs &a, const MultiArgs &h, uint32_t q, uint32_t pos)
+{
+    const uint32_t *po = a.pair_off + (size_t)q * (a.nprobe + 1);
+    int lo = 0, hi = a.nprobe - 1;
+    while (lo < hi) { // largest r with po[r] <= pos
+        const int mid = (lo + hi + 1) >> 1;
+        if (po[mid] <= pos) lo = mid;
+        else hi = mid - 1;
+    }
+    const uint32_t row = pos - po[lo];
+    const uint32_t list = (uint32_t)a.probes[(size_t)q * a.nprobe + lo];
+    const DevIndex &ix = *h.ix[a.qagent[q]];
+    const uint32_t lp = row / (uint32_t)ix.P;
+    const uint32_t pg = phys_page(ix, list, lp);
+    const Arena &ar = arena_of(ix, pg);
+    return ar.ids[(size_t)(pg - ar.first_page) * ix.P + (row - lp * ix.P)];
+}
+
+__global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, MultiArgs h)
+{
+    __shared__ u64 keys[kSelCap];
+    __shared__ uint32_t s_cnt;
+    __shared__ int64_t s_id[PK_MAX_K];
+    __shared__ long long s_red[kSelThreads / 64];
+    __shared__ long long s_pick;
+    const uint32_t q = blockIdx.x;
+    const int k = a.k;
+    Selector sel;
+    sel.init(keys, &s_cnt, a.K);
+    const uint32_t n = merge_partials(sel, a.partial + (size_t)q * a.nchunks * a.K, a.nchunks, a.K);
+
+    // entries carrying the padding value are not candidates
+    const uint32_t worst = order_bits(a.metric == PK_METRIC_IP ? -INFINITY : INFINITY, a.metric);
+    uint32_t n_valid = 0;
+    for (uint32_t i = 0; i < n; ++i) { // n <= K, uniform loop
+        if ((uint32_t)(keys[i] >> 32) >= worst) break;
+        ++n_valid;
+    }
+    const uint32_t kk = n_valid < (uint32_t)k ? n_valid : (uint32_t)k;
+    for (uint32_t i = threadIdx.x; i < kk; i += blockDim.x) s_id[i] = resolve_id(a, h, q, (uint32_t)keys[i]);
+    __syncthreads();
+
+    // Equal values must come in ascending id order.  If the tie group of the k-th value
+    // reaches past position k, its members inside the top k are the lowest ids of the
+    // whole group, which may include candidates no partial list kept: rescan for them.
+    if (n_valid > (uint32_t)k && (uint32_t)(keys[k - 1] >> 32) == (uint32_t)(keys[k] >> 32)) {
+        const uint32_t tau = (uint32_t)(keys[k - 1] >> 32);
+        uint32_t nb = 0;
+        while (nb < (uint32_t)k && (uint32_t)(keys[nb] >> 32) < tau) ++nb;
+        const uint32_t base = a.qoff[q], total = a.qcnt[q];
+        long long last = INT64_MIN;
+        for (uint32_t t = nb; t < (uint32_t)k; ++t) {
+            long long best = INT64_MAX;
+            for (uint32_t p = threadIdx.x; p < total; p += blockDim.x) {
+                if (order_bits(a.vals[base + p], a.metric) == tau) {
+                    const long long id = resolve_id(a, h, q, p);
+                    if (id > last && id < best) best = id;
+                }
+            }
+            for (int off = 32; off > 0; off >>= 1) {
+                const long long o = __shfl_xor(best, off);
+                best = o < best ? o : best;
+            }
+            if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = best;
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                long long b = s_red[0];
+                for (int w = 1; w < kSelThreads / 64; ++w) b = s_red[w] < b ? s_red[w] : b;
+                s_pick = b;
+                s_id[t] = b;
+                keys[t] = ((u64)tau << 32) | (uint32_t)t; // keeps the value; the low word is no longer used
+            }
+            __syncthreads();
+            last = s_pick;
+            __syncthreads();
+        }
+    }
+
+    // final order: (value key, id) ascending; ranks are unique because ids are
+    for (uint32_t i = threadIdx.x; i < (uint32_t)k; i += blockDim.x) {
+        if (i < kk) {
+            const uint32_t ki = (uint32_t)(keys[i] >> 32);
+            const int64_t idi = s_id[i];
+            uint32_t rank = 0;
+            for (uint32_t j = 0; j < kk; ++j) {
+                const uint32_t kj = (uint32_t)(keys[j] >> 32);
+                rank += (kj < ki || (kj == ki && s_id[j] < idi)) ? 1u : 0u;
+            }
+            a.out_ids[(size_t)q * k + rank] = idi;
+            a.out_dist[(size_t)q * k + rank] = value_of(ki, a.metric);
+        } else {
+            a.out_ids[(size_t)q * k + i] = -1;
+            a.out_dist[(size_t)q * k + i] = a.metric == PK_METRIC_IP ? -INFINITY : INFINITY;
+        }
+    }
+}
+
+hipError_t launch_select_partial(const SelectArgs &a, int64_t nq, hipStream_t s)
+{
+    if (nq <= 0) return hipSuccess;
+    hipLaunchKernelGGL(select_partial_kernel, dim3(a.nchunks, (uint32_t)nq), dim3(kSelThreads), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_select_probes(const unsigned long long *partial, int nchunks, int K, int nprobe, int64_t nq,
+                                int32_t *probes, hipStream_t s)
+{
+    if (nq <= 0) return hipSuccess;
+    hipLaunchKernelGGL(select_probes_kernel, dim3((uint32_t)nq), dim3(kSelThreads), 0, s, partial, nchunks, K, nprobe,
+                       probes);
+    return hipGetLastError();
+}
+
+hipError_t launch_select_final(const FinalArgs &a, const MultiArgs &h, int64_t nq, hipStream_t s)
+{
+    if (nq <= 0) return hipSuccess;
+    hipLaunchKernelGGL(select_final_kernel, dim3((uint32_t)nq), dim3(kSelThreads), 0, s, a, h);
+    return hipGetLastError();
+}
+
+} // namespace pk

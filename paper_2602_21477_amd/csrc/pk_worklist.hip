@@ -1,0 +1,282 @@
+// Query preparation and work-list construction (device side, no host round trip).
+//
+// Section 5 of the paper batches operations; Section 3.2 keeps one index per agent and
+// Section 4.4 notes that a per-cluster GPU launch is dominated by launch cost.  Here one
+// batch (possibly addressed to many agents' indexes) becomes ONE list of fixed-size
+// tiles: the (query, probed list) pairs are grouped by list, every list is cut into its
+// pages and every page is paired with groups of at most MQ of the queries that probe it.
+// Lists therefore are read once per batch, not once per query, and a 400 k-vector list
+// is as good a citizen as a 50-vector one.
+#include "pk_internal.h"
+
+namespace pk {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------- small utilities
+
+__global__ void fill_u32_kernel(uint32_t *p, uint32_t v, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
+hipError_t launch_fill_u32(uint32_t *p, uint32_t v, size_t n, hipStream_t s)
+{
+    if (n == 0) return hipSuccess;
+    const int grid = (int)((n + 255) / 256 < 1024 ? (n + 255) / 256 : 1024);
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(grid), dim3(256), 0, s, p, v, n);
+    return hipGetLastError();
+}
+
+// exclusive scan of in[0,n) into out[0,n) by one workgroup of 1024 threads; returns the total
+__device__ uint32_t block_exscan(const uint32_t *in, uint32_t *out, uint32_t n, uint32_t *s_wave /*[17]*/)
+{
+    uint32_t carry = 0;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    for (uint32_t base = 0; base < n; base += blockDim.x) {
+        const uint32_t i = base + threadIdx.x;
+        const uint32_t v = i < n ? in[i] : 0u;
+        uint32_t x = v;
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t y = __shfl_up(x, off);
+            if (lane >= off) x += y;
+        }
+        if (lane == 63) s_wave[wave] = x;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t acc = 0;
+            for (int w = 0; w < nwaves; ++w) {
+                const uint32_t t = s_wave[w];
+                s_wave[w] = acc;
+                acc += t;
+            }
+            s_wave[16] = acc;
+        }
+        __syncthreads();
+        if (i < n) out[i] = carry + s_wave[wave] + x - v;
+        carry += s_wave[16];
+        __syncthreads();
+    }
+    return carry;
+}
+
+// ------------------------------------------------------------ query preparation
+
+// one workgroup per query: convert to the storage type, zero pad to row_bytes, squared norm
+// of the converted values (fp32 sum)
+__global__ __launch_bounds__(256) void prep_queries_kernel(const float *q, int d, int storage, int row_bytes, char *qs,
+                                                           float *qnorm)
+{
+    __shared__ float s_part[4];
+    const size_t row = blockIdx.x;
+    const float *src = q + row * d;
+    const int n_el = storage == PK_F16 ? row_bytes / 2 : row_bytes / 4;
+    float acc = 0.f;
+    for (int i = threadIdx.x; i < n_el; i += blockDim.x) {
+        float v = i < d ? src[i] : 0.f;
+        if (storage == PK_F16) {
+            const _Float16 h = (_Float16)v; // round to nearest even
+            reinterpret_cast<_Float16 *>(qs + row * row_bytes)[i] = h;
+            v = (float)h;
+        } else {
+            reinterpret_cast<float *>(qs + row * row_bytes)[i] = v;
+        }
+        acc += v * v;
+    }
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+    if ((threadIdx.x & 63) == 0) s_part[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) qnorm[row] = s_part[0] + s_part[1] + s_part[2] + s_part[3];
+}
+
+hipError_t launch_prep_queries(const float *q, int64_t nq, int d, int storage, int row_bytes, void *qs, float *qnorm,
+                               hipStream_t s)
+{
+    if (nq <= 0) return hipSuccess;
+    hipLaunchKernelGGL(prep_queries_kernel, dim3((uint32_t)nq), dim3(256), 0, s, q, d, storage, row_bytes,
+                       static_cast<char *>(qs), qnorm);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ coarse tiles
+
+// Tiles of the coarse step: handle a's centroid table in slices of kCoarsePage rows, times
+// groups of mq of its queries.  Slots are the queries themselves (slot i = query i).
+__global__ void coarse_tiles_kernel(CoarseArgs a, MultiArgs m)
+{
+    const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
+    const uint32_t nq = m.qlo[m.n];
+    if (t < nq) {
+        int h = 0;
+        while (h + 1 < m.n && t >= m.qlo[h + 1]) ++h;
+        a.slot_query[t] = t;
+        a.slot_out[t] = t * a.stride;
+        a.cand_off[t] = t * a.stride;
+        a.cand_cnt[t] = (uint32_t)m.ix[h]->nlist;
+        a.qagent[t] = (uint16_t)h;
+    }
+    if (t == 0) {
+        a.scalars[0] = m.ctile[m.n];
+        a.scalars[1] = 0;
+        uint32_t g = m.ctile[m.n] / (uint32_t)(a.scan_grid * 4);
+        a.scalars[2] = g < 1 ? 1 : (g > 8 ? 8 : g);
+    }
+    if (t >= m.ctile[m.n]) return;
+    int h = 0;
+    while (h + 1 < m.n && t >= m.ctile[h + 1]) ++h;
+    const DevIndex &ix = *m.ix[h];
+    const uint32_t pages = (uint32_t)ix.nlist_pad / kCoarsePage;
+    const uint32_t local = t - m.ctile[h];
+    const uint32_t g = local / pages, p = local - g * pages;
+    const uint32_t nqa = m.qlo[h + 1] - m.qlo[h];
+    Tile tl;
+    tl.x = reinterpret_cast<const char *>(ix.cent) + (size_t)p * kCoarsePage * ix.dpad32 * 4;
+    tl.xn = ix.cnorm + (size_t)p * kCoarsePage;
+    tl.row0 = p * kCoarsePage;
+    tl.qbeg = m.qlo[h] + g * a.mq;
+    const uint32_t left = (uint32_t)ix.nlist - p * kCoarsePage;
+    tl.nrows = (uint16_t)(left < (uint32_t)kCoarsePage ? left : kCoarsePage);
+    const uint32_t ql = nqa - g * a.mq;
+    tl.qcnt = (uint16_t)(ql < (uint32_t)a.mq ? ql : a.mq);
+    tl.pad = 0;
+    a.tiles[t] = tl;
+}
+
+hipError_t launch_coarse_tiles(const CoarseArgs &a, const MultiArgs &m, hipStream_t s)
+{
+    const uint32_t n = m.ctile[m.n] > m.qlo[m.n] ? m.ctile[m.n] : m.qlo[m.n];
+    hipLaunchKernelGGL(coarse_tiles_kernel, dim3((n + 255) / 256 + 1), dim3(256), 0, s, a, m);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- list work list
+
+// per query: count the pairs per list, lay the query's candidate range out probe by probe
+__global__ __launch_bounds__(256) void wl_count_kernel(WorklistArgs a, MultiArgs m)
+{
+    __shared__ uint32_t s_len[PK_MAX_NPROBE];
+    const uint32_t q = blockIdx.x;
+    const uint32_t ag = a.qagent[q];
+    const DevIndex &ix = *m.ix[ag];
+    for (int r = threadIdx.x; r < a.nprobe; r += blockDim.x) {
+        const uint32_t l = (uint32_t)a.probes[(size_t)q * a.nprobe + r];
+        uint32_t len = 0;
+        if (l < (uint32_t)ix.nlist) {
+            atomicAdd(&a.lcnt[(size_t)ag * a.nlist_max + l], 1u);
+            len = (ix.list_len[l] + 15u) & ~15u; // segments are padded to the 16-row MFMA tile
+        }
+        s_len[r] = len;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t acc = 0;
+        uint32_t *po = a.pair_off + (size_t)q * (a.nprobe + 1);
+        for (int r = 0; r < a.nprobe; ++r) {
+            po[r] = acc;
+            acc += s_len[r];
+        }
+        po[a.nprobe] = acc;
+        a.qtot[q] = acc;
+    }
+}
+
+// one workgroup: offsets of the queries' candidate ranges, of the lists' slot ranges and tile ranges
+__global__ __launch_bounds__(1024) void wl_scan_kernel(WorklistArgs a, MultiArgs m)
+{
+    __shared__ uint32_t s_wave[17];
+    const uint32_t total = block_exscan(a.qtot, a.qoff, (uint32_t)a.nq, s_wave);
+    const uint32_t nl = (uint32_t)a.n_handles * (uint32_t)a.nlist_max;
+    block_exscan(a.lcnt, a.lstart, nl, s_wave);
+    // tiles per list -> ltile (in place: first the counts, then their exclusive scan)
+    for (uint32_t gl = threadIdx.x; gl < nl; gl += blockDim.x) {
+        const uint32_t h = gl / (uint32_t)a.nlist_max, l = gl - h * (uint32_t)a.nlist_max;
+        uint32_t nt = 0;
+        const uint32_t c = a.lcnt[gl];
+        if (c > 0) {
+            const DevIndex &ix = *m.ix[h];
+            const uint32_t pages = (ix.list_len[l] + (uint32_t)ix.P - 1) / (uint32_t)ix.P;
+            nt = pages * ((c + (uint32_t)a.mq - 1) / (uint32_t)a.mq);
+        }
+        a.lfill[gl] = nt;
+    }
+    __syncthreads();
+    const uint32_t ntiles = block_exscan(a.lfill, a.ltile, nl, s_wave);
+    __syncthreads();
+    for (uint32_t gl = threadIdx.x; gl < nl; gl += blockDim.x) a.lfill[gl] = 0;
+    if (threadIdx.x == 0) {
+        uint32_t nt = ntiles;
+        if (ntiles > a.tile_cap || total > a.cand_cap) {
+            // cannot happen while the host bounds hold; refuse to scan rather than overrun
+            nt = 0;
+            atomicOr(&m.ix[0]->ctr[1], (uint32_t)kErrWorklist);
+        }
+        a.scalars[0] = nt;
+        a.scalars[1] = 0;
+        uint32_t g = nt / (uint32_t)(a.scan_grid * 4);
+        a.scalars[2] = g < 1 ? 1 : (g > 8 ? 8 : g);
+        a.scalars[3] = total;
+    }
+}
+
+// slots: every (query, probe) pair takes the next free slot of its list
+__global__ void wl_slots_kernel(WorklistArgs a, MultiArgs m)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (size_t)a.nq * a.nprobe) return;
+    const uint32_t q = (uint32_t)(i / a.nprobe), r = (uint32_t)(i - (size_t)q * a.nprobe);
+    const uint32_t ag = a.qagent[q];
+    if ((uint32_t)a.probes[i] >= (uint32_t)m.ix[ag]->nlist) return;
+    const size_t gl = (size_t)ag * a.nlist_max + (uint32_t)a.probes[i];
+    const uint32_t slot = a.lstart[gl] + atomicAdd(&a.lfill[gl], 1u);
+    a.slot_query[slot] = q;
+    a.slot_out[slot] = a.qoff[q] + a.pair_off[(size_t)q * (a.nprobe + 1) + r];
+}
+
+// tiles: one wave per list; tile order inside a list is [query group][page], so that
+// neighbouring tiles share their query group
+__global__ __launch_bounds__(64) void wl_tiles_kernel(WorklistArgs a, MultiArgs m)
+{
+    const uint32_t gl = blockIdx.x;
+    const uint32_t c = a.lcnt[gl];
+    if (c == 0) return;
+    if (a.scalars[0] == 0) return; // overflow guard tripped
+    const uint32_t h = gl / (uint32_t)a.nlist_max, l = gl - h * (uint32_t)a.nlist_max;
+    const DevIndex &ix = *m.ix[h];
+    const uint32_t len = ix.list_len[l];
+    const uint32_t P = (uint32_t)ix.P;
+    const uint32_t pages = (len + P - 1) / P;
+    const uint32_t groups = (c + (uint32_t)a.mq - 1) / (uint32_t)a.mq;
+    const uint32_t t0 = a.ltile[gl];
+    for (uint32_t j = threadIdx.x; j < pages * groups; j += blockDim.x) {
+        const uint32_t g = j / pages, p = j - g * pages;
+        const uint32_t pg = phys_page(ix, l, p);
+        const Arena &ar = arena_of(ix, pg);
+        const size_t local = pg - ar.first_page;
+        Tile tl;
+        tl.x = ar.vec + local * P * (size_t)ix.row_bytes;
+        tl.xn = ar.norm + local * P;
+        tl.row0 = p * P;
+        tl.qbeg = a.lstart[gl] + g * a.mq;
+        const uint32_t left = len - p * P;
+        tl.nrows = (uint16_t)(left < P ? left : P);
+        const uint32_t ql = c - g * a.mq;
+        tl.qcnt = (uint16_t)(ql < (uint32_t)a.mq ? ql : a.mq);
+        tl.pad = 0;
+        a.tiles[t0 + j] = tl;
+    }
+}
+
+hipError_t launch_worklist(const WorklistArgs &a, const MultiArgs &m, hipStream_t s)
+{
+    const uint32_t nl = (uint32_t)a.n_handles * (uint32_t)a.nlist_max;
+    hipError_t e = launch_fill_u32(a.lcnt, 0u, nl, s);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(wl_count_kernel, dim3((uint32_t)a.nq), dim3(256), 0, s, a, m);
+    hipLaunchKernelGGL(wl_scan_kernel, dim3(1), dim3(1024), 0, s, a, m);
+    const size_t pairs = (size_t)a.nq * a.nprobe;
+    hipLaunchKernelGGL(wl_slots_kernel, dim3((uint32_t)((pairs + 255) / 256)), dim3(256), 0, s, a, m);
+    hipLaunchKernelGGL(wl_tiles_kernel, dim3(nl), dim3(64), 0, s, a, m);
+    return hipGetLastError();
+}
+
+} // namespace pk

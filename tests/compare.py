@@ -4,11 +4,11 @@ Rule (north star + the readings listed in the design doc):
   * values: |g - r| <= tol * max(|r|, scale) position by position, where scale is
     ||q||*||x|| for inner product and ||q||^2 + ||x||^2 for squared L2 (a purely
     relative test is meaningless at the self-match value 0);
-  * ids: the oracle row (extended past k) is cut into tie groups -- runs whose
-    adjacent values differ by no more than the tolerance.  Inside a group that
-    lies wholly in the top k the GPU ids must be a permutation of the oracle's;
-    the group straddling position k may contribute any of its members; every
-    other position is exact;
+  * ids: position j must hold the oracle's j-th id, unless another candidate's
+    oracle value lies within the tolerance of the oracle's j-th value -- then that
+    candidate is accepted too (the oracle row is extended past k so that such
+    candidates can be looked up); no id may repeat.  So ids are exact wherever
+    the value gap exceeds the tolerance, at position k and everywhere else;
   * candidates with exactly equal GPU values must come in ascending id order;
   * padding (id -1, value -inf / +inf) must agree exactly.
 """
@@ -55,25 +55,22 @@ def check_row(ids_g, val_g, ids_o, val_o, k, tol, scale, metric, where=""):
         if val_g[j] == val_g[j - 1]:
             assert ids_g[j] > ids_g[j - 1], f"{where} pos {j}: equal values not in ascending id order"
     assert len(set(ids_g[:kk].tolist())) == kk, f"{where}: repeated id in GPU row"
-    # tie groups over the oracle's valid entries
-    a = 0
-    while a < kk:
-        b = a + 1
-        while b < n_valid and abs(val_o[b] - val_o[b - 1]) <= _tol_at(val_o[b - 1], tol, scale):
-            b += 1
-        group = set(ids_o[a:b].tolist())
-        if b <= kk:
-            got = set(ids_g[a:b].tolist())
-            assert got == group, f"{where} pos [{a},{b}): ids {sorted(got)} != oracle group {sorted(group)}"
-            if b - a == 1:
-                exact += 1
-        else:
-            # straddles position k: the oracle row must show the whole group
-            assert b < kx or n_valid < kx, (
-                f"{where}: tie group at the k boundary runs past the oracle's extended row; raise kx")
-            got = set(ids_g[a:kk].tolist())
-            assert got <= group, f"{where} pos [{a},{kk}): ids {sorted(got - group)} not in boundary tie group"
-        a = b
+    # ids: exact, or a candidate whose oracle value is within tolerance of the j-th oracle value
+    where_o = {int(v): i for i, v in enumerate(ids_o[:n_valid].tolist())}
+    for j in range(kk):
+        if ids_g[j] == ids_o[j]:
+            exact += 1
+            continue
+        tolj = _tol_at(val_o[j], tol, scale)
+        pos = where_o.get(int(ids_g[j]))
+        if pos is None:
+            assert n_valid == kx and abs(val_o[kx - 1] - val_o[j]) <= tolj, (
+                f"{where} pos {j}: id {ids_g[j]} is not among the oracle's {n_valid} best "
+                f"(oracle has {ids_o[j]} with value {val_o[j]!r})")
+            raise AssertionError(f"{where} pos {j}: near-tie run reaches past the oracle's extended row; raise kx")
+        assert abs(val_o[pos] - val_o[j]) <= tolj, (
+            f"{where} pos {j}: id {ids_g[j]} (oracle value {val_o[pos]!r}, oracle rank {pos}) where the oracle "
+            f"has id {ids_o[j]} (value {val_o[j]!r}); gap exceeds the tolerance")
     return exact
 
 
@@ -98,23 +95,19 @@ def check_probes(probes_g, probes_o_ext, scores_o, nprobe, tol, scale, where="")
 
 
 def check_row_ids_only(ids_g, ids_o, val_o, k, tol, scale, where=""):
-    """Tie-group id check without GPU values (used for probe lists and assignments)."""
+    """The id rule of check_row without GPU values (probe lists, assignments).  ids_o / val_o: the
+    oracle's full ranking and the values in that order."""
     ids_g = np.asarray(ids_g)
-    n_valid = len(ids_o)
     assert len(set(ids_g.tolist())) == len(ids_g), f"{where}: repeated id"
-    a = 0
-    while a < k:
-        b = a + 1
-        while b < n_valid and abs(val_o[b] - val_o[b - 1]) <= _tol_at(val_o[b - 1], tol, scale):
-            b += 1
-        group = set(np.asarray(ids_o[a:b]).tolist())
-        if b <= k:
-            got = set(ids_g[a:b].tolist())
-            assert got == group, f"{where} pos [{a},{b}): {sorted(got)} != oracle group {sorted(group)}"
-        else:
-            got = set(ids_g[a:k].tolist())
-            assert got <= group, f"{where} pos [{a},{k}): {sorted(got - group)} not in boundary tie group"
-        a = b
+    where_o = {int(v): i for i, v in enumerate(np.asarray(ids_o).tolist())}
+    for j in range(k):
+        if ids_g[j] == ids_o[j]:
+            continue
+        pos = where_o.get(int(ids_g[j]))
+        assert pos is not None, f"{where} pos {j}: id {ids_g[j]} unknown to the oracle"
+        assert abs(val_o[pos] - val_o[j]) <= _tol_at(val_o[j], tol, scale), (
+            f"{where} pos {j}: {ids_g[j]} (oracle value {val_o[pos]!r}, rank {pos}) vs oracle {ids_o[j]} "
+            f"(value {val_o[j]!r}); gap exceeds the tolerance")
 
 
 def recall_at(ids_found, ids_true, k):

@@ -42,8 +42,16 @@ def test_equal_values_need_ascending_ids():
         check_row([8, 2], [1.0, 1.0], ids_o, val_o, 2, 1e-4, 1.0, IP)
 
 
+def test_missing_id_needs_a_longer_oracle_row():
+    ids_o = np.array([5, 3, 9]); val_o = np.array([0.5, 0.40001, 0.4])
+    with pytest.raises(AssertionError, match="raise kx"):
+        check_row([5, 77], [0.5, 0.4], ids_o, val_o, 2, 1e-4, 1.0, IP)
+    with pytest.raises(AssertionError, match="not among"):
+        check_row([77, 3], [0.5, 0.4], ids_o, val_o, 2, 1e-4, 1.0, IP)
+
+
 def test_ids_only_variant():
-    ids_o = np.array([4, 1, 6, 2]); val_o = np.array([9.0, 8.0, 7.99999, 3.0])
+    ids_o = np.array([4, 1, 6, 2]); val_o = np.array([9.0, 8.0, 7.9995, 3.0])
     check_row_ids_only(np.array([4, 6]), ids_o, val_o, 2, 1e-4, 1.0)
     with pytest.raises(AssertionError):
         check_row_ids_only(np.array([4, 2]), ids_o, val_o, 2, 1e-4, 1.0)

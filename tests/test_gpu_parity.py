@@ -1,0 +1,287 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by element.
+
+Sizes are chosen so the oracle finishes in seconds while the scan still crosses several
+pages per list, several query groups and ragged tails.  Bar: ids exact outside near-ties,
+values within 1e-4 relative (fp32 storage) / 1e-2 (fp16 storage); see tests/compare.py.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from compare import check_results, recall_at
+from gpu_util import KX, Pair, dev, make_pair
+from paper_2602_21477_amd import binding as B
+from paper_2602_21477_amd import workload as W
+
+pytestmark = pytest.mark.gpu
+
+IP, L2 = B.PK_METRIC_IP, B.PK_METRIC_L2
+F32, F16 = B.PK_F32, B.PK_F16
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+@pytest.fixture(scope="module")
+def tiny(gpu_device):
+    """Config 1: 20 000 x 128, 64 lists from 10 Lloyd iterations; built once per variant."""
+    cache = {}
+
+    def get(metric, storage):
+        key = (metric, storage)
+        if key not in cache:
+            say(f"build tiny index metric={metric} storage={storage}")
+            cache[key] = make_pair(W.C1, metric=metric, storage=storage)[0]
+        return cache[key]
+
+    yield get
+    for p in cache.values():
+        p.close()
+
+
+@pytest.mark.parametrize("storage", [F32, F16])
+@pytest.mark.parametrize("metric", [IP, L2])
+def test_build_lists_match_oracle(tiny, metric, storage):
+    p = tiny(metric, storage)
+    glen = p.gpu.list_lengths()
+    olen = p.orc.list_lengths()
+    st = p.gpu.stats()
+    assert st.n_total == 20000 and st.device_error == 0
+    assert glen.sum() == 20000
+    # assignment flips need a centroid near-tie; on this mixture none is expected
+    assert np.array_equal(glen, olen)
+
+
+@pytest.mark.parametrize("storage", [F32, F16])
+@pytest.mark.parametrize("metric", [IP, L2])
+def test_scan_with_oracle_probes(tiny, metric, storage):
+    p = tiny(metric, storage)
+    q = W.queries(W.C1, 0)
+    probes = p.orc.coarse(q, 8)
+    say(f"scan parity metric={metric} storage={storage} nq={len(q)}")
+    exact = p.check_scan(q, 10, probes)
+    assert exact >= 0.5 * q.shape[0] * 10  # positions that are not part of any near-tie group
+
+
+@pytest.mark.parametrize("metric", [IP, L2])
+def test_coarse_probe_lists(tiny, metric):
+    p = tiny(metric, F32)
+    q = W.queries(W.C1, 1)
+    for nprobe in (1, 8, 64):
+        say(f"coarse parity metric={metric} nprobe={nprobe}")
+        p.check_coarse(q, nprobe)
+
+
+@pytest.mark.parametrize("storage", [F32, F16])
+@pytest.mark.parametrize("metric", [IP, L2])
+def test_search_end_to_end_and_recall(tiny, metric, storage):
+    p = tiny(metric, storage)
+    q = W.queries(W.C1, 2)
+    say(f"search parity metric={metric} storage={storage}")
+    agree = p.check_search(q, 10, 8)
+    assert agree > 0.98
+    gi, _ = p.gpu.search(dev(q), 10, 8)
+    bi, _ = oracle.bruteforce(p.x, q, 10, metric)
+    assert recall_at(gi.cpu().numpy(), bi, 10) >= 0.9
+
+
+@pytest.mark.parametrize("metric", [IP, L2])
+def test_full_probe_equals_exact_search(tiny, metric):
+    p = tiny(metric, F32)
+    q = W.queries(W.C1, 3, nq=32)
+    gi, gv = p.gpu.search(dev(q), 20, 64)
+    bi, bv = oracle.bruteforce(p.x, q, 20 + KX, metric)
+    check_results(gi.cpu().numpy(), gv.cpu().numpy(), bi, bv, 20, p.tol, p.scale(q), metric, where="nprobe=nlist")
+
+
+@pytest.mark.parametrize("storage", [F32, F16])
+@pytest.mark.parametrize("metric", [IP, L2])
+def test_interleaved_inserts_and_searches(gpu_device, metric, storage):
+    """Config 1 stream: 32 rounds of {insert one fresh vector; search 8 queries + the vector itself}."""
+    p, cfg = make_pair(W.C1, metric=metric, storage=storage, insert_reserve=4096)
+    n0 = cfg.n
+    try:
+        for r in range(32):
+            x = W.inserts(cfg, r, 1)
+            say(f"insert round {r} metric={metric} storage={storage}")
+            p.insert_both(x, where=f"round {r}")
+            xs = x.astype(np.float16).astype(np.float32) if storage == F16 else x
+            q = np.concatenate([W.queries(cfg, 100 + r, 8), xs])
+            p.check_search(q, 10, 8, where=f"round {r}")
+            gi, gv = p.gpu.search(dev(xs), 1, 1)
+            assert int(gi[0, 0]) == n0 + r  # the vector's list is the rank-1 probe of itself
+            v = float(gv[0, 0])
+            if metric == L2:
+                assert abs(v) <= p.tol * float(p.scale(xs)[0])
+            else:
+                assert abs(v - float((xs.astype(np.float64) ** 2).sum())) <= p.tol
+        st = p.gpu.stats()
+        assert st.n_total == n0 + 32 and st.n_inserted == 32 and st.device_error == 0
+        assert np.array_equal(p.gpu.list_lengths(), p.orc.list_lengths())
+    finally:
+        p.close()
+
+
+def test_batch_inserts_grow_delta_pages_and_match_rebuild(gpu_device):
+    """Small pages so lists open many delta pages; build(n) + inserts == build(n + m) (same results)."""
+    cfg = W.scaled(W.C1, n=6000)
+    x = W.vectors(cfg, 0, cfg.n)
+    cent = W.train_centroids(cfg, x)
+    extra = np.concatenate([W.inserts(cfg, b, 37) for b in range(40)])  # 1480 vectors
+    a = Pair(x, cent, IP, F32, page_vecs=32, insert_reserve=4000)
+    b = Pair(np.concatenate([x, extra]), cent, IP, F32, page_vecs=32)
+    try:
+        for s in range(0, len(extra), 37):
+            a.insert_both(extra[s:s + 37], where=f"batch {s // 37}")
+        q = W.queries(cfg, 7, 64)
+        ai, av = a.gpu.search(dev(q), 10, 8)
+        bi, bv = b.gpu.search(dev(q), 10, 8)
+        assert torch.equal(ai, bi) and torch.equal(av, bv)
+        a.check_search(q, 10, 8, where="after inserts")
+        st = a.gpu.stats()
+        lens = a.gpu.list_lengths()
+        assert st.device_error == 0 and np.array_equal(lens, b.gpu.list_lengths())
+        assert st.pages_used == int(np.sum((lens + 31) // 32))
+    finally:
+        a.close()
+        b.close()
+
+
+def test_ragged_shapes_padding_and_user_ids(gpu_device):
+    """d not a multiple of the load width, nlist not a multiple of the coarse tile, empty lists,
+    fewer candidates than k, arbitrary int64 ids."""
+    rng = np.random.default_rng(5)
+    n, d, nlist = 700, 100, 50
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    cent = np.concatenate([x[rng.permutation(n)[:nlist - 3]], 50 + rng.standard_normal((3, d)).astype(np.float32)])
+    ids = (rng.permutation(10 ** 6)[:n] + 2 ** 40).astype(np.int64)
+    q = rng.standard_normal((37, d)).astype(np.float32)
+    for metric in (L2, IP):
+        for storage in (F32, F16):
+            say(f"ragged metric={metric} storage={storage}")
+            p = Pair(x, cent, metric, storage, ids=ids)
+            try:
+                if metric == L2:
+                    assert (p.gpu.list_lengths()[-3:] == 0).all()  # far-away centroids own nothing
+                p.check_search(q, 60, 2)       # most rows shorter than k -> padding
+                p.check_search(q, 7, nlist)    # every list probed
+                p.check_search(q[:1], 1, 1)
+            finally:
+                p.close()
+
+
+def test_duplicates_across_the_k_boundary(gpu_device):
+    """Nine exact copies of one vector with scrambled ids, k cuts through them: the lowest ids win."""
+    rng = np.random.default_rng(6)
+    n, d = 3000, 64
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    x /= np.linalg.norm(x, axis=1, keepdims=True)
+    dup_rows = [11, 500, 501, 777, 1200, 1999, 2500, 2501, 2999]
+    x[dup_rows] = x[11]
+    ids = rng.permutation(n).astype(np.int64)
+    cent = x[rng.permutation(n)[:16]].copy()
+    q = np.stack([x[11], x[42]])
+    for metric in (IP, L2):
+        p = Pair(x, cent, metric, F32, ids=ids)
+        try:
+            for k in (1, 4, 9, 12):
+                p.check_search(q, k, 4, where=f"dup k={k}")
+                gi, _ = p.gpu.search(dev(q), k, 4)
+                want = sorted(ids[dup_rows].tolist())[:min(k, 9)]
+                assert gi[0, :min(k, 9)].cpu().tolist() == want
+        finally:
+            p.close()
+
+
+def test_multi_agent_equals_per_handle_calls(gpu_device):
+    """Config 3 shape, scaled: several independent indexes, one segmented call."""
+    cfg = W.scaled(W.C3, d=256, ncomp=32, nlist=48, n_agents=5)
+    sizes = [2500, 4000, 1500, 3000, 2000]
+    pairs, qs, offs = [], [], [0]
+    try:
+        for a, n in enumerate(sizes):
+            p, _ = make_pair(cfg, n=n, agent=a, insert_reserve=256)
+            pairs.append(p)
+            nq = [32, 5, 0, 17, 32][a]
+            qs.append(W.queries(cfg, 0, nq, agent=a) if nq else np.zeros((0, cfg.d), np.float32))
+            offs.append(offs[-1] + nq)
+        q = np.concatenate(qs)
+        say("multi-agent launch")
+        mi, mv = B.search_multi([p.gpu for p in pairs], offs, dev(q), 20, 16)
+        for a, p in enumerate(pairs):
+            if offs[a + 1] == offs[a]:
+                continue
+            si, sv = p.gpu.search(dev(qs[a]), 20, 16)
+            assert torch.equal(mi[offs[a]:offs[a + 1]], si) and torch.equal(mv[offs[a]:offs[a + 1]], sv)
+            p.check_search(qs[a], 20, 16, where=f"agent {a}")
+        # inserts between launches, then again
+        for a, p in enumerate(pairs):
+            p.insert_both(W.inserts(cfg, 0, 1 + 3 * a, agent=a))
+        mi2, mv2 = B.search_multi([p.gpu for p in pairs], offs, dev(q), 20, 16)
+        oi, ov = oracle.search_multi([p.orc for p in pairs], offs, q, 20, 16)
+        for a, p in enumerate(pairs):
+            if offs[a + 1] == offs[a]:
+                continue
+            si, sv = p.gpu.search(dev(qs[a]), 20, 16)
+            assert torch.equal(mi2[offs[a]:offs[a + 1]], si) and torch.equal(mv2[offs[a]:offs[a + 1]], sv)
+        assert np.mean(oi == mi2.cpu().numpy()) > 0.98
+    finally:
+        for p in pairs:
+            p.close()
+
+
+def test_wide_rows_many_queries_per_list(gpu_device):
+    """d = 1536 (config 5 width) with few lists, so lists see more queries than one group holds."""
+    cfg = W.scaled(W.C5, n=5000, ncomp=24, nlist=24, zipf_s=1.2)
+    for storage in (F32, F16):
+        p, _ = make_pair(cfg, storage=storage)
+        try:
+            q = W.queries(cfg, 0, 80)
+            say(f"wide rows storage={storage}")
+            p.check_search(q, 10, 6)
+            p.check_search(q, 100, 24)
+        finally:
+            p.close()
+
+
+def test_arena_exhaustion_is_reported_and_recoverable(gpu_device):
+    cfg = W.scaled(W.C1, n=3000)
+    x = W.vectors(cfg, 0, cfg.n)
+    cent = W.train_centroids(cfg, x)
+    c = B.pk_config(cfg.d, cfg.nlist, IP, F32, 32, 0)
+    with pytest.raises(B.PancakeError) as e:
+        B.Index(dev(cent), dev(x), page_vecs=32, arena_bytes=B.pk_arena_bytes(c, 100, 0))
+    assert e.value.status == B.PK_ERR_NOMEM
+    ix = B.Index(dev(cent), dev(x), page_vecs=32, arena_bytes=B.pk_arena_bytes(c, cfg.n, 0))
+    try:
+        free = ix.stats().pages_total - ix.stats().pages_used
+        new = dev(W.inserts(cfg, 0, int(free) + 5))
+        with pytest.raises(B.PancakeError) as e:
+            ix.insert(new)
+        assert e.value.status == B.PK_ERR_NOMEM and ix.stats().n_total == cfg.n
+        ix.add_arena(B.pk_arena_bytes(c, 0, 4096))
+        ix.insert(new)
+        st = ix.stats()
+        assert st.n_total == cfg.n + new.shape[0] and st.device_error == 0 and st.n_arenas == 2
+        ids, dist = ix.search(new[:16], 1, 1)
+        assert ids[:, 0].cpu().tolist() == list(range(cfg.n, cfg.n + 16))
+    finally:
+        ix.close()
+
+
+def test_argument_errors_on_device(gpu_device):
+    cfg = W.scaled(W.C1, n=500)
+    x = W.vectors(cfg, 0, cfg.n)
+    ix = B.Index(dev(x[:8].copy()), dev(x))
+    try:
+        q = dev(x[:4].copy())
+        for k, nprobe in ((0, 1), (1025, 1), (1, 0), (1, 9)):
+            with pytest.raises(B.PancakeError) as e:
+                ix.search(q, k, nprobe)
+            assert e.value.status == B.PK_ERR_INVALID_ARG
+        ids, dist = ix.search(q[:0], 3, 2)  # empty batch is a no-op
+        assert ids.shape == (0, 3)
+    finally:
+        ix.close()
