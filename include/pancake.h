@@ -171,6 +171,26 @@ int pk_index_stats(pk_index *index, pk_stats *out, void *stream);
 /* Current length of every list; synchronises `stream`.  out_len: HOST [nlist] int64. */
 int pk_list_lengths(pk_index *index, int64_t *out_len, void *stream);
 
+/*
+ * Stage timing for benchmarks.  Between pk_profile_begin and pk_profile_end every search
+ * launch sequence on this handle is bracketed by HIP events on its stream (at most 1024
+ * sequences are recorded) and the device adds up what the work lists contained.
+ *   coarse_ms   Section 2.2 coarse search: centroid scoring + top-nprobe
+ *   worklist_ms grouping of (query, list) pairs into page tiles
+ *   scan_ms     Section 2.2 fine search: the list-scan kernel alone
+ *   select_ms   per-query top-k over the scored candidates (Section 4.4 merge)
+ * scanned_rows counts each probed list once per launch sequence (the rows the scan must
+ * read from memory); candidates counts (query, vector) pairs.  pk_profile_end synchronises
+ * `stream`.  out: HOST.
+ */
+typedef struct {
+    int32_t launches;
+    float coarse_ms, worklist_ms, scan_ms, select_ms; /* sums over the recorded sequences */
+    int64_t scanned_rows, candidates, tiles;          /* sums over all sequences          */
+} pk_profile;
+int pk_profile_begin(pk_index *index, void *stream);
+int pk_profile_end(pk_index *index, pk_profile *out, void *stream);
+
 /* Frees the host object and the library-owned workspace (not the arenas).  The caller
  * must have synchronised every stream that still uses the index. */
 int pk_index_free(pk_index *index);

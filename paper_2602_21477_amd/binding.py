@@ -22,8 +22,8 @@ PK_ERR_INVALID_ARG, PK_ERR_BAD_HANDLE, PK_ERR_DIM_MISMATCH, PK_ERR_NOMEM, PK_ERR
     -1, -2, -3, -4, -5, -6)
 
 EXPORTS = ["pk_arena_bytes", "pk_index_build", "pk_index_add_arena", "pk_insert", "pk_insert_assigned", "pk_search",
-           "pk_search_multi", "pk_coarse", "pk_scan_probes", "pk_index_stats", "pk_list_lengths", "pk_index_free",
-           "pk_strerror"]
+           "pk_search_multi", "pk_coarse", "pk_scan_probes", "pk_index_stats", "pk_list_lengths", "pk_profile_begin",
+           "pk_profile_end", "pk_index_free", "pk_strerror"]
 
 
 class pk_config(C.Structure):
@@ -35,6 +35,12 @@ class pk_stats(C.Structure):
     _fields_ = [("n_total", C.c_int64), ("n_inserted", C.c_int64), ("pages_total", C.c_int64),
                 ("pages_used", C.c_int64), ("arena_bytes", C.c_int64), ("workspace_bytes", C.c_int64),
                 ("max_list_len", C.c_int64), ("device_error", C.c_int32), ("n_arenas", C.c_int32)]
+
+
+class pk_profile(C.Structure):
+    _fields_ = [("launches", C.c_int32), ("coarse_ms", C.c_float), ("worklist_ms", C.c_float),
+                ("scan_ms", C.c_float), ("select_ms", C.c_float), ("scanned_rows", C.c_int64),
+                ("candidates", C.c_int64), ("tiles", C.c_int64)]
 
 
 class PancakeError(RuntimeError):
@@ -66,6 +72,8 @@ def lib():
         L.pk_scan_probes.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp, vp]
         L.pk_index_stats.argtypes = [vp, C.POINTER(pk_stats), vp]
         L.pk_list_lengths.argtypes = [vp, vp, vp]
+        L.pk_profile_begin.argtypes = [vp, vp]
+        L.pk_profile_end.argtypes = [vp, C.POINTER(pk_profile), vp]
         L.pk_index_free.argtypes = [vp]
         L.pk_strerror.restype = C.c_char_p
         L.pk_strerror.argtypes = [C.c_int]
@@ -167,6 +175,16 @@ def pk_list_lengths(handle: int, nlist: int):
     out = np.empty(nlist, dtype=np.int64)
     _check(lib().pk_list_lengths(handle, out.ctypes.data_as(C.c_void_p), _stream()), "pk_list_lengths")
     return out
+
+
+def pk_profile_begin(handle: int):
+    _check(lib().pk_profile_begin(handle, _stream()), "pk_profile_begin")
+
+
+def pk_profile_end(handle: int) -> pk_profile:
+    pr = pk_profile()
+    _check(lib().pk_profile_end(handle, C.byref(pr), _stream()), "pk_profile_end")
+    return pr
 
 
 def pk_index_free(handle: int):

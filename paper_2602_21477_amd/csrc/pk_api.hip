@@ -51,11 +51,31 @@ struct pk_index {
     char *ws;
     size_t ws_bytes;
     int lds_limit, num_cu;
+    // stage timing (pk_profile_begin .. pk_profile_end)
+    bool prof_on;
+    std::vector<hipEvent_t> prof_ev; // 5 events per recorded launch sequence
+    size_t prof_used;
 };
 
 namespace {
 
 bool live(const pk_index *ix) { return ix && ix->magic == kMagic; }
+
+constexpr size_t kProfEvents = 5;
+constexpr size_t kProfMaxLaunches = 1024;
+
+// records the next stage boundary of the current launch sequence, if timing is on
+int mark(pk_index *ix, hipStream_t s)
+{
+    if (!ix->prof_on || ix->prof_used >= kProfEvents * kProfMaxLaunches) return PK_OK;
+    if (ix->prof_used == ix->prof_ev.size()) {
+        hipEvent_t e;
+        PK_HIP(hipEventCreate(&e));
+        ix->prof_ev.push_back(e);
+    }
+    PK_HIP(hipEventRecord(ix->prof_ev[ix->prof_used++], s));
+    return PK_OK;
+}
 
 struct Carver {
     char *base;
@@ -279,8 +299,8 @@ int run_coarse(const Plan &p, const MultiArgs &m, const pk_index *own, const flo
 }
 
 // Fine search of one batch over p.probes.
-int run_fine(const Plan &p, const MultiArgs &m, const pk_index *own, const float *q, int64_t *out_ids, float *out_dist,
-             hipStream_t s)
+int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, int64_t *out_ids, float *out_dist,
+             hipStream_t s, bool timed)
 {
     if (p.f16) PK_HIP(launch_prep_queries(q, p.nq, own->cfg.d, PK_F16, own->row_bytes, p.qs, p.qn, s));
     WorklistArgs w{};
@@ -306,6 +326,7 @@ int run_fine(const Plan &p, const MultiArgs &m, const pk_index *own, const float
     w.cand_cap = p.cand_cap;
     w.scalars = p.scalars + 4;
     PK_HIP(launch_worklist(w, m, s));
+    if (timed) PK_TRY(mark(own, s));
     ScanArgs sa{};
     sa.tiles = p.tiles;
     sa.ntiles = p.scalars + 4;
@@ -321,6 +342,7 @@ int run_fine(const Plan &p, const MultiArgs &m, const pk_index *own, const float
     sa.storage = own->cfg.storage;
     sa.mq = p.mq_f;
     PK_HIP(launch_scan(sa, 4, p.grid_f, s));
+    if (timed) PK_TRY(mark(own, s));
     SelectArgs se{};
     se.vals = p.cand;
     se.qoff = p.qoff;
@@ -346,6 +368,7 @@ int run_fine(const Plan &p, const MultiArgs &m, const pk_index *own, const float
     f.out_ids = out_ids;
     f.out_dist = out_dist;
     PK_HIP(launch_select_final(f, m, p.nq, s));
+    if (timed) PK_TRY(mark(own, s));
     return PK_OK;
 }
 
@@ -380,6 +403,8 @@ int search_impl(pk_index *const *hs, int nh, const int64_t *q_offsets, const flo
         MultiArgs m;
         fill_multi(m, hs, nh, qlo.data(), p.mq_c);
         const float *q = queries + (size_t)q0 * d;
+        const bool timed = mode == kFull && own->prof_on;
+        if (timed) PK_TRY(mark(own, s));
         if (mode == kForced) {
             PK_TRY(set_single_agent(p, s));
             PK_HIP(launch_copy_i32(forced + (size_t)q0 * nprobe, p.probes, nq * nprobe, s));
@@ -387,10 +412,11 @@ int search_impl(pk_index *const *hs, int nh, const int64_t *q_offsets, const flo
         } else {
             PK_TRY(run_coarse(p, m, own, q, s));
         }
+        if (timed) PK_TRY(mark(own, s));
         if (mode == kCoarseOnly) {
             PK_HIP(launch_copy_i32(p.probes, out_probes + (size_t)q0 * nprobe, nq * nprobe, s));
         } else {
-            PK_TRY(run_fine(p, m, own, q, out_ids + (size_t)q0 * k, out_dist + (size_t)q0 * k, s));
+            PK_TRY(run_fine(p, m, own, q, out_ids + (size_t)q0 * k, out_dist + (size_t)q0 * k, s, timed));
         }
     }
     return PK_OK;
@@ -438,6 +464,7 @@ Dims dims_of(const pk_config *c)
     h.take<uint32_t>(c->nlist);
     h.take<uint32_t>((size_t)c->nlist * x.max_dp);
     h.take<uint32_t>(16);
+    h.take<unsigned long long>(8);
     h.take<DevIndex>(1);
     x.header = round_up(h.off, 4096);
     x.page_stride = (size_t)x.P * x.row_bytes + (size_t)x.P * 12;
@@ -503,6 +530,7 @@ void destroy(pk_index *ix)
     if (ix->ws) (void)hipFree(ix->ws);
     if (ix->pin_pages) (void)hipHostFree(ix->pin_pages);
     if (ix->ev) (void)hipEventDestroy(ix->ev);
+    for (hipEvent_t e : ix->prof_ev) (void)hipEventDestroy(e);
     ix->magic = 0;
     delete ix;
 }
@@ -628,6 +656,7 @@ int pk_index_build(const pk_config *cfg, const float *centroids, const float *ve
     D.main_pages = h.take<uint32_t>(cfg->nlist);
     D.dtab = h.take<uint32_t>((size_t)cfg->nlist * x.max_dp);
     D.ctr = h.take<uint32_t>(16);
+    D.stats = h.take<unsigned long long>(8);
     ix->dev = h.take<DevIndex>(1);
     D.nlist = cfg->nlist;
     D.nlist_pad = x.nlist_pad;
@@ -648,6 +677,7 @@ int pk_index_build(const pk_config *cfg, const float *centroids, const float *ve
         launch_fill_u32(D.main_pages, 0u, cfg->nlist, s) != hipSuccess ||
         launch_fill_u32(D.dtab, 0xffffffffu, (size_t)cfg->nlist * x.max_dp, s) != hipSuccess ||
         launch_fill_u32(D.ctr, 0u, 16, s) != hipSuccess ||
+        launch_fill_u32(reinterpret_cast<uint32_t *>(D.stats), 0u, 16, s) != hipSuccess ||
         launch_fill_u32(D.ctr + 2, ix->pages_total, 1, s) != hipSuccess ||
         launch_store_centroids(centroids, cfg->nlist, cfg->d, x.dpad32, x.nlist_pad, cfg->metric, cent, cnorm, s) !=
             hipSuccess)
@@ -843,6 +873,44 @@ int pk_list_lengths(pk_index *ix, int64_t *out_len, void *stream)
     PK_HIP(hipMemcpyAsync(len.data(), ix->host.list_len, len.size() * 4, hipMemcpyDeviceToHost, s));
     PK_HIP(hipStreamSynchronize(s));
     for (size_t i = 0; i < len.size(); ++i) out_len[i] = len[i];
+    return PK_OK;
+}
+
+int pk_profile_begin(pk_index *ix, void *stream)
+{
+    if (!live(ix)) return PK_ERR_BAD_HANDLE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    PK_HIP(launch_fill_u32(reinterpret_cast<uint32_t *>(ix->host.stats), 0u, 16, s));
+    ix->prof_used = 0;
+    ix->prof_on = true;
+    return PK_OK;
+}
+
+int pk_profile_end(pk_index *ix, pk_profile *out, void *stream)
+{
+    if (!live(ix)) return PK_ERR_BAD_HANDLE;
+    if (!out) return PK_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    ix->prof_on = false;
+    unsigned long long st[3] = {0, 0, 0};
+    PK_HIP(hipMemcpyAsync(st, ix->host.stats, sizeof(st), hipMemcpyDeviceToHost, s));
+    PK_HIP(hipStreamSynchronize(s));
+    std::memset(out, 0, sizeof(*out));
+    const size_t n = ix->prof_used / kProfEvents;
+    for (size_t i = 0; i < n; ++i) {
+        float ms[4];
+        for (int j = 0; j < 4; ++j)
+            PK_HIP(hipEventElapsedTime(&ms[j], ix->prof_ev[i * kProfEvents + j], ix->prof_ev[i * kProfEvents + j + 1]));
+        out->coarse_ms += ms[0];
+        out->worklist_ms += ms[1];
+        out->scan_ms += ms[2];
+        out->select_ms += ms[3];
+    }
+    out->launches = (int32_t)n;
+    out->scanned_rows = (int64_t)st[0];
+    out->candidates = (int64_t)st[1];
+    out->tiles = (int64_t)st[2];
+    ix->prof_used = 0;
     return PK_OK;
 }
 

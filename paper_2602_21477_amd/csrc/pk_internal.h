@@ -41,6 +41,7 @@ struct DevIndex {
     uint32_t *main_pages;// [nlist] pages in that extent
     uint32_t *dtab;      // [nlist][max_dp] delta page numbers
     uint32_t *ctr;       // [0] next free page, [1] sticky error flags, [2] pages total
+    unsigned long long *stats; // [0] rows of distinct probed lists, [1] candidates, [2] tiles (running sums)
     int32_t nlist, nlist_pad, d, dpad32, P, max_dp, metric, storage;
     int32_t row_bytes;   // padded bytes of one stored row
     int32_t n_arenas;

@@ -188,17 +188,21 @@ __global__ __launch_bounds__(1024) void wl_scan_kernel(WorklistArgs a, MultiArgs
     const uint32_t nl = (uint32_t)a.n_handles * (uint32_t)a.nlist_max;
     block_exscan(a.lcnt, a.lstart, nl, s_wave);
     // tiles per list -> ltile (in place: first the counts, then their exclusive scan)
+    unsigned long long rows = 0;
     for (uint32_t gl = threadIdx.x; gl < nl; gl += blockDim.x) {
         const uint32_t h = gl / (uint32_t)a.nlist_max, l = gl - h * (uint32_t)a.nlist_max;
         uint32_t nt = 0;
         const uint32_t c = a.lcnt[gl];
         if (c > 0) {
             const DevIndex &ix = *m.ix[h];
-            const uint32_t pages = (ix.list_len[l] + (uint32_t)ix.P - 1) / (uint32_t)ix.P;
+            const uint32_t len = ix.list_len[l];
+            const uint32_t pages = (len + (uint32_t)ix.P - 1) / (uint32_t)ix.P;
             nt = pages * ((c + (uint32_t)a.mq - 1) / (uint32_t)a.mq);
+            rows += len;
         }
         a.lfill[gl] = nt;
     }
+    if (rows) atomicAdd(&m.ix[0]->stats[0], rows);
     __syncthreads();
     const uint32_t ntiles = block_exscan(a.lfill, a.ltile, nl, s_wave);
     __syncthreads();
@@ -215,6 +219,8 @@ __global__ __launch_bounds__(1024) void wl_scan_kernel(WorklistArgs a, MultiArgs
         uint32_t g = nt / (uint32_t)(a.scan_grid * 4);
         a.scalars[2] = g < 1 ? 1 : (g > 8 ? 8 : g);
         a.scalars[3] = total;
+        atomicAdd(&m.ix[0]->stats[1], (unsigned long long)total);
+        atomicAdd(&m.ix[0]->stats[2], (unsigned long long)nt);
     }
 }
 

@@ -25,6 +25,7 @@ can be regenerated independently and in parallel.
 from __future__ import annotations
 
 import dataclasses
+import functools
 from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass
 
@@ -102,7 +103,9 @@ def _to_storage(cfg: Config, x: np.ndarray) -> np.ndarray:
     return x
 
 
+@functools.lru_cache(maxsize=32)
 def centres(cfg: Config, agent: int = 0) -> np.ndarray:
+    """Mixture centres [ncomp, d]; cached, treat as read-only."""
     return _rng(cfg, agent, S_CENTRES).standard_normal((cfg.ncomp, cfg.d), dtype=np.float32)
 
 
@@ -216,27 +219,33 @@ def init_rows(cfg: Config, ntrain: int, agent: int = 0) -> np.ndarray:
     return _rng(cfg, agent, S_TRAIN, 0).permutation(ntrain)[:cfg.nlist].astype(np.int64)
 
 
-def lloyd(x: np.ndarray, init: np.ndarray, iters: int, block: int = 16384) -> np.ndarray:
+def lloyd(x: np.ndarray, init: np.ndarray, iters: int, block: int = 16384, threads: int = 8) -> np.ndarray:
     """Lloyd's k-means under L2 with BLAS-backed distance blocks: assign each row to
     its nearest centroid (ties to the lower index), move each non-empty centroid to
     the mean of its members, keep empty ones.  Same algorithm as the oracle's plain
     ``orc_kmeans``; used where that one would take hours."""
+    from scipy import sparse
     c = x[init].astype(np.float64)
     n, d = x.shape
     nlist = c.shape[0]
     for _ in range(iters):
         c32 = c.astype(np.float32)
         cn = np.einsum("ij,ij->i", c32, c32)
-        a = np.empty(n, dtype=np.int64)
-        for s in range(0, n, block):
+        def part(s, c32=c32, cn=cn):
             xb = x[s:s + block]
-            a[s:s + block] = np.argmin(cn[None, :] - 2.0 * (xb @ c32.T), axis=1)
-        order = np.argsort(a, kind="stable")
-        cnt = np.bincount(a, minlength=nlist)
-        starts = np.concatenate(([0], np.cumsum(cnt)[:-1]))
+            a = np.argmin(cn[None, :] - 2.0 * (xb @ c32.T), axis=1)
+            m = len(a)
+            onehot = sparse.csr_matrix((np.ones(m), (a, np.arange(m))), shape=(nlist, m))
+            return onehot @ xb.astype(np.float64), np.bincount(a, minlength=nlist)
+
+        sums = np.zeros((nlist, d), dtype=np.float64)
+        cnt = np.zeros(nlist, dtype=np.int64)
+        with ThreadPoolExecutor(max_workers=threads) as ex:
+            for ps, pc in ex.map(part, range(0, n, block)):  # summed in block order: deterministic
+                sums += ps
+                cnt += pc
         nz = cnt > 0
-        sums = np.add.reduceat(x[order].astype(np.float64), starts[nz], axis=0)
-        c[nz] = sums / cnt[nz][:, None]
+        c[nz] = sums[nz] / cnt[nz][:, None]
     return c.astype(np.float32)
 
 
