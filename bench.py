@@ -180,7 +180,8 @@ def run(args):
     alg_bytes = pr.scanned_rows / n * wl.row_bytes()
     achieved = alg_bytes / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else 0.0
     stages = {"coarse_ms": pr.coarse_ms / n, "worklist_ms": pr.worklist_ms / n, "scan_ms": scan_ms,
-              "select_ms": pr.select_ms / n, "tiles": pr.tiles / n, "candidates": pr.candidates / n}
+              "select_ms": pr.select_ms / n, "tiles": pr.tiles / n, "candidates": pr.candidates / n,
+              "emitted": pr.emitted / n}
     log(f"stages per search: {stages}")
     st = wl.index.stats()
     if st.device_error:

@@ -147,7 +147,7 @@ int pk_search(pk_index *index, const float *queries, int64_t nq, int32_t k, int3
  * addressed to many handles are served by one launch sequence.  Segment a = query rows
  * [q_offsets[a], q_offsets[a+1]) is searched in handles[a]; results equal per-handle
  * pk_search calls bit for bit.
- *   handles    HOST [n_handles]; all share d, metric and storage; each at most once
+ *   handles    HOST [n_handles]; all share d, metric, storage and page_vecs; each at most once
  *   q_offsets  HOST [n_handles + 1], non-decreasing, q_offsets[0] == 0
  *   queries    DEVICE [q_offsets[n_handles], d];  outputs as in pk_search
  */
@@ -180,13 +180,14 @@ int pk_list_lengths(pk_index *index, int64_t *out_len, void *stream);
  *   scan_ms     Section 2.2 fine search: the list-scan kernel alone
  *   select_ms   per-query top-k over the scored candidates (Section 4.4 merge)
  * scanned_rows counts each probed list once per launch sequence (the rows the scan must
- * read from memory); candidates counts (query, vector) pairs.  pk_profile_end synchronises
+ * read from memory); candidates counts (query, vector) pairs scored, emitted those that
+ * passed the running per-query threshold and reached the top-k selection.  pk_profile_end synchronises
  * `stream`.  out: HOST.
  */
 typedef struct {
     int32_t launches;
     float coarse_ms, worklist_ms, scan_ms, select_ms; /* sums over the recorded sequences */
-    int64_t scanned_rows, candidates, tiles;          /* sums over all sequences          */
+    int64_t scanned_rows, candidates, tiles, emitted; /* sums over all sequences          */
 } pk_profile;
 int pk_profile_begin(pk_index *index, void *stream);
 int pk_profile_end(pk_index *index, pk_profile *out, void *stream);

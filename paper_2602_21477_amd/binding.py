@@ -40,7 +40,7 @@ class pk_stats(C.Structure):
 class pk_profile(C.Structure):
     _fields_ = [("launches", C.c_int32), ("coarse_ms", C.c_float), ("worklist_ms", C.c_float),
                 ("scan_ms", C.c_float), ("select_ms", C.c_float), ("scanned_rows", C.c_int64),
-                ("candidates", C.c_int64), ("tiles", C.c_int64)]
+                ("candidates", C.c_int64), ("tiles", C.c_int64), ("emitted", C.c_int64)]
 
 
 class PancakeError(RuntimeError):

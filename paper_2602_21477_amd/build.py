@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpancake.so")
-SOURCES = ["pk_api.hip", "pk_scan.hip", "pk_select.hip", "pk_worklist.hip", "pk_index.hip"]
+SOURCES = ["pk_api.hip", "pk_scan.hip", "pk_select.hip", "pk_worklist.hip", "pk_index.hip", "pk_gemm.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]

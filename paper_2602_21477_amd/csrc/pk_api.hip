@@ -1,6 +1,7 @@
 // C ABI of libpancake: handle management, arena layout, host-side bounds and the launch
 // sequences of build, insert and search.  See include/pancake.h for the contract.
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -125,17 +126,17 @@ uint64_t wq_ub(const pk_index *ix, int nprobe)
 struct Plan {
     int64_t nq;
     int nprobe, k, nh;
-    int mq_c, mq_f, grid_c, grid_f, cchunks, nchunks, K, nlist_max;
-    uint32_t stride, cand_cap, tile_cap, ctiles;
+    int mq_c, mq_f, grid_c, grid_f, grid_s, cchunks, nchunks, K, nlist_max, sp;
+    uint32_t stride, cand_cap, tile_cap, ctiles, span;
     bool need_coarse, need_fine, f16;
     // buffers
     char *qs32, *qs;
-    float *qn32, *qn, *S, *cand;
+    float *qn32, *qn, *S, *svals;
     uint32_t *cand_off, *cand_cnt, *cslot_q, *cslot_o, *lcnt, *lstart, *lfill, *ltile, *pair_off, *qtot, *qoff, *slot_q,
-        *slot_o, *scalars;
+        *slot_o, *scalars, *tau, *tlo, *thi, *tcur, *hist, *ccnt, *sslot_q, *sslot_o;
     uint16_t *qagent;
-    Tile *ctile_buf, *tiles;
-    unsigned long long *cpartial, *partial;
+    Tile *ctile_buf, *tiles, *stiles;
+    unsigned long long *cpartial, *partial, *cbuf;
     int32_t *probes;
     size_t bytes;
 };
@@ -154,7 +155,7 @@ void carve(Plan &p, char *base, const pk_index *own)
         p.qn = p.qn32;
     }
     p.qagent = c.take<uint16_t>(nq);
-    p.scalars = c.take<uint32_t>(16);
+    p.scalars = c.take<uint32_t>(32);
     p.probes = c.take<int32_t>(nq * p.nprobe);
     p.cand_off = c.take<uint32_t>(nq);
     p.cand_cnt = c.take<uint32_t>(nq);
@@ -177,10 +178,26 @@ void carve(Plan &p, char *base, const pk_index *own)
         p.slot_q = c.take<uint32_t>(nq * p.nprobe);
         p.slot_o = c.take<uint32_t>(nq * p.nprobe);
         p.tiles = c.take<Tile>((size_t)p.tile_cap + 1);
-        p.cand = c.take<float>((size_t)p.cand_cap + 16);
+        p.tau = c.take<uint32_t>(nq);
+        p.tlo = c.take<uint32_t>(nq);
+        p.thi = c.take<uint32_t>(nq);
+        p.tcur = c.take<uint32_t>(nq);
+        p.hist = c.take<uint32_t>(nq * kHistBins);
+        p.ccnt = c.take<uint32_t>(nq);
+        p.sslot_q = c.take<uint32_t>(nq);
+        p.sslot_o = c.take<uint32_t>(nq);
+        p.stiles = c.take<Tile>(nq * p.sp + 1);
+        p.svals = c.take<float>(nq * p.span + 16);
+        p.cbuf = c.take<unsigned long long>((size_t)p.cand_cap + 16);
         p.partial = c.take<unsigned long long>(nq * p.nchunks * p.K);
     }
     p.bytes = round_up(c.off, 256);
+}
+
+int tune(const char *name, int dflt)
+{
+    const char *v = getenv(name);
+    return v ? atoi(v) : dflt;
 }
 
 int grid_for(const pk_index *ix, int row_bytes, int mq, int waves)
@@ -188,7 +205,7 @@ int grid_for(const pk_index *ix, int row_bytes, int mq, int waves)
     if (waves == 1) return ix->num_cu * 8;
     const int lds = scan_lds_bytes(row_bytes, mq);
     int per_cu = (160 * 1024) / lds;
-    per_cu = std::max(1, std::min(per_cu, 4));
+    per_cu = std::max(1, std::min(per_cu, tune("PK_TUNE_WGS", 4)));
     return ix->num_cu * per_cu;
 }
 
@@ -207,10 +224,23 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
     p.f16 = own->cfg.storage == PK_F16;
     p.mq_c = scan_max_mq(own->rb32, PK_F32, own->lds_limit);
     p.mq_f = scan_max_mq(own->row_bytes, own->cfg.storage, own->lds_limit);
+    {
+        // query slots per scan tile: the smallest group that holds the expected number of
+        // queries per probed list (a list with more is scanned once per group); small
+        // groups keep the LDS tile small and the occupancy high
+        double avg = 0;
+        for (int a = 0; a < nh; ++a)
+            avg = std::max(avg, (double)(qlo[a + 1] - qlo[a]) * nprobe / hs[a]->cfg.nlist);
+        const int want = avg <= 6 ? 16 : (avg <= 20 ? 32 : 64);
+        p.mq_f = std::min(p.mq_f, tune("PK_TUNE_MQ", want));
+    }
     if (p.mq_c < 16 || p.mq_f < 16) return PK_ERR_UNSUPPORTED;
     p.grid_c = grid_for(own, own->rb32, p.mq_c, 1);
     p.grid_f = grid_for(own, own->row_bytes, p.mq_f, 4);
+    p.grid_s = grid_for(own, own->row_bytes, 16, 4);
     p.K = k + 1;
+    p.sp = (k + own->P - 1) / own->P; // sample pages: at least k rows of the first probed list
+    p.span = (uint32_t)(p.sp * own->P);
     uint64_t cand = 0, tiles = 0, ctiles = 0, wmax = 0;
     int nlist_hi = 0, pad_hi = 0;
     for (int a = 0; a < nh; ++a) {
@@ -238,6 +268,9 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
     return PK_OK;
 }
 
+// handles whose query segment is long enough go through the MFMA GEMM instead of coarse tiles
+bool coarse_by_gemm(uint32_t nqa) { return nqa >= (uint32_t)tune("PK_TUNE_GEMM_MIN", 48); }
+
 void fill_multi(MultiArgs &m, pk_index *const *hs, int nh, const uint32_t *qlo, int mq_c)
 {
     std::memset(&m, 0, sizeof(m));
@@ -248,15 +281,16 @@ void fill_multi(MultiArgs &m, pk_index *const *hs, int nh, const uint32_t *qlo, 
         m.qlo[a] = qlo[a];
         m.ctile[a] = ct;
         const uint32_t nqa = qlo[a + 1] - qlo[a];
-        ct += (nqa + mq_c - 1) / mq_c * (uint32_t)(hs[a]->nlist_pad / kCoarsePage);
+        if (!coarse_by_gemm(nqa)) ct += (nqa + mq_c - 1) / mq_c * (uint32_t)(hs[a]->nlist_pad / kCoarsePage);
     }
     m.qlo[nh] = qlo[nh];
     m.ctile[nh] = ct;
 }
 
 // Coarse search of one batch: probes[nq][nprobe] in the plan's workspace.
-int run_coarse(const Plan &p, const MultiArgs &m, const pk_index *own, const float *q, hipStream_t s)
+int run_coarse(const Plan &p, const MultiArgs &m, pk_index *const *hs, const float *q, hipStream_t s)
 {
+    const pk_index *own = hs[0];
     PK_HIP(launch_prep_queries(q, p.nq, own->cfg.d, PK_F32, own->rb32, p.qs32, p.qn32, s));
     CoarseArgs ca{};
     ca.mq = p.mq_c;
@@ -284,7 +318,26 @@ int run_coarse(const Plan &p, const MultiArgs &m, const pk_index *own, const flo
     sa.metric = own->cfg.metric;
     sa.storage = PK_F32;
     sa.mq = p.mq_c;
-    PK_HIP(launch_scan(sa, 1, p.grid_c, s));
+    if (m.ctile[m.n] > 0) PK_HIP(launch_scan(sa, 1, std::min<int>(p.grid_c, (int)m.ctile[m.n]), s));
+    for (int a = 0; a < m.n; ++a) {
+        const uint32_t nqa = m.qlo[a + 1] - m.qlo[a];
+        if (!coarse_by_gemm(nqa)) continue;
+        const pk_index *ix = hs[a];
+        GemmArgs g{};
+        g.q = reinterpret_cast<const float *>(p.qs32) + (size_t)m.qlo[a] * ix->dpad32;
+        g.c = ix->host.cent;
+        g.qnorm = p.qn32 + m.qlo[a];
+        g.cnorm = ix->host.cnorm;
+        g.out = p.S + (size_t)m.qlo[a] * p.stride;
+        g.m = (int)nqa;
+        g.n = ix->cfg.nlist;
+        g.n_pad = ix->nlist_pad;
+        g.n_store = ix->nlist_pad;
+        g.ld = ix->dpad32;
+        g.metric = ix->cfg.metric;
+        g.stride = p.stride;
+        PK_HIP(launch_gemm_scores(g, s));
+    }
     SelectArgs se{};
     se.vals = p.S;
     se.qoff = p.cand_off;
@@ -303,6 +356,45 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
              hipStream_t s, bool timed)
 {
     if (p.f16) PK_HIP(launch_prep_queries(q, p.nq, own->cfg.d, PK_F16, own->row_bytes, p.qs, p.qn, s));
+    // threshold sampling: k-th best of the first pages of each query's first probed list
+    SampleArgs sm{};
+    sm.probes = p.probes;
+    sm.qagent = p.qagent;
+    sm.nq = p.nq;
+    sm.nprobe = p.nprobe;
+    sm.sp = p.sp;
+    sm.k = p.k;
+    sm.metric = own->cfg.metric;
+    sm.scan_grid = p.grid_s;
+    sm.span = p.span;
+    sm.tiles = p.stiles;
+    sm.slot_query = p.sslot_q;
+    sm.slot_out = p.sslot_o;
+    sm.vals = p.svals;
+    sm.scalars = p.scalars + 8;
+    sm.tau = p.tau;
+    sm.tlo = p.tlo;
+    sm.thi = p.thi;
+    sm.tcur = p.tcur;
+    sm.hist = p.hist;
+    PK_HIP(launch_sample_tiles(sm, m, s));
+    ScanArgs ss{};
+    ss.tiles = p.stiles;
+    ss.ntiles = p.scalars + 8;
+    ss.tile_ctr = p.scalars + 9;
+    ss.batch = p.scalars + 10;
+    ss.qs = p.qs;
+    ss.qnorm = p.qn;
+    ss.slot_query = p.sslot_q;
+    ss.slot_out = p.sslot_o;
+    ss.out = p.svals;
+    ss.row_bytes = own->row_bytes;
+    ss.metric = own->cfg.metric;
+    ss.storage = own->cfg.storage;
+    ss.mq = 16;
+    PK_HIP(launch_scan(ss, 4, p.grid_s, s));
+    PK_HIP(launch_tau(sm, s));
+
     WorklistArgs w{};
     w.probes = p.probes;
     w.qagent = p.qagent;
@@ -312,6 +404,7 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
     w.nlist_max = p.nlist_max;
     w.mq = p.mq_f;
     w.scan_grid = p.grid_f;
+    w.grab_div = tune("PK_TUNE_GRABDIV", 8);
     w.lcnt = p.lcnt;
     w.lstart = p.lstart;
     w.lfill = p.lfill;
@@ -319,6 +412,7 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
     w.pair_off = p.pair_off;
     w.qtot = p.qtot;
     w.qoff = p.qoff;
+    w.ccnt = p.ccnt;
     w.slot_query = p.slot_q;
     w.slot_out = p.slot_o;
     w.tiles = p.tiles;
@@ -336,7 +430,17 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
     sa.qnorm = p.qn;
     sa.slot_query = p.slot_q;
     sa.slot_out = p.slot_o;
-    sa.out = p.cand;
+    sa.out = nullptr;
+    sa.tau = p.tau;
+    sa.tlo = p.tlo;
+    sa.thi = p.thi;
+    sa.tcur = p.tcur;
+    sa.use_hist = tune("PK_TUNE_HIST", 1);
+    sa.hist = p.hist;
+    sa.k = p.k;
+    sa.qoff = p.qoff;
+    sa.ccnt = p.ccnt;
+    sa.cbuf = p.cbuf;
     sa.row_bytes = own->row_bytes;
     sa.metric = own->cfg.metric;
     sa.storage = own->cfg.storage;
@@ -344,9 +448,10 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
     PK_HIP(launch_scan(sa, 4, p.grid_f, s));
     if (timed) PK_TRY(mark(own, s));
     SelectArgs se{};
-    se.vals = p.cand;
+    se.vals = nullptr;
+    se.keys = p.cbuf;
     se.qoff = p.qoff;
-    se.qcnt = p.qtot;
+    se.qcnt = p.ccnt;
     se.metric = own->cfg.metric;
     se.K = p.K;
     se.nchunks = p.nchunks;
@@ -359,9 +464,9 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
     f.k = p.k;
     f.nprobe = p.nprobe;
     f.metric = own->cfg.metric;
-    f.vals = p.cand;
+    f.keys = p.cbuf;
     f.qoff = p.qoff;
-    f.qcnt = p.qtot;
+    f.qcnt = p.ccnt;
     f.pair_off = p.pair_off;
     f.probes = p.probes;
     f.qagent = p.qagent;
@@ -410,7 +515,7 @@ int search_impl(pk_index *const *hs, int nh, const int64_t *q_offsets, const flo
             PK_HIP(launch_copy_i32(forced + (size_t)q0 * nprobe, p.probes, nq * nprobe, s));
             if (!p.f16) PK_HIP(launch_prep_queries(q, nq, d, PK_F32, own->rb32, p.qs32, p.qn32, s));
         } else {
-            PK_TRY(run_coarse(p, m, own, q, s));
+            PK_TRY(run_coarse(p, m, hs, q, s));
         }
         if (timed) PK_TRY(mark(own, s));
         if (mode == kCoarseOnly) {
@@ -566,7 +671,7 @@ int insert_impl(pk_index *ix, const float *x, const int64_t *ids, int64_t m, con
         } else {
             MultiArgs mm;
             fill_multi(mm, hs, 1, qlo, p.mq_c);
-            PK_TRY(run_coarse(p, mm, ix, xc, s));
+            PK_TRY(run_coarse(p, mm, hs, xc, s));
             assign = p.probes;
         }
         PK_HIP(launch_reserve(ix->dev, assign, mc, slots, assigned_out ? assigned_out + i0 : nullptr, s));
@@ -712,7 +817,7 @@ int pk_index_build(const pk_config *cfg, const float *centroids, const float *ve
             carve(p, ix->ws, ix);
             MultiArgs mm;
             fill_multi(mm, hs, 1, qlo, p.mq_c);
-            rc = run_coarse(p, mm, ix, vectors + (size_t)i0 * cfg->d, s);
+            rc = run_coarse(p, mm, hs, vectors + (size_t)i0 * cfg->d, s);
             if (rc == PK_OK && launch_copy_i32(p.probes, d_assign + i0, mc, s) != hipSuccess) rc = PK_ERR_HIP;
         }
         if (rc != PK_OK) return fail2(rc);
@@ -807,7 +912,8 @@ int pk_search_multi(pk_index *const *handles, int32_t n_handles, const int64_t *
         for (int b = 0; b < a; ++b)
             if (handles[b] == handles[a]) return PK_ERR_INVALID_ARG;
         const pk_config &c0 = handles[0]->cfg, &c = handles[a]->cfg;
-        if (c.d != c0.d || c.metric != c0.metric || c.storage != c0.storage) return PK_ERR_DIM_MISMATCH;
+        if (c.d != c0.d || c.metric != c0.metric || c.storage != c0.storage || c.page_vecs != c0.page_vecs)
+            return PK_ERR_DIM_MISMATCH;
         PK_TRY(check_search_args(handles[a], queries, q_offsets[n_handles], k, nprobe));
     }
     const int64_t nq = q_offsets[n_handles];
@@ -892,7 +998,7 @@ int pk_profile_end(pk_index *ix, pk_profile *out, void *stream)
     if (!out) return PK_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     ix->prof_on = false;
-    unsigned long long st[3] = {0, 0, 0};
+    unsigned long long st[4] = {0, 0, 0, 0};
     PK_HIP(hipMemcpyAsync(st, ix->host.stats, sizeof(st), hipMemcpyDeviceToHost, s));
     PK_HIP(hipStreamSynchronize(s));
     std::memset(out, 0, sizeof(*out));
@@ -910,6 +1016,7 @@ int pk_profile_end(pk_index *ix, pk_profile *out, void *stream)
     out->scanned_rows = (int64_t)st[0];
     out->candidates = (int64_t)st[1];
     out->tiles = (int64_t)st[2];
+    out->emitted = (int64_t)st[3];
     ix->prof_used = 0;
     return PK_OK;
 }

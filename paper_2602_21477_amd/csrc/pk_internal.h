@@ -21,6 +21,7 @@ constexpr int kSelVec = 4;            // candidates per thread per round
 constexpr int kSelCap = 4096;         // LDS key buffer of the select kernels (K + one round <= cap)
 constexpr int kSelChunk = 32768;      // candidates per (query, chunk) workgroup
 constexpr unsigned long long kMaxKey = ~0ull;
+constexpr int kHistBins = 64;         // per-query key histogram that tightens the emission threshold
 
 constexpr int kErrPages = 1, kErrListFull = 2, kErrWorklist = 4;
 
@@ -41,7 +42,7 @@ struct DevIndex {
     uint32_t *main_pages;// [nlist] pages in that extent
     uint32_t *dtab;      // [nlist][max_dp] delta page numbers
     uint32_t *ctr;       // [0] next free page, [1] sticky error flags, [2] pages total
-    unsigned long long *stats; // [0] rows of distinct probed lists, [1] candidates, [2] tiles (running sums)
+    unsigned long long *stats; // running sums: [0] rows of distinct probed lists, [1] candidates, [2] tiles, [3] emitted
     int32_t nlist, nlist_pad, d, dpad32, P, max_dp, metric, storage;
     int32_t row_bytes;   // padded bytes of one stored row
     int32_t n_arenas;
@@ -61,6 +62,25 @@ __device__ __forceinline__ uint32_t phys_page(const DevIndex &ix, uint32_t l, ui
     uint32_t mp = ix.main_pages[l];
     return lp < mp ? ix.main_base[l] + lp : ix.dtab[(size_t)l * ix.max_dp + (lp - mp)];
 }
+
+// A value as an unsigned key whose ascending order is best-first (smaller = better) under
+// the metric; exact inverse below.  Padding (-inf for inner product, +inf for L2) maps to
+// 0xff800000 under both metrics; finite values map below it.
+__device__ __forceinline__ uint32_t order_bits(float v, int metric)
+{
+    const uint32_t b = __float_as_uint(v);
+    const uint32_t asc = b ^ ((b >> 31) ? 0xffffffffu : 0x80000000u);
+    return metric == PK_METRIC_L2 ? asc : ~asc;
+}
+
+__device__ __forceinline__ float value_of(uint32_t ob, int metric)
+{
+    const uint32_t asc = metric == PK_METRIC_L2 ? ob : ~ob;
+    const uint32_t b = (asc & 0x80000000u) ? (asc ^ 0x80000000u) : ~asc;
+    return __uint_as_float(b);
+}
+
+constexpr uint32_t kWorstBits = 0xff800000u;
 
 // One unit of scan work: one page of rows against one group of query slots.
 struct Tile {
@@ -95,13 +115,24 @@ hipError_t launch_prep_queries(const float *q, int64_t nq, int d, int storage, i
 struct ScanArgs {
     const Tile *tiles;
     const uint32_t *ntiles;      // device scalar
-    uint32_t *tile_ctr;          // device scalar, zero before the launch
     const uint32_t *batch;       // device scalar: tiles taken per grab (>= 1)
     const char *qs;              // prepared queries [nq][row_bytes]
     const float *qnorm;          // [nq]
     const uint32_t *slot_query;  // slot -> query row
     const uint32_t *slot_out;    // slot -> first output element of the (query, list) pair
-    float *out;                  // values
+    float *out;                  // dense mode: values, one per (slot, row)
+    // gated mode (tau != NULL): a value is emitted only if its key is <= tau[query]; it is
+    // appended as (key << 32 | position) to the query's region of cbuf
+    const uint32_t *tau;         // [nq] initial threshold keys (from the sample)
+    const uint32_t *tlo;         // [nq] best sample key: lower end of the histogram range
+    const uint32_t *thi;         // [nq] upper end of the histogram range (k-th best sample key, or the worst one)
+    uint32_t *hist;              // [nq][kHistBins] emitted candidates per key bucket (zero before the launch)
+    uint32_t *tcur;              // [nq] running threshold shared by all workgroups (starts at tau)
+    const uint32_t *qoff;        // [nq] first element of each query's region
+    uint32_t *ccnt;              // [nq] emitted so far (zero before the launch)
+    unsigned long long *cbuf;
+    uint32_t *tile_ctr;          // device scalar, zero before the launch: batches handed out after the first round
+    int k, use_hist;
     int row_bytes, metric, storage, mq;
 };
 hipError_t launch_scan(const ScanArgs &a, int waves_per_wg, int grid, hipStream_t s);
@@ -109,7 +140,8 @@ int scan_lds_bytes(int row_bytes, int mq);
 int scan_max_mq(int row_bytes, int storage, int lds_limit);
 
 struct SelectArgs {
-    const float *vals;            // candidate values
+    const float *vals;            // candidate values, or NULL when keys are given
+    const unsigned long long *keys; // candidate keys (value key << 32 | position)
     const uint32_t *qoff;         // [nq] first candidate of each query
     const uint32_t *qcnt;         // [nq] candidates of each query
     int metric, K, nchunks;
@@ -122,8 +154,8 @@ hipError_t launch_select_probes(const unsigned long long *partial, int nchunks, 
 struct FinalArgs {
     const unsigned long long *partial; // [nq][nchunks][K]
     int nchunks, K, k, nprobe, metric;
-    const float *vals;
-    const uint32_t *qoff, *qcnt;      // candidate ranges
+    const unsigned long long *keys;   // emitted candidates of all queries
+    const uint32_t *qoff, *qcnt;      // candidate ranges inside keys
     const uint32_t *pair_off;         // [nq][nprobe+1] start of each probe's segment inside the range
     const int32_t *probes;            // [nq][nprobe]
     const uint16_t *qagent;           // [nq] handle number
@@ -147,16 +179,51 @@ struct WorklistArgs {
     const int32_t *probes;     // [nq][nprobe]; entries outside [0, nlist) are ignored
     const uint16_t *qagent;    // [nq]
     int64_t nq;
-    int nprobe, n_handles, nlist_max, mq, scan_grid;
+    int nprobe, n_handles, nlist_max, mq, scan_grid, grab_div;
     uint32_t *lcnt, *lstart, *lfill, *ltile; // [n_handles * nlist_max]
     uint32_t *pair_off;        // [nq][nprobe+1]
     uint32_t *qtot, *qoff;     // [nq]
+    uint32_t *ccnt;            // [nq] zeroed here (emission counters of the gated scan)
     uint32_t *slot_query, *slot_out; // [nq * nprobe]
     Tile *tiles;
     uint32_t tile_cap, cand_cap;
     uint32_t *scalars;         // [0] ntiles [1] tile counter [2] grab size [3] total candidates
 };
 hipError_t launch_worklist(const WorklistArgs &a, const MultiArgs &m, hipStream_t s);
+
+// Threshold sampling: the first `sp` pages of each query's first probed list are scored
+// densely; the k-th best of them bounds the query's k-th best overall.
+struct SampleArgs {
+    const int32_t *probes;     // [nq][nprobe]
+    const uint16_t *qagent;
+    int64_t nq;
+    int nprobe, sp, k, metric, scan_grid;
+    uint32_t span;             // values per query = sp * rows per page (same for all handles)
+    Tile *tiles;               // [nq * sp]
+    uint32_t *slot_query;      // [nq] = q
+    uint32_t *slot_out;        // [nq] = q * span
+    float *vals;               // [nq][span], pre-filled with the padding value by the kernel
+    uint32_t *scalars;         // [0] ntiles [1] tile counter [2] grab size
+    uint32_t *tau;             // [nq] out: k-th best sample key, or 0xffffffff
+    uint32_t *tlo;             // [nq] out: best sample key
+    uint32_t *thi;             // [nq] out: k-th best sample key, or the worst one if there are fewer than k
+    uint32_t *hist;            // [nq][kHistBins] zeroed here
+    uint32_t *tcur;            // [nq] out: running threshold, starts at tau
+};
+hipError_t launch_sample_tiles(const SampleArgs &a, const MultiArgs &m, hipStream_t s);
+hipError_t launch_tau(const SampleArgs &a, hipStream_t s);
+
+// dense coarse scoring on the matrix cores (large query batches, build)
+struct GemmArgs {
+    const float *q;      // [m][ld] prepared fp32 queries (zero padded rows)
+    const float *c;      // [n_pad][ld] centroid table
+    const float *qnorm;  // [m]
+    const float *cnorm;  // [n_pad]
+    float *out;          // [m][stride]
+    int m, n, n_pad, n_store, ld, metric;
+    uint32_t stride;
+};
+hipError_t launch_gemm_scores(const GemmArgs &a, hipStream_t s);
 
 // build / insert
 hipError_t launch_hist(const int32_t *assign, int64_t n, uint32_t *cnt, hipStream_t s);

@@ -39,8 +39,10 @@ __device__ __forceinline__ void mfma_step(f32x4 &acc, const u32x4 &qa, const u32
     }
 }
 
-// MT = query tiles of 16 slots held in LDS (MQ = 16*MT); WAVES = waves per workgroup.
-template <int STORAGE, int MT, int WAVES>
+// MT = query tiles of 16 slots held in LDS (MQ = 16*MT); WAVES = waves per workgroup;
+// GATED = emit only values that pass the per-query threshold (fine search) instead of
+// writing every value (coarse search, threshold sampling).
+template <int STORAGE, int MT, int WAVES, bool GATED>
 __global__ __launch_bounds__(WAVES * 64) void scan_kernel(ScanArgs a)
 {
     extern __shared__ __align__(16) char smem[];
@@ -50,7 +52,12 @@ __global__ __launch_bounds__(WAVES * 64) void scan_kernel(ScanArgs a)
     char *qtile = smem;
     uint32_t *s_out = reinterpret_cast<uint32_t *>(smem + (size_t)MQ * qstride);
     float *s_qn = reinterpret_cast<float *>(s_out + MQ);
-    uint32_t *s_misc = reinterpret_cast<uint32_t *>(s_qn + MQ);
+    uint32_t *s_thr = reinterpret_cast<uint32_t *>(s_qn + MQ); // gated: threshold key per slot
+    uint32_t *s_q = s_thr + MQ;                                 // gated: query of the slot
+    uint32_t *s_base = s_q + MQ;                                // gated: start of the query's region
+    uint32_t *s_lo = s_base + MQ;                               // gated: histogram origin (key)
+    uint32_t *s_sh = s_lo + MQ;                                 // gated: histogram bucket shift
+    uint32_t *s_misc = s_sh + MQ;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int ln = lane & 15, lg = lane >> 4;
@@ -61,13 +68,15 @@ __global__ __launch_bounds__(WAVES * 64) void scan_kernel(ScanArgs a)
     const float worst = a.metric == PK_METRIC_IP ? -INFINITY : INFINITY;
     uint32_t cur_qbeg = 0xffffffffu, cur_qcnt = 0;
 
+    // Schedule: the first batch of every workgroup is fixed (tile b for workgroup b), later
+    // batches of `grab` tiles are handed out by a counter, so uneven tiles (hot lists scored
+    // against many query groups) still balance while the launch does not start with a burst
+    // of atomics.  The first batch is a single tile so that the emission thresholds get
+    // their first refresh early.  Every workgroup leaves the loop the first time it is handed
+    // a batch past the end.
+    uint32_t t0 = blockIdx.x, t1 = min(t0 + 1u, ntiles);
     for (;;) {
-        __syncthreads();
-        if (tid == 0) s_misc[0] = atomicAdd(a.tile_ctr, grab);
-        __syncthreads();
-        const uint32_t t0 = s_misc[0];
-        if (t0 >= ntiles) break; // every wave of every workgroup reaches this once the counter passes ntiles
-        const uint32_t t1 = min(t0 + grab, ntiles);
+        if (t0 >= ntiles) break;
         for (uint32_t t = t0; t < t1; ++t) {
             const Tile *tp = a.tiles + t;
             const char *tx = tp->x;
@@ -89,12 +98,67 @@ __global__ __launch_bounds__(WAVES * 64) void scan_kernel(ScanArgs a)
                 }
                 if (tid < MQ) {
                     const bool on = (uint32_t)tid < qcnt;
+                    const uint32_t q = on ? a.slot_query[qbeg + tid] : 0u;
                     s_out[tid] = on ? a.slot_out[qbeg + tid] : 0u;
-                    s_qn[tid] = on ? a.qnorm[a.slot_query[qbeg + tid]] : 0.f;
+                    s_qn[tid] = on ? a.qnorm[q] : 0.f;
+                    if constexpr (GATED) {
+                        const uint32_t base = on ? a.qoff[q] : 0u;
+                        s_q[tid] = q;
+                        s_base[tid] = base;
+                        s_out[tid] -= base; // position inside the query's candidate range
+                        // Threshold of the slot.  It starts at the k-th best key of the query's
+                        // sample and tightens as candidates are emitted: the histogram counts
+                        // the emitted keys per bucket of [lo, tau0], and the upper edge of the
+                        // first bucket at which the running count reaches k bounds the k-th best.
+                        uint32_t thr = 0u, lo = 0u, sh = 0u;
+                        if (on) {
+                            thr = a.tau[q];
+                            lo = a.tlo[q];
+                            const uint32_t hi = a.thi[q];
+                            const uint32_t range = hi > lo ? hi - lo : 0u;
+                            const int bits = 32 - __clz((int)range | 1);
+                            sh = bits > 6 ? (uint32_t)(bits - 6) : 0u; // (key - lo) >> sh < kHistBins for keys <= hi
+                        }
+                        if (on && a.use_hist) {
+                            const uint32_t *hp = a.hist + (size_t)q * kHistBins;
+                            uint32_t h[kHistBins];
+#pragma unroll
+                            for (int j = 0; j < kHistBins; ++j) // device-scope loads: counts other CUs just added
+                                h[j] = __hip_atomic_load(hp + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            uint32_t cum = 0;
+                            bool found = false;
+#pragma unroll
+                            for (int j = 0; j < kHistBins - 1; ++j) { // the last bucket also takes keys past the range
+                                cum += h[j];
+                                if (!found && cum >= (uint32_t)a.k) {
+                                    found = true;
+                                    const unsigned long long edge =
+                                        (unsigned long long)lo + ((unsigned long long)(j + 1) << sh) - 1ull;
+                                    if (edge < thr) thr = (uint32_t)edge;
+                                }
+                            }
+                        }
+                        if (on && a.use_hist) {
+                            // share the tightened threshold with every workgroup scoring this query
+                            const uint32_t seen = atomicMin(a.tcur + q, thr);
+                            thr = seen < thr ? seen : thr;
+                        }
+                        s_thr[tid] = thr;
+                        s_lo[tid] = lo;
+                        s_sh[tid] = sh;
+                    }
                 }
                 __syncthreads();
                 cur_qbeg = qbeg;
                 cur_qcnt = qcnt;
+            }
+            else if (GATED && a.use_hist) {
+                // same query group as the previous tile: pick up thresholds others have tightened
+                if ((uint32_t)tid < qcnt) {
+                    const uint32_t seen = __hip_atomic_load(a.tcur + s_q[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (seen < s_thr[tid]) s_thr[tid] = seen;
+                }
+                __syncthreads();
             }
             const int mt_used = (int)((qcnt + 15u) >> 4);
             const int nrows_pad = (nrows + 15) & ~15;
@@ -145,20 +209,54 @@ __global__ __launch_bounds__(WAVES * 64) void scan_kernel(ScanArgs a)
 #pragma unroll
                 for (int nt = 0; nt < 2; ++nt) {
                     const int row = rb * kRowBlock + nt * 16 + ln;
-                    if (row < nrows_pad) {
-                        const bool live = row < nrows;
-                        float xn = 0.f;
-                        if (a.metric == PK_METRIC_L2 && live) xn = txn[row];
+                    const bool live = row < nrows;
+                    float xn = 0.f;
+                    if (a.metric == PK_METRIC_L2 && live) xn = txn[row];
 #pragma unroll
-                        for (int mt = 0; mt < MT; ++mt) {
+                    for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
-                            for (int i = 0; i < 4; ++i) {
-                                const int m = mt * 16 + lg * 4 + i;
-                                if ((uint32_t)m < qcnt) {
-                                    float v = acc[mt][nt][i];
-                                    if (a.metric == PK_METRIC_L2) v = fmaxf(xn - 2.f * v + s_qn[m], 0.f);
-                                    if (!live) v = worst;
-                                    a.out[(size_t)s_out[m] + row0 + row] = v;
+                        for (int i = 0; i < 4; ++i) {
+                            const int m = mt * 16 + lg * 4 + i;
+                            float v = acc[mt][nt][i];
+                            if (a.metric == PK_METRIC_L2) v = fmaxf(xn - 2.f * v + s_qn[m & (MQ - 1)], 0.f);
+                            if constexpr (!GATED) {
+                                if ((uint32_t)m < qcnt && row < nrows_pad)
+                                    a.out[(size_t)s_out[m] + row0 + row] = live ? v : worst;
+                            } else {
+                                // The 16 lanes of a group share slot m.  Values that pass the
+                                // query's threshold are rare: one ballot, and only then one
+                                // aggregated atomic per group to reserve room in the query's region.
+                                const uint32_t bits = order_bits(v, a.metric);
+                                const bool pass = live && (uint32_t)m < qcnt && bits <= s_thr[m];
+                                const unsigned long long mask = __ballot(pass);
+                                if (mask == 0ull) continue;
+                                const uint32_t gmask = (uint32_t)(mask >> (lg * 16)) & 0xffffu;
+                                if (gmask) {
+                                    const int leader = __ffs(gmask) - 1;
+                                    uint32_t base = 0;
+                                    if (ln == leader) base = atomicAdd(&a.ccnt[s_q[m]], (uint32_t)__popc(gmask));
+                                    base = __shfl(base, lg * 16 + leader);
+                                    if (pass) {
+                                        const uint32_t rank = __popc(gmask & ((1u << ln) - 1u));
+                                        a.cbuf[(size_t)s_base[m] + base + rank] =
+                                            ((unsigned long long)bits << 32) | (s_out[m] + row0 + (uint32_t)row);
+                                    }
+                                    if (a.use_hist) {
+                                        // count the emitted keys per bucket; one atomic for the group
+                                        // when its keys share a bucket (the usual case)
+                                        const uint32_t lo = s_lo[m];
+                                        uint32_t b = bits > lo ? (bits - lo) >> s_sh[m] : 0u;
+                                        b = b < (uint32_t)kHistBins ? b : (uint32_t)kHistBins - 1u;
+                                        const uint32_t b0 = __shfl(b, lg * 16 + leader);
+                                        const uint32_t odd =
+                                            (uint32_t)(__ballot(pass && b != b0) >> (lg * 16)) & 0xffffu;
+                                        uint32_t *hq = a.hist + (size_t)s_q[m] * kHistBins;
+                                        if (odd == 0u) {
+                                            if (ln == leader) atomicAdd(hq + b0, (uint32_t)__popc(gmask));
+                                        } else if (pass) {
+                                            atomicAdd(hq + b, 1u);
+                                        }
+                                    }
                                 }
                             }
                         }
@@ -166,12 +264,17 @@ __global__ __launch_bounds__(WAVES * 64) void scan_kernel(ScanArgs a)
                 }
             }
         }
+        __syncthreads();
+        if (tid == 0) s_misc[0] = gridDim.x + atomicAdd(a.tile_ctr, 1u) * grab;
+        __syncthreads();
+        t0 = s_misc[0];
+        t1 = min(t0 + grab, ntiles);
     }
 }
 
 int scan_lds_bytes(int row_bytes, int mq)
 {
-    return mq * (row_bytes + kQPadBytes) + mq * 8 + 16;
+    return mq * (row_bytes + kQPadBytes) + mq * 28 + 16;
 }
 
 // Largest query group (16, 32 or 64 slots) whose LDS tile fits.  fp32 storage is held to
@@ -187,39 +290,44 @@ int scan_max_mq(int row_bytes, int storage, int lds_limit)
     return best;
 }
 
-template <int STORAGE, int MT, int WAVES>
+template <int STORAGE, int MT, int WAVES, bool GATED>
 static hipError_t launch_one(const ScanArgs &a, int grid, hipStream_t s)
 {
     const int lds = scan_lds_bytes(a.row_bytes, MT * 16);
     static int attr_bytes = 0; // per instantiation: dynamic LDS size the kernel is cleared for
     if (lds > attr_bytes) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_kernel<STORAGE, MT, WAVES>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_kernel<STORAGE, MT, WAVES, GATED>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
         attr_bytes = lds;
     }
-    hipLaunchKernelGGL((scan_kernel<STORAGE, MT, WAVES>), dim3(grid), dim3(WAVES * 64), lds, s, a);
+    hipLaunchKernelGGL((scan_kernel<STORAGE, MT, WAVES, GATED>), dim3(grid), dim3(WAVES * 64), lds, s, a);
     return hipGetLastError();
 }
 
-template <int STORAGE, int WAVES>
+template <int STORAGE, int WAVES, bool GATED>
 static hipError_t launch_mt(const ScanArgs &a, int grid, hipStream_t s)
 {
     switch (a.mq) {
-    case 16: return launch_one<STORAGE, 1, WAVES>(a, grid, s);
-    case 32: return launch_one<STORAGE, 2, WAVES>(a, grid, s);
-    case 64: return launch_one<STORAGE, 4, WAVES>(a, grid, s);
+    case 16: return launch_one<STORAGE, 1, WAVES, GATED>(a, grid, s);
+    case 32: return launch_one<STORAGE, 2, WAVES, GATED>(a, grid, s);
+    case 64: return launch_one<STORAGE, 4, WAVES, GATED>(a, grid, s);
     default: return hipErrorInvalidValue;
     }
 }
 
+// waves_per_wg: 4 for list pages, 1 for the narrow tiles of the coarse and sampling passes
 hipError_t launch_scan(const ScanArgs &a, int waves_per_wg, int grid, hipStream_t s)
 {
     if (a.row_bytes <= 0 || a.row_bytes % kIterBytes != 0) return hipErrorInvalidValue;
+    const bool gated = a.tau != nullptr;
+    if (gated && waves_per_wg != 4) return hipErrorInvalidValue;
     if (a.storage == PK_F16) {
-        return waves_per_wg == 1 ? launch_mt<PK_F16, 1>(a, grid, s) : launch_mt<PK_F16, 4>(a, grid, s);
+        if (gated) return launch_mt<PK_F16, 4, true>(a, grid, s);
+        return waves_per_wg == 1 ? launch_mt<PK_F16, 1, false>(a, grid, s) : launch_mt<PK_F16, 4, false>(a, grid, s);
     }
-    return waves_per_wg == 1 ? launch_mt<PK_F32, 1>(a, grid, s) : launch_mt<PK_F32, 4>(a, grid, s);
+    if (gated) return launch_mt<PK_F32, 4, true>(a, grid, s);
+    return waves_per_wg == 1 ? launch_mt<PK_F32, 1, false>(a, grid, s) : launch_mt<PK_F32, 4, false>(a, grid, s);
 }
 
 } // namespace pk

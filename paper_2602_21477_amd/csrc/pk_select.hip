@@ -16,20 +16,6 @@ namespace pk {
 typedef unsigned long long u64;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ uint32_t order_bits(float v, int metric)
-{
-    const uint32_t b = __float_as_uint(v);
-    const uint32_t asc = b ^ ((b >> 31) ? 0xffffffffu : 0x80000000u);
-    return metric == PK_METRIC_L2 ? asc : ~asc;
-}
-
-__device__ __forceinline__ float value_of(uint32_t ob, int metric)
-{
-    const uint32_t asc = metric == PK_METRIC_L2 ? ob : ~ob;
-    const uint32_t b = (asc & 0x80000000u) ? (asc ^ 0x80000000u) : ~asc;
-    return __uint_as_float(b);
-}
-
 __device__ __forceinline__ uint32_t next_pow2(uint32_t n)
 {
     uint32_t p = 2;
@@ -112,20 +98,38 @@ __global__ __launch_bounds__(kSelThreads) void select_partial_kernel(SelectArgs 
     const uint32_t total = a.qcnt[q];
     const uint32_t beg = c * (uint32_t)kSelChunk;
     const uint32_t end = min(beg + (uint32_t)kSelChunk, total);
+    // nothing in this chunk; and a query whose emitted keys fit one chunk is merged directly
+    // by the final kernel
+    if (beg >= total || (!a.vals && total <= (uint32_t)kSelChunk)) return;
     u64 *out = a.partial + ((size_t)q * a.nchunks + c) * a.K;
 
     Selector sel;
     sel.init(keys, &s_cnt, a.K);
-    const float *v = a.vals + base;
     constexpr uint32_t kRound = kSelThreads * kSelVec;
-    for (uint32_t r = beg; r < end; r += kRound) {
-        sel.reserve(kRound);
-        const uint32_t p = r + threadIdx.x * kSelVec;
-        if (p < end) {
-            const f32x4 x = *reinterpret_cast<const f32x4 *>(v + p);
+    if (a.vals) {
+        const float *v = a.vals + base;
+        for (uint32_t r = beg; r < end; r += kRound) {
+            sel.reserve(kRound);
+            const uint32_t p = r + threadIdx.x * kSelVec;
+            if (p < end) {
+                const f32x4 x = *reinterpret_cast<const f32x4 *>(v + p);
+#pragma unroll
+                for (int j = 0; j < kSelVec; ++j)
+                    if (p + j < end) sel.push(((u64)order_bits(x[j], a.metric) << 32) | (p + j));
+            }
+        }
+    } else {
+        // keys were emitted under a threshold that tightened over time, so the latest are
+        // the best: reading the range backwards sets a tight selection threshold at once
+        const u64 *v = a.keys + base;
+        for (uint32_t r = end; r > beg;) {
+            const uint32_t lo = r - beg > kRound ? r - kRound : beg;
+            sel.reserve(kRound);
+            const uint32_t p = lo + threadIdx.x * kSelVec;
 #pragma unroll
             for (int j = 0; j < kSelVec; ++j)
-                if (p + j < end) sel.push(((u64)order_bits(x[j], a.metric) << 32) | (p + j));
+                if (p + j < r) sel.push(v[p + j]);
+            r = lo;
         }
     }
     sel.flush();
@@ -191,10 +195,31 @@ __global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, 
     const int k = a.k;
     Selector sel;
     sel.init(keys, &s_cnt, a.K);
-    const uint32_t n = merge_partials(sel, a.partial + (size_t)q * a.nchunks * a.K, a.nchunks, a.K);
+    const uint32_t cnt_q = a.qcnt[q];
+    if (threadIdx.x == 0) atomicAdd(&h.ix[0]->stats[3], (unsigned long long)cnt_q);
+    uint32_t n;
+    if (cnt_q <= (uint32_t)kSelChunk) {
+        // few emitted candidates: select straight from the query's region
+        const u64 *v = a.keys + a.qoff[q];
+        constexpr uint32_t kRound = kSelThreads * kSelVec;
+        for (uint32_t r = cnt_q; r > 0;) { // latest (best) keys first, see select_partial_kernel
+            const uint32_t lo = r > kRound ? r - kRound : 0u;
+            sel.reserve(kRound);
+            const uint32_t p = lo + threadIdx.x * kSelVec;
+#pragma unroll
+            for (int j = 0; j < kSelVec; ++j)
+                if (p + j < r) sel.push(v[p + j]);
+            r = lo;
+        }
+        sel.flush();
+        n = s_cnt;
+    } else {
+        const int used = (int)((cnt_q + kSelChunk - 1) / kSelChunk);
+        n = merge_partials(sel, a.partial + (size_t)q * a.nchunks * a.K, used, a.K);
+    }
 
     // entries carrying the padding value are not candidates
-    const uint32_t worst = order_bits(a.metric == PK_METRIC_IP ? -INFINITY : INFINITY, a.metric);
+    const uint32_t worst = kWorstBits;
     uint32_t n_valid = 0;
     for (uint32_t i = 0; i < n; ++i) { // n <= K, uniform loop
         if ((uint32_t)(keys[i] >> 32) >= worst) break;
@@ -216,8 +241,9 @@ __global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, 
         for (uint32_t t = nb; t < (uint32_t)k; ++t) {
             long long best = INT64_MAX;
             for (uint32_t p = threadIdx.x; p < total; p += blockDim.x) {
-                if (order_bits(a.vals[base + p], a.metric) == tau) {
-                    const long long id = resolve_id(a, h, q, p);
+                const u64 key = a.keys[base + p];
+                if ((uint32_t)(key >> 32) == tau) {
+                    const long long id = resolve_id(a, h, q, (uint32_t)key);
                     if (id > last && id < best) best = id;
                 }
             }
@@ -257,6 +283,46 @@ __global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, 
             a.out_dist[(size_t)q * k + i] = a.metric == PK_METRIC_IP ? -INFINITY : INFINITY;
         }
     }
+}
+
+// k-th best of each query's sample -> threshold key; fewer than k real samples: no threshold
+__global__ __launch_bounds__(kSelThreads) void tau_kernel(SampleArgs a)
+{
+    __shared__ u64 keys[kSelCap];
+    __shared__ uint32_t s_cnt;
+    const uint32_t q = blockIdx.x;
+    Selector sel;
+    sel.init(keys, &s_cnt, a.k);
+    const float *v = a.vals + (size_t)q * a.span;
+    constexpr uint32_t kRound = kSelThreads * kSelVec;
+    for (uint32_t r = 0; r < a.span; r += kRound) {
+        sel.reserve(kRound);
+        const uint32_t p = r + threadIdx.x * kSelVec;
+        if (p < a.span) {
+            const f32x4 x = *reinterpret_cast<const f32x4 *>(v + p);
+#pragma unroll
+            for (int j = 0; j < kSelVec; ++j) {
+                const uint32_t b = order_bits(x[j], a.metric);
+                if (b < kWorstBits) sel.push(((u64)b << 32) | (p + j));
+            }
+        }
+    }
+    sel.flush();
+    if (threadIdx.x == 0) {
+        a.tau[q] = s_cnt >= (uint32_t)a.k ? (uint32_t)(keys[a.k - 1] >> 32) : 0xffffffffu;
+        a.tcur[q] = a.tau[q];
+        a.tlo[q] = s_cnt > 0 ? (uint32_t)(keys[0] >> 32) : 0u;
+        a.thi[q] = s_cnt >= (uint32_t)a.k ? (uint32_t)(keys[a.k - 1] >> 32)
+                                          : (s_cnt > 0 ? (uint32_t)(keys[s_cnt - 1] >> 32) : 0u);
+    }
+    if (threadIdx.x < kHistBins) a.hist[(size_t)q * kHistBins + threadIdx.x] = 0u;
+}
+
+hipError_t launch_tau(const SampleArgs &a, hipStream_t s)
+{
+    if (a.nq <= 0) return hipSuccess;
+    hipLaunchKernelGGL(tau_kernel, dim3((uint32_t)a.nq), dim3(kSelThreads), 0, s, a);
+    return hipGetLastError();
 }
 
 hipError_t launch_select_partial(const SelectArgs &a, int64_t nq, hipStream_t s)

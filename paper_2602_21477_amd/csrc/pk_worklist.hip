@@ -7,6 +7,8 @@
 // pages and every page is paired with groups of at most MQ of the queries that probe it.
 // Lists therefore are read once per batch, not once per query, and a 400 k-vector list
 // is as good a citizen as a 50-vector one.
+#include <algorithm>
+
 #include "pk_internal.h"
 
 namespace pk {
@@ -177,6 +179,7 @@ __global__ __launch_bounds__(256) void wl_count_kernel(WorklistArgs a, MultiArgs
         }
         po[a.nprobe] = acc;
         a.qtot[q] = acc;
+        a.ccnt[q] = 0;
     }
 }
 
@@ -216,7 +219,7 @@ __global__ __launch_bounds__(1024) void wl_scan_kernel(WorklistArgs a, MultiArgs
         }
         a.scalars[0] = nt;
         a.scalars[1] = 0;
-        uint32_t g = nt / (uint32_t)(a.scan_grid * 4);
+        uint32_t g = nt / (uint32_t)(a.scan_grid * a.grab_div);
         a.scalars[2] = g < 1 ? 1 : (g > 8 ? 8 : g);
         a.scalars[3] = total;
         atomicAdd(&m.ix[0]->stats[1], (unsigned long long)total);
@@ -270,6 +273,65 @@ __global__ __launch_bounds__(64) void wl_tiles_kernel(WorklistArgs a, MultiArgs 
         tl.pad = 0;
         a.tiles[t0 + j] = tl;
     }
+}
+
+// ------------------------------------------------------------- threshold sampling
+
+// One tile per (query, sample page): pages 0 .. sp-1 of the query's first probed list, one
+// query slot each.  Also pre-fills the sample values with the padding value, so rows that
+// do not exist (short lists) never count.
+__global__ void sample_tiles_kernel(SampleArgs a, MultiArgs m)
+{
+    const size_t nvals = (size_t)a.nq * a.span;
+    const float worst = a.metric == PK_METRIC_IP ? -INFINITY : INFINITY;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvals; i += (size_t)gridDim.x * blockDim.x)
+        a.vals[i] = worst;
+    const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
+    const uint32_t ntiles = (uint32_t)a.nq * (uint32_t)a.sp;
+    if (t == 0) {
+        a.scalars[0] = ntiles;
+        a.scalars[1] = 0;
+        uint32_t g = ntiles / (uint32_t)(a.scan_grid * 4);
+        a.scalars[2] = g < 1 ? 1 : (g > 8 ? 8 : g);
+    }
+    if (t >= ntiles) return;
+    const uint32_t q = t / (uint32_t)a.sp, p = t - q * (uint32_t)a.sp;
+    if (p == 0) {
+        a.slot_query[q] = q;
+        a.slot_out[q] = q * a.span;
+    }
+    const DevIndex &ix = *m.ix[a.qagent[q]];
+    const uint32_t l = (uint32_t)a.probes[(size_t)q * a.nprobe];
+    const uint32_t P = (uint32_t)ix.P;
+    Tile tl;
+    tl.x = ix.arenas[0].vec;
+    tl.xn = ix.arenas[0].norm;
+    tl.row0 = p * P;
+    tl.qbeg = q;
+    tl.nrows = 0;
+    tl.qcnt = 1;
+    tl.pad = 0;
+    if (l < (uint32_t)ix.nlist) {
+        const uint32_t len = ix.list_len[l];
+        if (p * P < len) {
+            const uint32_t pg = phys_page(ix, l, p);
+            const Arena &ar = arena_of(ix, pg);
+            const size_t local = pg - ar.first_page;
+            tl.x = ar.vec + local * P * (size_t)ix.row_bytes;
+            tl.xn = ar.norm + local * P;
+            const uint32_t left = len - p * P;
+            tl.nrows = (uint16_t)(left < P ? left : P);
+        }
+    }
+    a.tiles[t] = tl;
+}
+
+hipError_t launch_sample_tiles(const SampleArgs &a, const MultiArgs &m, hipStream_t s)
+{
+    const size_t n = (size_t)a.nq * a.span;
+    const uint32_t grid = (uint32_t)std::min<size_t>((n + 255) / 256, 4096) + (uint32_t)((a.nq * a.sp + 255) / 256);
+    hipLaunchKernelGGL(sample_tiles_kernel, dim3(grid), dim3(256), 0, s, a, m);
+    return hipGetLastError();
 }
 
 hipError_t launch_worklist(const WorklistArgs &a, const MultiArgs &m, hipStream_t s)

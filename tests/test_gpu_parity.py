@@ -246,6 +246,21 @@ def test_wide_rows_many_queries_per_list(gpu_device):
             p.close()
 
 
+def test_large_k_no_threshold_and_chunked_selection(gpu_device):
+    """k larger than the first probed list: no threshold can be drawn, every candidate is emitted,
+    and the per-query selection runs over several chunks (> 32768 candidates)."""
+    cfg = W.scaled(W.C1, n=45000)
+    p, _ = make_pair(cfg, metric=L2)
+    try:
+        q = W.queries(cfg, 9, 6)
+        say("large k")
+        p.check_search(q, 1000, 64)
+        p.check_search(q, 1024, 64)
+        p.check_search(q, 300, 20)
+    finally:
+        p.close()
+
+
 def test_arena_exhaustion_is_reported_and_recoverable(gpu_device):
     cfg = W.scaled(W.C1, n=3000)
     x = W.vectors(cfg, 0, cfg.n)
