@@ -1,12 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of the IVF hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4]
 
-A step is one pass of the whole hot path over one batch of the workload: coarse search,
-work-list build, list scan, top-k merge for the query batch, plus the insert batch the
-config interleaves (assign + append).  All inputs are resident in HBM before the timed
-region.  Prints ONE JSON line (see the design doc for the fields).
+A step is one pass of the whole hot path over one batch of the workload: coarse search
+(centroid scoring + top-nprobe), threshold sampling, work-list build, list scan, top-k
+merge for the query batch, plus the insert batch the config interleaves (assign +
+append).  All inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+
+Workloads (benchmark configs): c1 tiny, c2 single agent, c3 multi agent, c4 large
+static fp16 index under both metrics (c4l2 / c4ip: one of them), c5 skewed dynamic.  The
+default, c4, is the 10 M-vector config the HBM target is quoted on; its headline value is
+the slower of its two metric variants.
 """
 from __future__ import annotations
 
@@ -23,102 +28,152 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X datasheet HBM3E bandwidth
+METRIC_NAME = "search queries/sec at recall@10>=0.9 (1 GPU); list-scan HBM GB/s vs peak"
 
 
 def log(msg):
     print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
 
 
-class SingleIndexWorkload:
-    """Configs with one index: c1 (tiny), c2 (single agent), c4 (large static fp16), c5 (skewed dynamic)."""
+def host_threads():
+    return min(16, len(os.sched_getaffinity(0)))
 
-    def __init__(self, cfg, steps_total, threads):
+
+class Data:
+    """Host-side inputs of one agent's memory: rows, centroids (and mixture components)."""
+
+    def __init__(self, cfg, n=None, agent=0):
+        from paper_2602_21477_amd import workload as W
+        n = cfg.n if n is None else n
+        t0 = time.time()
+        if cfg.train == "component_means":
+            self.x, comp = W.vectors(cfg, 0, n, agent=agent, threads=host_threads(), with_components=True)
+            self.cent = W.train_centroids(cfg, self.x, agent=agent, comp=comp)
+        else:
+            self.x = W.vectors(cfg, 0, n, agent=agent, threads=host_threads())
+            self.cent = W.train_centroids(cfg, self.x, agent=agent)
+        self.n, self.agent = n, agent
+        log(f"agent {agent}: generated {n} x {cfg.d} and trained {cfg.nlist} centroids in {time.time() - t0:.1f}s")
+
+    def upload(self):
+        import torch
+        xd = torch.empty(self.x.shape, dtype=torch.float32, device="cuda")
+        step = 1 << 20
+        for s in range(0, self.n, step):
+            xd[s:s + step].copy_(torch.from_numpy(self.x[s:s + step]))
+        return xd
+
+
+class Scenario:
+    """One timed configuration: indexes on the GPU, query / insert batches resident in HBM."""
+
+    INSERTS = {1: 1, 2: 8, 3: 16, 4: 0, 5: 1}  # insert batch per step (c3: up to 16 per agent)
+    N_QUERY_BATCHES = 16
+
+    def __init__(self, cfg, datas, steps_total, xd=None, reserve=None):
         import torch
         from paper_2602_21477_amd import binding as B
         from paper_2602_21477_amd import workload as W
-        self.cfg, self.W, self.B, self.torch = cfg, W, B, torch
-        self.threads = threads
-        self.insert_m = {1: 1, 2: 8, 4: 0, 5: 1}[cfg.index]
-        self.n_query_batches = 16
-        self.steps_total = steps_total
-
-    def setup(self):
-        cfg, W, B, torch = self.cfg, self.W, self.B, self.torch
+        self.cfg, self.B, self.W, self.torch = cfg, B, W, torch
+        self.datas = datas
+        self.insert_m = self.INSERTS[cfg.index]
         t0 = time.time()
-        if cfg.train == "component_means":
-            self.x, comp = W.vectors(cfg, 0, cfg.n, threads=self.threads, with_components=True)
-            self.cent = W.train_centroids(cfg, self.x, comp=comp)
-        else:
-            self.x = W.vectors(cfg, 0, cfg.n, threads=self.threads)
-            log(f"generated {cfg.n} x {cfg.d} in {time.time() - t0:.1f}s")
-            t1 = time.time()
-            self.cent = W.train_centroids(cfg, self.x)
-            log(f"trained {cfg.nlist} centroids in {time.time() - t1:.1f}s")
-        t1 = time.time()
-        xd = torch.empty((cfg.n, cfg.d), dtype=torch.float32, device="cuda")
-        step = 1 << 20
-        for s in range(0, cfg.n, step):
-            xd[s:s + step].copy_(torch.from_numpy(self.x[s:s + step]))
-        reserve = self.insert_m * self.steps_total
-        self.index = B.Index(torch.from_numpy(self.cent).cuda(), xd, metric=cfg.metric, storage=cfg.storage,
-                             insert_reserve=reserve + 1024)
-        del xd
+        self.indexes = []
+        for a, dat in enumerate(datas):
+            xa = xd if xd is not None else dat.upload()
+            self.indexes.append(B.Index(torch.from_numpy(dat.cent).cuda(), xa, metric=cfg.metric, storage=cfg.storage,
+                                        insert_reserve=(self.insert_m * steps_total + 1024) if reserve is None
+                                        else reserve))
+            del xa
         torch.cuda.synchronize()
         torch.cuda.empty_cache()
-        log(f"uploaded and built the index in {time.time() - t1:.1f}s")
-        self.q_host = [W.queries(cfg, b) for b in range(self.n_query_batches)]
+        log(f"built {len(datas)} index(es) ({'ip' if cfg.metric == W.METRIC_IP else 'l2'}) in {time.time() - t0:.1f}s")
+        na = len(datas)
+        self.q_host = [np.concatenate([W.queries(cfg, b, agent=a) for a in range(na)])
+                       for b in range(self.N_QUERY_BATCHES)]
         self.q = [torch.from_numpy(q).cuda() for q in self.q_host]
-        self.out_ids = torch.empty((cfg.nq, cfg.k), dtype=torch.int64, device="cuda")
-        self.out_dist = torch.empty((cfg.nq, cfg.k), dtype=torch.float32, device="cuda")
+        self.q_offsets = [a * cfg.nq for a in range(na + 1)]
+        nq = na * cfg.nq
+        self.out_ids = torch.empty((nq, cfg.k), dtype=torch.int64, device="cuda")
+        self.out_dist = torch.empty((nq, cfg.k), dtype=torch.float32, device="cuda")
+        self.ins, self.ins_sizes = [], []
         if self.insert_m:
-            ins = np.concatenate([W.inserts(cfg, b, 256) for b in range((reserve + 255) // 256)])
-            self.ins = torch.from_numpy(ins).cuda()
+            for a in range(na):
+                total = self.insert_m * steps_total
+                ins = np.concatenate([W.inserts(cfg, b, 256, agent=a) for b in range((total + 255) // 256)])
+                self.ins.append(torch.from_numpy(ins).cuda())
+                if cfg.index == 3:
+                    self.ins_sizes.append(W.insert_batch_sizes(cfg, steps_total, agent=a))
+        self.ins_pos = [0] * na
         self.step_no = 0
         torch.cuda.synchronize()
 
     @property
     def handle(self):
-        return self.index.handle
+        return self.indexes[0].handle
+
+    def _insert(self, a, m):
+        lo = self.ins_pos[a]
+        self.B.pk_insert(self.indexes[a].handle, self.ins[a][lo:lo + m])
+        self.ins_pos[a] = lo + m
 
     def step(self):
         B, cfg, i = self.B, self.cfg, self.step_no
-        if cfg.index == 5 and self.insert_m:  # skewed dynamic: insert first, then search
-            B.pk_insert(self.handle, self.ins[i:i + 1])
-        B.pk_search(self.handle, self.q[i % self.n_query_batches], cfg.k, cfg.nprobe, self.out_ids, self.out_dist)
-        if cfg.index != 5 and self.insert_m:
-            m = self.insert_m
-            B.pk_insert(self.handle, self.ins[i * m:(i + 1) * m])
+        q = self.q[i % self.N_QUERY_BATCHES]
+        if cfg.index == 5:  # skewed dynamic: 1:1 interleave, the insert comes first
+            self._insert(0, 1)
+        if len(self.indexes) == 1:
+            B.pk_search(self.handle, q, cfg.k, cfg.nprobe, self.out_ids, self.out_dist)
+        else:
+            B.pk_search_multi([ix.handle for ix in self.indexes], self.q_offsets, q, cfg.k, cfg.nprobe,
+                              self.out_ids, self.out_dist)
+        if cfg.index == 3:
+            for a in range(len(self.indexes)):
+                self._insert(a, int(self.ins_sizes[a][i]))
+        elif cfg.index != 5 and self.insert_m:
+            self._insert(0, self.insert_m)
         self.step_no += 1
 
     def queries_per_step(self):
-        return self.cfg.nq
+        return self.cfg.nq * len(self.indexes)
 
     def row_bytes(self):
         return self.cfg.d * (2 if self.cfg.storage == self.B.PK_F16 else 4)
 
+    def n_total(self):
+        return int(sum(ix.stats().n_total for ix in self.indexes))
+
+    def check_errors(self):
+        for ix in self.indexes:
+            st = ix.stats()
+            if st.device_error:
+                raise SystemExit(f"device error flag {st.device_error}")
+
     def recall(self, nsample):
-        """recall@10 of the GPU search against the oracle's exact search on a few queries."""
+        """recall@10 of the GPU search against the oracle's exact search on a few queries of agent 0
+        (base rows only: called before the timed steps insert anything)."""
         import oracle
         q = self.q_host[0][:nsample]
-        ids, _ = self.index.search(self.q[0][:nsample].contiguous(), max(10, self.cfg.k), self.cfg.nprobe)
-        bi, _ = oracle.bruteforce(self.x, q, 10, self.cfg.metric)
+        ids, _ = self.indexes[0].search(self.q[0][:nsample].contiguous(), max(10, self.cfg.k), self.cfg.nprobe)
+        bi, _ = oracle.bruteforce(self.datas[0].x, q, 10, self.cfg.metric)
         got = ids.cpu().numpy()
         return float(np.mean([len(set(a[:10].tolist()) & set(b.tolist())) / 10.0 for a, b in zip(got, bi)]))
 
     def cpu_baseline(self, budget_s=12.0):
-        """The oracle as it stands, on a bounded sample: an index over the first n/f rows with nlist/f
-        lists (same list length, same nprobe and k, so the same number of vectors scanned per query)."""
+        """The oracle as it stands, on a bounded sample: an index over the first n/f rows of agent 0 with
+        nlist/f lists (same list length, same nprobe and k, so the same number of vectors scanned per
+        query as in the full workload)."""
         import oracle
-        cfg, W = self.cfg, self.W
+        cfg, W, dat = self.cfg, self.W, self.datas[0]
         f = 1
-        while cfg.n // f * (cfg.nlist // f) * cfg.d > 2.5e10 and cfg.nlist // (f * 2) >= cfg.nprobe:
+        while dat.n // f * (cfg.nlist // f) * cfg.d > 2.5e10 and cfg.nlist // (f * 2) >= cfg.nprobe:
             f *= 2
-        n_s, nlist_s = cfg.n // f, cfg.nlist // f
-        xs = self.x[:n_s]
+        n_s, nlist_s = dat.n // f, cfg.nlist // f
+        xs = dat.x[:n_s]
         if f == 1:
-            cent = self.cent
+            cent = dat.cent
         elif cfg.train == "component_means":
-            cent = self.cent[:nlist_s]
+            cent = dat.cent[:nlist_s]
         else:
             sub = W.scaled(cfg, nlist=nlist_s)
             rows = W.train_rows(sub, n_s)
@@ -142,6 +197,51 @@ class SingleIndexWorkload:
                           f"vectors scanned per query; <= {scanned:.0f} per query); oracle build {build_s:.1f}s not "
                           f"included"}
 
+    def close(self):
+        for ix in self.indexes:
+            ix.close()
+        self.indexes = []
+        self.torch.cuda.empty_cache()
+
+
+def measure(sc, steps, warmup, recall_queries):
+    """Warm-up, K timed steps, the same K steps again with stage events; returns the result dict."""
+    import torch
+    B = sc.B
+    rec = sc.recall(recall_queries) if recall_queries else None
+    for _ in range(warmup):
+        sc.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        sc.step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    qps = sc.queries_per_step() * steps / dt
+    # stage timing: HIP events recorded by the library on the search's own stream
+    B.pk_profile_begin(sc.handle)
+    for _ in range(steps):
+        sc.step()
+    pr = B.pk_profile_end(sc.handle)
+    sc.check_errors()
+    n = max(pr.launches, 1)
+    scan_ms = pr.scan_ms / n
+    alg_bytes = pr.scanned_rows / n * sc.row_bytes()
+    achieved = alg_bytes / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else 0.0
+    res = {
+        "qps": qps, "ms_per_step": dt / steps * 1e3, "recall_at_10": rec,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "pk::scan_kernel (gated list scan)",
+                     "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": scan_ms},
+        "stages_ms": {"coarse": pr.coarse_ms / n, "sample_and_worklist": pr.worklist_ms / n, "scan": scan_ms,
+                      "select": pr.select_ms / n},
+        "per_search": {"tiles": pr.tiles / n, "candidates": pr.candidates / n, "emitted": pr.emitted / n,
+                       "scanned_rows": pr.scanned_rows / n},
+    }
+    log(f"{qps:.0f} queries/s, {res['ms_per_step']:.3f} ms/step, scan {scan_ms:.3f} ms = {achieved:.0f} GB/s "
+        f"({achieved / HBM_PEAK_GBS:.3f} of peak), recall@10 {rec}, stages {res['stages_ms']}")
+    return res
+
 
 def run(args):
     import torch
@@ -152,59 +252,46 @@ def run(args):
         raise SystemExit("bench.py needs a GPU (the HIP path has no CPU fallback)")
     torch.cuda.set_device(0)
     B.lib()
-    cfg = {"c1": W.C1, "c2": W.C2, "c4": W.C4, "c4ip": W.scaled(W.C4, metric=W.METRIC_IP), "c5": W.C5}[args.workload]
+    name = args.workload
+    base = {"c1": W.C1, "c2": W.C2, "c3": W.C3, "c4": W.C4, "c4l2": W.C4, "c4ip": W.C4, "c5": W.C5}[name]
+    metrics = {"c4": [W.METRIC_L2, W.METRIC_IP], "c4l2": [W.METRIC_L2], "c4ip": [W.METRIC_IP]}.get(name, [base.metric])
     steps_total = args.warmup + 2 * args.steps + 8
-    threads = min(16, len(os.sched_getaffinity(0)))
-    wl = SingleIndexWorkload(cfg, steps_total, threads)
-    wl.setup()
+    if base.n_agents > 1:
+        sizes = W.agent_sizes(base)
+        datas = [Data(base, int(sizes[a]), a) for a in range(base.n_agents)]
+    else:
+        datas = [Data(base)]
+    xd = datas[0].upload() if len(metrics) > 1 else None  # shared by the variants' builds
 
-    for _ in range(args.warmup):
-        wl.step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        wl.step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt / args.steps * 1e3
-    qps = wl.queries_per_step() * args.steps / dt
-    log(f"{args.steps} steps in {dt:.3f}s -> {qps:.0f} queries/s")
-
-    # same steps again with HIP events around the stages of every search (on the search's stream)
-    B.pk_profile_begin(wl.handle)
-    for _ in range(args.steps):
-        wl.step()
-    pr = B.pk_profile_end(wl.handle)
-    n = max(pr.launches, 1)
-    scan_ms = pr.scan_ms / n
-    alg_bytes = pr.scanned_rows / n * wl.row_bytes()
-    achieved = alg_bytes / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else 0.0
-    stages = {"coarse_ms": pr.coarse_ms / n, "worklist_ms": pr.worklist_ms / n, "scan_ms": scan_ms,
-              "select_ms": pr.select_ms / n, "tiles": pr.tiles / n, "candidates": pr.candidates / n,
-              "emitted": pr.emitted / n}
-    log(f"stages per search: {stages}")
-    st = wl.index.stats()
-    if st.device_error:
-        raise SystemExit(f"device error flag {st.device_error}")
-
+    results = {}
+    for metric in metrics:
+        cfg = W.scaled(base, metric=metric)
+        sc = Scenario(cfg, datas, steps_total, xd=xd)
+        res = measure(sc, args.steps, args.warmup, 0 if args.no_recall else args.recall_queries)
+        res["n"] = sc.n_total()
+        results["ip" if metric == W.METRIC_IP else "l2"] = (res, sc, cfg)
+        if metric != metrics[-1]:
+            sc.close()
+    del xd
+    # headline: the slower variant
+    head = min(results, key=lambda m: results[m][0]["qps"])
+    res, sc, cfg = results[head]
     out = {
-        "metric": "search queries/sec at recall@10>=0.9 (1 GPU); list-scan HBM GB/s vs peak",
-        "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16" if cfg.storage == B.PK_F16 else "f32", "data": "synthetic",
-        "config": {"workload": cfg.name, "n": int(st.n_total), "d": cfg.d, "nlist": cfg.nlist, "nprobe": cfg.nprobe,
-                   "k": cfg.k, "queries_per_step": cfg.nq, "inserts_per_step": wl.insert_m,
-                   "metric": "ip" if cfg.metric == W.METRIC_IP else "l2"},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "scan_kernel (list scan)",
-                     "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": scan_ms},
-        "stages_ms": stages,
+        "metric": METRIC_NAME, "value": res["qps"], "unit": "queries/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16" if cfg.storage == B.PK_F16 else "f32", "data": "synthetic",
+        "config": {"workload": base.name, "n": res["n"], "d": cfg.d, "nlist": cfg.nlist, "nprobe": cfg.nprobe,
+                   "k": cfg.k, "agents": len(datas), "queries_per_step": sc.queries_per_step(),
+                   "inserts_per_step": sc.insert_m, "metric": head},
+        "roofline": res["roofline"], "stages_ms": res["stages_ms"], "per_search": res["per_search"],
+        "recall_at_10": res["recall_at_10"],
     }
-    if not args.no_recall:
-        out["recall_at_10"] = wl.recall(args.recall_queries)
-        log(f"recall@10 = {out['recall_at_10']:.4f}")
+    if len(results) > 1:
+        out["variants"] = {m: {k: v for k, v in r[0].items()} for m, r in results.items()}
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = wl.cpu_baseline()
+        # the headline scenario is the last one still open only if it ran last; rebuild nothing: the
+        # baseline needs host data only
+        out["cpu_baseline"] = sc.cpu_baseline()
         log(f"cpu baseline: {out['cpu_baseline']['value']:.1f} queries/s on {out['cpu_baseline']['cores']} threads")
     print(json.dumps(out), flush=True)
 
@@ -212,9 +299,9 @@ def run(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c4", "c4ip", "c5"])
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4", "c4l2", "c4ip", "c5"])
     ap.add_argument("--recall-queries", type=int, default=8)
     ap.add_argument("--no-recall", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")

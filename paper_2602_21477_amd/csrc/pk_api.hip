@@ -109,9 +109,16 @@ int ensure_ws(pk_index *ix, size_t bytes, hipStream_t s)
     return PK_OK;
 }
 
+// Pages that `t` more vectors can open at most: one per touched list (its tail page may be
+// full) plus one per P vectors.
+uint64_t pages_for(const pk_index *ix, uint64_t t)
+{
+    return (t + ix->P - 1) / ix->P + std::min<uint64_t>(t, (uint64_t)ix->cfg.nlist);
+}
+
 uint32_t pages_used_ub(const pk_index *ix)
 {
-    const uint64_t ub = (uint64_t)ix->pages_known + (uint64_t)(ix->n_inserted - ix->inserted_at_known);
+    const uint64_t ub = (uint64_t)ix->pages_known + pages_for(ix, (uint64_t)(ix->n_inserted - ix->inserted_at_known));
     return (uint32_t)std::min<uint64_t>(ub, ix->pages_total);
 }
 
@@ -131,9 +138,9 @@ struct Plan {
     bool need_coarse, need_fine, f16;
     // buffers
     char *qs32, *qs;
-    float *qn32, *qn, *S, *svals;
+    float *qn32, *qn, *S, *svals, *tlo, *tinv;
     uint32_t *cand_off, *cand_cnt, *cslot_q, *cslot_o, *lcnt, *lstart, *lfill, *ltile, *pair_off, *qtot, *qoff, *slot_q,
-        *slot_o, *scalars, *tau, *tlo, *thi, *tcur, *hist, *ccnt, *sslot_q, *sslot_o;
+        *slot_o, *scalars, *tau, *tcur, *hist, *ccnt, *sslot_q, *sslot_o;
     uint16_t *qagent;
     Tile *ctile_buf, *tiles, *stiles;
     unsigned long long *cpartial, *partial, *cbuf;
@@ -179,8 +186,8 @@ void carve(Plan &p, char *base, const pk_index *own)
         p.slot_o = c.take<uint32_t>(nq * p.nprobe);
         p.tiles = c.take<Tile>((size_t)p.tile_cap + 1);
         p.tau = c.take<uint32_t>(nq);
-        p.tlo = c.take<uint32_t>(nq);
-        p.thi = c.take<uint32_t>(nq);
+        p.tlo = c.take<float>(nq);
+        p.tinv = c.take<float>(nq);
         p.tcur = c.take<uint32_t>(nq);
         p.hist = c.take<uint32_t>(nq * kHistBins);
         p.ccnt = c.take<uint32_t>(nq);
@@ -374,7 +381,7 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
     sm.scalars = p.scalars + 8;
     sm.tau = p.tau;
     sm.tlo = p.tlo;
-    sm.thi = p.thi;
+    sm.tinv = p.tinv;
     sm.tcur = p.tcur;
     sm.hist = p.hist;
     PK_HIP(launch_sample_tiles(sm, m, s));
@@ -433,7 +440,7 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
     sa.out = nullptr;
     sa.tau = p.tau;
     sa.tlo = p.tlo;
-    sa.thi = p.thi;
+    sa.tinv = p.tinv;
     sa.tcur = p.tcur;
     sa.use_hist = tune("PK_TUNE_HIST", 1);
     sa.hist = p.hist;
@@ -646,13 +653,33 @@ int insert_impl(pk_index *ix, const float *x, const int64_t *ids, int64_t m, con
     if (!live(ix)) return PK_ERR_BAD_HANDLE;
     if (m < 0 || (m > 0 && !x)) return PK_ERR_INVALID_ARG;
     if (m == 0) return PK_OK;
-    // host-side capacity check: every vector may open at most one page
-    if ((uint64_t)pages_used_ub(ix) + (uint64_t)m > ix->pages_total ||
-        (uint64_t)ix->pages_known + (uint64_t)(ix->n_inserted - ix->inserted_at_known) + (uint64_t)m > ix->pages_total) {
+    // Host-side capacity check, before anything is enqueued.  Fast path: a bound from the last
+    // page counter read back.  If that does not clear the batch, synchronise, read the exact
+    // page counter and list lengths, and test the exact worst case: m vectors open the most
+    // pages when they first top up the fullest tail pages (cost: free slots + 1 each) and then
+    // fill whole pages.
+    if ((uint64_t)ix->pages_known + pages_for(ix, (uint64_t)(ix->n_inserted - ix->inserted_at_known + m)) >
+        ix->pages_total) {
+        PK_HIP(hipStreamSynchronize(s));
         PK_TRY(settle_pages(ix));
-        if ((uint64_t)ix->pages_known + (uint64_t)(ix->n_inserted - ix->inserted_at_known) + (uint64_t)m >
-            ix->pages_total)
-            return PK_ERR_NOMEM;
+        std::vector<uint32_t> len((size_t)ix->cfg.nlist);
+        uint32_t used = 0;
+        PK_HIP(hipMemcpy(len.data(), ix->host.list_len, len.size() * 4, hipMemcpyDeviceToHost));
+        PK_HIP(hipMemcpy(&used, ix->host.ctr, 4, hipMemcpyDeviceToHost));
+        ix->pages_known = used;
+        ix->inserted_at_known = ix->n_inserted;
+        std::vector<uint32_t> first(len.size());
+        const uint32_t P = (uint32_t)ix->P;
+        for (size_t l = 0; l < len.size(); ++l) first[l] = (P - len[l] % P) % P + 1;
+        std::sort(first.begin(), first.end());
+        uint64_t budget = (uint64_t)m, pages = 0;
+        for (uint32_t c : first) {
+            if (budget < c) break;
+            budget -= c;
+            ++pages;
+        }
+        pages += budget / P;
+        if ((uint64_t)used + pages > ix->pages_total) return PK_ERR_NOMEM;
     }
     pk_index *hs[1] = {ix};
     for (int64_t i0 = 0; i0 < m; i0 += 1024) {

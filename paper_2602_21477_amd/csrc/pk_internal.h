@@ -82,6 +82,19 @@ __device__ __forceinline__ float value_of(uint32_t ob, int metric)
 
 constexpr uint32_t kWorstBits = 0xff800000u;
 
+// Bucket of a value on a per-query scale: the distance of the value from the best sampled
+// value `lo`, in units of 1/inv, cut into kHistBins-1 equal buckets; everything past the
+// sampled range lands in the last bucket.  Monotone in the value (each float operation
+// involved is), better values get lower buckets, so "bucket <= b" is a valid cut wherever
+// k candidates are known to have bucket <= b.
+__device__ __forceinline__ uint32_t bucket_of(float v, float lo, float inv, int metric)
+{
+    float off = metric == PK_METRIC_L2 ? v - lo : lo - v;
+    off = fmaxf(off, 0.f);
+    const float t = fminf(off * inv, (float)(kHistBins - 1));
+    return (uint32_t)t;
+}
+
 // One unit of scan work: one page of rows against one group of query slots.
 struct Tile {
     const char *x;    // first row of the page
@@ -123,11 +136,11 @@ struct ScanArgs {
     float *out;                  // dense mode: values, one per (slot, row)
     // gated mode (tau != NULL): a value is emitted only if its key is <= tau[query]; it is
     // appended as (key << 32 | position) to the query's region of cbuf
-    const uint32_t *tau;         // [nq] initial threshold keys (from the sample)
-    const uint32_t *tlo;         // [nq] best sample key: lower end of the histogram range
-    const uint32_t *thi;         // [nq] upper end of the histogram range (k-th best sample key, or the worst one)
-    uint32_t *hist;              // [nq][kHistBins] emitted candidates per key bucket (zero before the launch)
-    uint32_t *tcur;              // [nq] running threshold shared by all workgroups (starts at tau)
+    const uint32_t *tau;         // [nq] threshold keys from the sample (never change)
+    const float *tlo;            // [nq] best sample value: origin of the bucket scale
+    const float *tinv;           // [nq] bucket scale (see bucket_of)
+    uint32_t *hist;              // [nq][kHistBins] emitted candidates per bucket (zero before the launch)
+    uint32_t *tcur;              // [nq] running bucket limit shared by all workgroups (starts at kHistBins-1)
     const uint32_t *qoff;        // [nq] first element of each query's region
     uint32_t *ccnt;              // [nq] emitted so far (zero before the launch)
     unsigned long long *cbuf;
@@ -205,10 +218,10 @@ struct SampleArgs {
     float *vals;               // [nq][span], pre-filled with the padding value by the kernel
     uint32_t *scalars;         // [0] ntiles [1] tile counter [2] grab size
     uint32_t *tau;             // [nq] out: k-th best sample key, or 0xffffffff
-    uint32_t *tlo;             // [nq] out: best sample key
-    uint32_t *thi;             // [nq] out: k-th best sample key, or the worst one if there are fewer than k
+    float *tlo;                // [nq] out: best sample value
+    float *tinv;               // [nq] out: bucket scale = (kHistBins-1) / |k-th best (or worst) sample value - best|
     uint32_t *hist;            // [nq][kHistBins] zeroed here
-    uint32_t *tcur;            // [nq] out: running threshold, starts at tau
+    uint32_t *tcur;            // [nq] out: running bucket limit, starts at kHistBins-1
 };
 hipError_t launch_sample_tiles(const SampleArgs &a, const MultiArgs &m, hipStream_t s);
 hipError_t launch_tau(const SampleArgs &a, hipStream_t s);

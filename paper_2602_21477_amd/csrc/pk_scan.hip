@@ -24,6 +24,9 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// per-slot LDS arrays of the scan kernel: out, qn, thr, q, base, lo, inv, bmax
+constexpr int kScanSlotWords = 8;
+
 template <int STORAGE>
 __device__ __forceinline__ void mfma_step(f32x4 &acc, const u32x4 &qa, const u32x4 &xb)
 {
@@ -55,9 +58,10 @@ __global__ __launch_bounds__(WAVES * 64) void scan_kernel(ScanArgs a)
     uint32_t *s_thr = reinterpret_cast<uint32_t *>(s_qn + MQ); // gated: threshold key per slot
     uint32_t *s_q = s_thr + MQ;                                 // gated: query of the slot
     uint32_t *s_base = s_q + MQ;                                // gated: start of the query's region
-    uint32_t *s_lo = s_base + MQ;                               // gated: histogram origin (key)
-    uint32_t *s_sh = s_lo + MQ;                                 // gated: histogram bucket shift
-    uint32_t *s_misc = s_sh + MQ;
+    float *s_lo = reinterpret_cast<float *>(s_base + MQ);       // gated: origin of the bucket scale
+    float *s_inv = s_lo + MQ;                                   // gated: bucket scale
+    uint32_t *s_bmax = reinterpret_cast<uint32_t *>(s_inv + MQ);// gated: buckets above this are cut
+    uint32_t *s_misc = s_bmax + MQ; // kScanSlotWords per-slot arrays precede this: keep scan_lds_bytes in step
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int ln = lane & 15, lg = lane >> 4;
@@ -106,19 +110,11 @@ __global__ __launch_bounds__(WAVES * 64) void scan_kernel(ScanArgs a)
                         s_q[tid] = q;
                         s_base[tid] = base;
                         s_out[tid] -= base; // position inside the query's candidate range
-                        // Threshold of the slot.  It starts at the k-th best key of the query's
-                        // sample and tightens as candidates are emitted: the histogram counts
-                        // the emitted keys per bucket of [lo, tau0], and the upper edge of the
-                        // first bucket at which the running count reaches k bounds the k-th best.
-                        uint32_t thr = 0u, lo = 0u, sh = 0u;
-                        if (on) {
-                            thr = a.tau[q];
-                            lo = a.tlo[q];
-                            const uint32_t hi = a.thi[q];
-                            const uint32_t range = hi > lo ? hi - lo : 0u;
-                            const int bits = 32 - __clz((int)range | 1);
-                            sh = bits > 6 ? (uint32_t)(bits - 6) : 0u; // (key - lo) >> sh < kHistBins for keys <= hi
-                        }
+                        // Emission gate of the slot: a fixed key threshold from the query's
+                        // sample, and a bucket limit that tightens while the scan runs: the
+                        // histogram counts the emitted candidates per bucket, and the first
+                        // bucket at which the running count reaches k bounds the k-th best.
+                        uint32_t bmax = (uint32_t)kHistBins - 1u;
                         if (on && a.use_hist) {
                             const uint32_t *hp = a.hist + (size_t)q * kHistBins;
                             uint32_t h[kHistBins];
@@ -128,35 +124,32 @@ __global__ __launch_bounds__(WAVES * 64) void scan_kernel(ScanArgs a)
                             uint32_t cum = 0;
                             bool found = false;
 #pragma unroll
-                            for (int j = 0; j < kHistBins - 1; ++j) { // the last bucket also takes keys past the range
+                            for (int j = 0; j < kHistBins; ++j) {
                                 cum += h[j];
                                 if (!found && cum >= (uint32_t)a.k) {
                                     found = true;
-                                    const unsigned long long edge =
-                                        (unsigned long long)lo + ((unsigned long long)(j + 1) << sh) - 1ull;
-                                    if (edge < thr) thr = (uint32_t)edge;
+                                    bmax = (uint32_t)j;
                                 }
                             }
+                            // share the limit with every workgroup scoring this query
+                            const uint32_t seen = atomicMin(a.tcur + q, bmax);
+                            bmax = seen < bmax ? seen : bmax;
                         }
-                        if (on && a.use_hist) {
-                            // share the tightened threshold with every workgroup scoring this query
-                            const uint32_t seen = atomicMin(a.tcur + q, thr);
-                            thr = seen < thr ? seen : thr;
-                        }
-                        s_thr[tid] = thr;
-                        s_lo[tid] = lo;
-                        s_sh[tid] = sh;
+                        s_thr[tid] = on ? a.tau[q] : 0u;
+                        s_lo[tid] = on ? a.tlo[q] : 0.f;
+                        s_inv[tid] = on ? a.tinv[q] : 0.f;
+                        s_bmax[tid] = bmax;
                     }
                 }
                 __syncthreads();
                 cur_qbeg = qbeg;
                 cur_qcnt = qcnt;
             }
-            else if (GATED && a.use_hist) {
+            else if (GATED && a.use_hist == 1) {
                 // same query group as the previous tile: pick up thresholds others have tightened
                 if ((uint32_t)tid < qcnt) {
                     const uint32_t seen = __hip_atomic_load(a.tcur + s_q[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    if (seen < s_thr[tid]) s_thr[tid] = seen;
+                    if (seen < s_bmax[tid]) s_bmax[tid] = seen;
                 }
                 __syncthreads();
             }
@@ -227,9 +220,14 @@ __global__ __launch_bounds__(WAVES * 64) void scan_kernel(ScanArgs a)
                                 // query's threshold are rare: one ballot, and only then one
                                 // aggregated atomic per group to reserve room in the query's region.
                                 const uint32_t bits = order_bits(v, a.metric);
-                                const bool pass = live && (uint32_t)m < qcnt && bits <= s_thr[m];
+                                bool pass = live && (uint32_t)m < qcnt && bits <= s_thr[m];
+                                if (__ballot(pass) == 0ull) continue; // the usual case: nothing survives
+                                uint32_t b = 0;
+                                if (pass) {
+                                    b = bucket_of(v, s_lo[m], s_inv[m], a.metric);
+                                    pass = b <= s_bmax[m];
+                                }
                                 const unsigned long long mask = __ballot(pass);
-                                if (mask == 0ull) continue;
                                 const uint32_t gmask = (uint32_t)(mask >> (lg * 16)) & 0xffffu;
                                 if (gmask) {
                                     const int leader = __ffs(gmask) - 1;
@@ -242,11 +240,8 @@ __global__ __launch_bounds__(WAVES * 64) void scan_kernel(ScanArgs a)
                                             ((unsigned long long)bits << 32) | (s_out[m] + row0 + (uint32_t)row);
                                     }
                                     if (a.use_hist) {
-                                        // count the emitted keys per bucket; one atomic for the group
-                                        // when its keys share a bucket (the usual case)
-                                        const uint32_t lo = s_lo[m];
-                                        uint32_t b = bits > lo ? (bits - lo) >> s_sh[m] : 0u;
-                                        b = b < (uint32_t)kHistBins ? b : (uint32_t)kHistBins - 1u;
+                                        // count the emitted candidates per bucket; one atomic for the
+                                        // group when its candidates share a bucket (the usual case)
                                         const uint32_t b0 = __shfl(b, lg * 16 + leader);
                                         const uint32_t odd =
                                             (uint32_t)(__ballot(pass && b != b0) >> (lg * 16)) & 0xffffu;
@@ -274,7 +269,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan_kernel(ScanArgs a)
 
 int scan_lds_bytes(int row_bytes, int mq)
 {
-    return mq * (row_bytes + kQPadBytes) + mq * 28 + 16;
+    return mq * (row_bytes + kQPadBytes) + mq * kScanSlotWords * 4 + 16; // query tile + per-slot arrays + scratch
 }
 
 // Largest query group (16, 32 or 64 slots) whose LDS tile fits.  fp32 storage is held to

@@ -309,11 +309,18 @@ __global__ __launch_bounds__(kSelThreads) void tau_kernel(SampleArgs a)
     }
     sel.flush();
     if (threadIdx.x == 0) {
-        a.tau[q] = s_cnt >= (uint32_t)a.k ? (uint32_t)(keys[a.k - 1] >> 32) : 0xffffffffu;
-        a.tcur[q] = a.tau[q];
-        a.tlo[q] = s_cnt > 0 ? (uint32_t)(keys[0] >> 32) : 0u;
-        a.thi[q] = s_cnt >= (uint32_t)a.k ? (uint32_t)(keys[a.k - 1] >> 32)
-                                          : (s_cnt > 0 ? (uint32_t)(keys[s_cnt - 1] >> 32) : 0u);
+        const bool full = s_cnt >= (uint32_t)a.k;
+        a.tau[q] = full ? (uint32_t)(keys[a.k - 1] >> 32) : 0xffffffffu;
+        a.tcur[q] = (uint32_t)kHistBins - 1u;
+        float lo = 0.f, inv = 0.f;
+        if (s_cnt > 0) {
+            lo = value_of((uint32_t)(keys[0] >> 32), a.metric);
+            const float far = value_of((uint32_t)(keys[(full ? (uint32_t)a.k : s_cnt) - 1] >> 32), a.metric);
+            const float range = fabsf(far - lo);
+            if (range > 0.f && range < INFINITY) inv = ((float)kHistBins - 1.001f) / range;
+        }
+        a.tlo[q] = lo;
+        a.tinv[q] = inv;
     }
     if (threadIdx.x < kHistBins) a.hist[(size_t)q * kHistBins + threadIdx.x] = 0u;
 }

@@ -272,7 +272,7 @@ def test_arena_exhaustion_is_reported_and_recoverable(gpu_device):
     ix = B.Index(dev(cent), dev(x), page_vecs=32, arena_bytes=B.pk_arena_bytes(c, cfg.n, 0))
     try:
         free = ix.stats().pages_total - ix.stats().pages_used
-        new = dev(W.inserts(cfg, 0, int(free) + 5))
+        new = dev(W.inserts(cfg, 0, (int(free) + 2) * 32 + 64 * 32))  # cannot fit whatever the assignment
         with pytest.raises(B.PancakeError) as e:
             ix.insert(new)
         assert e.value.status == B.PK_ERR_NOMEM and ix.stats().n_total == cfg.n
