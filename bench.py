@@ -8,7 +8,7 @@ A step is one pass of the whole hot path over one batch of the workload: coarse 
 merge for the query batch, plus the insert batch the config interleaves (assign +
 append).  All inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 
-Workloads (benchmark configs): c1 tiny, c2 single agent, c3 multi agent, c4 large
+Workloads (the five benchmark configs): c1 tiny, c2 single agent, c3 multi agent, c4 large
 static fp16 index under both metrics (c4l2 / c4ip: one of them), c5 skewed dynamic.  The
 default, c4, is the 10 M-vector config the HBM target is quoted on; its headline value is
 the slower of its two metric variants.
@@ -29,6 +29,18 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X datasheet HBM3E bandwidth
 METRIC_NAME = "search queries/sec at recall@10>=0.9 (1 GPU); list-scan HBM GB/s vs peak"
+
+
+def profiled_traffic(workload, metric):
+    """HBM bytes per scan launch from the committed rocprofv3 counter summary (FETCH_SIZE + WRITE_SIZE,
+    calibrated against a plain copy), if there is one for this workload variant."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"scan_kernel_{workload}_{metric}.md")
+    try:
+        m = re.search(r"^traffic_bytes_per_launch:\s*(\d+)", open(path).read(), re.M)
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
 
 
 def log(msg):
@@ -286,6 +298,8 @@ def run(args):
         "roofline": res["roofline"], "stages_ms": res["stages_ms"], "per_search": res["per_search"],
         "recall_at_10": res["recall_at_10"],
     }
+    for m, r in results.items():
+        r[0]["roofline"]["traffic"] = profiled_traffic(base.name.split("_")[0], m)
     if len(results) > 1:
         out["variants"] = {m: {k: v for k, v in r[0].items()} for m, r in results.items()}
     if not args.no_cpu_baseline:
@@ -307,8 +321,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); run with --gpus 1. "
-              "DESIGN.md describes how the path would shard.", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); run with --gpus 1.", file=sys.stderr)
         raise SystemExit(2)
     run(args)
 

@@ -5,7 +5,7 @@ WRITE_SIZE counters:
 
 Each copy reads and writes exactly SIZE bytes; whatever the counters report per copy
 dispatch, divided into SIZE, is the factor the same counters are scaled by for the scan
-kernel (DESIGN.md, "Measurement").
+kernel.
 """
 import torch
 

@@ -1,6 +1,6 @@
 """Comparator for search results: HIP path against the CPU oracle.
 
-Rule (north star + the readings listed in the design doc):
+Rule:
   * values: |g - r| <= tol * max(|r|, scale) position by position, where scale is
     ||q||*||x|| for inner product and ||q||^2 + ||x||^2 for squared L2 (a purely
     relative test is meaningless at the self-match value 0);
