@@ -133,16 +133,17 @@ uint64_t wq_ub(const pk_index *ix, int nprobe)
 struct Plan {
     int64_t nq;
     int nprobe, k, nh;
-    int mq_c, mq_f, grid_c, grid_f, grid_s, cchunks, nchunks, K, nlist_max, sp;
+    int mq_c, mq_f, mq_h, grid_c, grid_f, grid_h, grid_s, cchunks, nchunks, K, nlist_max, sp;
+    uint32_t hot_from;
     uint32_t stride, cand_cap, tile_cap, ctiles, span;
     bool need_coarse, need_fine, f16;
     // buffers
     char *qs32, *qs;
     float *qn32, *qn, *S, *svals, *tlo, *tinv;
-    uint32_t *cand_off, *cand_cnt, *cslot_q, *cslot_o, *lcnt, *lstart, *lfill, *ltile, *pair_off, *qtot, *qoff, *slot_q,
+    uint32_t *cand_off, *cand_cnt, *cslot_q, *cslot_o, *lcnt, *lstart, *lfill, *ltile, *lhtile, *pair_off, *qtot, *qoff, *slot_q,
         *slot_o, *scalars, *tau, *tcur, *hist, *ccnt, *sslot_q, *sslot_o;
     uint16_t *qagent;
-    Tile *ctile_buf, *tiles, *stiles;
+    Tile *ctile_buf, *tiles, *tiles_hot, *stiles;
     unsigned long long *cpartial, *partial, *cbuf;
     int32_t *probes;
     size_t bytes;
@@ -179,12 +180,14 @@ void carve(Plan &p, char *base, const pk_index *own)
         p.lstart = c.take<uint32_t>(nl);
         p.lfill = c.take<uint32_t>(nl);
         p.ltile = c.take<uint32_t>(nl);
+        p.lhtile = c.take<uint32_t>(nl);
         p.pair_off = c.take<uint32_t>(nq * (p.nprobe + 1));
         p.qtot = c.take<uint32_t>(nq);
         p.qoff = c.take<uint32_t>(nq);
         p.slot_q = c.take<uint32_t>(nq * p.nprobe);
         p.slot_o = c.take<uint32_t>(nq * p.nprobe);
         p.tiles = c.take<Tile>((size_t)p.tile_cap + 1);
+        p.tiles_hot = c.take<Tile>((size_t)p.tile_cap + 1);
         p.tau = c.take<uint32_t>(nq);
         p.tlo = c.take<float>(nq);
         p.tinv = c.take<float>(nq);
@@ -232,18 +235,35 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
     p.mq_c = scan_max_mq(own->rb32, PK_F32, own->lds_limit);
     p.mq_f = scan_max_mq(own->row_bytes, own->cfg.storage, own->lds_limit);
     {
-        // query slots per scan tile: the smallest group that holds the expected number of
-        // queries per probed list (a list with more is scanned once per group); small
-        // groups keep the LDS tile small and the occupancy high
+        // Query slots per scan tile: the smallest group that holds the expected number of
+        // queries per probed list; small groups keep the LDS tile small and the occupancy
+        // high, and a list probed by more queries is scored once per group (its pages are
+        // re-read from L2 / Infinity Cache, which measured faster than larger groups).
+        // If even that tile would leave one workgroup per CU (wide fp32 rows), the
+        // sliced-query kernel, whose LDS use does not depend on the row length, takes every
+        // list.  PK_TUNE_KS can force either kernel, or route only lists with more queries
+        // than one group to the sliced kernel (3).
         double avg = 0;
         for (int a = 0; a < nh; ++a)
             avg = std::max(avg, (double)(qlo[a + 1] - qlo[a]) * nprobe / hs[a]->cfg.nlist);
         const int want = avg <= 6 ? 16 : (avg <= 20 ? 32 : 64);
         p.mq_f = std::min(p.mq_f, tune("PK_TUNE_MQ", want));
+        p.mq_h = own->cfg.storage == PK_F16 ? 128 : 32;
+        p.mq_h = std::min(p.mq_h, tune("PK_TUNE_MQH", 128));
+        const int ks = tune("PK_TUNE_KS", 1); // 0: never, 1: automatic, 2: every list, 3: hot lists
+        const bool wide = p.mq_f < 16 || scan_lds_bytes(own->row_bytes, p.mq_f) > 64 * 1024;
+        if (ks == 2 || (ks == 1 && wide)) p.hot_from = 0;
+        else if (ks == 3) p.hot_from = (uint32_t)p.mq_f;
+        else p.hot_from = 0xffffffffu;
+        if (p.hot_from == 0) {
+            p.mq_h = std::min(p.mq_h, std::max(want, 16));
+            if (p.mq_f < 16) p.mq_f = 16; // unused, but keeps the tile arithmetic defined
+        }
     }
     if (p.mq_c < 16 || p.mq_f < 16) return PK_ERR_UNSUPPORTED;
     p.grid_c = grid_for(own, own->rb32, p.mq_c, 1);
     p.grid_f = grid_for(own, own->row_bytes, p.mq_f, 4);
+    p.grid_h = own->num_cu * std::max(1, std::min((160 * 1024) / scan_ks_lds_bytes(p.mq_h), tune("PK_TUNE_WGS", 4)));
     p.grid_s = grid_for(own, own->row_bytes, 16, 4);
     p.K = k + 1;
     p.sp = (k + own->P - 1) / own->P; // sample pages: at least k rows of the first probed list
@@ -261,7 +281,7 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
         wmax = std::max(wmax, w);
         cand += nqa * w;
         const uint64_t pp = w / ix->P + nprobe;
-        tiles += std::min<uint64_t>(pages_used_ub(ix), nqa * pp) + nqa * pp / p.mq_f + 1;
+        tiles += std::min<uint64_t>(pages_used_ub(ix), nqa * pp) + nqa * pp / std::min(p.mq_f, p.mq_h) + 1;
     }
     if (cand > 0xfffffff0ull || tiles > 0xfffffff0ull || ctiles > 0xfffffff0ull) return PK_ERR_UNSUPPORTED;
     p.nlist_max = nlist_hi;
@@ -410,12 +430,15 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
     w.n_handles = p.nh;
     w.nlist_max = p.nlist_max;
     w.mq = p.mq_f;
+    w.mq_hot = p.mq_h;
+    w.hot_from = p.hot_from;
     w.scan_grid = p.grid_f;
     w.grab_div = tune("PK_TUNE_GRABDIV", 8);
     w.lcnt = p.lcnt;
     w.lstart = p.lstart;
     w.lfill = p.lfill;
     w.ltile = p.ltile;
+    w.lhtile = p.lhtile;
     w.pair_off = p.pair_off;
     w.qtot = p.qtot;
     w.qoff = p.qoff;
@@ -423,9 +446,11 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
     w.slot_query = p.slot_q;
     w.slot_out = p.slot_o;
     w.tiles = p.tiles;
+    w.tiles_hot = p.tiles_hot;
     w.tile_cap = p.tile_cap;
     w.cand_cap = p.cand_cap;
     w.scalars = p.scalars + 4;
+    w.scalars_hot = p.scalars + 12;
     PK_HIP(launch_worklist(w, m, s));
     if (timed) PK_TRY(mark(own, s));
     ScanArgs sa{};
@@ -452,7 +477,15 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
     sa.metric = own->cfg.metric;
     sa.storage = own->cfg.storage;
     sa.mq = p.mq_f;
-    PK_HIP(launch_scan(sa, 4, p.grid_f, s));
+    if (p.hot_from > 0) PK_HIP(launch_scan(sa, 4, p.grid_f, s));
+    if (p.hot_from != 0xffffffffu) {
+        sa.tiles = p.tiles_hot;
+        sa.ntiles = p.scalars + 12;
+        sa.tile_ctr = p.scalars + 13;
+        sa.batch = p.scalars + 14;
+        sa.mq = p.mq_h;
+        PK_HIP(launch_scan_ks(sa, p.grid_h, s));
+    }
     if (timed) PK_TRY(mark(own, s));
     SelectArgs se{};
     se.vals = nullptr;

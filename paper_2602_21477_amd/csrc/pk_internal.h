@@ -149,7 +149,9 @@ struct ScanArgs {
     int row_bytes, metric, storage, mq;
 };
 hipError_t launch_scan(const ScanArgs &a, int waves_per_wg, int grid, hipStream_t s);
+hipError_t launch_scan_ks(const ScanArgs &a, int grid, hipStream_t s);
 int scan_lds_bytes(int row_bytes, int mq);
+int scan_ks_lds_bytes(int mq);
 int scan_max_mq(int row_bytes, int storage, int lds_limit);
 
 struct SelectArgs {
@@ -192,15 +194,19 @@ struct WorklistArgs {
     const int32_t *probes;     // [nq][nprobe]; entries outside [0, nlist) are ignored
     const uint16_t *qagent;    // [nq]
     int64_t nq;
-    int nprobe, n_handles, nlist_max, mq, scan_grid, grab_div;
-    uint32_t *lcnt, *lstart, *lfill, *ltile; // [n_handles * nlist_max]
+    int nprobe, n_handles, nlist_max, scan_grid, grab_div;
+    int mq;                    // slots per group of a regular tile
+    int mq_hot;                // slots per group of a hot tile (sliced-query kernel)
+    uint32_t hot_from;         // lists probed by more than this many queries of the batch are hot
+    uint32_t *lcnt, *lstart, *lfill, *ltile, *lhtile; // [n_handles * nlist_max]
     uint32_t *pair_off;        // [nq][nprobe+1]
     uint32_t *qtot, *qoff;     // [nq]
     uint32_t *ccnt;            // [nq] zeroed here (emission counters of the gated scan)
     uint32_t *slot_query, *slot_out; // [nq * nprobe]
-    Tile *tiles;
+    Tile *tiles, *tiles_hot;
     uint32_t tile_cap, cand_cap;
     uint32_t *scalars;         // [0] ntiles [1] tile counter [2] grab size [3] total candidates
+    uint32_t *scalars_hot;     // [0] hot tiles [1] tile counter [2] grab size
 };
 hipError_t launch_worklist(const WorklistArgs &a, const MultiArgs &m, hipStream_t s);
 

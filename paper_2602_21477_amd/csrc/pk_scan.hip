@@ -1,21 +1,28 @@
-// List scan (fine search) and centroid scoring (coarse search) for gfx950.
+// List scan (fine search) and small-batch centroid scoring (coarse search) for gfx950.
 //
 // Section 2.2 of the paper: the coarse step scores a query against every centroid, the
 // fine step against every vector of the probed clusters.  Both are "rows streamed from
-// HBM once, scored against a small group of queries", so one kernel serves both: a tile
-// is one page of rows (list page or a slice of the centroid table) plus a group of up to
-// MQ query slots.  Inserted vectors (Section 4.4's buffer) live in ordinary pages of the
+// HBM once, scored against a small group of queries", so one kernel family serves both: a
+// tile is one page of rows (list page or a slice of the centroid table) plus a group of
+// query slots.  Inserted vectors (Section 4.4's buffer) live in ordinary pages of the
 // list and are scored by the same tiles.
 //
 // Mapping to CDNA4.  The rows are the streaming operand and go HBM -> registers directly
-// in MFMA operand layout; the query group is staged once in LDS and re-read per pass.
-// With A = queries (M = 16 slots) and B = rows (N = 16 rows) the 16x16 accumulator puts
-// rows along lanes, so each store instruction writes 64 contiguous bytes per 16 lanes.
-// The contraction index may be permuted freely as long as A and B use the same
-// permutation, which lets every lane fetch 16 contiguous bytes per load (4 lanes cover a
-// 64-byte segment of one row, 16 rows per instruction) and feed them straight into
-// v_mfma_f32_16x16x32_f16 (fp16 storage) or four v_mfma_f32_16x16x4_f32 (fp32 storage),
-// always with fp32 accumulation.
+// in MFMA operand layout; the queries come from LDS.  With A = queries (M = 16 slots) and
+// B = rows (N = 16 rows) the 16x16 accumulator puts rows along lanes, so each store
+// instruction writes 64 contiguous bytes per 16 lanes.  The contraction index may be
+// permuted freely as long as A and B use the same permutation, which lets every lane fetch
+// 16 contiguous bytes per load (4 lanes cover a 64-byte segment of one row, 16 rows per
+// instruction) and feed them straight into v_mfma_f32_16x16x32_f16 (fp16 storage) or four
+// v_mfma_f32_16x16x4_f32 (fp32 storage), always with fp32 accumulation.
+//
+// Two kernels differ in how the queries reach LDS:
+//   scan_kernel     the whole query group (up to 64 slots x full rows) sits in LDS and is
+//                   reused over a batch of tiles: least traffic when groups are small;
+//   scan_ks_kernel  the queries are staged 256 bytes of every row at a time (double
+//                   buffered), so LDS use is independent of the row length and up to 128
+//                   slots fit: for lists probed by many queries of the batch and for rows
+//                   too wide for the first kernel to keep several workgroups per CU.
 #include "pk_internal.h"
 
 namespace pk {
@@ -24,8 +31,9 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// per-slot LDS arrays of the scan kernel: out, qn, thr, q, base, lo, inv, bmax
+// per-slot LDS arrays of the scan kernels: out, qn, thr, q, base, lo, inv, bmax
 constexpr int kScanSlotWords = 8;
+constexpr int kKsStride = kIterBytes + kQPadBytes; // LDS bytes per slot and staged slice
 
 template <int STORAGE>
 __device__ __forceinline__ void mfma_step(f32x4 &acc, const u32x4 &qa, const u32x4 &xb)
@@ -42,9 +50,168 @@ __device__ __forceinline__ void mfma_step(f32x4 &acc, const u32x4 &qa, const u32
     }
 }
 
+// What a workgroup knows about the query slots of the group it is scoring (all in LDS).
+struct Slots {
+    uint32_t *out;  // dense: first output element of the (slot, list) pair; gated: its position in the query's range
+    float *qn;      // squared norm of the query
+    uint32_t *thr;  // gated: key threshold from the query's sample
+    uint32_t *q;    // gated: query of the slot
+    uint32_t *base; // gated: start of the query's emission region
+    float *lo;      // gated: origin of the bucket scale
+    float *inv;     // gated: bucket scale
+    uint32_t *bmax; // gated: buckets above this are cut
+    __device__ __forceinline__ void carve(char *p, int mq)
+    {
+        out = reinterpret_cast<uint32_t *>(p);
+        qn = reinterpret_cast<float *>(out + mq);
+        thr = reinterpret_cast<uint32_t *>(qn + mq);
+        q = thr + mq;
+        base = q + mq;
+        lo = reinterpret_cast<float *>(base + mq);
+        inv = lo + mq;
+        bmax = reinterpret_cast<uint32_t *>(inv + mq);
+    }
+};
+
+// Thread `tid` (< MQ) fills slot `tid` of the group [qbeg, qbeg + qcnt).
+template <bool GATED>
+__device__ __forceinline__ void load_slot(const ScanArgs &a, const Slots &s, int tid, uint32_t qbeg, uint32_t qcnt)
+{
+    const bool on = (uint32_t)tid < qcnt;
+    const uint32_t q = on ? a.slot_query[qbeg + tid] : 0u;
+    s.out[tid] = on ? a.slot_out[qbeg + tid] : 0u;
+    s.qn[tid] = on ? a.qnorm[q] : 0.f;
+    if constexpr (GATED) {
+        const uint32_t base = on ? a.qoff[q] : 0u;
+        s.q[tid] = q;
+        s.base[tid] = base;
+        s.out[tid] -= base; // position inside the query's candidate range
+        // Emission gate of the slot: a fixed key threshold from the query's sample, and a
+        // bucket limit that tightens while the scan runs: the histogram counts the emitted
+        // candidates per bucket, and the first bucket at which the running count reaches k
+        // bounds the k-th best.
+        uint32_t bmax = (uint32_t)kHistBins - 1u;
+        if (on && a.use_hist) {
+            const uint32_t *hp = a.hist + (size_t)q * kHistBins;
+            uint32_t h[kHistBins];
+#pragma unroll
+            for (int j = 0; j < kHistBins; ++j) // device-scope loads: counts other CUs just added
+                h[j] = __hip_atomic_load(hp + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            uint32_t cum = 0;
+            bool found = false;
+#pragma unroll
+            for (int j = 0; j < kHistBins; ++j) {
+                cum += h[j];
+                if (!found && cum >= (uint32_t)a.k) {
+                    found = true;
+                    bmax = (uint32_t)j;
+                }
+            }
+            // share the limit with every workgroup scoring this query
+            const uint32_t seen = atomicMin(a.tcur + q, bmax);
+            bmax = seen < bmax ? seen : bmax;
+        }
+        s.thr[tid] = on ? a.tau[q] : 0u;
+        s.lo[tid] = on ? a.tlo[q] : 0.f;
+        s.inv[tid] = on ? a.tinv[q] : 0.f;
+        s.bmax[tid] = bmax;
+    }
+}
+
+// same query group as the previous tile: pick up bucket limits other workgroups have tightened
+__device__ __forceinline__ void refresh_slot(const ScanArgs &a, const Slots &s, int tid, uint32_t qcnt)
+{
+    if ((uint32_t)tid < qcnt) {
+        const uint32_t seen = __hip_atomic_load(a.tcur + s.q[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (seen < s.bmax[tid]) s.bmax[tid] = seen;
+    }
+}
+
+// Epilogue of one 32-row block: the lane holds rows (rb*32 + nt*16 + ln) for slots
+// mt*16 + lg*4 + i.  Dense mode writes every value; gated mode emits the survivors.
+template <int MT, bool GATED>
+__device__ __forceinline__ void finish_block(const ScanArgs &a, const Slots &s, f32x4 (&acc)[MT][2], int rb, int ln, int lg,
+                                             int nrows, uint32_t qcnt, uint32_t row0, const float *txn)
+{
+    constexpr int MQ = MT * 16;
+    const float worst = a.metric == PK_METRIC_IP ? -INFINITY : INFINITY;
+    const int nrows_pad = (nrows + 15) & ~15;
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+        const int row = rb * kRowBlock + nt * 16 + ln;
+        const bool live = row < nrows;
+        float xn = 0.f;
+        if (a.metric == PK_METRIC_L2 && live) xn = txn[row];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            if ((uint32_t)(mt * 16) >= qcnt) break; // wave-uniform
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int m = mt * 16 + lg * 4 + i;
+                float v = acc[mt][nt][i];
+                if (a.metric == PK_METRIC_L2) v = fmaxf(xn - 2.f * v + s.qn[m & (MQ - 1)], 0.f);
+                if constexpr (!GATED) {
+                    if ((uint32_t)m < qcnt && row < nrows_pad) a.out[(size_t)s.out[m] + row0 + row] = live ? v : worst;
+                } else {
+                    // The 16 lanes of a group share slot m.  Survivors are rare: one ballot, and
+                    // only then one aggregated atomic per group to reserve room in the query's region.
+                    const uint32_t bits = order_bits(v, a.metric);
+                    bool pass = live && (uint32_t)m < qcnt && bits <= s.thr[m];
+                    if (__ballot(pass) == 0ull) continue; // the usual case: nothing survives
+                    uint32_t b = 0;
+                    if (pass) {
+                        b = bucket_of(v, s.lo[m], s.inv[m], a.metric);
+                        pass = b <= s.bmax[m];
+                    }
+                    const unsigned long long mask = __ballot(pass);
+                    const uint32_t gmask = (uint32_t)(mask >> (lg * 16)) & 0xffffu;
+                    if (gmask) {
+                        const int leader = __ffs(gmask) - 1;
+                        uint32_t base = 0;
+                        if (ln == leader) base = atomicAdd(&a.ccnt[s.q[m]], (uint32_t)__popc(gmask));
+                        base = __shfl(base, lg * 16 + leader);
+                        if (pass) {
+                            const uint32_t rank = __popc(gmask & ((1u << ln) - 1u));
+                            a.cbuf[(size_t)s.base[m] + base + rank] =
+                                ((unsigned long long)bits << 32) | (s.out[m] + row0 + (uint32_t)row);
+                        }
+                        if (a.use_hist) {
+                            // count the emitted candidates per bucket; one atomic for the group
+                            // when its candidates share a bucket (the usual case)
+                            const uint32_t b0 = __shfl(b, lg * 16 + leader);
+                            const uint32_t odd = (uint32_t)(__ballot(pass && b != b0) >> (lg * 16)) & 0xffffu;
+                            uint32_t *hq = a.hist + (size_t)s.q[m] * kHistBins;
+                            if (odd == 0u) {
+                                if (ln == leader) atomicAdd(hq + b0, (uint32_t)__popc(gmask));
+                            } else if (pass) {
+                                atomicAdd(hq + b, 1u);
+                            }
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+// Schedule shared by both kernels: the first tile of every workgroup is fixed (tile b for
+// workgroup b), later batches of `grab` tiles are handed out by a counter, so uneven tiles
+// still balance while the launch does not start with a burst of atomics.  The first batch is
+// a single tile so that the emission gates get their first refresh early.  Every workgroup
+// stops the first time it is handed a batch past the end.
+__device__ __forceinline__ uint32_t next_batch(const ScanArgs &a, uint32_t *s_misc, uint32_t grab)
+{
+    __syncthreads();
+    if (threadIdx.x == 0) s_misc[0] = gridDim.x + atomicAdd(a.tile_ctr, 1u) * grab;
+    __syncthreads();
+    return s_misc[0];
+}
+
+// ------------------------------------------------------------------ whole-group kernel
+
 // MT = query tiles of 16 slots held in LDS (MQ = 16*MT); WAVES = waves per workgroup;
-// GATED = emit only values that pass the per-query threshold (fine search) instead of
-// writing every value (coarse search, threshold sampling).
+// GATED = emit only values that pass the per-query gate (fine search) instead of writing
+// every value (coarse search, threshold sampling).
 template <int STORAGE, int MT, int WAVES, bool GATED>
 __global__ __launch_bounds__(WAVES * 64) void scan_kernel(ScanArgs a)
 {
@@ -53,15 +220,9 @@ __global__ __launch_bounds__(WAVES * 64) void scan_kernel(ScanArgs a)
     const int row_bytes = a.row_bytes;
     const int qstride = row_bytes + kQPadBytes;
     char *qtile = smem;
-    uint32_t *s_out = reinterpret_cast<uint32_t *>(smem + (size_t)MQ * qstride);
-    float *s_qn = reinterpret_cast<float *>(s_out + MQ);
-    uint32_t *s_thr = reinterpret_cast<uint32_t *>(s_qn + MQ); // gated: threshold key per slot
-    uint32_t *s_q = s_thr + MQ;                                 // gated: query of the slot
-    uint32_t *s_base = s_q + MQ;                                // gated: start of the query's region
-    float *s_lo = reinterpret_cast<float *>(s_base + MQ);       // gated: origin of the bucket scale
-    float *s_inv = s_lo + MQ;                                   // gated: bucket scale
-    uint32_t *s_bmax = reinterpret_cast<uint32_t *>(s_inv + MQ);// gated: buckets above this are cut
-    uint32_t *s_misc = s_bmax + MQ; // kScanSlotWords per-slot arrays precede this: keep scan_lds_bytes in step
+    Slots s;
+    s.carve(smem + (size_t)MQ * qstride, MQ);
+    uint32_t *s_misc = s.bmax + MQ; // kScanSlotWords per-slot arrays precede this: keep scan_lds_bytes in step
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int ln = lane & 15, lg = lane >> 4;
@@ -69,18 +230,10 @@ __global__ __launch_bounds__(WAVES * 64) void scan_kernel(ScanArgs a)
     const uint32_t grab = *a.batch;
     const int nit = row_bytes / kIterBytes;
     const int chunks_per_row = row_bytes / 16;
-    const float worst = a.metric == PK_METRIC_IP ? -INFINITY : INFINITY;
     uint32_t cur_qbeg = 0xffffffffu, cur_qcnt = 0;
 
-    // Schedule: the first batch of every workgroup is fixed (tile b for workgroup b), later
-    // batches of `grab` tiles are handed out by a counter, so uneven tiles (hot lists scored
-    // against many query groups) still balance while the launch does not start with a burst
-    // of atomics.  The first batch is a single tile so that the emission thresholds get
-    // their first refresh early.  Every workgroup leaves the loop the first time it is handed
-    // a batch past the end.
     uint32_t t0 = blockIdx.x, t1 = min(t0 + 1u, ntiles);
-    for (;;) {
-        if (t0 >= ntiles) break;
+    while (t0 < ntiles) {
         for (uint32_t t = t0; t < t1; ++t) {
             const Tile *tp = a.tiles + t;
             const char *tx = tp->x;
@@ -100,61 +253,15 @@ __global__ __launch_bounds__(WAVES * 64) void scan_kernel(ScanArgs a)
                                                              (size_t)c * 16);
                     *reinterpret_cast<u32x4 *>(qtile + (size_t)m * qstride + (size_t)c * 16) = v;
                 }
-                if (tid < MQ) {
-                    const bool on = (uint32_t)tid < qcnt;
-                    const uint32_t q = on ? a.slot_query[qbeg + tid] : 0u;
-                    s_out[tid] = on ? a.slot_out[qbeg + tid] : 0u;
-                    s_qn[tid] = on ? a.qnorm[q] : 0.f;
-                    if constexpr (GATED) {
-                        const uint32_t base = on ? a.qoff[q] : 0u;
-                        s_q[tid] = q;
-                        s_base[tid] = base;
-                        s_out[tid] -= base; // position inside the query's candidate range
-                        // Emission gate of the slot: a fixed key threshold from the query's
-                        // sample, and a bucket limit that tightens while the scan runs: the
-                        // histogram counts the emitted candidates per bucket, and the first
-                        // bucket at which the running count reaches k bounds the k-th best.
-                        uint32_t bmax = (uint32_t)kHistBins - 1u;
-                        if (on && a.use_hist) {
-                            const uint32_t *hp = a.hist + (size_t)q * kHistBins;
-                            uint32_t h[kHistBins];
-#pragma unroll
-                            for (int j = 0; j < kHistBins; ++j) // device-scope loads: counts other CUs just added
-                                h[j] = __hip_atomic_load(hp + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            uint32_t cum = 0;
-                            bool found = false;
-#pragma unroll
-                            for (int j = 0; j < kHistBins; ++j) {
-                                cum += h[j];
-                                if (!found && cum >= (uint32_t)a.k) {
-                                    found = true;
-                                    bmax = (uint32_t)j;
-                                }
-                            }
-                            // share the limit with every workgroup scoring this query
-                            const uint32_t seen = atomicMin(a.tcur + q, bmax);
-                            bmax = seen < bmax ? seen : bmax;
-                        }
-                        s_thr[tid] = on ? a.tau[q] : 0u;
-                        s_lo[tid] = on ? a.tlo[q] : 0.f;
-                        s_inv[tid] = on ? a.tinv[q] : 0.f;
-                        s_bmax[tid] = bmax;
-                    }
-                }
+                if (tid < MQ) load_slot<GATED>(a, s, tid, qbeg, qcnt);
                 __syncthreads();
                 cur_qbeg = qbeg;
                 cur_qcnt = qcnt;
-            }
-            else if (GATED && a.use_hist == 1) {
-                // same query group as the previous tile: pick up thresholds others have tightened
-                if ((uint32_t)tid < qcnt) {
-                    const uint32_t seen = __hip_atomic_load(a.tcur + s_q[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    if (seen < s_bmax[tid]) s_bmax[tid] = seen;
-                }
+            } else if (GATED && a.use_hist == 1) {
+                if (tid < MQ) refresh_slot(a, s, tid, qcnt);
                 __syncthreads();
             }
             const int mt_used = (int)((qcnt + 15u) >> 4);
-            const int nrows_pad = (nrows + 15) & ~15;
 
             for (int rb = wave; rb * kRowBlock < nrows; rb += WAVES) {
                 const int row_a = rb * kRowBlock + ln;
@@ -170,21 +277,21 @@ __global__ __launch_bounds__(WAVES * 64) void scan_kernel(ScanArgs a)
                 const char *qbase = qtile + (size_t)ln * qstride + lg * 16;
 
 #define PK_LOAD(buf, it)                                                                          \
-    _Pragma("unroll") for (int s = 0; s < 4; ++s)                                                 \
+    _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4)                                              \
     {                                                                                             \
-        buf[0][s] = *reinterpret_cast<const u32x4 *>(p0 + (size_t)(it) * kIterBytes + s * 64);    \
-        buf[1][s] = *reinterpret_cast<const u32x4 *>(p1 + (size_t)(it) * kIterBytes + s * 64);    \
+        buf[0][s4] = *reinterpret_cast<const u32x4 *>(p0 + (size_t)(it) * kIterBytes + s4 * 64);  \
+        buf[1][s4] = *reinterpret_cast<const u32x4 *>(p1 + (size_t)(it) * kIterBytes + s4 * 64);  \
     }
 #define PK_COMPUTE(buf, it)                                                                       \
     _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                             \
     {                                                                                             \
         if (mt < mt_used) {                                                                       \
             const char *qrow = qbase + (size_t)mt * 16 * qstride + (size_t)(it) * kIterBytes;     \
-            _Pragma("unroll") for (int s = 0; s < 4; ++s)                                         \
+            _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4)                                      \
             {                                                                                     \
-                const u32x4 qa = *reinterpret_cast<const u32x4 *>(qrow + s * 64);                 \
-                mfma_step<STORAGE>(acc[mt][0], qa, buf[0][s]);                                    \
-                mfma_step<STORAGE>(acc[mt][1], qa, buf[1][s]);                                    \
+                const u32x4 qa = *reinterpret_cast<const u32x4 *>(qrow + s4 * 64);                \
+                mfma_step<STORAGE>(acc[mt][0], qa, buf[0][s4]);                                   \
+                mfma_step<STORAGE>(acc[mt][1], qa, buf[1][s4]);                                   \
             }                                                                                     \
         }                                                                                         \
     }
@@ -197,79 +304,169 @@ __global__ __launch_bounds__(WAVES * 64) void scan_kernel(ScanArgs a)
                 }
 #undef PK_LOAD
 #undef PK_COMPUTE
-
-                // epilogue: lane holds row (rb*32 + nt*16 + ln) for slots mt*16 + lg*4 + i
-#pragma unroll
-                for (int nt = 0; nt < 2; ++nt) {
-                    const int row = rb * kRowBlock + nt * 16 + ln;
-                    const bool live = row < nrows;
-                    float xn = 0.f;
-                    if (a.metric == PK_METRIC_L2 && live) xn = txn[row];
-#pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) {
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const int m = mt * 16 + lg * 4 + i;
-                            float v = acc[mt][nt][i];
-                            if (a.metric == PK_METRIC_L2) v = fmaxf(xn - 2.f * v + s_qn[m & (MQ - 1)], 0.f);
-                            if constexpr (!GATED) {
-                                if ((uint32_t)m < qcnt && row < nrows_pad)
-                                    a.out[(size_t)s_out[m] + row0 + row] = live ? v : worst;
-                            } else {
-                                // The 16 lanes of a group share slot m.  Values that pass the
-                                // query's threshold are rare: one ballot, and only then one
-                                // aggregated atomic per group to reserve room in the query's region.
-                                const uint32_t bits = order_bits(v, a.metric);
-                                bool pass = live && (uint32_t)m < qcnt && bits <= s_thr[m];
-                                if (__ballot(pass) == 0ull) continue; // the usual case: nothing survives
-                                uint32_t b = 0;
-                                if (pass) {
-                                    b = bucket_of(v, s_lo[m], s_inv[m], a.metric);
-                                    pass = b <= s_bmax[m];
-                                }
-                                const unsigned long long mask = __ballot(pass);
-                                const uint32_t gmask = (uint32_t)(mask >> (lg * 16)) & 0xffffu;
-                                if (gmask) {
-                                    const int leader = __ffs(gmask) - 1;
-                                    uint32_t base = 0;
-                                    if (ln == leader) base = atomicAdd(&a.ccnt[s_q[m]], (uint32_t)__popc(gmask));
-                                    base = __shfl(base, lg * 16 + leader);
-                                    if (pass) {
-                                        const uint32_t rank = __popc(gmask & ((1u << ln) - 1u));
-                                        a.cbuf[(size_t)s_base[m] + base + rank] =
-                                            ((unsigned long long)bits << 32) | (s_out[m] + row0 + (uint32_t)row);
-                                    }
-                                    if (a.use_hist) {
-                                        // count the emitted candidates per bucket; one atomic for the
-                                        // group when its candidates share a bucket (the usual case)
-                                        const uint32_t b0 = __shfl(b, lg * 16 + leader);
-                                        const uint32_t odd =
-                                            (uint32_t)(__ballot(pass && b != b0) >> (lg * 16)) & 0xffffu;
-                                        uint32_t *hq = a.hist + (size_t)s_q[m] * kHistBins;
-                                        if (odd == 0u) {
-                                            if (ln == leader) atomicAdd(hq + b0, (uint32_t)__popc(gmask));
-                                        } else if (pass) {
-                                            atomicAdd(hq + b, 1u);
-                                        }
-                                    }
-                                }
-                            }
-                        }
-                    }
-                }
+                finish_block<MT, GATED>(a, s, acc, rb, ln, lg, nrows, qcnt, row0, txn);
             }
         }
-        __syncthreads();
-        if (tid == 0) s_misc[0] = gridDim.x + atomicAdd(a.tile_ctr, 1u) * grab;
-        __syncthreads();
-        t0 = s_misc[0];
+        t0 = next_batch(a, s_misc, grab);
         t1 = min(t0 + grab, ntiles);
     }
 }
 
+// ------------------------------------------------------------------ sliced-query kernel
+
+// The query group is staged through LDS one 256-byte slice of every row at a time, double
+// buffered: while the waves multiply slice c, the next slice of the rows (registers) and of
+// the queries (registers, then LDS) is already on its way.  One barrier per slice keeps the
+// four waves of the workgroup in step.  MT up to 8 (128 slots): a lane then holds 64
+// accumulator registers.  Always 4 waves, one 32-row block each per pass over the page.
+template <int STORAGE, int MT, bool GATED>
+__global__ __launch_bounds__(256) void scan_ks_kernel(ScanArgs a)
+{
+    extern __shared__ __align__(16) char smem[];
+    constexpr int MQ = MT * 16;
+    constexpr int QLOADS = MQ / 16; // 16-byte pieces of a slice each thread moves: MQ slots x 16 pieces / 256 threads
+    char *qbuf = smem;              // [2][MQ][kKsStride]
+    Slots s;
+    s.carve(smem + (size_t)2 * MQ * kKsStride, MQ);
+    uint32_t *s_slotq = reinterpret_cast<uint32_t *>(s.bmax + MQ); // query row of each slot (all modes)
+    uint32_t *s_misc = s_slotq + MQ;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int ln = lane & 15, lg = lane >> 4;
+    const uint32_t ntiles = *a.ntiles;
+    const uint32_t grab = *a.batch;
+    const int row_bytes = a.row_bytes;
+    const int nit = row_bytes / kIterBytes;
+    uint32_t cur_qbeg = 0xffffffffu, cur_qcnt = 0;
+    const int qm = tid >> 4, qpiece = (tid & 15) * 16; // this thread's slot (mod 16) and piece of a slice
+
+    uint32_t t0 = blockIdx.x, t1 = min(t0 + 1u, ntiles);
+    while (t0 < ntiles) {
+        for (uint32_t t = t0; t < t1; ++t) {
+            const Tile *tp = a.tiles + t;
+            const char *tx = tp->x;
+            const float *txn = tp->xn;
+            const uint32_t row0 = tp->row0;
+            const uint32_t qbeg = __builtin_amdgcn_readfirstlane(tp->qbeg);
+            const uint32_t qcnt = __builtin_amdgcn_readfirstlane((uint32_t)tp->qcnt);
+            const int nrows = __builtin_amdgcn_readfirstlane((int)tp->nrows);
+            if (qbeg != cur_qbeg || qcnt != cur_qcnt) {
+                __syncthreads();
+                if (tid < MQ) {
+                    load_slot<GATED>(a, s, tid, qbeg, qcnt);
+                    s_slotq[tid] = (uint32_t)tid < qcnt ? a.slot_query[qbeg + tid] : 0xffffffffu;
+                }
+                __syncthreads();
+                cur_qbeg = qbeg;
+                cur_qcnt = qcnt;
+            } else if (GATED && a.use_hist == 1) {
+                if (tid < MQ) refresh_slot(a, s, tid, qcnt);
+                __syncthreads();
+            }
+            const int mt_used = (int)((qcnt + 15u) >> 4);
+            // global addresses of this thread's pieces of the query slices
+            const char *qsrc[QLOADS];
+#pragma unroll
+            for (int j = 0; j < QLOADS; ++j) {
+                const uint32_t q = s_slotq[j * 16 + qm];
+                qsrc[j] = q == 0xffffffffu ? nullptr : a.qs + (size_t)q * row_bytes + qpiece;
+            }
+
+            const int npass = (nrows + 4 * kRowBlock - 1) / (4 * kRowBlock);
+            for (int pass = 0; pass < npass; ++pass) {
+                const int rb = pass * 4 + wave;
+                // a wave past the end of the page keeps in step (barriers) on the page's first rows
+                const bool active = rb * kRowBlock < nrows;
+                const int row_a = (active ? rb * kRowBlock : 0) + ln;
+                const char *p0 = tx + (size_t)row_a * row_bytes + lg * 16;
+                const char *p1 = p0 + (size_t)16 * row_bytes;
+                f32x4 acc[MT][2];
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    acc[mt][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    acc[mt][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+                u32x4 xa[2][4], xb[2][4], qr[QLOADS];
+                const char *qrd = qbuf + (size_t)ln * kKsStride + lg * 16;
+
+#define PK_LOAD(buf, it)                                                                          \
+    _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4)                                              \
+    {                                                                                             \
+        buf[0][s4] = *reinterpret_cast<const u32x4 *>(p0 + (size_t)(it) * kIterBytes + s4 * 64);  \
+        buf[1][s4] = *reinterpret_cast<const u32x4 *>(p1 + (size_t)(it) * kIterBytes + s4 * 64);  \
+    }
+#define PK_QLOAD(it)                                                                              \
+    _Pragma("unroll") for (int j = 0; j < QLOADS; ++j)                                            \
+    {                                                                                             \
+        qr[j] = u32x4{0u, 0u, 0u, 0u};                                                            \
+        if (j < mt_used && qsrc[j])                                                               \
+            qr[j] = *reinterpret_cast<const u32x4 *>(qsrc[j] + (size_t)(it) * kIterBytes);        \
+    }
+#define PK_QSTORE(b)                                                                              \
+    _Pragma("unroll") for (int j = 0; j < QLOADS; ++j)                                            \
+    {                                                                                             \
+        if (j < mt_used)                                                                          \
+            *reinterpret_cast<u32x4 *>(qbuf + ((size_t)(b) * MQ + j * 16 + qm) * kKsStride + qpiece) = qr[j]; \
+    }
+#define PK_COMPUTE(buf, b)                                                                        \
+    _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                             \
+    {                                                                                             \
+        if (mt < mt_used) {                                                                       \
+            const char *qrow = qrd + ((size_t)(b) * MQ + mt * 16) * kKsStride;                    \
+            _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4)                                      \
+            {                                                                                     \
+                const u32x4 qa = *reinterpret_cast<const u32x4 *>(qrow + s4 * 64);                \
+                mfma_step<STORAGE>(acc[mt][0], qa, buf[0][s4]);                                   \
+                mfma_step<STORAGE>(acc[mt][1], qa, buf[1][s4]);                                   \
+            }                                                                                     \
+        }                                                                                         \
+    }
+                // slice 0 of the queries into LDS buffer 0, slice 0 of the rows into xa
+                __syncthreads(); // the previous pass / tile no longer reads the query buffers
+                PK_LOAD(xa, 0)
+                PK_QLOAD(0)
+                PK_QSTORE(0)
+                __syncthreads();
+                for (int it = 0; it < nit; it += 2) {
+                    if (it + 1 < nit) {
+                        PK_LOAD(xb, it + 1)
+                        PK_QLOAD(it + 1)
+                    }
+                    PK_COMPUTE(xa, 0)
+                    if (it + 1 < nit) { PK_QSTORE(1) }
+                    __syncthreads();
+                    if (it + 1 < nit) {
+                        if (it + 2 < nit) {
+                            PK_LOAD(xa, it + 2)
+                            PK_QLOAD(it + 2)
+                        }
+                        PK_COMPUTE(xb, 1)
+                        if (it + 2 < nit) { PK_QSTORE(0) }
+                        __syncthreads();
+                    }
+                }
+#undef PK_LOAD
+#undef PK_QLOAD
+#undef PK_QSTORE
+#undef PK_COMPUTE
+                if (active) finish_block<MT, GATED>(a, s, acc, rb, ln, lg, nrows, qcnt, row0, txn);
+            }
+        }
+        t0 = next_batch(a, s_misc, grab);
+        t1 = min(t0 + grab, ntiles);
+    }
+}
+
+// ------------------------------------------------------------------------ host side
+
 int scan_lds_bytes(int row_bytes, int mq)
 {
     return mq * (row_bytes + kQPadBytes) + mq * kScanSlotWords * 4 + 16; // query tile + per-slot arrays + scratch
+}
+
+int scan_ks_lds_bytes(int mq)
+{
+    return 2 * mq * kKsStride + mq * (kScanSlotWords + 1) * 4 + 16; // two slices + per-slot arrays + scratch
 }
 
 // Largest query group (16, 32 or 64 slots) whose LDS tile fits.  fp32 storage is held to
@@ -285,19 +482,32 @@ int scan_max_mq(int row_bytes, int storage, int lds_limit)
     return best;
 }
 
+template <typename K>
+static hipError_t launch_with_lds(K kernel, int &cleared, int lds, const ScanArgs &a, int grid, int threads, hipStream_t s)
+{
+    if (lds > cleared) { // dynamic LDS size the kernel is cleared for (per instantiation)
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        cleared = lds;
+    }
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(threads), lds, s, a);
+    return hipGetLastError();
+}
+
 template <int STORAGE, int MT, int WAVES, bool GATED>
 static hipError_t launch_one(const ScanArgs &a, int grid, hipStream_t s)
 {
-    const int lds = scan_lds_bytes(a.row_bytes, MT * 16);
-    static int attr_bytes = 0; // per instantiation: dynamic LDS size the kernel is cleared for
-    if (lds > attr_bytes) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_kernel<STORAGE, MT, WAVES, GATED>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        attr_bytes = lds;
-    }
-    hipLaunchKernelGGL((scan_kernel<STORAGE, MT, WAVES, GATED>), dim3(grid), dim3(WAVES * 64), lds, s, a);
-    return hipGetLastError();
+    static int cleared = 0;
+    return launch_with_lds(&scan_kernel<STORAGE, MT, WAVES, GATED>, cleared, scan_lds_bytes(a.row_bytes, MT * 16), a, grid,
+                           WAVES * 64, s);
+}
+
+template <int STORAGE, int MT, bool GATED>
+static hipError_t launch_ks_one(const ScanArgs &a, int grid, hipStream_t s)
+{
+    static int cleared = 0;
+    return launch_with_lds(&scan_ks_kernel<STORAGE, MT, GATED>, cleared, scan_ks_lds_bytes(MT * 16), a, grid, 256, s);
 }
 
 template <int STORAGE, int WAVES, bool GATED>
@@ -311,7 +521,19 @@ static hipError_t launch_mt(const ScanArgs &a, int grid, hipStream_t s)
     }
 }
 
-// waves_per_wg: 4 for list pages, 1 for the narrow tiles of the coarse and sampling passes
+template <int STORAGE, bool GATED>
+static hipError_t launch_ks_mt(const ScanArgs &a, int grid, hipStream_t s)
+{
+    switch (a.mq) {
+    case 16: return launch_ks_one<STORAGE, 1, GATED>(a, grid, s);
+    case 32: return launch_ks_one<STORAGE, 2, GATED>(a, grid, s);
+    case 64: return launch_ks_one<STORAGE, 4, GATED>(a, grid, s);
+    case 128: return launch_ks_one<STORAGE, 8, GATED>(a, grid, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+// waves_per_wg: 4 for list pages, 1 for the narrow tiles of the coarse pass
 hipError_t launch_scan(const ScanArgs &a, int waves_per_wg, int grid, hipStream_t s)
 {
     if (a.row_bytes <= 0 || a.row_bytes % kIterBytes != 0) return hipErrorInvalidValue;
@@ -323,6 +545,15 @@ hipError_t launch_scan(const ScanArgs &a, int waves_per_wg, int grid, hipStream_
     }
     if (gated) return launch_mt<PK_F32, 4, true>(a, grid, s);
     return waves_per_wg == 1 ? launch_mt<PK_F32, 1, false>(a, grid, s) : launch_mt<PK_F32, 4, false>(a, grid, s);
+}
+
+// the sliced-query kernel (gated fine search only; fp32 rows are held to 32 slots)
+hipError_t launch_scan_ks(const ScanArgs &a, int grid, hipStream_t s)
+{
+    if (a.row_bytes <= 0 || a.row_bytes % kIterBytes != 0 || a.tau == nullptr) return hipErrorInvalidValue;
+    if (a.storage == PK_F16) return launch_ks_mt<PK_F16, true>(a, grid, s);
+    if (a.mq > 32) return hipErrorInvalidValue;
+    return launch_ks_mt<PK_F32, true>(a, grid, s);
 }
 
 } // namespace pk

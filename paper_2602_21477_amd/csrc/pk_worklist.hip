@@ -190,41 +190,48 @@ __global__ __launch_bounds__(1024) void wl_scan_kernel(WorklistArgs a, MultiArgs
     const uint32_t total = block_exscan(a.qtot, a.qoff, (uint32_t)a.nq, s_wave);
     const uint32_t nl = (uint32_t)a.n_handles * (uint32_t)a.nlist_max;
     block_exscan(a.lcnt, a.lstart, nl, s_wave);
-    // tiles per list -> ltile (in place: first the counts, then their exclusive scan)
+    // tiles per list: regular lists -> ltile, hot lists -> lhtile (counts first, then their scans)
     unsigned long long rows = 0;
-    for (uint32_t gl = threadIdx.x; gl < nl; gl += blockDim.x) {
-        const uint32_t h = gl / (uint32_t)a.nlist_max, l = gl - h * (uint32_t)a.nlist_max;
-        uint32_t nt = 0;
-        const uint32_t c = a.lcnt[gl];
-        if (c > 0) {
-            const DevIndex &ix = *m.ix[h];
-            const uint32_t len = ix.list_len[l];
-            const uint32_t pages = (len + (uint32_t)ix.P - 1) / (uint32_t)ix.P;
-            nt = pages * ((c + (uint32_t)a.mq - 1) / (uint32_t)a.mq);
-            rows += len;
+    for (int hot = 0; hot < 2; ++hot) {
+        for (uint32_t gl = threadIdx.x; gl < nl; gl += blockDim.x) {
+            const uint32_t h = gl / (uint32_t)a.nlist_max, l = gl - h * (uint32_t)a.nlist_max;
+            uint32_t nt = 0;
+            const uint32_t c = a.lcnt[gl];
+            if (c > 0 && (c > a.hot_from) == (hot == 1)) {
+                const DevIndex &ix = *m.ix[h];
+                const uint32_t len = ix.list_len[l];
+                const uint32_t pages = (len + (uint32_t)ix.P - 1) / (uint32_t)ix.P;
+                const uint32_t mq = hot ? (uint32_t)a.mq_hot : (uint32_t)a.mq;
+                nt = pages * ((c + mq - 1) / mq);
+                rows += len;
+            }
+            a.lfill[gl] = nt;
         }
-        a.lfill[gl] = nt;
+        __syncthreads();
+        const uint32_t ntiles = block_exscan(a.lfill, hot ? a.lhtile : a.ltile, nl, s_wave);
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t nt = ntiles;
+            if (ntiles > a.tile_cap || total > a.cand_cap) {
+                // cannot happen while the host bounds hold; refuse to scan rather than overrun
+                nt = 0;
+                atomicOr(&m.ix[0]->ctr[1], (uint32_t)kErrWorklist);
+            }
+            uint32_t *sc = hot ? a.scalars_hot : a.scalars;
+            sc[0] = nt;
+            sc[1] = 0;
+            uint32_t g = nt / (uint32_t)(a.scan_grid * a.grab_div);
+            sc[2] = g < 1 ? 1 : (g > 8 ? 8 : g);
+            if (!hot) {
+                sc[3] = total;
+                atomicAdd(&m.ix[0]->stats[1], (unsigned long long)total);
+            }
+            atomicAdd(&m.ix[0]->stats[2], (unsigned long long)nt);
+        }
     }
     if (rows) atomicAdd(&m.ix[0]->stats[0], rows);
     __syncthreads();
-    const uint32_t ntiles = block_exscan(a.lfill, a.ltile, nl, s_wave);
-    __syncthreads();
     for (uint32_t gl = threadIdx.x; gl < nl; gl += blockDim.x) a.lfill[gl] = 0;
-    if (threadIdx.x == 0) {
-        uint32_t nt = ntiles;
-        if (ntiles > a.tile_cap || total > a.cand_cap) {
-            // cannot happen while the host bounds hold; refuse to scan rather than overrun
-            nt = 0;
-            atomicOr(&m.ix[0]->ctr[1], (uint32_t)kErrWorklist);
-        }
-        a.scalars[0] = nt;
-        a.scalars[1] = 0;
-        uint32_t g = nt / (uint32_t)(a.scan_grid * a.grab_div);
-        a.scalars[2] = g < 1 ? 1 : (g > 8 ? 8 : g);
-        a.scalars[3] = total;
-        atomicAdd(&m.ix[0]->stats[1], (unsigned long long)total);
-        atomicAdd(&m.ix[0]->stats[2], (unsigned long long)nt);
-    }
 }
 
 // slots: every (query, probe) pair takes the next free slot of its list
@@ -248,14 +255,16 @@ __global__ __launch_bounds__(64) void wl_tiles_kernel(WorklistArgs a, MultiArgs 
     const uint32_t gl = blockIdx.x;
     const uint32_t c = a.lcnt[gl];
     if (c == 0) return;
-    if (a.scalars[0] == 0) return; // overflow guard tripped
+    const bool hot = c > a.hot_from;
+    if ((hot ? a.scalars_hot[0] : a.scalars[0]) == 0) return; // overflow guard tripped
     const uint32_t h = gl / (uint32_t)a.nlist_max, l = gl - h * (uint32_t)a.nlist_max;
     const DevIndex &ix = *m.ix[h];
     const uint32_t len = ix.list_len[l];
     const uint32_t P = (uint32_t)ix.P;
     const uint32_t pages = (len + P - 1) / P;
-    const uint32_t groups = (c + (uint32_t)a.mq - 1) / (uint32_t)a.mq;
-    const uint32_t t0 = a.ltile[gl];
+    const uint32_t mq = hot ? (uint32_t)a.mq_hot : (uint32_t)a.mq;
+    const uint32_t groups = (c + mq - 1) / mq;
+    Tile *out = (hot ? a.tiles_hot : a.tiles) + (hot ? a.lhtile[gl] : a.ltile[gl]);
     for (uint32_t j = threadIdx.x; j < pages * groups; j += blockDim.x) {
         const uint32_t g = j / pages, p = j - g * pages;
         const uint32_t pg = phys_page(ix, l, p);
@@ -265,13 +274,13 @@ __global__ __launch_bounds__(64) void wl_tiles_kernel(WorklistArgs a, MultiArgs 
         tl.x = ar.vec + local * P * (size_t)ix.row_bytes;
         tl.xn = ar.norm + local * P;
         tl.row0 = p * P;
-        tl.qbeg = a.lstart[gl] + g * a.mq;
+        tl.qbeg = a.lstart[gl] + g * mq;
         const uint32_t left = len - p * P;
         tl.nrows = (uint16_t)(left < P ? left : P);
-        const uint32_t ql = c - g * a.mq;
-        tl.qcnt = (uint16_t)(ql < (uint32_t)a.mq ? ql : a.mq);
+        const uint32_t ql = c - g * mq;
+        tl.qcnt = (uint16_t)(ql < mq ? ql : mq);
         tl.pad = 0;
-        a.tiles[t0 + j] = tl;
+        out[j] = tl;
     }
 }
 
