@@ -365,6 +365,11 @@ int run_coarse(const Plan &p, const MultiArgs &m, pk_index *const *hs, const flo
         g.stride = p.stride;
         PK_HIP(launch_gemm_scores(g, s));
     }
+    if (p.nlist_max <= kDenseSelectMax && tune("PK_TUNE_DENSESEL", 1)) {
+        PK_HIP(launch_select_dense(p.S, p.cand_off, p.cand_cnt, (uint32_t)p.nlist_max, own->cfg.metric, p.nprobe, p.nq,
+                                   p.probes, s));
+        return PK_OK;
+    }
     SelectArgs se{};
     se.vals = p.S;
     se.qoff = p.cand_off;

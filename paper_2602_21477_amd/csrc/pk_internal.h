@@ -163,6 +163,9 @@ struct SelectArgs {
     unsigned long long *partial;  // [nq][nchunks][K]
 };
 hipError_t launch_select_partial(const SelectArgs &a, int64_t nq, hipStream_t s);
+constexpr int kDenseSelectMax = 8192; // longest score row the register-resident selection takes
+hipError_t launch_select_dense(const float *vals, const uint32_t *qoff, const uint32_t *qcnt, uint32_t max_cnt, int metric,
+                               int K, int64_t nq, int32_t *probes, hipStream_t s);
 hipError_t launch_select_probes(const unsigned long long *partial, int nchunks, int K, int nprobe, int64_t nq,
                                 int32_t *probes, hipStream_t s);
 

@@ -307,7 +307,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan_kernel(ScanArgs a)
                 finish_block<MT, GATED>(a, s, acc, rb, ln, lg, nrows, qcnt, row0, txn);
             }
         }
-        t0 = next_batch(a, s_misc, grab);
+        t0 = gridDim.x >= ntiles ? ntiles : next_batch(a, s_misc, grab); // nothing left when every tile had its own workgroup
         t1 = min(t0 + grab, ntiles);
     }
 }
@@ -452,7 +452,7 @@ __global__ __launch_bounds__(256) void scan_ks_kernel(ScanArgs a)
                 if (active) finish_block<MT, GATED>(a, s, acc, rb, ln, lg, nrows, qcnt, row0, txn);
             }
         }
-        t0 = next_batch(a, s_misc, grab);
+        t0 = gridDim.x >= ntiles ? ntiles : next_batch(a, s_misc, grab); // nothing left when every tile had its own workgroup
         t1 = min(t0 + grab, ntiles);
     }
 }

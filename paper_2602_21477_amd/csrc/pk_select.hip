@@ -80,7 +80,10 @@ struct Selector {
         __syncthreads();
         const uint32_t n = *cnt; // read by everyone before anyone pushes again
         __syncthreads();
-        const uint32_t limit = (uint32_t)K + room <= 2048u ? 2048u : (uint32_t)kSelCap;
+        // flush threshold: the smallest power of two that holds the kept keys plus one round
+        // (small rounds and small K sort small buffers)
+        uint32_t limit = next_pow2((uint32_t)K + room);
+        limit = limit < 512u ? 512u : (limit > (uint32_t)kSelCap ? (uint32_t)kSelCap : limit);
         if (n + room > limit) flush();
     }
     __device__ __forceinline__ void push(u64 key)
@@ -165,6 +168,109 @@ __global__ __launch_bounds__(kSelThreads) void select_probes_kernel(const u64 *p
     for (int r = threadIdx.x; r < nprobe; r += blockDim.x) probes[(size_t)q * nprobe + r] = (int32_t)(uint32_t)keys[r];
 }
 
+
+// ---------------------------------------------------------------- dense rows (coarse search)
+
+// Best K of a row of n <= 256 * VPT scores (Section 2.2: the top-nprobe clusters), for the
+// coarse step and for the top-1 assignment of inserts and the build.  Every thread keeps
+// VPT keys in registers; the exact K-th smallest key is found digit by digit (four 8-bit
+// radix passes over a 256-bin LDS histogram), then the keys below it and as many of the keys
+// equal to it as are needed, lowest positions first, are collected and sorted.  Positions
+// are list numbers, so ties go to the lower list number.
+template <int VPT>
+__global__ __launch_bounds__(256) void select_dense_kernel(const float *vals, const uint32_t *qoff, const uint32_t *qcnt,
+                                                           int metric, int K, int32_t *probes)
+{
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t s_w[4];
+    __shared__ uint32_t s_digit, s_krem, s_ties, s_n;
+    __shared__ u64 sel[PK_MAX_NPROBE];
+    const uint32_t q = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t n = qcnt[q];
+    const float *v = vals + qoff[q];
+    uint32_t key[VPT];
+#pragma unroll
+    for (int j = 0; j < VPT; ++j) {
+        const uint32_t p = tid + 256u * j;
+        key[j] = p < n ? order_bits(v[p], metric) : 0xffffffffu;
+    }
+    uint32_t prefix = 0, krem = (uint32_t)K;
+    for (int pass = 0; pass < 4; ++pass) {
+        const int shift = 24 - 8 * pass;
+        const uint32_t himask = pass == 0 ? 0u : 0xffffffffu << (shift + 8);
+        hist[tid] = 0;
+        if (tid == 0) s_n = 0;
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < VPT; ++j)
+            if (tid + 256u * j < n && (key[j] & himask) == prefix) atomicAdd(&hist[(key[j] >> shift) & 255u], 1u);
+        __syncthreads();
+        // which digit holds the krem-th smallest of the keys that share the prefix
+        const uint32_t c = hist[tid];
+        uint32_t incl = c;
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t y = __shfl_up(incl, off);
+            if (lane >= (uint32_t)off) incl += y;
+        }
+        if (lane == 63) s_w[wave] = incl;
+        __syncthreads();
+        uint32_t before = 0;
+        for (uint32_t w = 0; w < wave; ++w) before += s_w[w];
+        incl += before;
+        if (incl - c < krem && krem <= incl) {
+            s_digit = tid;
+            s_krem = krem - (incl - c);
+            s_ties = c;
+        }
+        __syncthreads();
+        prefix |= s_digit << shift;
+        krem = s_krem;
+        __syncthreads();
+    }
+    // prefix is the K-th smallest key; krem of the s_ties keys equal to it are needed
+    const uint32_t ties = s_ties;
+#pragma unroll
+    for (int j = 0; j < VPT; ++j) {
+        const uint32_t p = tid + 256u * j;
+        if (p < n && (key[j] < prefix || (key[j] == prefix && ties == krem)))
+            sel[atomicAdd(&s_n, 1u)] = ((u64)key[j] << 32) | p;
+    }
+    if (ties != krem) { // more equal keys than needed: take them in position order
+        uint32_t taken = 0;
+        for (int j = 0; j < VPT && taken < krem; ++j) { // position = tid + 256 j: ascending in j, then tid
+            const uint32_t p = tid + 256u * j;
+            const bool tie = p < n && key[j] == prefix;
+            const unsigned long long m = __ballot(tie);
+            if (lane == 0) s_w[wave] = (uint32_t)__popcll(m);
+            __syncthreads();
+            uint32_t rank = taken + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+            for (uint32_t w = 0; w < wave; ++w) rank += s_w[w];
+            const uint32_t total = s_w[0] + s_w[1] + s_w[2] + s_w[3];
+            if (tie && rank < krem) sel[atomicAdd(&s_n, 1u)] = ((u64)prefix << 32) | p;
+            taken += total;
+            __syncthreads();
+        }
+    }
+    __syncthreads();
+    const uint32_t np2 = next_pow2((uint32_t)K);
+    for (uint32_t i = (uint32_t)K + tid; i < np2; i += 256) sel[i] = kMaxKey;
+    __syncthreads();
+    bitonic_sort(sel, np2);
+    for (uint32_t r = tid; r < (uint32_t)K; r += 256) probes[(size_t)q * K + r] = (int32_t)(uint32_t)sel[r];
+}
+
+hipError_t launch_select_dense(const float *vals, const uint32_t *qoff, const uint32_t *qcnt, uint32_t max_cnt, int metric,
+                               int K, int64_t nq, int32_t *probes, hipStream_t s)
+{
+    if (nq <= 0) return hipSuccess;
+    if (max_cnt > (uint32_t)kDenseSelectMax || K > PK_MAX_NPROBE) return hipErrorInvalidValue;
+    const dim3 g((uint32_t)nq), b(256);
+    if (max_cnt <= 1024) hipLaunchKernelGGL(select_dense_kernel<4>, g, b, 0, s, vals, qoff, qcnt, metric, K, probes);
+    else if (max_cnt <= 4096) hipLaunchKernelGGL(select_dense_kernel<16>, g, b, 0, s, vals, qoff, qcnt, metric, K, probes);
+    else hipLaunchKernelGGL(select_dense_kernel<32>, g, b, 0, s, vals, qoff, qcnt, metric, K, probes);
+    return hipGetLastError();
+}
+
 // position inside the query's candidate range -> id stored in the list page
 __device__ int64_t resolve_id(const FinalArgs &a, const MultiArgs &h, uint32_t q, uint32_t pos)
 {
@@ -201,13 +307,14 @@ __global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, 
     if (cnt_q <= (uint32_t)kSelChunk) {
         // few emitted candidates: select straight from the query's region
         const u64 *v = a.keys + a.qoff[q];
-        constexpr uint32_t kRound = kSelThreads * kSelVec;
+        // short ranges go one key per thread and round, so the buffer that gets sorted stays small
+        const uint32_t per = cnt_q <= 8192u ? 1u : (uint32_t)kSelVec;
+        const uint32_t round = kSelThreads * per;
         for (uint32_t r = cnt_q; r > 0;) { // latest (best) keys first, see select_partial_kernel
-            const uint32_t lo = r > kRound ? r - kRound : 0u;
-            sel.reserve(kRound);
-            const uint32_t p = lo + threadIdx.x * kSelVec;
-#pragma unroll
-            for (int j = 0; j < kSelVec; ++j)
+            const uint32_t lo = r > round ? r - round : 0u;
+            sel.reserve(round);
+            const uint32_t p = lo + threadIdx.x * per;
+            for (uint32_t j = 0; j < per; ++j)
                 if (p + j < r) sel.push(v[p + j]);
             r = lo;
         }
