@@ -73,48 +73,75 @@ struct Slots {
     }
 };
 
-// Thread `tid` (< MQ) fills slot `tid` of the group [qbeg, qbeg + qcnt).
-template <bool GATED>
-__device__ __forceinline__ void load_slot(const ScanArgs &a, const Slots &s, int tid, uint32_t qbeg, uint32_t qcnt)
+// Fills the per-slot arrays of the group [qbeg, qbeg + qcnt); every thread of the workgroup
+// calls it.  Dense kernels: thread m fills slot m.  Gated kernels (256 threads): 256 / MQ
+// neighbouring lanes share a slot and split its 64 histogram counters between them.
+template <int MQ, bool GATED>
+__device__ __forceinline__ void load_slots(const ScanArgs &a, const Slots &s, int tid, uint32_t qbeg, uint32_t qcnt)
 {
-    const bool on = (uint32_t)tid < qcnt;
-    const uint32_t q = on ? a.slot_query[qbeg + tid] : 0u;
-    s.out[tid] = on ? a.slot_out[qbeg + tid] : 0u;
-    s.qn[tid] = on ? a.qnorm[q] : 0.f;
-    if constexpr (GATED) {
-        const uint32_t base = on ? a.qoff[q] : 0u;
-        s.q[tid] = q;
-        s.base[tid] = base;
-        s.out[tid] -= base; // position inside the query's candidate range
+    if constexpr (!GATED) {
+        if (tid < MQ) {
+            const bool on = (uint32_t)tid < qcnt;
+            s.out[tid] = on ? a.slot_out[qbeg + tid] : 0u;
+            s.qn[tid] = on ? a.qnorm[a.slot_query[qbeg + tid]] : 0.f;
+        }
+    } else {
+        constexpr int TPS = 256 / MQ;       // threads per slot
+        constexpr int NB = kHistBins / TPS; // counters per thread
+        const int m = tid / TPS, sub = tid % TPS;
+        const bool on = (uint32_t)m < qcnt;
+        const uint32_t q = on ? a.slot_query[qbeg + m] : 0u;
         // Emission gate of the slot: a fixed key threshold from the query's sample, and a
         // bucket limit that tightens while the scan runs: the histogram counts the emitted
         // candidates per bucket, and the first bucket at which the running count reaches k
         // bounds the k-th best.
         uint32_t bmax = (uint32_t)kHistBins - 1u;
-        if (on && a.use_hist) {
-            const uint32_t *hp = a.hist + (size_t)q * kHistBins;
-            uint32_t h[kHistBins];
+        if (a.use_hist) {
+            uint32_t h[NB], sum = 0;
 #pragma unroll
-            for (int j = 0; j < kHistBins; ++j) // device-scope loads: counts other CUs just added
-                h[j] = __hip_atomic_load(hp + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            uint32_t cum = 0;
+            for (int j = 0; j < NB; ++j) { // device-scope loads: counts other CUs just added
+                h[j] = on ? __hip_atomic_load(a.hist + (size_t)q * kHistBins + sub * NB + j, __ATOMIC_RELAXED,
+                                              __HIP_MEMORY_SCOPE_AGENT)
+                          : 0u;
+                sum += h[j];
+            }
+            uint32_t incl = sum;
+#pragma unroll
+            for (int off = 1; off < TPS; off <<= 1) {
+                const uint32_t y = __shfl_up(incl, off);
+                if (sub >= off) incl += y;
+            }
+            uint32_t run = incl - sum; // emitted in the buckets before this thread's
             bool found = false;
 #pragma unroll
-            for (int j = 0; j < kHistBins; ++j) {
-                cum += h[j];
-                if (!found && cum >= (uint32_t)a.k) {
+            for (int j = 0; j < NB; ++j) {
+                run += h[j];
+                if (!found && run >= (uint32_t)a.k) {
                     found = true;
-                    bmax = (uint32_t)j;
+                    bmax = (uint32_t)(sub * NB + j);
                 }
             }
-            // share the limit with every workgroup scoring this query
-            const uint32_t seen = atomicMin(a.tcur + q, bmax);
-            bmax = seen < bmax ? seen : bmax;
+#pragma unroll
+            for (int off = 1; off < TPS; off <<= 1) {
+                const uint32_t y = __shfl_xor(bmax, off);
+                bmax = y < bmax ? y : bmax;
+            }
         }
-        s.thr[tid] = on ? a.tau[q] : 0u;
-        s.lo[tid] = on ? a.tlo[q] : 0.f;
-        s.inv[tid] = on ? a.tinv[q] : 0.f;
-        s.bmax[tid] = bmax;
+        if (sub == 0) {
+            if (on && a.use_hist) { // share the limit with every workgroup scoring this query
+                const uint32_t seen = atomicMin(a.tcur + q, bmax);
+                bmax = seen < bmax ? seen : bmax;
+            }
+            const uint32_t base = on ? a.qoff[q] : 0u;
+            s.out[m] = on ? a.slot_out[qbeg + m] - base : 0u; // position inside the query's candidate range
+            s.qn[m] = on ? a.qnorm[q] : 0.f;
+            s.q[m] = q;
+            s.base[m] = base;
+            s.thr[m] = on ? a.tau[q] : 0u;
+            s.lo[m] = on ? a.tlo[q] : 0.f;
+            s.inv[m] = on ? a.tinv[q] : 0.f;
+            s.bmax[m] = bmax;
+        }
     }
 }
 
@@ -194,18 +221,57 @@ __device__ __forceinline__ void finish_block(const ScanArgs &a, const Slots &s, 
     }
 }
 
-// Schedule shared by both kernels: the first tile of every workgroup is fixed (tile b for
-// workgroup b), later batches of `grab` tiles are handed out by a counter, so uneven tiles
-// still balance while the launch does not start with a burst of atomics.  The first batch is
-// a single tile so that the emission gates get their first refresh early.  Every workgroup
-// stops the first time it is handed a batch past the end.
-__device__ __forceinline__ uint32_t next_batch(const ScanArgs &a, uint32_t *s_misc, uint32_t grab)
-{
-    __syncthreads();
-    if (threadIdx.x == 0) s_misc[0] = gridDim.x + atomicAdd(a.tile_ctr, 1u) * grab;
-    __syncthreads();
-    return s_misc[0];
-}
+// Schedule shared by both kernels.  The first tile of every workgroup is fixed (tile b for
+// workgroup b); later batches come from one counter, so uneven tiles still balance while
+// the launch does not start with a burst of atomics.  A batch is `grab` tiles; the first batch
+// is a single tile so that the emission gates get their first refresh early.  The request for the next
+// batch is issued when a batch starts and collected when it ends, and the descriptor of the
+// next tile is fetched while the current tile is scored.  Every workgroup stops the first
+// time it is handed a batch past the end.
+struct Sched {
+    uint32_t t, end, ntiles, grab;
+    int parity;
+    bool fresh; // t is the first tile of a batch
+    __device__ __forceinline__ void start(uint32_t nt, uint32_t g)
+    {
+        ntiles = nt;
+        grab = g;
+        t = blockIdx.x;
+        end = t + 1 < nt ? t + 1 : nt;
+        parity = 0;
+        fresh = true;
+    }
+    // thread 0 asks for the batch after the current one (s_misc[2*parity], [2*parity+1] = start, size)
+    __device__ __forceinline__ void request(const ScanArgs &a, uint32_t *s_misc) const
+    {
+        if (threadIdx.x == 0 && gridDim.x < ntiles) {
+            // One atomic per batch and no other access to the counter: every workgroup of the
+            // grid claims from this one address, and a second access per claim (a load, to
+            // size the batch by what is left) measurably slows the whole scan.
+            const uint32_t want = grab;
+            s_misc[2 * parity] = gridDim.x + atomicAdd(a.tile_ctr, want);
+            s_misc[2 * parity + 1] = want;
+        }
+    }
+    // index of the tile after t; at the end of a batch this collects the requested batch (block-wide)
+    __device__ __forceinline__ uint32_t peek(const uint32_t *s_misc, uint32_t &next_end, bool &next_fresh) const
+    {
+        if (t + 1 < end) {
+            next_end = end;
+            next_fresh = false;
+            return t + 1;
+        }
+        next_fresh = true;
+        if (gridDim.x >= ntiles) {
+            next_end = ntiles;
+            return ntiles;
+        }
+        __syncthreads();
+        const uint32_t st = s_misc[2 * parity], sz = s_misc[2 * parity + 1];
+        next_end = st + sz < ntiles ? st + sz : ntiles;
+        return st;
+    }
+};
 
 // ------------------------------------------------------------------ whole-group kernel
 
@@ -213,7 +279,7 @@ __device__ __forceinline__ uint32_t next_batch(const ScanArgs &a, uint32_t *s_mi
 // GATED = emit only values that pass the per-query gate (fine search) instead of writing
 // every value (coarse search, threshold sampling).
 template <int STORAGE, int MT, int WAVES, bool GATED>
-__global__ __launch_bounds__(WAVES * 64) void scan_kernel(ScanArgs a)
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(3, 8))) void scan_kernel(ScanArgs a)
 {
     extern __shared__ __align__(16) char smem[];
     constexpr int MQ = MT * 16;
@@ -226,56 +292,28 @@ __global__ __launch_bounds__(WAVES * 64) void scan_kernel(ScanArgs a)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int ln = lane & 15, lg = lane >> 4;
-    const uint32_t ntiles = *a.ntiles;
-    const uint32_t grab = *a.batch;
     const int nit = row_bytes / kIterBytes;
     const int chunks_per_row = row_bytes / 16;
     uint32_t cur_qbeg = 0xffffffffu, cur_qcnt = 0;
+    const char *qbase = qtile + (size_t)ln * qstride + lg * 16;
 
-    uint32_t t0 = blockIdx.x, t1 = min(t0 + 1u, ntiles);
-    while (t0 < ntiles) {
-        for (uint32_t t = t0; t < t1; ++t) {
-            const Tile *tp = a.tiles + t;
-            const char *tx = tp->x;
-            const float *txn = tp->xn;
-            const uint32_t row0 = tp->row0;
-            const uint32_t qbeg = __builtin_amdgcn_readfirstlane(tp->qbeg);
-            const uint32_t qcnt = __builtin_amdgcn_readfirstlane((uint32_t)tp->qcnt);
-            const int nrows = __builtin_amdgcn_readfirstlane((int)tp->nrows);
-            if (qbeg != cur_qbeg || qcnt != cur_qcnt) {
-                __syncthreads(); // everyone is done with the previous query group
-                const int mrows = (int)((qcnt + 15u) & ~15u);
-                for (int idx = tid; idx < mrows * chunks_per_row; idx += WAVES * 64) {
-                    const int m = idx / chunks_per_row, c = idx - m * chunks_per_row;
-                    u32x4 v = {0u, 0u, 0u, 0u};
-                    if ((uint32_t)m < qcnt)
-                        v = *reinterpret_cast<const u32x4 *>(a.qs + (size_t)a.slot_query[qbeg + m] * row_bytes +
-                                                             (size_t)c * 16);
-                    *reinterpret_cast<u32x4 *>(qtile + (size_t)m * qstride + (size_t)c * 16) = v;
-                }
-                if (tid < MQ) load_slot<GATED>(a, s, tid, qbeg, qcnt);
-                __syncthreads();
-                cur_qbeg = qbeg;
-                cur_qcnt = qcnt;
-            } else if (GATED && a.use_hist == 1) {
-                if (tid < MQ) refresh_slot(a, s, tid, qcnt);
-                __syncthreads();
-            }
-            const int mt_used = (int)((qcnt + 15u) >> 4);
+    Sched sc;
+    sc.start(*a.ntiles, *a.batch);
+    if (sc.t >= sc.ntiles) return;
+    Tile cur = a.tiles[sc.t];
+    while (sc.t < sc.ntiles) {
+        const char *tx = cur.x;
+        const float *txn = cur.xn;
+        const uint32_t row0 = cur.row0;
+        const uint32_t qbeg = __builtin_amdgcn_readfirstlane(cur.qbeg);
+        const uint32_t qcnt = __builtin_amdgcn_readfirstlane((uint32_t)cur.qcnt);
+        const int nrows = __builtin_amdgcn_readfirstlane((int)cur.nrows);
 
-            for (int rb = wave; rb * kRowBlock < nrows; rb += WAVES) {
-                const int row_a = rb * kRowBlock + ln;
-                const char *p0 = tx + (size_t)row_a * row_bytes + lg * 16;
-                const char *p1 = p0 + (size_t)16 * row_bytes;
-                f32x4 acc[MT][2];
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    acc[mt][0] = f32x4{0.f, 0.f, 0.f, 0.f};
-                    acc[mt][1] = f32x4{0.f, 0.f, 0.f, 0.f};
-                }
-                u32x4 xa[2][4], xb[2][4]; // two register buffers of one iteration each
-                const char *qbase = qtile + (size_t)ln * qstride + lg * 16;
-
+        u32x4 xa[2][4], xb[2][4]; // two register buffers of one 256-byte slice of 32 rows each
+        const char *p0, *p1;
+#define PK_ROWS(rb)                                                                               \
+    p0 = tx + (size_t)((rb) * kRowBlock + ln) * row_bytes + lg * 16;                              \
+    p1 = p0 + (size_t)16 * row_bytes;
 #define PK_LOAD(buf, it)                                                                          \
     _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4)                                              \
     {                                                                                             \
@@ -295,20 +333,70 @@ __global__ __launch_bounds__(WAVES * 64) void scan_kernel(ScanArgs a)
             }                                                                                     \
         }                                                                                         \
     }
+        // The wave's first slice of rows is requested first of all: the batch bookkeeping, the
+        // fetch of the next tile's descriptor and a reload of the query group then overlap with
+        // the memory latency.
+        int rb = wave;
+        bool preloaded = false;
+        if (rb * kRowBlock < nrows) {
+            PK_ROWS(rb)
+            PK_LOAD(xa, 0)
+            preloaded = true;
+        }
+        if (sc.fresh) sc.request(a, s_misc);
+        uint32_t next_end;
+        bool next_fresh;
+        const uint32_t tn = sc.peek(s_misc, next_end, next_fresh);
+        const Tile nxt = a.tiles[tn < sc.ntiles ? tn : sc.ntiles - 1]; // in flight while this tile is scored
+        if (qbeg != cur_qbeg || qcnt != cur_qcnt) {
+            __syncthreads(); // everyone is done with the previous query group
+            const int mrows = (int)((qcnt + 15u) & ~15u);
+            for (int idx = tid; idx < mrows * chunks_per_row; idx += WAVES * 64) {
+                const int m = idx / chunks_per_row, c = idx - m * chunks_per_row;
+                u32x4 v = {0u, 0u, 0u, 0u};
+                if ((uint32_t)m < qcnt)
+                    v = *reinterpret_cast<const u32x4 *>(a.qs + (size_t)a.slot_query[qbeg + m] * row_bytes +
+                                                         (size_t)c * 16);
+                *reinterpret_cast<u32x4 *>(qtile + (size_t)m * qstride + (size_t)c * 16) = v;
+            }
+            load_slots<MQ, GATED>(a, s, tid, qbeg, qcnt);
+            __syncthreads();
+            cur_qbeg = qbeg;
+            cur_qcnt = qcnt;
+        } else if (GATED && a.use_hist == 1) {
+            if (tid < MQ) refresh_slot(a, s, tid, qcnt);
+            __syncthreads();
+        }
+        const int mt_used = (int)((qcnt + 15u) >> 4);
+
+        for (; rb * kRowBlock < nrows; rb += WAVES) {
+            f32x4 acc[MT][2];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                acc[mt][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+                acc[mt][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+            if (!preloaded) {
+                PK_ROWS(rb)
                 PK_LOAD(xa, 0)
-                for (int it = 0; it < nit; it += 2) {
-                    if (it + 1 < nit) { PK_LOAD(xb, it + 1) }
-                    PK_COMPUTE(xa, it)
-                    if (it + 2 < nit) { PK_LOAD(xa, it + 2) }
-                    if (it + 1 < nit) { PK_COMPUTE(xb, it + 1) }
-                }
+            }
+            preloaded = false;
+            for (int it = 0; it < nit; it += 2) {
+                if (it + 1 < nit) { PK_LOAD(xb, it + 1) }
+                PK_COMPUTE(xa, it)
+                if (it + 2 < nit) { PK_LOAD(xa, it + 2) }
+                if (it + 1 < nit) { PK_COMPUTE(xb, it + 1) }
+            }
+            finish_block<MT, GATED>(a, s, acc, rb, ln, lg, nrows, qcnt, row0, txn);
+        }
+#undef PK_ROWS
 #undef PK_LOAD
 #undef PK_COMPUTE
-                finish_block<MT, GATED>(a, s, acc, rb, ln, lg, nrows, qcnt, row0, txn);
-            }
-        }
-        t0 = gridDim.x >= ntiles ? ntiles : next_batch(a, s_misc, grab); // nothing left when every tile had its own workgroup
-        t1 = min(t0 + grab, ntiles);
+        sc.t = tn;
+        sc.end = next_end;
+        if (next_fresh) sc.parity ^= 1;
+        sc.fresh = next_fresh;
+        cur = nxt;
     }
 }
 
@@ -320,7 +408,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan_kernel(ScanArgs a)
 // four waves of the workgroup in step.  MT up to 8 (128 slots): a lane then holds 64
 // accumulator registers.  Always 4 waves, one 32-row block each per pass over the page.
 template <int STORAGE, int MT, bool GATED>
-__global__ __launch_bounds__(256) void scan_ks_kernel(ScanArgs a)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 8))) void scan_ks_kernel(ScanArgs a)
 {
     extern __shared__ __align__(16) char smem[];
     constexpr int MQ = MT * 16;
@@ -333,29 +421,32 @@ __global__ __launch_bounds__(256) void scan_ks_kernel(ScanArgs a)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int ln = lane & 15, lg = lane >> 4;
-    const uint32_t ntiles = *a.ntiles;
-    const uint32_t grab = *a.batch;
     const int row_bytes = a.row_bytes;
     const int nit = row_bytes / kIterBytes;
     uint32_t cur_qbeg = 0xffffffffu, cur_qcnt = 0;
     const int qm = tid >> 4, qpiece = (tid & 15) * 16; // this thread's slot (mod 16) and piece of a slice
 
-    uint32_t t0 = blockIdx.x, t1 = min(t0 + 1u, ntiles);
-    while (t0 < ntiles) {
-        for (uint32_t t = t0; t < t1; ++t) {
-            const Tile *tp = a.tiles + t;
-            const char *tx = tp->x;
-            const float *txn = tp->xn;
-            const uint32_t row0 = tp->row0;
-            const uint32_t qbeg = __builtin_amdgcn_readfirstlane(tp->qbeg);
-            const uint32_t qcnt = __builtin_amdgcn_readfirstlane((uint32_t)tp->qcnt);
-            const int nrows = __builtin_amdgcn_readfirstlane((int)tp->nrows);
+    Sched sc;
+    sc.start(*a.ntiles, *a.batch);
+    if (sc.t >= sc.ntiles) return;
+    Tile cur = a.tiles[sc.t];
+    while (sc.t < sc.ntiles) {
+        if (sc.fresh) sc.request(a, s_misc);
+        uint32_t next_end;
+        bool next_fresh;
+        const uint32_t tn = sc.peek(s_misc, next_end, next_fresh);
+        const Tile nxt = a.tiles[tn < sc.ntiles ? tn : sc.ntiles - 1]; // in flight while this tile is scored
+        {
+            const char *tx = cur.x;
+            const float *txn = cur.xn;
+            const uint32_t row0 = cur.row0;
+            const uint32_t qbeg = __builtin_amdgcn_readfirstlane(cur.qbeg);
+            const uint32_t qcnt = __builtin_amdgcn_readfirstlane((uint32_t)cur.qcnt);
+            const int nrows = __builtin_amdgcn_readfirstlane((int)cur.nrows);
             if (qbeg != cur_qbeg || qcnt != cur_qcnt) {
                 __syncthreads();
-                if (tid < MQ) {
-                    load_slot<GATED>(a, s, tid, qbeg, qcnt);
-                    s_slotq[tid] = (uint32_t)tid < qcnt ? a.slot_query[qbeg + tid] : 0xffffffffu;
-                }
+                load_slots<MQ, GATED>(a, s, tid, qbeg, qcnt);
+                if (tid < MQ) s_slotq[tid] = (uint32_t)tid < qcnt ? a.slot_query[qbeg + tid] : 0xffffffffu;
                 __syncthreads();
                 cur_qbeg = qbeg;
                 cur_qcnt = qcnt;
@@ -452,8 +543,11 @@ __global__ __launch_bounds__(256) void scan_ks_kernel(ScanArgs a)
                 if (active) finish_block<MT, GATED>(a, s, acc, rb, ln, lg, nrows, qcnt, row0, txn);
             }
         }
-        t0 = gridDim.x >= ntiles ? ntiles : next_batch(a, s_misc, grab); // nothing left when every tile had its own workgroup
-        t1 = min(t0 + grab, ntiles);
+        sc.t = tn;
+        sc.end = next_end;
+        if (next_fresh) sc.parity ^= 1;
+        sc.fresh = next_fresh;
+        cur = nxt;
     }
 }
 
