@@ -133,17 +133,17 @@ uint64_t wq_ub(const pk_index *ix, int nprobe)
 struct Plan {
     int64_t nq;
     int nprobe, k, nh;
-    int mq_c, mq_f, mq_h, grid_c, grid_f, grid_h, grid_s, cchunks, nchunks, K, nlist_max, sp;
+    int mq_f, mq_h, grid_f, grid_h, grid_s, cchunks, nchunks, K, nlist_max, sp;
     uint32_t hot_from;
-    uint32_t stride, cand_cap, tile_cap, ctiles, span;
+    uint32_t stride, cand_cap, tile_cap, span;
     bool need_coarse, need_fine, f16;
     // buffers
     char *qs32, *qs;
     float *qn32, *qn, *S, *svals, *tlo, *tinv;
-    uint32_t *cand_off, *cand_cnt, *cslot_q, *cslot_o, *lcnt, *lstart, *lfill, *ltile, *lhtile, *pair_off, *qtot, *qoff, *slot_q,
+    uint32_t *cand_off, *cand_cnt, *lcnt, *lstart, *lfill, *ltile, *lhtile, *pair_off, *qtot, *qoff, *slot_q,
         *slot_o, *scalars, *tau, *tcur, *hist, *ccnt, *sslot_q, *sslot_o;
     uint16_t *qagent;
-    Tile *ctile_buf, *tiles, *tiles_hot, *stiles;
+    Tile *tiles, *tiles_hot, *stiles;
     unsigned long long *cpartial, *partial, *cbuf;
     int32_t *probes;
     size_t bytes;
@@ -167,11 +167,8 @@ void carve(Plan &p, char *base, const pk_index *own)
     p.probes = c.take<int32_t>(nq * p.nprobe);
     p.cand_off = c.take<uint32_t>(nq);
     p.cand_cnt = c.take<uint32_t>(nq);
-    p.cslot_q = c.take<uint32_t>(nq);
-    p.cslot_o = c.take<uint32_t>(nq);
     if (p.need_coarse) {
         p.S = c.take<float>(nq * p.stride + 16);
-        p.ctile_buf = c.take<Tile>(p.ctiles + 1);
         p.cpartial = c.take<unsigned long long>(nq * p.cchunks * p.nprobe);
     }
     if (p.need_fine) {
@@ -210,9 +207,8 @@ int tune(const char *name, int dflt)
     return v ? atoi(v) : dflt;
 }
 
-int grid_for(const pk_index *ix, int row_bytes, int mq, int waves)
+int grid_for(const pk_index *ix, int row_bytes, int mq)
 {
-    if (waves == 1) return ix->num_cu * 8;
     const int lds = scan_lds_bytes(row_bytes, mq);
     int per_cu = (160 * 1024) / lds;
     per_cu = std::max(1, std::min(per_cu, tune("PK_TUNE_WGS", 4)));
@@ -232,7 +228,6 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
     p.need_coarse = need_coarse;
     p.need_fine = need_fine;
     p.f16 = own->cfg.storage == PK_F16;
-    p.mq_c = scan_max_mq(own->rb32, PK_F32, own->lds_limit);
     p.mq_f = scan_max_mq(own->row_bytes, own->cfg.storage, own->lds_limit);
     {
         // Query slots per scan tile: the smallest group that holds the expected number of
@@ -260,22 +255,20 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
             if (p.mq_f < 16) p.mq_f = 16; // unused, but keeps the tile arithmetic defined
         }
     }
-    if (p.mq_c < 16 || p.mq_f < 16) return PK_ERR_UNSUPPORTED;
-    p.grid_c = grid_for(own, own->rb32, p.mq_c, 1);
-    p.grid_f = grid_for(own, own->row_bytes, p.mq_f, 4);
+    if (p.mq_f < 16) return PK_ERR_UNSUPPORTED;
+    p.grid_f = grid_for(own, own->row_bytes, p.mq_f);
     p.grid_h = own->num_cu * std::max(1, std::min((160 * 1024) / scan_ks_lds_bytes(p.mq_h), tune("PK_TUNE_WGS", 4)));
-    p.grid_s = grid_for(own, own->row_bytes, 16, 4);
+    p.grid_s = grid_for(own, own->row_bytes, 16);
     p.K = k + 1;
     p.sp = (k + own->P - 1) / own->P; // sample pages: at least k rows of the first probed list
     p.span = (uint32_t)(p.sp * own->P);
-    uint64_t cand = 0, tiles = 0, ctiles = 0, wmax = 0;
+    uint64_t cand = 0, tiles = 0, wmax = 0;
     int nlist_hi = 0, pad_hi = 0;
     for (int a = 0; a < nh; ++a) {
         const pk_index *ix = hs[a];
         const uint64_t nqa = qlo[a + 1] - qlo[a];
         nlist_hi = std::max(nlist_hi, ix->cfg.nlist);
         pad_hi = std::max(pad_hi, ix->nlist_pad);
-        ctiles += (nqa + p.mq_c - 1) / p.mq_c * (uint64_t)(ix->nlist_pad / kCoarsePage);
         if (nqa == 0) continue;
         const uint64_t w = wq_ub(ix, nprobe);
         wmax = std::max(wmax, w);
@@ -283,10 +276,9 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
         const uint64_t pp = w / ix->P + nprobe;
         tiles += std::min<uint64_t>(pages_used_ub(ix), nqa * pp) + nqa * pp / std::min(p.mq_f, p.mq_h) + 1;
     }
-    if (cand > 0xfffffff0ull || tiles > 0xfffffff0ull || ctiles > 0xfffffff0ull) return PK_ERR_UNSUPPORTED;
+    if (cand > 0xfffffff0ull || tiles > 0xfffffff0ull) return PK_ERR_UNSUPPORTED;
     p.nlist_max = nlist_hi;
     p.stride = (uint32_t)pad_hi;
-    p.ctiles = (uint32_t)ctiles;
     p.cchunks = (nlist_hi + kSelChunk - 1) / kSelChunk;
     p.cand_cap = (uint32_t)cand;
     p.tile_cap = (uint32_t)tiles;
@@ -295,60 +287,62 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
     return PK_OK;
 }
 
-// handles whose query segment is long enough go through the MFMA GEMM instead of coarse tiles
-bool coarse_by_gemm(uint32_t nqa) { return nqa >= (uint32_t)tune("PK_TUNE_GEMM_MIN", 48); }
+// A query segment goes through the 128 x 128-tile MFMA GEMM when it has enough tiles to
+// occupy a good part of the chip; smaller segments take the finely cut centroid kernel.
+bool coarse_by_gemm(uint32_t nqa, const pk_index *ix)
+{
+    const uint64_t wgs = (uint64_t)((nqa + 127) / 128) * (uint64_t)((ix->nlist_pad + 127) / 128);
+    return wgs >= (uint64_t)tune("PK_TUNE_GEMM_WGS", 128);
+}
 
-void fill_multi(MultiArgs &m, pk_index *const *hs, int nh, const uint32_t *qlo, int mq_c)
+void fill_multi(MultiArgs &m, pk_index *const *hs, int nh, const uint32_t *qlo)
 {
     std::memset(&m, 0, sizeof(m));
     m.n = nh;
-    uint32_t ct = 0;
     for (int a = 0; a < nh; ++a) {
         m.ix[a] = hs[a]->dev;
         m.qlo[a] = qlo[a];
-        m.ctile[a] = ct;
-        const uint32_t nqa = qlo[a + 1] - qlo[a];
-        if (!coarse_by_gemm(nqa)) ct += (nqa + mq_c - 1) / mq_c * (uint32_t)(hs[a]->nlist_pad / kCoarsePage);
     }
     m.qlo[nh] = qlo[nh];
-    m.ctile[nh] = ct;
 }
 
 // Coarse search of one batch: probes[nq][nprobe] in the plan's workspace.
 int run_coarse(const Plan &p, const MultiArgs &m, pk_index *const *hs, const float *q, hipStream_t s)
 {
     const pk_index *own = hs[0];
-    PK_HIP(launch_prep_queries(q, p.nq, own->cfg.d, PK_F32, own->rb32, p.qs32, p.qn32, s));
-    CoarseArgs ca{};
-    ca.mq = p.mq_c;
-    ca.scan_grid = p.grid_c;
+    QueryMeta qm{};
+    qm.stride = p.stride;
+    qm.cand_off = p.cand_off;
+    qm.cand_cnt = p.cand_cnt;
+    qm.qagent = p.qagent;
+    PK_HIP(launch_prep_coarse(q, p.nq, own->cfg.d, own->rb32, p.qs32, p.qn32, qm, m, s));
+    // small segments: one launch of the centroid kernel for all of them
+    CentroidArgs ca{};
+    ca.qs = p.qs32;
+    ca.qnorm = p.qn32;
+    ca.out = p.S;
     ca.stride = p.stride;
-    ca.slot_query = p.cslot_q;
-    ca.slot_out = p.cslot_o;
-    ca.cand_off = p.cand_off;
-    ca.cand_cnt = p.cand_cnt;
-    ca.qagent = p.qagent;
-    ca.tiles = p.ctile_buf;
-    ca.scalars = p.scalars;
-    PK_HIP(launch_coarse_tiles(ca, m, s));
-    ScanArgs sa{};
-    sa.tiles = p.ctile_buf;
-    sa.ntiles = p.scalars + 0;
-    sa.tile_ctr = p.scalars + 1;
-    sa.batch = p.scalars + 2;
-    sa.qs = p.qs32;
-    sa.qnorm = p.qn32;
-    sa.slot_query = p.cslot_q;
-    sa.slot_out = p.cslot_o;
-    sa.out = p.S;
-    sa.row_bytes = own->rb32;
-    sa.metric = own->cfg.metric;
-    sa.storage = PK_F32;
-    sa.mq = p.mq_c;
-    if (m.ctile[m.n] > 0) PK_HIP(launch_scan(sa, 1, std::min<int>(p.grid_c, (int)m.ctile[m.n]), s));
+    ca.row_bytes = own->rb32;
+    ca.metric = own->cfg.metric;
+    uint32_t longest = 0;
     for (int a = 0; a < m.n; ++a) {
         const uint32_t nqa = m.qlo[a + 1] - m.qlo[a];
-        if (!coarse_by_gemm(nqa)) continue;
+        if (!coarse_by_gemm(nqa, hs[a])) longest = std::max(longest, nqa);
+    }
+    ca.chunk = (int)std::min<uint32_t>(64, (longest + 15) / 16 * 16);
+    uint64_t wgs = 0;
+    for (int a = 0; a < m.n; ++a) {
+        const uint32_t nqa = m.qlo[a + 1] - m.qlo[a];
+        ca.blk[a] = (uint32_t)wgs;
+        if (nqa > 0 && !coarse_by_gemm(nqa, hs[a]))
+            wgs += (uint64_t)((nqa + ca.chunk - 1) / ca.chunk) * (uint64_t)(hs[a]->nlist_pad / 16);
+    }
+    if (wgs > 0x7fffffffull) return PK_ERR_UNSUPPORTED;
+    ca.blk[m.n] = (uint32_t)wgs;
+    if (wgs > 0) PK_HIP(launch_centroid_scores(ca, m, s));
+    for (int a = 0; a < m.n; ++a) {
+        const uint32_t nqa = m.qlo[a + 1] - m.qlo[a];
+        if (nqa == 0 || !coarse_by_gemm(nqa, hs[a])) continue;
         const pk_index *ix = hs[a];
         GemmArgs g{};
         g.q = reinterpret_cast<const float *>(p.qs32) + (size_t)m.qlo[a] * ix->dpad32;
@@ -424,7 +418,7 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
     ss.metric = own->cfg.metric;
     ss.storage = own->cfg.storage;
     ss.mq = 16;
-    PK_HIP(launch_scan(ss, 4, p.grid_s, s));
+    PK_HIP(launch_scan(ss, p.grid_s, s));
     PK_HIP(launch_tau(sm, s));
 
     WorklistArgs w{};
@@ -482,7 +476,7 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
     sa.metric = own->cfg.metric;
     sa.storage = own->cfg.storage;
     sa.mq = p.mq_f;
-    if (p.hot_from > 0) PK_HIP(launch_scan(sa, 4, p.grid_f, s));
+    if (p.hot_from > 0) PK_HIP(launch_scan(sa, p.grid_f, s));
     if (p.hot_from != 0xffffffffu) {
         sa.tiles = p.tiles_hot;
         sa.ntiles = p.scalars + 12;
@@ -551,7 +545,7 @@ int search_impl(pk_index *const *hs, int nh, const int64_t *q_offsets, const flo
         PK_TRY(ensure_ws(own, p.bytes, s));
         carve(p, own->ws, own);
         MultiArgs m;
-        fill_multi(m, hs, nh, qlo.data(), p.mq_c);
+        fill_multi(m, hs, nh, qlo.data());
         const float *q = queries + (size_t)q0 * d;
         const bool timed = mode == kFull && own->prof_on;
         if (timed) PK_TRY(mark(own, s));
@@ -603,7 +597,7 @@ Dims dims_of(const pk_config *c)
     x.rb32 = (int)round_up((size_t)c->d * 4, kIterBytes);
     x.dpad32 = x.rb32 / 4;
     x.row_bytes = c->storage == PK_F16 ? (int)round_up((size_t)c->d * 2, kIterBytes) : x.rb32;
-    x.nlist_pad = (int)round_up(c->nlist, kCoarsePage);
+    x.nlist_pad = (int)round_up(c->nlist, kCentroidPad);
     x.P = c->page_vecs ? c->page_vecs : 128;
     x.max_dp = c->max_delta_pages ? c->max_delta_pages : 1024;
     Carver h{nullptr, 0};
@@ -735,7 +729,7 @@ int insert_impl(pk_index *ix, const float *x, const int64_t *ids, int64_t m, con
             assign = forced + i0;
         } else {
             MultiArgs mm;
-            fill_multi(mm, hs, 1, qlo, p.mq_c);
+            fill_multi(mm, hs, 1, qlo);
             PK_TRY(run_coarse(p, mm, hs, xc, s));
             assign = p.probes;
         }
@@ -881,7 +875,7 @@ int pk_index_build(const pk_config *cfg, const float *centroids, const float *ve
             if (rc != PK_OK) break;
             carve(p, ix->ws, ix);
             MultiArgs mm;
-            fill_multi(mm, hs, 1, qlo, p.mq_c);
+            fill_multi(mm, hs, 1, qlo);
             rc = run_coarse(p, mm, hs, vectors + (size_t)i0 * cfg->d, s);
             if (rc == PK_OK && launch_copy_i32(p.probes, d_assign + i0, mc, s) != hipSuccess) rc = PK_ERR_HIP;
         }

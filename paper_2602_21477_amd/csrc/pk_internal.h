@@ -15,7 +15,7 @@ constexpr int kScanThreads = 256;     // 4 waves per workgroup in the scan kerne
 constexpr int kRowBlock = 32;         // rows one wave scores per pass (two 16-wide MFMA tiles)
 constexpr int kIterBytes = 256;       // bytes of one row consumed per inner iteration
 constexpr int kQPadBytes = 16;        // LDS row padding of the query tile (bank spread)
-constexpr int kCoarsePage = 32;       // rows per coarse tile (one wave per workgroup there)
+constexpr int kCentroidPad = 32;      // the centroid table is zero padded to a multiple of this many rows
 constexpr int kSelThreads = 256;
 constexpr int kSelVec = 4;            // candidates per thread per round
 constexpr int kSelCap = 4096;         // LDS key buffer of the select kernels (K + one round <= cap)
@@ -111,7 +111,6 @@ static_assert(sizeof(Tile) == 32, "Tile is 32 bytes");
 struct MultiArgs {
     const DevIndex *ix[PK_MAX_HANDLES];
     uint32_t qlo[PK_MAX_HANDLES + 1];   // handle a owns query rows [qlo[a], qlo[a+1])
-    uint32_t ctile[PK_MAX_HANDLES + 1]; // first coarse tile of handle a; [n] = total
     int32_t n;
 };
 
@@ -148,7 +147,7 @@ struct ScanArgs {
     int k, use_hist;
     int row_bytes, metric, storage, mq;
 };
-hipError_t launch_scan(const ScanArgs &a, int waves_per_wg, int grid, hipStream_t s);
+hipError_t launch_scan(const ScanArgs &a, int grid, hipStream_t s);
 hipError_t launch_scan_ks(const ScanArgs &a, int grid, hipStream_t s);
 int scan_lds_bytes(int row_bytes, int mq);
 int scan_ks_lds_bytes(int mq);
@@ -182,16 +181,27 @@ struct FinalArgs {
 };
 hipError_t launch_select_final(const FinalArgs &a, const MultiArgs &m, int64_t nq, hipStream_t s);
 
-struct CoarseArgs {
-    int mq, scan_grid;
-    uint32_t stride;              // elements between the score rows of consecutive queries
-    uint32_t *slot_query, *slot_out;
+// Per-query bookkeeping of the coarse step, filled while the queries are prepared.
+struct QueryMeta {
+    uint32_t stride;               // elements between the score rows of consecutive queries
     uint32_t *cand_off, *cand_cnt; // [nq] score row of each query and its length (nlist of its handle)
-    uint16_t *qagent;             // [nq] out: handle number of each query
-    Tile *tiles;
-    uint32_t *scalars;            // [0] ntiles [1] tile counter [2] grab size
+    uint16_t *qagent;              // [nq] handle number of each query
 };
-hipError_t launch_coarse_tiles(const CoarseArgs &a, const MultiArgs &m, hipStream_t s);
+// fp32 queries -> zero padded rows and squared norms, plus the bookkeeping above
+hipError_t launch_prep_coarse(const float *q, int64_t nq, int d, int row_bytes, void *qs, float *qnorm,
+                              const QueryMeta &meta, const MultiArgs &m, hipStream_t s);
+
+// Centroid scoring of small query segments (16 centroids x `chunk` queries per workgroup).
+struct CentroidArgs {
+    const char *qs;      // prepared fp32 queries [nq][row_bytes]
+    const float *qnorm;  // [nq]
+    float *out;          // score of (query q, centroid c of q's handle) at out[q * stride + c]
+    uint32_t stride;
+    int row_bytes, metric;
+    int chunk;           // queries per workgroup: 16, 32, 48 or 64
+    uint32_t blk[PK_MAX_HANDLES + 1]; // first workgroup of handle a, [n] = all; a handle scored elsewhere owns none
+};
+hipError_t launch_centroid_scores(const CentroidArgs &a, const MultiArgs &m, hipStream_t s);
 
 struct WorklistArgs {
     const int32_t *probes;     // [nq][nprobe]; entries outside [0, nlist) are ignored

@@ -1,11 +1,10 @@
 // List scan (fine search) and small-batch centroid scoring (coarse search) for gfx950.
 //
 // Section 2.2 of the paper: the coarse step scores a query against every centroid, the
-// fine step against every vector of the probed clusters.  Both are "rows streamed from
-// HBM once, scored against a small group of queries", so one kernel family serves both: a
-// tile is one page of rows (list page or a slice of the centroid table) plus a group of
-// query slots.  Inserted vectors (Section 4.4's buffer) live in ordinary pages of the
-// list and are scored by the same tiles.
+// fine step against every vector of the probed clusters.  The fine step is "rows streamed
+// from HBM once, scored against a small group of queries": a tile is one page of a list
+// plus a group of query slots.  Inserted vectors (Section 4.4's buffer) live in ordinary
+// pages of the list and are scored by the same tiles.
 //
 // Mapping to CDNA4.  The rows are the streaming operand and go HBM -> registers directly
 // in MFMA operand layout; the queries come from LDS.  With A = queries (M = 16 slots) and
@@ -16,13 +15,15 @@
 // instruction) and feed them straight into v_mfma_f32_16x16x32_f16 (fp16 storage) or four
 // v_mfma_f32_16x16x4_f32 (fp32 storage), always with fp32 accumulation.
 //
-// Two kernels differ in how the queries reach LDS:
+// Two list-scan kernels differ in how the queries reach LDS:
 //   scan_kernel     the whole query group (up to 64 slots x full rows) sits in LDS and is
 //                   reused over a batch of tiles: least traffic when groups are small;
 //   scan_ks_kernel  the queries are staged 256 bytes of every row at a time (double
 //                   buffered), so LDS use is independent of the row length and up to 128
 //                   slots fit: for lists probed by many queries of the batch and for rows
 //                   too wide for the first kernel to keep several workgroups per CU.
+// centroid_scores_kernel is the coarse step for small query segments (the same operand
+// layout, no LDS staging); large segments go through the GEMM in pk_gemm.hip.
 #include "pk_internal.h"
 
 namespace pk {
@@ -551,7 +552,116 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 8))) voi
     }
 }
 
+// ------------------------------------------------------------------ centroid scoring, small batches
+
+// Coarse step (Section 2.2) for query segments too small to fill the GEMM's 128 x 128
+// tiles: inserts of a few vectors, search batches of tens of queries.  The whole centroid
+// table is a few MB, so latency, not bandwidth, sets the time: the work is cut fine.  A
+// workgroup scores 16 centroids against up to 16*MT queries; its 4 waves split the
+// contraction index, so each wave streams a quarter of every row (centroids and queries
+// alike come straight from global memory / L2 in MFMA operand layout, no LDS staging), and
+// the four partial accumulators meet in LDS.  Output: out[query * stride + centroid].
+template <int MT>
+__global__ __launch_bounds__(256) void centroid_scores_kernel(CentroidArgs a, MultiArgs m)
+{
+    __shared__ float s_red[4][MT][4][64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int ln = lane & 15, lg = lane >> 4;
+    int h = 0;
+    while (h + 1 < m.n && blockIdx.x >= a.blk[h + 1]) ++h;
+    const DevIndex &ix = *m.ix[h];
+    const uint32_t nblk = (uint32_t)ix.nlist_pad / 16u;
+    const uint32_t local = blockIdx.x - a.blk[h];
+    const uint32_t qc = local / nblk, cb = local - qc * nblk;
+    const uint32_t q0 = m.qlo[h] + qc * (uint32_t)(MT * 16);
+    const uint32_t left = m.qlo[h + 1] - q0;
+    const uint32_t qcnt = left < (uint32_t)(MT * 16) ? left : (uint32_t)(MT * 16);
+    const int mt_used = (int)((qcnt + 15u) >> 4);
+    const int row_bytes = a.row_bytes;
+    const int nit = row_bytes / kIterBytes;
+    const int per = (nit + 3) / 4;
+    const int it0 = wave * per, it1 = it0 + per < nit ? it0 + per : nit;
+
+    const char *xp = reinterpret_cast<const char *>(ix.cent) + (size_t)(cb * 16u + ln) * row_bytes + lg * 16;
+    const char *qp[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const uint32_t slot = (uint32_t)(mt * 16 + ln);
+        qp[mt] = slot < qcnt ? a.qs + (size_t)(q0 + slot) * row_bytes + lg * 16 : nullptr;
+    }
+    f32x4 acc[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    u32x4 xa[4], xb[4], qa[MT][4], qb[MT][4];
+#define PK_CLOAD(xbuf, qbuf, it)                                                                  \
+    _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4)                                              \
+    {                                                                                             \
+        xbuf[s4] = *reinterpret_cast<const u32x4 *>(xp + (size_t)(it) * kIterBytes + s4 * 64);    \
+        _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                         \
+        {                                                                                         \
+            qbuf[mt][s4] = u32x4{0u, 0u, 0u, 0u};                                                 \
+            if (mt < mt_used && qp[mt])                                                           \
+                qbuf[mt][s4] = *reinterpret_cast<const u32x4 *>(qp[mt] + (size_t)(it) * kIterBytes + s4 * 64); \
+        }                                                                                         \
+    }
+#define PK_CCOMPUTE(xbuf, qbuf)                                                                   \
+    _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                             \
+    {                                                                                             \
+        if (mt < mt_used) {                                                                       \
+            _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4) mfma_step<PK_F32>(acc[mt], qbuf[mt][s4], xbuf[s4]); \
+        }                                                                                         \
+    }
+    if (it0 < it1) { PK_CLOAD(xa, qa, it0) }
+    for (int it = it0; it < it1; it += 2) {
+        if (it + 1 < it1) { PK_CLOAD(xb, qb, it + 1) }
+        PK_CCOMPUTE(xa, qa)
+        if (it + 2 < it1) { PK_CLOAD(xa, qa, it + 2) }
+        if (it + 1 < it1) { PK_CCOMPUTE(xb, qb) }
+    }
+#undef PK_CLOAD
+#undef PK_CCOMPUTE
+    // lane (ln, lg) of a wave holds centroid cb*16 + ln against slots mt*16 + lg*4 + i
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) s_red[wave][mt][i][lane] = acc[mt][i];
+    __syncthreads();
+    const int i = wave; // after the barrier wave w adds up element i = w of every lane
+    const uint32_t c = cb * 16u + (uint32_t)ln;
+    float cn = 0.f;
+    if (a.metric == PK_METRIC_L2 && c < (uint32_t)ix.nlist) cn = ix.cnorm[c];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const uint32_t slot = (uint32_t)(mt * 16 + lg * 4 + i);
+        if (slot >= qcnt || c >= (uint32_t)ix.nlist) continue;
+        float v = (s_red[0][mt][i][lane] + s_red[1][mt][i][lane]) + (s_red[2][mt][i][lane] + s_red[3][mt][i][lane]);
+        if (a.metric == PK_METRIC_L2) v = fmaxf(cn - 2.f * v + a.qnorm[q0 + slot], 0.f);
+        a.out[(size_t)(q0 + slot) * a.stride + c] = v;
+    }
+}
+
 // ------------------------------------------------------------------------ host side
+
+template <int MT>
+static hipError_t launch_centroid_mt(const CentroidArgs &a, const MultiArgs &m, hipStream_t s)
+{
+    hipLaunchKernelGGL(centroid_scores_kernel<MT>, dim3(a.blk[m.n]), dim3(256), 0, s, a, m);
+    return hipGetLastError();
+}
+
+// a.chunk = queries per workgroup (16, 32, 48 or 64); a.blk as filled by the caller for that chunk
+hipError_t launch_centroid_scores(const CentroidArgs &a, const MultiArgs &m, hipStream_t s)
+{
+    if (a.row_bytes <= 0 || a.row_bytes % kIterBytes != 0) return hipErrorInvalidValue;
+    if (a.blk[m.n] == 0) return hipSuccess;
+    switch (a.chunk) {
+    case 16: return launch_centroid_mt<1>(a, m, s);
+    case 32: return launch_centroid_mt<2>(a, m, s);
+    case 48: return launch_centroid_mt<3>(a, m, s);
+    case 64: return launch_centroid_mt<4>(a, m, s);
+    default: return hipErrorInvalidValue;
+    }
+}
 
 int scan_lds_bytes(int row_bytes, int mq)
 {
@@ -627,18 +737,13 @@ static hipError_t launch_ks_mt(const ScanArgs &a, int grid, hipStream_t s)
     }
 }
 
-// waves_per_wg: 4 for list pages, 1 for the narrow tiles of the coarse pass
-hipError_t launch_scan(const ScanArgs &a, int waves_per_wg, int grid, hipStream_t s)
+// whole-group kernel: gated (fine search) when a.tau is set, else every value is written (threshold sampling)
+hipError_t launch_scan(const ScanArgs &a, int grid, hipStream_t s)
 {
     if (a.row_bytes <= 0 || a.row_bytes % kIterBytes != 0) return hipErrorInvalidValue;
     const bool gated = a.tau != nullptr;
-    if (gated && waves_per_wg != 4) return hipErrorInvalidValue;
-    if (a.storage == PK_F16) {
-        if (gated) return launch_mt<PK_F16, 4, true>(a, grid, s);
-        return waves_per_wg == 1 ? launch_mt<PK_F16, 1, false>(a, grid, s) : launch_mt<PK_F16, 4, false>(a, grid, s);
-    }
-    if (gated) return launch_mt<PK_F32, 4, true>(a, grid, s);
-    return waves_per_wg == 1 ? launch_mt<PK_F32, 1, false>(a, grid, s) : launch_mt<PK_F32, 4, false>(a, grid, s);
+    if (a.storage == PK_F16) return gated ? launch_mt<PK_F16, 4, true>(a, grid, s) : launch_mt<PK_F16, 4, false>(a, grid, s);
+    return gated ? launch_mt<PK_F32, 4, true>(a, grid, s) : launch_mt<PK_F32, 4, false>(a, grid, s);
 }
 
 // the sliced-query kernel (gated fine search only; fp32 rows are held to 32 slots)

@@ -66,8 +66,7 @@ __device__ uint32_t block_exscan(const uint32_t *in, uint32_t *out, uint32_t n, 
 
 // one workgroup per query: convert to the storage type, zero pad to row_bytes, squared norm
 // of the converted values (fp32 sum)
-__global__ __launch_bounds__(256) void prep_queries_kernel(const float *q, int d, int storage, int row_bytes, char *qs,
-                                                           float *qnorm)
+__device__ __forceinline__ void prep_row(const float *q, int d, int storage, int row_bytes, char *qs, float *qnorm)
 {
     __shared__ float s_part[4];
     const size_t row = blockIdx.x;
@@ -91,6 +90,28 @@ __global__ __launch_bounds__(256) void prep_queries_kernel(const float *q, int d
     if (threadIdx.x == 0) qnorm[row] = s_part[0] + s_part[1] + s_part[2] + s_part[3];
 }
 
+__global__ __launch_bounds__(256) void prep_queries_kernel(const float *q, int d, int storage, int row_bytes, char *qs,
+                                                           float *qnorm)
+{
+    prep_row(q, d, storage, row_bytes, qs, qnorm);
+}
+
+// the same for the coarse step (fp32), which also notes which handle each query belongs to
+// and where its row of centroid scores lies
+__global__ __launch_bounds__(256) void prep_coarse_kernel(const float *q, int d, int row_bytes, char *qs, float *qnorm,
+                                                          QueryMeta meta, MultiArgs m)
+{
+    prep_row(q, d, PK_F32, row_bytes, qs, qnorm);
+    if (threadIdx.x == 0) {
+        const uint32_t t = blockIdx.x;
+        int h = 0;
+        while (h + 1 < m.n && t >= m.qlo[h + 1]) ++h;
+        meta.cand_off[t] = t * meta.stride;
+        meta.cand_cnt[t] = (uint32_t)m.ix[h]->nlist;
+        meta.qagent[t] = (uint16_t)h;
+    }
+}
+
 hipError_t launch_prep_queries(const float *q, int64_t nq, int d, int storage, int row_bytes, void *qs, float *qnorm,
                                hipStream_t s)
 {
@@ -100,54 +121,12 @@ hipError_t launch_prep_queries(const float *q, int64_t nq, int d, int storage, i
     return hipGetLastError();
 }
 
-// ------------------------------------------------------------------ coarse tiles
-
-// Tiles of the coarse step: handle a's centroid table in slices of kCoarsePage rows, times
-// groups of mq of its queries.  Slots are the queries themselves (slot i = query i).
-__global__ void coarse_tiles_kernel(CoarseArgs a, MultiArgs m)
+hipError_t launch_prep_coarse(const float *q, int64_t nq, int d, int row_bytes, void *qs, float *qnorm,
+                              const QueryMeta &meta, const MultiArgs &m, hipStream_t s)
 {
-    const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
-    const uint32_t nq = m.qlo[m.n];
-    if (t < nq) {
-        int h = 0;
-        while (h + 1 < m.n && t >= m.qlo[h + 1]) ++h;
-        a.slot_query[t] = t;
-        a.slot_out[t] = t * a.stride;
-        a.cand_off[t] = t * a.stride;
-        a.cand_cnt[t] = (uint32_t)m.ix[h]->nlist;
-        a.qagent[t] = (uint16_t)h;
-    }
-    if (t == 0) {
-        a.scalars[0] = m.ctile[m.n];
-        a.scalars[1] = 0;
-        uint32_t g = m.ctile[m.n] / (uint32_t)(a.scan_grid * 4);
-        a.scalars[2] = g < 1 ? 1 : (g > 8 ? 8 : g);
-    }
-    if (t >= m.ctile[m.n]) return;
-    int h = 0;
-    while (h + 1 < m.n && t >= m.ctile[h + 1]) ++h;
-    const DevIndex &ix = *m.ix[h];
-    const uint32_t pages = (uint32_t)ix.nlist_pad / kCoarsePage;
-    const uint32_t local = t - m.ctile[h];
-    const uint32_t g = local / pages, p = local - g * pages;
-    const uint32_t nqa = m.qlo[h + 1] - m.qlo[h];
-    Tile tl;
-    tl.x = reinterpret_cast<const char *>(ix.cent) + (size_t)p * kCoarsePage * ix.dpad32 * 4;
-    tl.xn = ix.cnorm + (size_t)p * kCoarsePage;
-    tl.row0 = p * kCoarsePage;
-    tl.qbeg = m.qlo[h] + g * a.mq;
-    const uint32_t left = (uint32_t)ix.nlist - p * kCoarsePage;
-    tl.nrows = (uint16_t)(left < (uint32_t)kCoarsePage ? left : kCoarsePage);
-    const uint32_t ql = nqa - g * a.mq;
-    tl.qcnt = (uint16_t)(ql < (uint32_t)a.mq ? ql : a.mq);
-    tl.pad = 0;
-    a.tiles[t] = tl;
-}
-
-hipError_t launch_coarse_tiles(const CoarseArgs &a, const MultiArgs &m, hipStream_t s)
-{
-    const uint32_t n = m.ctile[m.n] > m.qlo[m.n] ? m.ctile[m.n] : m.qlo[m.n];
-    hipLaunchKernelGGL(coarse_tiles_kernel, dim3((n + 255) / 256 + 1), dim3(256), 0, s, a, m);
+    if (nq <= 0) return hipSuccess;
+    hipLaunchKernelGGL(prep_coarse_kernel, dim3((uint32_t)nq), dim3(256), 0, s, q, d, row_bytes, static_cast<char *>(qs),
+                       qnorm, meta, m);
     return hipGetLastError();
 }
 
