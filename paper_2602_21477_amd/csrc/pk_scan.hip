@@ -32,6 +32,15 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// Pointers taken out of a tile descriptor are generic pointers to the compiler, and loads
+// through them would be flat loads: those count on the LDS counter as well, so a wait for
+// an LDS read would also wait for the rows being prefetched.  These types say "global".
+typedef const char __attribute__((address_space(1))) *gbytes;
+typedef const float __attribute__((address_space(1))) *gfloats;
+typedef const u32x4 __attribute__((address_space(1))) *gvec4;
+__device__ __forceinline__ gbytes in_global(const char *p) { return (gbytes)p; }
+__device__ __forceinline__ gfloats in_global(const float *p) { return (gfloats)p; }
+
 // per-slot LDS arrays of the scan kernels: out, qn, thr, q, base, lo, inv, bmax
 constexpr int kScanSlotWords = 8;
 constexpr int kKsStride = kIterBytes + kQPadBytes; // LDS bytes per slot and staged slice
@@ -159,7 +168,7 @@ __device__ __forceinline__ void refresh_slot(const ScanArgs &a, const Slots &s, 
 // mt*16 + lg*4 + i.  Dense mode writes every value; gated mode emits the survivors.
 template <int MT, bool GATED>
 __device__ __forceinline__ void finish_block(const ScanArgs &a, const Slots &s, f32x4 (&acc)[MT][2], int rb, int ln, int lg,
-                                             int nrows, uint32_t qcnt, uint32_t row0, const float *txn)
+                                             int nrows, uint32_t qcnt, uint32_t row0, gfloats txn)
 {
     constexpr int MQ = MT * 16;
     const float worst = a.metric == PK_METRIC_IP ? -INFINITY : INFINITY;
@@ -303,23 +312,23 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(3, 8
     if (sc.t >= sc.ntiles) return;
     Tile cur = a.tiles[sc.t];
     while (sc.t < sc.ntiles) {
-        const char *tx = cur.x;
-        const float *txn = cur.xn;
+        const gbytes tx = in_global(cur.x);
+        const gfloats txn = in_global(cur.xn);
         const uint32_t row0 = cur.row0;
         const uint32_t qbeg = __builtin_amdgcn_readfirstlane(cur.qbeg);
         const uint32_t qcnt = __builtin_amdgcn_readfirstlane((uint32_t)cur.qcnt);
         const int nrows = __builtin_amdgcn_readfirstlane((int)cur.nrows);
 
         u32x4 xa[2][4], xb[2][4]; // two register buffers of one 256-byte slice of 32 rows each
-        const char *p0, *p1;
+        gbytes p0, p1;
 #define PK_ROWS(rb)                                                                               \
     p0 = tx + (size_t)((rb) * kRowBlock + ln) * row_bytes + lg * 16;                              \
     p1 = p0 + (size_t)16 * row_bytes;
 #define PK_LOAD(buf, it)                                                                          \
     _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4)                                              \
     {                                                                                             \
-        buf[0][s4] = *reinterpret_cast<const u32x4 *>(p0 + (size_t)(it) * kIterBytes + s4 * 64);  \
-        buf[1][s4] = *reinterpret_cast<const u32x4 *>(p1 + (size_t)(it) * kIterBytes + s4 * 64);  \
+        buf[0][s4] = *reinterpret_cast<gvec4>(p0 + (size_t)(it) * kIterBytes + s4 * 64);  \
+        buf[1][s4] = *reinterpret_cast<gvec4>(p1 + (size_t)(it) * kIterBytes + s4 * 64);  \
     }
 #define PK_COMPUTE(buf, it)                                                                       \
     _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                             \
@@ -438,8 +447,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 8))) voi
         const uint32_t tn = sc.peek(s_misc, next_end, next_fresh);
         const Tile nxt = a.tiles[tn < sc.ntiles ? tn : sc.ntiles - 1]; // in flight while this tile is scored
         {
-            const char *tx = cur.x;
-            const float *txn = cur.xn;
+            const gbytes tx = in_global(cur.x);
+            const gfloats txn = in_global(cur.xn);
             const uint32_t row0 = cur.row0;
             const uint32_t qbeg = __builtin_amdgcn_readfirstlane(cur.qbeg);
             const uint32_t qcnt = __builtin_amdgcn_readfirstlane((uint32_t)cur.qcnt);
@@ -470,8 +479,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 8))) voi
                 // a wave past the end of the page keeps in step (barriers) on the page's first rows
                 const bool active = rb * kRowBlock < nrows;
                 const int row_a = (active ? rb * kRowBlock : 0) + ln;
-                const char *p0 = tx + (size_t)row_a * row_bytes + lg * 16;
-                const char *p1 = p0 + (size_t)16 * row_bytes;
+                const gbytes p0 = tx + (size_t)row_a * row_bytes + lg * 16;
+                const gbytes p1 = p0 + (size_t)16 * row_bytes;
                 f32x4 acc[MT][2];
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
@@ -484,8 +493,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 8))) voi
 #define PK_LOAD(buf, it)                                                                          \
     _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4)                                              \
     {                                                                                             \
-        buf[0][s4] = *reinterpret_cast<const u32x4 *>(p0 + (size_t)(it) * kIterBytes + s4 * 64);  \
-        buf[1][s4] = *reinterpret_cast<const u32x4 *>(p1 + (size_t)(it) * kIterBytes + s4 * 64);  \
+        buf[0][s4] = *reinterpret_cast<gvec4>(p0 + (size_t)(it) * kIterBytes + s4 * 64);  \
+        buf[1][s4] = *reinterpret_cast<gvec4>(p1 + (size_t)(it) * kIterBytes + s4 * 64);  \
     }
 #define PK_QLOAD(it)                                                                              \
     _Pragma("unroll") for (int j = 0; j < QLOADS; ++j)                                            \
