@@ -1,4 +1,4 @@
-"""Compile libpancake.so (HIP, gfx950 only) in-tree.
+"""Compile libpancake.so and the read-pattern probe (HIP, gfx950 only) in-tree.
 
     python -m paper_2602_21477_amd.build
 """
@@ -12,6 +12,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpancake.so")
+PROBE_SRC = os.path.join(HERE, "read_pattern_probe.hip")  # measurement aid: the memory system's rate for the scan's load pattern
+PROBE = os.path.join(HERE, "read_pattern_probe.bin")
 SOURCES = ["pk_api.hip", "pk_scan.hip", "pk_select.hip", "pk_worklist.hip", "pk_index.hip", "pk_gemm.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -27,6 +29,10 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + err)
     if verbose and err.strip():
         print(err, file=sys.stderr)
+    r = subprocess.run(["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", PROBE_SRC, "-o", PROBE],
+                       capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed (read_pattern_probe):\n" + r.stderr)
     return LIB
 
 
