@@ -209,6 +209,51 @@ class Scenario:
                           f"vectors scanned per query; <= {scanned:.0f} per query); oracle build {build_s:.1f}s not "
                           f"included"}
 
+    def maintenance(self, extra_inserts, steps=20):
+        """Grow agent 0's lists by `extra_inserts` vectors (batches of 1024: delta pages open all over the
+        arena), then fold everything into contiguous extents in a fresh arena (pk_index_compact) and report
+        what the copy cost and what a search step costs before and after."""
+        torch, B, W, cfg = self.torch, self.B, self.W, self.cfg
+        ix = self.indexes[0]
+        done = 0
+        while done < extra_inserts:
+            m = min(1024, extra_inserts - done)
+            rows = np.concatenate([W.inserts(cfg, 100000 + (done + j) // 256, 256) for j in range(0, m, 256)])[:m]
+            try:
+                ix.insert(torch.from_numpy(rows).cuda())
+            except B.PancakeError as e:
+                if e.status != B.PK_ERR_NOMEM:
+                    raise
+                ix.add_arena(B.pk_arena_bytes(ix.cfg, 0, max(extra_inserts - done, 1024)))
+                continue
+            done += m
+
+        def ms_per_step():
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                self.step()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / steps * 1e3
+
+        before = ms_per_step()
+        st = ix.stats()
+        nbytes = B.pk_arena_bytes(ix.cfg, int(st.n_total), self.insert_m * (steps + 8) + 1024)
+        new_arena = torch.empty(nbytes, dtype=torch.uint8, device="cuda")  # allocated outside the timed call
+        page_bytes = (128 if ix.cfg.page_vecs == 0 else ix.cfg.page_vecs) * (self.row_bytes() + 12)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        B.pk_index_compact(ix.handle, new_arena)
+        dt = time.perf_counter() - t0
+        ix.arenas = [new_arena]
+        after = ms_per_step()
+        self.check_errors()
+        copied = int(st.pages_used) * page_bytes
+        return {"extra_inserts": extra_inserts, "n_total": int(st.n_total), "arenas_before": int(st.n_arenas),
+                "compaction_ms": dt * 1e3, "bytes_copied": copied,
+                "copy_GBps_read_plus_write": 2 * copied / dt / 1e9, "ms_per_step_before": before,
+                "ms_per_step_after": after}
+
     def close(self):
         for ix in self.indexes:
             ix.close()
@@ -307,6 +352,9 @@ def run(args):
         # baseline needs host data only
         out["cpu_baseline"] = sc.cpu_baseline()
         log(f"cpu baseline: {out['cpu_baseline']['value']:.1f} queries/s on {out['cpu_baseline']['cores']} threads")
+    if args.maintenance:
+        out["maintenance"] = sc.maintenance(args.maintenance)
+        log(f"maintenance: {out['maintenance']}")
     print(json.dumps(out), flush=True)
 
 
@@ -319,6 +367,9 @@ def main():
     ap.add_argument("--recall-queries", type=int, default=8)
     ap.add_argument("--no-recall", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--maintenance", type=int, default=0, metavar="N",
+                    help="after the timed steps: insert N more vectors, compact the index into a fresh arena "
+                         "(pk_index_compact) and report the cost (extra field, the headline is unchanged)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); run with --gpus 1.", file=sys.stderr)

@@ -115,6 +115,22 @@ int pk_index_build(const pk_config *cfg, const float *centroids, const float *ve
 int pk_index_add_arena(pk_index *index, void *arena, size_t arena_bytes, void *stream);
 
 /*
+ * Section 4.4, asynchronous cluster expansion (allocate room for the grown cluster, copy
+ * the old data and the insertion buffer into it, swap, release the old), done here for
+ * the whole index at once: every list is copied, in list order, into one contiguous extent
+ * of pages in `arena` (its delta pages folded in), and the index then lives in `arena`
+ * alone.  Positions inside a list are kept, so search results do not change; inserts go on
+ * as before (tail page first, then new delta pages).
+ *   arena   DEVICE, 256-byte aligned, caller-owned, must not overlap a current arena and
+ *           must stay allocated until pk_index_free or the next compaction
+ * Synchronises `stream` twice: to read the list lengths that fix the extents, and after the
+ * copy, so that on return the arenas the index had before are no longer referenced and may
+ * be freed or reused by the caller.  PK_ERR_NOMEM if `arena` cannot hold the index
+ * (pk_arena_bytes(cfg, n_total, reserve) is sufficient); the index is unchanged then.
+ */
+int pk_index_compact(pk_index *index, void *arena, size_t arena_bytes, void *stream);
+
+/*
  * Section 3.1 / Section 6.1 "IVF-Static" insert + Section 4.4 insertion buffer.
  * Each of the m vectors is assigned to its best centroid (same rule as the build) and
  * appended to the tail page of that list, opening a delta page when the tail is full.

@@ -21,7 +21,7 @@ PK_OK = 0
 PK_ERR_INVALID_ARG, PK_ERR_BAD_HANDLE, PK_ERR_DIM_MISMATCH, PK_ERR_NOMEM, PK_ERR_HIP, PK_ERR_UNSUPPORTED = (
     -1, -2, -3, -4, -5, -6)
 
-EXPORTS = ["pk_arena_bytes", "pk_index_build", "pk_index_add_arena", "pk_insert", "pk_insert_assigned", "pk_search",
+EXPORTS = ["pk_arena_bytes", "pk_index_build", "pk_index_add_arena", "pk_index_compact", "pk_insert", "pk_insert_assigned", "pk_search",
            "pk_search_multi", "pk_coarse", "pk_scan_probes", "pk_index_stats", "pk_list_lengths", "pk_profile_begin",
            "pk_profile_end", "pk_index_free", "pk_strerror"]
 
@@ -64,6 +64,7 @@ def lib():
         L.pk_arena_bytes.argtypes = [C.POINTER(pk_config), i64, i64]
         L.pk_index_build.argtypes = [C.POINTER(pk_config), vp, vp, vp, i64, vp, C.c_size_t, vp, C.POINTER(vp)]
         L.pk_index_add_arena.argtypes = [vp, vp, C.c_size_t, vp]
+        L.pk_index_compact.argtypes = [vp, vp, C.c_size_t, vp]
         L.pk_insert.argtypes = [vp, vp, vp, i64, vp, vp]
         L.pk_insert_assigned.argtypes = [vp, vp, vp, i64, vp, vp]
         L.pk_search.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
@@ -123,6 +124,11 @@ def pk_index_build(cfg: pk_config, centroids, vectors, ids, arena) -> int:
 def pk_index_add_arena(handle: int, arena):
     _check(lib().pk_index_add_arena(handle, _dev(arena, torch.uint8, "arena"), arena.numel(), _stream()),
            "pk_index_add_arena")
+
+
+def pk_index_compact(handle: int, arena):
+    _check(lib().pk_index_compact(handle, _dev(arena, torch.uint8, "arena"), arena.numel(), _stream()),
+           "pk_index_compact")
 
 
 def pk_insert(handle: int, vectors, ids=None, assigned_lists=None):
@@ -212,6 +218,12 @@ class Index:
         t = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
         pk_index_add_arena(self.handle, t)
         self.arenas.append(t)
+
+    def compact(self, nbytes: int):
+        """Moves the index into one new arena of nbytes; the old arena tensors are released."""
+        t = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        pk_index_compact(self.handle, t)
+        self.arenas = [t]
 
     def insert(self, vectors, ids=None, want_lists=False):
         out = torch.empty(vectors.shape[0], dtype=torch.int32, device=self.device) if want_lists else None

@@ -39,7 +39,8 @@ struct pk_index {
     DevIndex *dev;          // device copy, inside the first arena
     uint32_t pages_total;
     size_t arena_bytes;
-    std::vector<uint64_t> top_len; // [j] = total length of the j longest build-time lists
+    std::vector<uint64_t> top_len; // [j] = total length of the j longest lists when the layout was last fixed (build, compaction)
+    int64_t inserted_at_top;       // n_inserted at that moment
     int64_t n_total, n_inserted;
     // page accounting: last page counter read back, and how many vectors were inserted by then
     uint32_t pages_known;
@@ -126,7 +127,7 @@ uint32_t pages_used_ub(const pk_index *ix)
 uint64_t wq_ub(const pk_index *ix, int nprobe)
 {
     const int np = std::min(nprobe, ix->cfg.nlist);
-    return round_up(ix->top_len[np] + (uint64_t)ix->n_inserted + 15ull * np, 16);
+    return round_up(ix->top_len[np] + (uint64_t)(ix->n_inserted - ix->inserted_at_top) + 15ull * np, 16);
 }
 
 // Everything one launch sequence needs, carved out of the owner's workspace.
@@ -633,6 +634,39 @@ void place_arena(Arena &a, char *base, uint32_t first_page, uint32_t npages, con
     a.ids = c.take<int64_t>((size_t)npages * x.P);
 }
 
+// Lays the header of an index (centroid table, per-list tables, counters, device descriptor)
+// and one arena of pages out in `base`; fills the host descriptor D.  Nothing is written to
+// the device.
+void place_header(DevIndex &D, DevIndex **dev, uint32_t *pages_total, float **cent, float **cnorm, const pk_config *cfg,
+                  char *base, size_t arena_bytes, const Dims &x)
+{
+    Carver h{base, 0};
+    std::memset(&D, 0, sizeof(D));
+    *cent = h.take<float>((size_t)x.nlist_pad * x.dpad32);
+    *cnorm = h.take<float>(x.nlist_pad);
+    D.cent = *cent;
+    D.cnorm = *cnorm;
+    D.list_len = h.take<uint32_t>(cfg->nlist);
+    D.main_base = h.take<uint32_t>(cfg->nlist);
+    D.main_pages = h.take<uint32_t>(cfg->nlist);
+    D.dtab = h.take<uint32_t>((size_t)cfg->nlist * x.max_dp);
+    D.ctr = h.take<uint32_t>(16);
+    D.stats = h.take<unsigned long long>(8);
+    *dev = h.take<DevIndex>(1);
+    D.nlist = cfg->nlist;
+    D.nlist_pad = x.nlist_pad;
+    D.d = cfg->d;
+    D.dpad32 = x.dpad32;
+    D.P = x.P;
+    D.max_dp = x.max_dp;
+    D.metric = cfg->metric;
+    D.storage = cfg->storage;
+    D.row_bytes = x.row_bytes;
+    D.n_arenas = 1;
+    *pages_total = pages_in(arena_bytes - x.header, x);
+    place_arena(D.arenas[0], base + x.header, 0, *pages_total, x);
+}
+
 int snapshot_pages(pk_index *ix, hipStream_t s)
 {
     if (ix->ev_pending) {
@@ -807,33 +841,9 @@ int pk_index_build(const pk_config *cfg, const float *centroids, const float *ve
     if (hipEventCreateWithFlags(&ix->ev, hipEventDisableTiming) != hipSuccess) return fail(PK_ERR_HIP);
 
     // header of the first arena
-    char *base = static_cast<char *>(arena);
-    Carver h{base, 0};
     DevIndex &D = ix->host;
-    std::memset(&D, 0, sizeof(D));
-    float *cent = h.take<float>((size_t)x.nlist_pad * x.dpad32);
-    float *cnorm = h.take<float>(x.nlist_pad);
-    D.cent = cent;
-    D.cnorm = cnorm;
-    D.list_len = h.take<uint32_t>(cfg->nlist);
-    D.main_base = h.take<uint32_t>(cfg->nlist);
-    D.main_pages = h.take<uint32_t>(cfg->nlist);
-    D.dtab = h.take<uint32_t>((size_t)cfg->nlist * x.max_dp);
-    D.ctr = h.take<uint32_t>(16);
-    D.stats = h.take<unsigned long long>(8);
-    ix->dev = h.take<DevIndex>(1);
-    D.nlist = cfg->nlist;
-    D.nlist_pad = x.nlist_pad;
-    D.d = cfg->d;
-    D.dpad32 = x.dpad32;
-    D.P = x.P;
-    D.max_dp = x.max_dp;
-    D.metric = cfg->metric;
-    D.storage = cfg->storage;
-    D.row_bytes = x.row_bytes;
-    D.n_arenas = 1;
-    ix->pages_total = pages_in(arena_bytes - x.header, x);
-    place_arena(D.arenas[0], base + x.header, 0, ix->pages_total, x);
+    float *cent = nullptr, *cnorm = nullptr;
+    place_header(D, &ix->dev, &ix->pages_total, &cent, &cnorm, cfg, static_cast<char *>(arena), arena_bytes, x);
 
     if (hipMemcpyAsync(ix->dev, &D, sizeof(D), hipMemcpyHostToDevice, s) != hipSuccess) return fail(PK_ERR_HIP);
     if (launch_fill_u32(D.list_len, 0u, cfg->nlist, s) != hipSuccess ||
@@ -910,6 +920,7 @@ int pk_index_build(const pk_config *cfg, const float *centroids, const float *ve
     ix->n_total = n;
     ix->n_inserted = 0;
     ix->inserted_at_known = 0;
+    ix->inserted_at_top = 0;
     std::vector<uint32_t> sorted(cnt);
     std::sort(sorted.begin(), sorted.end(), [](uint32_t a, uint32_t b) { return a > b; });
     for (int j = 0; j < cfg->nlist; ++j) ix->top_len[j + 1] = ix->top_len[j] + sorted[j];
@@ -933,6 +944,62 @@ int pk_index_add_arena(pk_index *ix, void *arena, size_t arena_bytes, void *stre
     ix->arena_bytes += arena_bytes;
     PK_HIP(hipMemcpyAsync(ix->dev, &D, sizeof(D), hipMemcpyHostToDevice, s));
     PK_HIP(launch_fill_u32(D.ctr + 2, ix->pages_total, 1, s));
+    return PK_OK;
+}
+
+int pk_index_compact(pk_index *ix, void *arena, size_t arena_bytes, void *stream)
+{
+    if (!live(ix)) return PK_ERR_BAD_HANDLE;
+    if (!arena || reinterpret_cast<uintptr_t>(arena) % 256 != 0) return PK_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const pk_config *cfg = &ix->cfg;
+    const Dims x = dims_of(cfg);
+    if (arena_bytes < x.header + 1024 + x.page_stride) return PK_ERR_NOMEM;
+    for (int a = 0; a < ix->host.n_arenas; ++a)
+        if (ix->host.arenas[a].vec >= static_cast<char *>(arena) &&
+            ix->host.arenas[a].vec < static_cast<char *>(arena) + arena_bytes)
+            return PK_ERR_INVALID_ARG; // the new arena overlaps a current one
+    // exact list lengths decide the new extents
+    PK_HIP(hipStreamSynchronize(s));
+    PK_TRY(settle_pages(ix));
+    std::vector<uint32_t> len((size_t)cfg->nlist), mbase((size_t)cfg->nlist), mpages((size_t)cfg->nlist);
+    PK_HIP(hipMemcpy(len.data(), ix->host.list_len, len.size() * 4, hipMemcpyDeviceToHost));
+    uint64_t used = 0;
+    for (int l = 0; l < cfg->nlist; ++l) {
+        mbase[l] = (uint32_t)used;
+        mpages[l] = (len[l] + x.P - 1) / x.P;
+        used += mpages[l];
+    }
+    DevIndex N;
+    DevIndex *ndev = nullptr;
+    uint32_t npages = 0;
+    float *cent = nullptr, *cnorm = nullptr;
+    place_header(N, &ndev, &npages, &cent, &cnorm, cfg, static_cast<char *>(arena), arena_bytes, x);
+    if (used > npages) return PK_ERR_NOMEM;
+    const DevIndex &O = ix->host;
+    const uint32_t head[3] = {(uint32_t)used, 0u, npages};
+    PK_HIP(hipMemcpyAsync(ndev, &N, sizeof(N), hipMemcpyHostToDevice, s));
+    PK_HIP(hipMemcpyAsync(cent, O.cent, (size_t)x.nlist_pad * x.dpad32 * sizeof(float), hipMemcpyDeviceToDevice, s));
+    PK_HIP(hipMemcpyAsync(cnorm, O.cnorm, (size_t)x.nlist_pad * sizeof(float), hipMemcpyDeviceToDevice, s));
+    PK_HIP(hipMemcpyAsync(N.list_len, len.data(), len.size() * 4, hipMemcpyHostToDevice, s));
+    PK_HIP(hipMemcpyAsync(N.main_base, mbase.data(), mbase.size() * 4, hipMemcpyHostToDevice, s));
+    PK_HIP(hipMemcpyAsync(N.main_pages, mpages.data(), mpages.size() * 4, hipMemcpyHostToDevice, s));
+    PK_HIP(launch_fill_u32(N.dtab, 0xffffffffu, (size_t)cfg->nlist * x.max_dp, s));
+    PK_HIP(hipMemcpyAsync(N.ctr, O.ctr, 16 * sizeof(uint32_t), hipMemcpyDeviceToDevice, s)); // keeps the sticky error flags
+    PK_HIP(hipMemcpyAsync(N.ctr, head, 4, hipMemcpyHostToDevice, s));
+    PK_HIP(hipMemcpyAsync(N.ctr + 2, head + 2, 4, hipMemcpyHostToDevice, s));
+    PK_HIP(hipMemcpyAsync(N.stats, O.stats, 8 * sizeof(unsigned long long), hipMemcpyDeviceToDevice, s));
+    PK_HIP(launch_compact_pages(ix->dev, ndev, (uint32_t)used, s));
+    PK_HIP(hipStreamSynchronize(s)); // the old arenas are out of use from here on
+    ix->host = N;
+    ix->dev = ndev;
+    ix->pages_total = npages;
+    ix->arena_bytes = arena_bytes;
+    ix->pages_known = (uint32_t)used;
+    ix->inserted_at_known = ix->n_inserted;
+    ix->inserted_at_top = ix->n_inserted;
+    std::sort(len.begin(), len.end(), [](uint32_t a, uint32_t b) { return a > b; });
+    for (int j = 0; j < cfg->nlist; ++j) ix->top_len[j + 1] = ix->top_len[j] + len[j];
     return PK_OK;
 }
 

@@ -202,6 +202,56 @@ hipError_t launch_append(const DevIndex *ix, const float *x, const int64_t *ids,
 
 // probes[:, 0] of a top-1 coarse search -> assignment array (stride nprobe = 1 is the identity;
 // kept as a kernel so the copy stays on the stream)
+// ------------------------------------------------------------------ compaction
+
+// One workgroup per page of the new layout: page pg belongs to the list whose new extent
+// contains it; its rows, norms and ids are copied from wherever the old layout keeps that
+// logical page (build-time extent or delta page, any arena).  Positions inside a list do
+// not change.
+__global__ __launch_bounds__(256) void compact_pages_kernel(const DevIndex *srcp, const DevIndex *dstp)
+{
+    __shared__ uint32_t s_list;
+    const DevIndex &src = *srcp, &dst = *dstp;
+    const uint32_t pg = blockIdx.x;
+    if (threadIdx.x == 0) {
+        // last list whose extent starts at or before pg (extents are in list order; a list
+        // without pages shares its start with the next one and can never be the answer)
+        uint32_t lo = 0, hi = (uint32_t)dst.nlist;
+        while (hi - lo > 1) {
+            const uint32_t mid = (lo + hi) / 2;
+            if (dst.main_base[mid] <= pg) lo = mid;
+            else hi = mid;
+        }
+        s_list = lo;
+    }
+    __syncthreads();
+    const uint32_t l = s_list;
+    const uint32_t lp = pg - dst.main_base[l];
+    const uint32_t P = (uint32_t)dst.P;
+    const uint32_t len = dst.list_len[l];
+    if (lp >= dst.main_pages[l] || lp * P >= len) return;
+    const uint32_t nrows = len - lp * P < P ? len - lp * P : P;
+    const uint32_t opg = phys_page(src, l, lp);
+    const Arena &sa = arena_of(src, opg), &da = arena_of(dst, pg);
+    const size_t so = opg - sa.first_page, dn = pg - da.first_page;
+    const int row_bytes = dst.row_bytes;
+    const uint4 *sv = reinterpret_cast<const uint4 *>(sa.vec + so * P * (size_t)row_bytes);
+    uint4 *dv = reinterpret_cast<uint4 *>(da.vec + dn * P * (size_t)row_bytes);
+    const size_t nvec = (size_t)nrows * row_bytes / 16;
+    for (size_t i = threadIdx.x; i < nvec; i += blockDim.x) dv[i] = sv[i];
+    for (uint32_t i = threadIdx.x; i < nrows; i += blockDim.x) {
+        da.norm[dn * P + i] = sa.norm[so * P + i];
+        da.ids[dn * P + i] = sa.ids[so * P + i];
+    }
+}
+
+hipError_t launch_compact_pages(const DevIndex *src, const DevIndex *dst, uint32_t new_pages, hipStream_t s)
+{
+    if (new_pages == 0) return hipSuccess;
+    hipLaunchKernelGGL(compact_pages_kernel, dim3(new_pages), dim3(256), 0, s, src, dst);
+    return hipGetLastError();
+}
+
 __global__ void copy_i32_kernel(const int32_t *src, int32_t *dst, int64_t n)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;

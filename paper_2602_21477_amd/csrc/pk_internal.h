@@ -263,6 +263,8 @@ hipError_t launch_scatter_build(const DevIndex *ix, const float *x, const int64_
                                 int64_t n, int64_t id0, uint32_t *fill, hipStream_t s);
 hipError_t launch_store_centroids(const float *c, int nlist, int d, int dpad32, int nlist_pad, int metric,
                                   float *cent, float *cnorm, hipStream_t s);
+// copies every list into the contiguous extents of `dst` (dst's tables are already in place)
+hipError_t launch_compact_pages(const DevIndex *src, const DevIndex *dst, uint32_t new_pages, hipStream_t s);
 hipError_t launch_reserve(const DevIndex *ix, const int32_t *assign, int m, uint32_t *slots, int32_t *assigned_out,
                           hipStream_t s);
 hipError_t launch_append(const DevIndex *ix, const float *x, const int64_t *ids, const int32_t *assign,

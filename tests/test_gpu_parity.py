@@ -149,6 +149,52 @@ def test_batch_inserts_grow_delta_pages_and_match_rebuild(gpu_device):
         b.close()
 
 
+@pytest.mark.parametrize("storage,metric", [(F32, IP), (F16, L2)])
+def test_compaction_keeps_results_and_inserts_go_on(gpu_device, storage, metric):
+    """Delta pages folded into contiguous extents in a new arena: identical search output before
+    and after (positions inside a list do not move), oracle parity, then more inserts and another
+    compaction into a third arena."""
+    cfg = W.scaled(W.C1, n=5000)
+    x = W.vectors(cfg, 0, cfg.n)
+    cent = W.train_centroids(cfg, x)
+    extra = np.concatenate([W.inserts(cfg, b, 61) for b in range(30)])  # 1830 vectors
+    p = Pair(x, cent, metric, storage, page_vecs=32, insert_reserve=3000)
+    try:
+        for s in range(0, 20 * 61, 61):
+            p.insert_both(extra[s:s + 61], where=f"batch {s // 61}")
+        q = W.queries(cfg, 9, 96)
+        i0, v0 = p.gpu.search(dev(q), 10, 8)
+        before = p.gpu.stats()
+        lens = p.gpu.list_lengths()
+        assert before.pages_used == int(np.sum((lens + 31) // 32))
+        nbytes = B.pk_arena_bytes(p.gpu.cfg, int(before.n_total), 2000)
+        p.gpu.compact(nbytes)
+        after = p.gpu.stats()
+        assert after.n_arenas == 1 and after.n_total == before.n_total and after.n_inserted == before.n_inserted
+        assert after.pages_used == before.pages_used and after.device_error == 0 and after.arena_bytes == nbytes
+        assert np.array_equal(p.gpu.list_lengths(), lens)
+        i1, v1 = p.gpu.search(dev(q), 10, 8)
+        assert torch.equal(i0, i1) and torch.equal(v0, v1)
+        p.check_search(q, 10, 8, where="after compaction")
+        for s in range(20 * 61, 30 * 61, 61):
+            p.insert_both(extra[s:s + 61], where=f"batch {s // 61} after compaction")
+        p.check_search(q, 10, 8, where="inserts after compaction")
+        assert np.array_equal(p.gpu.list_lengths(), p.orc.list_lengths())
+        i2, v2 = p.gpu.search(dev(q), 10, 8)
+        p.gpu.compact(B.pk_arena_bytes(p.gpu.cfg, int(p.gpu.stats().n_total), 0))
+        i3, v3 = p.gpu.search(dev(q), 10, 8)
+        assert torch.equal(i2, i3) and torch.equal(v2, v3)
+        # too small an arena: refused, index untouched
+        small = torch.empty(1 << 16, dtype=torch.uint8, device="cuda")
+        with pytest.raises(B.PancakeError) as e:
+            B.pk_index_compact(p.gpu.handle, small)
+        assert e.value.status == B.PK_ERR_NOMEM
+        i4, _ = p.gpu.search(dev(q), 10, 8)
+        assert torch.equal(i3, i4)
+    finally:
+        p.close()
+
+
 def test_ragged_shapes_padding_and_user_ids(gpu_device):
     """d not a multiple of the load width, nlist not a multiple of the coarse tile, empty lists,
     fewer candidates than k, arbitrary int64 ids."""
