@@ -254,6 +254,27 @@ class Scenario:
                 "copy_GBps_read_plus_write": 2 * copied / dt / 1e9, "ms_per_step_before": before,
                 "ms_per_step_after": after}
 
+    def training(self, iters):
+        """pk_kmeans on the workload's own training sample (the rows and initial centroids its index was
+        trained from on the host): time per Lloyd iteration and the rate of the assignment GEMM."""
+        torch, B, W, cfg, dat = self.torch, self.B, self.W, self.cfg, self.datas[0]
+        rows = W.train_rows(cfg, dat.n)
+        xs = torch.from_numpy(np.ascontiguousarray(dat.x[rows])).cuda()
+        init = W.init_rows(cfg, len(rows))
+        c0 = xs[torch.from_numpy(init).cuda()].contiguous()
+        c = c0.clone()
+        B.pk_kmeans(xs, c, 1)  # warm-up: workspace, code objects
+        c = c0.clone()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        inertia = B.pk_kmeans(xs, c, iters)
+        dt = time.perf_counter() - t0
+        flops = 2.0 * len(rows) * cfg.nlist * cfg.d
+        return {"n": int(len(rows)), "d": cfg.d, "nlist": cfg.nlist, "iters": iters, "ms_per_iter": dt / iters * 1e3,
+                "assignment_TFLOPs_incl_update": flops * iters / dt / 1e12,
+                "frac_of_fp32_mfma_peak": flops * iters / dt / 1e12 / 157.3,
+                "inertia_first": inertia[0], "inertia_last": inertia[-1]}
+
     def close(self):
         for ix in self.indexes:
             ix.close()
@@ -352,6 +373,9 @@ def run(args):
         # baseline needs host data only
         out["cpu_baseline"] = sc.cpu_baseline()
         log(f"cpu baseline: {out['cpu_baseline']['value']:.1f} queries/s on {out['cpu_baseline']['cores']} threads")
+    if args.train:
+        out["training"] = sc.training(args.train)
+        log(f"training: {out['training']}")
     if args.maintenance:
         out["maintenance"] = sc.maintenance(args.maintenance)
         log(f"maintenance: {out['maintenance']}")
@@ -367,6 +391,9 @@ def main():
     ap.add_argument("--recall-queries", type=int, default=8)
     ap.add_argument("--no-recall", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--train", type=int, default=0, metavar="ITERS",
+                    help="also run ITERS Lloyd iterations of pk_kmeans on the workload's training sample and report "
+                         "the time per iteration (extra field)")
     ap.add_argument("--maintenance", type=int, default=0, metavar="N",
                     help="after the timed steps: insert N more vectors, compact the index into a fresh arena "
                          "(pk_index_compact) and report the cost (extra field, the headline is unchanged)")

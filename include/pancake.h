@@ -115,6 +115,24 @@ int pk_index_build(const pk_config *cfg, const float *centroids, const float *ve
 int pk_index_add_arena(pk_index *index, void *arena, size_t arena_bytes, void *stream);
 
 /*
+ * Index training on the device (Section 2.2: the clusters of an IVF index come from a
+ * k-means over the data; Section 4.4 / 6.1, the IVF-Split variant, re-clusters with a light
+ * k-means on the GPU).  `iters` Lloyd iterations under squared L2: every vector goes to its
+ * nearest centroid (ties to the lower cluster number: the coarse search with nprobe = 1),
+ * every cluster that has members moves to their mean (summed in float64), a cluster without
+ * members keeps its centroid.
+ *   vectors      DEVICE [n, d] float32
+ *   centroids    DEVICE [nlist, d] float32: initial centroids on entry, result on return
+ *   assign_out   DEVICE [n] int32 or NULL: the assignment of the last iteration (made with
+ *                the centroids that iteration started from)
+ *   inertia_out  HOST [iters] float64 or NULL: the sum of squared distances measured by the
+ *                assignment step of each iteration
+ * Allocates and frees its own scratch memory; synchronises `stream` before returning.
+ */
+int pk_kmeans(const float *vectors, int64_t n, int32_t d, int32_t nlist, int32_t iters, float *centroids,
+              int32_t *assign_out, double *inertia_out, void *stream);
+
+/*
  * Section 4.4, asynchronous cluster expansion (allocate room for the grown cluster, copy
  * the old data and the insertion buffer into it, swap, release the old), done here for
  * the whole index at once: every list is copied, in list order, into one contiguous extent

@@ -21,7 +21,7 @@ PK_OK = 0
 PK_ERR_INVALID_ARG, PK_ERR_BAD_HANDLE, PK_ERR_DIM_MISMATCH, PK_ERR_NOMEM, PK_ERR_HIP, PK_ERR_UNSUPPORTED = (
     -1, -2, -3, -4, -5, -6)
 
-EXPORTS = ["pk_arena_bytes", "pk_index_build", "pk_index_add_arena", "pk_index_compact", "pk_insert", "pk_insert_assigned", "pk_search",
+EXPORTS = ["pk_arena_bytes", "pk_index_build", "pk_index_add_arena", "pk_index_compact", "pk_kmeans", "pk_insert", "pk_insert_assigned", "pk_search",
            "pk_search_multi", "pk_coarse", "pk_scan_probes", "pk_index_stats", "pk_list_lengths", "pk_profile_begin",
            "pk_profile_end", "pk_index_free", "pk_strerror"]
 
@@ -65,6 +65,7 @@ def lib():
         L.pk_index_build.argtypes = [C.POINTER(pk_config), vp, vp, vp, i64, vp, C.c_size_t, vp, C.POINTER(vp)]
         L.pk_index_add_arena.argtypes = [vp, vp, C.c_size_t, vp]
         L.pk_index_compact.argtypes = [vp, vp, C.c_size_t, vp]
+        L.pk_kmeans.argtypes = [vp, i64, i32, i32, i32, vp, vp, C.POINTER(C.c_double), vp]
         L.pk_insert.argtypes = [vp, vp, vp, i64, vp, vp]
         L.pk_insert_assigned.argtypes = [vp, vp, vp, i64, vp, vp]
         L.pk_search.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
@@ -124,6 +125,16 @@ def pk_index_build(cfg: pk_config, centroids, vectors, ids, arena) -> int:
 def pk_index_add_arena(handle: int, arena):
     _check(lib().pk_index_add_arena(handle, _dev(arena, torch.uint8, "arena"), arena.numel(), _stream()),
            "pk_index_add_arena")
+
+
+def pk_kmeans(vectors, centroids, iters: int, assign_out=None):
+    """Lloyd iterations in place on `centroids`; returns the per-iteration objective (host floats)."""
+    n, d = vectors.shape
+    inertia = (C.c_double * iters)()
+    _check(lib().pk_kmeans(_dev(vectors, torch.float32, "vectors"), n, d, centroids.shape[0], iters,
+                           _dev(centroids, torch.float32, "centroids"), _dev(assign_out, torch.int32, "assign_out"),
+                           inertia, _stream()), "pk_kmeans")
+    return [float(v) for v in inertia]
 
 
 def pk_index_compact(handle: int, arena):

@@ -14,7 +14,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpancake.so")
 PROBE_SRC = os.path.join(HERE, "read_pattern_probe.hip")  # measurement aid: the memory system's rate for the scan's load pattern
 PROBE = os.path.join(HERE, "read_pattern_probe.bin")
-SOURCES = ["pk_api.hip", "pk_scan.hip", "pk_select.hip", "pk_worklist.hip", "pk_index.hip", "pk_gemm.hip"]
+SOURCES = ["pk_api.hip", "pk_scan.hip", "pk_select.hip", "pk_worklist.hip", "pk_index.hip", "pk_gemm.hip", "pk_kmeans.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]

@@ -947,6 +947,77 @@ int pk_index_add_arena(pk_index *ix, void *arena, size_t arena_bytes, void *stre
     return PK_OK;
 }
 
+int pk_kmeans(const float *vectors, int64_t n, int32_t d, int32_t nlist, int32_t iters, float *centroids,
+              int32_t *assign_out, double *inertia_out, void *stream)
+{
+    if (!vectors || !centroids || n < 1 || nlist < 1 || iters < 1) return PK_ERR_INVALID_ARG;
+    if (d < 1) return PK_ERR_INVALID_ARG;
+    if (d > PK_MAX_DIM || n > 0x7fffffffll) return PK_ERR_UNSUPPORTED;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // the assignment step is a top-1 coarse search under L2: an index without vectors carries the centroid table
+    pk_config cfg{d, nlist, PK_METRIC_L2, PK_F32, 32, 1};
+    const size_t abytes = pk_arena_bytes(&cfg, 0, 0);
+    char *scratch = nullptr;
+    const size_t nl4 = round_up((size_t)nlist * 4, 256), n4 = round_up((size_t)n * 4, 256);
+    const size_t sbytes = round_up(abytes, 256) + 3 * nl4 + 2 * n4 + round_up((size_t)iters * 8, 256);
+    if (hipMalloc(reinterpret_cast<void **>(&scratch), sbytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return PK_ERR_NOMEM;
+    }
+    pk_index *ix = nullptr;
+    int rc = pk_index_build(&cfg, centroids, nullptr, nullptr, 0, scratch, abytes, stream, &ix);
+    if (rc != PK_OK) {
+        (void)hipFree(scratch);
+        return rc;
+    }
+    KmeansArgs ka{};
+    char *p = scratch + round_up(abytes, 256);
+    ka.cnt = reinterpret_cast<uint32_t *>(p);
+    ka.start = reinterpret_cast<uint32_t *>(p + nl4);
+    ka.fill = reinterpret_cast<uint32_t *>(p + 2 * nl4);
+    ka.members = reinterpret_cast<uint32_t *>(p + 3 * nl4);
+    int32_t *assign = reinterpret_cast<int32_t *>(p + 3 * nl4 + n4);
+    double *inertia = reinterpret_cast<double *>(p + 3 * nl4 + 2 * n4);
+    ka.x = vectors;
+    ka.assign = assign;
+    ka.n = n;
+    ka.d = d;
+    ka.nlist = nlist;
+    ka.centroids = centroids;
+    pk_index *hs[1] = {ix};
+    auto run = [&]() -> int {
+        for (int it = 0; it < iters; ++it) {
+            if (it > 0)
+                PK_HIP(launch_store_centroids(centroids, nlist, d, ix->dpad32, ix->nlist_pad, PK_METRIC_L2,
+                                              const_cast<float *>(ix->host.cent), const_cast<float *>(ix->host.cnorm), s));
+            for (int64_t i0 = 0; i0 < n; i0 += kBuildChunk) {
+                const int64_t mc = std::min<int64_t>(kBuildChunk, n - i0);
+                const uint32_t qlo[2] = {0, (uint32_t)mc};
+                Plan pl;
+                PK_TRY(make_plan(pl, hs, 1, qlo, mc, 1, 1, true, false));
+                PK_TRY(ensure_ws(ix, pl.bytes, s));
+                carve(pl, ix->ws, ix);
+                MultiArgs mm;
+                fill_multi(mm, hs, 1, qlo);
+                PK_TRY(run_coarse(pl, mm, hs, vectors + (size_t)i0 * d, s));
+                PK_HIP(launch_copy_i32(pl.probes, assign + i0, mc, s));
+            }
+            ka.inertia = inertia + it;
+            PK_HIP(launch_kmeans_update(ka, s));
+        }
+        if (assign_out) PK_HIP(hipMemcpyAsync(assign_out, assign, (size_t)n * 4, hipMemcpyDeviceToDevice, s));
+        if (inertia_out)
+            PK_HIP(hipMemcpyAsync(inertia_out, inertia, (size_t)iters * 8, hipMemcpyDeviceToHost, s));
+        PK_HIP(hipStreamSynchronize(s));
+        return PK_OK;
+    };
+    rc = run();
+    if (rc != PK_OK) (void)hipStreamSynchronize(s);
+    destroy(ix);
+    (void)hipFree(scratch);
+    return rc;
+}
+
 int pk_index_compact(pk_index *ix, void *arena, size_t arena_bytes, void *stream)
 {
     if (!live(ix)) return PK_ERR_BAD_HANDLE;

@@ -95,6 +95,38 @@ __device__ __forceinline__ uint32_t bucket_of(float v, float lo, float inv, int 
     return (uint32_t)t;
 }
 
+// exclusive scan of in[0,n) into out[0,n) by one workgroup of 1024 threads; returns the total
+__device__ __forceinline__ uint32_t block_exscan(const uint32_t *in, uint32_t *out, uint32_t n, uint32_t *s_wave /*[17]*/)
+{
+    uint32_t carry = 0;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    for (uint32_t base = 0; base < n; base += blockDim.x) {
+        const uint32_t i = base + threadIdx.x;
+        const uint32_t v = i < n ? in[i] : 0u;
+        uint32_t x = v;
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t y = __shfl_up(x, off);
+            if (lane >= off) x += y;
+        }
+        if (lane == 63) s_wave[wave] = x;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t acc = 0;
+            for (int w = 0; w < nwaves; ++w) {
+                const uint32_t t = s_wave[w];
+                s_wave[w] = acc;
+                acc += t;
+            }
+            s_wave[16] = acc;
+        }
+        __syncthreads();
+        if (i < n) out[i] = carry + s_wave[wave] + x - v;
+        carry += s_wave[16];
+        __syncthreads();
+    }
+    return carry;
+}
+
 // One unit of scan work: one page of rows against one group of query slots.
 struct Tile {
     const char *x;    // first row of the page
@@ -265,6 +297,18 @@ hipError_t launch_store_centroids(const float *c, int nlist, int d, int dpad32, 
                                   float *cent, float *cnorm, hipStream_t s);
 // copies every list into the contiguous extents of `dst` (dst's tables are already in place)
 hipError_t launch_compact_pages(const DevIndex *src, const DevIndex *dst, uint32_t new_pages, hipStream_t s);
+// k-means update step (Lloyd): members of every cluster gathered, then one workgroup per cluster
+struct KmeansArgs {
+    const float *x;        // [n][d] training rows
+    const int32_t *assign; // [n] cluster of each row
+    int64_t n;
+    int d, nlist;
+    uint32_t *cnt, *start, *fill; // [nlist] each (scratch)
+    uint32_t *members;     // [n] row numbers in cluster-major order (scratch)
+    float *centroids;      // [nlist][d] in: centroids the assignment used; out: means of the members
+    double *inertia;       // one word: receives the sum of squared distances of the assignment
+};
+hipError_t launch_kmeans_update(const KmeansArgs &a, hipStream_t s);
 hipError_t launch_reserve(const DevIndex *ix, const int32_t *assign, int m, uint32_t *slots, int32_t *assigned_out,
                           hipStream_t s);
 hipError_t launch_append(const DevIndex *ix, const float *x, const int64_t *ids, const int32_t *assign,

@@ -30,38 +30,6 @@ hipError_t launch_fill_u32(uint32_t *p, uint32_t v, size_t n, hipStream_t s)
     return hipGetLastError();
 }
 
-// exclusive scan of in[0,n) into out[0,n) by one workgroup of 1024 threads; returns the total
-__device__ uint32_t block_exscan(const uint32_t *in, uint32_t *out, uint32_t n, uint32_t *s_wave /*[17]*/)
-{
-    uint32_t carry = 0;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
-    for (uint32_t base = 0; base < n; base += blockDim.x) {
-        const uint32_t i = base + threadIdx.x;
-        const uint32_t v = i < n ? in[i] : 0u;
-        uint32_t x = v;
-        for (int off = 1; off < 64; off <<= 1) {
-            const uint32_t y = __shfl_up(x, off);
-            if (lane >= off) x += y;
-        }
-        if (lane == 63) s_wave[wave] = x;
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            uint32_t acc = 0;
-            for (int w = 0; w < nwaves; ++w) {
-                const uint32_t t = s_wave[w];
-                s_wave[w] = acc;
-                acc += t;
-            }
-            s_wave[16] = acc;
-        }
-        __syncthreads();
-        if (i < n) out[i] = carry + s_wave[wave] + x - v;
-        carry += s_wave[16];
-        __syncthreads();
-    }
-    return carry;
-}
-
 // ------------------------------------------------------------ query preparation
 
 // one workgroup per query: convert to the storage type, zero pad to row_bytes, squared norm

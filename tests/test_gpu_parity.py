@@ -195,6 +195,64 @@ def test_compaction_keeps_results_and_inserts_go_on(gpu_device, storage, metric)
         p.close()
 
 
+def _sq_dists(x, c):
+    x64, c64 = x.astype(np.float64), c.astype(np.float64)
+    return (x64 ** 2).sum(1)[:, None] - 2.0 * x64 @ c64.T + (c64 ** 2).sum(1)[None, :]
+
+
+def test_kmeans_one_iteration_matches_oracle(gpu_device):
+    """Lloyd step by step: the assignment is the oracle's argmin outside near-ties, the new centroids are
+    the float64 means of the members the GPU chose, the objective is the float64 sum over that assignment,
+    a cluster without members keeps its centroid."""
+    cfg = W.scaled(W.C1, n=20000)  # 20000 x 128: two assignment chunks, the second one ragged
+    x = W.vectors(cfg, 0, cfg.n)
+    rows = W.init_rows(cfg, cfg.n)[:64].copy()
+    rows[63] = rows[5]  # a duplicate initial centroid: ties go to the lower number, cluster 63 stays empty
+    c0 = x[rows]
+    oc, oin, oas = oracle.kmeans(x, 64, 1, rows)
+    cg = dev(c0)
+    ag = torch.empty(cfg.n, dtype=torch.int32, device="cuda")
+    inertia = B.pk_kmeans(dev(x), cg, 1, ag)
+    a, c1 = ag.cpu().numpy(), cg.cpu().numpy()
+    d0 = _sq_dists(x, c0)
+    diff = np.nonzero(a != oas)[0]
+    assert len(diff) <= 0.001 * cfg.n
+    for i in diff:  # a flip is legitimate only between near-tied centroids
+        assert abs(d0[i, a[i]] - d0[i, oas[i]]) <= 1e-4 * (d0[i, oas[i]] + 2.0), (i, a[i], oas[i])
+    assert not np.any(a == 63) and np.array_equal(c1[63], c0[63])
+    for l in range(64):
+        m = x[a == l].astype(np.float64)
+        want = m.mean(0) if len(m) else c0[l].astype(np.float64)
+        np.testing.assert_allclose(c1[l], want, rtol=2e-6, atol=1e-7, err_msg=f"cluster {l}")
+    np.testing.assert_allclose(inertia[0], d0[np.arange(cfg.n), a].sum(), rtol=1e-9)
+    if len(diff) == 0:
+        np.testing.assert_allclose(c1, oc, rtol=2e-6, atol=1e-7)
+        np.testing.assert_allclose(inertia[0], oin[0], rtol=1e-9)
+
+
+def test_kmeans_training_run_tracks_oracle(gpu_device):
+    """Ten iterations: the objective never goes up, ends where the oracle's ends (a flipped near-tie
+    moves single points, not the solution), and an index built on the trained centroids searches like
+    one built on the oracle's."""
+    cfg = W.scaled(W.C1, n=12000)
+    x = W.vectors(cfg, 0, cfg.n)
+    rows = W.init_rows(cfg, cfg.n)[:64]
+    oc, oin, _ = oracle.kmeans(x, 64, 10, rows)
+    cg = dev(x[rows])
+    inertia = B.pk_kmeans(dev(x), cg, 10)
+    assert all(b <= a * (1 + 1e-12) for a, b in zip(inertia, inertia[1:]))
+    np.testing.assert_allclose(inertia[0], oin[0], rtol=1e-6)
+    np.testing.assert_allclose(inertia[-1], oin[-1], rtol=5e-3)
+    c = cg.cpu().numpy()
+    close = np.isclose(c, oc, rtol=1e-3, atol=1e-4).all(1)
+    assert close.mean() >= 0.8, close.mean()
+    p = Pair(x, c, IP, F32)
+    try:
+        p.check_search(W.queries(cfg, 3, 64), 10, 8, where="index on GPU-trained centroids")
+    finally:
+        p.close()
+
+
 def test_ragged_shapes_padding_and_user_ids(gpu_device):
     """d not a multiple of the load width, nlist not a multiple of the coarse tile, empty lists,
     fewer candidates than k, arbitrary int64 ids."""
