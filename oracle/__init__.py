@@ -45,6 +45,8 @@ def lib():
         L.orc_search.argtypes = [vp, vp, i64, i32, i32, vp, vp]
         L.orc_search_multi.argtypes = [vp, i32, vp, vp, i32, i32, vp, vp]
         L.orc_bruteforce.argtypes = [vp, vp, i64, i32, i32, vp, i64, i32, vp, vp]
+        L.orc_union_probes.argtypes = [vp, i32, vp, i64, i32, i32, vp, vp, vp, vp]
+        L.orc_search_union.argtypes = [vp, i32, vp, i64, i32, i32, vp, vp, vp]
         L.orc_pair_values.argtypes = [vp, vp, i64, i32, i32, vp]
         L.orc_kmeans.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp, vp]
         L.orc_num_threads.restype = i32
@@ -164,6 +166,26 @@ def search_multi(indexes, q_offsets, q, k: int, nprobe: int):
     rc = lib().orc_search_multi(hs, len(indexes), _ptr(offs), _ptr(q), k, nprobe, _ptr(ids), _ptr(val))
     assert rc == 0
     return ids, val
+
+
+def search_union(indexes, q, k: int, nprobe: int, probes=None):
+    """Every query searched in every index of the scope, results merged (Section 3.2); probes, if given,
+    are [n_indexes, nq, nprobe].  Returns (source position, ids, values)."""
+    d = indexes[0].d
+    q = _f32(q).reshape(-1, d)
+    hs = (C.c_void_p * len(indexes))(*[ix._h for ix in indexes])
+    src = np.empty((q.shape[0], k), dtype=np.int32)
+    ids = np.empty((q.shape[0], k), dtype=np.int64)
+    val = np.empty((q.shape[0], k), dtype=np.float64)
+    if probes is None:
+        rc = lib().orc_search_union(hs, len(indexes), _ptr(q), q.shape[0], k, nprobe, _ptr(src), _ptr(ids), _ptr(val))
+    else:
+        probes = np.ascontiguousarray(probes, dtype=np.int32)
+        assert probes.shape == (len(indexes), q.shape[0], nprobe)
+        rc = lib().orc_union_probes(hs, len(indexes), _ptr(q), q.shape[0], k, nprobe, _ptr(probes), _ptr(src),
+                                    _ptr(ids), _ptr(val))
+    assert rc == 0
+    return src, ids, val
 
 
 def bruteforce(x, q, k: int, metric: int, ids=None):

@@ -386,6 +386,99 @@ int orc_search_multi(orc_index *const *handles, int n_handles, const int64_t *q_
 }
 
 /*
+ * Search over a scope of several memories (Section 3.2: every agent keeps its own
+ * index, a request names the agents whose memories it may read, each of their indexes
+ * is searched and the results are merged).  Every query is searched in every handle
+ * (orc_scan_probes with that handle's probe lists, probes[h][i][r]); of the union of
+ * the per-handle results the k best are returned, equal values ordered by the handle's
+ * position in the scope, then by id.  src_out[i][j] is that position (-1 for padding).
+ */
+typedef struct {
+    double v;
+    int src;
+    int64_t id;
+} orc_ucand;
+
+static int ucand_cmp(const void *pa, const void *pb)
+{
+    const orc_ucand *a = (const orc_ucand *)pa, *b = (const orc_ucand *)pb;
+    if (a->v != b->v) {
+        int a_first = g_sort_metric == ORC_IP ? (a->v > b->v) : (a->v < b->v);
+        return a_first ? -1 : 1;
+    }
+    if (a->src != b->src) return a->src < b->src ? -1 : 1;
+    if (a->id != b->id) return a->id < b->id ? -1 : 1;
+    return 0;
+}
+
+int orc_union_probes(orc_index *const *handles, int n_handles, const float *q, int64_t nq, int k, int nprobe,
+                     const int32_t *probes, int32_t *src_out, int64_t *ids_out, double *val_out)
+{
+    if (!handles || n_handles < 1 || !q || !probes || k < 1 || nq < 0) return -1;
+    const int metric = handles[0]->metric, d = handles[0]->d;
+    for (int h = 0; h < n_handles; ++h)
+        if (!handles[h] || handles[h]->metric != metric || handles[h]->d != d) return -1;
+    const size_t per = (size_t)(nq > 0 ? nq : 1) * k;
+    int64_t *ids = (int64_t *)malloc(sizeof(int64_t) * per * n_handles);
+    double *val = (double *)malloc(sizeof(double) * per * n_handles);
+    if (!ids || !val) return -1;
+    for (int h = 0; h < n_handles; ++h) {
+        int rc = orc_scan_probes(handles[h], q, nq, k, nprobe, probes + (size_t)h * nq * nprobe, ids + per * h,
+                                 val + per * h);
+        if (rc) return rc;
+    }
+    orc_ucand *c = (orc_ucand *)malloc(sizeof(orc_ucand) * (size_t)n_handles * k);
+    if (!c) return -1;
+    for (int64_t i = 0; i < nq; ++i) {
+        int64_t m = 0;
+        for (int h = 0; h < n_handles; ++h)
+            for (int j = 0; j < k; ++j) {
+                const size_t at = per * h + (size_t)i * k + j;
+                if (ids[at] < 0) continue; /* padding of a handle with fewer than k candidates */
+                c[m].v = val[at];
+                c[m].src = h;
+                c[m].id = ids[at];
+                ++m;
+            }
+        g_sort_metric = metric;
+        qsort(c, (size_t)m, sizeof(orc_ucand), ucand_cmp);
+        for (int j = 0; j < k; ++j) {
+            const size_t at = (size_t)i * k + j;
+            if (j < m) {
+                src_out[at] = c[j].src;
+                ids_out[at] = c[j].id;
+                val_out[at] = c[j].v;
+            } else {
+                src_out[at] = -1;
+                ids_out[at] = -1;
+                val_out[at] = metric == ORC_IP ? -INFINITY : INFINITY;
+            }
+        }
+    }
+    free(c);
+    free(ids);
+    free(val);
+    return 0;
+}
+
+/* the same with each handle's own coarse search (orc_coarse) */
+int orc_search_union(orc_index *const *handles, int n_handles, const float *q, int64_t nq, int k, int nprobe,
+                     int32_t *src_out, int64_t *ids_out, double *val_out)
+{
+    if (!handles || n_handles < 1 || nprobe < 1) return -1;
+    int32_t *p = (int32_t *)malloc(sizeof(int32_t) * (size_t)n_handles * (nq > 0 ? nq : 1) * nprobe);
+    if (!p) return -1;
+    for (int h = 0; h < n_handles; ++h) {
+        if (!handles[h] || nprobe > handles[h]->nlist) return -1;
+        int rc = orc_coarse(handles[h], q, nq, nprobe, p + (size_t)h * nq * nprobe, NULL);
+        if (rc) return rc;
+    }
+    int rc = orc_union_probes(handles, n_handles, q, nq, k, nprobe, p, src_out, ids_out, val_out);
+    free(p);
+    return rc;
+}
+
+/*
  * Exact k nearest neighbours over a raw array: what IVF approximates.  Does not
  * touch any index structure, so "nprobe = nlist equals brute force" compares
  * two separate code paths.

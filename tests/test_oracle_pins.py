@@ -310,6 +310,43 @@ def test_search_multi_is_a_loop_over_indexes():
 
 
 @pytest.mark.parametrize("metric", [oracle.IP, oracle.L2])
+def test_scope_union_with_full_probe_is_exact_knn_over_all_memories(metric):
+    """Section 3.2 scope search: with nprobe = nlist in every index the union search must equal exact kNN
+    over the concatenated memories (a separate code path: float64 matmul + lexsort), with the source
+    index as the first tie-breaker; one row sits in two memories and one memory is shorter than k."""
+    parts, idx = [], []
+    for s, n in enumerate((500, 23, 800)):
+        x, q, c, _ = _small(40 + s, n=n, nlist=5)
+        if s == 2:
+            x[7] = parts[0][11]  # the same vector in memories 0 and 2: equal values, source 0 first
+        ix = oracle.Index(c, metric)
+        ix.build(x)
+        parts.append(x)
+        idx.append(ix)
+    _, q, _, _ = _small(50)
+    k = 30
+    src, ids, val = oracle.search_union(idx, q, k, 5)
+    allx = np.concatenate(parts)
+    code = np.concatenate([np.arange(len(x), dtype=np.int64) + (s << 32) for s, x in enumerate(parts)])
+    bi, bv = _numpy_exact(allx, code, q, k, metric)
+    assert np.array_equal((src.astype(np.int64) << 32) + ids, bi)
+    np.testing.assert_allclose(val, bv, rtol=1e-12, atol=1e-12)
+    # the duplicated row: found in both memories by its own query, memory 0 listed first
+    s1, i1, v1 = oracle.search_union(idx, parts[0][11:12], 2, 5)
+    assert list(zip(s1[0], i1[0])) == [(0, 11), (2, 7)] and v1[0, 0] == v1[0, 1]
+    # a scope of one memory is an ordinary search; a scope smaller than k is padded
+    s2, i2, v2 = oracle.search_union(idx[1:2], q, k, 5)
+    i3, v3 = idx[1].search(q, k, 5)
+    assert np.array_equal(i2, i3) and np.array_equal(v2, v3)
+    assert np.all(s2[:, 23:] == -1) and np.all(i2[:, 23:] == -1) and np.all(s2[:, :23] == 0)
+    # forced probe lists: the oracle's own probes reproduce the unforced call
+    probes = np.stack([ix.coarse(q, 2) for ix in idx])
+    a = oracle.search_union(idx, q, k, 2)
+    b = oracle.search_union(idx, q, k, 2, probes=probes)
+    assert all(np.array_equal(u, v) for u, v in zip(a, b))
+
+
+@pytest.mark.parametrize("metric", [oracle.IP, oracle.L2])
 def test_short_rows_are_padded(metric):
     x, q, c, _ = _small(11, n=30, nlist=6)
     ix = oracle.Index(c, metric)
