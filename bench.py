@@ -254,6 +254,24 @@ class Scenario:
                 "copy_GBps_read_plus_write": 2 * copied / dt / 1e9, "ms_per_step_before": before,
                 "ms_per_step_after": after}
 
+    def scope_union(self, steps=30):
+        """One agent's query batch searched across the memories of ALL agents of the workload
+        (pk_search_union): the same number of (query, index) searches as one multi-agent step."""
+        torch, B, cfg = self.torch, self.B, self.cfg
+        q = self.q[0][:cfg.nq].contiguous()
+        src = torch.empty((cfg.nq, cfg.k), dtype=torch.int32, device="cuda")
+        hs = [ix.handle for ix in self.indexes]
+        for _ in range(3):
+            B.pk_search_union(hs, q, cfg.k, cfg.nprobe, src, self.out_ids[:cfg.nq], self.out_dist[:cfg.nq])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            B.pk_search_union(hs, q, cfg.k, cfg.nprobe, src, self.out_ids[:cfg.nq], self.out_dist[:cfg.nq])
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / steps
+        return {"handles": len(hs), "queries": cfg.nq, "ms_per_call": dt * 1e3,
+                "index_searches_per_s": cfg.nq * len(hs) / dt, "queries_per_s": cfg.nq / dt}
+
     def training(self, iters):
         """pk_kmeans on the workload's own training sample (the rows and initial centroids its index was
         trained from on the host): time per Lloyd iteration and the rate of the assignment GEMM."""
@@ -373,6 +391,9 @@ def run(args):
         # baseline needs host data only
         out["cpu_baseline"] = sc.cpu_baseline()
         log(f"cpu baseline: {out['cpu_baseline']['value']:.1f} queries/s on {out['cpu_baseline']['cores']} threads")
+    if args.union:
+        out["scope_union"] = sc.scope_union()
+        log(f"scope union: {out['scope_union']}")
     if args.train:
         out["training"] = sc.training(args.train)
         log(f"training: {out['training']}")
@@ -391,6 +412,8 @@ def main():
     ap.add_argument("--recall-queries", type=int, default=8)
     ap.add_argument("--no-recall", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--union", action="store_true",
+                    help="also time pk_search_union: one agent's batch searched across all agents' memories (extra field)")
     ap.add_argument("--train", type=int, default=0, metavar="ITERS",
                     help="also run ITERS Lloyd iterations of pk_kmeans on the workload's training sample and report "
                          "the time per iteration (extra field)")

@@ -188,6 +188,23 @@ int pk_search(pk_index *index, const float *queries, int64_t nq, int32_t k, int3
 int pk_search_multi(pk_index *const *handles, int32_t n_handles, const int64_t *q_offsets, const float *queries,
                     int32_t k, int32_t nprobe, int64_t *out_ids, float *out_dist, void *stream);
 
+/*
+ * Section 3.2: a request may read the memories of a set of agents (its scope), e.g. the
+ * shared memory plus the agent's private one; each index of the scope is searched and the
+ * results are merged.  Every query is searched in every handle (coarse + fine search per
+ * handle, with that handle's own centroids), and the k best of the union are returned;
+ * equal values are ordered by the position of the handle in `handles`, then by id.
+ *   handles   HOST [n_handles] distinct live handles of equal d, metric, storage, page size
+ *   queries   DEVICE [nq, d] float32
+ *   out_src   DEVICE [nq, k] int32: position in `handles` of the index each result came
+ *             from (-1 for padding)
+ *   out_ids   DEVICE [nq, k] int64;  out_dist DEVICE [nq, k] float32
+ * Asynchronous; the work is that of n_handles searches of the batch, in one segmented
+ * launch sequence.  The first handle owns the staging buffer (grown on demand).
+ */
+int pk_search_union(pk_index *const *handles, int32_t n_handles, const float *queries, int64_t nq, int32_t k,
+                    int32_t nprobe, int32_t *out_src, int64_t *out_ids, float *out_dist, void *stream);
+
 /* Stage seams (tests isolate coarse and fine search with them). */
 
 /* Coarse search only: out_probes DEVICE [nq, nprobe] int32, best list first. */

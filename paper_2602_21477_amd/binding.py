@@ -21,7 +21,7 @@ PK_OK = 0
 PK_ERR_INVALID_ARG, PK_ERR_BAD_HANDLE, PK_ERR_DIM_MISMATCH, PK_ERR_NOMEM, PK_ERR_HIP, PK_ERR_UNSUPPORTED = (
     -1, -2, -3, -4, -5, -6)
 
-EXPORTS = ["pk_arena_bytes", "pk_index_build", "pk_index_add_arena", "pk_index_compact", "pk_kmeans", "pk_insert", "pk_insert_assigned", "pk_search",
+EXPORTS = ["pk_search_union", "pk_arena_bytes", "pk_index_build", "pk_index_add_arena", "pk_index_compact", "pk_kmeans", "pk_insert", "pk_insert_assigned", "pk_search",
            "pk_search_multi", "pk_coarse", "pk_scan_probes", "pk_index_stats", "pk_list_lengths", "pk_profile_begin",
            "pk_profile_end", "pk_index_free", "pk_strerror"]
 
@@ -70,6 +70,7 @@ def lib():
         L.pk_insert_assigned.argtypes = [vp, vp, vp, i64, vp, vp]
         L.pk_search.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
         L.pk_search_multi.argtypes = [C.POINTER(vp), i32, C.POINTER(i64), vp, i32, i32, vp, vp, vp]
+        L.pk_search_union.argtypes = [C.POINTER(vp), i32, vp, i64, i32, i32, vp, vp, vp, vp]
         L.pk_coarse.argtypes = [vp, vp, i64, i32, vp, vp]
         L.pk_scan_probes.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp, vp]
         L.pk_index_stats.argtypes = [vp, C.POINTER(pk_stats), vp]
@@ -279,6 +280,22 @@ class Index:
             self.close()
         except Exception:
             pass
+
+
+def pk_search_union(handles, queries, k: int, nprobe: int, out_src, out_ids, out_dist):
+    hs = (C.c_void_p * len(handles))(*handles)
+    _check(lib().pk_search_union(hs, len(handles), _dev(queries, torch.float32, "queries"), queries.shape[0], k, nprobe,
+                                 _dev(out_src, torch.int32, "out_src"), _dev(out_ids, torch.int64, "out_ids"),
+                                 _dev(out_dist, torch.float32, "out_dist"), _stream()), "pk_search_union")
+
+
+def search_union(indexes, queries, k, nprobe):
+    dev = queries.device
+    src = torch.empty((queries.shape[0], k), dtype=torch.int32, device=dev)
+    ids = torch.empty((queries.shape[0], k), dtype=torch.int64, device=dev)
+    dist = torch.empty((queries.shape[0], k), dtype=torch.float32, device=dev)
+    pk_search_union([ix.handle for ix in indexes], queries, k, nprobe, src, ids, dist)
+    return src, ids, dist
 
 
 def search_multi(indexes, q_offsets, queries, k, nprobe):

@@ -52,6 +52,9 @@ struct pk_index {
     // library-owned workspace
     char *ws;
     size_t ws_bytes;
+    // staging of scope-union searches (replicated queries, per-handle results); grow-only
+    char *ubuf;
+    size_t ubuf_bytes;
     int lds_limit, num_cu;
     // stage timing (pk_profile_begin .. pk_profile_end)
     bool prof_on;
@@ -706,6 +709,7 @@ void destroy(pk_index *ix)
 {
     if (!ix) return;
     if (ix->ws) (void)hipFree(ix->ws);
+    if (ix->ubuf) (void)hipFree(ix->ubuf);
     if (ix->pin_pages) (void)hipHostFree(ix->pin_pages);
     if (ix->ev) (void)hipEventDestroy(ix->ev);
     for (hipEvent_t e : ix->prof_ev) (void)hipEventDestroy(e);
@@ -1118,6 +1122,71 @@ int pk_search_multi(pk_index *const *handles, int32_t n_handles, const int64_t *
     if (nq == 0) return PK_OK;
     return search_impl(handles, n_handles, q_offsets, queries, k, nprobe, kFull, nullptr, nullptr, out_ids, out_dist,
                        static_cast<hipStream_t>(stream));
+}
+
+static_assert(PK_MAX_K <= 1024 && PK_MAX_HANDLES <= 128, "union_merge_kernel packs rank and handle into 17 bits");
+
+int pk_search_union(pk_index *const *handles, int32_t n_handles, const float *queries, int64_t nq, int32_t k,
+                    int32_t nprobe, int32_t *out_src, int64_t *out_ids, float *out_dist, void *stream)
+{
+    if (!handles || n_handles < 1 || n_handles > PK_MAX_HANDLES) return PK_ERR_INVALID_ARG;
+    for (int a = 0; a < n_handles; ++a) {
+        if (!live(handles[a])) return PK_ERR_BAD_HANDLE;
+        for (int b = 0; b < a; ++b)
+            if (handles[b] == handles[a]) return PK_ERR_INVALID_ARG;
+        const pk_config &c0 = handles[0]->cfg, &c = handles[a]->cfg;
+        if (c.d != c0.d || c.metric != c0.metric || c.storage != c0.storage || c.page_vecs != c0.page_vecs)
+            return PK_ERR_DIM_MISMATCH;
+        PK_TRY(check_search_args(handles[a], queries, nq, k, nprobe));
+    }
+    if (nq > 0 && (!out_src || !out_ids || !out_dist)) return PK_ERR_INVALID_ARG;
+    if (nq == 0) return PK_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    pk_index *own = handles[0];
+    const int d = own->cfg.d;
+    const int64_t H = n_handles;
+    // every query is searched in every handle: the segmented launch over H copies of the batch
+    const int64_t chunk = std::max<int64_t>(1, std::min<int64_t>(nq, 32768 / H));
+    const size_t qb = round_up((size_t)H * chunk * d * sizeof(float), 256);
+    const size_t ib = round_up((size_t)H * chunk * k * sizeof(int64_t), 256);
+    const size_t need = qb + ib + round_up((size_t)H * chunk * k * sizeof(float), 256);
+    if (need > own->ubuf_bytes) {
+        PK_HIP(hipStreamSynchronize(s));
+        if (own->ubuf) PK_HIP(hipFree(own->ubuf));
+        own->ubuf = nullptr;
+        own->ubuf_bytes = 0;
+        void *p = nullptr;
+        if (hipMalloc(&p, need) != hipSuccess) {
+            (void)hipGetLastError();
+            return PK_ERR_NOMEM;
+        }
+        own->ubuf = static_cast<char *>(p);
+        own->ubuf_bytes = need;
+    }
+    float *uq = reinterpret_cast<float *>(own->ubuf);
+    int64_t *uids = reinterpret_cast<int64_t *>(own->ubuf + qb);
+    float *udist = reinterpret_cast<float *>(own->ubuf + qb + ib);
+    std::vector<int64_t> offs((size_t)H + 1);
+    for (int64_t q0 = 0; q0 < nq; q0 += chunk) {
+        const int64_t nc = std::min(chunk, nq - q0);
+        for (int64_t h = 0; h <= H; ++h) offs[(size_t)h] = h * nc;
+        for (int64_t h = 0; h < H; ++h)
+            PK_HIP(hipMemcpyAsync(uq + (size_t)h * nc * d, queries + (size_t)q0 * d, (size_t)nc * d * sizeof(float),
+                                  hipMemcpyDeviceToDevice, s));
+        PK_TRY(search_impl(handles, n_handles, offs.data(), uq, k, nprobe, kFull, nullptr, nullptr, uids, udist, s));
+        UnionArgs u{};
+        u.ids = uids;
+        u.dist = udist;
+        u.n_handles = n_handles;
+        u.k = k;
+        u.metric = own->cfg.metric;
+        u.nq = nc;
+        u.out_src = out_src + (size_t)q0 * k;
+        u.out_ids = out_ids + (size_t)q0 * k;
+        u.out_dist = out_dist + (size_t)q0 * k;
+        PK_HIP(launch_union_merge(u, s));
+    }
+    return PK_OK;
 }
 
 int pk_coarse(pk_index *ix, const float *queries, int64_t nq, int32_t nprobe, int32_t *out_probes, void *stream)

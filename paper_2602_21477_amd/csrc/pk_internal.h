@@ -235,6 +235,18 @@ struct CentroidArgs {
 };
 hipError_t launch_centroid_scores(const CentroidArgs &a, const MultiArgs &m, hipStream_t s);
 
+// merge of per-handle result rows into one row per query (k <= 1024: rank fits 10 bits, handle 7)
+struct UnionArgs {
+    const int64_t *ids;  // [n_handles][nq][k] rows of the handles, each sorted best first, -1 padded
+    const float *dist;   // [n_handles][nq][k]
+    int n_handles, k, metric;
+    int64_t nq;
+    int32_t *out_src;    // [nq][k] position of the handle in the scope, -1 for padding
+    int64_t *out_ids;    // [nq][k]
+    float *out_dist;     // [nq][k]
+};
+hipError_t launch_union_merge(const UnionArgs &a, hipStream_t s);
+
 struct WorklistArgs {
     const int32_t *probes;     // [nq][nprobe]; entries outside [0, nlist) are ignored
     const uint16_t *qagent;    // [nq]

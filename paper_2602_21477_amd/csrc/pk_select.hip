@@ -462,4 +462,54 @@ hipError_t launch_select_final(const FinalArgs &a, const MultiArgs &h, int64_t n
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------ scope union
+
+// Merge of the per-handle results of one query (Section 3.2: a request searches the memories
+// of a set of agents and merges what each returns).  Every handle's row is already sorted
+// (value, id); a candidate's key is (value key, position of the handle in the scope, rank
+// inside that handle's row), so equal values come out by handle, then by id.
+__global__ __launch_bounds__(kSelThreads) void union_merge_kernel(UnionArgs a)
+{
+    __shared__ u64 keys[kSelCap];
+    __shared__ uint32_t s_cnt;
+    const size_t q = blockIdx.x;
+    const uint32_t k = (uint32_t)a.k, total = (uint32_t)a.n_handles * k;
+    Selector sel;
+    sel.init(keys, &s_cnt, a.k);
+    for (uint32_t base = 0; base < total; base += kSelThreads) {
+        sel.reserve(kSelThreads);
+        const uint32_t i = base + threadIdx.x;
+        if (i < total) {
+            const uint32_t h = i / k, j = i - h * k;
+            const size_t at = ((size_t)h * a.nq + q) * k + j;
+            if (a.ids[at] >= 0) sel.push(((u64)order_bits(a.dist[at], a.metric) << 32) | (u64)(h << 10 | j));
+        }
+    }
+    sel.flush();
+    const uint32_t n = s_cnt;
+    for (uint32_t j = threadIdx.x; j < k; j += kSelThreads) {
+        const size_t o = q * k + j;
+        if (j < n) {
+            const uint32_t lo = (uint32_t)keys[j];
+            const uint32_t h = (lo >> 10) & 0x7fu, r = lo & 0x3ffu;
+            const size_t at = ((size_t)h * a.nq + q) * k + r;
+            a.out_src[o] = (int32_t)h;
+            a.out_ids[o] = a.ids[at];
+            a.out_dist[o] = a.dist[at];
+        } else {
+            a.out_src[o] = -1;
+            a.out_ids[o] = -1;
+            a.out_dist[o] = a.metric == PK_METRIC_IP ? -INFINITY : INFINITY;
+        }
+    }
+}
+
+hipError_t launch_union_merge(const UnionArgs &a, hipStream_t s)
+{
+    if (a.nq <= 0) return hipSuccess;
+    if (a.k < 1 || a.k > PK_MAX_K || a.n_handles < 1 || a.n_handles > PK_MAX_HANDLES) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(union_merge_kernel, dim3((uint32_t)a.nq), dim3(kSelThreads), 0, s, a);
+    return hipGetLastError();
+}
+
 } // namespace pk

@@ -336,6 +336,42 @@ def test_multi_agent_equals_per_handle_calls(gpu_device):
             p.close()
 
 
+@pytest.mark.parametrize("metric", [IP, L2])
+def test_scope_union_search(gpu_device, metric):
+    """One query batch searched across three memories of different sizes (one shorter than k, one row
+    present in two of them): each handle's probe lists are validated against the oracle, then the
+    oracle merges its own per-handle scans of those lists; sources and ids must agree."""
+    cfg = W.scaled(W.C1, n=4000, nlist=16)
+    pairs = []
+    try:
+        for a, n in enumerate((4000, 37, 2500)):
+            x = W.vectors(cfg, 0, n, agent=a)
+            if a == 2:
+                x[5] = pairs[0].x[9]
+            cent = W.train_centroids(W.scaled(cfg, n=n), x, agent=a) if n >= 16 * 4 else x[:16].copy()
+            pairs.append(Pair(x, cent, metric, F32))
+        q = np.concatenate([W.queries(cfg, 4, 40), pairs[0].x[9:10]])
+        k, nprobe = 50, 6
+        probes = np.stack([p.check_coarse(q, nprobe, where=f"memory {a}") for a, p in enumerate(pairs)])
+        gs, gi, gv = B.search_union([p.gpu for p in pairs], dev(q), k, nprobe)
+        os_, oi, ov = oracle.search_union([p.orc for p in pairs], q, k + KX, nprobe, probes=probes)
+        enc = lambda s_, i_: np.where(i_ < 0, -1, (s_.astype(np.int64) << 40) + i_)
+        scale = np.max([p.scale(q) for p in pairs], axis=0)
+        check_results(enc(gs.cpu().numpy(), gi.cpu().numpy()), gv.cpu().numpy(), enc(os_, oi), ov, k, 1e-4, scale,
+                      metric, where="union")
+        g = gs.cpu().numpy()
+        assert set(np.unique(g)) <= {-1, 0, 1, 2} and np.all((g == -1) == (gi.cpu().numpy() == -1))
+        # the row stored in memories 0 and 2 is its own best match in both: memory 0 first
+        assert (g[-1, 0], int(gi[-1, 0]), g[-1, 1], int(gi[-1, 1])) == (0, 9, 2, 5)
+        # a scope of one memory is an ordinary search
+        s1, i1, v1 = B.search_union([pairs[1].gpu], dev(q), k, nprobe)
+        i2, v2 = pairs[1].gpu.search(dev(q), k, nprobe)
+        assert torch.equal(i1, i2) and torch.equal(v1, v2) and bool(torch.all((s1 == 0) == (i1 >= 0)))
+    finally:
+        for p in pairs:
+            p.close()
+
+
 def test_wide_rows_many_queries_per_list(gpu_device):
     """d = 1536 (config 5 width) with few lists, so lists see more queries than one group holds."""
     cfg = W.scaled(W.C5, n=5000, ncomp=24, nlist=24, zipf_s=1.2)

@@ -65,6 +65,8 @@ def test_host_side_argument_checks_without_gpu(lib):
     offs = (C.c_int64 * 2)(0, 1)
     assert lib.pk_search_multi(hs, 1, offs, null, 1, 1, null, null, null) == B.PK_ERR_BAD_HANDLE
     assert lib.pk_search_multi(hs, 0, offs, null, 1, 1, null, null, null) == B.PK_ERR_INVALID_ARG
+    assert lib.pk_search_union(hs, 1, null, 1, 1, 1, null, null, null, null) == B.PK_ERR_BAD_HANDLE
+    assert lib.pk_search_union(hs, 0, null, 1, 1, 1, null, null, null, null) == B.PK_ERR_INVALID_ARG
 
 
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
