@@ -37,6 +37,8 @@ def lib():
         L.orc_insert.argtypes = [vp, vp, vp, i64, vp, vp]
         L.orc_ntotal.restype = i64
         L.orc_ntotal.argtypes = [vp]
+        L.orc_delete.restype = i64
+        L.orc_delete.argtypes = [vp, vp, i64]
         L.orc_list_lengths.argtypes = [vp, vp]
         L.orc_list_ids.restype = i64
         L.orc_list_ids.argtypes = [vp, i32, vp, i64]
@@ -110,6 +112,12 @@ class Index:
         rc = lib().orc_insert(self._h, _ptr(x), _ptr(ids), m, _ptr(forced_lists), _ptr(out))
         assert rc == 0
         return out
+
+    def delete(self, ids) -> int:
+        ids = np.ascontiguousarray(ids, dtype=np.int64)
+        n = int(lib().orc_delete(self._h, _ptr(ids), ids.shape[0]))
+        assert n >= 0
+        return n
 
     @property
     def ntotal(self) -> int:

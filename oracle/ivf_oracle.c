@@ -266,6 +266,34 @@ int orc_insert(orc_index *ix, const float *x, const int64_t *ids, int64_t m,
     return 0;
 }
 
+/*
+ * Delete (the interface of Section 5 has search, insert, delete and update): every stored
+ * vector whose id is among ids[0..m) leaves its list, all of them if several carry the id;
+ * the others keep their relative order.  Returns how many were removed, or -1.  An update
+ * is a delete followed by an insert.
+ */
+int64_t orc_delete(orc_index *ix, const int64_t *ids, int64_t m)
+{
+    if (!ix || (!ids && m > 0) || m < 0) return -1;
+    int64_t removed = 0;
+    for (int j = 0; j < ix->nlist; ++j) {
+        orc_list *L = &ix->lists[j];
+        int64_t w = 0;
+        for (int64_t r = 0; r < L->len; ++r) {
+            int hit = 0;
+            for (int64_t t = 0; t < m && !hit; ++t) hit = L->e[r].id == ids[t];
+            if (hit) {
+                ++removed;
+            } else {
+                L->e[w++] = L->e[r];
+            }
+        }
+        L->len = w;
+    }
+    ix->ntotal -= removed;
+    return removed;
+}
+
 int64_t orc_ntotal(const orc_index *ix) { return ix ? ix->ntotal : -1; }
 
 int orc_list_lengths(const orc_index *ix, int64_t *len_out)

@@ -347,6 +347,36 @@ def test_scope_union_with_full_probe_is_exact_knn_over_all_memories(metric):
 
 
 @pytest.mark.parametrize("metric", [oracle.IP, oracle.L2])
+def test_delete_then_search_is_exact_knn_over_what_is_left(metric):
+    """Delete removes every carrier of an id and nothing else: with nprobe = nlist the search equals
+    exact kNN (float64 matmul + lexsort) over the remaining rows; an update is delete + insert."""
+    x, q, c, rng = _small(60)
+    ids = np.arange(len(x), dtype=np.int64) * 3 + 1
+    ids[100] = ids[7]  # one id carried by two rows: both go
+    ix = oracle.Index(c, metric)
+    ix.build(x, ids)
+    gone = np.concatenate([ids[rng.permutation(len(x))[:200]], [ids[7], 10 ** 12]])  # + an id nobody has
+    keep = ~np.isin(ids, gone)
+    before = ix.list_lengths().sum()
+    assert ix.delete(gone) == int((~keep).sum()) and ix.ntotal == int(keep.sum())
+    assert ix.list_lengths().sum() == before - int((~keep).sum())
+    assert ix.delete(gone) == 0
+    got_i, got_v = ix.search(q, 25, ix.nlist)
+    want_i, want_v = _numpy_exact(x[keep], ids[keep], q, 25, metric)
+    assert np.array_equal(got_i, want_i)
+    np.testing.assert_allclose(got_v, want_v, rtol=1e-12, atol=1e-12)
+    # update: the deleted row comes back under its old id with a new vector
+    new = q[:1].copy()
+    ix.insert(new, np.array([ids[7]]))
+    i2, v2 = ix.search(new, 1, ix.nlist)
+    assert i2[0, 0] == ids[7]
+    # deleting everything leaves empty lists and padded results
+    assert ix.delete(ids) + ix.delete(np.array([ids[7]])) >= int(keep.sum())
+    i3, _ = ix.search(q, 3, ix.nlist)
+    assert ix.ntotal == 0 and np.all(i3 == -1)
+
+
+@pytest.mark.parametrize("metric", [oracle.IP, oracle.L2])
 def test_short_rows_are_padded(metric):
     x, q, c, _ = _small(11, n=30, nlist=6)
     ix = oracle.Index(c, metric)
