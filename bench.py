@@ -236,6 +236,13 @@ class Scenario:
             torch.cuda.synchronize()
             return (time.perf_counter() - t0) / steps * 1e3
 
+        # deletes: 4096 ids drawn over the whole id range (build rows carry ids 0 .. n-1)
+        gone = torch.from_numpy(np.random.default_rng(7).choice(self.datas[0].n, 4096, replace=False)).cuda()
+        ix.delete(gone[:8])  # warm-up
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        n_del = ix.delete(gone[8:])
+        del_ms = (time.perf_counter() - t0) * 1e3
         before = ms_per_step()
         st = ix.stats()
         nbytes = B.pk_arena_bytes(ix.cfg, int(st.n_total), self.insert_m * (steps + 8) + 1024)
@@ -249,7 +256,8 @@ class Scenario:
         after = ms_per_step()
         self.check_errors()
         copied = int(st.pages_used) * page_bytes
-        return {"extra_inserts": extra_inserts, "n_total": int(st.n_total), "arenas_before": int(st.n_arenas),
+        return {"extra_inserts": extra_inserts, "deleted": n_del, "delete_ms_per_4088_ids": del_ms,
+                "ids_scanned_per_s": float(st.n_total + n_del) / (del_ms * 1e-3), "n_total": int(st.n_total), "arenas_before": int(st.n_arenas),
                 "compaction_ms": dt * 1e3, "bytes_copied": copied,
                 "copy_GBps_read_plus_write": 2 * copied / dt / 1e9, "ms_per_step_before": before,
                 "ms_per_step_after": after}

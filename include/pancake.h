@@ -77,7 +77,7 @@ typedef struct {
 } pk_config;
 
 typedef struct {
-    int64_t n_total;         /* vectors in the index (build + inserts)                 */
+    int64_t n_total;         /* vectors in the index (build + inserts - deletes)       */
     int64_t n_inserted;      /* vectors added by pk_insert                             */
     int64_t pages_total;     /* pages available in all arenas                          */
     int64_t pages_used;      /* pages handed to lists                                  */
@@ -154,13 +154,27 @@ int pk_index_compact(pk_index *index, void *arena, size_t arena_bytes, void *str
  * appended to the tail page of that list, opening a delta page when the tail is full.
  *   vectors         DEVICE [m, d] float32
  *   ids             DEVICE [m] int64, or NULL to continue the running counter
- *                   (n_total before the call, +1 per vector)
+ *                   (vectors ever added before the call, +1 per vector)
  *   assigned_lists  DEVICE [m] int32, optional (NULL): receives the chosen lists
  * Asynchronous.  PK_ERR_NOMEM if the arenas may not hold m more vectors (nothing is
  * enqueued then).
  */
 int pk_insert(pk_index *index, const float *vectors, const int64_t *ids, int64_t m, int32_t *assigned_lists,
               void *stream);
+
+/*
+ * Section 5 (the interface offers search, insert, delete and update).  Every stored vector
+ * whose id is among ids[0..m) is removed, all of them if several carry the id; ids nobody
+ * carries are ignored.  A removed row is overwritten by the last row of its list and the
+ * list shrinks by one (lists are unordered sets: search results, ordered by value and id,
+ * show nothing but the removal; no tombstones are left for searches to skip).  Pages a list
+ * no longer reaches stay with the list and are used again when it grows.  An update is a
+ * pk_delete followed by a pk_insert on the same stream.
+ *   ids        DEVICE [m] int64
+ *   n_removed  HOST, optional (NULL): receives the number of vectors removed
+ * Synchronises `stream` (the handle keeps the live count).
+ */
+int pk_delete(pk_index *index, const int64_t *ids, int64_t m, int64_t *n_removed, void *stream);
 
 /* As pk_insert, with the lists given by the caller (DEVICE [m] int32, each in [0, nlist)). */
 int pk_insert_assigned(pk_index *index, const float *vectors, const int64_t *ids, int64_t m,

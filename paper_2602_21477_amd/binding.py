@@ -21,7 +21,7 @@ PK_OK = 0
 PK_ERR_INVALID_ARG, PK_ERR_BAD_HANDLE, PK_ERR_DIM_MISMATCH, PK_ERR_NOMEM, PK_ERR_HIP, PK_ERR_UNSUPPORTED = (
     -1, -2, -3, -4, -5, -6)
 
-EXPORTS = ["pk_search_union", "pk_arena_bytes", "pk_index_build", "pk_index_add_arena", "pk_index_compact", "pk_kmeans", "pk_insert", "pk_insert_assigned", "pk_search",
+EXPORTS = ["pk_search_union", "pk_delete", "pk_arena_bytes", "pk_index_build", "pk_index_add_arena", "pk_index_compact", "pk_kmeans", "pk_insert", "pk_insert_assigned", "pk_search",
            "pk_search_multi", "pk_coarse", "pk_scan_probes", "pk_index_stats", "pk_list_lengths", "pk_profile_begin",
            "pk_profile_end", "pk_index_free", "pk_strerror"]
 
@@ -68,6 +68,7 @@ def lib():
         L.pk_kmeans.argtypes = [vp, i64, i32, i32, i32, vp, vp, C.POINTER(C.c_double), vp]
         L.pk_insert.argtypes = [vp, vp, vp, i64, vp, vp]
         L.pk_insert_assigned.argtypes = [vp, vp, vp, i64, vp, vp]
+        L.pk_delete.argtypes = [vp, vp, i64, C.POINTER(i64), vp]
         L.pk_search.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
         L.pk_search_multi.argtypes = [C.POINTER(vp), i32, C.POINTER(i64), vp, i32, i32, vp, vp, vp]
         L.pk_search_union.argtypes = [C.POINTER(vp), i32, vp, i64, i32, i32, vp, vp, vp, vp]
@@ -136,6 +137,12 @@ def pk_kmeans(vectors, centroids, iters: int, assign_out=None):
                            _dev(centroids, torch.float32, "centroids"), _dev(assign_out, torch.int32, "assign_out"),
                            inertia, _stream()), "pk_kmeans")
     return [float(v) for v in inertia]
+
+
+def pk_delete(handle: int, ids) -> int:
+    n = C.c_int64(0)
+    _check(lib().pk_delete(handle, _dev(ids, torch.int64, "ids"), ids.shape[0], C.byref(n), _stream()), "pk_delete")
+    return int(n.value)
 
 
 def pk_index_compact(handle: int, arena):
@@ -241,6 +248,9 @@ class Index:
         out = torch.empty(vectors.shape[0], dtype=torch.int32, device=self.device) if want_lists else None
         pk_insert(self.handle, vectors, ids, out)
         return out
+
+    def delete(self, ids) -> int:
+        return pk_delete(self.handle, ids)
 
     def insert_assigned(self, vectors, lists, ids=None):
         pk_insert_assigned(self.handle, vectors, ids, lists)

@@ -42,6 +42,7 @@ struct pk_index {
     std::vector<uint64_t> top_len; // [j] = total length of the j longest lists when the layout was last fixed (build, compaction)
     int64_t inserted_at_top;       // n_inserted at that moment
     int64_t n_total, n_inserted;
+    int64_t next_id;               // vectors ever added: the running id counter (deletes do not lower it)
     // page accounting: last page counter read back, and how many vectors were inserted by then
     uint32_t pages_known;
     int64_t inserted_at_known;
@@ -772,8 +773,9 @@ int insert_impl(pk_index *ix, const float *x, const int64_t *ids, int64_t m, con
             assign = p.probes;
         }
         PK_HIP(launch_reserve(ix->dev, assign, mc, slots, assigned_out ? assigned_out + i0 : nullptr, s));
-        PK_HIP(launch_append(ix->dev, xc, ids ? ids + i0 : nullptr, assign, slots, mc, ix->n_total, s));
+        PK_HIP(launch_append(ix->dev, xc, ids ? ids + i0 : nullptr, assign, slots, mc, ix->next_id, s));
         ix->n_total += mc;
+        ix->next_id += mc;
         ix->n_inserted += mc;
     }
     return snapshot_pages(ix, s);
@@ -922,6 +924,7 @@ int pk_index_build(const pk_config *cfg, const float *centroids, const float *ve
     }
     if (hipStreamSynchronize(s) != hipSuccess) return fail(PK_ERR_HIP);
     ix->n_total = n;
+    ix->next_id = n;
     ix->n_inserted = 0;
     ix->inserted_at_known = 0;
     ix->inserted_at_top = 0;
@@ -948,6 +951,31 @@ int pk_index_add_arena(pk_index *ix, void *arena, size_t arena_bytes, void *stre
     ix->arena_bytes += arena_bytes;
     PK_HIP(hipMemcpyAsync(ix->dev, &D, sizeof(D), hipMemcpyHostToDevice, s));
     PK_HIP(launch_fill_u32(D.ctr + 2, ix->pages_total, 1, s));
+    return PK_OK;
+}
+
+int pk_delete(pk_index *ix, const int64_t *ids, int64_t m, int64_t *n_removed, void *stream)
+{
+    if (!live(ix)) return PK_ERR_BAD_HANDLE;
+    if (m < 0 || (m > 0 && !ids)) return PK_ERR_INVALID_ARG;
+    if (n_removed) *n_removed = 0;
+    if (m == 0) return PK_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t need = round_up((size_t)kDeleteChunk * sizeof(int64_t), 256) + 256;
+    PK_TRY(ensure_ws(ix, need, s));
+    int64_t *sorted = reinterpret_cast<int64_t *>(ix->ws);
+    unsigned long long *counter =
+        reinterpret_cast<unsigned long long *>(ix->ws + round_up((size_t)kDeleteChunk * sizeof(int64_t), 256));
+    PK_HIP(launch_fill_u32(reinterpret_cast<uint32_t *>(counter), 0u, 2, s));
+    for (int64_t i0 = 0; i0 < m; i0 += kDeleteChunk) {
+        const int mc = (int)std::min<int64_t>(kDeleteChunk, m - i0);
+        PK_HIP(launch_delete(ix->dev, ix->cfg.nlist, ids + i0, mc, sorted, counter, s));
+    }
+    unsigned long long removed = 0;
+    PK_HIP(hipMemcpyAsync(&removed, counter, sizeof(removed), hipMemcpyDeviceToHost, s));
+    PK_HIP(hipStreamSynchronize(s));
+    ix->n_total -= (int64_t)removed;
+    if (n_removed) *n_removed = (int64_t)removed;
     return PK_OK;
 }
 

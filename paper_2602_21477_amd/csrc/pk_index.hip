@@ -143,9 +143,11 @@ __global__ __launch_bounds__(1024) void reserve_kernel(const DevIndex *ixp, cons
         slot = ix.list_len[l] + rank;
         const uint32_t lp = slot / (uint32_t)ix.P;
         if (slot % (uint32_t)ix.P == 0 && lp >= ix.main_pages[l]) {
-            opens = true;
             di = lp - ix.main_pages[l];
             if (di >= (uint32_t)ix.max_dp) atomicOr(&s_bad, (uint32_t)kErrListFull);
+            // a list that shrank (deletes) still owns the delta pages it had: take a new one
+            // only where the table has none
+            else opens = ix.dtab[(size_t)l * ix.max_dp + di] == 0xffffffffu;
         }
     } else if (i < m) {
         atomicOr(&s_bad, (uint32_t)kErrListFull);
@@ -202,6 +204,121 @@ hipError_t launch_append(const DevIndex *ix, const float *x, const int64_t *ids,
 
 // probes[:, 0] of a top-1 coarse search -> assignment array (stride nprobe = 1 is the identity;
 // kept as a kernel so the copy stays on the stream)
+// ------------------------------------------------------------------ delete
+
+// location of position `pos` of list l: arena and row number inside the arena
+__device__ __forceinline__ const Arena &locate(const DevIndex &ix, uint32_t l, uint32_t pos, size_t &local)
+{
+    const uint32_t P = (uint32_t)ix.P, lp = pos / P;
+    const uint32_t pg = phys_page(ix, l, lp);
+    const Arena &ar = arena_of(ix, pg);
+    local = (size_t)(pg - ar.first_page) * P + (pos - lp * P);
+    return ar;
+}
+
+// sorts the ids to delete (at most kDeleteChunk) so that the list kernel can search them
+__global__ __launch_bounds__(1024) void delete_sort_kernel(const int64_t *ids, int m, int64_t *sorted)
+{
+    __shared__ unsigned long long s_keys[kDeleteChunk];
+    for (int i = threadIdx.x; i < kDeleteChunk; i += blockDim.x)
+        s_keys[i] = i < m ? (unsigned long long)ids[i] ^ 0x8000000000000000ull : ~0ull; // order of signed values
+    __syncthreads();
+    for (int k = 2; k <= kDeleteChunk; k <<= 1)
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int i = threadIdx.x; i < kDeleteChunk; i += blockDim.x) {
+                const int p = i ^ j;
+                if (p > i) {
+                    const unsigned long long a = s_keys[i], b = s_keys[p];
+                    if (((i & k) == 0) == (a > b)) {
+                        s_keys[i] = b;
+                        s_keys[p] = a;
+                    }
+                }
+            }
+            __syncthreads();
+        }
+    for (int i = threadIdx.x; i < m; i += blockDim.x) sorted[i] = (int64_t)(s_keys[i] ^ 0x8000000000000000ull);
+}
+
+// One workgroup per list.  Positions are examined from the end of the list downwards; a row
+// whose id is to go is overwritten by the list's last row (already examined, so it stays)
+// and the list shrinks by one: lists are unordered sets, no tombstones, nothing for the scan
+// to skip.  The pages the list no longer reaches stay its own for later inserts.
+__global__ __launch_bounds__(256) void delete_kernel(const DevIndex *ixp, const int64_t *sorted, int m,
+                                                     unsigned long long *removed)
+{
+    __shared__ uint32_t s_hit[256];
+    __shared__ uint32_t s_nhit;
+    const DevIndex &ix = *ixp;
+    const uint32_t l = blockIdx.x;
+    const uint32_t len0 = ix.list_len[l];
+    if (len0 == 0) return;
+    uint32_t len = len0;
+    const int row_bytes = ix.row_bytes;
+    for (int64_t base = (int64_t)((len0 - 1) / 256u) * 256; base >= 0; base -= 256) {
+        if (threadIdx.x == 0) s_nhit = 0;
+        __syncthreads();
+        // descending positions inside the chunk: thread 0 takes the highest
+        const uint32_t pos = (uint32_t)base + 255u - threadIdx.x;
+        bool hit = false;
+        if (pos < len0) {
+            size_t local;
+            const Arena &ar = locate(ix, l, pos, local);
+            const int64_t id = ar.ids[local];
+            int lo = 0, hi = m;
+            while (lo < hi) {
+                const int mid = (lo + hi) / 2;
+                if (sorted[mid] < id) lo = mid + 1;
+                else hi = mid;
+            }
+            hit = lo < m && sorted[lo] == id;
+        }
+        // hits in descending position order: wave by wave, lane by lane
+        for (int w = 0; w < 4; ++w) {
+            if ((int)(threadIdx.x >> 6) == w) {
+                const unsigned long long mask = __ballot(hit);
+                const uint32_t before = (uint32_t)__popcll(mask & ((1ull << (threadIdx.x & 63)) - 1ull));
+                if (hit) s_hit[s_nhit + before] = pos;
+                __builtin_amdgcn_wave_barrier();
+                if ((threadIdx.x & 63) == 0) s_nhit += (uint32_t)__popcll(mask);
+            }
+            __syncthreads();
+        }
+        const uint32_t nhit = s_nhit;
+        for (uint32_t h = 0; h < nhit; ++h) {
+            const uint32_t p = s_hit[h], last = len - 1;
+            if (p != last) {
+                size_t ls, ld;
+                const Arena &as = locate(ix, l, last, ls);
+                const Arena &ad = locate(ix, l, p, ld);
+                const uint4 *src = reinterpret_cast<const uint4 *>(as.vec + ls * (size_t)row_bytes);
+                uint4 *dst = reinterpret_cast<uint4 *>(ad.vec + ld * (size_t)row_bytes);
+                for (int i = threadIdx.x; i < row_bytes / 16; i += blockDim.x) dst[i] = src[i];
+                if (threadIdx.x == 0) {
+                    ad.norm[ld] = as.norm[ls];
+                    ad.ids[ld] = as.ids[ls];
+                }
+            }
+            len -= 1;
+            __syncthreads(); // the moved row may be the source of the next move
+        }
+    }
+    if (threadIdx.x == 0 && len != len0) {
+        ix.list_len[l] = len;
+        atomicAdd(removed, (unsigned long long)(len0 - len));
+    }
+}
+
+hipError_t launch_delete(const DevIndex *ix, int nlist, const int64_t *ids, int m, int64_t *sorted,
+                         unsigned long long *removed, hipStream_t s)
+{
+    if (m <= 0) return hipSuccess;
+    if (m > kDeleteChunk) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(delete_sort_kernel, dim3(1), dim3(1024), 0, s, ids, m, sorted);
+    hipLaunchKernelGGL(delete_kernel, dim3(nlist), dim3(256), 0, s, ix, sorted, m, removed);
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------ compaction
 
 // One workgroup per page of the new layout: page pg belongs to the list whose new extent

@@ -307,6 +307,11 @@ hipError_t launch_scatter_build(const DevIndex *ix, const float *x, const int64_
                                 int64_t n, int64_t id0, uint32_t *fill, hipStream_t s);
 hipError_t launch_store_centroids(const float *c, int nlist, int d, int dpad32, int nlist_pad, int metric,
                                   float *cent, float *cnorm, hipStream_t s);
+// removes the rows whose id is among ids[0..m), m <= kDeleteChunk (sorted: scratch of kDeleteChunk ids;
+// removed: device counter that receives the number of rows removed, added to)
+constexpr int kDeleteChunk = 4096;
+hipError_t launch_delete(const DevIndex *ix, int nlist, const int64_t *ids, int m, int64_t *sorted,
+                         unsigned long long *removed, hipStream_t s);
 // copies every list into the contiguous extents of `dst` (dst's tables are already in place)
 hipError_t launch_compact_pages(const DevIndex *src, const DevIndex *dst, uint32_t new_pages, hipStream_t s);
 // k-means update step (Lloyd): members of every cluster gathered, then one workgroup per cluster

@@ -372,6 +372,65 @@ def test_scope_union_search(gpu_device, metric):
             p.close()
 
 
+@pytest.mark.parametrize("storage,metric", [(F32, L2), (F16, IP)])
+def test_delete_update_and_page_reuse(gpu_device, storage, metric):
+    """Deletes by id (duplicated ids, ids nobody carries, a whole list, rows in delta pages), then
+    inserts into the shrunken lists (their pages are reused) and an update (delete + insert under the
+    old id); list lengths, counts and every search follow the oracle."""
+    cfg = W.scaled(W.C1, n=5000)
+    x = W.vectors(cfg, 0, cfg.n)
+    cent = W.train_centroids(cfg, x)
+    ids = np.arange(cfg.n, dtype=np.int64) * 7 + 3
+    ids[1234] = ids[77]  # two rows under one id
+    p = Pair(x, cent, metric, storage, ids=ids, page_vecs=32, insert_reserve=3000)
+    try:
+        extra = np.concatenate([W.inserts(cfg, b, 50) for b in range(12)])
+        eids = 10 ** 9 + np.arange(len(extra), dtype=np.int64)
+        for s in range(0, 400, 50):
+            p.insert_both(extra[s:s + 50], eids[s:s + 50], where=f"batch {s // 50}")
+        q = W.queries(cfg, 5, 64)
+        rng = np.random.default_rng(5)
+        big = int(np.argmax(p.orc.list_lengths()))
+        gone = np.concatenate([ids[rng.permutation(cfg.n)[:700]], eids[:400:3], [ids[77], -5, 10 ** 15],
+                               p.orc.list_ids(big)])  # the longest list goes entirely
+        pages_before = p.gpu.stats().pages_used
+        n_o = p.orc.delete(gone)
+        n_g = p.gpu.delete(dev(gone))
+        assert n_g == n_o > 700
+        st = p.gpu.stats()
+        assert st.n_total == p.orc.ntotal and st.device_error == 0 and st.pages_used == pages_before
+        assert np.array_equal(p.gpu.list_lengths(), p.orc.list_lengths()) and p.gpu.list_lengths()[big] == 0
+        assert p.gpu.delete(dev(gone)) == 0
+        p.check_search(q, 10, 8, where="after delete")
+        full = p.check_scan(q, 40, np.tile(np.arange(cfg.nlist, dtype=np.int32), (len(q), 1)), where="all lists")
+        # growth after shrinking: the emptied list takes its old pages back, no new page is opened
+        refill = extra[400:440] if storage == F32 else extra[400:440].astype(np.float16).astype(np.float32)
+        forced = np.full(len(refill), big, dtype=np.int32)
+        p.gpu.insert_assigned(dev(refill), dev(forced), dev(eids[400:440]))
+        p.orc.insert(refill, eids[400:440], forced_lists=forced)
+        p.note_inserted(refill)
+        assert p.gpu.stats().pages_used == pages_before and p.gpu.list_lengths()[big] == 40
+        for s in range(440, 600, 40):
+            p.insert_both(extra[s:s + 40], eids[s:s + 40], where=f"batch {s // 40} after delete")
+        assert np.array_equal(p.gpu.list_lengths(), p.orc.list_lengths())
+        p.check_search(q, 10, 8, where="inserts after delete")
+        # update: a surviving id gets a new vector
+        keep = ids[~np.isin(ids, gone)][0]
+        newv = q[3:4] if storage == F32 else q[3:4].astype(np.float16).astype(np.float32)
+        assert p.gpu.delete(dev(np.array([keep]))) == 1 and p.orc.delete(np.array([keep])) == 1
+        p.insert_both(newv, np.array([keep]), where="update")
+        gi, gv = p.gpu.search(dev(q[3:4]), 1, 8)
+        assert int(gi[0, 0]) == keep
+        p.check_search(q, 10, 8, where="after update")
+        # compaction after deletes drops the unused pages
+        p.gpu.compact(B.pk_arena_bytes(p.gpu.cfg, int(p.gpu.stats().n_total), 100))
+        lens = p.gpu.list_lengths()
+        assert p.gpu.stats().pages_used == int(np.sum((lens + 31) // 32)) < pages_before
+        p.check_search(q, 10, 8, where="compacted after deletes")
+    finally:
+        p.close()
+
+
 def test_wide_rows_many_queries_per_list(gpu_device):
     """d = 1536 (config 5 width) with few lists, so lists see more queries than one group holds."""
     cfg = W.scaled(W.C5, n=5000, ncomp=24, nlist=24, zipf_s=1.2)

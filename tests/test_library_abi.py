@@ -57,6 +57,7 @@ def test_host_side_argument_checks_without_gpu(lib):
     assert lib.pk_coarse(null, null, 1, 1, null, null) == B.PK_ERR_BAD_HANDLE
     assert lib.pk_index_free(null) == B.PK_ERR_BAD_HANDLE
     assert lib.pk_index_compact(null, null, 0, null) == B.PK_ERR_BAD_HANDLE
+    assert lib.pk_delete(null, null, 1, None, null) == B.PK_ERR_BAD_HANDLE
     assert lib.pk_kmeans(null, 10, 8, 4, 1, null, null, None, null) == B.PK_ERR_INVALID_ARG
     # a buffer that is not a handle is rejected by the magic check
     fake = (C.c_uint64 * 64)()
