@@ -37,6 +37,9 @@ def lib():
         L.orc_insert.argtypes = [vp, vp, vp, i64, vp, vp]
         L.orc_ntotal.restype = i64
         L.orc_ntotal.argtypes = [vp]
+        L.orc_split.argtypes = [vp, i64, i32]
+        L.orc_nlist.argtypes = [vp]
+        L.orc_centroids.argtypes = [vp, vp]
         L.orc_delete.restype = i64
         L.orc_delete.argtypes = [vp, vp, i64]
         L.orc_list_lengths.argtypes = [vp, vp]
@@ -111,6 +114,18 @@ class Index:
         out = np.empty(m, dtype=np.int32)
         rc = lib().orc_insert(self._h, _ptr(x), _ptr(ids), m, _ptr(forced_lists), _ptr(out))
         assert rc == 0
+        return out
+
+    def split(self, threshold: int, iters: int) -> int:
+        """IVF-Split: lists longer than threshold are split by a 2-means; returns the number of splits."""
+        n = int(lib().orc_split(self._h, int(threshold), int(iters)))
+        assert n >= 0
+        self.nlist = int(lib().orc_nlist(self._h))
+        return n
+
+    def centroids(self):
+        out = np.empty((self.nlist, self.d), dtype=np.float32)
+        assert lib().orc_centroids(self._h, _ptr(out)) == 0
         return out
 
     def delete(self, ids) -> int:

@@ -294,6 +294,98 @@ int64_t orc_delete(orc_index *ix, const int64_t *ids, int64_t m)
     return removed;
 }
 
+/*
+ * IVF-Split (Section 4.4 "on-GPU cluster splitting", Section 6.1 "Pancake-IVF-Split"): a
+ * cluster that has grown past `threshold` vectors is split in two by a light k-means over
+ * its members.  The paper gives no further rule; the reading taken here: lists are examined
+ * in list order, only the lists that exist when the call starts; the two initial centroids
+ * are the member with the smallest id and the member with the largest id (the first such
+ * member in storage order if ids repeat); `iters` Lloyd iterations under L2 exactly as in
+ * orc_kmeans (ties to the first of the two, a side without members keeps its centroid); the
+ * members the last assignment put on the first side stay in the list, whose centroid
+ * becomes the first centroid; the others form a new list appended after the last one, with
+ * the second centroid.  Members keep their relative order.  Returns the number of splits.
+ */
+int orc_split(orc_index *ix, int64_t threshold, int iters)
+{
+    if (!ix || threshold < 1 || iters < 1) return -1;
+    const int d = ix->d, nlist0 = ix->nlist;
+    int nsplit = 0;
+    for (int l = 0; l < nlist0; ++l) {
+        orc_list *L = &ix->lists[l];
+        const int64_t n = L->len;
+        if (n <= threshold) continue;
+        int64_t lo = 0, hi = 0;
+        for (int64_t r = 1; r < n; ++r) {
+            if (L->e[r].id < L->e[lo].id) lo = r;
+            if (L->e[r].id > L->e[hi].id) hi = r;
+        }
+        double *c = (double *)malloc(sizeof(double) * 2 * d), *sum = (double *)malloc(sizeof(double) * 2 * d);
+        int *a = (int *)malloc(sizeof(int) * (size_t)n);
+        if (!c || !sum || !a) return -1;
+        for (int t = 0; t < d; ++t) {
+            c[t] = L->e[lo].vec[t];
+            c[d + t] = L->e[hi].vec[t];
+        }
+        for (int it = 0; it < iters; ++it) {
+            int64_t cnt[2] = {0, 0};
+            memset(sum, 0, sizeof(double) * 2 * d);
+            for (int64_t r = 0; r < n; ++r) {
+                double s0 = 0.0, s1 = 0.0;
+                for (int t = 0; t < d; ++t) {
+                    double u0 = (double)L->e[r].vec[t] - c[t], u1 = (double)L->e[r].vec[t] - c[d + t];
+                    s0 += u0 * u0;
+                    s1 += u1 * u1;
+                }
+                a[r] = s1 < s0 ? 1 : 0;
+                cnt[a[r]]++;
+                for (int t = 0; t < d; ++t) sum[(size_t)a[r] * d + t] += L->e[r].vec[t];
+            }
+            for (int j = 0; j < 2; ++j)
+                if (cnt[j] > 0)
+                    for (int t = 0; t < d; ++t) c[(size_t)j * d + t] = sum[(size_t)j * d + t] / (double)cnt[j];
+        }
+        /* grow the tables by one list */
+        float *nc = (float *)realloc(ix->centroids, sizeof(float) * (size_t)(ix->nlist + 1) * d);
+        if (!nc) return -1;
+        ix->centroids = nc;
+        orc_list *nl = (orc_list *)realloc(ix->lists, sizeof(orc_list) * (size_t)(ix->nlist + 1));
+        if (!nl) return -1;
+        ix->lists = nl;
+        L = &ix->lists[l];
+        orc_list *N = &ix->lists[ix->nlist];
+        memset(N, 0, sizeof(*N));
+        for (int t = 0; t < d; ++t) {
+            ix->centroids[(size_t)l * d + t] = (float)c[t];
+            ix->centroids[(size_t)ix->nlist * d + t] = (float)c[d + t];
+        }
+        int64_t w = 0;
+        for (int64_t r = 0; r < n; ++r) {
+            if (a[r]) {
+                if (list_push(N, L->e[r].id, L->e[r].vec)) return -1;
+            } else {
+                L->e[w++] = L->e[r];
+            }
+        }
+        L->len = w;
+        ix->nlist += 1;
+        ++nsplit;
+        free(c);
+        free(sum);
+        free(a);
+    }
+    return nsplit;
+}
+
+int orc_nlist(const orc_index *ix) { return ix ? ix->nlist : -1; }
+
+int orc_centroids(const orc_index *ix, float *out)
+{
+    if (!ix || !out) return -1;
+    memcpy(out, ix->centroids, sizeof(float) * (size_t)ix->nlist * ix->d);
+    return 0;
+}
+
 int64_t orc_ntotal(const orc_index *ix) { return ix ? ix->ntotal : -1; }
 
 int orc_list_lengths(const orc_index *ix, int64_t *len_out)

@@ -376,6 +376,41 @@ def test_delete_then_search_is_exact_knn_over_what_is_left(metric):
     assert ix.ntotal == 0 and np.all(i3 == -1)
 
 
+def test_split_separates_two_blobs_and_leaves_the_rest_alone():
+    """IVF-Split on a list that holds two well-separated blobs: the closed-form outcome is the blobs
+    themselves, centroids their means; short lists are untouched; nothing is lost; exact search over
+    all lists is unchanged."""
+    rng = np.random.default_rng(70)
+    d = 8
+    a = rng.normal(0.0, 0.05, (300, d)).astype(np.float32) + 5.0
+    b = rng.normal(0.0, 0.05, (200, d)).astype(np.float32) - 5.0
+    far = rng.normal(0.0, 0.05, (40, d)).astype(np.float32) + np.float32(40.0)
+    x = np.concatenate([a, b, far])
+    order = rng.permutation(len(x))
+    x, tag = x[order], np.concatenate([np.zeros(300), np.ones(200), np.full(40, 2)])[order]
+    cent = np.stack([np.zeros(d, np.float32), np.full(d, 40.0, np.float32)])  # list 0 gets both blobs
+    ix = oracle.Index(cent, oracle.L2)
+    ix.build(x)
+    assert list(ix.list_lengths()) == [500, 40]
+    q = rng.normal(0.0, 3.0, (20, d)).astype(np.float32)
+    before = ix.search(q, 15, 2)
+    assert ix.split(100, 5) == 1 and ix.nlist == 3 and ix.ntotal == 540
+    ids0, ids2 = set(ix.list_ids(0).tolist()), set(ix.list_ids(2).tolist())
+    blob_a, blob_b = set(np.nonzero(tag == 0)[0].tolist()), set(np.nonzero(tag == 1)[0].tolist())
+    assert {frozenset(ids0), frozenset(ids2)} == {frozenset(blob_a), frozenset(blob_b)}
+    assert set(ix.list_ids(1).tolist()) == set(np.nonzero(tag == 2)[0].tolist())
+    c = ix.centroids()
+    for l, members in ((0, ids0), (2, ids2)):
+        np.testing.assert_allclose(c[l], x[sorted(members)].astype(np.float64).mean(0), rtol=1e-6)
+    np.testing.assert_array_equal(c[1], cent[1])
+    # the side that holds the smallest id stays in the old list; storage order is kept
+    assert min(ids0) == 0 and list(ix.list_ids(0)) == sorted(ids0) and list(ix.list_ids(2)) == sorted(ids2)
+    after = ix.search(q, 15, 3)
+    assert np.array_equal(before[0], after[0]) and np.array_equal(before[1], after[1])
+    assert ix.split(100, 5) == 2 and ix.nlist == 5  # both blobs are still over the threshold and split again
+    assert ix.split(1000, 5) == 0 and ix.nlist == 5 and ix.ntotal == 540
+
+
 @pytest.mark.parametrize("metric", [oracle.IP, oracle.L2])
 def test_short_rows_are_padded(metric):
     x, q, c, _ = _small(11, n=30, nlist=6)
