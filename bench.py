@@ -255,12 +255,26 @@ class Scenario:
         ix.arenas = [new_arena]
         after = ms_per_step()
         self.check_errors()
+        # IVF-Split: lists over 8 x the mean length are split by a 2-means on the device
+        thr = int(8 * st.n_total / cfg.nlist)
+        arena2 = torch.empty(nbytes + (64 << 20), dtype=torch.uint8, device="cuda")
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        n_split = B.pk_index_split(ix.handle, arena2, thr, 4)
+        split_ms = (time.perf_counter() - t0) * 1e3
+        ix.arenas = [arena2]
+        ix.nlist += n_split
+        ix.cfg.nlist = ix.nlist
+        del new_arena
+        after_split = ms_per_step()
+        self.check_errors()
         copied = int(st.pages_used) * page_bytes
         return {"extra_inserts": extra_inserts, "deleted": n_del, "delete_ms_per_4088_ids": del_ms,
                 "ids_scanned_per_s": float(st.n_total + n_del) / (del_ms * 1e-3), "n_total": int(st.n_total), "arenas_before": int(st.n_arenas),
                 "compaction_ms": dt * 1e3, "bytes_copied": copied,
                 "copy_GBps_read_plus_write": 2 * copied / dt / 1e9, "ms_per_step_before": before,
-                "ms_per_step_after": after}
+                "ms_per_step_after": after, "split_threshold": thr, "lists_split": n_split, "split_ms": split_ms,
+                "ms_per_step_after_split": after_split}
 
     def scope_union(self, steps=30):
         """One agent's query batch searched across the memories of ALL agents of the workload

@@ -163,6 +163,33 @@ int pk_insert(pk_index *index, const float *vectors, const int64_t *ids, int64_t
               void *stream);
 
 /*
+ * Section 4.4 (on-GPU cluster splitting) / Section 6.1 (the IVF-Split variant): a cluster
+ * that has grown past `threshold` vectors is split in two by a light k-means over its
+ * members, run on the device.  Done together with a compaction, because the number of
+ * lists changes: the index moves into `arena` as in pk_index_compact, and every list that
+ * is longer than `threshold` when the call starts is first split: 2-means under squared
+ * L2 over its stored vectors (initial centroids: the member with the smallest id and the
+ * member with the largest id; `iters` Lloyd iterations as in pk_kmeans), the members of
+ * the first side stay in the list, whose centroid becomes the first centroid, the others
+ * form a new list appended after the last one (list numbers nlist, nlist + 1, ... in the
+ * order of the lists they came from) with the second centroid.  cfg.nlist grows by the
+ * number of splits; all other lists and centroids are unchanged.
+ *   n_split  HOST, optional: receives the number of lists split
+ * Synchronises `stream`; on return the former arenas are no longer referenced.
+ * PK_ERR_NOMEM if `arena` cannot hold the index with its new tables (the index is unchanged).
+ */
+int pk_index_split(pk_index *index, void *arena, size_t arena_bytes, int64_t threshold, int32_t iters,
+                   int32_t *n_split, void *stream);
+
+/* Read-back for callers that keep their own copy of the clustering (tests, after a split).
+ *   pk_index_centroids  out: DEVICE [nlist, d] float32, the current centroid table
+ *   pk_list_ids         out: DEVICE [cap] int64, receives the ids of the first min(cap, length)
+ *                       members of `list` in storage order (lengths: pk_list_lengths)
+ * Asynchronous. */
+int pk_index_centroids(pk_index *index, float *out, void *stream);
+int pk_list_ids(pk_index *index, int32_t list, int64_t *out, int64_t cap, void *stream);
+
+/*
  * Section 5 (the interface offers search, insert, delete and update).  Every stored vector
  * whose id is among ids[0..m) is removed, all of them if several carry the id; ids nobody
  * carries are ignored.  A removed row is overwritten by the last row of its list and the

@@ -21,7 +21,7 @@ PK_OK = 0
 PK_ERR_INVALID_ARG, PK_ERR_BAD_HANDLE, PK_ERR_DIM_MISMATCH, PK_ERR_NOMEM, PK_ERR_HIP, PK_ERR_UNSUPPORTED = (
     -1, -2, -3, -4, -5, -6)
 
-EXPORTS = ["pk_search_union", "pk_delete", "pk_arena_bytes", "pk_index_build", "pk_index_add_arena", "pk_index_compact", "pk_kmeans", "pk_insert", "pk_insert_assigned", "pk_search",
+EXPORTS = ["pk_search_union", "pk_delete", "pk_index_split", "pk_index_centroids", "pk_list_ids", "pk_arena_bytes", "pk_index_build", "pk_index_add_arena", "pk_index_compact", "pk_kmeans", "pk_insert", "pk_insert_assigned", "pk_search",
            "pk_search_multi", "pk_coarse", "pk_scan_probes", "pk_index_stats", "pk_list_lengths", "pk_profile_begin",
            "pk_profile_end", "pk_index_free", "pk_strerror"]
 
@@ -65,6 +65,9 @@ def lib():
         L.pk_index_build.argtypes = [C.POINTER(pk_config), vp, vp, vp, i64, vp, C.c_size_t, vp, C.POINTER(vp)]
         L.pk_index_add_arena.argtypes = [vp, vp, C.c_size_t, vp]
         L.pk_index_compact.argtypes = [vp, vp, C.c_size_t, vp]
+        L.pk_index_split.argtypes = [vp, vp, C.c_size_t, i64, i32, C.POINTER(i32), vp]
+        L.pk_index_centroids.argtypes = [vp, vp, vp]
+        L.pk_list_ids.argtypes = [vp, i32, vp, i64, vp]
         L.pk_kmeans.argtypes = [vp, i64, i32, i32, i32, vp, vp, C.POINTER(C.c_double), vp]
         L.pk_insert.argtypes = [vp, vp, vp, i64, vp, vp]
         L.pk_insert_assigned.argtypes = [vp, vp, vp, i64, vp, vp]
@@ -137,6 +140,21 @@ def pk_kmeans(vectors, centroids, iters: int, assign_out=None):
                            _dev(centroids, torch.float32, "centroids"), _dev(assign_out, torch.int32, "assign_out"),
                            inertia, _stream()), "pk_kmeans")
     return [float(v) for v in inertia]
+
+
+def pk_index_split(handle: int, arena, threshold: int, iters: int) -> int:
+    n = C.c_int32(0)
+    _check(lib().pk_index_split(handle, _dev(arena, torch.uint8, "arena"), arena.numel(), threshold, iters,
+                                C.byref(n), _stream()), "pk_index_split")
+    return int(n.value)
+
+
+def pk_index_centroids(handle: int, out):
+    _check(lib().pk_index_centroids(handle, _dev(out, torch.float32, "out"), _stream()), "pk_index_centroids")
+
+
+def pk_list_ids(handle: int, lst: int, out):
+    _check(lib().pk_list_ids(handle, lst, _dev(out, torch.int64, "out"), out.numel(), _stream()), "pk_list_ids")
 
 
 def pk_delete(handle: int, ids) -> int:
@@ -248,6 +266,26 @@ class Index:
         out = torch.empty(vectors.shape[0], dtype=torch.int32, device=self.device) if want_lists else None
         pk_insert(self.handle, vectors, ids, out)
         return out
+
+    def split(self, threshold: int, iters: int, nbytes: int) -> int:
+        """IVF-Split into one new arena of nbytes; returns the number of lists split (nlist grows by it)."""
+        t = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        n = pk_index_split(self.handle, t, threshold, iters)
+        self.arenas = [t]
+        self.nlist += n
+        self.cfg.nlist = self.nlist
+        return n
+
+    def centroids(self):
+        out = torch.empty((self.nlist, self.d), dtype=torch.float32, device=self.device)
+        pk_index_centroids(self.handle, out)
+        return out
+
+    def list_ids(self, lst: int):
+        n = int(self.list_lengths()[lst])
+        out = torch.empty(max(n, 1), dtype=torch.int64, device=self.device)
+        pk_list_ids(self.handle, lst, out[:n])
+        return out[:n]
 
     def delete(self, ids) -> int:
         return pk_delete(self.handle, ids)

@@ -991,7 +991,8 @@ int pk_kmeans(const float *vectors, int64_t n, int32_t d, int32_t nlist, int32_t
     const size_t abytes = pk_arena_bytes(&cfg, 0, 0);
     char *scratch = nullptr;
     const size_t nl4 = round_up((size_t)nlist * 4, 256), n4 = round_up((size_t)n * 4, 256);
-    const size_t sbytes = round_up(abytes, 256) + 3 * nl4 + 2 * n4 + round_up((size_t)iters * 8, 256);
+    const size_t sums8 = round_up((size_t)nlist * d * 8, 256), sq8 = round_up((size_t)nlist * 8, 256);
+    const size_t sbytes = round_up(abytes, 256) + 3 * nl4 + 2 * n4 + round_up((size_t)iters * 8, 256) + sums8 + sq8;
     if (hipMalloc(reinterpret_cast<void **>(&scratch), sbytes) != hipSuccess) {
         (void)hipGetLastError();
         return PK_ERR_NOMEM;
@@ -1010,6 +1011,8 @@ int pk_kmeans(const float *vectors, int64_t n, int32_t d, int32_t nlist, int32_t
     ka.members = reinterpret_cast<uint32_t *>(p + 3 * nl4);
     int32_t *assign = reinterpret_cast<int32_t *>(p + 3 * nl4 + n4);
     double *inertia = reinterpret_cast<double *>(p + 3 * nl4 + 2 * n4);
+    ka.sums = reinterpret_cast<double *>(p + 3 * nl4 + 2 * n4 + round_up((size_t)iters * 8, 256));
+    ka.sq = reinterpret_cast<double *>(p + 3 * nl4 + 2 * n4 + round_up((size_t)iters * 8, 256) + sums8);
     ka.x = vectors;
     ka.assign = assign;
     ka.n = n;
@@ -1050,14 +1053,27 @@ int pk_kmeans(const float *vectors, int64_t n, int32_t d, int32_t nlist, int32_t
     return rc;
 }
 
-int pk_index_compact(pk_index *ix, void *arena, size_t arena_bytes, void *stream)
+namespace {
+
+// one list that is being split: its 2-means result
+struct SplitJob {
+    int list;              // the list (keeps side 0); the new list is nlist_old + (position of the job)
+    uint32_t len, len_new; // members before the split, members that move to the new list
+    int32_t *side;         // DEVICE [len] 0 / 1
+    float *cent2;          // DEVICE [2][d] the two centroids
+};
+
+// Moves the index into `arena`, every list in one contiguous extent.  threshold > 0: lists
+// longer than that are split by a 2-means over their members first (the new lists are
+// appended after the last one).
+int relayout(pk_index *ix, void *arena, size_t arena_bytes, int64_t threshold, int iters, int32_t *n_split_out,
+             hipStream_t s)
 {
     if (!live(ix)) return PK_ERR_BAD_HANDLE;
     if (!arena || reinterpret_cast<uintptr_t>(arena) % 256 != 0) return PK_ERR_INVALID_ARG;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const pk_config *cfg = &ix->cfg;
-    const Dims x = dims_of(cfg);
-    if (arena_bytes < x.header + 1024 + x.page_stride) return PK_ERR_NOMEM;
+    if (n_split_out) *n_split_out = 0;
+    const pk_config old_cfg = ix->cfg;
+    const int d = old_cfg.d, nlist0 = old_cfg.nlist;
     for (int a = 0; a < ix->host.n_arenas; ++a)
         if (ix->host.arenas[a].vec >= static_cast<char *>(arena) &&
             ix->host.arenas[a].vec < static_cast<char *>(arena) + arena_bytes)
@@ -1065,35 +1081,163 @@ int pk_index_compact(pk_index *ix, void *arena, size_t arena_bytes, void *stream
     // exact list lengths decide the new extents
     PK_HIP(hipStreamSynchronize(s));
     PK_TRY(settle_pages(ix));
-    std::vector<uint32_t> len((size_t)cfg->nlist), mbase((size_t)cfg->nlist), mpages((size_t)cfg->nlist);
+    std::vector<uint32_t> len((size_t)nlist0);
     PK_HIP(hipMemcpy(len.data(), ix->host.list_len, len.size() * 4, hipMemcpyDeviceToHost));
+
+    // ---- 2-means of the lists to split (Section 4.4: a light k-means on the device)
+    std::vector<SplitJob> jobs;
+    std::vector<void *> owned; // device scratch freed on every way out
+    auto release = [&]() {
+        for (void *p : owned) (void)hipFree(p);
+        owned.clear();
+    };
+    auto fail = [&](int code) {
+        (void)hipStreamSynchronize(s);
+        release();
+        return code;
+    };
+    if (threshold > 0) {
+        uint32_t longest = 0;
+        for (int l = 0; l < nlist0; ++l)
+            if ((int64_t)len[l] > threshold) longest = std::max(longest, len[l]);
+        float *rows = nullptr;
+        int64_t *ids = nullptr;
+        if (longest > 0) {
+            if (hipMalloc(reinterpret_cast<void **>(&rows), (size_t)longest * d * sizeof(float)) != hipSuccess)
+                return fail(PK_ERR_NOMEM);
+            owned.push_back(rows);
+            if (hipMalloc(reinterpret_cast<void **>(&ids), (size_t)longest * sizeof(int64_t)) != hipSuccess)
+                return fail(PK_ERR_NOMEM);
+            owned.push_back(ids);
+        }
+        std::vector<int64_t> hid;
+        std::vector<int32_t> hside;
+        for (int l = 0; l < nlist0; ++l) {
+            if ((int64_t)len[l] <= threshold) continue;
+            if (nlist0 + (int)jobs.size() + 1 > 0x3fffffff) return fail(PK_ERR_UNSUPPORTED);
+            SplitJob j{};
+            j.list = l;
+            j.len = len[l];
+            if (hipMalloc(reinterpret_cast<void **>(&j.side), (size_t)j.len * sizeof(int32_t)) != hipSuccess)
+                return fail(PK_ERR_NOMEM);
+            owned.push_back(j.side);
+            if (hipMalloc(reinterpret_cast<void **>(&j.cent2), (size_t)2 * d * sizeof(float)) != hipSuccess)
+                return fail(PK_ERR_NOMEM);
+            owned.push_back(j.cent2);
+            if (launch_gather_list(ix->dev, (uint32_t)l, j.len, rows, ids, s) != hipSuccess) return fail(PK_ERR_HIP);
+            // initial centroids: the member with the smallest id and the member with the largest id
+            hid.resize(j.len);
+            if (hipMemcpyAsync(hid.data(), ids, (size_t)j.len * sizeof(int64_t), hipMemcpyDeviceToHost, s) != hipSuccess ||
+                hipStreamSynchronize(s) != hipSuccess)
+                return fail(PK_ERR_HIP);
+            size_t lo = 0, hi = 0;
+            for (size_t r = 1; r < hid.size(); ++r) {
+                if (hid[r] < hid[lo]) lo = r;
+                if (hid[r] > hid[hi]) hi = r;
+            }
+            if (hipMemcpyAsync(j.cent2, rows + lo * d, (size_t)d * sizeof(float), hipMemcpyDeviceToDevice, s) != hipSuccess ||
+                hipMemcpyAsync(j.cent2 + d, rows + hi * d, (size_t)d * sizeof(float), hipMemcpyDeviceToDevice, s) != hipSuccess)
+                return fail(PK_ERR_HIP);
+            const int rc = pk_kmeans(rows, j.len, d, 2, iters, j.cent2, j.side, nullptr, s);
+            if (rc != PK_OK) return fail(rc);
+            hside.resize(j.len);
+            if (hipMemcpy(hside.data(), j.side, (size_t)j.len * sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess)
+                return fail(PK_ERR_HIP);
+            uint32_t ones = 0;
+            for (int32_t v : hside) ones += v != 0;
+            j.len_new = ones;
+            jobs.push_back(j);
+        }
+    }
+    const int ns = (int)jobs.size(), nlist1 = nlist0 + ns;
+
+    // ---- new layout
+    pk_config cfg = old_cfg;
+    cfg.nlist = nlist1;
+    const Dims x = dims_of(&cfg);
+    if (arena_bytes < x.header + 1024 + x.page_stride) return fail(PK_ERR_NOMEM);
+    std::vector<uint32_t> nlen((size_t)nlist1), mbase((size_t)nlist1), mpages((size_t)nlist1);
+    std::vector<uint8_t> skip((size_t)nlist1, 0);
+    for (int l = 0; l < nlist0; ++l) nlen[l] = len[l];
+    for (int t = 0; t < ns; ++t) {
+        nlen[jobs[t].list] = jobs[t].len - jobs[t].len_new;
+        nlen[nlist0 + t] = jobs[t].len_new;
+        skip[jobs[t].list] = skip[nlist0 + t] = 1;
+    }
     uint64_t used = 0;
-    for (int l = 0; l < cfg->nlist; ++l) {
+    for (int l = 0; l < nlist1; ++l) {
         mbase[l] = (uint32_t)used;
-        mpages[l] = (len[l] + x.P - 1) / x.P;
+        mpages[l] = (nlen[l] + x.P - 1) / x.P;
         used += mpages[l];
     }
     DevIndex N;
     DevIndex *ndev = nullptr;
     uint32_t npages = 0;
     float *cent = nullptr, *cnorm = nullptr;
-    place_header(N, &ndev, &npages, &cent, &cnorm, cfg, static_cast<char *>(arena), arena_bytes, x);
-    if (used > npages) return PK_ERR_NOMEM;
+    place_header(N, &ndev, &npages, &cent, &cnorm, &cfg, static_cast<char *>(arena), arena_bytes, x);
+    if (used > npages) return fail(PK_ERR_NOMEM);
     const DevIndex &O = ix->host;
     const uint32_t head[3] = {(uint32_t)used, 0u, npages};
-    PK_HIP(hipMemcpyAsync(ndev, &N, sizeof(N), hipMemcpyHostToDevice, s));
-    PK_HIP(hipMemcpyAsync(cent, O.cent, (size_t)x.nlist_pad * x.dpad32 * sizeof(float), hipMemcpyDeviceToDevice, s));
-    PK_HIP(hipMemcpyAsync(cnorm, O.cnorm, (size_t)x.nlist_pad * sizeof(float), hipMemcpyDeviceToDevice, s));
-    PK_HIP(hipMemcpyAsync(N.list_len, len.data(), len.size() * 4, hipMemcpyHostToDevice, s));
-    PK_HIP(hipMemcpyAsync(N.main_base, mbase.data(), mbase.size() * 4, hipMemcpyHostToDevice, s));
-    PK_HIP(hipMemcpyAsync(N.main_pages, mpages.data(), mpages.size() * 4, hipMemcpyHostToDevice, s));
-    PK_HIP(launch_fill_u32(N.dtab, 0xffffffffu, (size_t)cfg->nlist * x.max_dp, s));
-    PK_HIP(hipMemcpyAsync(N.ctr, O.ctr, 16 * sizeof(uint32_t), hipMemcpyDeviceToDevice, s)); // keeps the sticky error flags
-    PK_HIP(hipMemcpyAsync(N.ctr, head, 4, hipMemcpyHostToDevice, s));
-    PK_HIP(hipMemcpyAsync(N.ctr + 2, head + 2, 4, hipMemcpyHostToDevice, s));
-    PK_HIP(hipMemcpyAsync(N.stats, O.stats, 8 * sizeof(unsigned long long), hipMemcpyDeviceToDevice, s));
-    PK_HIP(launch_compact_pages(ix->dev, ndev, (uint32_t)used, s));
-    PK_HIP(hipStreamSynchronize(s)); // the old arenas are out of use from here on
+    auto enqueue = [&]() -> int {
+        PK_HIP(hipMemcpyAsync(ndev, &N, sizeof(N), hipMemcpyHostToDevice, s));
+        if (ns == 0) {
+            PK_HIP(hipMemcpyAsync(cent, O.cent, (size_t)x.nlist_pad * x.dpad32 * sizeof(float), hipMemcpyDeviceToDevice, s));
+            PK_HIP(hipMemcpyAsync(cnorm, O.cnorm, (size_t)x.nlist_pad * sizeof(float), hipMemcpyDeviceToDevice, s));
+        } else {
+            // dense copy of the centroids, the split lists' rows replaced, the new lists' rows appended,
+            // then laid out again (padding, squared norms)
+            float *dense = nullptr;
+            if (hipMalloc(reinterpret_cast<void **>(&dense), (size_t)nlist1 * d * sizeof(float)) != hipSuccess) {
+                (void)hipGetLastError();
+                return PK_ERR_NOMEM;
+            }
+            owned.push_back(dense);
+            PK_HIP(hipMemcpy2DAsync(dense, (size_t)d * sizeof(float), O.cent, (size_t)ix->dpad32 * sizeof(float),
+                                    (size_t)d * sizeof(float), (size_t)nlist0, hipMemcpyDeviceToDevice, s));
+            for (int t = 0; t < ns; ++t) {
+                PK_HIP(hipMemcpyAsync(dense + (size_t)jobs[t].list * d, jobs[t].cent2, (size_t)d * sizeof(float),
+                                      hipMemcpyDeviceToDevice, s));
+                PK_HIP(hipMemcpyAsync(dense + (size_t)(nlist0 + t) * d, jobs[t].cent2 + d, (size_t)d * sizeof(float),
+                                      hipMemcpyDeviceToDevice, s));
+            }
+            PK_HIP(launch_store_centroids(dense, nlist1, d, x.dpad32, x.nlist_pad, cfg.metric, cent, cnorm, s));
+        }
+        PK_HIP(hipMemcpyAsync(N.list_len, nlen.data(), nlen.size() * 4, hipMemcpyHostToDevice, s));
+        PK_HIP(hipMemcpyAsync(N.main_base, mbase.data(), mbase.size() * 4, hipMemcpyHostToDevice, s));
+        PK_HIP(hipMemcpyAsync(N.main_pages, mpages.data(), mpages.size() * 4, hipMemcpyHostToDevice, s));
+        PK_HIP(launch_fill_u32(N.dtab, 0xffffffffu, (size_t)nlist1 * x.max_dp, s));
+        PK_HIP(hipMemcpyAsync(N.ctr, O.ctr, 16 * sizeof(uint32_t), hipMemcpyDeviceToDevice, s)); // keeps the sticky error flags
+        PK_HIP(hipMemcpyAsync(N.ctr, head, 4, hipMemcpyHostToDevice, s));
+        PK_HIP(hipMemcpyAsync(N.ctr + 2, head + 2, 4, hipMemcpyHostToDevice, s));
+        PK_HIP(hipMemcpyAsync(N.stats, O.stats, 8 * sizeof(unsigned long long), hipMemcpyDeviceToDevice, s));
+        uint8_t *dskip = nullptr;
+        if (ns > 0) {
+            if (hipMalloc(reinterpret_cast<void **>(&dskip), skip.size()) != hipSuccess) {
+                (void)hipGetLastError();
+                return PK_ERR_NOMEM;
+            }
+            owned.push_back(dskip);
+            PK_HIP(hipMemcpyAsync(dskip, skip.data(), skip.size(), hipMemcpyHostToDevice, s));
+        }
+        PK_HIP(launch_compact_pages(ix->dev, ndev, (uint32_t)used, dskip, s));
+        for (int t = 0; t < ns; ++t) {
+            uint32_t *slot = nullptr;
+            if (hipMalloc(reinterpret_cast<void **>(&slot), (size_t)jobs[t].len * sizeof(uint32_t)) != hipSuccess) {
+                (void)hipGetLastError();
+                return PK_ERR_NOMEM;
+            }
+            owned.push_back(slot);
+            PK_HIP(launch_split_list(ix->dev, ndev, (uint32_t)jobs[t].list, (uint32_t)(nlist0 + t), jobs[t].side, slot,
+                                     jobs[t].len, s));
+        }
+        PK_HIP(hipStreamSynchronize(s)); // the old arenas are out of use from here on
+        return PK_OK;
+    };
+    const int rc = enqueue();
+    if (rc != PK_OK) return fail(rc);
+    release();
+    ix->cfg = cfg;
+    ix->nlist_pad = x.nlist_pad;
     ix->host = N;
     ix->dev = ndev;
     ix->pages_total = npages;
@@ -1101,8 +1245,44 @@ int pk_index_compact(pk_index *ix, void *arena, size_t arena_bytes, void *stream
     ix->pages_known = (uint32_t)used;
     ix->inserted_at_known = ix->n_inserted;
     ix->inserted_at_top = ix->n_inserted;
-    std::sort(len.begin(), len.end(), [](uint32_t a, uint32_t b) { return a > b; });
-    for (int j = 0; j < cfg->nlist; ++j) ix->top_len[j + 1] = ix->top_len[j] + len[j];
+    std::sort(nlen.begin(), nlen.end(), [](uint32_t a, uint32_t b) { return a > b; });
+    ix->top_len.assign((size_t)nlist1 + 1, 0);
+    for (int j = 0; j < nlist1; ++j) ix->top_len[j + 1] = ix->top_len[j] + nlen[j];
+    if (n_split_out) *n_split_out = ns;
+    return PK_OK;
+}
+
+} // namespace
+
+int pk_index_compact(pk_index *ix, void *arena, size_t arena_bytes, void *stream)
+{
+    return relayout(ix, arena, arena_bytes, 0, 0, nullptr, static_cast<hipStream_t>(stream));
+}
+
+int pk_index_split(pk_index *ix, void *arena, size_t arena_bytes, int64_t threshold, int32_t iters, int32_t *n_split,
+                   void *stream)
+{
+    if (threshold < 1 || iters < 1) return live(ix) ? PK_ERR_INVALID_ARG : PK_ERR_BAD_HANDLE;
+    return relayout(ix, arena, arena_bytes, threshold, iters, n_split, static_cast<hipStream_t>(stream));
+}
+
+int pk_index_centroids(pk_index *ix, float *out, void *stream)
+{
+    if (!live(ix)) return PK_ERR_BAD_HANDLE;
+    if (!out) return PK_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    PK_HIP(hipMemcpy2DAsync(out, (size_t)ix->cfg.d * sizeof(float), ix->host.cent, (size_t)ix->dpad32 * sizeof(float),
+                            (size_t)ix->cfg.d * sizeof(float), (size_t)ix->cfg.nlist, hipMemcpyDeviceToDevice, s));
+    return PK_OK;
+}
+
+int pk_list_ids(pk_index *ix, int32_t list, int64_t *out, int64_t cap, void *stream)
+{
+    if (!live(ix)) return PK_ERR_BAD_HANDLE;
+    if (list < 0 || list >= ix->cfg.nlist || cap < 0 || (cap > 0 && !out)) return PK_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t most = std::min<int64_t>(cap, std::max<int64_t>(ix->n_total, 0)); // no list is longer than the index
+    PK_HIP(launch_gather_list(ix->dev, (uint32_t)list, (uint32_t)std::min<int64_t>(most, 0x7fffffff), nullptr, out, s));
     return PK_OK;
 }
 

@@ -325,7 +325,8 @@ hipError_t launch_delete(const DevIndex *ix, int nlist, const int64_t *ids, int 
 // contains it; its rows, norms and ids are copied from wherever the old layout keeps that
 // logical page (build-time extent or delta page, any arena).  Positions inside a list do
 // not change.
-__global__ __launch_bounds__(256) void compact_pages_kernel(const DevIndex *srcp, const DevIndex *dstp)
+__global__ __launch_bounds__(256) void compact_pages_kernel(const DevIndex *srcp, const DevIndex *dstp,
+                                                            const uint8_t *skip)
 {
     __shared__ uint32_t s_list;
     const DevIndex &src = *srcp, &dst = *dstp;
@@ -343,6 +344,8 @@ __global__ __launch_bounds__(256) void compact_pages_kernel(const DevIndex *srcp
     }
     __syncthreads();
     const uint32_t l = s_list;
+    // lists the caller fills itself (split lists and the lists they give rise to)
+    if (l >= (uint32_t)src.nlist || (skip && skip[l])) return;
     const uint32_t lp = pg - dst.main_base[l];
     const uint32_t P = (uint32_t)dst.P;
     const uint32_t len = dst.list_len[l];
@@ -362,10 +365,90 @@ __global__ __launch_bounds__(256) void compact_pages_kernel(const DevIndex *srcp
     }
 }
 
-hipError_t launch_compact_pages(const DevIndex *src, const DevIndex *dst, uint32_t new_pages, hipStream_t s)
+hipError_t launch_compact_pages(const DevIndex *src, const DevIndex *dst, uint32_t new_pages, const uint8_t *skip,
+                                hipStream_t s)
 {
     if (new_pages == 0) return hipSuccess;
-    hipLaunchKernelGGL(compact_pages_kernel, dim3(new_pages), dim3(256), 0, s, src, dst);
+    hipLaunchKernelGGL(compact_pages_kernel, dim3(new_pages), dim3(256), 0, s, src, dst, skip);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ list read-back and split
+
+// one wave per member of list l: the stored row as fp32 [d] (rows may be NULL) and its id (ids may be NULL)
+__global__ __launch_bounds__(256) void gather_list_kernel(const DevIndex *ixp, uint32_t l, uint32_t limit, float *rows,
+                                                          int64_t *ids)
+{
+    const DevIndex &ix = *ixp;
+    const uint32_t r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= ix.list_len[l] || r >= limit) return;
+    size_t local;
+    const Arena &ar = locate(ix, l, r, local);
+    const int lane = threadIdx.x & 63;
+    if (rows) {
+        const char *src = ar.vec + local * (size_t)ix.row_bytes;
+        for (int i = lane; i < ix.d; i += 64)
+            rows[(size_t)r * ix.d + i] = ix.storage == PK_F16 ? (float)reinterpret_cast<const _Float16 *>(src)[i]
+                                                               : reinterpret_cast<const float *>(src)[i];
+    }
+    if (ids && lane == 0) ids[r] = ar.ids[local];
+}
+
+hipError_t launch_gather_list(const DevIndex *ix, uint32_t l, uint32_t len, float *rows, int64_t *ids, hipStream_t s)
+{
+    if (len == 0) return hipSuccess;
+    hipLaunchKernelGGL(gather_list_kernel, dim3((len + 3) / 4), dim3(256), 0, s, ix, l, len, rows, ids);
+    return hipGetLastError();
+}
+
+// Stable partition of a list by side[r] in {0, 1}: slot[r] = number of earlier members on the
+// same side (one workgroup walks the list)
+__global__ __launch_bounds__(1024) void split_slots_kernel(const int32_t *side, uint32_t len, uint32_t *slot)
+{
+    __shared__ uint32_t s_wave[17];
+    __shared__ uint32_t s_in[1024], s_out[1024];
+    uint32_t ones = 0;
+    for (uint32_t base = 0; base < len; base += 1024) {
+        const uint32_t r = base + threadIdx.x;
+        const uint32_t b = r < len && side[r] != 0 ? 1u : 0u;
+        s_in[threadIdx.x] = b;
+        __syncthreads();
+        const uint32_t n = len - base < 1024u ? len - base : 1024u;
+        const uint32_t total = block_exscan(s_in, s_out, n, s_wave);
+        if (r < len) slot[r] = b ? ones + s_out[threadIdx.x] : r - (ones + s_out[threadIdx.x]);
+        ones += total;
+        __syncthreads();
+    }
+}
+
+// one wave per member of list l of the old layout: to slot[r] of list l (side 0) or of list lnew (side 1)
+// of the new layout, stored bytes, norm and id unchanged
+__global__ __launch_bounds__(256) void split_scatter_kernel(const DevIndex *srcp, const DevIndex *dstp, uint32_t l,
+                                                            uint32_t lnew, const int32_t *side, const uint32_t *slot,
+                                                            uint32_t len)
+{
+    const DevIndex &src = *srcp, &dst = *dstp;
+    const uint32_t r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= len) return;
+    size_t ls, ld;
+    const Arena &as = locate(src, l, r, ls);
+    const Arena &ad = locate(dst, side[r] ? lnew : l, slot[r], ld);
+    const int lane = threadIdx.x & 63, row_bytes = src.row_bytes;
+    const uint4 *from = reinterpret_cast<const uint4 *>(as.vec + ls * (size_t)row_bytes);
+    uint4 *to = reinterpret_cast<uint4 *>(ad.vec + ld * (size_t)row_bytes);
+    for (int i = lane; i < row_bytes / 16; i += 64) to[i] = from[i];
+    if (lane == 0) {
+        ad.norm[ld] = as.norm[ls];
+        ad.ids[ld] = as.ids[ls];
+    }
+}
+
+hipError_t launch_split_list(const DevIndex *src, const DevIndex *dst, uint32_t l, uint32_t lnew, const int32_t *side,
+                             uint32_t *slot, uint32_t len, hipStream_t s)
+{
+    if (len == 0) return hipSuccess;
+    hipLaunchKernelGGL(split_slots_kernel, dim3(1), dim3(1024), 0, s, side, len, slot);
+    hipLaunchKernelGGL(split_scatter_kernel, dim3((len + 3) / 4), dim3(256), 0, s, src, dst, l, lnew, side, slot, len);
     return hipGetLastError();
 }
 

@@ -313,7 +313,14 @@ constexpr int kDeleteChunk = 4096;
 hipError_t launch_delete(const DevIndex *ix, int nlist, const int64_t *ids, int m, int64_t *sorted,
                          unsigned long long *removed, hipStream_t s);
 // copies every list into the contiguous extents of `dst` (dst's tables are already in place)
-hipError_t launch_compact_pages(const DevIndex *src, const DevIndex *dst, uint32_t new_pages, hipStream_t s);
+// (skip: optional [dst nlist] flags of lists the caller fills itself; lists beyond src's are skipped too)
+hipError_t launch_compact_pages(const DevIndex *src, const DevIndex *dst, uint32_t new_pages, const uint8_t *skip,
+                                hipStream_t s);
+// the first min(len, length of list l) members of list l as dense fp32 rows [.][d] and / or their ids
+hipError_t launch_gather_list(const DevIndex *ix, uint32_t l, uint32_t len, float *rows, int64_t *ids, hipStream_t s);
+// list l of src split by side[r]: side 0 stays list l of dst, side 1 becomes list lnew of dst (slot: scratch [len])
+hipError_t launch_split_list(const DevIndex *src, const DevIndex *dst, uint32_t l, uint32_t lnew, const int32_t *side,
+                             uint32_t *slot, uint32_t len, hipStream_t s);
 // k-means update step (Lloyd): members of every cluster gathered, then one workgroup per cluster
 struct KmeansArgs {
     const float *x;        // [n][d] training rows
@@ -323,6 +330,8 @@ struct KmeansArgs {
     uint32_t *cnt, *start, *fill; // [nlist] each (scratch)
     uint32_t *members;     // [n] row numbers in cluster-major order (scratch)
     float *centroids;      // [nlist][d] in: centroids the assignment used; out: means of the members
+    double *sums;          // [nlist][d] scratch: per-cluster totals
+    double *sq;            // [nlist] scratch: per-cluster totals of |x|^2
     double *inertia;       // one word: receives the sum of squared distances of the assignment
 };
 hipError_t launch_kmeans_update(const KmeansArgs &a, hipStream_t s);

@@ -431,6 +431,67 @@ def test_delete_update_and_page_reuse(gpu_device, storage, metric):
         p.close()
 
 
+@pytest.mark.parametrize("storage,metric", [(F32, L2), (F16, IP)])
+def test_ivf_split(gpu_device, storage, metric):
+    """Lists over the threshold are split by a 2-means on the device.  Against the oracle's own split:
+    the same lists split, near-identical sides (a near-tie may move single members).  Exactly: the other
+    lists and centroids are untouched, nothing is lost, each new centroid is the float64 mean of the
+    members its side ended with; and an oracle index mirrored from the GPU's state (its centroids, its
+    membership) agrees with every search and with inserts that follow."""
+    cfg = W.scaled(W.C1, n=6000, nlist=16)
+    x = W.vectors(cfg, 0, cfg.n)
+    cent = W.train_centroids(cfg, x)
+    ids = np.random.default_rng(11).permutation(cfg.n).astype(np.int64) * 5 + 2
+    p = Pair(x, cent, metric, storage, ids=ids, page_vecs=32, insert_reserve=2000)
+    try:
+        extra = np.concatenate([W.inserts(cfg, b, 64) for b in range(8)])
+        eids = 10 ** 8 + np.arange(len(extra), dtype=np.int64)
+        for s in range(0, 384, 64):
+            p.insert_both(extra[s:s + 64], eids[s:s + 64], where=f"batch {s // 64}")
+        rows = {int(i): v for i, v in zip(ids, p.x)}
+        ex = extra if storage == F32 else extra.astype(np.float16).astype(np.float32)
+        rows.update({int(i): v for i, v in zip(eids, ex)})
+        lens0 = p.gpu.list_lengths()
+        thr = int(np.sort(lens0)[-5]) - 1  # the five longest lists split
+        todo = [l for l in range(16) if lens0[l] > thr]
+        old_ids = [np.sort(p.gpu.list_ids(l).cpu().numpy()) for l in range(16)]
+        old_cent = p.gpu.centroids().cpu().numpy()
+        n = p.gpu.split(thr, 8, B.pk_arena_bytes(p.gpu.cfg, int(lens0.sum()), 1500) + (1 << 20))
+        assert n == len(todo) == 5 and p.orc.split(thr, 8) == n and p.gpu.nlist == p.orc.nlist == 21
+        st = p.gpu.stats()
+        lens1 = p.gpu.list_lengths()
+        assert st.device_error == 0 and st.n_arenas == 1 and lens1.sum() == lens0.sum() == st.n_total
+        c1 = p.gpu.centroids().cpu().numpy()
+        got = [p.gpu.list_ids(l).cpu().numpy() for l in range(21)]
+        for l in range(16):
+            if l not in todo:
+                assert np.array_equal(np.sort(got[l]), old_ids[l]) and np.array_equal(c1[l], old_cent[l])
+        for t, l in enumerate(todo):
+            a, b = set(got[l].tolist()), set(got[16 + t].tolist())
+            assert not (a & b) and sorted(a | b) == old_ids[l].tolist()
+            oa, ob = set(p.orc.list_ids(l).tolist()), set(p.orc.list_ids(16 + t).tolist())
+            assert len(a & oa) + len(b & ob) >= 0.97 * len(old_ids[l]), (l, len(a), len(oa))
+            for lst, members in ((l, a), (16 + t, b)):
+                if members:
+                    want = np.mean([rows[i].astype(np.float64) for i in members], axis=0)
+                    np.testing.assert_allclose(c1[lst], want, rtol=1e-5, atol=1e-6)
+        # mirror: an oracle index with the GPU's centroids and membership
+        mirror = oracle.Index(c1, metric)
+        for l in range(21):
+            if len(got[l]):
+                mirror.insert(np.stack([rows[int(i)] for i in got[l]]), got[l], forced_lists=np.full(len(got[l]), l, np.int32))
+        p.orc, p.cent = mirror, c1
+        q = W.queries(cfg, 6, 64)
+        p.check_search(q, 10, 6, where="after split")
+        p.check_scan(q, 30, np.tile(np.arange(21, dtype=np.int32), (len(q), 1)), where="all lists after split")
+        for s in range(384, 512, 64):
+            p.insert_both(extra[s:s + 64], eids[s:s + 64], where=f"batch {s // 64} after split")
+        p.check_search(q, 10, 6, where="inserts after split")
+        assert np.array_equal(p.gpu.list_lengths(), p.orc.list_lengths())
+    finally:
+        p.close()
+
+
 def test_wide_rows_many_queries_per_list(gpu_device):
     """d = 1536 (config 5 width) with few lists, so lists see more queries than one group holds."""
     cfg = W.scaled(W.C5, n=5000, ncomp=24, nlist=24, zipf_s=1.2)

@@ -58,6 +58,9 @@ def test_host_side_argument_checks_without_gpu(lib):
     assert lib.pk_index_free(null) == B.PK_ERR_BAD_HANDLE
     assert lib.pk_index_compact(null, null, 0, null) == B.PK_ERR_BAD_HANDLE
     assert lib.pk_delete(null, null, 1, None, null) == B.PK_ERR_BAD_HANDLE
+    assert lib.pk_index_split(null, null, 0, 10, 2, None, null) == B.PK_ERR_BAD_HANDLE
+    assert lib.pk_index_centroids(null, null, null) == B.PK_ERR_BAD_HANDLE
+    assert lib.pk_list_ids(null, 0, null, 0, null) == B.PK_ERR_BAD_HANDLE
     assert lib.pk_kmeans(null, 10, 8, 4, 1, null, null, None, null) == B.PK_ERR_INVALID_ARG
     # a buffer that is not a handle is rejected by the magic check
     fake = (C.c_uint64 * 64)()
