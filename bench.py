@@ -130,7 +130,7 @@ class Scenario:
         self.ins_pos[a] = lo + m
 
     def step(self):
-        B, cfg, i = self.B, self.cfg, self.step_no
+        B, cfg, i, torch = self.B, self.cfg, self.step_no, self.torch
         q = self.q[i % self.N_QUERY_BATCHES]
         if cfg.index == 5:  # skewed dynamic: 1:1 interleave, the insert comes first
             self._insert(0, 1)
@@ -139,9 +139,12 @@ class Scenario:
         else:
             B.pk_search_multi([ix.handle for ix in self.indexes], self.q_offsets, q, cfg.k, cfg.nprobe,
                               self.out_ids, self.out_dist)
-        if cfg.index == 3:
-            for a in range(len(self.indexes)):
-                self._insert(a, int(self.ins_sizes[a][i]))
+        if cfg.index == 3:  # the agents' insert batches of this round, one call
+            sizes = [int(self.ins_sizes[a][i]) for a in range(len(self.indexes))]
+            rows = torch.cat([self.ins[a][self.ins_pos[a]:self.ins_pos[a] + m] for a, m in enumerate(sizes)])
+            B.pk_insert_multi([ix.handle for ix in self.indexes], np.concatenate([[0], np.cumsum(sizes)]), rows)
+            for a, m in enumerate(sizes):
+                self.ins_pos[a] += m
         elif cfg.index != 5 and self.insert_m:
             self._insert(0, self.insert_m)
         self.step_no += 1

@@ -163,6 +163,20 @@ int pk_insert(pk_index *index, const float *vectors, const int64_t *ids, int64_t
               void *stream);
 
 /*
+ * Section 3.2 / Section 5: every agent has its own index and operations arrive in batches.
+ * pk_insert for the indexes of several agents in one launch sequence: rows
+ * [v_offsets[a], v_offsets[a+1]) of `vectors` (and of ids / assigned_lists) go to handles[a],
+ * each assigned with that handle's own centroids.  Same semantics as n_handles pk_insert
+ * calls in handle order.
+ *   handles    HOST [n_handles] distinct live handles of equal d, metric, storage, page size
+ *   v_offsets  HOST [n_handles + 1], v_offsets[0] = 0, non-decreasing
+ * Asynchronous.  PK_ERR_NOMEM if any handle may not hold its share (nothing is enqueued).
+ * The first handle owns the workspace used.
+ */
+int pk_insert_multi(pk_index *const *handles, int32_t n_handles, const int64_t *v_offsets, const float *vectors,
+                    const int64_t *ids, int32_t *assigned_lists, void *stream);
+
+/*
  * Section 4.4 (on-GPU cluster splitting) / Section 6.1 (the IVF-Split variant): a cluster
  * that has grown past `threshold` vectors is split in two by a light k-means over its
  * members, run on the device.  Done together with a compaction, because the number of

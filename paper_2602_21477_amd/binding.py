@@ -21,7 +21,7 @@ PK_OK = 0
 PK_ERR_INVALID_ARG, PK_ERR_BAD_HANDLE, PK_ERR_DIM_MISMATCH, PK_ERR_NOMEM, PK_ERR_HIP, PK_ERR_UNSUPPORTED = (
     -1, -2, -3, -4, -5, -6)
 
-EXPORTS = ["pk_search_union", "pk_delete", "pk_index_split", "pk_index_centroids", "pk_list_ids", "pk_arena_bytes", "pk_index_build", "pk_index_add_arena", "pk_index_compact", "pk_kmeans", "pk_insert", "pk_insert_assigned", "pk_search",
+EXPORTS = ["pk_search_union", "pk_insert_multi", "pk_delete", "pk_index_split", "pk_index_centroids", "pk_list_ids", "pk_arena_bytes", "pk_index_build", "pk_index_add_arena", "pk_index_compact", "pk_kmeans", "pk_insert", "pk_insert_assigned", "pk_search",
            "pk_search_multi", "pk_coarse", "pk_scan_probes", "pk_index_stats", "pk_list_lengths", "pk_profile_begin",
            "pk_profile_end", "pk_index_free", "pk_strerror"]
 
@@ -71,6 +71,7 @@ def lib():
         L.pk_kmeans.argtypes = [vp, i64, i32, i32, i32, vp, vp, C.POINTER(C.c_double), vp]
         L.pk_insert.argtypes = [vp, vp, vp, i64, vp, vp]
         L.pk_insert_assigned.argtypes = [vp, vp, vp, i64, vp, vp]
+        L.pk_insert_multi.argtypes = [C.POINTER(vp), i32, C.POINTER(i64), vp, vp, vp, vp]
         L.pk_delete.argtypes = [vp, vp, i64, C.POINTER(i64), vp]
         L.pk_search.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
         L.pk_search_multi.argtypes = [C.POINTER(vp), i32, C.POINTER(i64), vp, i32, i32, vp, vp, vp]
@@ -140,6 +141,14 @@ def pk_kmeans(vectors, centroids, iters: int, assign_out=None):
                            _dev(centroids, torch.float32, "centroids"), _dev(assign_out, torch.int32, "assign_out"),
                            inertia, _stream()), "pk_kmeans")
     return [float(v) for v in inertia]
+
+
+def pk_insert_multi(handles, v_offsets, vectors, ids=None, assigned_lists=None):
+    hs = (C.c_void_p * len(handles))(*handles)
+    offs = (C.c_int64 * len(v_offsets))(*[int(v) for v in v_offsets])
+    _check(lib().pk_insert_multi(hs, len(handles), offs, _dev(vectors, torch.float32, "vectors"),
+                                 _dev(ids, torch.int64, "ids"), _dev(assigned_lists, torch.int32, "assigned_lists"),
+                                 _stream()), "pk_insert_multi")
 
 
 def pk_index_split(handle: int, arena, threshold: int, iters: int) -> int:

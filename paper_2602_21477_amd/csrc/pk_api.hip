@@ -718,67 +718,94 @@ void destroy(pk_index *ix)
     delete ix;
 }
 
+// Host-side capacity check of an insert of m vectors, before anything is enqueued.  Fast
+// path: a bound from the last page counter read back.  If that does not clear the batch,
+// synchronise, read the exact page counter and list lengths, and test the exact worst case:
+// m vectors open the most pages when they first top up the fullest tail pages (cost: free
+// slots + 1 each) and then fill whole pages.
+int check_capacity(pk_index *ix, int64_t m, hipStream_t s)
+{
+    if ((uint64_t)ix->pages_known + pages_for(ix, (uint64_t)(ix->n_inserted - ix->inserted_at_known + m)) <=
+        ix->pages_total)
+        return PK_OK;
+    PK_HIP(hipStreamSynchronize(s));
+    PK_TRY(settle_pages(ix));
+    std::vector<uint32_t> len((size_t)ix->cfg.nlist);
+    uint32_t used = 0;
+    PK_HIP(hipMemcpy(len.data(), ix->host.list_len, len.size() * 4, hipMemcpyDeviceToHost));
+    PK_HIP(hipMemcpy(&used, ix->host.ctr, 4, hipMemcpyDeviceToHost));
+    ix->pages_known = used;
+    ix->inserted_at_known = ix->n_inserted;
+    std::vector<uint32_t> first(len.size());
+    const uint32_t P = (uint32_t)ix->P;
+    for (size_t l = 0; l < len.size(); ++l) first[l] = (P - len[l] % P) % P + 1;
+    std::sort(first.begin(), first.end());
+    uint64_t budget = (uint64_t)m, pages = 0;
+    for (uint32_t c : first) {
+        if (budget < c) break;
+        budget -= c;
+        ++pages;
+    }
+    pages += budget / P;
+    return (uint64_t)used + pages > ix->pages_total ? PK_ERR_NOMEM : PK_OK;
+}
+
+// after an insert: count it, and start a read-back of the page counter once the bound above
+// is close enough to the limit that a later batch of 4096 might fail the fast path
+int note_inserted(pk_index *ix, int64_t m, hipStream_t s)
+{
+    ix->n_total += m;
+    ix->next_id += m;
+    ix->n_inserted += m;
+    if ((uint64_t)ix->pages_known + pages_for(ix, (uint64_t)(ix->n_inserted - ix->inserted_at_known + 4096)) <=
+        ix->pages_total)
+        return PK_OK;
+    return snapshot_pages(ix, s);
+}
+
+// One launch sequence: top-1 coarse search (unless the lists are given), slot reservation and
+// append for the vectors of hs[0..nh), rows [qlo[a], qlo[a+1]) of the batch going to handle a
+// (at most 1024 each).  The workspace is that of hs[0].
+int insert_batch(pk_index *const *hs, int nh, const uint32_t *qlo, const float *x, const int64_t *ids,
+                 const int32_t *forced, int32_t *assigned_out, hipStream_t s)
+{
+    pk_index *own = hs[0];
+    const int64_t m = qlo[nh];
+    Plan p;
+    PK_TRY(make_plan(p, hs, nh, qlo, m, 1, 1, forced == nullptr, false));
+    const size_t extra = round_up(p.bytes, 256);
+    PK_TRY(ensure_ws(own, extra + round_up((size_t)m * 4, 256), s));
+    carve(p, own->ws, own);
+    uint32_t *slots = reinterpret_cast<uint32_t *>(own->ws + extra);
+    MultiArgs mm;
+    fill_multi(mm, hs, nh, qlo);
+    const int32_t *assign = forced;
+    if (!forced) {
+        PK_TRY(run_coarse(p, mm, hs, x, s));
+        assign = p.probes;
+    }
+    AppendIds idc{};
+    for (int a = 0; a < nh; ++a) idc.id0[a] = hs[a]->next_id;
+    PK_HIP(launch_reserve(mm, assign, slots, assigned_out, s));
+    PK_HIP(launch_append(mm, idc, x, ids, assign, slots, s));
+    for (int a = 0; a < nh; ++a) PK_TRY(note_inserted(hs[a], (int64_t)(qlo[a + 1] - qlo[a]), s));
+    return PK_OK;
+}
+
 int insert_impl(pk_index *ix, const float *x, const int64_t *ids, int64_t m, const int32_t *forced,
                 int32_t *assigned_out, hipStream_t s)
 {
     if (!live(ix)) return PK_ERR_BAD_HANDLE;
     if (m < 0 || (m > 0 && !x)) return PK_ERR_INVALID_ARG;
     if (m == 0) return PK_OK;
-    // Host-side capacity check, before anything is enqueued.  Fast path: a bound from the last
-    // page counter read back.  If that does not clear the batch, synchronise, read the exact
-    // page counter and list lengths, and test the exact worst case: m vectors open the most
-    // pages when they first top up the fullest tail pages (cost: free slots + 1 each) and then
-    // fill whole pages.
-    if ((uint64_t)ix->pages_known + pages_for(ix, (uint64_t)(ix->n_inserted - ix->inserted_at_known + m)) >
-        ix->pages_total) {
-        PK_HIP(hipStreamSynchronize(s));
-        PK_TRY(settle_pages(ix));
-        std::vector<uint32_t> len((size_t)ix->cfg.nlist);
-        uint32_t used = 0;
-        PK_HIP(hipMemcpy(len.data(), ix->host.list_len, len.size() * 4, hipMemcpyDeviceToHost));
-        PK_HIP(hipMemcpy(&used, ix->host.ctr, 4, hipMemcpyDeviceToHost));
-        ix->pages_known = used;
-        ix->inserted_at_known = ix->n_inserted;
-        std::vector<uint32_t> first(len.size());
-        const uint32_t P = (uint32_t)ix->P;
-        for (size_t l = 0; l < len.size(); ++l) first[l] = (P - len[l] % P) % P + 1;
-        std::sort(first.begin(), first.end());
-        uint64_t budget = (uint64_t)m, pages = 0;
-        for (uint32_t c : first) {
-            if (budget < c) break;
-            budget -= c;
-            ++pages;
-        }
-        pages += budget / P;
-        if ((uint64_t)used + pages > ix->pages_total) return PK_ERR_NOMEM;
-    }
+    PK_TRY(check_capacity(ix, m, s));
     pk_index *hs[1] = {ix};
     for (int64_t i0 = 0; i0 < m; i0 += 1024) {
-        const int mc = (int)std::min<int64_t>(1024, m - i0);
-        const uint32_t qlo[2] = {0, (uint32_t)mc};
-        Plan p;
-        PK_TRY(make_plan(p, hs, 1, qlo, mc, 1, 1, forced == nullptr, false));
-        const size_t extra = round_up(p.bytes, 256);
-        PK_TRY(ensure_ws(ix, extra + 4096 * 2, s));
-        carve(p, ix->ws, ix);
-        uint32_t *slots = reinterpret_cast<uint32_t *>(ix->ws + extra);
-        const float *xc = x + (size_t)i0 * ix->cfg.d;
-        const int32_t *assign;
-        if (forced) {
-            assign = forced + i0;
-        } else {
-            MultiArgs mm;
-            fill_multi(mm, hs, 1, qlo);
-            PK_TRY(run_coarse(p, mm, hs, xc, s));
-            assign = p.probes;
-        }
-        PK_HIP(launch_reserve(ix->dev, assign, mc, slots, assigned_out ? assigned_out + i0 : nullptr, s));
-        PK_HIP(launch_append(ix->dev, xc, ids ? ids + i0 : nullptr, assign, slots, mc, ix->next_id, s));
-        ix->n_total += mc;
-        ix->next_id += mc;
-        ix->n_inserted += mc;
+        const uint32_t qlo[2] = {0, (uint32_t)std::min<int64_t>(1024, m - i0)};
+        PK_TRY(insert_batch(hs, 1, qlo, x + (size_t)i0 * ix->cfg.d, ids ? ids + i0 : nullptr, forced ? forced + i0 : nullptr,
+                            assigned_out ? assigned_out + i0 : nullptr, s));
     }
-    return snapshot_pages(ix, s);
+    return PK_OK;
 }
 
 } // namespace
@@ -1289,6 +1316,42 @@ int pk_list_ids(pk_index *ix, int32_t list, int64_t *out, int64_t cap, void *str
 int pk_insert(pk_index *ix, const float *vectors, const int64_t *ids, int64_t m, int32_t *assigned_lists, void *stream)
 {
     return insert_impl(ix, vectors, ids, m, nullptr, assigned_lists, static_cast<hipStream_t>(stream));
+}
+
+int pk_insert_multi(pk_index *const *handles, int32_t n_handles, const int64_t *v_offsets, const float *vectors,
+                    const int64_t *ids, int32_t *assigned_lists, void *stream)
+{
+    if (!handles || !v_offsets || n_handles < 1 || n_handles > PK_MAX_HANDLES) return PK_ERR_INVALID_ARG;
+    if (v_offsets[0] != 0) return PK_ERR_INVALID_ARG;
+    bool small = true;
+    for (int a = 0; a < n_handles; ++a) {
+        if (!live(handles[a])) return PK_ERR_BAD_HANDLE;
+        if (v_offsets[a + 1] < v_offsets[a]) return PK_ERR_INVALID_ARG;
+        for (int b = 0; b < a; ++b)
+            if (handles[b] == handles[a]) return PK_ERR_INVALID_ARG;
+        const pk_config &c0 = handles[0]->cfg, &c = handles[a]->cfg;
+        if (c.d != c0.d || c.metric != c0.metric || c.storage != c0.storage || c.page_vecs != c0.page_vecs)
+            return PK_ERR_DIM_MISMATCH;
+        small = small && v_offsets[a + 1] - v_offsets[a] <= 1024;
+    }
+    const int64_t m = v_offsets[n_handles];
+    if (m > 0 && !vectors) return PK_ERR_INVALID_ARG;
+    if (m == 0) return PK_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int d = handles[0]->cfg.d;
+    // all capacity checks first: nothing is enqueued if any handle cannot take its share
+    for (int a = 0; a < n_handles; ++a) PK_TRY(check_capacity(handles[a], v_offsets[a + 1] - v_offsets[a], s));
+    if (small && m <= 0x7fffffff) {
+        std::vector<uint32_t> qlo((size_t)n_handles + 1);
+        for (int a = 0; a <= n_handles; ++a) qlo[(size_t)a] = (uint32_t)v_offsets[a];
+        return insert_batch(handles, n_handles, qlo.data(), vectors, ids, nullptr, assigned_lists, s);
+    }
+    for (int a = 0; a < n_handles; ++a) { // long segments: handle by handle
+        const int64_t lo = v_offsets[a], ma = v_offsets[a + 1] - lo;
+        PK_TRY(insert_impl(handles[a], vectors + (size_t)lo * d, ids ? ids + lo : nullptr, ma, nullptr,
+                           assigned_lists ? assigned_lists + lo : nullptr, s));
+    }
+    return PK_OK;
 }
 
 int pk_insert_assigned(pk_index *ix, const float *vectors, const int64_t *ids, int64_t m, const int32_t *lists,

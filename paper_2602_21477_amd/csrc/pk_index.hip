@@ -111,12 +111,19 @@ hipError_t launch_scatter_build(const DevIndex *ix, const float *x, const int64_
 // the build-time extent opens a delta page.  If the arena or a list's delta table cannot
 // take the whole batch, nothing is changed, every slot is 0xffffffff and the sticky error
 // flag is set.
-__global__ __launch_bounds__(1024) void reserve_kernel(const DevIndex *ixp, const int32_t *assign, int m, uint32_t *slots,
+__global__ __launch_bounds__(1024) void reserve_kernel(MultiArgs ma, const int32_t *assign, uint32_t *slots,
                                                        int32_t *assigned_out)
 {
     __shared__ int32_t s_l[1024];
     __shared__ uint32_t s_need, s_bad, s_page0;
-    const DevIndex &ix = *ixp;
+    // workgroup a serves handle a: its vectors are rows [qlo[a], qlo[a+1]) of the batch
+    const DevIndex &ix = *ma.ix[blockIdx.x];
+    const uint32_t row0 = ma.qlo[blockIdx.x];
+    const int m = (int)(ma.qlo[blockIdx.x + 1] - row0);
+    if (m == 0) return;
+    assign += row0;
+    slots += row0;
+    if (assigned_out) assigned_out += row0;
     const int i = threadIdx.x;
     if (i == 0) {
         s_need = 0;
@@ -172,33 +179,36 @@ __global__ __launch_bounds__(1024) void reserve_kernel(const DevIndex *ixp, cons
     }
 }
 
-hipError_t launch_reserve(const DevIndex *ix, const int32_t *assign, int m, uint32_t *slots, int32_t *assigned_out,
-                          hipStream_t s)
+hipError_t launch_reserve(const MultiArgs &ma, const int32_t *assign, uint32_t *slots, int32_t *assigned_out, hipStream_t s)
 {
-    if (m <= 0) return hipSuccess;
-    if (m > 1024) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(reserve_kernel, dim3(1), dim3(1024), 0, s, ix, assign, m, slots, assigned_out);
+    if (ma.n <= 0 || ma.qlo[ma.n] == 0) return hipSuccess;
+    for (int a = 0; a < ma.n; ++a)
+        if (ma.qlo[a + 1] - ma.qlo[a] > 1024u) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(reserve_kernel, dim3(ma.n), dim3(1024), 0, s, ma, assign, slots, assigned_out);
     return hipGetLastError();
 }
 
 // Insert, step 3: write the vectors into their reserved slots
-__global__ __launch_bounds__(256) void append_kernel(const DevIndex *ixp, const float *x, const int64_t *ids,
-                                                     const int32_t *assign, const uint32_t *slots, int m, int64_t id0)
+__global__ __launch_bounds__(256) void append_kernel(MultiArgs ma, AppendIds idc, const float *x, const int64_t *ids,
+                                                     const int32_t *assign, const uint32_t *slots)
 {
-    const DevIndex &ix = *ixp;
     const int wave = threadIdx.x >> 6;
-    const int i = blockIdx.x * 4 + wave;
-    if (i >= m) return;
+    const uint32_t i = blockIdx.x * 4 + wave;
+    if (i >= ma.qlo[ma.n]) return;
+    int h = 0;
+    while (h + 1 < ma.n && i >= ma.qlo[h + 1]) ++h;
+    const DevIndex &ix = *ma.ix[h];
     const uint32_t slot = slots[i];
     if (slot == 0xffffffffu) return;
-    write_row(ix, (uint32_t)assign[i], slot, x + (size_t)i * ix.d, ids ? ids[i] : id0 + i);
+    write_row(ix, (uint32_t)assign[i], slot, x + (size_t)i * ix.d, ids ? ids[i] : idc.id0[h] + (int64_t)(i - ma.qlo[h]));
 }
 
-hipError_t launch_append(const DevIndex *ix, const float *x, const int64_t *ids, const int32_t *assign,
-                         const uint32_t *slots, int m, int64_t id0, hipStream_t s)
+hipError_t launch_append(const MultiArgs &ma, const AppendIds &idc, const float *x, const int64_t *ids,
+                         const int32_t *assign, const uint32_t *slots, hipStream_t s)
 {
-    if (m <= 0) return hipSuccess;
-    hipLaunchKernelGGL(append_kernel, dim3((m + 3) / 4), dim3(256), 0, s, ix, x, ids, assign, slots, m, id0);
+    const uint32_t m = ma.n > 0 ? ma.qlo[ma.n] : 0u;
+    if (m == 0) return hipSuccess;
+    hipLaunchKernelGGL(append_kernel, dim3((m + 3) / 4), dim3(256), 0, s, ma, idc, x, ids, assign, slots);
     return hipGetLastError();
 }
 

@@ -335,9 +335,13 @@ struct KmeansArgs {
     double *inertia;       // one word: receives the sum of squared distances of the assignment
 };
 hipError_t launch_kmeans_update(const KmeansArgs &a, hipStream_t s);
-hipError_t launch_reserve(const DevIndex *ix, const int32_t *assign, int m, uint32_t *slots, int32_t *assigned_out,
-                          hipStream_t s);
-hipError_t launch_append(const DevIndex *ix, const float *x, const int64_t *ids, const int32_t *assign,
-                         const uint32_t *slots, int m, int64_t id0, hipStream_t s);
+// Insert: slots for the vectors of every handle of the batch (one workgroup per handle, at most 1024
+// vectors each; rows [qlo[a], qlo[a+1]) of assign / slots / assigned_out belong to handle a), then the rows.
+struct AppendIds {
+    int64_t id0[PK_MAX_HANDLES]; // first id of each handle's segment when the caller gives no ids
+};
+hipError_t launch_reserve(const MultiArgs &ma, const int32_t *assign, uint32_t *slots, int32_t *assigned_out, hipStream_t s);
+hipError_t launch_append(const MultiArgs &ma, const AppendIds &idc, const float *x, const int64_t *ids,
+                         const int32_t *assign, const uint32_t *slots, hipStream_t s);
 
 } // namespace pk

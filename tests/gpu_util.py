@@ -82,6 +82,11 @@ class Pair:
         if self.storage == B.PK_F16:
             x = x.astype(np.float16).astype(np.float32)
         lists = self.gpu.insert(dev(x), None if ids is None else dev(ids), want_lists=True).cpu().numpy()
+        return self.accept_inserted(x, lists, ids, where)
+
+    def accept_inserted(self, x, lists, ids=None, where=""):
+        """The GPU put the (already rounded) rows x into `lists`: check them against the oracle's rule
+        and mirror them into the oracle."""
         op, sc = self.orc.coarse(x, min(2, self.orc.nlist), with_scores=True)
         cn2 = float((self.cent.astype(np.float64) ** 2).sum(1).max())
         for i in range(len(x)):

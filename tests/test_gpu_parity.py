@@ -492,6 +492,44 @@ def test_ivf_split(gpu_device, storage, metric):
         p.close()
 
 
+def test_insert_multi_across_agents(gpu_device):
+    """Insert batches of several agents in one call: per agent the same lists as its own centroids
+    dictate (oracle rule), running ids per agent, an agent without rows, and a segment over 1024
+    rows (handled agent by agent); searches follow the oracle afterwards."""
+    cfg = W.scaled(W.C1, n=3000)
+    pairs = []
+    try:
+        for a in range(3):
+            x = W.vectors(cfg, 0, 3000 - 500 * a, agent=a)
+            pairs.append(Pair(x, W.train_centroids(W.scaled(cfg, n=len(x)), x, agent=a), IP, F32, insert_reserve=4000))
+        hs = [p.gpu.handle for p in pairs]
+        for sizes, with_ids in (((5, 0, 17), True), ((64, 1, 9), False), ((3, 1500, 2), False)):
+            xs = [W.inserts(cfg, 50 + a, max(n, 1), agent=a)[:n] for a, n in enumerate(sizes)]
+            offs = np.concatenate([[0], np.cumsum(sizes)])
+            ids = (10 ** 6 * (1 + np.arange(offs[-1], dtype=np.int64))) if with_ids else None
+            out = torch.empty(int(offs[-1]), dtype=torch.int32, device="cuda")
+            n_before = [p.gpu.stats().n_total for p in pairs]
+            next_id = [p.orc.ntotal for p in pairs]
+            B.pk_insert_multi(hs, offs, dev(np.concatenate(xs)), None if ids is None else dev(ids), out)
+            lists = out.cpu().numpy()
+            for a, p in enumerate(pairs):
+                lo, hi = int(offs[a]), int(offs[a + 1])
+                if hi > lo:
+                    # without ids the library continues the agent's own counter of vectors ever added
+                    mirror_ids = ids[lo:hi] if ids is not None else next_id[a] + np.arange(hi - lo, dtype=np.int64)
+                    p.accept_inserted(xs[a], lists[lo:hi], mirror_ids, where=f"agent {a}")
+                assert p.gpu.stats().n_total == n_before[a] + sizes[a]
+                assert np.array_equal(p.gpu.list_lengths(), p.orc.list_lengths())
+                if ids is None and hi > lo:  # running ids: the agent's own counter
+                    got, _ = p.gpu.search(dev(xs[a][:1]), 1, p.gpu.nlist)
+                    assert int(got[0, 0]) == next_id[a]
+        for a, p in enumerate(pairs):
+            p.check_search(W.queries(cfg, 8, 32, agent=a), 10, 8, where=f"agent {a} after multi inserts")
+    finally:
+        for p in pairs:
+            p.close()
+
+
 def test_wide_rows_many_queries_per_list(gpu_device):
     """d = 1536 (config 5 width) with few lists, so lists see more queries than one group holds."""
     cfg = W.scaled(W.C5, n=5000, ncomp=24, nlist=24, zipf_s=1.2)

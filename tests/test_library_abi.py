@@ -70,6 +70,7 @@ def test_host_side_argument_checks_without_gpu(lib):
     assert lib.pk_search_multi(hs, 1, offs, null, 1, 1, null, null, null) == B.PK_ERR_BAD_HANDLE
     assert lib.pk_search_multi(hs, 0, offs, null, 1, 1, null, null, null) == B.PK_ERR_INVALID_ARG
     assert lib.pk_search_union(hs, 1, null, 1, 1, 1, null, null, null, null) == B.PK_ERR_BAD_HANDLE
+    assert lib.pk_insert_multi(hs, 1, offs, null, null, null, null) == B.PK_ERR_BAD_HANDLE
     assert lib.pk_search_union(hs, 0, null, 1, 1, 1, null, null, null, null) == B.PK_ERR_INVALID_ARG
 
 
