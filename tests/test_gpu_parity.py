@@ -336,6 +336,44 @@ def test_multi_agent_equals_per_handle_calls(gpu_device):
             p.close()
 
 
+def test_limits_128_handles_and_k_1024(gpu_device):
+    """The documented maxima in one place: 128 handles in one multi-agent search, one multi-agent insert
+    and one scope-union search with k = 1024 (more than any single memory holds)."""
+    cfg = W.scaled(W.C1, n=300, d=32, ncomp=8, nlist=4)
+    pairs = []
+    try:
+        for a in range(128):
+            x = W.vectors(cfg, 0, 150 + a, agent=a)
+            pairs.append(Pair(x, x[:4].copy(), L2, F32, insert_reserve=64))
+        gpus, orcs = [p.gpu for p in pairs], [p.orc for p in pairs]
+        q = W.queries(cfg, 1, 128)  # one query per agent
+        offs = list(range(129))
+        gi, gv = B.search_multi(gpus, offs, dev(q), 5, 4)
+        oi, ov = oracle.search_multi(orcs, offs, q, 5 + KX, 4)
+        check_results(gi.cpu().numpy(), gv.cpu().numpy(), oi, ov, 5, 1e-4, np.max([p.scale(q) for p in pairs], axis=0),
+                      L2, where="128-handle search")
+        sizes = [(a % 3) for a in range(128)]  # 0, 1 or 2 rows per agent
+        xs = [W.inserts(cfg, 9, 2, agent=a)[:m] for a, m in enumerate(sizes)]
+        out = torch.empty(sum(sizes), dtype=torch.int32, device="cuda")
+        voffs = np.concatenate([[0], np.cumsum(sizes)])
+        B.pk_insert_multi([g.handle for g in gpus], voffs, dev(np.concatenate(xs)), None, out)
+        lists = out.cpu().numpy()
+        for a, p in enumerate(pairs):
+            if sizes[a]:
+                p.accept_inserted(xs[a], lists[voffs[a]:voffs[a + 1]],
+                                  150 + a + np.arange(sizes[a], dtype=np.int64), where=f"agent {a}")
+        q8 = q[:8]
+        gs, gi, gv = B.search_union(gpus, dev(q8), 1024, 4)
+        os_, oi, ov = oracle.search_union(orcs, q8, 1024 + KX, 4)
+        enc = lambda s_, i_: np.where(i_ < 0, -1, (s_.astype(np.int64) << 40) + i_)
+        check_results(enc(gs.cpu().numpy(), gi.cpu().numpy()), gv.cpu().numpy(), enc(os_, oi), ov, 1024, 1e-4,
+                      np.max([p.scale(q8) for p in pairs], axis=0), L2, where="128-handle union, k=1024")
+        assert int((gi >= 0).sum()) == 8 * 1024  # 128 memories of 150+ rows: every slot is filled
+    finally:
+        for p in pairs:
+            p.close()
+
+
 @pytest.mark.parametrize("metric", [IP, L2])
 def test_scope_union_search(gpu_device, metric):
     """One query batch searched across three memories of different sizes (one shorter than k, one row
