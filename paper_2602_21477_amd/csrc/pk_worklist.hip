@@ -140,6 +140,21 @@ __global__ __launch_bounds__(1024) void wl_scan_kernel(WorklistArgs a, MultiArgs
     // tiles per list: regular lists -> ltile, hot lists -> lhtile (counts first, then their scans)
     unsigned long long rows = 0;
     for (int hot = 0; hot < 2; ++hot) {
+        // a class no list can fall into (no hot class at all, or every list hot) needs no scan
+        const bool none = hot ? a.hot_from == 0xffffffffu : a.hot_from == 0u;
+        if (none) {
+            if (threadIdx.x == 0) {
+                uint32_t *sc = hot ? a.scalars_hot : a.scalars;
+                sc[0] = 0;
+                sc[1] = 0;
+                sc[2] = 1;
+                if (!hot) {
+                    sc[3] = total;
+                    atomicAdd(&m.ix[0]->stats[1], (unsigned long long)total);
+                }
+            }
+            continue;
+        }
         for (uint32_t gl = threadIdx.x; gl < nl; gl += blockDim.x) {
             const uint32_t h = gl / (uint32_t)a.nlist_max, l = gl - h * (uint32_t)a.nlist_max;
             uint32_t nt = 0;
