@@ -43,18 +43,20 @@ __device__ void bitonic_sort(u64 *keys, uint32_t np2)
     }
 }
 
-// Streaming selector state.  keys: LDS [kSelCap]; cnt: LDS counter.
+// Streaming selector state.  keys: LDS [cap]; cnt: LDS counter.
 struct Selector {
     u64 *keys;
     uint32_t *cnt;
     int K;
+    uint32_t cap; // entries of keys (a power of two >= 512)
     u64 thr;
 
-    __device__ void init(u64 *k, uint32_t *c, int kk)
+    __device__ void init(u64 *k, uint32_t *c, int kk, uint32_t capacity = (uint32_t)kSelCap)
     {
         keys = k;
         cnt = c;
         K = kk;
+        cap = capacity;
         thr = kMaxKey;
         if (threadIdx.x == 0) *cnt = 0;
         __syncthreads();
@@ -83,7 +85,7 @@ struct Selector {
         // flush threshold: the smallest power of two that holds the kept keys plus one round
         // (small rounds and small K sort small buffers)
         uint32_t limit = next_pow2((uint32_t)K + room);
-        limit = limit < 512u ? 512u : (limit > (uint32_t)kSelCap ? (uint32_t)kSelCap : limit);
+        limit = limit < 512u ? 512u : (limit > cap ? cap : limit);
         if (n + room > limit) flush();
     }
     __device__ __forceinline__ void push(u64 key)
@@ -290,17 +292,28 @@ __device__ int64_t resolve_id(const FinalArgs &a, const MultiArgs &h, uint32_t q
     return ar.ids[(size_t)(pg - ar.first_page) * ix.P + (row - lp * ix.P)];
 }
 
-__global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, MultiArgs h)
+// buffer of the final selection: K kept keys plus the largest round pushed at once, as a power of two
+static uint32_t final_cap(int K)
 {
-    __shared__ u64 keys[kSelCap];
+    uint32_t c = 512;
+    while (c < (uint32_t)K + (uint32_t)(kSelThreads * kSelVec) && c < (uint32_t)kSelCap) c <<= 1;
+    return c;
+}
+
+__global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, MultiArgs h, uint32_t cap)
+{
+    // LDS sized by K, not by the largest K the library takes: small k leaves room for every
+    // query's workgroup to be resident at once
+    extern __shared__ __align__(16) unsigned char s_dyn[];
+    u64 *keys = reinterpret_cast<u64 *>(s_dyn);                  // [cap]
+    int64_t *s_id = reinterpret_cast<int64_t *>(keys + cap);     // [k]
     __shared__ uint32_t s_cnt;
-    __shared__ int64_t s_id[PK_MAX_K];
     __shared__ long long s_red[kSelThreads / 64];
     __shared__ long long s_pick;
     const uint32_t q = blockIdx.x;
     const int k = a.k;
     Selector sel;
-    sel.init(keys, &s_cnt, a.K);
+    sel.init(keys, &s_cnt, a.K, cap);
     const uint32_t cnt_q = a.qcnt[q];
     if (threadIdx.x == 0) atomicAdd(&h.ix[0]->stats[3], (unsigned long long)cnt_q);
     uint32_t n;
@@ -458,7 +471,9 @@ hipError_t launch_select_probes(const unsigned long long *partial, int nchunks, 
 hipError_t launch_select_final(const FinalArgs &a, const MultiArgs &h, int64_t nq, hipStream_t s)
 {
     if (nq <= 0) return hipSuccess;
-    hipLaunchKernelGGL(select_final_kernel, dim3((uint32_t)nq), dim3(kSelThreads), 0, s, a, h);
+    const uint32_t cap = final_cap(a.K);
+    const size_t lds = (size_t)cap * sizeof(u64) + (size_t)a.k * sizeof(int64_t);
+    hipLaunchKernelGGL(select_final_kernel, dim3((uint32_t)nq), dim3(kSelThreads), lds, s, a, h, cap);
     return hipGetLastError();
 }
 
