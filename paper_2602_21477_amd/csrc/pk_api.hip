@@ -138,7 +138,7 @@ uint64_t wq_ub(const pk_index *ix, int nprobe)
 struct Plan {
     int64_t nq;
     int nprobe, k, nh;
-    int mq_f, mq_h, grid_f, grid_h, grid_s, cchunks, nchunks, K, nlist_max, sp;
+    int mq_f, mq_h, grid_f, grid_h, grid_s, cchunks, nchunks, sel_chunk, K, nlist_max, sp;
     uint32_t hot_from;
     uint32_t stride, cand_cap, tile_cap, span;
     bool need_coarse, need_fine, f16;
@@ -287,7 +287,12 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
     p.cchunks = (nlist_hi + kSelChunk - 1) / kSelChunk;
     p.cand_cap = (uint32_t)cand;
     p.tile_cap = (uint32_t)tiles;
-    p.nchunks = (int)std::max<uint64_t>(1, (wmax + kSelChunk - 1) / kSelChunk);
+    // Emitted candidates are selected per (query, chunk): a batch of few queries is cut into small
+    // chunks so that enough workgroups share the work, within 16 M partial entries.
+    p.sel_chunk = nq >= 128 ? kSelChunk : 1024;
+    while (p.sel_chunk < kSelChunk && (uint64_t)nq * ((wmax + p.sel_chunk - 1) / p.sel_chunk) * (uint64_t)p.K > (16ull << 20))
+        p.sel_chunk *= 2;
+    p.nchunks = (int)std::max<uint64_t>(1, (wmax + p.sel_chunk - 1) / p.sel_chunk);
     carve(p, nullptr, own);
     return PK_OK;
 }
@@ -376,6 +381,7 @@ int run_coarse(const Plan &p, const MultiArgs &m, pk_index *const *hs, const flo
     se.metric = own->cfg.metric;
     se.K = p.nprobe;
     se.nchunks = p.cchunks;
+    se.chunk = kSelChunk;
     se.partial = p.cpartial;
     PK_HIP(launch_select_partial(se, p.nq, s));
     PK_HIP(launch_select_probes(p.cpartial, p.cchunks, p.nprobe, p.nprobe, p.nq, p.probes, s));
@@ -499,11 +505,13 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
     se.metric = own->cfg.metric;
     se.K = p.K;
     se.nchunks = p.nchunks;
+    se.chunk = p.sel_chunk;
     se.partial = p.partial;
     PK_HIP(launch_select_partial(se, p.nq, s));
     FinalArgs f{};
     f.partial = p.partial;
     f.nchunks = p.nchunks;
+    f.chunk = p.sel_chunk;
     f.K = p.K;
     f.k = p.k;
     f.nprobe = p.nprobe;

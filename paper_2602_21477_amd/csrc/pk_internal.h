@@ -19,7 +19,7 @@ constexpr int kCentroidPad = 32;      // the centroid table is zero padded to a 
 constexpr int kSelThreads = 256;
 constexpr int kSelVec = 4;            // candidates per thread per round
 constexpr int kSelCap = 4096;         // LDS key buffer of the select kernels (K + one round <= cap)
-constexpr int kSelChunk = 32768;      // candidates per (query, chunk) workgroup
+constexpr int kSelChunk = 32768;      // candidates per (query, chunk) workgroup (large batches; small ones cut finer)
 constexpr unsigned long long kMaxKey = ~0ull;
 constexpr int kHistBins = 64;         // per-query key histogram that tightens the emission threshold
 
@@ -191,6 +191,7 @@ struct SelectArgs {
     const uint32_t *qoff;         // [nq] first candidate of each query
     const uint32_t *qcnt;         // [nq] candidates of each query
     int metric, K, nchunks;
+    int chunk;                    // candidates per (query, chunk) workgroup
     unsigned long long *partial;  // [nq][nchunks][K]
 };
 hipError_t launch_select_partial(const SelectArgs &a, int64_t nq, hipStream_t s);
@@ -202,7 +203,7 @@ hipError_t launch_select_probes(const unsigned long long *partial, int nchunks, 
 
 struct FinalArgs {
     const unsigned long long *partial; // [nq][nchunks][K]
-    int nchunks, K, k, nprobe, metric;
+    int nchunks, chunk, K, k, nprobe, metric; // chunk: as in SelectArgs (a query with at most that many keys skips the partial step)
     const unsigned long long *keys;   // emitted candidates of all queries
     const uint32_t *qoff, *qcnt;      // candidate ranges inside keys
     const uint32_t *pair_off;         // [nq][nprobe+1] start of each probe's segment inside the range

@@ -101,11 +101,11 @@ __global__ __launch_bounds__(kSelThreads) void select_partial_kernel(SelectArgs 
     const uint32_t q = blockIdx.y, c = blockIdx.x;
     const uint32_t base = a.qoff[q];
     const uint32_t total = a.qcnt[q];
-    const uint32_t beg = c * (uint32_t)kSelChunk;
-    const uint32_t end = min(beg + (uint32_t)kSelChunk, total);
+    const uint32_t beg = c * (uint32_t)a.chunk;
+    const uint32_t end = min(beg + (uint32_t)a.chunk, total);
     // nothing in this chunk; and a query whose emitted keys fit one chunk is merged directly
     // by the final kernel
-    if (beg >= total || (!a.vals && total <= (uint32_t)kSelChunk)) return;
+    if (beg >= total || (!a.vals && total <= (uint32_t)a.chunk)) return;
     u64 *out = a.partial + ((size_t)q * a.nchunks + c) * a.K;
 
     Selector sel;
@@ -317,7 +317,7 @@ __global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, 
     const uint32_t cnt_q = a.qcnt[q];
     if (threadIdx.x == 0) atomicAdd(&h.ix[0]->stats[3], (unsigned long long)cnt_q);
     uint32_t n;
-    if (cnt_q <= (uint32_t)kSelChunk) {
+    if (cnt_q <= (uint32_t)a.chunk) {
         // few emitted candidates: select straight from the query's region
         const u64 *v = a.keys + a.qoff[q];
         // short ranges go one key per thread and round, so the buffer that gets sorted stays small
@@ -334,7 +334,7 @@ __global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, 
         sel.flush();
         n = s_cnt;
     } else {
-        const int used = (int)((cnt_q + kSelChunk - 1) / kSelChunk);
+        const int used = (int)((cnt_q + (uint32_t)a.chunk - 1) / (uint32_t)a.chunk);
         n = merge_partials(sel, a.partial + (size_t)q * a.nchunks * a.K, used, a.K);
     }
 
