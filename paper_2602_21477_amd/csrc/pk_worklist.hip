@@ -210,9 +210,9 @@ __global__ void wl_slots_kernel(WorklistArgs a, MultiArgs m)
     a.slot_out[slot] = a.qoff[q] + a.pair_off[(size_t)q * (a.nprobe + 1) + r];
 }
 
-// tiles: one wave per list; tile order inside a list is [query group][page], so that
+// tiles: one workgroup per list; tile order inside a list is [query group][page], so that
 // neighbouring tiles share their query group
-__global__ __launch_bounds__(64) void wl_tiles_kernel(WorklistArgs a, MultiArgs m)
+__global__ __launch_bounds__(256) void wl_tiles_kernel(WorklistArgs a, MultiArgs m)
 {
     const uint32_t gl = blockIdx.x;
     const uint32_t c = a.lcnt[gl];
@@ -314,7 +314,7 @@ hipError_t launch_worklist(const WorklistArgs &a, const MultiArgs &m, hipStream_
     hipLaunchKernelGGL(wl_scan_kernel, dim3(1), dim3(1024), 0, s, a, m);
     const size_t pairs = (size_t)a.nq * a.nprobe;
     hipLaunchKernelGGL(wl_slots_kernel, dim3((uint32_t)((pairs + 255) / 256)), dim3(256), 0, s, a, m);
-    hipLaunchKernelGGL(wl_tiles_kernel, dim3(nl), dim3(64), 0, s, a, m);
+    hipLaunchKernelGGL(wl_tiles_kernel, dim3(nl), dim3(256), 0, s, a, m);
     return hipGetLastError();
 }
 
