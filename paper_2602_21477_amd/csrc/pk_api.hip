@@ -212,6 +212,9 @@ int tune(const char *name, int dflt)
     return v ? atoi(v) : dflt;
 }
 
+// a tile of the threshold sample scores one query against one page of its first probed list
+constexpr int kSampleSlots = 1;
+
 int grid_for(const pk_index *ix, int row_bytes, int mq)
 {
     const int lds = scan_lds_bytes(row_bytes, mq);
@@ -263,10 +266,9 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
     if (p.mq_f < 16) return PK_ERR_UNSUPPORTED;
     p.grid_f = grid_for(own, own->row_bytes, p.mq_f);
     p.grid_h = own->num_cu * std::max(1, std::min((160 * 1024) / scan_ks_lds_bytes(p.mq_h), tune("PK_TUNE_WGS", 4)));
-    p.grid_s = grid_for(own, own->row_bytes, 16);
+    p.grid_s = grid_for(own, own->row_bytes, kSampleSlots);
     p.K = k + 1;
     p.sp = (k + own->P - 1) / own->P; // sample pages: at least k rows of the first probed list
-    p.span = (uint32_t)(p.sp * own->P);
     uint64_t cand = 0, tiles = 0, wmax = 0;
     int nlist_hi = 0, pad_hi = 0;
     for (int a = 0; a < nh; ++a) {
@@ -282,6 +284,21 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
         tiles += std::min<uint64_t>(pages_used_ub(ix), nqa * pp) + nqa * pp / std::min(p.mq_f, p.mq_h) + 1;
     }
     if (cand > 0xfffffff0ull || tiles > 0xfffffff0ull) return PK_ERR_UNSUPPORTED;
+    {
+        // Sample pages per query.  A larger sample gives a tighter threshold and a finer bucket
+        // scale, hence fewer emitted candidates; it costs one tile per query and page.  Wanted:
+        // the k-th best of the sample at most its 30 % quantile (large k); and, for batches of
+        // few queries, whose emitted candidates all meet at a handful of counters and
+        // serialise there, a sample of 0.5 % of the most rows a query can meet (long lists).
+        // Spent: at most 3 % of the scan's tiles, and 16 pages.
+        const uint64_t afford = tiles * 3u / 100u / (uint64_t)std::max<int64_t>(nq, 1);
+        const uint64_t by_quantile = ((uint64_t)p.K * 10 + 3 * own->P - 1) / (3 * own->P);
+        const uint64_t by_size = nq <= 64 ? (wmax / 200 + own->P - 1) / own->P : 0;
+        uint64_t more = std::min(afford, std::max(by_quantile, by_size));
+        more = std::min<uint64_t>(more, (uint64_t)tune("PK_TUNE_SP_MAX", 16));
+        p.sp = std::max(p.sp, (int)more);
+    }
+    p.span = (uint32_t)(p.sp * own->P);
     p.nlist_max = nlist_hi;
     p.stride = (uint32_t)pad_hi;
     p.cchunks = (nlist_hi + kSelChunk - 1) / kSelChunk;
@@ -428,7 +445,7 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
     ss.row_bytes = own->row_bytes;
     ss.metric = own->cfg.metric;
     ss.storage = own->cfg.storage;
-    ss.mq = 16;
+    ss.mq = kSampleSlots;
     PK_HIP(launch_scan(ss, p.grid_s, s));
     PK_HIP(launch_tau(sm, s));
 

@@ -296,8 +296,13 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(3, 8
     const int row_bytes = a.row_bytes;
     const int qstride = row_bytes + kQPadBytes;
     char *qtile = smem;
+    // Groups of fewer than 16 slots (a.mq of 1 to 15, MT = 1): only that many query rows are
+    // held, plus one row of zeros that the MFMA columns without a slot read.  The threshold
+    // sample, one query per tile, runs this way: its LDS use stays small for any row length.
+    const int qrows = a.mq < MQ ? a.mq : MQ;
+    const int qheld = qrows < MQ ? qrows + 1 : MQ;
     Slots s;
-    s.carve(smem + (size_t)MQ * qstride, MQ);
+    s.carve(smem + (size_t)qheld * qstride, MQ);
     uint32_t *s_misc = s.bmax + MQ; // kScanSlotWords per-slot arrays precede this: keep scan_lds_bytes in step
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -305,7 +310,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(3, 8
     const int nit = row_bytes / kIterBytes;
     const int chunks_per_row = row_bytes / 16;
     uint32_t cur_qbeg = 0xffffffffu, cur_qcnt = 0;
-    const char *qbase = qtile + (size_t)ln * qstride + lg * 16;
+    const char *qbase = qtile + (size_t)(ln < qrows ? ln : qrows) * qstride + lg * 16;
 
     Sched sc;
     sc.start(*a.ntiles, *a.batch);
@@ -360,7 +365,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(3, 8
         const Tile nxt = a.tiles[tn < sc.ntiles ? tn : sc.ntiles - 1]; // in flight while this tile is scored
         if (qbeg != cur_qbeg || qcnt != cur_qcnt) {
             __syncthreads(); // everyone is done with the previous query group
-            const int mrows = (int)((qcnt + 15u) & ~15u);
+            const int mrows = qrows < MQ ? qheld : (int)((qcnt + 15u) & ~15u); // rows past the group's last: zeros
             for (int idx = tid; idx < mrows * chunks_per_row; idx += WAVES * 64) {
                 const int m = idx / chunks_per_row, c = idx - m * chunks_per_row;
                 u32x4 v = {0u, 0u, 0u, 0u};
@@ -674,7 +679,9 @@ hipError_t launch_centroid_scores(const CentroidArgs &a, const MultiArgs &m, hip
 
 int scan_lds_bytes(int row_bytes, int mq)
 {
-    return mq * (row_bytes + kQPadBytes) + mq * kScanSlotWords * 4 + 16; // query tile + per-slot arrays + scratch
+    const int rows = mq < 16 ? mq + 1 : mq; // small groups: their query rows and one row of zeros
+    const int cols = mq < 16 ? 16 : mq;     // MFMA columns = length of the per-slot arrays
+    return rows * (row_bytes + kQPadBytes) + cols * kScanSlotWords * 4 + 16; // query tile + per-slot arrays + scratch
 }
 
 int scan_ks_lds_bytes(int mq)
@@ -712,7 +719,7 @@ template <int STORAGE, int MT, int WAVES, bool GATED>
 static hipError_t launch_one(const ScanArgs &a, int grid, hipStream_t s)
 {
     static int cleared = 0;
-    return launch_with_lds(&scan_kernel<STORAGE, MT, WAVES, GATED>, cleared, scan_lds_bytes(a.row_bytes, MT * 16), a, grid,
+    return launch_with_lds(&scan_kernel<STORAGE, MT, WAVES, GATED>, cleared, scan_lds_bytes(a.row_bytes, a.mq), a, grid,
                            WAVES * 64, s);
 }
 
@@ -726,6 +733,7 @@ static hipError_t launch_ks_one(const ScanArgs &a, int grid, hipStream_t s)
 template <int STORAGE, int WAVES, bool GATED>
 static hipError_t launch_mt(const ScanArgs &a, int grid, hipStream_t s)
 {
+    if (a.mq >= 1 && a.mq < 16) return launch_one<STORAGE, 1, WAVES, GATED>(a, grid, s);
     switch (a.mq) {
     case 16: return launch_one<STORAGE, 1, WAVES, GATED>(a, grid, s);
     case 32: return launch_one<STORAGE, 2, WAVES, GATED>(a, grid, s);
