@@ -342,6 +342,8 @@ int run_coarse(const Plan &p, const MultiArgs &m, pk_index *const *hs, const flo
     qm.cand_off = p.cand_off;
     qm.cand_cnt = p.cand_cnt;
     qm.qagent = p.qagent;
+    qm.clear = p.need_fine ? p.lcnt : nullptr;
+    qm.nclear = p.need_fine ? (uint32_t)p.nh * (uint32_t)p.nlist_max : 0u;
     PK_HIP(launch_prep_coarse(q, p.nq, own->cfg.d, own->rb32, p.qs32, p.qn32, qm, m, s));
     // small segments: one launch of the centroid kernel for all of them
     CentroidArgs ca{};
@@ -431,24 +433,6 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
     sm.tinv = p.tinv;
     sm.tcur = p.tcur;
     sm.hist = p.hist;
-    PK_HIP(launch_sample_tiles(sm, m, s));
-    ScanArgs ss{};
-    ss.tiles = p.stiles;
-    ss.ntiles = p.scalars + 8;
-    ss.tile_ctr = p.scalars + 9;
-    ss.batch = p.scalars + 10;
-    ss.qs = p.qs;
-    ss.qnorm = p.qn;
-    ss.slot_query = p.sslot_q;
-    ss.slot_out = p.sslot_o;
-    ss.out = p.svals;
-    ss.row_bytes = own->row_bytes;
-    ss.metric = own->cfg.metric;
-    ss.storage = own->cfg.storage;
-    ss.mq = kSampleSlots;
-    PK_HIP(launch_scan(ss, p.grid_s, s));
-    PK_HIP(launch_tau(sm, s));
-
     WorklistArgs w{};
     w.probes = p.probes;
     w.qagent = p.qagent;
@@ -478,7 +462,26 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
     w.cand_cap = p.cand_cap;
     w.scalars = p.scalars + 4;
     w.scalars_hot = p.scalars + 12;
-    PK_HIP(launch_worklist(w, m, s));
+    w.lcnt_cleared = p.need_coarse;
+    PK_HIP(launch_worklist_count(w, sm, m, s));
+    ScanArgs ss{};
+    ss.tiles = p.stiles;
+    ss.ntiles = p.scalars + 8;
+    ss.tile_ctr = p.scalars + 9;
+    ss.batch = p.scalars + 10;
+    ss.qs = p.qs;
+    ss.qnorm = p.qn;
+    ss.slot_query = p.sslot_q;
+    ss.slot_out = p.sslot_o;
+    ss.out = p.svals;
+    ss.row_bytes = own->row_bytes;
+    ss.metric = own->cfg.metric;
+    ss.storage = own->cfg.storage;
+    ss.mq = kSampleSlots;
+    PK_HIP(launch_scan(ss, p.grid_s, s));
+    PK_HIP(launch_tau(sm, s));
+
+    PK_HIP(launch_worklist_tiles(w, m, s));
     if (timed) PK_TRY(mark(own, s));
     ScanArgs sa{};
     sa.tiles = p.tiles;

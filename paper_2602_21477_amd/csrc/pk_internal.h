@@ -219,6 +219,8 @@ struct QueryMeta {
     uint32_t stride;               // elements between the score rows of consecutive queries
     uint32_t *cand_off, *cand_cnt; // [nq] score row of each query and its length (nlist of its handle)
     uint16_t *qagent;              // [nq] handle number of each query
+    uint32_t *clear;               // words the fine step wants zeroed before it starts (or null)
+    uint32_t nclear;
 };
 // fp32 queries -> zero padded rows and squared norms, plus the bookkeeping above
 hipError_t launch_prep_coarse(const float *q, int64_t nq, int d, int row_bytes, void *qs, float *qnorm,
@@ -257,6 +259,7 @@ struct WorklistArgs {
     int mq_hot;                // slots per group of a hot tile (sliced-query kernel)
     uint32_t hot_from;         // lists probed by more than this many queries of the batch are hot
     uint32_t *lcnt, *lstart, *lfill, *ltile, *lhtile; // [n_handles * nlist_max]
+    bool lcnt_cleared;         // the coarse step of the same search has zeroed lcnt already
     uint32_t *pair_off;        // [nq][nprobe+1]
     uint32_t *qtot, *qoff;     // [nq]
     uint32_t *ccnt;            // [nq] zeroed here (emission counters of the gated scan)
@@ -266,7 +269,6 @@ struct WorklistArgs {
     uint32_t *scalars;         // [0] ntiles [1] tile counter [2] grab size [3] total candidates
     uint32_t *scalars_hot;     // [0] hot tiles [1] tile counter [2] grab size
 };
-hipError_t launch_worklist(const WorklistArgs &a, const MultiArgs &m, hipStream_t s);
 
 // Threshold sampling: the first `sp` pages of each query's first probed list are scored
 // densely; the k-th best of them bounds the query's k-th best overall.
@@ -287,7 +289,8 @@ struct SampleArgs {
     uint32_t *hist;            // [nq][kHistBins] zeroed here
     uint32_t *tcur;            // [nq] out: running bucket limit, starts at kHistBins-1
 };
-hipError_t launch_sample_tiles(const SampleArgs &a, const MultiArgs &m, hipStream_t s);
+hipError_t launch_worklist_count(const WorklistArgs &a, const SampleArgs &sm, const MultiArgs &m, hipStream_t s);
+hipError_t launch_worklist_tiles(const WorklistArgs &a, const MultiArgs &m, hipStream_t s);
 hipError_t launch_tau(const SampleArgs &a, hipStream_t s);
 
 // dense coarse scoring on the matrix cores (large query batches, build)

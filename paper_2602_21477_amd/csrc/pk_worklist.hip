@@ -70,6 +70,8 @@ __global__ __launch_bounds__(256) void prep_coarse_kernel(const float *q, int d,
                                                           QueryMeta meta, MultiArgs m)
 {
     prep_row(q, d, PK_F32, row_bytes, qs, qnorm);
+    // first kernel of a search: also clears the per-list pair counters of the fine step
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < meta.nclear; i += gridDim.x * blockDim.x) meta.clear[i] = 0u;
     if (threadIdx.x == 0) {
         const uint32_t t = blockIdx.x;
         int h = 0;
@@ -100,13 +102,55 @@ hipError_t launch_prep_coarse(const float *q, int64_t nq, int d, int row_bytes, 
 
 // ---------------------------------------------------------------- list work list
 
-// per query: count the pairs per list, lay the query's candidate range out probe by probe
-__global__ __launch_bounds__(256) void wl_count_kernel(WorklistArgs a, MultiArgs m)
+// per query: count the pairs per list, lay the query's candidate range out probe by probe;
+// and the tiles of the query's threshold sample: the first sm.sp pages of its first probed list
+__global__ __launch_bounds__(256) void wl_count_kernel(WorklistArgs a, SampleArgs sm, MultiArgs m)
 {
     __shared__ uint32_t s_len[PK_MAX_NPROBE];
     const uint32_t q = blockIdx.x;
     const uint32_t ag = a.qagent[q];
     const DevIndex &ix = *m.ix[ag];
+    {
+        const float worst = sm.metric == PK_METRIC_IP ? -INFINITY : INFINITY;
+        float *v = sm.vals + (size_t)q * sm.span;
+        for (uint32_t i = threadIdx.x; i < sm.span; i += blockDim.x) v[i] = worst;
+        if (threadIdx.x == 0) {
+            sm.slot_query[q] = q;
+            sm.slot_out[q] = q * sm.span;
+            if (q == 0) {
+                const uint32_t ntiles = (uint32_t)sm.nq * (uint32_t)sm.sp;
+                sm.scalars[0] = ntiles;
+                sm.scalars[1] = 0;
+                const uint32_t g = ntiles / (uint32_t)(sm.scan_grid * 4);
+                sm.scalars[2] = g < 1 ? 1 : (g > 8 ? 8 : g);
+            }
+        }
+        const uint32_t l = (uint32_t)sm.probes[(size_t)q * sm.nprobe];
+        const uint32_t P = (uint32_t)ix.P;
+        for (uint32_t p = threadIdx.x; p < (uint32_t)sm.sp; p += blockDim.x) {
+            Tile tl;
+            tl.x = ix.arenas[0].vec;
+            tl.xn = ix.arenas[0].norm;
+            tl.row0 = p * P;
+            tl.qbeg = q;
+            tl.nrows = 0;
+            tl.qcnt = 1;
+            tl.pad = 0;
+            if (l < (uint32_t)ix.nlist) {
+                const uint32_t len = ix.list_len[l];
+                if (p * P < len) {
+                    const uint32_t pg = phys_page(ix, l, p);
+                    const Arena &ar = arena_of(ix, pg);
+                    const size_t local = pg - ar.first_page;
+                    tl.x = ar.vec + local * P * (size_t)ix.row_bytes;
+                    tl.xn = ar.norm + local * P;
+                    const uint32_t left = len - p * P;
+                    tl.nrows = (uint16_t)(left < P ? left : P);
+                }
+            }
+            sm.tiles[(size_t)q * sm.sp + p] = tl;
+        }
+    }
     for (int r = threadIdx.x; r < a.nprobe; r += blockDim.x) {
         const uint32_t l = (uint32_t)a.probes[(size_t)q * a.nprobe + r];
         uint32_t len = 0;
@@ -248,69 +292,22 @@ __global__ __launch_bounds__(256) void wl_tiles_kernel(WorklistArgs a, MultiArgs
 
 // ------------------------------------------------------------- threshold sampling
 
-// One tile per (query, sample page): pages 0 .. sp-1 of the query's first probed list, one
-// query slot each.  Also pre-fills the sample values with the padding value, so rows that
-// do not exist (short lists) never count.
-__global__ void sample_tiles_kernel(SampleArgs a, MultiArgs m)
+// first half of the work list: pairs per list and the candidate layout of every query, and the
+// tiles of the threshold sample (which the caller scores next)
+hipError_t launch_worklist_count(const WorklistArgs &a, const SampleArgs &sm, const MultiArgs &m, hipStream_t s)
 {
-    const size_t nvals = (size_t)a.nq * a.span;
-    const float worst = a.metric == PK_METRIC_IP ? -INFINITY : INFINITY;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvals; i += (size_t)gridDim.x * blockDim.x)
-        a.vals[i] = worst;
-    const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
-    const uint32_t ntiles = (uint32_t)a.nq * (uint32_t)a.sp;
-    if (t == 0) {
-        a.scalars[0] = ntiles;
-        a.scalars[1] = 0;
-        uint32_t g = ntiles / (uint32_t)(a.scan_grid * 4);
-        a.scalars[2] = g < 1 ? 1 : (g > 8 ? 8 : g);
+    if (!a.lcnt_cleared) {
+        const hipError_t e = launch_fill_u32(a.lcnt, 0u, (size_t)a.n_handles * (size_t)a.nlist_max, s);
+        if (e != hipSuccess) return e;
     }
-    if (t >= ntiles) return;
-    const uint32_t q = t / (uint32_t)a.sp, p = t - q * (uint32_t)a.sp;
-    if (p == 0) {
-        a.slot_query[q] = q;
-        a.slot_out[q] = q * a.span;
-    }
-    const DevIndex &ix = *m.ix[a.qagent[q]];
-    const uint32_t l = (uint32_t)a.probes[(size_t)q * a.nprobe];
-    const uint32_t P = (uint32_t)ix.P;
-    Tile tl;
-    tl.x = ix.arenas[0].vec;
-    tl.xn = ix.arenas[0].norm;
-    tl.row0 = p * P;
-    tl.qbeg = q;
-    tl.nrows = 0;
-    tl.qcnt = 1;
-    tl.pad = 0;
-    if (l < (uint32_t)ix.nlist) {
-        const uint32_t len = ix.list_len[l];
-        if (p * P < len) {
-            const uint32_t pg = phys_page(ix, l, p);
-            const Arena &ar = arena_of(ix, pg);
-            const size_t local = pg - ar.first_page;
-            tl.x = ar.vec + local * P * (size_t)ix.row_bytes;
-            tl.xn = ar.norm + local * P;
-            const uint32_t left = len - p * P;
-            tl.nrows = (uint16_t)(left < P ? left : P);
-        }
-    }
-    a.tiles[t] = tl;
-}
-
-hipError_t launch_sample_tiles(const SampleArgs &a, const MultiArgs &m, hipStream_t s)
-{
-    const size_t n = (size_t)a.nq * a.span;
-    const uint32_t grid = (uint32_t)std::min<size_t>((n + 255) / 256, 4096) + (uint32_t)((a.nq * a.sp + 255) / 256);
-    hipLaunchKernelGGL(sample_tiles_kernel, dim3(grid), dim3(256), 0, s, a, m);
+    hipLaunchKernelGGL(wl_count_kernel, dim3((uint32_t)a.nq), dim3(256), 0, s, a, sm, m);
     return hipGetLastError();
 }
 
-hipError_t launch_worklist(const WorklistArgs &a, const MultiArgs &m, hipStream_t s)
+// second half: slot ranges of the lists, slots of the pairs, tiles
+hipError_t launch_worklist_tiles(const WorklistArgs &a, const MultiArgs &m, hipStream_t s)
 {
     const uint32_t nl = (uint32_t)a.n_handles * (uint32_t)a.nlist_max;
-    hipError_t e = launch_fill_u32(a.lcnt, 0u, nl, s);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(wl_count_kernel, dim3((uint32_t)a.nq), dim3(256), 0, s, a, m);
     hipLaunchKernelGGL(wl_scan_kernel, dim3(1), dim3(1024), 0, s, a, m);
     const size_t pairs = (size_t)a.nq * a.nprobe;
     hipLaunchKernelGGL(wl_slots_kernel, dim3((uint32_t)((pairs + 255) / 256)), dim3(256), 0, s, a, m);
