@@ -219,17 +219,42 @@ class Scenario:
         torch, B, W, cfg = self.torch, self.B, self.W, self.cfg
         ix = self.indexes[0]
         done = 0
+        ins_s, ins_n = 0.0, 0
         while done < extra_inserts:
             m = min(1024, extra_inserts - done)
             rows = np.concatenate([W.inserts(cfg, 100000 + (done + j) // 256, 256) for j in range(0, m, 256)])[:m]
+            dev_rows = torch.from_numpy(rows).cuda()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
             try:
-                ix.insert(torch.from_numpy(rows).cuda())
+                ix.insert(dev_rows)
             except B.PancakeError as e:
                 if e.status != B.PK_ERR_NOMEM:
                     raise
                 ix.add_arena(B.pk_arena_bytes(ix.cfg, 0, max(extra_inserts - done, 1024)))
                 continue
+            torch.cuda.synchronize()
+            if m == 1024 and done > 0:  # the first batch warms the path up
+                ins_s += time.perf_counter() - t0
+                ins_n += m
             done += m
+        # single-vector inserts, back to back on the stream (rows already resident)
+        singles = torch.from_numpy(W.inserts(cfg, 200000, 256)).cuda()
+        single_us = None
+        for attempt in range(2):
+            try:
+                ix.insert(singles[:1])
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for j in range(1, 201):
+                    ix.insert(singles[j:j + 1])
+                torch.cuda.synchronize()
+                single_us = (time.perf_counter() - t0) / 200 * 1e6
+                break
+            except B.PancakeError as e:
+                if e.status != B.PK_ERR_NOMEM or attempt:
+                    raise
+                ix.add_arena(B.pk_arena_bytes(ix.cfg, 0, 1024))
 
         def ms_per_step():
             torch.cuda.synchronize()
@@ -272,7 +297,9 @@ class Scenario:
         after_split = ms_per_step()
         self.check_errors()
         copied = int(st.pages_used) * page_bytes
-        return {"extra_inserts": extra_inserts, "deleted": n_del, "delete_ms_per_4088_ids": del_ms,
+        return {"extra_inserts": extra_inserts,
+                "insert_vectors_per_s_batches_of_1024": (ins_n / ins_s) if ins_s > 0 else None,
+                "insert_us_per_single_vector_call": single_us, "deleted": n_del, "delete_ms_per_4088_ids": del_ms,
                 "ids_scanned_per_s": float(st.n_total + n_del) / (del_ms * 1e-3), "n_total": int(st.n_total), "arenas_before": int(st.n_arenas),
                 "compaction_ms": dt * 1e3, "bytes_copied": copied,
                 "copy_GBps_read_plus_write": 2 * copied / dt / 1e9, "ms_per_step_before": before,
