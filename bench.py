@@ -306,6 +306,46 @@ class Scenario:
                 "ms_per_step_after": after, "split_threshold": thr, "lists_split": n_split, "split_ms": split_ms,
                 "ms_per_step_after_split": after_split}
 
+    def graph_replay(self, steps=50):
+        """The search of a step (no insert: an insert also advances host-side counters) captured into
+        a HIP graph and replayed: what the launches themselves cost on small batches."""
+        torch, B, cfg = self.torch, self.B, self.cfg
+        q = self.q[0]
+
+        def search():
+            if len(self.indexes) == 1:
+                B.pk_search(self.handle, q, cfg.k, cfg.nprobe, self.out_ids, self.out_dist)
+            else:
+                B.pk_search_multi([ix.handle for ix in self.indexes], self.q_offsets, q, cfg.k, cfg.nprobe,
+                                  self.out_ids, self.out_dist)
+
+        def timed(fn):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / steps * 1e3
+
+        search()
+        torch.cuda.synchronize()
+        want_ids, want_dist = self.out_ids.clone(), self.out_dist.clone()
+        eager = timed(search)
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                search()
+        torch.cuda.synchronize()
+        self.out_ids.fill_(-7)
+        graph.replay()
+        torch.cuda.synchronize()
+        same = bool(torch.equal(self.out_ids, want_ids) and torch.equal(self.out_dist, want_dist))
+        replay = timed(graph.replay)
+        self.check_errors()
+        return {"eager_ms_per_search": eager, "graph_ms_per_search": replay, "replay_equals_eager": same,
+                "queries_per_s_graph": self.queries_per_step() / (replay * 1e-3)}
+
     def scope_union(self, steps=30):
         """One agent's query batch searched across the memories of ALL agents of the workload
         (pk_search_union): the same number of (query, index) searches as one multi-agent step."""
@@ -443,6 +483,9 @@ def run(args):
         # baseline needs host data only
         out["cpu_baseline"] = sc.cpu_baseline()
         log(f"cpu baseline: {out['cpu_baseline']['value']:.1f} queries/s on {out['cpu_baseline']['cores']} threads")
+    if args.graph:
+        out["hip_graph"] = sc.graph_replay()
+        log(f"hip graph: {out['hip_graph']}")
     if args.union:
         out["scope_union"] = sc.scope_union()
         log(f"scope union: {out['scope_union']}")
@@ -464,6 +507,8 @@ def main():
     ap.add_argument("--recall-queries", type=int, default=8)
     ap.add_argument("--no-recall", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="also capture one search into a HIP graph and time its replays (extra field)")
     ap.add_argument("--union", action="store_true",
                     help="also time pk_search_union: one agent's batch searched across all agents' memories (extra field)")
     ap.add_argument("--train", type=int, default=0, metavar="ITERS",

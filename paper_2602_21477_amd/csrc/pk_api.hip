@@ -527,7 +527,8 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
     se.nchunks = p.nchunks;
     se.chunk = p.sel_chunk;
     se.partial = p.partial;
-    PK_HIP(launch_select_partial(se, p.nq, s));
+    // no query can have more candidates than one chunk: the final kernel selects straight from the regions
+    if (p.nchunks > 1) PK_HIP(launch_select_partial(se, p.nq, s));
     FinalArgs f{};
     f.partial = p.partial;
     f.nchunks = p.nchunks;

@@ -240,10 +240,10 @@ __global__ __launch_bounds__(1024) void wl_scan_kernel(WorklistArgs a, MultiArgs
     for (uint32_t gl = threadIdx.x; gl < nl; gl += blockDim.x) a.lfill[gl] = 0;
 }
 
-// slots: every (query, probe) pair takes the next free slot of its list
-__global__ void wl_slots_kernel(WorklistArgs a, MultiArgs m)
+// slots: every (query, probe) pair takes the next free slot of its list (one thread per pair)
+__device__ __forceinline__ void wl_slots_block(const WorklistArgs &a, const MultiArgs &m, uint32_t block)
 {
-    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t i = (size_t)block * blockDim.x + threadIdx.x;
     if (i >= (size_t)a.nq * a.nprobe) return;
     const uint32_t q = (uint32_t)(i / a.nprobe), r = (uint32_t)(i - (size_t)q * a.nprobe);
     const uint32_t ag = a.qagent[q];
@@ -256,9 +256,8 @@ __global__ void wl_slots_kernel(WorklistArgs a, MultiArgs m)
 
 // tiles: one workgroup per list; tile order inside a list is [query group][page], so that
 // neighbouring tiles share their query group
-__global__ __launch_bounds__(256) void wl_tiles_kernel(WorklistArgs a, MultiArgs m)
+__device__ __forceinline__ void wl_tiles_block(const WorklistArgs &a, const MultiArgs &m, uint32_t gl)
 {
-    const uint32_t gl = blockIdx.x;
     const uint32_t c = a.lcnt[gl];
     if (c == 0) return;
     const bool hot = c > a.hot_from;
@@ -290,7 +289,14 @@ __global__ __launch_bounds__(256) void wl_tiles_kernel(WorklistArgs a, MultiArgs
     }
 }
 
-// ------------------------------------------------------------- threshold sampling
+// Slots and tiles both need only the offsets wl_scan wrote, not each other: one launch, the
+// first slot_blocks workgroups place the pairs, the others write one list's tiles each.
+__global__ __launch_bounds__(256) void wl_slots_tiles_kernel(WorklistArgs a, MultiArgs m, uint32_t slot_blocks)
+{
+    if (blockIdx.x < slot_blocks) wl_slots_block(a, m, blockIdx.x);
+    else wl_tiles_block(a, m, blockIdx.x - slot_blocks);
+}
+
 
 // first half of the work list: pairs per list and the candidate layout of every query, and the
 // tiles of the threshold sample (which the caller scores next)
@@ -309,9 +315,8 @@ hipError_t launch_worklist_tiles(const WorklistArgs &a, const MultiArgs &m, hipS
 {
     const uint32_t nl = (uint32_t)a.n_handles * (uint32_t)a.nlist_max;
     hipLaunchKernelGGL(wl_scan_kernel, dim3(1), dim3(1024), 0, s, a, m);
-    const size_t pairs = (size_t)a.nq * a.nprobe;
-    hipLaunchKernelGGL(wl_slots_kernel, dim3((uint32_t)((pairs + 255) / 256)), dim3(256), 0, s, a, m);
-    hipLaunchKernelGGL(wl_tiles_kernel, dim3(nl), dim3(256), 0, s, a, m);
+    const uint32_t slot_blocks = (uint32_t)(((size_t)a.nq * a.nprobe + 255) / 256);
+    hipLaunchKernelGGL(wl_slots_tiles_kernel, dim3(slot_blocks + nl), dim3(256), 0, s, a, m, slot_blocks);
     return hipGetLastError();
 }
 

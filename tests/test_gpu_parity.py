@@ -582,6 +582,48 @@ def test_wide_rows_many_queries_per_list(gpu_device):
             p.close()
 
 
+def test_search_replays_from_a_hip_graph(gpu_device):
+    """A search enqueues kernels only (no allocation, no host synchronisation once the handle's workspace
+    has been sized by an earlier call of the same shape), so it can be captured into a HIP graph.  Every
+    replay, with eager work between the replays, must give exactly what the eager call gives on the
+    queries then in the input buffer; the eager call itself is checked against the oracle."""
+    cfg = W.scaled(W.C1, n=6000)
+    for storage, metric in ((F32, IP), (F16, L2)):
+        p, _ = make_pair(cfg, metric=metric, storage=storage)
+        try:
+            k, nprobe, nq = 10, 8, 48
+            qbuf = torch.empty((nq, cfg.d), dtype=torch.float32, device="cuda")
+            ids = torch.empty((nq, k), dtype=torch.int64, device="cuda")
+            dist = torch.empty((nq, k), dtype=torch.float32, device="cuda")
+            qbuf.copy_(dev(W.queries(cfg, 20, nq)))
+            B.pk_search(p.gpu.handle, qbuf, k, nprobe, ids, dist)  # sizes the workspace
+            torch.cuda.synchronize()
+            side = torch.cuda.Stream()
+            graph = torch.cuda.CUDAGraph()
+            say(f"graph capture storage={storage} metric={metric}")
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(graph, stream=side):
+                    B.pk_search(p.gpu.handle, qbuf, k, nprobe, ids, dist)
+            torch.cuda.synchronize()
+            for rep in range(3):
+                q = W.queries(cfg, 21 + rep, nq)
+                qbuf.copy_(dev(q))
+                ids.fill_(-7)
+                dist.fill_(0)
+                torch.cuda.synchronize()
+                say(f"graph replay {rep}")
+                graph.replay()
+                torch.cuda.synchronize()
+                gi, gv = ids.cpu().numpy().copy(), dist.cpu().numpy().copy()
+                ei, ev = p.gpu.search(qbuf, k, nprobe)  # eager, between the replays
+                torch.cuda.synchronize()
+                assert np.array_equal(gi, ei.cpu().numpy()), f"replay {rep}: ids differ from the eager call"
+                assert np.array_equal(gv, ev.cpu().numpy()), f"replay {rep}: values differ from the eager call"
+                p.check_search(q, k, nprobe, where=f"eager after replay {rep}")
+        finally:
+            p.close()
+
+
 def test_large_k_no_threshold_and_chunked_selection(gpu_device):
     """k larger than the first probed list: no threshold can be drawn, every candidate is emitted,
     and the per-query selection runs over several chunks (> 32768 candidates)."""
