@@ -815,8 +815,14 @@ int insert_batch(pk_index *const *hs, int nh, const uint32_t *qlo, const float *
     }
     AppendIds idc{};
     for (int a = 0; a < nh; ++a) idc.id0[a] = hs[a]->next_id;
-    PK_HIP(launch_reserve(mm, assign, slots, assigned_out, s));
-    PK_HIP(launch_append(mm, idc, x, ids, assign, slots, s));
+    bool small = true;
+    for (int a = 0; a < nh; ++a) small = small && qlo[a + 1] - qlo[a] <= (uint32_t)kFusedAppend;
+    if (small) {
+        PK_HIP(launch_reserve_append(mm, idc, x, ids, assign, slots, assigned_out, s));
+    } else {
+        PK_HIP(launch_reserve(mm, assign, slots, assigned_out, s));
+        PK_HIP(launch_append(mm, idc, x, ids, assign, slots, s));
+    }
     for (int a = 0; a < nh; ++a) PK_TRY(note_inserted(hs[a], (int64_t)(qlo[a + 1] - qlo[a]), s));
     return PK_OK;
 }

@@ -110,11 +110,14 @@ hipError_t launch_scatter_build(const DevIndex *ix, const float *x, const int64_
 // the order inside a list is the arrival order.  A vector whose slot starts a page beyond
 // the build-time extent opens a delta page.  If the arena or a list's delta table cannot
 // take the whole batch, nothing is changed, every slot is 0xffffffff and the sticky error
-// flag is set.
+// flag is set.  Small batches (x given): the workgroup's 16 waves also write the rows
+// (step 3), which saves the launch that would otherwise follow.
 __global__ __launch_bounds__(1024) void reserve_kernel(MultiArgs ma, const int32_t *assign, uint32_t *slots,
-                                                       int32_t *assigned_out)
+                                                       int32_t *assigned_out, AppendIds idc, const float *x,
+                                                       const int64_t *ids)
 {
     __shared__ int32_t s_l[1024];
+    __shared__ uint32_t s_slot[1024];
     __shared__ uint32_t s_need, s_bad, s_page0;
     // workgroup a serves handle a: its vectors are rows [qlo[a], qlo[a+1]) of the batch
     const DevIndex &ix = *ma.ix[blockIdx.x];
@@ -177,6 +180,15 @@ __global__ __launch_bounds__(1024) void reserve_kernel(MultiArgs ma, const int32
         slots[i] = ok ? slot : 0xffffffffu;
         if (assigned_out) assigned_out[i] = l;
     }
+    if (!x) return;
+    s_slot[i] = ok ? slot : 0xffffffffu;
+    __syncthreads(); // slots, and the page table entries just written, are visible to the whole workgroup
+    for (int r = i >> 6; r < m; r += 16) {
+        if (s_slot[r] == 0xffffffffu) continue;
+        const uint32_t row = row0 + (uint32_t)r;
+        write_row(ix, (uint32_t)s_l[r], s_slot[r], x + (size_t)row * ix.d,
+                  ids ? ids[row] : idc.id0[blockIdx.x] + (int64_t)r);
+    }
 }
 
 hipError_t launch_reserve(const MultiArgs &ma, const int32_t *assign, uint32_t *slots, int32_t *assigned_out, hipStream_t s)
@@ -184,7 +196,20 @@ hipError_t launch_reserve(const MultiArgs &ma, const int32_t *assign, uint32_t *
     if (ma.n <= 0 || ma.qlo[ma.n] == 0) return hipSuccess;
     for (int a = 0; a < ma.n; ++a)
         if (ma.qlo[a + 1] - ma.qlo[a] > 1024u) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(reserve_kernel, dim3(ma.n), dim3(1024), 0, s, ma, assign, slots, assigned_out);
+    hipLaunchKernelGGL(reserve_kernel, dim3(ma.n), dim3(1024), 0, s, ma, assign, slots, assigned_out, AppendIds{}, nullptr,
+                       nullptr);
+    return hipGetLastError();
+}
+
+// steps 2 and 3 in one launch, for batches of at most kFusedAppend vectors per handle
+hipError_t launch_reserve_append(const MultiArgs &ma, const AppendIds &idc, const float *x, const int64_t *ids,
+                                 const int32_t *assign, uint32_t *slots, int32_t *assigned_out, hipStream_t s)
+{
+    if (ma.n <= 0 || ma.qlo[ma.n] == 0) return hipSuccess;
+    if (!x) return hipErrorInvalidValue;
+    for (int a = 0; a < ma.n; ++a)
+        if (ma.qlo[a + 1] - ma.qlo[a] > (uint32_t)kFusedAppend) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(reserve_kernel, dim3(ma.n), dim3(1024), 0, s, ma, assign, slots, assigned_out, idc, x, ids);
     return hipGetLastError();
 }
 

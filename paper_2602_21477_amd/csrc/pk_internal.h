@@ -341,11 +341,15 @@ struct KmeansArgs {
 hipError_t launch_kmeans_update(const KmeansArgs &a, hipStream_t s);
 // Insert: slots for the vectors of every handle of the batch (one workgroup per handle, at most 1024
 // vectors each; rows [qlo[a], qlo[a+1]) of assign / slots / assigned_out belong to handle a), then the rows.
+// batches of at most this many vectors per handle: reservation and row writes share one launch
+constexpr int kFusedAppend = 64;
 struct AppendIds {
     int64_t id0[PK_MAX_HANDLES]; // first id of each handle's segment when the caller gives no ids
 };
 hipError_t launch_reserve(const MultiArgs &ma, const int32_t *assign, uint32_t *slots, int32_t *assigned_out, hipStream_t s);
 hipError_t launch_append(const MultiArgs &ma, const AppendIds &idc, const float *x, const int64_t *ids,
                          const int32_t *assign, const uint32_t *slots, hipStream_t s);
+hipError_t launch_reserve_append(const MultiArgs &ma, const AppendIds &idc, const float *x, const int64_t *ids,
+                                 const int32_t *assign, uint32_t *slots, int32_t *assigned_out, hipStream_t s);
 
 } // namespace pk
