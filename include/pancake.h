@@ -20,7 +20,11 @@
  * Conventions
  *   - Every pointer is marked HOST or DEVICE.  Device buffers belong to the caller
  *     (including arenas); the library owns only the host-side handle and one
- *     grow-only device workspace per handle that it allocates itself.
+ *     grow-only device workspace per handle that it allocates itself.  The workspace
+ *     grows (stream synchronisation, hipFree, hipMalloc) only when a search or insert
+ *     needs more than any earlier call on the handle did; a call of a shape seen before
+ *     allocates nothing and waits for nothing, so the pk_search* calls may then be
+ *     captured into a HIP graph (inserts may not: they advance host-side counters).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work
  *     is enqueued on it; outputs are valid once the caller has synchronised the stream.
  *     Calls on one handle must come from one thread and one stream at a time; an

@@ -206,10 +206,32 @@ void carve(Plan &p, char *base, const pk_index *own)
     p.bytes = round_up(c.off, 256);
 }
 
-int tune(const char *name, int dflt)
+// Developer knobs: environment variables read once per process.  The defaults are the
+// measured choices; the variables exist so that a sweep needs no rebuild.
+struct Tunables {
+    int wgs;      // PK_TUNE_WGS: most scan workgroups per CU
+    int mq;       // PK_TUNE_MQ: most query slots per regular tile (0: by expected queries per list)
+    int mqh;      // PK_TUNE_MQH: most query slots per tile of the sliced-query kernel
+    int ks;       // PK_TUNE_KS: sliced-query kernel 0 never, 1 automatic, 2 every list, 3 lists above one group
+    int sp_max;   // PK_TUNE_SP_MAX: most sample pages per query beyond the k rows needed
+    int gemm_wgs; // PK_TUNE_GEMM_WGS: fewest 128 x 128 tiles for which the coarse step uses the GEMM
+    int densesel; // PK_TUNE_DENSESEL: register top-nprobe selection of the coarse scores (1) or chunked (0)
+    int grabdiv;  // PK_TUNE_GRABDIV: tiles per claimed batch = tiles / (grid * this), at most 8
+    int hist;     // PK_TUNE_HIST: emission gate tightened by the bucket histogram (1) or sample threshold only (0)
+};
+
+const Tunables &tunables()
 {
-    const char *v = getenv(name);
-    return v ? atoi(v) : dflt;
+    static const Tunables t = [] {
+        auto env = [](const char *name, int dflt) {
+            const char *v = getenv(name);
+            return v ? atoi(v) : dflt;
+        };
+        return Tunables{env("PK_TUNE_WGS", 4),       env("PK_TUNE_MQ", 0),        env("PK_TUNE_MQH", 128),
+                        env("PK_TUNE_KS", 1),        env("PK_TUNE_SP_MAX", 16),   env("PK_TUNE_GEMM_WGS", 128),
+                        env("PK_TUNE_DENSESEL", 1),  env("PK_TUNE_GRABDIV", 8),   env("PK_TUNE_HIST", 1)};
+    }();
+    return t;
 }
 
 // a tile of the threshold sample scores one query against one page of its first probed list
@@ -219,7 +241,7 @@ int grid_for(const pk_index *ix, int row_bytes, int mq)
 {
     const int lds = scan_lds_bytes(row_bytes, mq);
     int per_cu = (160 * 1024) / lds;
-    per_cu = std::max(1, std::min(per_cu, tune("PK_TUNE_WGS", 4)));
+    per_cu = std::max(1, std::min(per_cu, tunables().wgs));
     return ix->num_cu * per_cu;
 }
 
@@ -250,10 +272,10 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
         for (int a = 0; a < nh; ++a)
             avg = std::max(avg, (double)(qlo[a + 1] - qlo[a]) * nprobe / hs[a]->cfg.nlist);
         const int want = avg <= 6 ? 16 : (avg <= 20 ? 32 : 64);
-        p.mq_f = std::min(p.mq_f, tune("PK_TUNE_MQ", want));
+        p.mq_f = std::min(p.mq_f, tunables().mq > 0 ? tunables().mq : want);
         p.mq_h = own->cfg.storage == PK_F16 ? 128 : 32;
-        p.mq_h = std::min(p.mq_h, tune("PK_TUNE_MQH", 128));
-        const int ks = tune("PK_TUNE_KS", 1); // 0: never, 1: automatic, 2: every list, 3: hot lists
+        p.mq_h = std::min(p.mq_h, tunables().mqh);
+        const int ks = tunables().ks;
         const bool wide = p.mq_f < 16 || scan_lds_bytes(own->row_bytes, p.mq_f) > 64 * 1024;
         if (ks == 2 || (ks == 1 && wide)) p.hot_from = 0;
         else if (ks == 3) p.hot_from = (uint32_t)p.mq_f;
@@ -265,7 +287,7 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
     }
     if (p.mq_f < 16) return PK_ERR_UNSUPPORTED;
     p.grid_f = grid_for(own, own->row_bytes, p.mq_f);
-    p.grid_h = own->num_cu * std::max(1, std::min((160 * 1024) / scan_ks_lds_bytes(p.mq_h), tune("PK_TUNE_WGS", 4)));
+    p.grid_h = own->num_cu * std::max(1, std::min((160 * 1024) / scan_ks_lds_bytes(p.mq_h), tunables().wgs));
     p.grid_s = grid_for(own, own->row_bytes, kSampleSlots);
     p.K = k + 1;
     p.sp = (k + own->P - 1) / own->P; // sample pages: at least k rows of the first probed list
@@ -295,7 +317,7 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
         const uint64_t by_quantile = ((uint64_t)p.K * 10 + 3 * own->P - 1) / (3 * own->P);
         const uint64_t by_size = nq <= 64 ? (wmax / 200 + own->P - 1) / own->P : 0;
         uint64_t more = std::min(afford, std::max(by_quantile, by_size));
-        more = std::min<uint64_t>(more, (uint64_t)tune("PK_TUNE_SP_MAX", 16));
+        more = std::min<uint64_t>(more, (uint64_t)tunables().sp_max);
         p.sp = std::max(p.sp, (int)more);
     }
     p.span = (uint32_t)(p.sp * own->P);
@@ -319,7 +341,7 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
 bool coarse_by_gemm(uint32_t nqa, const pk_index *ix)
 {
     const uint64_t wgs = (uint64_t)((nqa + 127) / 128) * (uint64_t)((ix->nlist_pad + 127) / 128);
-    return wgs >= (uint64_t)tune("PK_TUNE_GEMM_WGS", 128);
+    return wgs >= (uint64_t)tunables().gemm_wgs;
 }
 
 void fill_multi(MultiArgs &m, pk_index *const *hs, int nh, const uint32_t *qlo)
@@ -388,7 +410,7 @@ int run_coarse(const Plan &p, const MultiArgs &m, pk_index *const *hs, const flo
         g.stride = p.stride;
         PK_HIP(launch_gemm_scores(g, s));
     }
-    if (p.nlist_max <= kDenseSelectMax && tune("PK_TUNE_DENSESEL", 1)) {
+    if (p.nlist_max <= kDenseSelectMax && tunables().densesel) {
         PK_HIP(launch_select_dense(p.S, p.cand_off, p.cand_cnt, (uint32_t)p.nlist_max, own->cfg.metric, p.nprobe, p.nq,
                                    p.probes, s));
         return PK_OK;
@@ -444,7 +466,7 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
     w.mq_hot = p.mq_h;
     w.hot_from = p.hot_from;
     w.scan_grid = p.grid_f;
-    w.grab_div = tune("PK_TUNE_GRABDIV", 8);
+    w.grab_div = tunables().grabdiv;
     w.lcnt = p.lcnt;
     w.lstart = p.lstart;
     w.lfill = p.lfill;
@@ -497,7 +519,7 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
     sa.tlo = p.tlo;
     sa.tinv = p.tinv;
     sa.tcur = p.tcur;
-    sa.use_hist = tune("PK_TUNE_HIST", 1);
+    sa.use_hist = tunables().hist;
     sa.hist = p.hist;
     sa.k = p.k;
     sa.qoff = p.qoff;
