@@ -5,6 +5,8 @@
 //   python -m paper_2602_21477_amd.build        (builds read_pattern_probe.bin beside this file)
 //   ./read_pattern_probe.bin        (buffer of constant bytes)
 //   ./read_pattern_probe.bin r      (buffer of pseudo-random bytes)
+//   ./read_pattern_probe.bin r w    (also: both patterns re-reading a window of 16 MB .. 1 GB that
+//                                    wraps around, i.e. served by L2 / Infinity Cache instead of HBM)
 #include <hip/hip_runtime.h>
 #include <cstdio>
 #include <cstdlib>
@@ -12,13 +14,13 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 #define CK(x) do{hipError_t e=(x); if(e!=hipSuccess){printf("err %s line %d\n", hipGetErrorString(e), __LINE__); exit(1);} }while(0)
 
 template<int UNROLL>
-__global__ __launch_bounds__(256) void readA(const u32x4* p, size_t n16, uint32_t* out){
+__global__ __launch_bounds__(256) void readA(const u32x4* p, size_t n16, uint32_t* out, size_t wrap16){
   size_t i = (size_t)blockIdx.x*blockDim.x + threadIdx.x, stride=(size_t)gridDim.x*blockDim.x;
   u32x4 acc = {0,0,0,0};
   for (; i + (UNROLL-1)*stride < n16; i += UNROLL*stride){
     u32x4 v[UNROLL];
     #pragma unroll
-    for(int u=0;u<UNROLL;++u) v[u]=p[i+u*stride];
+    for(int u=0;u<UNROLL;++u) v[u]=p[(i+u*stride) % wrap16];
     #pragma unroll
     for(int u=0;u<UNROLL;++u) acc ^= v[u];
   }
@@ -26,12 +28,12 @@ __global__ __launch_bounds__(256) void readA(const u32x4* p, size_t n16, uint32_
 }
 // pattern B: page of 128 rows x rowbytes; WG of 4 waves; wave handles 32 rows; lane (ln=l&15, lg=l>>4) loads 16B at row ln (+16), offset it*256 + s*64 + lg*16
 template<int DEPTH>
-__global__ __launch_bounds__(256) void readB(const char* base, size_t npages, int rowbytes, uint32_t* out){
+__global__ __launch_bounds__(256) void readB(const char* base, size_t npages, int rowbytes, uint32_t* out, size_t wrap){
   const int lane=threadIdx.x&63, wave=threadIdx.x>>6, ln=lane&15, lg=lane>>4;
   const int nit=rowbytes/256;
   u32x4 acc={0,0,0,0};
   for(size_t pg=blockIdx.x; pg<npages; pg+=gridDim.x){
-    const char* p0 = base + pg*(size_t)128*rowbytes + (size_t)(wave*32+ln)*rowbytes + lg*16;
+    const char* p0 = base + (pg % wrap)*(size_t)128*rowbytes + (size_t)(wave*32+ln)*rowbytes + lg*16;
     const char* p1 = p0 + (size_t)16*rowbytes;
     u32x4 buf[DEPTH][8];
     #pragma unroll
@@ -66,13 +68,22 @@ int main(int argc, char** argv){
   };
   for (int wgs : {256*8}) {
     char nm[64];
-    snprintf(nm,64,"A unroll4 grid=%d",wgs); timeit(nm,[&]{ hipLaunchKernelGGL(readA<4>, dim3(wgs), dim3(256),0,0,(const u32x4*)d, bytes/16, o);});
-    snprintf(nm,64,"A unroll8 grid=%d",wgs); timeit(nm,[&]{ hipLaunchKernelGGL(readA<8>, dim3(wgs), dim3(256),0,0,(const u32x4*)d, bytes/16, o);});
+    snprintf(nm,64,"A unroll4 grid=%d",wgs); timeit(nm,[&]{ hipLaunchKernelGGL(readA<4>, dim3(wgs), dim3(256),0,0,(const u32x4*)d, bytes/16, o, bytes/16);});
+    snprintf(nm,64,"A unroll8 grid=%d",wgs); timeit(nm,[&]{ hipLaunchKernelGGL(readA<8>, dim3(wgs), dim3(256),0,0,(const u32x4*)d, bytes/16, o, bytes/16);});
   }
   for (int rb : {1536, 3072}) for (int wgs : {256*3,256*8}) {
     size_t npages = bytes/((size_t)128*rb); char nm[64];
-    snprintf(nm,64,"B depth2 rowbytes=%d grid=%d",rb,wgs); timeit(nm,[&]{ hipLaunchKernelGGL(readB<2>, dim3(wgs), dim3(256),0,0,d,npages,rb,o);});
-    snprintf(nm,64,"B depth3 rowbytes=%d grid=%d",rb,wgs); timeit(nm,[&]{ hipLaunchKernelGGL(readB<3>, dim3(wgs), dim3(256),0,0,d,npages,rb,o);});
+    snprintf(nm,64,"B depth2 rowbytes=%d grid=%d",rb,wgs); timeit(nm,[&]{ hipLaunchKernelGGL(readB<2>, dim3(wgs), dim3(256),0,0,d,npages,rb,o,npages);});
+    snprintf(nm,64,"B depth3 rowbytes=%d grid=%d",rb,wgs); timeit(nm,[&]{ hipLaunchKernelGGL(readB<3>, dim3(wgs), dim3(256),0,0,d,npages,rb,o,npages);});
+  }
+  if (argc > 2) {
+    const int rb = 1536;
+    const size_t npages = bytes/((size_t)128*rb);
+    for (size_t mb : {16, 32, 64, 128, 256, 512, 1024}) {
+      const size_t wrap = (mb<<20)/((size_t)128*rb); char nm[64];
+      snprintf(nm,64,"B depth2 window=%zu MB grid=768",mb); timeit(nm,[&]{ hipLaunchKernelGGL(readB<2>, dim3(768), dim3(256),0,0,d,npages,rb,o,wrap);});
+      snprintf(nm,64,"A unroll4 window=%zu MB grid=4096",mb); timeit(nm,[&]{ hipLaunchKernelGGL(readA<4>, dim3(4096), dim3(256),0,0,(const u32x4*)d, bytes/16, o, (mb<<20)/16);});
+    }
   }
   return 0;
 }
