@@ -140,6 +140,7 @@ struct Plan {
     int nprobe, k, nh;
     int mq_f, mq_h, grid_f, grid_h, grid_s, cchunks, nchunks, sel_chunk, K, nlist_max, sp;
     uint32_t hot_from;
+    bool hot_rs; // the hot class is scored by the rows-stationary kernel (tiles of kRsRows rows x all slots of a list)
     uint32_t stride, cand_cap, tile_cap, span;
     bool need_coarse, need_fine, f16;
     // buffers
@@ -218,6 +219,7 @@ struct Tunables {
     int densesel; // PK_TUNE_DENSESEL: register top-nprobe selection of the coarse scores (1) or chunked (0)
     int grabdiv;  // PK_TUNE_GRABDIV: tiles per claimed batch = tiles / (grid * this), at most 8
     int hist;     // PK_TUNE_HIST: emission gate tightened by the bucket histogram (1) or sample threshold only (0)
+    int rs_from;  // PK_TUNE_RS_FROM: lists probed by more queries than this go to the rows-stationary kernel (0: none)
 };
 
 const Tunables &tunables()
@@ -229,7 +231,8 @@ const Tunables &tunables()
         };
         return Tunables{env("PK_TUNE_WGS", 4),       env("PK_TUNE_MQ", 0),        env("PK_TUNE_MQH", 128),
                         env("PK_TUNE_KS", 1),        env("PK_TUNE_SP_MAX", 16),   env("PK_TUNE_GEMM_WGS", 128),
-                        env("PK_TUNE_DENSESEL", 1),  env("PK_TUNE_GRABDIV", 8),   env("PK_TUNE_HIST", 1)};
+                        env("PK_TUNE_DENSESEL", 1),  env("PK_TUNE_GRABDIV", 8),   env("PK_TUNE_HIST", 1),
+                        env("PK_TUNE_RS_FROM", 256)};
     }();
     return t;
 }
@@ -280,6 +283,18 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
         if (ks == 2 || (ks == 1 && wide)) p.hot_from = 0;
         else if (ks == 3) p.hot_from = (uint32_t)p.mq_f;
         else p.hot_from = 0xffffffffu;
+        // Large batches over narrow rows: a list probed by more than rs_from queries is scored with its
+        // rows stationary in LDS, all its queries streaming past them, instead of once per query group.
+        if (p.hot_from == 0xffffffffu && tunables().rs_from > 0 && nq >= 512 && own->row_bytes <= 1536 &&
+            own->P % kRsRows == 0 && scan_rs_lds_bytes(own->row_bytes) <= own->lds_limit) {
+            bool same = true; // one tile geometry for all handles of the call
+            for (int a = 1; a < nh; ++a) same = same && hs[a]->P == own->P;
+            if (same) {
+                p.hot_rs = true;
+                p.hot_from = (uint32_t)tunables().rs_from;
+                p.mq_h = kRsSlots;
+            }
+        }
         if (p.hot_from == 0) {
             p.mq_h = std::min(p.mq_h, std::max(want, 16));
             if (p.mq_f < 16) p.mq_f = 16; // unused, but keeps the tile arithmetic defined
@@ -288,6 +303,7 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
     if (p.mq_f < 16) return PK_ERR_UNSUPPORTED;
     p.grid_f = grid_for(own, own->row_bytes, p.mq_f);
     p.grid_h = own->num_cu * std::max(1, std::min((160 * 1024) / scan_ks_lds_bytes(p.mq_h), tunables().wgs));
+    if (p.hot_rs) p.grid_h = own->num_cu; // one workgroup of 8 waves per CU (its LDS holds the rows and every slot)
     p.grid_s = grid_for(own, own->row_bytes, kSampleSlots);
     p.K = k + 1;
     p.sp = (k + own->P - 1) / own->P; // sample pages: at least k rows of the first probed list
@@ -304,6 +320,8 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
         cand += nqa * w;
         const uint64_t pp = w / ix->P + nprobe;
         tiles += std::min<uint64_t>(pages_used_ub(ix), nqa * pp) + nqa * pp / std::min(p.mq_f, p.mq_h) + 1;
+        // tiles of the rows-stationary kernel are parts of a page: P / kRsRows times the pages
+        if (p.hot_rs) tiles += (uint64_t)(ix->P / kRsRows - 1) * std::min<uint64_t>(pages_used_ub(ix), nqa * pp);
     }
     if (cand > 0xfffffff0ull || tiles > 0xfffffff0ull) return PK_ERR_UNSUPPORTED;
     {
@@ -465,7 +483,9 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
     w.mq = p.mq_f;
     w.mq_hot = p.mq_h;
     w.hot_from = p.hot_from;
+    w.hot_rows = p.hot_rs ? kRsRows : 0;
     w.scan_grid = p.grid_f;
+    w.scan_grid_hot = p.grid_h;
     w.grab_div = tunables().grabdiv;
     w.lcnt = p.lcnt;
     w.lstart = p.lstart;
@@ -536,7 +556,12 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
         sa.tile_ctr = p.scalars + 13;
         sa.batch = p.scalars + 14;
         sa.mq = p.mq_h;
-        PK_HIP(launch_scan_ks(sa, p.grid_h, s));
+        if (p.hot_rs) {
+            sa.use_hist = 0; // the regular lists' scan has published its limits; this one only reads them
+            PK_HIP(launch_scan_rs(sa, p.grid_h, s));
+        } else {
+            PK_HIP(launch_scan_ks(sa, p.grid_h, s));
+        }
     }
     if (timed) PK_TRY(mark(own, s));
     SelectArgs se{};

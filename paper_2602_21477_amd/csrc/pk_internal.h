@@ -12,6 +12,8 @@ namespace pk {
 // ------------------------------------------------------------------ constants
 constexpr int kWave = 64;
 constexpr int kScanThreads = 256;     // 4 waves per workgroup in the scan kernel
+constexpr int kRsRows = 64;           // rows per tile of the rows-stationary scan kernel
+constexpr int kRsSlots = 1024;        // most query slots per tile of that kernel
 constexpr int kRowBlock = 32;         // rows one wave scores per pass (two 16-wide MFMA tiles)
 constexpr int kIterBytes = 256;       // bytes of one row consumed per inner iteration
 constexpr int kQPadBytes = 16;        // LDS row padding of the query tile (bank spread)
@@ -181,6 +183,8 @@ struct ScanArgs {
 };
 hipError_t launch_scan(const ScanArgs &a, int grid, hipStream_t s);
 hipError_t launch_scan_ks(const ScanArgs &a, int grid, hipStream_t s);
+hipError_t launch_scan_rs(const ScanArgs &a, int grid, hipStream_t s);
+int scan_rs_lds_bytes(int row_bytes);
 int scan_lds_bytes(int row_bytes, int mq);
 int scan_ks_lds_bytes(int mq);
 int scan_max_mq(int row_bytes, int storage, int lds_limit);
@@ -254,9 +258,10 @@ struct WorklistArgs {
     const int32_t *probes;     // [nq][nprobe]; entries outside [0, nlist) are ignored
     const uint16_t *qagent;    // [nq]
     int64_t nq;
-    int nprobe, n_handles, nlist_max, scan_grid, grab_div;
+    int nprobe, n_handles, nlist_max, scan_grid, scan_grid_hot, grab_div;
     int mq;                    // slots per group of a regular tile
-    int mq_hot;                // slots per group of a hot tile (sliced-query kernel)
+    int mq_hot;                // slots per group of a hot tile
+    int hot_rows;              // rows per hot tile: 0 = a page; else a divisor of the page size (rows-stationary kernel)
     uint32_t hot_from;         // lists probed by more than this many queries of the batch are hot
     uint32_t *lcnt, *lstart, *lfill, *ltile, *lhtile; // [n_handles * nlist_max]
     bool lcnt_cleared;         // the coarse step of the same search has zeroed lcnt already

@@ -164,6 +164,44 @@ __device__ __forceinline__ void refresh_slot(const ScanArgs &a, const Slots &s, 
     }
 }
 
+// Gated emission, the part after the threshold test: some lane of the wave holds a value
+// that passed its slot's sample threshold (pass).  The 16 lanes of a group share slot m;
+// position = the row's position in its list.  Wave-uniform call.
+__device__ __forceinline__ void emit_survivors(const ScanArgs &a, const Slots &s, float v, uint32_t bits, bool pass, int m,
+                                               uint32_t position, int ln, int lg)
+{
+    uint32_t b = 0;
+    if (pass) {
+        b = bucket_of(v, s.lo[m], s.inv[m], a.metric);
+        pass = b <= s.bmax[m];
+    }
+    const unsigned long long mask = __ballot(pass);
+    const uint32_t gmask = (uint32_t)(mask >> (lg * 16)) & 0xffffu;
+    if (gmask) {
+        // one aggregated atomic per group reserves room in the query's region
+        const int leader = __ffs(gmask) - 1;
+        uint32_t base = 0;
+        if (ln == leader) base = atomicAdd(&a.ccnt[s.q[m]], (uint32_t)__popc(gmask));
+        base = __shfl(base, lg * 16 + leader);
+        if (pass) {
+            const uint32_t rank = __popc(gmask & ((1u << ln) - 1u));
+            a.cbuf[(size_t)s.base[m] + base + rank] = ((unsigned long long)bits << 32) | (s.out[m] + position);
+        }
+        if (a.use_hist) {
+            // count the emitted candidates per bucket; one atomic for the group
+            // when its candidates share a bucket (the usual case)
+            const uint32_t b0 = __shfl(b, lg * 16 + leader);
+            const uint32_t odd = (uint32_t)(__ballot(pass && b != b0) >> (lg * 16)) & 0xffffu;
+            uint32_t *hq = a.hist + (size_t)s.q[m] * kHistBins;
+            if (odd == 0u) {
+                if (ln == leader) atomicAdd(hq + b0, (uint32_t)__popc(gmask));
+            } else if (pass) {
+                atomicAdd(hq + b, 1u);
+            }
+        }
+    }
+}
+
 // Epilogue of one 32-row block: the lane holds rows (rb*32 + nt*16 + ln) for slots
 // mt*16 + lg*4 + i.  Dense mode writes every value; gated mode emits the survivors.
 template <int MT, bool GATED>
@@ -190,41 +228,11 @@ __device__ __forceinline__ void finish_block(const ScanArgs &a, const Slots &s, 
                 if constexpr (!GATED) {
                     if ((uint32_t)m < qcnt && row < nrows_pad) a.out[(size_t)s.out[m] + row0 + row] = live ? v : worst;
                 } else {
-                    // The 16 lanes of a group share slot m.  Survivors are rare: one ballot, and
-                    // only then one aggregated atomic per group to reserve room in the query's region.
+                    // survivors are rare: one ballot decides whether the wave goes on to emit
                     const uint32_t bits = order_bits(v, a.metric);
-                    bool pass = live && (uint32_t)m < qcnt && bits <= s.thr[m];
+                    const bool pass = live && (uint32_t)m < qcnt && bits <= s.thr[m];
                     if (__ballot(pass) == 0ull) continue; // the usual case: nothing survives
-                    uint32_t b = 0;
-                    if (pass) {
-                        b = bucket_of(v, s.lo[m], s.inv[m], a.metric);
-                        pass = b <= s.bmax[m];
-                    }
-                    const unsigned long long mask = __ballot(pass);
-                    const uint32_t gmask = (uint32_t)(mask >> (lg * 16)) & 0xffffu;
-                    if (gmask) {
-                        const int leader = __ffs(gmask) - 1;
-                        uint32_t base = 0;
-                        if (ln == leader) base = atomicAdd(&a.ccnt[s.q[m]], (uint32_t)__popc(gmask));
-                        base = __shfl(base, lg * 16 + leader);
-                        if (pass) {
-                            const uint32_t rank = __popc(gmask & ((1u << ln) - 1u));
-                            a.cbuf[(size_t)s.base[m] + base + rank] =
-                                ((unsigned long long)bits << 32) | (s.out[m] + row0 + (uint32_t)row);
-                        }
-                        if (a.use_hist) {
-                            // count the emitted candidates per bucket; one atomic for the group
-                            // when its candidates share a bucket (the usual case)
-                            const uint32_t b0 = __shfl(b, lg * 16 + leader);
-                            const uint32_t odd = (uint32_t)(__ballot(pass && b != b0) >> (lg * 16)) & 0xffffu;
-                            uint32_t *hq = a.hist + (size_t)s.q[m] * kHistBins;
-                            if (odd == 0u) {
-                                if (ln == leader) atomicAdd(hq + b0, (uint32_t)__popc(gmask));
-                            } else if (pass) {
-                                atomicAdd(hq + b, 1u);
-                            }
-                        }
-                    }
+                    emit_survivors(a, s, v, bits, pass, m, row0 + (uint32_t)row, ln, lg);
                 }
             }
         }
@@ -566,6 +574,205 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 8))) voi
     }
 }
 
+// ------------------------------------------------------------------ rows-stationary kernel
+
+// Lists probed by hundreds of the batch's queries.  Scored group by group with the kernels
+// above, such a list is read once per group; here the roles are swapped.  A tile is kRsRows
+// rows of one page against ALL slots of the list (up to kRsSlots): the rows are staged once,
+// coalesced, into LDS and stay there; the 8 waves then each take every 8th group of 32
+// slots and stream those queries' operands straight from global memory (the query rows of
+// a hot list are a few hundred KB that every workgroup reads: L2 traffic, not HBM), one
+// 256-byte slice ahead of the MFMAs.  The rows of the next tile are fetched into registers
+// meanwhile.  Per (row, query) the same MFMAs run in the same order as in scan_kernel, so
+// the values are bit-identical and the thresholds of the sample apply.  This launch runs
+// after the regular lists' scan: it reads the bucket limits that scan has published and does
+// not maintain the histogram any further.
+constexpr int kRsStage = kRsRows * 1536 / 16 / 512; // 16-byte pieces of a tile each thread moves, at the widest row
+
+template <int STORAGE>
+__global__ __launch_bounds__(512) void scan_rs_kernel(ScanArgs a)
+{
+    extern __shared__ __align__(16) char smem[];
+    constexpr int MT = 2;
+    const int row_bytes = a.row_bytes;
+    const int xstride = row_bytes + kQPadBytes;
+    char *xrows = smem; // [kRsRows][xstride]
+    Slots s;
+    s.carve(smem + (size_t)kRsRows * xstride, kRsSlots);
+    uint32_t *s_misc = s.bmax + kRsSlots; // keep scan_rs_lds_bytes in step
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int ln = lane & 15, lg = lane >> 4;
+    const int nit = row_bytes / kIterBytes;
+    const int pieces_per_row = row_bytes / 16;
+    const int per_thread = kRsRows * pieces_per_row / 512; // row_bytes / 128, at most kRsStage
+    const gbytes qs = in_global(a.qs);
+    uint32_t cur_qbeg = 0xffffffffu, cur_qcnt = 0;
+
+    Sched sc;
+    sc.start(*a.ntiles, *a.batch);
+    if (sc.t >= sc.ntiles) return;
+    Tile cur = a.tiles[sc.t];
+    // the rows of a tile are contiguous in the page: piece i of the tile is 16 bytes at x + 16 i
+    u32x4 pre[kRsStage];
+#define PK_PREFETCH(tile)                                                                         \
+    {                                                                                             \
+        const gbytes px = in_global((tile).x);                                                    \
+        _Pragma("unroll") for (int j = 0; j < kRsStage; ++j)                                      \
+        {                                                                                         \
+            if (j < per_thread) pre[j] = *reinterpret_cast<gvec4>(px + (size_t)(j * 512 + tid) * 16); \
+        }                                                                                         \
+    }
+    PK_PREFETCH(cur)
+    while (sc.t < sc.ntiles) {
+        const gfloats txn = in_global(cur.xn);
+        const uint32_t row0 = cur.row0;
+        const uint32_t qbeg = __builtin_amdgcn_readfirstlane(cur.qbeg);
+        const uint32_t qcnt = __builtin_amdgcn_readfirstlane((uint32_t)cur.qcnt);
+        const int nrows = __builtin_amdgcn_readfirstlane((int)cur.nrows);
+        if (sc.fresh) sc.request(a, s_misc);
+        uint32_t next_end;
+        bool next_fresh;
+        const uint32_t tn = sc.peek(s_misc, next_end, next_fresh);
+        const Tile nxt = a.tiles[tn < sc.ntiles ? tn : sc.ntiles - 1];
+
+        __syncthreads(); // every wave is done with the previous tile's rows and slot arrays
+#pragma unroll
+        for (int j = 0; j < kRsStage; ++j) {
+            if (j < per_thread) {
+                const int idx = j * 512 + tid, row = idx / pieces_per_row, col = idx - row * pieces_per_row;
+                *reinterpret_cast<u32x4 *>(xrows + (size_t)row * xstride + col * 16) = pre[j];
+            }
+        }
+        if (qbeg != cur_qbeg || qcnt != cur_qcnt) {
+            for (uint32_t m = tid; m < qcnt; m += 512) {
+                const uint32_t q = a.slot_query[qbeg + m];
+                const uint32_t base = a.qoff[q];
+                s.out[m] = a.slot_out[qbeg + m] - base; // position inside the query's candidate range
+                s.qn[m] = a.qnorm[q];
+                s.q[m] = q;
+                s.base[m] = base;
+                s.thr[m] = a.tau[q];
+                s.lo[m] = a.tlo[q];
+                s.inv[m] = a.tinv[q];
+                s.bmax[m] = __hip_atomic_load(a.tcur + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            cur_qbeg = qbeg;
+            cur_qcnt = qcnt;
+        }
+        __syncthreads();
+        if (tn < sc.ntiles) PK_PREFETCH(nxt) // on its way while this tile is scored
+
+        const int groups = (int)((qcnt + 31u) >> 5);
+        for (int g = wave; g < groups; g += 8) {
+            const uint32_t s0 = (uint32_t)g * 32u;
+            const uint32_t gq = qcnt - s0 < 32u ? qcnt - s0 : 32u; // slots of this group
+            const int mt_used = (int)((gq + 15u) >> 4);
+            gbytes qp[MT];
+            bool qlive[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const uint32_t m = (uint32_t)(mt * 16 + ln);
+                qlive[mt] = m < gq; // slots past the group's last contribute zeros
+                qp[mt] = qs + (size_t)(qlive[mt] ? s.q[s0 + m] : 0u) * row_bytes + lg * 16;
+            }
+            f32x4 acc[2][MT][2]; // [half of the tile's rows][slot tile][row tile of the half]
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    acc[h][mt][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    acc[h][mt][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+            u32x4 qa[MT][4], qb[MT][4];
+#define PK_QLOAD(buf, it)                                                                         \
+    _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                             \
+    {                                                                                             \
+        _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4)                                          \
+        {                                                                                         \
+            buf[mt][s4] = u32x4{0u, 0u, 0u, 0u};                                                  \
+            if (qlive[mt]) buf[mt][s4] = *reinterpret_cast<gvec4>(qp[mt] + (size_t)(it) * kIterBytes + s4 * 64); \
+        }                                                                                         \
+    }
+#define PK_COMPUTE(buf, it)                                                                       \
+    {                                                                                             \
+        const char *xb = xrows + (size_t)ln * xstride + (size_t)(it) * kIterBytes + lg * 16;      \
+        _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4)                                          \
+        {                                                                                         \
+            u32x4 xv[4];                                                                          \
+            _Pragma("unroll") for (int nt = 0; nt < 4; ++nt)                                      \
+                xv[nt] = *reinterpret_cast<const u32x4 *>(xb + (size_t)nt * 16 * xstride + s4 * 64); \
+            _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                     \
+            {                                                                                     \
+                if (mt < mt_used) {                                                               \
+                    _Pragma("unroll") for (int nt = 0; nt < 4; ++nt)                              \
+                        mfma_step<STORAGE>(acc[nt >> 1][mt][nt & 1], buf[mt][s4], xv[nt]);        \
+                }                                                                                 \
+            }                                                                                     \
+        }                                                                                         \
+    }
+            PK_QLOAD(qa, 0)
+            for (int it = 0; it < nit; it += 2) {
+                if (it + 1 < nit) { PK_QLOAD(qb, it + 1) }
+                PK_COMPUTE(qa, it)
+                if (it + 2 < nit) { PK_QLOAD(qa, it + 2) }
+                if (it + 1 < nit) { PK_COMPUTE(qb, it + 1) }
+            }
+#undef PK_QLOAD
+#undef PK_COMPUTE
+            Slots sg = s; // the group's slots are 0 .. gq-1 to the epilogue
+            sg.out += s0;
+            sg.qn += s0;
+            sg.thr += s0;
+            sg.q += s0;
+            sg.base += s0;
+            sg.lo += s0;
+            sg.inv += s0;
+            sg.bmax += s0;
+            // Epilogue.  This kernel is not waiting for memory most of the time, so the gate test is
+            // kept off LDS: the lane's 8 slots' thresholds (and norms) sit in registers, and only a
+            // value that some lane of the wave passes goes on to the emission path.
+            uint32_t thr_r[MT][4];
+            float qn_r[MT][4];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int m = mt * 16 + lg * 4 + i;
+                    thr_r[mt][i] = sg.thr[m];
+                    qn_r[mt][i] = sg.qn[m];
+                }
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) {
+                if (nt * 16 >= nrows) break; // wave-uniform
+                const int row = nt * 16 + ln;
+                const bool live = row < nrows;
+                float xn = 0.f;
+                if (a.metric == PK_METRIC_L2 && live) xn = txn[row];
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    if (mt >= mt_used) break; // wave-uniform
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        float v = acc[nt >> 1][mt][nt & 1][i];
+                        if (a.metric == PK_METRIC_L2) v = fmaxf(xn - 2.f * v + qn_r[mt][i], 0.f);
+                        const uint32_t bits = order_bits(v, a.metric);
+                        const bool pass = live && (uint32_t)(mt * 16 + lg * 4 + i) < gq && bits <= thr_r[mt][i];
+                        if (__ballot(pass) == 0ull) continue;
+                        emit_survivors(a, sg, v, bits, pass, mt * 16 + lg * 4 + i, row0 + (uint32_t)row, ln, lg);
+                    }
+                }
+            }
+        }
+        sc.t = tn;
+        sc.end = next_end;
+        if (next_fresh) sc.parity ^= 1;
+        sc.fresh = next_fresh;
+        cur = nxt;
+    }
+#undef PK_PREFETCH
+}
+
 // ------------------------------------------------------------------ centroid scoring, small batches
 
 // Coarse step (Section 2.2) for query segments too small to fill the GEMM's 128 x 128
@@ -761,6 +968,23 @@ hipError_t launch_scan(const ScanArgs &a, int grid, hipStream_t s)
     const bool gated = a.tau != nullptr;
     if (a.storage == PK_F16) return gated ? launch_mt<PK_F16, 4, true>(a, grid, s) : launch_mt<PK_F16, 4, false>(a, grid, s);
     return gated ? launch_mt<PK_F32, 4, true>(a, grid, s) : launch_mt<PK_F32, 4, false>(a, grid, s);
+}
+
+int scan_rs_lds_bytes(int row_bytes)
+{
+    return kRsRows * (row_bytes + kQPadBytes) + kRsSlots * kScanSlotWords * 4 + 16; // rows + per-slot arrays + scratch
+}
+
+// the rows-stationary kernel (gated fine search; tiles of kRsRows rows x up to kRsSlots slots; rows of at most 1536 bytes)
+hipError_t launch_scan_rs(const ScanArgs &a, int grid, hipStream_t s)
+{
+    if (a.row_bytes <= 0 || a.row_bytes % kIterBytes != 0 || a.row_bytes > 1536 || a.tau == nullptr || a.mq != kRsSlots ||
+        a.use_hist != 0)
+        return hipErrorInvalidValue;
+    static int cleared_h = 0, cleared_f = 0;
+    if (a.storage == PK_F16)
+        return launch_with_lds(&scan_rs_kernel<PK_F16>, cleared_h, scan_rs_lds_bytes(a.row_bytes), a, grid, 512, s);
+    return launch_with_lds(&scan_rs_kernel<PK_F32>, cleared_f, scan_rs_lds_bytes(a.row_bytes), a, grid, 512, s);
 }
 
 // the sliced-query kernel (gated fine search only; fp32 rows are held to 32 slots)

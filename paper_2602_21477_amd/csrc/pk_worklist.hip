@@ -208,7 +208,9 @@ __global__ __launch_bounds__(1024) void wl_scan_kernel(WorklistArgs a, MultiArgs
                 const uint32_t len = ix.list_len[l];
                 const uint32_t pages = (len + (uint32_t)ix.P - 1) / (uint32_t)ix.P;
                 const uint32_t mq = hot ? (uint32_t)a.mq_hot : (uint32_t)a.mq;
-                nt = pages * ((c + mq - 1) / mq);
+                // hot tiles of the rows-stationary kernel cover hot_rows rows, not a page
+                const uint32_t units = hot && a.hot_rows ? (len + (uint32_t)a.hot_rows - 1) / (uint32_t)a.hot_rows : pages;
+                nt = units * ((c + mq - 1) / mq);
                 rows += len;
             }
             a.lfill[gl] = nt;
@@ -226,7 +228,9 @@ __global__ __launch_bounds__(1024) void wl_scan_kernel(WorklistArgs a, MultiArgs
             uint32_t *sc = hot ? a.scalars_hot : a.scalars;
             sc[0] = nt;
             sc[1] = 0;
-            uint32_t g = nt / (uint32_t)(a.scan_grid * a.grab_div);
+            // tiles per claimed batch; the rows-stationary kernel keeps a list's slot arrays across the
+            // consecutive tiles of a batch, so its batches are cut coarser
+            uint32_t g = hot && a.hot_rows ? nt / (uint32_t)(a.scan_grid_hot * 4) : nt / (uint32_t)(a.scan_grid * a.grab_div);
             sc[2] = g < 1 ? 1 : (g > 8 ? 8 : g);
             if (!hot) {
                 sc[3] = total;
@@ -270,18 +274,23 @@ __device__ __forceinline__ void wl_tiles_block(const WorklistArgs &a, const Mult
     const uint32_t mq = hot ? (uint32_t)a.mq_hot : (uint32_t)a.mq;
     const uint32_t groups = (c + mq - 1) / mq;
     Tile *out = (hot ? a.tiles_hot : a.tiles) + (hot ? a.lhtile[gl] : a.ltile[gl]);
-    for (uint32_t j = threadIdx.x; j < pages * groups; j += blockDim.x) {
-        const uint32_t g = j / pages, p = j - g * pages;
+    // rows per tile: a page, or (hot tiles of the rows-stationary kernel) a fixed part of one
+    const uint32_t R = hot && a.hot_rows ? (uint32_t)a.hot_rows : P;
+    const uint32_t units = hot && a.hot_rows ? (len + R - 1) / R : pages;
+    for (uint32_t j = threadIdx.x; j < units * groups; j += blockDim.x) {
+        const uint32_t g = j / units, u = j - g * units;
+        const uint32_t first = u * R;          // position of the tile's first row in the list
+        const uint32_t p = first / P, in_page = first - p * P;
         const uint32_t pg = phys_page(ix, l, p);
         const Arena &ar = arena_of(ix, pg);
-        const size_t local = pg - ar.first_page;
+        const size_t local = (size_t)(pg - ar.first_page) * P + in_page;
         Tile tl;
-        tl.x = ar.vec + local * P * (size_t)ix.row_bytes;
-        tl.xn = ar.norm + local * P;
-        tl.row0 = p * P;
+        tl.x = ar.vec + local * (size_t)ix.row_bytes;
+        tl.xn = ar.norm + local;
+        tl.row0 = first;
         tl.qbeg = a.lstart[gl] + g * mq;
-        const uint32_t left = len - p * P;
-        tl.nrows = (uint16_t)(left < P ? left : P);
+        const uint32_t left = len - first;
+        tl.nrows = (uint16_t)(left < R ? left : R);
         const uint32_t ql = c - g * mq;
         tl.qcnt = (uint16_t)(ql < mq ? ql : mq);
         tl.pad = 0;

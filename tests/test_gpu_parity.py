@@ -582,6 +582,36 @@ def test_wide_rows_many_queries_per_list(gpu_device):
             p.close()
 
 
+def test_hot_lists_rows_stationary_kernel(gpu_device):
+    """Batches of >= 512 queries over few lists: every list is probed by hundreds of queries and goes
+    to the rows-stationary kernel (64-row tiles against all slots of the list), next to regular lists;
+    ragged list tails, delta pages, more than 1024 queries on one list (two slot groups)."""
+    cfg = W.scaled(W.C1, n=9000, ncomp=12, nlist=12)
+    for storage, metric in ((F32, IP), (F16, L2), (F32, L2)):
+        p, _ = make_pair(cfg, metric=metric, storage=storage, insert_reserve=2048)
+        try:
+            q = W.queries(cfg, 30, 640)
+            say(f"hot lists storage={storage} metric={metric}: 640 queries, nprobe 6")
+            p.check_search(q, 10, 6)
+            p.insert_both(W.inserts(cfg, 0, 700), where="hot lists")
+            say("hot lists: after 700 inserts, k 100")
+            p.check_search(q, 100, 5)
+            q2 = W.queries(cfg, 31, 1300)
+            say("hot lists: 1300 queries on every list")
+            p.check_search(q2, 10, 12)
+        finally:
+            p.close()
+    # wide-ish fp16 rows (d = 768: the widest rows the kernel takes), lists of uneven length
+    cfg = W.scaled(W.C4, n=6000, ncomp=40, nlist=40)
+    p, _ = make_pair(cfg, metric=L2, storage=F16)
+    try:
+        q = W.queries(cfg, 32, 768)
+        say("hot lists: d=768 fp16, 768 queries, nprobe 16")
+        p.check_search(q, 20, 16)
+    finally:
+        p.close()
+
+
 def test_search_replays_from_a_hip_graph(gpu_device):
     """A search enqueues kernels only (no allocation, no host synchronisation once the handle's workspace
     has been sized by an earlier call of the same shape), so it can be captured into a HIP graph.  Every
