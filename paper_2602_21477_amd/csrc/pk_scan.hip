@@ -664,27 +664,11 @@ __global__ __launch_bounds__(512) void scan_rs_kernel(ScanArgs a)
         if (tn < sc.ntiles) PK_PREFETCH(nxt) // on its way while this tile is scored
 
         const int groups = (int)((qcnt + 31u) >> 5);
-        for (int g = wave; g < groups; g += 8) {
-            const uint32_t s0 = (uint32_t)g * 32u;
-            const uint32_t gq = qcnt - s0 < 32u ? qcnt - s0 : 32u; // slots of this group
-            const int mt_used = (int)((gq + 15u) >> 4);
-            gbytes qp[MT];
-            bool qlive[MT];
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                const uint32_t m = (uint32_t)(mt * 16 + ln);
-                qlive[mt] = m < gq; // slots past the group's last contribute zeros
-                qp[mt] = qs + (size_t)(qlive[mt] ? s.q[s0 + m] : 0u) * row_bytes + lg * 16;
-            }
-            f32x4 acc[2][MT][2]; // [half of the tile's rows][slot tile][row tile of the half]
-#pragma unroll
-            for (int h = 0; h < 2; ++h)
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    acc[h][mt][0] = f32x4{0.f, 0.f, 0.f, 0.f};
-                    acc[h][mt][1] = f32x4{0.f, 0.f, 0.f, 0.f};
-                }
-            u32x4 qa[MT][4], qb[MT][4];
+        // The first slice of a group's query operands is requested before the epilogue of the
+        // group before it (both register buffers are free by then), so its latency hides there.
+        gbytes qp[MT];
+        bool qlive[MT];
+        u32x4 qa[MT][4], qb[MT][4];
 #define PK_QLOAD(buf, it)                                                                         \
     _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                             \
     {                                                                                             \
@@ -694,6 +678,30 @@ __global__ __launch_bounds__(512) void scan_rs_kernel(ScanArgs a)
             if (qlive[mt]) buf[mt][s4] = *reinterpret_cast<gvec4>(qp[mt] + (size_t)(it) * kIterBytes + s4 * 64); \
         }                                                                                         \
     }
+#define PK_QGROUP(g)                                                                              \
+    {                                                                                             \
+        const uint32_t left = qcnt - (uint32_t)(g) * 32u;                                         \
+        _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                         \
+        {                                                                                         \
+            const uint32_t m = (uint32_t)(mt * 16 + ln);                                          \
+            qlive[mt] = m < left; /* slots past the group's last contribute zeros */              \
+            qp[mt] = qs + (size_t)(qlive[mt] ? s.q[(uint32_t)(g) * 32u + m] : 0u) * row_bytes + lg * 16; \
+        }                                                                                         \
+        PK_QLOAD(qa, 0)                                                                           \
+    }
+        if (wave < groups) PK_QGROUP(wave)
+        for (int g = wave; g < groups; g += 8) {
+            const uint32_t s0 = (uint32_t)g * 32u;
+            const uint32_t gq = qcnt - s0 < 32u ? qcnt - s0 : 32u; // slots of this group
+            const int mt_used = (int)((gq + 15u) >> 4);
+            f32x4 acc[2][MT][2]; // [half of the tile's rows][slot tile][row tile of the half]
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    acc[h][mt][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    acc[h][mt][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+                }
 #define PK_COMPUTE(buf, it)                                                                       \
     {                                                                                             \
         const char *xb = xrows + (size_t)ln * xstride + (size_t)(it) * kIterBytes + lg * 16;      \
@@ -711,15 +719,14 @@ __global__ __launch_bounds__(512) void scan_rs_kernel(ScanArgs a)
             }                                                                                     \
         }                                                                                         \
     }
-            PK_QLOAD(qa, 0)
             for (int it = 0; it < nit; it += 2) {
                 if (it + 1 < nit) { PK_QLOAD(qb, it + 1) }
                 PK_COMPUTE(qa, it)
                 if (it + 2 < nit) { PK_QLOAD(qa, it + 2) }
                 if (it + 1 < nit) { PK_COMPUTE(qb, it + 1) }
             }
-#undef PK_QLOAD
 #undef PK_COMPUTE
+            if (g + 8 < groups) PK_QGROUP(g + 8)
             Slots sg = s; // the group's slots are 0 .. gq-1 to the epilogue
             sg.out += s0;
             sg.qn += s0;
@@ -764,6 +771,8 @@ __global__ __launch_bounds__(512) void scan_rs_kernel(ScanArgs a)
                 }
             }
         }
+#undef PK_QLOAD
+#undef PK_QGROUP
         sc.t = tn;
         sc.end = next_end;
         if (next_fresh) sc.parity ^= 1;
