@@ -97,15 +97,20 @@ __device__ __forceinline__ uint32_t bucket_of(float v, float lo, float inv, int 
     return (uint32_t)t;
 }
 
-// exclusive scan of in[0,n) into out[0,n) by one workgroup of 1024 threads; returns the total
+// exclusive scan of in[0,n) into out[0,n) by one workgroup (up to 1024 threads); returns the
+// total.  A thread takes 4 consecutive elements, so 4096 elements need one round of barriers;
+// out may be the same array as in.
 __device__ __forceinline__ uint32_t block_exscan(const uint32_t *in, uint32_t *out, uint32_t n, uint32_t *s_wave /*[17]*/)
 {
     uint32_t carry = 0;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
-    for (uint32_t base = 0; base < n; base += blockDim.x) {
-        const uint32_t i = base + threadIdx.x;
-        const uint32_t v = i < n ? in[i] : 0u;
-        uint32_t x = v;
+    for (uint32_t base = 0; base < n; base += 4u * blockDim.x) {
+        const uint32_t i = base + 4u * threadIdx.x;
+        uint32_t v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = i + j < n ? in[i + j] : 0u;
+        const uint32_t t = v[0] + v[1] + v[2] + v[3];
+        uint32_t x = t;
         for (int off = 1; off < 64; off <<= 1) {
             const uint32_t y = __shfl_up(x, off);
             if (lane >= off) x += y;
@@ -115,14 +120,19 @@ __device__ __forceinline__ uint32_t block_exscan(const uint32_t *in, uint32_t *o
         if (threadIdx.x == 0) {
             uint32_t acc = 0;
             for (int w = 0; w < nwaves; ++w) {
-                const uint32_t t = s_wave[w];
+                const uint32_t tw = s_wave[w];
                 s_wave[w] = acc;
-                acc += t;
+                acc += tw;
             }
             s_wave[16] = acc;
         }
         __syncthreads();
-        if (i < n) out[i] = carry + s_wave[wave] + x - v;
+        uint32_t run = carry + s_wave[wave] + x - t;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (i + j < n) out[i + j] = run;
+            run += v[j];
+        }
         carry += s_wave[16];
         __syncthreads();
     }

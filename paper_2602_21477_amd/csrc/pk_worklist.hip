@@ -181,43 +181,34 @@ __global__ __launch_bounds__(1024) void wl_scan_kernel(WorklistArgs a, MultiArgs
     const uint32_t total = block_exscan(a.qtot, a.qoff, (uint32_t)a.nq, s_wave);
     const uint32_t nl = (uint32_t)a.n_handles * (uint32_t)a.nlist_max;
     block_exscan(a.lcnt, a.lstart, nl, s_wave);
-    // tiles per list: regular lists -> ltile, hot lists -> lhtile (counts first, then their scans)
+    // tiles per list: regular lists -> ltile, hot lists -> lhtile (counts first, then their scans in place)
     unsigned long long rows = 0;
+    for (uint32_t gl = threadIdx.x; gl < nl; gl += blockDim.x) {
+        const uint32_t h = gl / (uint32_t)a.nlist_max, l = gl - h * (uint32_t)a.nlist_max;
+        uint32_t nt_reg = 0, nt_hot = 0;
+        const uint32_t c = a.lcnt[gl];
+        if (c > 0) {
+            const DevIndex &ix = *m.ix[h];
+            const uint32_t len = ix.list_len[l];
+            const uint32_t pages = (len + (uint32_t)ix.P - 1) / (uint32_t)ix.P;
+            if (c > a.hot_from) {
+                // hot tiles of the rows-stationary kernel cover hot_rows rows, not a page
+                const uint32_t units = a.hot_rows ? (len + (uint32_t)a.hot_rows - 1) / (uint32_t)a.hot_rows : pages;
+                nt_hot = units * ((c + (uint32_t)a.mq_hot - 1) / (uint32_t)a.mq_hot);
+            } else {
+                nt_reg = pages * ((c + (uint32_t)a.mq - 1) / (uint32_t)a.mq);
+            }
+            rows += len;
+        }
+        a.ltile[gl] = nt_reg;
+        a.lhtile[gl] = nt_hot;
+    }
+    __syncthreads();
     for (int hot = 0; hot < 2; ++hot) {
         // a class no list can fall into (no hot class at all, or every list hot) needs no scan
         const bool none = hot ? a.hot_from == 0xffffffffu : a.hot_from == 0u;
-        if (none) {
-            if (threadIdx.x == 0) {
-                uint32_t *sc = hot ? a.scalars_hot : a.scalars;
-                sc[0] = 0;
-                sc[1] = 0;
-                sc[2] = 1;
-                if (!hot) {
-                    sc[3] = total;
-                    atomicAdd(&m.ix[0]->stats[1], (unsigned long long)total);
-                }
-            }
-            continue;
-        }
-        for (uint32_t gl = threadIdx.x; gl < nl; gl += blockDim.x) {
-            const uint32_t h = gl / (uint32_t)a.nlist_max, l = gl - h * (uint32_t)a.nlist_max;
-            uint32_t nt = 0;
-            const uint32_t c = a.lcnt[gl];
-            if (c > 0 && (c > a.hot_from) == (hot == 1)) {
-                const DevIndex &ix = *m.ix[h];
-                const uint32_t len = ix.list_len[l];
-                const uint32_t pages = (len + (uint32_t)ix.P - 1) / (uint32_t)ix.P;
-                const uint32_t mq = hot ? (uint32_t)a.mq_hot : (uint32_t)a.mq;
-                // hot tiles of the rows-stationary kernel cover hot_rows rows, not a page
-                const uint32_t units = hot && a.hot_rows ? (len + (uint32_t)a.hot_rows - 1) / (uint32_t)a.hot_rows : pages;
-                nt = units * ((c + mq - 1) / mq);
-                rows += len;
-            }
-            a.lfill[gl] = nt;
-        }
-        __syncthreads();
-        const uint32_t ntiles = block_exscan(a.lfill, hot ? a.lhtile : a.ltile, nl, s_wave);
-        __syncthreads();
+        uint32_t *lt = hot ? a.lhtile : a.ltile;
+        const uint32_t ntiles = none ? 0u : block_exscan(lt, lt, nl, s_wave);
         if (threadIdx.x == 0) {
             uint32_t nt = ntiles;
             if (ntiles > a.tile_cap || total > a.cand_cap) {
@@ -236,8 +227,9 @@ __global__ __launch_bounds__(1024) void wl_scan_kernel(WorklistArgs a, MultiArgs
                 sc[3] = total;
                 atomicAdd(&m.ix[0]->stats[1], (unsigned long long)total);
             }
-            atomicAdd(&m.ix[0]->stats[2], (unsigned long long)nt);
+            if (nt) atomicAdd(&m.ix[0]->stats[2], (unsigned long long)nt);
         }
+        __syncthreads();
     }
     if (rows) atomicAdd(&m.ix[0]->stats[0], rows);
     __syncthreads();
