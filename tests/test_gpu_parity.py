@@ -612,6 +612,31 @@ def test_hot_lists_rows_stationary_kernel(gpu_device):
         p.close()
 
 
+def test_hot_lists_across_agents_in_one_call(gpu_device):
+    """Two agents, hundreds of queries each over few lists, one segmented call: the rows-stationary tiles
+    of both indexes share a launch.  Same results as the per-handle calls (which, 400 queries each, stay
+    below the batch size that enables that kernel: the two paths must agree bit for bit) and parity with
+    the oracle."""
+    cfg = W.scaled(W.C3, d=128, ncomp=10, nlist=10, n_agents=2)
+    pairs, qs, offs = [], [], [0]
+    try:
+        for a, n in enumerate((5000, 3500)):
+            p, _ = make_pair(cfg, n=n, agent=a, insert_reserve=256)
+            pairs.append(p)
+            qs.append(W.queries(cfg, 3, 400, agent=a))
+            offs.append(offs[-1] + 400)
+        q = np.concatenate(qs)
+        say("hot lists, two agents, one launch")
+        mi, mv = B.search_multi([p.gpu for p in pairs], offs, dev(q), 10, 8)
+        for a, p in enumerate(pairs):
+            si, sv = p.gpu.search(dev(qs[a]), 10, 8)
+            assert torch.equal(mi[offs[a]:offs[a + 1]], si) and torch.equal(mv[offs[a]:offs[a + 1]], sv)
+            p.check_search(qs[a], 10, 8, where=f"agent {a}")
+    finally:
+        for p in pairs:
+            p.close()
+
+
 def test_search_replays_from_a_hip_graph(gpu_device):
     """A search enqueues kernels only (no allocation, no host synchronisation once the handle's workspace
     has been sized by an earlier call of the same shape), so it can be captured into a HIP graph.  Every
