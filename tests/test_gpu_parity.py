@@ -637,6 +637,27 @@ def test_hot_lists_across_agents_in_one_call(gpu_device):
             p.close()
 
 
+def test_very_large_query_batch(gpu_device):
+    """More queries than one launch sequence takes (32768): the call is cut into batches; every list
+    is probed by thousands of queries (many slot groups per rows-stationary tile)."""
+    cfg = W.scaled(W.C1, n=2000, d=64, ncomp=8, nlist=8)
+    p, _ = make_pair(cfg, metric=L2)
+    try:
+        q = np.concatenate([W.queries(cfg, 40 + b, 3000) for b in range(11)])  # 33 000 queries
+        say("33 000 queries in one call")
+        gi, gv = p.gpu.search(dev(q), 5, 2)
+        gp = p.gpu.coarse(dev(q), 2).cpu().numpy()
+        oi, ov = p.orc.scan_probes(q, 5 + KX, gp)
+        check_results(gi.cpu().numpy(), gv.cpu().numpy(), oi, ov, 5, p.tol, p.scale(q), L2, where="large batch")
+        assert p.gpu.stats().device_error == 0
+        # the first and the last queries alone give the same rows
+        for lo, hi in ((0, 100), (32900, 33000)):
+            si, sv = p.gpu.search(dev(q[lo:hi]), 5, 2)
+            assert torch.equal(si, gi[lo:hi]) and torch.equal(sv, gv[lo:hi])
+    finally:
+        p.close()
+
+
 def test_search_replays_from_a_hip_graph(gpu_device):
     """A search enqueues kernels only (no allocation, no host synchronisation once the handle's workspace
     has been sized by an earlier call of the same shape), so it can be captured into a HIP graph.  Every
