@@ -211,6 +211,42 @@ def search_union(indexes, q, k: int, nprobe: int, probes=None):
     return src, ids, val
 
 
+def search_levels(levels, q, k: int, nprobes, stop, kx: int = 0, probes=None):
+    """Search down a stack of indexes, top level first, with the early-termination rule of Section 4.2:
+    a query stops at a level as soon as that level gives it k candidates all of which are closer than
+    stop[q] (= alpha_et * d_agent of its agent; inner product: all scores above stop[q]); otherwise it
+    is searched again in the next level, whose result replaces the upper one (every level holds a subset
+    of the one below).  The last level always ends the search.  The decision looks at the first k
+    results; kx more are returned for the comparator.  probes, if given, is one [nq, nprobes[l]] array
+    per level (the lists to scan instead of the coarse step's).  Returns (level, ids, values)."""
+    d = levels[0].d
+    q = _f32(q).reshape(-1, d)
+    nq = q.shape[0]
+    stop = np.asarray(stop, dtype=np.float64).reshape(nq)
+    ip = levels[0].metric == 0
+    ids = np.full((nq, k + kx), -1, dtype=np.int64)
+    val = np.full((nq, k + kx), -np.inf if ip else np.inf, dtype=np.float64)
+    level = np.full(nq, len(levels) - 1, dtype=np.int32)
+    active = np.arange(nq)
+    for l, ix in enumerate(levels):
+        if active.size == 0:
+            break
+        if probes is None:
+            li, lv = ix.search(q[active], k + kx, int(nprobes[l]))
+        else:
+            li, lv = ix.scan_probes(q[active], k + kx, np.ascontiguousarray(probes[l][active], dtype=np.int32))
+        ids[active] = li
+        val[active] = lv
+        full = li[:, k - 1] >= 0
+        kth = lv[:, k - 1]  # rows are sorted best first: the k-th is the farthest of the top k
+        done = full & ((kth > stop[active]) if ip else (kth < stop[active]))
+        if l == len(levels) - 1:
+            done[:] = True
+        level[active[done]] = l
+        active = active[~done]
+    return level, ids, val
+
+
 def bruteforce(x, q, k: int, metric: int, ids=None):
     x = _f32(x)
     n, d = x.shape

@@ -451,3 +451,58 @@ def test_recall_on_tiny_config_is_high():
     bi, _ = oracle.bruteforce(x, q, 10, oracle.IP)
     rec = np.mean([len(set(a.tolist()) & set(b.tolist())) for a, b in zip(ids, bi)]) / 10
     assert rec >= 0.9
+
+
+def test_level_cascade_worked_example_on_a_line():
+    """Early termination (Section 4.2) on numbers one can check by hand.  Points on a line, L2 metric,
+    one list per index.  Top level: {0, 1, 2}; bottom level: {0, 1, 2, 10, 11, 12, 2.4}.  k = 2."""
+    def index(points, ids):
+        ix = oracle.Index(np.zeros((1, 1), np.float32), oracle.L2)
+        ix.build(np.asarray(points, np.float32).reshape(-1, 1), np.asarray(ids, np.int64))
+        return ix
+    top = index([0, 1, 2], [0, 1, 2])
+    bottom = index([0, 1, 2, 10, 11, 12, 2.4], [0, 1, 2, 10, 11, 12, 24])
+    q = np.asarray([[0.5], [2.2], [10.5], [0.5]], np.float32)
+    # squared distances to the top level's best two: 0.25, 0.25 | 0.04, 1.44 | 72.25, 90.25 | 0.25, 0.25
+    stop = np.asarray([1.0, 1.0, 1.0, 0.25])
+    level, ids, val = oracle.search_levels([top, bottom], q, 2, [1, 1], stop)
+    # query 0: both under 1.0 -> stops at the top.  Query 1: the second (1.44) is not under 1.0 -> bottom
+    # level, where 2.4 (id 24) beats 1.  Query 2: far from the top level -> bottom.  Query 3: 0.25 is
+    # not smaller than 0.25 -> bottom (same two points there).
+    assert level.tolist() == [0, 1, 1, 1]
+    assert ids.tolist() == [[0, 1], [2, 24], [10, 11], [0, 1]]
+    np.testing.assert_allclose(val, [[0.25, 0.25], [0.04, 0.04], [0.25, 0.25], [0.25, 0.25]], atol=1e-6)
+    # a top level with fewer than k points never ends a search
+    tiny = index([0.5], [7])
+    level, ids, _ = oracle.search_levels([tiny, bottom], q[:1], 2, [1, 1], [100.0])
+    assert level.tolist() == [1] and ids.tolist() == [[0, 1]]
+
+
+@pytest.mark.parametrize("metric", [oracle.IP, oracle.L2])
+def test_level_cascade_limits_reduce_to_plain_searches(metric):
+    """A threshold nothing passes -> the bottom level's search; a threshold everything passes -> the top
+    level's; in between every query carries the result of the level it stopped at, and a query stops at
+    the top exactly when its k-th value there beats the threshold."""
+    x, q, c, _ = _small(21, n=600, nlist=8)
+    bottom = oracle.Index(c, metric)
+    bottom.build(x)
+    sub = np.arange(0, 600, 3)
+    top = oracle.Index(c[:4].copy(), metric)
+    top.build(x[sub], sub.astype(np.int64))
+    k = 5
+    ti, tv = top.search(q, k, 2)
+    bi, bv = bottom.search(q, k, 3)
+    never = np.full(len(q), np.inf if metric == oracle.IP else -np.inf)
+    always = -never
+    lv, ids, val = oracle.search_levels([top, bottom], q, k, [2, 3], never)
+    assert np.all(lv == 1) and np.array_equal(ids, bi) and np.array_equal(val, bv)
+    lv, ids, val = oracle.search_levels([top, bottom], q, k, [2, 3], always)
+    assert np.all(lv == 0) and np.array_equal(ids, ti) and np.array_equal(val, tv)
+    stop = np.full(len(q), np.median(tv[:, k - 1]))
+    lv, ids, val = oracle.search_levels([top, bottom], q, k, [2, 3], stop)
+    beats = tv[:, k - 1] > stop if metric == oracle.IP else tv[:, k - 1] < stop
+    assert np.array_equal(lv == 0, beats) and 0 < beats.sum() < len(q)
+    for i in range(len(q)):
+        ref = (ti, tv) if lv[i] == 0 else (bi, bv)
+        assert np.array_equal(ids[i], ref[0][i]) and np.array_equal(val[i], ref[1][i])
+
