@@ -264,6 +264,29 @@ int pk_search_multi(pk_index *const *handles, int32_t n_handles, const int64_t *
 int pk_search_union(pk_index *const *handles, int32_t n_handles, const float *queries, int64_t nq, int32_t k,
                     int32_t nprobe, int32_t *out_src, int64_t *out_ids, float *out_dist, void *stream);
 
+/*
+ * Section 4.2 (multi-level index cache, early termination): the indexes of an agent form
+ * levels, every upper level a subset of the one below that follows the agent's recent
+ * accesses; a search starts at the top level and skips the levels below as soon as all
+ * top-k candidates of the current level are closer than alpha_et * d_agent (d_agent: the
+ * agent's mean top-k distance over its recent queries).  This call is that search rule over
+ * levels the caller maintains: every query is searched in levels[0]; a query whose row there
+ * holds k candidates and whose k-th value is smaller than stop[q] (inner product: greater)
+ * keeps that row; the others are searched in levels[1], whose row replaces the upper one,
+ * and so on; the last level ends every search.  Below the first level only the queries
+ * still open are scanned (the coarse step runs for the whole batch).
+ *   levels    HOST [n_levels] distinct live handles of equal d and metric, top level first
+ *   nprobes   HOST [n_levels] lists to probe per level, 1 <= nprobes[l] <= nlist of level l
+ *   stop      DEVICE [nq] float32: alpha_et * d_agent of each query's agent, in the unit
+ *             the index returns (squared distance for L2, score for inner product)
+ *   out_level DEVICE [nq] int32 or NULL: the level whose row the query carries
+ *   out_ids   DEVICE [nq, k] int64;  out_dist DEVICE [nq, k] float32
+ * Asynchronous.  The first handle owns the staging buffer (grown on demand).
+ */
+int pk_search_levels(pk_index *const *levels, int32_t n_levels, const int32_t *nprobes, const float *queries,
+                     int64_t nq, int32_t k, const float *stop, int32_t *out_level, int64_t *out_ids,
+                     float *out_dist, void *stream);
+
 /* Stage seams (tests isolate coarse and fine search with them). */
 
 /* Coarse search only: out_probes DEVICE [nq, nprobe] int32, best list first. */

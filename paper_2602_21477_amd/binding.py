@@ -21,7 +21,7 @@ PK_OK = 0
 PK_ERR_INVALID_ARG, PK_ERR_BAD_HANDLE, PK_ERR_DIM_MISMATCH, PK_ERR_NOMEM, PK_ERR_HIP, PK_ERR_UNSUPPORTED = (
     -1, -2, -3, -4, -5, -6)
 
-EXPORTS = ["pk_search_union", "pk_insert_multi", "pk_delete", "pk_index_split", "pk_index_centroids", "pk_list_ids", "pk_arena_bytes", "pk_index_build", "pk_index_add_arena", "pk_index_compact", "pk_kmeans", "pk_insert", "pk_insert_assigned", "pk_search",
+EXPORTS = ["pk_search_levels", "pk_search_union", "pk_insert_multi", "pk_delete", "pk_index_split", "pk_index_centroids", "pk_list_ids", "pk_arena_bytes", "pk_index_build", "pk_index_add_arena", "pk_index_compact", "pk_kmeans", "pk_insert", "pk_insert_assigned", "pk_search",
            "pk_search_multi", "pk_coarse", "pk_scan_probes", "pk_index_stats", "pk_list_lengths", "pk_profile_begin",
            "pk_profile_end", "pk_index_free", "pk_strerror"]
 
@@ -76,6 +76,7 @@ def lib():
         L.pk_search.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
         L.pk_search_multi.argtypes = [C.POINTER(vp), i32, C.POINTER(i64), vp, i32, i32, vp, vp, vp]
         L.pk_search_union.argtypes = [C.POINTER(vp), i32, vp, i64, i32, i32, vp, vp, vp, vp]
+        L.pk_search_levels.argtypes = [C.POINTER(vp), i32, C.POINTER(i32), vp, i64, i32, vp, vp, vp, vp, vp]
         L.pk_coarse.argtypes = [vp, vp, i64, i32, vp, vp]
         L.pk_scan_probes.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp, vp]
         L.pk_index_stats.argtypes = [vp, C.POINTER(pk_stats), vp]
@@ -344,6 +345,25 @@ def pk_search_union(handles, queries, k: int, nprobe: int, out_src, out_ids, out
     _check(lib().pk_search_union(hs, len(handles), _dev(queries, torch.float32, "queries"), queries.shape[0], k, nprobe,
                                  _dev(out_src, torch.int32, "out_src"), _dev(out_ids, torch.int64, "out_ids"),
                                  _dev(out_dist, torch.float32, "out_dist"), _stream()), "pk_search_union")
+
+
+def pk_search_levels(handles, nprobes, queries, k: int, stop, out_level, out_ids, out_dist):
+    hs = (C.c_void_p * len(handles))(*handles)
+    nps = (C.c_int32 * len(handles))(*[int(x) for x in nprobes])
+    _check(lib().pk_search_levels(hs, len(handles), nps, _dev(queries, torch.float32, "queries"), queries.shape[0], k,
+                                  _dev(stop, torch.float32, "stop"), _dev(out_level, torch.int32, "out_level"),
+                                  _dev(out_ids, torch.int64, "out_ids"), _dev(out_dist, torch.float32, "out_dist"),
+                                  _stream()), "pk_search_levels")
+
+
+def search_levels(indexes, nprobes, queries, k, stop):
+    """Top level first; returns (level each query ended at, ids, values)."""
+    dev = queries.device
+    level = torch.empty(queries.shape[0], dtype=torch.int32, device=dev)
+    ids = torch.empty((queries.shape[0], k), dtype=torch.int64, device=dev)
+    dist = torch.empty((queries.shape[0], k), dtype=torch.float32, device=dev)
+    pk_search_levels([ix.handle for ix in indexes], nprobes, queries, k, stop, level, ids, dist)
+    return level, ids, dist
 
 
 def search_union(indexes, queries, k, nprobe):

@@ -1479,6 +1479,24 @@ int pk_search_multi(pk_index *const *handles, int32_t n_handles, const int64_t *
 
 static_assert(PK_MAX_K <= 1024 && PK_MAX_HANDLES <= 128, "union_merge_kernel packs rank and handle into 17 bits");
 
+// grow-only staging buffer of the calls that run several searches (scope union, level cascade)
+static int ensure_ubuf(pk_index *own, size_t need, hipStream_t s)
+{
+    if (need <= own->ubuf_bytes) return PK_OK;
+    PK_HIP(hipStreamSynchronize(s)); // earlier work on this stream may still use the old buffer
+    if (own->ubuf) PK_HIP(hipFree(own->ubuf));
+    own->ubuf = nullptr;
+    own->ubuf_bytes = 0;
+    void *p = nullptr;
+    if (hipMalloc(&p, need) != hipSuccess) {
+        (void)hipGetLastError();
+        return PK_ERR_NOMEM;
+    }
+    own->ubuf = static_cast<char *>(p);
+    own->ubuf_bytes = need;
+    return PK_OK;
+}
+
 int pk_search_union(pk_index *const *handles, int32_t n_handles, const float *queries, int64_t nq, int32_t k,
                     int32_t nprobe, int32_t *out_src, int64_t *out_ids, float *out_dist, void *stream)
 {
@@ -1503,19 +1521,7 @@ int pk_search_union(pk_index *const *handles, int32_t n_handles, const float *qu
     const size_t qb = round_up((size_t)H * chunk * d * sizeof(float), 256);
     const size_t ib = round_up((size_t)H * chunk * k * sizeof(int64_t), 256);
     const size_t need = qb + ib + round_up((size_t)H * chunk * k * sizeof(float), 256);
-    if (need > own->ubuf_bytes) {
-        PK_HIP(hipStreamSynchronize(s));
-        if (own->ubuf) PK_HIP(hipFree(own->ubuf));
-        own->ubuf = nullptr;
-        own->ubuf_bytes = 0;
-        void *p = nullptr;
-        if (hipMalloc(&p, need) != hipSuccess) {
-            (void)hipGetLastError();
-            return PK_ERR_NOMEM;
-        }
-        own->ubuf = static_cast<char *>(p);
-        own->ubuf_bytes = need;
-    }
+    PK_TRY(ensure_ubuf(own, need, s));
     float *uq = reinterpret_cast<float *>(own->ubuf);
     int64_t *uids = reinterpret_cast<int64_t *>(own->ubuf + qb);
     float *udist = reinterpret_cast<float *>(own->ubuf + qb + ib);
@@ -1538,6 +1544,66 @@ int pk_search_union(pk_index *const *handles, int32_t n_handles, const float *qu
         u.out_ids = out_ids + (size_t)q0 * k;
         u.out_dist = out_dist + (size_t)q0 * k;
         PK_HIP(launch_union_merge(u, s));
+    }
+    return PK_OK;
+}
+
+int pk_search_levels(pk_index *const *levels, int32_t n_levels, const int32_t *nprobes, const float *queries,
+                     int64_t nq, int32_t k, const float *stop, int32_t *out_level, int64_t *out_ids,
+                     float *out_dist, void *stream)
+{
+    if (!levels || !nprobes || n_levels < 1 || n_levels > PK_MAX_HANDLES) return PK_ERR_INVALID_ARG;
+    int np_max = 1;
+    for (int l = 0; l < n_levels; ++l) {
+        if (!live(levels[l])) return PK_ERR_BAD_HANDLE;
+        for (int b = 0; b < l; ++b)
+            if (levels[b] == levels[l]) return PK_ERR_INVALID_ARG;
+        const pk_config &c0 = levels[0]->cfg, &c = levels[l]->cfg;
+        if (c.d != c0.d || c.metric != c0.metric) return PK_ERR_DIM_MISMATCH;
+        PK_TRY(check_search_args(levels[l], queries, nq, k, nprobes[l]));
+        np_max = std::max(np_max, (int)nprobes[l]);
+    }
+    if (nq > 0 && (!stop || !out_ids || !out_dist)) return PK_ERR_INVALID_ARG;
+    if (nq == 0) return PK_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    pk_index *own = levels[0];
+    // staging: open flags, the probes of a lower level, its rows
+    const size_t ob = round_up((size_t)nq * sizeof(uint32_t), 256);
+    const size_t pb = round_up((size_t)nq * np_max * sizeof(int32_t), 256);
+    const size_t ib = round_up((size_t)nq * k * sizeof(int64_t), 256);
+    const size_t db = round_up((size_t)nq * k * sizeof(float), 256);
+    if (n_levels > 1) PK_TRY(ensure_ubuf(own, ob + pb + ib + db, s));
+    else PK_TRY(ensure_ubuf(own, ob, s));
+    uint32_t *open = reinterpret_cast<uint32_t *>(own->ubuf);
+    int32_t *probes = reinterpret_cast<int32_t *>(own->ubuf + ob);
+    int64_t *row_ids = reinterpret_cast<int64_t *>(own->ubuf + ob + pb);
+    float *row_dist = reinterpret_cast<float *>(own->ubuf + ob + pb + ib);
+    const int64_t offs[2] = {0, nq};
+    for (int l = 0; l < n_levels; ++l) {
+        pk_index *hs[1] = {levels[l]};
+        LevelArgs a{};
+        a.nq = nq;
+        a.k = k;
+        a.metric = own->cfg.metric;
+        a.level = l;
+        a.first = l == 0;
+        a.last = l == n_levels - 1;
+        a.stop = stop;
+        a.open = open;
+        a.level_out = out_level;
+        a.out_ids = out_ids;
+        a.out_dist = out_dist;
+        if (l == 0) {
+            PK_TRY(search_impl(hs, 1, offs, queries, k, nprobes[0], kFull, nullptr, nullptr, out_ids, out_dist, s));
+        } else {
+            // coarse step for the batch, lists of the queries that have ended struck out, fine search
+            PK_TRY(search_impl(hs, 1, offs, queries, 1, nprobes[l], kCoarseOnly, nullptr, probes, nullptr, nullptr, s));
+            PK_HIP(launch_level_mask(probes, nprobes[l], open, nq, s));
+            PK_TRY(search_impl(hs, 1, offs, queries, k, nprobes[l], kForced, probes, nullptr, row_ids, row_dist, s));
+            a.row_ids = row_ids;
+            a.row_dist = row_dist;
+        }
+        PK_HIP(launch_level_accept(a, s));
     }
     return PK_OK;
 }

@@ -264,6 +264,24 @@ struct UnionArgs {
 };
 hipError_t launch_union_merge(const UnionArgs &a, hipStream_t s);
 
+// Level cascade (early termination): bookkeeping between the searches of two levels.
+struct LevelArgs {
+    int64_t nq;
+    int k, metric, level;
+    bool first, last;        // first: every query is open; last: this level ends every search
+    const float *stop;       // [nq]
+    uint32_t *open;          // [nq] 1 while the query has not ended (written when first)
+    int32_t *level_out;      // [nq] or null
+    const int64_t *row_ids;  // [nq][k] this level's rows (null when first: they are already in out_*)
+    const float *row_dist;   // [nq][k]
+    int64_t *out_ids;        // [nq][k]
+    float *out_dist;         // [nq][k]
+};
+// rows of this level -> output for the open queries; closes those the rule (or the last level) ends
+hipError_t launch_level_accept(const LevelArgs &a, hipStream_t s);
+// probes[q][*] = -1 for queries that are no longer open (their lists are not scanned)
+hipError_t launch_level_mask(int32_t *probes, int nprobe, const uint32_t *open, int64_t nq, hipStream_t s);
+
 struct WorklistArgs {
     const int32_t *probes;     // [nq][nprobe]; entries outside [0, nlist) are ignored
     const uint16_t *qagent;    // [nq]

@@ -527,4 +527,56 @@ hipError_t launch_union_merge(const UnionArgs &a, hipStream_t s)
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------ level cascade
+
+// Section 4.2, early termination: one wave per query.  An open query takes this level's row;
+// it ends here if the row holds k candidates and the k-th (the farthest of a row sorted best
+// first) beats the query's threshold, or if this is the last level.
+__global__ __launch_bounds__(256) void level_accept_kernel(LevelArgs a)
+{
+    const int64_t q = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (q >= a.nq) return;
+    if (!a.first && a.open[q] == 0u) return;
+    const size_t row = (size_t)q * a.k;
+    if (a.row_ids) {
+        for (int j = lane; j < a.k; j += 64) {
+            a.out_ids[row + j] = a.row_ids[row + j];
+            a.out_dist[row + j] = a.row_dist[row + j];
+        }
+    }
+    if (lane == 0) {
+        const int64_t *ids = a.row_ids ? a.row_ids : a.out_ids;
+        const float *dist = a.row_ids ? a.row_dist : a.out_dist;
+        const bool full = ids[row + a.k - 1] >= 0;
+        const float kth = dist[row + a.k - 1], t = a.stop[q];
+        const bool beats = a.metric == PK_METRIC_IP ? kth > t : kth < t;
+        const bool done = a.last || (full && beats);
+        a.open[q] = done ? 0u : 1u;
+        if (a.level_out && (done || a.first)) a.level_out[q] = a.level;
+    }
+}
+
+hipError_t launch_level_accept(const LevelArgs &a, hipStream_t s)
+{
+    if (a.nq <= 0) return hipSuccess;
+    hipLaunchKernelGGL(level_accept_kernel, dim3((uint32_t)((a.nq + 3) / 4)), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+__global__ void level_mask_kernel(int32_t *probes, int nprobe, const uint32_t *open, int64_t nq)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= nq * nprobe) return;
+    if (open[i / nprobe] == 0u) probes[i] = -1;
+}
+
+hipError_t launch_level_mask(int32_t *probes, int nprobe, const uint32_t *open, int64_t nq, hipStream_t s)
+{
+    if (nq <= 0) return hipSuccess;
+    const int64_t n = nq * nprobe;
+    hipLaunchKernelGGL(level_mask_kernel, dim3((uint32_t)((n + 255) / 256)), dim3(256), 0, s, probes, nprobe, open, nq);
+    return hipGetLastError();
+}
+
 } // namespace pk

@@ -658,6 +658,64 @@ def test_very_large_query_batch(gpu_device):
         p.close()
 
 
+@pytest.mark.parametrize("storage,metric", [(F32, L2), (F16, IP)])
+def test_level_cascade_with_early_termination(gpu_device, storage, metric):
+    """Section 4.2: three levels (every upper level a subset of the one below), per-query thresholds.
+    The level each query ends at must be the oracle's, its row that level's row (oracle parity with the
+    GPU's own probe lists, as for a plain search).  Thresholds sit between the k-th values the levels
+    give, far from any of them, so rounding cannot flip a decision."""
+    cfg = W.scaled(W.C1, n=8000)
+    x = W.vectors(cfg, 0, cfg.n)
+    if storage == F16:
+        x = x.astype(np.float16).astype(np.float32)
+    cent = W.train_centroids(cfg, x)
+    ids_all = np.arange(cfg.n, dtype=np.int64)
+    subsets = [ids_all[::16], ids_all[::4], ids_all]  # top level first
+    cents = [cent[:8].copy(), cent[:32].copy(), cent]
+    nprobes = [4, 6, 8]
+    k = 10
+    pairs = [Pair(x[sub], c, metric, storage, ids=sub) for sub, c in zip(subsets, cents)]
+    try:
+        q = W.queries(cfg, 50, 96)
+        kth = [p.orc.search(q, k, npb)[1][:, k - 1] for p, npb in zip(pairs, nprobes)]
+        # a third of the queries end at each level: threshold just past the level's own k-th value
+        # (and the upper levels' k-th values, sparser subsets, are farther than that)
+        want = np.arange(len(q)) % 3
+        worse = 1.0 if metric == L2 else -1.0
+        stop = np.empty(len(q), np.float32)
+        for i in range(len(q)):
+            span = abs(kth[0][i] - kth[2][i]) + 1e-3
+            if want[i] == 2:
+                stop[i] = kth[2][i] - worse * 10 * span  # nothing beats it: the search runs to the last level
+            else:
+                stop[i] = kth[want[i]][i] + worse * 0.3 * span
+        olevel, _, _ = oracle.search_levels([p.orc for p in pairs], q, k, nprobes, stop)
+        say(f"level cascade storage={storage} metric={metric}: oracle levels {np.bincount(olevel, minlength=3)}")
+        glevel, gi, gv = B.search_levels([p.gpu for p in pairs], nprobes, dev(q), k, dev(stop))
+        glevel = glevel.cpu().numpy()
+        # decisions whose margin is inside the tolerance may differ; the thresholds above keep clear of that
+        margin = np.minimum.reduce([np.abs(kv - stop) for kv in kth])
+        safe = margin > 20 * pairs[0].tol * pairs[0].scale(q)
+        assert safe.mean() > 0.6
+        assert np.array_equal(glevel[safe], olevel[safe])
+        assert len(set(glevel.tolist())) == 3
+        gi, gv = gi.cpu().numpy(), gv.cpu().numpy()
+        for l, (p, npb) in enumerate(zip(pairs, nprobes)):
+            rows = np.nonzero(glevel == l)[0]
+            if rows.size == 0:
+                continue
+            gp = p.gpu.coarse(dev(q[rows]), npb).cpu().numpy()
+            oi, ov = p.orc.scan_probes(q[rows], k + p.kx, gp)
+            check_results(gi[rows], gv[rows], oi, ov, k, p.tol, p.scale(q[rows]), metric, where=f"level {l}")
+            si, sv = p.gpu.search(dev(q[rows]), k, npb)  # and bit for bit the plain search of that level
+            assert np.array_equal(si.cpu().numpy(), gi[rows]) and np.array_equal(sv.cpu().numpy(), gv[rows])
+        for p in pairs:
+            assert p.gpu.stats().device_error == 0
+    finally:
+        for p in pairs:
+            p.close()
+
+
 def test_search_replays_from_a_hip_graph(gpu_device):
     """A search enqueues kernels only (no allocation, no host synchronisation once the handle's workspace
     has been sized by an earlier call of the same shape), so it can be captured into a HIP graph.  Every

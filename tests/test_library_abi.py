@@ -72,6 +72,10 @@ def test_host_side_argument_checks_without_gpu(lib):
     assert lib.pk_search_union(hs, 1, null, 1, 1, 1, null, null, null, null) == B.PK_ERR_BAD_HANDLE
     assert lib.pk_insert_multi(hs, 1, offs, null, null, null, null) == B.PK_ERR_BAD_HANDLE
     assert lib.pk_search_union(hs, 0, null, 1, 1, 1, null, null, null, null) == B.PK_ERR_INVALID_ARG
+    nps = (C.c_int32 * 1)(1)
+    assert lib.pk_search_levels(hs, 1, nps, null, 1, 1, null, null, null, null, null) == B.PK_ERR_BAD_HANDLE
+    assert lib.pk_search_levels(hs, 0, nps, null, 1, 1, null, null, null, null, null) == B.PK_ERR_INVALID_ARG
+    assert lib.pk_search_levels(hs, 1, None, null, 1, 1, null, null, null, null, null) == B.PK_ERR_INVALID_ARG
 
 
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
