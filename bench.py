@@ -346,6 +346,76 @@ class Scenario:
         return {"eager_ms_per_search": eager, "graph_ms_per_search": replay, "replay_equals_eager": same,
                 "queries_per_s_graph": self.queries_per_step() / (replay * 1e-3)}
 
+    def levels(self, steps=30):
+        """Early termination over two levels (pk_search_levels).  The top level is what the paper's L1
+        cache holds: the top-k' neighbours (k' = 4k) of the agent's recent queries (query batches 8..15),
+        as an IVF index of its own trained by pk_kmeans.  The measured batch is half recent queries
+        asked again with a little noise, half fresh ones.  On these synthetic mixtures every query's
+        top-k distances are alike, so the paper's alpha_et * d_agent with alpha_et = 0.6..0.8 ends no
+        search; the thresholds here are set to end a chosen share of the batch at the top level, which
+        shows what the mechanism costs and saves: 0 (none ends), 0.5, 1 (all end)."""
+        torch, B, W, cfg, dat = self.torch, self.B, self.W, self.cfg, self.datas[0]
+        full = self.indexes[0]
+        k, kp = cfg.k, min(4 * cfg.k, 1024)
+        recent = np.concatenate(self.q_host[8:16])[:8 * cfg.nq]
+        rq = torch.from_numpy(recent).cuda()
+        ids, vals = full.search(rq, kp, cfg.nprobe)
+        ids = ids.cpu().numpy().ravel()
+        top_ids = np.unique(ids[(ids >= 0) & (ids < dat.n)])
+        mean_topk = float(vals[:, :k].mean())
+        x_top = torch.from_numpy(np.ascontiguousarray(dat.x[top_ids])).cuda()
+        nlist_top = int(max(4, min(cfg.nlist, len(top_ids) // 256)))
+        rng = np.random.default_rng(11)
+        cent = x_top[torch.from_numpy(rng.choice(len(top_ids), nlist_top, replace=False)).cuda()].contiguous()
+        B.pk_kmeans(x_top, cent, 5)
+        top = B.Index(cent, x_top, metric=cfg.metric, storage=cfg.storage, ids=torch.from_numpy(top_ids).cuda())
+        half = cfg.nq // 2
+        again = recent[rng.choice(len(recent), half, replace=False)]
+        again = again + rng.normal(0.0, 0.01 / np.sqrt(cfg.d), again.shape).astype(np.float32)
+        q = torch.from_numpy(np.concatenate([again, self.q_host[0][:cfg.nq - half]]).astype(np.float32)).cuda()
+        nprobes = [min(cfg.nprobe, nlist_top), cfg.nprobe]
+        level = torch.empty(cfg.nq, dtype=torch.int32, device="cuda")
+        oi, od = self.out_ids[:cfg.nq], self.out_dist[:cfg.nq]
+
+        def timed(fn):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / steps * 1e3
+
+        plain = timed(lambda: B.pk_search(full.handle, q, k, cfg.nprobe, oi, od))
+        want = oi.clone()
+        top_only = timed(lambda: B.pk_search(top.handle, q, k, nprobes[0], oi, od))
+        kth = od[:, k - 1].clone()  # the top level's k-th value of every query
+        ip = cfg.metric == W.METRIC_IP
+        runs = []
+        for share in (0.0, 0.5, 1.0):
+            if share == 0.0:
+                stop = torch.full_like(kth, float("inf") if ip else float("-inf"))
+            elif share == 1.0:
+                stop = torch.full_like(kth, float("-inf") if ip else float("inf"))
+            else:
+                stop = torch.full_like(kth, float(torch.quantile(kth, (1.0 - share) if ip else share)))
+            ms = timed(lambda: B.pk_search_levels([top.handle, full.handle], nprobes, q, k, stop, level, oi, od))
+            ended = level == 0
+            same = (oi == want).float().mean(dim=1)
+            runs.append({"share_wanted": share, "ended_at_top": float(ended.float().mean()),
+                         "ended_at_top_among_repeated": float(ended[:half].float().mean()),
+                         "ended_at_top_among_fresh": float(ended[half:].float().mean()),
+                         "ms_per_call": ms,
+                         "ids_equal_to_full_search_where_ended_at_top":
+                             float(same[ended].mean()) if bool(ended.any()) else None})
+        out = {"top_level_vectors": int(len(top_ids)), "top_level_lists": nlist_top, "queries": cfg.nq,
+               "mean_top_k_value_of_recent_queries": mean_topk, "ms_full_index_search": plain,
+               "ms_top_level_search": top_only, "runs": runs}
+        self.check_errors()
+        top.close()
+        return out
+
     def scope_union(self, steps=30):
         """One agent's query batch searched across the memories of ALL agents of the workload
         (pk_search_union): the same number of (query, index) searches as one multi-agent step."""
@@ -486,6 +556,9 @@ def run(args):
     if args.graph:
         out["hip_graph"] = sc.graph_replay()
         log(f"hip graph: {out['hip_graph']}")
+    if args.levels:
+        out["levels"] = sc.levels()
+        log(f"levels: {out['levels']}")
     if args.union:
         out["scope_union"] = sc.scope_union()
         log(f"scope union: {out['scope_union']}")
@@ -509,6 +582,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="also capture one search into a HIP graph and time its replays (extra field)")
+    ap.add_argument("--levels", action="store_true",
+                    help="also time pk_search_levels over a two-level stack (cache of recent neighbours above the "
+                         "index) with early termination (extra field)")
     ap.add_argument("--union", action="store_true",
                     help="also time pk_search_union: one agent's batch searched across all agents' memories (extra field)")
     ap.add_argument("--train", type=int, default=0, metavar="ITERS",
