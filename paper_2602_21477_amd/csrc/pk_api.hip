@@ -229,7 +229,7 @@ const Tunables &tunables()
             const char *v = getenv(name);
             return v ? atoi(v) : dflt;
         };
-        return Tunables{env("PK_TUNE_WGS", 4),       env("PK_TUNE_MQ", 0),        env("PK_TUNE_MQH", 128),
+        return Tunables{env("PK_TUNE_WGS", 4),       env("PK_TUNE_MQ", 0),        env("PK_TUNE_MQH", 64),
                         env("PK_TUNE_KS", 1),        env("PK_TUNE_SP_MAX", 16),   env("PK_TUNE_GEMM_WGS", 128),
                         env("PK_TUNE_DENSESEL", 1),  env("PK_TUNE_GRABDIV", 8),   env("PK_TUNE_HIST", 1),
                         env("PK_TUNE_RS_FROM", 256)};
@@ -276,7 +276,7 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
             avg = std::max(avg, (double)(qlo[a + 1] - qlo[a]) * nprobe / hs[a]->cfg.nlist);
         const int want = avg <= 6 ? 16 : (avg <= 20 ? 32 : 64);
         p.mq_f = std::min(p.mq_f, tunables().mq > 0 ? tunables().mq : want);
-        p.mq_h = own->cfg.storage == PK_F16 ? 128 : 32;
+        p.mq_h = own->cfg.storage == PK_F16 ? 64 : 32;
         p.mq_h = std::min(p.mq_h, tunables().mqh);
         const int ks = tunables().ks;
         const bool wide = p.mq_f < 16 || scan_lds_bytes(own->row_bytes, p.mq_f) > 64 * 1024;

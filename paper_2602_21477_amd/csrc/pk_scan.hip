@@ -428,8 +428,8 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(3, 8
 // The query group is staged through LDS one 256-byte slice of every row at a time, double
 // buffered: while the waves multiply slice c, the next slice of the rows (registers) and of
 // the queries (registers, then LDS) is already on its way.  One barrier per slice keeps the
-// four waves of the workgroup in step.  MT up to 8 (128 slots): a lane then holds 64
-// accumulator registers.  Always 4 waves, one 32-row block each per pass over the page.
+// four waves of the workgroup in step.  MT up to 4 (64 slots).  Always 4 waves, one 32-row
+// block each per pass over the page.
 template <int STORAGE, int MT, bool GATED>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 8))) void scan_ks_kernel(ScanArgs a)
 {
@@ -965,7 +965,6 @@ static hipError_t launch_ks_mt(const ScanArgs &a, int grid, hipStream_t s)
     case 16: return launch_ks_one<STORAGE, 1, GATED>(a, grid, s);
     case 32: return launch_ks_one<STORAGE, 2, GATED>(a, grid, s);
     case 64: return launch_ks_one<STORAGE, 4, GATED>(a, grid, s);
-    case 128: return launch_ks_one<STORAGE, 8, GATED>(a, grid, s);
     default: return hipErrorInvalidValue;
     }
 }
