@@ -26,6 +26,8 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))  # the harness's index training (centroids are an input)
+import training  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0  # MI355X datasheet HBM3E bandwidth
 METRIC_NAME = "search queries/sec at recall@10>=0.9 (1 GPU); list-scan HBM GB/s vs peak"
@@ -60,10 +62,10 @@ class Data:
         t0 = time.time()
         if cfg.train == "component_means":
             self.x, comp = W.vectors(cfg, 0, n, agent=agent, threads=host_threads(), with_components=True)
-            self.cent = W.train_centroids(cfg, self.x, agent=agent, comp=comp)
+            self.cent = training.train_centroids(cfg, self.x, agent=agent, comp=comp)
         else:
             self.x = W.vectors(cfg, 0, n, agent=agent, threads=host_threads())
-            self.cent = W.train_centroids(cfg, self.x, agent=agent)
+            self.cent = training.train_centroids(cfg, self.x, agent=agent)
         self.n, self.agent = n, agent
         log(f"agent {agent}: generated {n} x {cfg.d} and trained {cfg.nlist} centroids in {time.time() - t0:.1f}s")
 
@@ -192,7 +194,7 @@ class Scenario:
         else:
             sub = W.scaled(cfg, nlist=nlist_s)
             rows = W.train_rows(sub, n_s)
-            cent = W.lloyd(xs[rows], W.init_rows(sub, len(rows)), 4)
+            cent = training.lloyd(xs[rows], W.init_rows(sub, len(rows)), 4)
         t0 = time.time()
         ix = oracle.Index(cent, cfg.metric)
         ix.build(xs)
@@ -593,7 +595,20 @@ def main():
     ap.add_argument("--maintenance", type=int, default=0, metavar="N",
                     help="after the timed steps: insert N more vectors, compact the index into a fresh arena "
                          "(pk_index_compact) and report the cost (extra field, the headline is unchanged)")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="counter calibration only: four plain 1 GiB device-to-device copies (a copy kernel of known "
+                         "size for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE), then exit")
     args = ap.parse_args()
+    if args.calib_copy:
+        import torch
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(3)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calib_copy_bytes_each_way": 1 << 30, "copies": 4}))
+        return
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); run with --gpus 1.", file=sys.stderr)
         raise SystemExit(2)

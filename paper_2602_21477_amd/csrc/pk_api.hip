@@ -42,6 +42,7 @@ struct pk_index {
     std::vector<uint64_t> top_len; // [j] = total length of the j longest lists when the layout was last fixed (build, compaction)
     int64_t inserted_at_top;       // n_inserted at that moment
     int64_t n_total, n_inserted;
+    int64_t n_refused;             // vectors of batches the device refused (found when the stats are read)
     int64_t next_id;               // vectors ever added: the running id counter (deletes do not lower it)
     // page accounting: last page counter read back, and how many vectors were inserted by then
     uint32_t pages_known;
@@ -207,8 +208,9 @@ void carve(Plan &p, char *base, const pk_index *own)
     p.bytes = round_up(c.off, 256);
 }
 
-// Developer knobs: environment variables read once per process.  The defaults are the
-// measured choices; the variables exist so that a sweep needs no rebuild.
+// Tuning constants: the measured choices.  A build with -DPK_DEV_TUNABLES reads each of them
+// from the environment variable named beside it (once per process), so that a sweep needs no
+// rebuild; the shipped library reads no environment variable.
 struct Tunables {
     int wgs;      // PK_TUNE_WGS: most scan workgroups per CU
     int mq;       // PK_TUNE_MQ: most query slots per regular tile (0: by expected queries per list)
@@ -226,8 +228,13 @@ const Tunables &tunables()
 {
     static const Tunables t = [] {
         auto env = [](const char *name, int dflt) {
+#ifdef PK_DEV_TUNABLES
             const char *v = getenv(name);
             return v ? atoi(v) : dflt;
+#else
+            (void)name;
+            return dflt;
+#endif
         };
         return Tunables{env("PK_TUNE_WGS", 4),       env("PK_TUNE_MQ", 0),        env("PK_TUNE_MQH", 64),
                         env("PK_TUNE_KS", 1),        env("PK_TUNE_SP_MAX", 16),   env("PK_TUNE_GEMM_WGS", 128),
@@ -1643,8 +1650,16 @@ int pk_index_stats(pk_index *ix, pk_stats *out, void *stream)
     PK_HIP(hipStreamSynchronize(s));
     PK_TRY(settle_pages(ix));
     std::memset(out, 0, sizeof(*out));
-    out->n_total = ix->n_total;
-    out->n_inserted = ix->n_inserted;
+    // The device's list lengths are the truth: a batch the device refused (sticky error flag:
+    // a list's delta-page table was full) was counted on the host when it was enqueued.
+    // (the host's own count of inserts only serves as an upper bound and stays as it is)
+    int64_t held = 0;
+    for (uint32_t v : len) held += v;
+    const int64_t refused = ctr[1] != 0 ? std::max<int64_t>(0, ix->n_total - held) : 0;
+    ix->n_total = held;
+    ix->n_refused += refused;
+    out->n_total = held;
+    out->n_inserted = std::max<int64_t>(0, ix->n_inserted - ix->n_refused);
     out->pages_total = ix->pages_total;
     out->pages_used = ctr[0];
     out->arena_bytes = (int64_t)ix->arena_bytes;

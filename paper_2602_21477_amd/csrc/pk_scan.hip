@@ -24,6 +24,8 @@
 //                   too wide for the first kernel to keep several workgroups per CU.
 // centroid_scores_kernel is the coarse step for small query segments (the same operand
 // layout, no LDS staging); large segments go through the GEMM in pk_gemm.hip.
+#include <atomic>
+
 #include "pk_internal.h"
 
 namespace pk {
@@ -918,14 +920,28 @@ int scan_max_mq(int row_bytes, int storage, int lds_limit)
     return best;
 }
 
+// Dynamic LDS beyond 64 KB has to be allowed per kernel and device.  Every scan kernel is cleared
+// once per device for the most a workgroup can have, so the value never depends on the call
+// that happens to come first and threads serving different handles cannot undo each other.
+constexpr int kMaxDevices = 64;
+struct LdsCleared {
+    std::atomic<int> on[kMaxDevices];
+};
+
 template <typename K>
-static hipError_t launch_with_lds(K kernel, int &cleared, int lds, const ScanArgs &a, int grid, int threads, hipStream_t s)
+static hipError_t launch_with_lds(K kernel, LdsCleared &c, int lds, const ScanArgs &a, int grid, int threads, hipStream_t s)
 {
-    if (lds > cleared) { // dynamic LDS size the kernel is cleared for (per instantiation)
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const bool tracked = dev >= 0 && dev < kMaxDevices;
+    if (!tracked || c.on[dev].load(std::memory_order_acquire) == 0) {
+        int most = 0;
+        e = hipDeviceGetAttribute(&most, hipDeviceAttributeMaxSharedMemoryPerBlock, dev);
         if (e != hipSuccess) return e;
-        cleared = lds;
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, most);
+        if (e != hipSuccess) return e;
+        if (tracked) c.on[dev].store(1, std::memory_order_release);
     }
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(threads), lds, s, a);
     return hipGetLastError();
@@ -934,7 +950,7 @@ static hipError_t launch_with_lds(K kernel, int &cleared, int lds, const ScanArg
 template <int STORAGE, int MT, int WAVES, bool GATED>
 static hipError_t launch_one(const ScanArgs &a, int grid, hipStream_t s)
 {
-    static int cleared = 0;
+    static LdsCleared cleared;
     return launch_with_lds(&scan_kernel<STORAGE, MT, WAVES, GATED>, cleared, scan_lds_bytes(a.row_bytes, a.mq), a, grid,
                            WAVES * 64, s);
 }
@@ -942,7 +958,7 @@ static hipError_t launch_one(const ScanArgs &a, int grid, hipStream_t s)
 template <int STORAGE, int MT, bool GATED>
 static hipError_t launch_ks_one(const ScanArgs &a, int grid, hipStream_t s)
 {
-    static int cleared = 0;
+    static LdsCleared cleared;
     return launch_with_lds(&scan_ks_kernel<STORAGE, MT, GATED>, cleared, scan_ks_lds_bytes(MT * 16), a, grid, 256, s);
 }
 
@@ -989,7 +1005,7 @@ hipError_t launch_scan_rs(const ScanArgs &a, int grid, hipStream_t s)
     if (a.row_bytes <= 0 || a.row_bytes % kIterBytes != 0 || a.row_bytes > 1536 || a.tau == nullptr || a.mq != kRsSlots ||
         a.use_hist != 0)
         return hipErrorInvalidValue;
-    static int cleared_h = 0, cleared_f = 0;
+    static LdsCleared cleared_h, cleared_f;
     if (a.storage == PK_F16)
         return launch_with_lds(&scan_rs_kernel<PK_F16>, cleared_h, scan_rs_lds_bytes(a.row_bytes), a, grid, 512, s);
     return launch_with_lds(&scan_rs_kernel<PK_F32>, cleared_f, scan_rs_lds_bytes(a.row_bytes), a, grid, 512, s);

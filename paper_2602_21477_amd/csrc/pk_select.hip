@@ -1,5 +1,5 @@
-// Top-k selection for gfx950: best `nprobe` centroids per query (Section 2.2 coarse
-// search, "only the top-nprobe clusters are selected") and best `k` vectors per query
+// Top-k selection for gfx950: best `nprobe` centroids per query (Section 2.2, coarse
+// search) and best `k` vectors per query
 // over the scored candidates of all probed lists, i.e. the merge of the per-list partial
 // results (Section 4.4: partial results are merged into the final result).
 //
@@ -309,7 +309,9 @@ __global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, 
     int64_t *s_id = reinterpret_cast<int64_t *>(keys + cap);     // [k]
     __shared__ uint32_t s_cnt;
     __shared__ long long s_red[kSelThreads / 64];
+    __shared__ uint32_t s_redpos[kSelThreads / 64];
     __shared__ long long s_pick;
+    __shared__ uint32_t s_pickpos;
     const uint32_t q = blockIdx.x;
     const int k = a.k;
     Selector sel;
@@ -357,36 +359,62 @@ __global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, 
         uint32_t nb = 0;
         while (nb < (uint32_t)k && (uint32_t)(keys[nb] >> 32) < tau) ++nb;
         const uint32_t base = a.qoff[q], total = a.qcnt[q];
-        long long last = INT64_MIN;
+        // Members are taken in (id, position) order: several rows may carry one id, and each
+        // of them is a candidate of its own.
+        long long last_id = 0;
+        uint32_t last_pos = 0;
+        bool have_last = false;
         for (uint32_t t = nb; t < (uint32_t)k; ++t) {
             long long best = INT64_MAX;
+            uint32_t best_pos = 0xffffffffu;
             for (uint32_t p = threadIdx.x; p < total; p += blockDim.x) {
                 const u64 key = a.keys[base + p];
                 if ((uint32_t)(key >> 32) == tau) {
-                    const long long id = resolve_id(a, h, q, (uint32_t)key);
-                    if (id > last && id < best) best = id;
+                    const uint32_t pos = (uint32_t)key;
+                    const long long id = resolve_id(a, h, q, pos);
+                    const bool after = !have_last || id > last_id || (id == last_id && pos > last_pos);
+                    if (after && (id < best || (id == best && pos < best_pos))) {
+                        best = id;
+                        best_pos = pos;
+                    }
                 }
             }
             for (int off = 32; off > 0; off >>= 1) {
                 const long long o = __shfl_xor(best, off);
-                best = o < best ? o : best;
+                const uint32_t op = __shfl_xor(best_pos, off);
+                if (o < best || (o == best && op < best_pos)) {
+                    best = o;
+                    best_pos = op;
+                }
             }
-            if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = best;
+            if ((threadIdx.x & 63) == 0) {
+                s_red[threadIdx.x >> 6] = best;
+                s_redpos[threadIdx.x >> 6] = best_pos;
+            }
             __syncthreads();
             if (threadIdx.x == 0) {
                 long long b = s_red[0];
-                for (int w = 1; w < kSelThreads / 64; ++w) b = s_red[w] < b ? s_red[w] : b;
+                uint32_t bp = s_redpos[0];
+                for (int w = 1; w < kSelThreads / 64; ++w)
+                    if (s_red[w] < b || (s_red[w] == b && s_redpos[w] < bp)) {
+                        b = s_red[w];
+                        bp = s_redpos[w];
+                    }
                 s_pick = b;
+                s_pickpos = bp;
                 s_id[t] = b;
                 keys[t] = ((u64)tau << 32) | (uint32_t)t; // keeps the value; the low word is no longer used
             }
             __syncthreads();
-            last = s_pick;
+            last_id = s_pick;
+            last_pos = s_pickpos;
+            have_last = true;
             __syncthreads();
         }
     }
 
-    // final order: (value key, id) ascending; ranks are unique because ids are
+    // final order: (value key, id) ascending; rows that carry the same id with the same value
+    // keep their order in keys[], so ranks are unique
     for (uint32_t i = threadIdx.x; i < (uint32_t)k; i += blockDim.x) {
         if (i < kk) {
             const uint32_t ki = (uint32_t)(keys[i] >> 32);
@@ -394,7 +422,7 @@ __global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, 
             uint32_t rank = 0;
             for (uint32_t j = 0; j < kk; ++j) {
                 const uint32_t kj = (uint32_t)(keys[j] >> 32);
-                rank += (kj < ki || (kj == ki && s_id[j] < idi)) ? 1u : 0u;
+                rank += (kj < ki || (kj == ki && (s_id[j] < idi || (s_id[j] == idi && j < i)))) ? 1u : 0u;
             }
             a.out_ids[(size_t)q * k + rank] = idi;
             a.out_dist[(size_t)q * k + rank] = value_of(ki, a.metric);

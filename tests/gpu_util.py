@@ -8,6 +8,7 @@ import oracle
 from compare import check_probes, check_results
 from paper_2602_21477_amd import binding as B
 from paper_2602_21477_amd import workload as W
+import training
 
 TOL = {B.PK_F32: 1e-4, B.PK_F16: 1e-2}  # spec: relative tolerance for fp32 / fp16-stored vectors
 KX = 48  # extra oracle results past k (fp32), so the comparator can look near-tied candidates up
@@ -109,10 +110,10 @@ def make_pair(cfg, n=None, metric=None, storage=None, agent=0, **kw):
     cfg = W.scaled(cfg, n=n)
     if cfg.train == "component_means":
         x, comp = W.vectors(cfg, 0, n, agent=agent, with_components=True)
-        cent = W.train_centroids(cfg, x, agent=agent, comp=comp)
+        cent = training.train_centroids(cfg, x, agent=agent, comp=comp)
     else:
         x = W.vectors(cfg, 0, n, agent=agent)
-        cent = W.train_centroids(cfg, x, agent=agent)
+        cent = training.train_centroids(cfg, x, agent=agent)
     metric = cfg.metric if metric is None else metric
     storage = cfg.storage if storage is None else storage
     return Pair(x, cent, metric, storage, **kw), cfg

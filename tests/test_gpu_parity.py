@@ -13,6 +13,7 @@ from compare import check_results, recall_at
 from gpu_util import KX, Pair, dev, make_pair
 from paper_2602_21477_amd import binding as B
 from paper_2602_21477_amd import workload as W
+import training
 
 pytestmark = pytest.mark.gpu
 
@@ -128,7 +129,7 @@ def test_batch_inserts_grow_delta_pages_and_match_rebuild(gpu_device):
     """Small pages so lists open many delta pages; build(n) + inserts == build(n + m) (same results)."""
     cfg = W.scaled(W.C1, n=6000)
     x = W.vectors(cfg, 0, cfg.n)
-    cent = W.train_centroids(cfg, x)
+    cent = training.train_centroids(cfg, x)
     extra = np.concatenate([W.inserts(cfg, b, 37) for b in range(40)])  # 1480 vectors
     a = Pair(x, cent, IP, F32, page_vecs=32, insert_reserve=4000)
     b = Pair(np.concatenate([x, extra]), cent, IP, F32, page_vecs=32)
@@ -156,7 +157,7 @@ def test_compaction_keeps_results_and_inserts_go_on(gpu_device, storage, metric)
     compaction into a third arena."""
     cfg = W.scaled(W.C1, n=5000)
     x = W.vectors(cfg, 0, cfg.n)
-    cent = W.train_centroids(cfg, x)
+    cent = training.train_centroids(cfg, x)
     extra = np.concatenate([W.inserts(cfg, b, 61) for b in range(30)])  # 1830 vectors
     p = Pair(x, cent, metric, storage, page_vecs=32, insert_reserve=3000)
     try:
@@ -299,6 +300,37 @@ def test_duplicates_across_the_k_boundary(gpu_device):
             p.close()
 
 
+def test_one_id_carried_by_equal_rows_across_the_k_boundary(gpu_device):
+    """Several rows may carry one id.  Seven exact copies of one vector carry only three distinct
+    ids (5, 5, 5, 9, 9, 30, 30), and k cuts through the runs: every carrier is a candidate of its own,
+    so the row is the multiset of the lowest (value, id) pairs, as in the oracle's sort."""
+    rng = np.random.default_rng(16)
+    n, d = 3000, 64
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    x /= np.linalg.norm(x, axis=1, keepdims=True)
+    dup_rows = [11, 500, 501, 777, 1200, 1999, 2500]
+    x[dup_rows] = x[11]
+    ids = (np.arange(n) + 1000).astype(np.int64)
+    ids[dup_rows] = [5, 9, 5, 30, 5, 9, 30]
+    cent = x[rng.permutation(n)[:16]].copy()
+    q = np.stack([x[11], x[42]])
+    carried = sorted(ids[dup_rows].tolist())
+    for metric in (IP, L2):
+        p = Pair(x, cent, metric, F32, ids=ids)
+        try:
+            for k in (1, 2, 3, 4, 5, 6, 7, 10):
+                say(f"shared ids metric={metric} k={k}")
+                gi, gv = p.gpu.search(dev(q), k, 16)
+                gi, gv = gi.cpu().numpy(), gv.cpu().numpy()
+                oi, ov = p.orc.search(q, k, 16)
+                m = min(k, 7)
+                assert gi[0, :m].tolist() == carried[:m], (k, gi[0].tolist())
+                assert np.array_equal(gi, oi[:, :k]), (k, gi.tolist(), oi[:, :k].tolist())
+                np.testing.assert_allclose(gv, ov[:, :k], rtol=1e-4, atol=1e-5)
+        finally:
+            p.close()
+
+
 def test_multi_agent_equals_per_handle_calls(gpu_device):
     """Config 3 shape, scaled: several independent indexes, one segmented call."""
     cfg = W.scaled(W.C3, d=256, ncomp=32, nlist=48, n_agents=5)
@@ -386,7 +418,7 @@ def test_scope_union_search(gpu_device, metric):
             x = W.vectors(cfg, 0, n, agent=a)
             if a == 2:
                 x[5] = pairs[0].x[9]
-            cent = W.train_centroids(W.scaled(cfg, n=n), x, agent=a) if n >= 16 * 4 else x[:16].copy()
+            cent = training.train_centroids(W.scaled(cfg, n=n), x, agent=a) if n >= 16 * 4 else x[:16].copy()
             pairs.append(Pair(x, cent, metric, F32))
         q = np.concatenate([W.queries(cfg, 4, 40), pairs[0].x[9:10]])
         k, nprobe = 50, 6
@@ -417,7 +449,7 @@ def test_delete_update_and_page_reuse(gpu_device, storage, metric):
     old id); list lengths, counts and every search follow the oracle."""
     cfg = W.scaled(W.C1, n=5000)
     x = W.vectors(cfg, 0, cfg.n)
-    cent = W.train_centroids(cfg, x)
+    cent = training.train_centroids(cfg, x)
     ids = np.arange(cfg.n, dtype=np.int64) * 7 + 3
     ids[1234] = ids[77]  # two rows under one id
     p = Pair(x, cent, metric, storage, ids=ids, page_vecs=32, insert_reserve=3000)
@@ -478,7 +510,7 @@ def test_ivf_split(gpu_device, storage, metric):
     membership) agrees with every search and with inserts that follow."""
     cfg = W.scaled(W.C1, n=6000, nlist=16)
     x = W.vectors(cfg, 0, cfg.n)
-    cent = W.train_centroids(cfg, x)
+    cent = training.train_centroids(cfg, x)
     ids = np.random.default_rng(11).permutation(cfg.n).astype(np.int64) * 5 + 2
     p = Pair(x, cent, metric, storage, ids=ids, page_vecs=32, insert_reserve=2000)
     try:
@@ -539,7 +571,7 @@ def test_insert_multi_across_agents(gpu_device):
     try:
         for a in range(3):
             x = W.vectors(cfg, 0, 3000 - 500 * a, agent=a)
-            pairs.append(Pair(x, W.train_centroids(W.scaled(cfg, n=len(x)), x, agent=a), IP, F32, insert_reserve=4000))
+            pairs.append(Pair(x, training.train_centroids(W.scaled(cfg, n=len(x)), x, agent=a), IP, F32, insert_reserve=4000))
         hs = [p.gpu.handle for p in pairs]
         for sizes, with_ids in (((5, 0, 17), True), ((64, 1, 9), False), ((3, 1500, 2), False)):
             xs = [W.inserts(cfg, 50 + a, max(n, 1), agent=a)[:n] for a, n in enumerate(sizes)]
@@ -668,7 +700,7 @@ def test_level_cascade_with_early_termination(gpu_device, storage, metric):
     x = W.vectors(cfg, 0, cfg.n)
     if storage == F16:
         x = x.astype(np.float16).astype(np.float32)
-    cent = W.train_centroids(cfg, x)
+    cent = training.train_centroids(cfg, x)
     ids_all = np.arange(cfg.n, dtype=np.int64)
     subsets = [ids_all[::16], ids_all[::4], ids_all]  # top level first
     cents = [cent[:8].copy(), cent[:32].copy(), cent]
@@ -776,7 +808,7 @@ def test_large_k_no_threshold_and_chunked_selection(gpu_device):
 def test_arena_exhaustion_is_reported_and_recoverable(gpu_device):
     cfg = W.scaled(W.C1, n=3000)
     x = W.vectors(cfg, 0, cfg.n)
-    cent = W.train_centroids(cfg, x)
+    cent = training.train_centroids(cfg, x)
     c = B.pk_config(cfg.d, cfg.nlist, IP, F32, 32, 0)
     with pytest.raises(B.PancakeError) as e:
         B.Index(dev(cent), dev(x), page_vecs=32, arena_bytes=B.pk_arena_bytes(c, 100, 0))

@@ -15,6 +15,7 @@ import pytest
 
 import oracle
 from paper_2602_21477_amd import workload as W
+import training
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden", "toy_ivf_2d.json")
 METRICS = {"IP": oracle.IP, "L2": oracle.L2}
@@ -250,7 +251,7 @@ def test_blas_lloyd_matches_plain_kmeans_on_tiny_config():
     x = W.vectors(cfg, 0, cfg.n)
     init = W.init_rows(cfg, cfg.n)
     c_plain, inertia, _ = oracle.kmeans(x, cfg.nlist, cfg.train_iters, init)
-    c_blas = W.lloyd(x, init, cfg.train_iters)
+    c_blas = training.lloyd(x, init, cfg.train_iters)
     close = np.all(np.abs(c_plain - c_blas) < 1e-5, axis=1)
     assert close.mean() >= 0.9  # fp32 BLAS distances may flip a near-tie in a few clusters
     ix = oracle.Index(c_blas, oracle.L2)
@@ -443,7 +444,7 @@ def test_recall_on_tiny_config_is_high():
     """Config 1 recipe end to end on the oracle: recall@10 at nprobe = 8 of 64."""
     cfg = W.scaled(W.C1, n=8000)
     x = W.vectors(cfg, 0, cfg.n)
-    cent = W.train_centroids(cfg, x)
+    cent = training.train_centroids(cfg, x)
     ix = oracle.Index(cent, oracle.IP)
     ix.build(x)
     q = W.queries(cfg, 0, 64)
