@@ -61,7 +61,8 @@ typedef enum {
     PK_ERR_DIM_MISMATCH = -3, /* handles of one multi-agent call differ in d / metric  */
     PK_ERR_NOMEM = -4,        /* arena (or host / workspace memory) exhausted          */
     PK_ERR_HIP = -5,          /* a HIP runtime call failed                             */
-    PK_ERR_UNSUPPORTED = -6   /* valid request outside the limits below                */
+    PK_ERR_UNSUPPORTED = -6,  /* valid request outside the limits below                */
+    PK_ERR_WORKSPACE = -7     /* the call does not fit the fixed-size workspace it must use */
 } pk_status;
 
 /* Limits (compile-time). */
@@ -70,6 +71,7 @@ typedef enum {
 #define PK_MAX_HANDLES 128   /* handles per pk_search_multi call                      */
 #define PK_MAX_ARENAS 8      /* arenas per index                                      */
 #define PK_MAX_DIM 1536      /* vector dimension                                      */
+#define PK_NOALLOC_WORKSPACE_BYTES (64u << 20) /* workspace of pk_search_noalloc, per GPU */
 
 typedef struct {
     int32_t d;               /* vector dimension, >= 1                                 */
@@ -234,6 +236,28 @@ int pk_insert_assigned(pk_index *index, const float *vectors, const int64_t *ids
  */
 int pk_search(pk_index *index, const float *queries, int64_t nq, int32_t k, int32_t nprobe, int64_t *out_ids,
               float *out_dist, void *stream);
+
+/*
+ * pk_search for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
+ * bit-identical results, but the workspace (prepared queries, centroid scores, probe lists,
+ * work list, tiles, emitted candidates: everything pk_search keeps in the handle's
+ * grow-only buffer) is a fixed array of PK_NOALLOC_WORKSPACE_BYTES that is part of the
+ * library's device image: every GPU the library is loaded on holds one copy until the
+ * process ends.  The call never calls hipMalloc / hipFree, never waits for the device and
+ * records no stage timing.
+ *   PK_ERR_WORKSPACE  the search needs more than the array holds; nothing is enqueued.
+ *                     pk_search_noalloc_bytes(index, nq, k, nprobe) tells the need
+ *                     beforehand (0: invalid arguments); it grows with nq, with nprobe
+ *                     times the longest lists, and with every vector inserted.
+ * All calls on one GPU share that GPU's array, whatever the handle: two such calls that
+ * overlap in time on one GPU (different streams or threads) race and give wrong results.
+ * Calls in stream order are safe; every call clears what it needs cleared itself.
+ * Asynchronous.
+ */
+int pk_search_noalloc(pk_index *index, const float *queries, int64_t nq, int32_t k, int32_t nprobe,
+                      int64_t *out_ids, float *out_dist, void *stream);
+size_t pk_search_noalloc_bytes(pk_index *index, int64_t nq, int32_t k, int32_t nprobe);
 
 /*
  * Section 3.2 (independent per-agent indexes) + Section 5 (batched operations): queries

@@ -20,8 +20,10 @@ PK_F32, PK_F16 = 0, 1
 PK_OK = 0
 PK_ERR_INVALID_ARG, PK_ERR_BAD_HANDLE, PK_ERR_DIM_MISMATCH, PK_ERR_NOMEM, PK_ERR_HIP, PK_ERR_UNSUPPORTED = (
     -1, -2, -3, -4, -5, -6)
+PK_ERR_WORKSPACE = -7
+PK_NOALLOC_WORKSPACE_BYTES = 64 << 20
 
-EXPORTS = ["pk_search_levels", "pk_search_union", "pk_insert_multi", "pk_delete", "pk_index_split", "pk_index_centroids", "pk_list_ids", "pk_arena_bytes", "pk_index_build", "pk_index_add_arena", "pk_index_compact", "pk_kmeans", "pk_insert", "pk_insert_assigned", "pk_search",
+EXPORTS = ["pk_search_noalloc", "pk_search_noalloc_bytes", "pk_search_levels", "pk_search_union", "pk_insert_multi", "pk_delete", "pk_index_split", "pk_index_centroids", "pk_list_ids", "pk_arena_bytes", "pk_index_build", "pk_index_add_arena", "pk_index_compact", "pk_kmeans", "pk_insert", "pk_insert_assigned", "pk_search",
            "pk_search_multi", "pk_coarse", "pk_scan_probes", "pk_index_stats", "pk_list_lengths", "pk_profile_begin",
            "pk_profile_end", "pk_index_free", "pk_strerror"]
 
@@ -74,6 +76,9 @@ def lib():
         L.pk_insert_multi.argtypes = [C.POINTER(vp), i32, C.POINTER(i64), vp, vp, vp, vp]
         L.pk_delete.argtypes = [vp, vp, i64, C.POINTER(i64), vp]
         L.pk_search.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
+        L.pk_search_noalloc.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
+        L.pk_search_noalloc_bytes.restype = C.c_size_t
+        L.pk_search_noalloc_bytes.argtypes = [vp, i64, i32, i32]
         L.pk_search_multi.argtypes = [C.POINTER(vp), i32, C.POINTER(i64), vp, i32, i32, vp, vp, vp]
         L.pk_search_union.argtypes = [C.POINTER(vp), i32, vp, i64, i32, i32, vp, vp, vp, vp]
         L.pk_search_levels.argtypes = [C.POINTER(vp), i32, C.POINTER(i32), vp, i64, i32, vp, vp, vp, vp, vp]
@@ -87,7 +92,7 @@ def lib():
         L.pk_strerror.restype = C.c_char_p
         L.pk_strerror.argtypes = [C.c_int]
         for name in EXPORTS:
-            if name not in ("pk_arena_bytes", "pk_strerror"):
+            if name not in ("pk_arena_bytes", "pk_strerror", "pk_search_noalloc_bytes"):
                 getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -194,6 +199,16 @@ def pk_search(handle: int, queries, k: int, nprobe: int, out_ids, out_dist):
     _check(lib().pk_search(handle, _dev(queries, torch.float32, "queries"), queries.shape[0], k, nprobe,
                            _dev(out_ids, torch.int64, "out_ids"), _dev(out_dist, torch.float32, "out_dist"),
                            _stream()), "pk_search")
+
+
+def pk_search_noalloc(handle: int, queries, k: int, nprobe: int, out_ids, out_dist):
+    _check(lib().pk_search_noalloc(handle, _dev(queries, torch.float32, "queries"), queries.shape[0], k, nprobe,
+                                   _dev(out_ids, torch.int64, "out_ids"), _dev(out_dist, torch.float32, "out_dist"),
+                                   _stream()), "pk_search_noalloc")
+
+
+def pk_search_noalloc_bytes(handle: int, nq: int, k: int, nprobe: int) -> int:
+    return int(lib().pk_search_noalloc_bytes(handle, int(nq), int(k), int(nprobe)))
 
 
 def pk_search_multi(handles, q_offsets, queries, k: int, nprobe: int, out_ids, out_dist):

@@ -1,6 +1,7 @@
 // C ABI of libpancake: handle management, arena layout, host-side bounds and the launch
 // sequences of build, insert and search.  See include/pancake.h for the contract.
 #include <algorithm>
+#include <atomic>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -27,6 +28,37 @@ constexpr int kBuildChunk = 16384;          // vectors assigned per coarse pass 
     } while (0)
 
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Workspace of pk_search_noalloc: a file-scope device array, so that the call needs no
+// hipMalloc.  Every GPU the library is loaded on holds its own copy until the process ends.
+// In host code the name `scratch` is only a stand-in for the symbol, never a device address:
+// the address on the current device comes from hipGetSymbolAddress (scratch_on_device) and
+// that pointer is what kernels and copies get.
+constexpr size_t kScratchBytes = (size_t)PK_NOALLOC_WORKSPACE_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kScratchDevices = 64;
+std::atomic<char *> g_scratch_ptr[kScratchDevices];
+
+// address of this device's copy of `scratch` (resolved once per device, with that device current)
+int scratch_on_device(char **out)
+{
+    int dev = 0;
+    PK_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kScratchDevices) return PK_ERR_UNSUPPORTED;
+    char *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        void *sym = nullptr;
+        if (hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)) != hipSuccess || !sym) {
+            (void)hipGetLastError();
+            return PK_ERR_HIP;
+        }
+        p = static_cast<char *>(sym);
+        g_scratch_ptr[dev].store(p, std::memory_order_release); // every thread resolves the same address
+    }
+    *out = p;
+    return PK_OK;
+}
 
 } // namespace
 
@@ -614,8 +646,11 @@ int set_single_agent(const Plan &p, hipStream_t s)
 
 enum Mode { kFull, kCoarseOnly, kForced };
 
+// fixed_ws: a workspace the call must fit into whole (no growth, no allocation, one launch
+// sequence), or null for the handle's own grow-only workspace.
 int search_impl(pk_index *const *hs, int nh, const int64_t *q_offsets, const float *queries, int k, int nprobe,
-                Mode mode, const int32_t *forced, int32_t *out_probes, int64_t *out_ids, float *out_dist, hipStream_t s)
+                Mode mode, const int32_t *forced, int32_t *out_probes, int64_t *out_ids, float *out_dist, hipStream_t s,
+                char *fixed_ws = nullptr, size_t fixed_bytes = 0)
 {
     pk_index *own = hs[0];
     const int64_t nq_all = q_offsets[nh];
@@ -630,12 +665,17 @@ int search_impl(pk_index *const *hs, int nh, const int64_t *q_offsets, const flo
             qlo[a] = (uint32_t)std::min<int64_t>(std::max<int64_t>(q_offsets[a] - q0, 0), nq);
         Plan p;
         PK_TRY(make_plan(p, hs, nh, qlo.data(), nq, k, nprobe, mode != kForced, mode != kCoarseOnly));
-        PK_TRY(ensure_ws(own, p.bytes, s));
-        carve(p, own->ws, own);
+        if (fixed_ws) {
+            if (nq != nq_all || p.bytes > fixed_bytes) return PK_ERR_WORKSPACE;
+            carve(p, fixed_ws, own);
+        } else {
+            PK_TRY(ensure_ws(own, p.bytes, s));
+            carve(p, own->ws, own);
+        }
         MultiArgs m;
         fill_multi(m, hs, nh, qlo.data());
         const float *q = queries + (size_t)q0 * d;
-        const bool timed = mode == kFull && own->prof_on;
+        const bool timed = mode == kFull && own->prof_on && !fixed_ws; // stage timing creates events
         if (timed) PK_TRY(mark(own, s));
         if (mode == kForced) {
             PK_TRY(set_single_agent(p, s));
@@ -961,6 +1001,12 @@ int pk_index_build(const pk_config *cfg, const float *centroids, const float *ve
     if (hipHostMalloc(reinterpret_cast<void **>(&ix->pin_pages), 64, hipHostMallocDefault) != hipSuccess)
         return fail(PK_ERR_HIP);
     if (hipEventCreateWithFlags(&ix->ev, hipEventDisableTiming) != hipSuccess) return fail(PK_ERR_HIP);
+    {
+        // set-up for pk_search_noalloc: resolve this device's copy of its workspace array now, so
+        // that the call itself finds the address ready (a failure here is reported by that call)
+        char *unused = nullptr;
+        (void)scratch_on_device(&unused);
+    }
 
     // header of the first arena
     DevIndex &D = ix->host;
@@ -1105,22 +1151,22 @@ int pk_kmeans(const float *vectors, int64_t n, int32_t d, int32_t nlist, int32_t
     // the assignment step is a top-1 coarse search under L2: an index without vectors carries the centroid table
     pk_config cfg{d, nlist, PK_METRIC_L2, PK_F32, 32, 1};
     const size_t abytes = pk_arena_bytes(&cfg, 0, 0);
-    char *scratch = nullptr;
+    char *kbuf = nullptr;
     const size_t nl4 = round_up((size_t)nlist * 4, 256), n4 = round_up((size_t)n * 4, 256);
     const size_t sums8 = round_up((size_t)nlist * d * 8, 256), sq8 = round_up((size_t)nlist * 8, 256);
     const size_t sbytes = round_up(abytes, 256) + 3 * nl4 + 2 * n4 + round_up((size_t)iters * 8, 256) + sums8 + sq8;
-    if (hipMalloc(reinterpret_cast<void **>(&scratch), sbytes) != hipSuccess) {
+    if (hipMalloc(reinterpret_cast<void **>(&kbuf), sbytes) != hipSuccess) {
         (void)hipGetLastError();
         return PK_ERR_NOMEM;
     }
     pk_index *ix = nullptr;
-    int rc = pk_index_build(&cfg, centroids, nullptr, nullptr, 0, scratch, abytes, stream, &ix);
+    int rc = pk_index_build(&cfg, centroids, nullptr, nullptr, 0, kbuf, abytes, stream, &ix);
     if (rc != PK_OK) {
-        (void)hipFree(scratch);
+        (void)hipFree(kbuf);
         return rc;
     }
     KmeansArgs ka{};
-    char *p = scratch + round_up(abytes, 256);
+    char *p = kbuf + round_up(abytes, 256);
     ka.cnt = reinterpret_cast<uint32_t *>(p);
     ka.start = reinterpret_cast<uint32_t *>(p + nl4);
     ka.fill = reinterpret_cast<uint32_t *>(p + 2 * nl4);
@@ -1165,7 +1211,7 @@ int pk_kmeans(const float *vectors, int64_t n, int32_t d, int32_t nlist, int32_t
     rc = run();
     if (rc != PK_OK) (void)hipStreamSynchronize(s);
     destroy(ix);
-    (void)hipFree(scratch);
+    (void)hipFree(kbuf);
     return rc;
 }
 
@@ -1462,6 +1508,32 @@ int pk_search(pk_index *ix, const float *queries, int64_t nq, int32_t k, int32_t
                        static_cast<hipStream_t>(stream));
 }
 
+int pk_search_noalloc(pk_index *ix, const float *queries, int64_t nq, int32_t k, int32_t nprobe, int64_t *out_ids,
+                      float *out_dist, void *stream)
+{
+    PK_TRY(check_search_args(ix, queries, nq, k, nprobe));
+    if (nq > 0 && (!out_ids || !out_dist)) return PK_ERR_INVALID_ARG;
+    if (nq == 0) return PK_OK;
+    char *ws = nullptr;
+    PK_TRY(scratch_on_device(&ws));
+    pk_index *hs[1] = {ix};
+    const int64_t offs[2] = {0, nq};
+    return search_impl(hs, 1, offs, queries, k, nprobe, kFull, nullptr, nullptr, out_ids, out_dist,
+                       static_cast<hipStream_t>(stream), ws, kScratchBytes);
+}
+
+size_t pk_search_noalloc_bytes(pk_index *ix, int64_t nq, int32_t k, int32_t nprobe)
+{
+    if (!live(ix) || nq < 1 || k < 1 || k > PK_MAX_K || nprobe < 1 || nprobe > ix->cfg.nlist || nprobe > PK_MAX_NPROBE ||
+        nq > 0x7fffffff)
+        return 0;
+    pk_index *hs[1] = {ix};
+    const uint32_t qlo[2] = {0, (uint32_t)nq};
+    Plan p;
+    if (make_plan(p, hs, 1, qlo, nq, k, nprobe, true, true) != PK_OK) return 0;
+    return p.bytes;
+}
+
 int pk_search_multi(pk_index *const *handles, int32_t n_handles, const int64_t *q_offsets, const float *queries,
                     int32_t k, int32_t nprobe, int64_t *out_ids, float *out_dist, void *stream)
 {
@@ -1738,6 +1810,7 @@ const char *pk_strerror(int status)
     case PK_ERR_NOMEM: return "out of arena, workspace or host memory";
     case PK_ERR_HIP: return "HIP runtime error";
     case PK_ERR_UNSUPPORTED: return "request outside the supported limits";
+    case PK_ERR_WORKSPACE: return "the call needs more workspace than the fixed-size one it was given";
     default: return "unknown status";
     }
 }

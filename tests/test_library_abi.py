@@ -53,6 +53,8 @@ def test_host_side_argument_checks_without_gpu(lib):
     cfg = B.pk_config(16, 4, 0, 0, 0, 0)
     assert lib.pk_index_build(C.byref(cfg), null, null, null, 0, null, 0, null, C.byref(out)) == B.PK_ERR_INVALID_ARG
     assert lib.pk_search(null, null, 1, 1, 1, null, null, null) == B.PK_ERR_BAD_HANDLE
+    assert lib.pk_search_noalloc(null, null, 1, 1, 1, null, null, null) == B.PK_ERR_BAD_HANDLE
+    assert lib.pk_search_noalloc_bytes(null, 1, 1, 1) == 0
     assert lib.pk_insert(null, null, null, 1, null, null) == B.PK_ERR_BAD_HANDLE
     assert lib.pk_coarse(null, null, 1, 1, null, null) == B.PK_ERR_BAD_HANDLE
     assert lib.pk_index_free(null) == B.PK_ERR_BAD_HANDLE
