@@ -20,11 +20,18 @@
  * Conventions
  *   - Every pointer is marked HOST or DEVICE.  Device buffers belong to the caller
  *     (including arenas); the library owns only the host-side handle and one
- *     grow-only device workspace per handle that it allocates itself.  The workspace
- *     grows (stream synchronisation, hipFree, hipMalloc) only when a search or insert
- *     needs more than any earlier call on the handle did; a call of a shape seen before
- *     allocates nothing and waits for nothing, so the pk_search* calls may then be
- *     captured into a HIP graph (inserts may not: they advance host-side counters).
+ *     grow-only device workspace per handle that it allocates itself (tens of MB for a
+ *     batch of 1024 queries: its size follows the batch, k and nprobe, not the index).
+ *     The workspace grows (stream synchronisation, hipFree, hipMalloc) only when a call
+ *     needs more than it holds.  pk_workspace_reserve sizes it once for every call
+ *     within stated limits, inserts to come included; after that no search or insert
+ *     within those limits allocates or waits (pk_stats.workspace_grows counts the
+ *     growths).  Searches may then be captured into a HIP graph (inserts may not: they
+ *     advance host-side counters).  A graph holds pointers into the workspace: growth
+ *     invalidates it, so reserve before capturing; a call that would have to grow the
+ *     workspace while its stream is capturing fails with PK_ERR_WORKSPACE instead.
+ *     Inserts between replays are fine as long as they stay within the reserved
+ *     `inserts_ahead` (the graph's tile list bound was taken at capture time).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work
  *     is enqueued on it; outputs are valid once the caller has synchronised the stream.
  *     Calls on one handle must come from one thread and one stream at a time; an
@@ -62,7 +69,7 @@ typedef enum {
     PK_ERR_NOMEM = -4,        /* arena (or host / workspace memory) exhausted          */
     PK_ERR_HIP = -5,          /* a HIP runtime call failed                             */
     PK_ERR_UNSUPPORTED = -6,  /* valid request outside the limits below                */
-    PK_ERR_WORKSPACE = -7     /* the call does not fit the fixed-size workspace it must use */
+    PK_ERR_WORKSPACE = -7     /* the call does not fit the workspace it must use (fixed, or growth under capture) */
 } pk_status;
 
 /* Limits (compile-time). */
@@ -89,6 +96,7 @@ typedef struct {
     int64_t pages_used;      /* pages handed to lists                                  */
     int64_t arena_bytes;     /* sum of arena sizes                                     */
     int64_t workspace_bytes; /* current size of the library-owned search workspace     */
+    int64_t workspace_grows; /* times that workspace was (re)allocated since the build  */
     int64_t max_list_len;    /* longest list                                           */
     int32_t device_error;    /* sticky device-side flag: 0 ok, 1 out of pages, 2 list full, 4 work list overflow */
     int32_t n_arenas;
@@ -238,6 +246,30 @@ int pk_search(pk_index *index, const float *queries, int64_t nq, int32_t k, int3
               float *out_dist, void *stream);
 
 /*
+ * Section 5 (operations must not block the caller).  Sizes the workspace of handles[0], the
+ * handle whose workspace a call uses (the index of a single-handle call, the first handle of
+ * a multi-handle call), so that every later pk_search / pk_search_multi / pk_insert /
+ * pk_insert_multi / pk_coarse / pk_scan_probes over these handles (any subset, handles[0]
+ * first) with at most nq_max queries (or vectors) in total, k <= k_max and nprobe <=
+ * nprobe_max finds it large enough, until inserts_ahead more vectors have been inserted into
+ * any one of the handles: such calls then never allocate and never wait for the device.
+ * The size does not depend on how many candidates the queries meet: a query's emitted
+ * candidates live in a region of a few dozen times k entries, and a query that emits more
+ * (no usable threshold, or a tie group larger than the region) is selected by rescoring its
+ * rows instead, with the same values.
+ *   handles   HOST [n_handles] live handles of equal d, metric, storage, page size
+ *   nq_max    1 .. 32768;  inserts_ahead >= 0
+ * May synchronise `stream` and allocate (once); PK_ERR_NOMEM if the device is out of memory.
+ */
+int pk_workspace_reserve(pk_index *const *handles, int32_t n_handles, int64_t nq_max, int32_t k_max,
+                         int32_t nprobe_max, int64_t inserts_ahead, void *stream);
+
+/* Test seam / tuning: entries of each query's emission region in later searches on this
+ * handle (0 = the default, a few dozen times k; the library never uses fewer than k + 1).
+ * A small value forces queries down the rescoring path. */
+int pk_index_set_emit_cap(pk_index *index, int32_t entries);
+
+/*
  * pk_search for callers that cannot allocate device memory: code under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
  * bit-identical results, but the workspace (prepared queries, centroid scores, probe lists,
@@ -248,8 +280,8 @@ int pk_search(pk_index *index, const float *queries, int64_t nq, int32_t k, int3
  * records no stage timing.
  *   PK_ERR_WORKSPACE  the search needs more than the array holds; nothing is enqueued.
  *                     pk_search_noalloc_bytes(index, nq, k, nprobe) tells the need
- *                     beforehand (0: invalid arguments); it grows with nq, with nprobe
- *                     times the longest lists, and with every vector inserted.
+ *                     beforehand (0: invalid arguments); it grows with nq, k and nprobe
+ *                     and, slowly, with the pages the index holds.
  * All calls on one GPU share that GPU's array, whatever the handle: two such calls that
  * overlap in time on one GPU (different streams or threads) race and give wrong results.
  * Calls in stream order are safe; every call clears what it needs cleared itself.
@@ -345,6 +377,8 @@ typedef struct {
     int32_t launches;
     float coarse_ms, worklist_ms, scan_ms, select_ms; /* sums over the recorded sequences */
     int64_t scanned_rows, candidates, tiles, emitted; /* sums over all sequences          */
+    int64_t overflowed;  /* queries whose emission region overflowed (selected by rescoring) */
+    int64_t max_emitted; /* most candidates a single query emitted                          */
 } pk_profile;
 int pk_profile_begin(pk_index *index, void *stream);
 int pk_profile_end(pk_index *index, pk_profile *out, void *stream);

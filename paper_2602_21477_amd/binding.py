@@ -23,7 +23,7 @@ PK_ERR_INVALID_ARG, PK_ERR_BAD_HANDLE, PK_ERR_DIM_MISMATCH, PK_ERR_NOMEM, PK_ERR
 PK_ERR_WORKSPACE = -7
 PK_NOALLOC_WORKSPACE_BYTES = 64 << 20
 
-EXPORTS = ["pk_search_noalloc", "pk_search_noalloc_bytes", "pk_search_levels", "pk_search_union", "pk_insert_multi", "pk_delete", "pk_index_split", "pk_index_centroids", "pk_list_ids", "pk_arena_bytes", "pk_index_build", "pk_index_add_arena", "pk_index_compact", "pk_kmeans", "pk_insert", "pk_insert_assigned", "pk_search",
+EXPORTS = ["pk_workspace_reserve", "pk_index_set_emit_cap", "pk_search_noalloc", "pk_search_noalloc_bytes", "pk_search_levels", "pk_search_union", "pk_insert_multi", "pk_delete", "pk_index_split", "pk_index_centroids", "pk_list_ids", "pk_arena_bytes", "pk_index_build", "pk_index_add_arena", "pk_index_compact", "pk_kmeans", "pk_insert", "pk_insert_assigned", "pk_search",
            "pk_search_multi", "pk_coarse", "pk_scan_probes", "pk_index_stats", "pk_list_lengths", "pk_profile_begin",
            "pk_profile_end", "pk_index_free", "pk_strerror"]
 
@@ -36,13 +36,15 @@ class pk_config(C.Structure):
 class pk_stats(C.Structure):
     _fields_ = [("n_total", C.c_int64), ("n_inserted", C.c_int64), ("pages_total", C.c_int64),
                 ("pages_used", C.c_int64), ("arena_bytes", C.c_int64), ("workspace_bytes", C.c_int64),
+                ("workspace_grows", C.c_int64),
                 ("max_list_len", C.c_int64), ("device_error", C.c_int32), ("n_arenas", C.c_int32)]
 
 
 class pk_profile(C.Structure):
     _fields_ = [("launches", C.c_int32), ("coarse_ms", C.c_float), ("worklist_ms", C.c_float),
                 ("scan_ms", C.c_float), ("select_ms", C.c_float), ("scanned_rows", C.c_int64),
-                ("candidates", C.c_int64), ("tiles", C.c_int64), ("emitted", C.c_int64)]
+                ("candidates", C.c_int64), ("tiles", C.c_int64), ("emitted", C.c_int64),
+                ("overflowed", C.c_int64), ("max_emitted", C.c_int64)]
 
 
 class PancakeError(RuntimeError):
@@ -76,6 +78,8 @@ def lib():
         L.pk_insert_multi.argtypes = [C.POINTER(vp), i32, C.POINTER(i64), vp, vp, vp, vp]
         L.pk_delete.argtypes = [vp, vp, i64, C.POINTER(i64), vp]
         L.pk_search.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
+        L.pk_workspace_reserve.argtypes = [C.POINTER(vp), i32, i64, i32, i32, i64, vp]
+        L.pk_index_set_emit_cap.argtypes = [vp, i32]
         L.pk_search_noalloc.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
         L.pk_search_noalloc_bytes.restype = C.c_size_t
         L.pk_search_noalloc_bytes.argtypes = [vp, i64, i32, i32]
@@ -199,6 +203,16 @@ def pk_search(handle: int, queries, k: int, nprobe: int, out_ids, out_dist):
     _check(lib().pk_search(handle, _dev(queries, torch.float32, "queries"), queries.shape[0], k, nprobe,
                            _dev(out_ids, torch.int64, "out_ids"), _dev(out_dist, torch.float32, "out_dist"),
                            _stream()), "pk_search")
+
+
+def pk_workspace_reserve(handles, nq_max: int, k_max: int, nprobe_max: int, inserts_ahead: int = 0):
+    hs = (C.c_void_p * len(handles))(*handles)
+    _check(lib().pk_workspace_reserve(hs, len(handles), int(nq_max), int(k_max), int(nprobe_max), int(inserts_ahead),
+                                      _stream()), "pk_workspace_reserve")
+
+
+def pk_index_set_emit_cap(handle: int, entries: int):
+    _check(lib().pk_index_set_emit_cap(handle, int(entries)), "pk_index_set_emit_cap")
 
 
 def pk_search_noalloc(handle: int, queries, k: int, nprobe: int, out_ids, out_dist):
@@ -337,6 +351,9 @@ class Index:
 
     def stats(self):
         return pk_index_stats(self.handle)
+
+    def reserve(self, nq_max, k_max, nprobe_max, inserts_ahead=0):
+        pk_workspace_reserve([self.handle], nq_max, k_max, nprobe_max, inserts_ahead)
 
     def list_lengths(self):
         return pk_list_lengths(self.handle, self.nlist)

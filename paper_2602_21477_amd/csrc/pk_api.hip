@@ -14,7 +14,7 @@ using namespace pk;
 namespace {
 
 constexpr uint64_t kMagic = 0x70616e63616b6531ull;
-constexpr uint64_t kCandLimit = 1ull << 30; // candidate values per launch sequence (4 GiB of fp32)
+constexpr uint64_t kRegionBytes = 256ull << 20; // emission regions of one launch sequence (all queries together)
 constexpr int kBuildChunk = 16384;          // vectors assigned per coarse pass during the build
 
 #define PK_HIP(expr)                                   \
@@ -86,6 +86,8 @@ struct pk_index {
     // library-owned workspace
     char *ws;
     size_t ws_bytes;
+    int64_t ws_grows;       // times the workspace was (re)allocated since the build
+    int32_t emit_cap;       // entries of a query's emission region set by the caller (0: by k)
     // staging of scope-union searches (replicated queries, per-handle results); grow-only
     char *ubuf;
     size_t ubuf_bytes;
@@ -128,9 +130,22 @@ struct Carver {
     }
 };
 
+// true when `s` is being captured into a graph (nothing may wait, free or allocate then)
+bool capturing(hipStream_t s)
+{
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &st) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return st != hipStreamCaptureStatusNone;
+}
+
 int ensure_ws(pk_index *ix, size_t bytes, hipStream_t s)
 {
     if (bytes <= ix->ws_bytes) return PK_OK;
+    // A captured graph would keep pointers into the buffer that is about to be freed.
+    if (capturing(s)) return PK_ERR_WORKSPACE;
     // grow: earlier work on this handle's stream may still use the old buffer
     PK_HIP(hipStreamSynchronize(s));
     if (ix->ws) PK_HIP(hipFree(ix->ws));
@@ -144,6 +159,7 @@ int ensure_ws(pk_index *ix, size_t bytes, hipStream_t s)
     }
     ix->ws = static_cast<char *>(p);
     ix->ws_bytes = want;
+    ix->ws_grows += 1;
     return PK_OK;
 }
 
@@ -154,36 +170,38 @@ uint64_t pages_for(const pk_index *ix, uint64_t t)
     return (t + ix->P - 1) / ix->P + std::min<uint64_t>(t, (uint64_t)ix->cfg.nlist);
 }
 
-uint32_t pages_used_ub(const pk_index *ix)
+uint32_t pages_used_ub(const pk_index *ix, int64_t ahead = 0)
 {
-    const uint64_t ub = (uint64_t)ix->pages_known + pages_for(ix, (uint64_t)(ix->n_inserted - ix->inserted_at_known));
+    const uint64_t ub =
+        (uint64_t)ix->pages_known + pages_for(ix, (uint64_t)(ix->n_inserted - ix->inserted_at_known + ahead));
     return (uint32_t)std::min<uint64_t>(ub, ix->pages_total);
 }
 
-// upper bound of one query's candidate range (padded segments) for `nprobe` lists
-uint64_t wq_ub(const pk_index *ix, int nprobe)
+// upper bound of one query's candidate range (padded segments) for `nprobe` lists, valid until
+// `ahead` more vectors have been inserted
+uint64_t wq_ub(const pk_index *ix, int nprobe, int64_t ahead = 0)
 {
     const int np = std::min(nprobe, ix->cfg.nlist);
-    return round_up(ix->top_len[np] + (uint64_t)(ix->n_inserted - ix->inserted_at_top) + 15ull * np, 16);
+    return round_up(ix->top_len[np] + (uint64_t)(ix->n_inserted - ix->inserted_at_top + ahead) + 15ull * np, 16);
 }
 
 // Everything one launch sequence needs, carved out of the owner's workspace.
 struct Plan {
     int64_t nq;
     int nprobe, k, nh;
-    int mq_f, mq_h, grid_f, grid_h, grid_s, cchunks, nchunks, sel_chunk, K, nlist_max, sp;
+    int mq_f, mq_h, grid_f, grid_h, grid_s, cchunks, K, nlist_max, sp;
     uint32_t hot_from;
     bool hot_rs; // the hot class is scored by the rows-stationary kernel (tiles of kRsRows rows x all slots of a list)
-    uint32_t stride, cand_cap, tile_cap, span;
+    uint32_t stride, ecap, tile_cap, span;
     bool need_coarse, need_fine, f16;
     // buffers
     char *qs32, *qs;
     float *qn32, *qn, *S, *svals, *tlo, *tinv;
-    uint32_t *cand_off, *cand_cnt, *lcnt, *lstart, *lfill, *ltile, *lhtile, *pair_off, *qtot, *qoff, *slot_q,
-        *slot_o, *scalars, *tau, *tcur, *hist, *ccnt, *sslot_q, *sslot_o;
+    uint32_t *cand_off, *cand_cnt, *lcnt, *lstart, *lfill, *ltile, *lhtile, *pair_off, *slot_q, *slot_o, *scalars,
+        *tau, *tcur, *hist, *ccnt, *sslot_q, *sslot_o;
     uint16_t *qagent;
     Tile *tiles, *tiles_hot, *stiles;
-    unsigned long long *cpartial, *partial, *cbuf;
+    unsigned long long *cpartial, *cbuf;
     int32_t *probes;
     size_t bytes;
 };
@@ -218,8 +236,6 @@ void carve(Plan &p, char *base, const pk_index *own)
         p.ltile = c.take<uint32_t>(nl);
         p.lhtile = c.take<uint32_t>(nl);
         p.pair_off = c.take<uint32_t>(nq * (p.nprobe + 1));
-        p.qtot = c.take<uint32_t>(nq);
-        p.qoff = c.take<uint32_t>(nq);
         p.slot_q = c.take<uint32_t>(nq * p.nprobe);
         p.slot_o = c.take<uint32_t>(nq * p.nprobe);
         p.tiles = c.take<Tile>((size_t)p.tile_cap + 1);
@@ -234,8 +250,7 @@ void carve(Plan &p, char *base, const pk_index *own)
         p.sslot_o = c.take<uint32_t>(nq);
         p.stiles = c.take<Tile>(nq * p.sp + 1);
         p.svals = c.take<float>(nq * p.span + 16);
-        p.cbuf = c.take<unsigned long long>((size_t)p.cand_cap + 16);
-        p.partial = c.take<unsigned long long>(nq * p.nchunks * p.K);
+        p.cbuf = c.take<unsigned long long>(nq * p.ecap + 16);
     }
     p.bytes = round_up(c.off, 256);
 }
@@ -287,9 +302,33 @@ int grid_for(const pk_index *ix, int row_bytes, int mq)
     return ix->num_cu * per_cu;
 }
 
+uint32_t pow2_at_least(uint64_t v)
+{
+    uint32_t p = 1;
+    while (p < v && p < (1u << 30)) p <<= 1;
+    return p;
+}
+
+// Entries of one query's emission region.  The gate (sample threshold + running histogram)
+// lets a few times k candidates through, so a few dozen times k with a floor is ample; a query
+// that emits more is selected by rescoring its rows (select_final_kernel), so the size is a
+// matter of speed, not of correctness.  If every candidate a query can have fits, nothing can
+// overflow and the region is just that large.
+uint32_t emit_cap_for(const pk_index *own, int K, uint64_t wmax)
+{
+    uint64_t e = std::min<uint64_t>(std::max<uint64_t>(pow2_at_least(32ull * (uint64_t)K), 2048), 32768);
+    if (own->emit_cap > 0) e = (uint64_t)own->emit_cap;
+    e = std::min<uint64_t>(e, round_up(wmax, 16));
+    return (uint32_t)std::max<uint64_t>(e, round_up((uint64_t)K, 16));
+}
+
 // Fills the plan for handles hs[0..nh) with query segments qlo (relative to this batch).
+// ahead > 0 sizes the buffers for what the same call would need after `ahead` more inserts
+// into every handle; worst also takes the largest value of every size that depends on how the
+// queries spread (tile groups, sample pages), which is how pk_workspace_reserve sizes the
+// workspace for every call within its limits.
 int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t nq, int k, int nprobe,
-              bool need_coarse, bool need_fine)
+              bool need_coarse, bool need_fine, int64_t ahead = 0, bool worst = false)
 {
     const pk_index *own = hs[0];
     std::memset(&p, 0, sizeof(p));
@@ -308,7 +347,7 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
         // re-read from L2 / Infinity Cache, which measured faster than larger groups).
         // If even that tile would leave one workgroup per CU (wide fp32 rows), the
         // sliced-query kernel, whose LDS use does not depend on the row length, takes every
-        // list.  PK_TUNE_KS can force either kernel, or route only lists with more queries
+        // list.  The ks tunable can force either kernel, or route only lists with more queries
         // than one group to the sliced kernel (3).
         double avg = 0;
         for (int a = 0; a < nh; ++a)
@@ -345,50 +384,48 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
     if (p.hot_rs) p.grid_h = own->num_cu; // one workgroup of 8 waves per CU (its LDS holds the rows and every slot)
     p.grid_s = grid_for(own, own->row_bytes, kSampleSlots);
     p.K = k + 1;
-    p.sp = (k + own->P - 1) / own->P; // sample pages: at least k rows of the first probed list
-    uint64_t cand = 0, tiles = 0, wmax = 0;
+    p.sp = (k + own->P - 1) / own->P; // sample pages: at least k rows when the first pages are full
+    uint64_t tiles = 0, wmax = 0;
     int nlist_hi = 0, pad_hi = 0;
+    const int mq_least = worst ? 16 : std::min(p.mq_f, p.mq_h);
+    const bool rs_tiles = worst ? (own->row_bytes <= 1536 && own->P % kRsRows == 0) : p.hot_rs;
     for (int a = 0; a < nh; ++a) {
         const pk_index *ix = hs[a];
-        const uint64_t nqa = qlo[a + 1] - qlo[a];
+        const uint64_t nqa = worst ? (uint64_t)nq : qlo[a + 1] - qlo[a];
         nlist_hi = std::max(nlist_hi, ix->cfg.nlist);
         pad_hi = std::max(pad_hi, ix->nlist_pad);
         if (nqa == 0) continue;
-        const uint64_t w = wq_ub(ix, nprobe);
+        const uint64_t w = wq_ub(ix, nprobe, ahead);
+        if (w > 0xfffffff0ull) return PK_ERR_UNSUPPORTED; // positions inside a query's range are 32-bit
         wmax = std::max(wmax, w);
-        cand += nqa * w;
         const uint64_t pp = w / ix->P + nprobe;
-        tiles += std::min<uint64_t>(pages_used_ub(ix), nqa * pp) + nqa * pp / std::min(p.mq_f, p.mq_h) + 1;
+        const uint64_t pages = std::min<uint64_t>(pages_used_ub(ix, ahead), nqa * pp);
+        tiles += pages + nqa * pp / mq_least + 1;
         // tiles of the rows-stationary kernel are parts of a page: P / kRsRows times the pages
-        if (p.hot_rs) tiles += (uint64_t)(ix->P / kRsRows - 1) * std::min<uint64_t>(pages_used_ub(ix), nqa * pp);
+        if (rs_tiles) tiles += (uint64_t)(ix->P / kRsRows - 1) * pages;
     }
-    if (cand > 0xfffffff0ull || tiles > 0xfffffff0ull) return PK_ERR_UNSUPPORTED;
+    if (tiles > 0xfffffff0ull) return PK_ERR_UNSUPPORTED;
     {
         // Sample pages per query.  A larger sample gives a tighter threshold and a finer bucket
         // scale, hence fewer emitted candidates; it costs one tile per query and page.  Wanted:
         // the k-th best of the sample at most its 30 % quantile (large k); and, for batches of
         // few queries, whose emitted candidates all meet at a handful of counters and
         // serialise there, a sample of 0.5 % of the most rows a query can meet (long lists).
-        // Spent: at most 3 % of the scan's tiles, and 16 pages.
+        // Spent: at most 3 % of the scan's tiles, and sp_max pages.
         const uint64_t afford = tiles * 3u / 100u / (uint64_t)std::max<int64_t>(nq, 1);
         const uint64_t by_quantile = ((uint64_t)p.K * 10 + 3 * own->P - 1) / (3 * own->P);
         const uint64_t by_size = nq <= 64 ? (wmax / 200 + own->P - 1) / own->P : 0;
         uint64_t more = std::min(afford, std::max(by_quantile, by_size));
         more = std::min<uint64_t>(more, (uint64_t)tunables().sp_max);
+        if (worst) more = (uint64_t)tunables().sp_max;
         p.sp = std::max(p.sp, (int)more);
     }
     p.span = (uint32_t)(p.sp * own->P);
     p.nlist_max = nlist_hi;
     p.stride = (uint32_t)pad_hi;
     p.cchunks = (nlist_hi + kSelChunk - 1) / kSelChunk;
-    p.cand_cap = (uint32_t)cand;
+    p.ecap = emit_cap_for(own, p.K, wmax);
     p.tile_cap = (uint32_t)tiles;
-    // Emitted candidates are selected per (query, chunk): a batch of few queries is cut into small
-    // chunks so that enough workgroups share the work, within 16 M partial entries.
-    p.sel_chunk = nq >= 128 ? kSelChunk : 1024;
-    while (p.sel_chunk < kSelChunk && (uint64_t)nq * ((wmax + p.sel_chunk - 1) / p.sel_chunk) * (uint64_t)p.K > (16ull << 20))
-        p.sel_chunk *= 2;
-    p.nchunks = (int)std::max<uint64_t>(1, (wmax + p.sel_chunk - 1) / p.sel_chunk);
     carve(p, nullptr, own);
     return PK_OK;
 }
@@ -532,15 +569,12 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
     w.ltile = p.ltile;
     w.lhtile = p.lhtile;
     w.pair_off = p.pair_off;
-    w.qtot = p.qtot;
-    w.qoff = p.qoff;
     w.ccnt = p.ccnt;
     w.slot_query = p.slot_q;
     w.slot_out = p.slot_o;
     w.tiles = p.tiles;
     w.tiles_hot = p.tiles_hot;
     w.tile_cap = p.tile_cap;
-    w.cand_cap = p.cand_cap;
     w.scalars = p.scalars + 4;
     w.scalars_hot = p.scalars + 12;
     w.lcnt_cleared = p.need_coarse;
@@ -581,7 +615,7 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
     sa.use_hist = tunables().hist;
     sa.hist = p.hist;
     sa.k = p.k;
-    sa.qoff = p.qoff;
+    sa.ecap = p.ecap;
     sa.ccnt = p.ccnt;
     sa.cbuf = p.cbuf;
     sa.row_bytes = own->row_bytes;
@@ -603,32 +637,22 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
         }
     }
     if (timed) PK_TRY(mark(own, s));
-    SelectArgs se{};
-    se.vals = nullptr;
-    se.keys = p.cbuf;
-    se.qoff = p.qoff;
-    se.qcnt = p.ccnt;
-    se.metric = own->cfg.metric;
-    se.K = p.K;
-    se.nchunks = p.nchunks;
-    se.chunk = p.sel_chunk;
-    se.partial = p.partial;
-    // no query can have more candidates than one chunk: the final kernel selects straight from the regions
-    if (p.nchunks > 1) PK_HIP(launch_select_partial(se, p.nq, s));
     FinalArgs f{};
-    f.partial = p.partial;
-    f.nchunks = p.nchunks;
-    f.chunk = p.sel_chunk;
     f.K = p.K;
     f.k = p.k;
     f.nprobe = p.nprobe;
     f.metric = own->cfg.metric;
+    f.storage = own->cfg.storage;
+    f.row_bytes = own->row_bytes;
     f.keys = p.cbuf;
-    f.qoff = p.qoff;
+    f.spill = p.cbuf;
+    f.ecap = p.ecap;
     f.qcnt = p.ccnt;
     f.pair_off = p.pair_off;
     f.probes = p.probes;
     f.qagent = p.qagent;
+    f.qs = p.qs;
+    f.qnorm = p.qn;
     f.out_ids = out_ids;
     f.out_dist = out_dist;
     PK_HIP(launch_select_final(f, m, p.nq, s));
@@ -655,9 +679,11 @@ int search_impl(pk_index *const *hs, int nh, const int64_t *q_offsets, const flo
     pk_index *own = hs[0];
     const int64_t nq_all = q_offsets[nh];
     const int d = own->cfg.d;
+    // queries per launch sequence: the emission regions of one sequence stay within kRegionBytes
     uint64_t wmax = 1;
     for (int a = 0; a < nh; ++a) wmax = std::max(wmax, wq_ub(hs[a], nprobe));
-    const int64_t step = std::max<int64_t>(1, std::min<int64_t>(32768, (int64_t)(kCandLimit / wmax)));
+    const uint64_t per_query = (uint64_t)emit_cap_for(own, k + 1, wmax) * sizeof(unsigned long long);
+    const int64_t step = std::max<int64_t>(1, std::min<int64_t>(32768, (int64_t)(kRegionBytes / per_query)));
     std::vector<uint32_t> qlo(nh + 1);
     for (int64_t q0 = 0; q0 < nq_all; q0 += step) {
         const int64_t nq = std::min(step, nq_all - q0);
@@ -1085,6 +1111,11 @@ int pk_index_build(const pk_config *cfg, const float *centroids, const float *ve
         ix->pages_known = used32;
     }
     if (hipStreamSynchronize(s) != hipSuccess) return fail(PK_ERR_HIP);
+    // the build's own scratch (score matrices of 16 384-vector chunks) is not what searches need
+    if (ix->ws) (void)hipFree(ix->ws);
+    ix->ws = nullptr;
+    ix->ws_bytes = 0;
+    ix->ws_grows = 0;
     ix->n_total = n;
     ix->next_id = n;
     ix->n_inserted = 0;
@@ -1534,6 +1565,40 @@ size_t pk_search_noalloc_bytes(pk_index *ix, int64_t nq, int32_t k, int32_t npro
     return p.bytes;
 }
 
+int pk_workspace_reserve(pk_index *const *handles, int32_t n_handles, int64_t nq_max, int32_t k_max, int32_t nprobe_max,
+                         int64_t inserts_ahead, void *stream)
+{
+    if (!handles || n_handles < 1 || n_handles > PK_MAX_HANDLES) return PK_ERR_INVALID_ARG;
+    for (int a = 0; a < n_handles; ++a) {
+        if (!live(handles[a])) return PK_ERR_BAD_HANDLE;
+        const pk_config &c0 = handles[0]->cfg, &c = handles[a]->cfg;
+        if (c.d != c0.d || c.metric != c0.metric || c.storage != c0.storage || c.page_vecs != c0.page_vecs)
+            return PK_ERR_DIM_MISMATCH;
+    }
+    if (nq_max < 1 || nq_max > 32768 || k_max < 1 || k_max > PK_MAX_K || nprobe_max < 1 || nprobe_max > PK_MAX_NPROBE ||
+        inserts_ahead < 0)
+        return PK_ERR_INVALID_ARG;
+    // sized as if every handle received all nq_max queries: every size is monotone in a handle's
+    // share of the batch, so this covers any split
+    std::vector<uint32_t> qlo((size_t)n_handles + 1);
+    for (int b = 0; b <= n_handles; ++b) qlo[(size_t)b] = (uint32_t)((nq_max * b) / n_handles);
+    int np = nprobe_max;
+    for (int a = 0; a < n_handles; ++a) np = std::min(np, handles[a]->cfg.nlist);
+    Plan p;
+    PK_TRY(make_plan(p, handles, n_handles, qlo.data(), nq_max, k_max, np, true, true, inserts_ahead, true));
+    size_t need = p.bytes;
+    need += round_up((size_t)nq_max * 4, 256) + 256; // slot array of an insert batch
+    return ensure_ws(handles[0], need, static_cast<hipStream_t>(stream));
+}
+
+int pk_index_set_emit_cap(pk_index *ix, int32_t entries)
+{
+    if (!live(ix)) return PK_ERR_BAD_HANDLE;
+    if (entries < 0 || entries > (1 << 20)) return PK_ERR_INVALID_ARG;
+    ix->emit_cap = entries;
+    return PK_OK;
+}
+
 int pk_search_multi(pk_index *const *handles, int32_t n_handles, const int64_t *q_offsets, const float *queries,
                     int32_t k, int32_t nprobe, int64_t *out_ids, float *out_dist, void *stream)
 {
@@ -1736,6 +1801,7 @@ int pk_index_stats(pk_index *ix, pk_stats *out, void *stream)
     out->pages_used = ctr[0];
     out->arena_bytes = (int64_t)ix->arena_bytes;
     out->workspace_bytes = (int64_t)ix->ws_bytes;
+    out->workspace_grows = ix->ws_grows;
     out->max_list_len = len.empty() ? 0 : *std::max_element(len.begin(), len.end());
     out->device_error = (int32_t)ctr[1];
     out->n_arenas = ix->host.n_arenas;
@@ -1770,7 +1836,7 @@ int pk_profile_end(pk_index *ix, pk_profile *out, void *stream)
     if (!out) return PK_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     ix->prof_on = false;
-    unsigned long long st[4] = {0, 0, 0, 0};
+    unsigned long long st[6] = {0, 0, 0, 0, 0, 0};
     PK_HIP(hipMemcpyAsync(st, ix->host.stats, sizeof(st), hipMemcpyDeviceToHost, s));
     PK_HIP(hipStreamSynchronize(s));
     std::memset(out, 0, sizeof(*out));
@@ -1789,6 +1855,8 @@ int pk_profile_end(pk_index *ix, pk_profile *out, void *stream)
     out->candidates = (int64_t)st[1];
     out->tiles = (int64_t)st[2];
     out->emitted = (int64_t)st[3];
+    out->overflowed = (int64_t)st[4];
+    out->max_emitted = (int64_t)st[5];
     ix->prof_used = 0;
     return PK_OK;
 }

@@ -44,7 +44,8 @@ struct DevIndex {
     uint32_t *main_pages;// [nlist] pages in that extent
     uint32_t *dtab;      // [nlist][max_dp] delta page numbers
     uint32_t *ctr;       // [0] next free page, [1] sticky error flags, [2] pages total
-    unsigned long long *stats; // running sums: [0] rows of distinct probed lists, [1] candidates, [2] tiles, [3] emitted
+    unsigned long long *stats; // running sums: [0] rows of distinct probed lists, [1] candidates, [2] tiles, [3] emitted,
+                               // [4] queries whose emission region overflowed; [5] most candidates one query emitted
     int32_t nlist, nlist_pad, d, dpad32, P, max_dp, metric, storage;
     int32_t row_bytes;   // padded bytes of one stored row
     int32_t n_arenas;
@@ -96,6 +97,43 @@ __device__ __forceinline__ uint32_t bucket_of(float v, float lo, float inv, int 
     const float t = fminf(off * inv, (float)(kHistBins - 1));
     return (uint32_t)t;
 }
+
+// ---- MFMA operand helpers shared by the scan kernels and the exact per-query rescoring
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Pointers taken out of a tile descriptor are generic pointers to the compiler, and loads
+// through them would be flat loads: those count on the LDS counter as well, so a wait for
+// an LDS read would also wait for the rows being prefetched.  These types say "global".
+typedef const char __attribute__((address_space(1))) *gbytes;
+typedef const float __attribute__((address_space(1))) *gfloats;
+typedef const u32x4 __attribute__((address_space(1))) *gvec4;
+__device__ __forceinline__ gbytes in_global(const char *p) { return (gbytes)p; }
+__device__ __forceinline__ gfloats in_global(const float *p) { return (gfloats)p; }
+
+// 16 bytes of a query row (A) against 16 bytes of a stored row (B), fp32 accumulation: one
+// v_mfma_f32_16x16x32_f16, or four v_mfma_f32_16x16x4_f32.  Every kernel that scores a
+// (row, query) pair issues these in the same order over the row, so the value of a pair does
+// not depend on the kernel that computed it.
+template <int STORAGE>
+__device__ __forceinline__ void mfma_step(f32x4 &acc, const u32x4 &qa, const u32x4 &xb)
+{
+    if constexpr (STORAGE == PK_F16) {
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, qa), __builtin_bit_cast(half8, xb),
+                                                     acc, 0, 0, 0);
+    } else {
+        f32x4 qf = __builtin_bit_cast(f32x4, qa), xf = __builtin_bit_cast(f32x4, xb);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(qf[0], xf[0], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(qf[1], xf[1], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(qf[2], xf[2], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(qf[3], xf[3], acc, 0, 0, 0);
+    }
+}
+
+// squared L2 distance from the inner product and the two squared norms (one expression, used
+// by every kernel that returns a fine-search value)
+__device__ __forceinline__ float l2_from_dot(float xn, float dot, float qn) { return fmaxf(xn - 2.f * dot + qn, 0.f); }
 
 // exclusive scan of in[0,n) into out[0,n) by one workgroup (up to 1024 threads); returns the
 // total.  A thread takes 4 consecutive elements, so 4096 elements need one round of barriers;
@@ -184,8 +222,9 @@ struct ScanArgs {
     const float *tinv;           // [nq] bucket scale (see bucket_of)
     uint32_t *hist;              // [nq][kHistBins] emitted candidates per bucket (zero before the launch)
     uint32_t *tcur;              // [nq] running bucket limit shared by all workgroups (starts at kHistBins-1)
-    const uint32_t *qoff;        // [nq] first element of each query's region
-    uint32_t *ccnt;              // [nq] emitted so far (zero before the launch)
+    uint32_t ecap;               // entries of each query's region of cbuf: query q owns [q * ecap, (q + 1) * ecap)
+    uint32_t *ccnt;              // [nq] candidates that passed the gate so far (zero before the launch); those past
+                                 // ecap are counted but not stored, and the query is then selected by rescoring
     unsigned long long *cbuf;
     uint32_t *tile_ctr;          // device scalar, zero before the launch: batches handed out after the first round
     int k, use_hist;
@@ -216,13 +255,16 @@ hipError_t launch_select_probes(const unsigned long long *partial, int nchunks, 
                                 int32_t *probes, hipStream_t s);
 
 struct FinalArgs {
-    const unsigned long long *partial; // [nq][nchunks][K]
-    int nchunks, chunk, K, k, nprobe, metric; // chunk: as in SelectArgs (a query with at most that many keys skips the partial step)
-    const unsigned long long *keys;   // emitted candidates of all queries
-    const uint32_t *qoff, *qcnt;      // candidate ranges inside keys
-    const uint32_t *pair_off;         // [nq][nprobe+1] start of each probe's segment inside the range
+    int K, k, nprobe, metric, storage, row_bytes;
+    const unsigned long long *keys;   // emitted candidates: query q owns [q * ecap, (q + 1) * ecap)
+    unsigned long long *spill;        // the same regions, writable: scratch of a query that is rescored
+    uint32_t ecap;
+    const uint32_t *qcnt;             // [nq] candidates that passed the gate (more than ecap: region overflowed)
+    const uint32_t *pair_off;         // [nq][nprobe+1] start of each probe's segment inside the query's range
     const int32_t *probes;            // [nq][nprobe]
     const uint16_t *qagent;           // [nq] handle number
+    const char *qs;                   // prepared queries [nq][row_bytes] (storage type), for the rescoring
+    const float *qnorm;               // [nq]
     int64_t *out_ids;
     float *out_dist;
 };
@@ -294,12 +336,11 @@ struct WorklistArgs {
     uint32_t *lcnt, *lstart, *lfill, *ltile, *lhtile; // [n_handles * nlist_max]
     bool lcnt_cleared;         // the coarse step of the same search has zeroed lcnt already
     uint32_t *pair_off;        // [nq][nprobe+1]
-    uint32_t *qtot, *qoff;     // [nq]
     uint32_t *ccnt;            // [nq] zeroed here (emission counters of the gated scan)
-    uint32_t *slot_query, *slot_out; // [nq * nprobe]
+    uint32_t *slot_query, *slot_out; // [nq * nprobe]; slot_out = first position of the pair inside the query's range
     Tile *tiles, *tiles_hot;
-    uint32_t tile_cap, cand_cap;
-    uint32_t *scalars;         // [0] ntiles [1] tile counter [2] grab size [3] total candidates
+    uint32_t tile_cap;
+    uint32_t *scalars;         // [0] ntiles [1] tile counter [2] grab size
     uint32_t *scalars_hot;     // [0] hot tiles [1] tile counter [2] grab size
 };
 

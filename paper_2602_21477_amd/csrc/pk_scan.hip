@@ -30,37 +30,9 @@
 
 namespace pk {
 
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-// Pointers taken out of a tile descriptor are generic pointers to the compiler, and loads
-// through them would be flat loads: those count on the LDS counter as well, so a wait for
-// an LDS read would also wait for the rows being prefetched.  These types say "global".
-typedef const char __attribute__((address_space(1))) *gbytes;
-typedef const float __attribute__((address_space(1))) *gfloats;
-typedef const u32x4 __attribute__((address_space(1))) *gvec4;
-__device__ __forceinline__ gbytes in_global(const char *p) { return (gbytes)p; }
-__device__ __forceinline__ gfloats in_global(const float *p) { return (gfloats)p; }
-
 // per-slot LDS arrays of the scan kernels: out, qn, thr, q, base, lo, inv, bmax
 constexpr int kScanSlotWords = 8;
 constexpr int kKsStride = kIterBytes + kQPadBytes; // LDS bytes per slot and staged slice
-
-template <int STORAGE>
-__device__ __forceinline__ void mfma_step(f32x4 &acc, const u32x4 &qa, const u32x4 &xb)
-{
-    if constexpr (STORAGE == PK_F16) {
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, qa), __builtin_bit_cast(half8, xb),
-                                                     acc, 0, 0, 0);
-    } else {
-        f32x4 qf = __builtin_bit_cast(f32x4, qa), xf = __builtin_bit_cast(f32x4, xb);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(qf[0], xf[0], acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(qf[1], xf[1], acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(qf[2], xf[2], acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(qf[3], xf[3], acc, 0, 0, 0);
-    }
-}
 
 // What a workgroup knows about the query slots of the group it is scoring (all in LDS).
 struct Slots {
@@ -144,8 +116,8 @@ __device__ __forceinline__ void load_slots(const ScanArgs &a, const Slots &s, in
                 const uint32_t seen = atomicMin(a.tcur + q, bmax);
                 bmax = seen < bmax ? seen : bmax;
             }
-            const uint32_t base = on ? a.qoff[q] : 0u;
-            s.out[m] = on ? a.slot_out[qbeg + m] - base : 0u; // position inside the query's candidate range
+            const uint32_t base = on ? q * a.ecap : 0u;
+            s.out[m] = on ? a.slot_out[qbeg + m] : 0u; // position of the pair inside the query's candidate range
             s.qn[m] = on ? a.qnorm[q] : 0.f;
             s.q[m] = q;
             s.base[m] = base;
@@ -186,8 +158,9 @@ __device__ __forceinline__ void emit_survivors(const ScanArgs &a, const Slots &s
         if (ln == leader) base = atomicAdd(&a.ccnt[s.q[m]], (uint32_t)__popc(gmask));
         base = __shfl(base, lg * 16 + leader);
         if (pass) {
-            const uint32_t rank = __popc(gmask & ((1u << ln) - 1u));
-            a.cbuf[(size_t)s.base[m] + base + rank] = ((unsigned long long)bits << 32) | (s.out[m] + position);
+            // a region that is full keeps counting (the selection then rescores the query) but stores nothing
+            const uint32_t at = base + __popc(gmask & ((1u << ln) - 1u));
+            if (at < a.ecap) a.cbuf[(size_t)s.base[m] + at] = ((unsigned long long)bits << 32) | (s.out[m] + position);
         }
         if (a.use_hist) {
             // count the emitted candidates per bucket; one atomic for the group
@@ -226,7 +199,7 @@ __device__ __forceinline__ void finish_block(const ScanArgs &a, const Slots &s, 
             for (int i = 0; i < 4; ++i) {
                 const int m = mt * 16 + lg * 4 + i;
                 float v = acc[mt][nt][i];
-                if (a.metric == PK_METRIC_L2) v = fmaxf(xn - 2.f * v + s.qn[m & (MQ - 1)], 0.f);
+                if (a.metric == PK_METRIC_L2) v = l2_from_dot(xn, v, s.qn[m & (MQ - 1)]);
                 if constexpr (!GATED) {
                     if ((uint32_t)m < qcnt && row < nrows_pad) a.out[(size_t)s.out[m] + row0 + row] = live ? v : worst;
                 } else {
@@ -649,8 +622,8 @@ __global__ __launch_bounds__(512) void scan_rs_kernel(ScanArgs a)
         if (qbeg != cur_qbeg || qcnt != cur_qcnt) {
             for (uint32_t m = tid; m < qcnt; m += 512) {
                 const uint32_t q = a.slot_query[qbeg + m];
-                const uint32_t base = a.qoff[q];
-                s.out[m] = a.slot_out[qbeg + m] - base; // position inside the query's candidate range
+                const uint32_t base = q * a.ecap;
+                s.out[m] = a.slot_out[qbeg + m]; // position of the pair inside the query's candidate range
                 s.qn[m] = a.qnorm[q];
                 s.q[m] = q;
                 s.base[m] = base;
@@ -764,7 +737,7 @@ __global__ __launch_bounds__(512) void scan_rs_kernel(ScanArgs a)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         float v = acc[nt >> 1][mt][nt & 1][i];
-                        if (a.metric == PK_METRIC_L2) v = fmaxf(xn - 2.f * v + qn_r[mt][i], 0.f);
+                        if (a.metric == PK_METRIC_L2) v = l2_from_dot(xn, v, qn_r[mt][i]);
                         const uint32_t bits = order_bits(v, a.metric);
                         const bool pass = live && (uint32_t)(mt * 16 + lg * 4 + i) < gq && bits <= thr_r[mt][i];
                         if (__ballot(pass) == 0ull) continue;

@@ -14,7 +14,6 @@
 namespace pk {
 
 typedef unsigned long long u64;
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ uint32_t next_pow2(uint32_t n)
 {
@@ -300,6 +299,76 @@ static uint32_t final_cap(int K)
     return c;
 }
 
+// Exact pass over every row the query probes, for a query whose emission region overflowed
+// (more candidates passed the gate than the region holds: no usable threshold, or a tie group
+// larger than the region).  One workgroup walks the probed lists page by page; each wave
+// scores 32 rows against the one query with the MFMA sequence of the scan kernels (the query
+// in MFMA row 0, zeros in the other rows), so the values are bit-identical to the scan's.
+//   by_id false: every value goes to the selector as (value key, position)  -> best K
+//   by_id true:  the ids of the rows whose value key equals `tau` go to the selector
+//                (lowest ids of a tie group; several rows may carry one id)
+// s_q: LDS, the query row then a row of zeros, qstride bytes apart.
+template <int STORAGE>
+__device__ void rescore_query(const FinalArgs &a, const MultiArgs &h, uint32_t q, const char *s_q, int qstride,
+                              Selector &sel, bool by_id, uint32_t tau)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int ln = lane & 15, lg = lane >> 4;
+    const DevIndex &ix = *h.ix[a.qagent[q]];
+    const int row_bytes = a.row_bytes, nit = row_bytes / kIterBytes;
+    const uint32_t P = (uint32_t)ix.P;
+    const float qn = a.qnorm[q];
+    const uint32_t *po = a.pair_off + (size_t)q * (a.nprobe + 1);
+    const char *qbase = s_q + (size_t)(ln == 0 ? 0 : 1) * qstride + lg * 16;
+    for (int r = 0; r < a.nprobe; ++r) {
+        const uint32_t l = (uint32_t)a.probes[(size_t)q * a.nprobe + r];
+        if (l >= (uint32_t)ix.nlist) continue;
+        const uint32_t len = ix.list_len[l];
+        for (uint32_t lp = 0; lp * P < len; ++lp) {
+            const uint32_t pg = phys_page(ix, l, lp);
+            const Arena &ar = arena_of(ix, pg);
+            const size_t local = (size_t)(pg - ar.first_page) * P;
+            const gbytes px = in_global(ar.vec + local * (size_t)row_bytes);
+            const uint32_t nrows = len - lp * P < P ? len - lp * P : P;
+            for (uint32_t rb0 = 0; rb0 < nrows; rb0 += 4 * kRowBlock) {
+                sel.reserve(4 * kRowBlock);
+                const uint32_t rb = rb0 + (uint32_t)wave * kRowBlock;
+                if (rb >= nrows) continue; // the next reserve() is a barrier every wave reaches
+                // rows rb .. rb + 31 lie inside the page (its size is a multiple of 32); those past
+                // nrows hold stale bytes and their values are not used
+                const gbytes p0 = px + (size_t)(rb + ln) * row_bytes + lg * 16;
+                const gbytes p1 = p0 + (size_t)16 * row_bytes;
+                f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+                for (int it = 0; it < nit; ++it) {
+#pragma unroll
+                    for (int s4 = 0; s4 < 4; ++s4) {
+                        const u32x4 qa = *reinterpret_cast<const u32x4 *>(qbase + (size_t)it * kIterBytes + s4 * 64);
+                        const u32x4 x0 = *reinterpret_cast<gvec4>(p0 + (size_t)it * kIterBytes + s4 * 64);
+                        const u32x4 x1 = *reinterpret_cast<gvec4>(p1 + (size_t)it * kIterBytes + s4 * 64);
+                        mfma_step<STORAGE>(acc0, qa, x0);
+                        mfma_step<STORAGE>(acc1, qa, x1);
+                    }
+                }
+                if (lg == 0) { // accumulator element 0 of lanes 0..15: MFMA row 0 (the query) x column ln (the row)
+#pragma unroll
+                    for (int nt = 0; nt < 2; ++nt) {
+                        const uint32_t row = rb + (uint32_t)nt * 16u + (uint32_t)ln;
+                        if (row >= nrows) continue;
+                        float v = nt == 0 ? acc0[0] : acc1[0];
+                        if (a.metric == PK_METRIC_L2) v = l2_from_dot(ar.norm[local + row], v, qn);
+                        const uint32_t bits = order_bits(v, a.metric);
+                        if (!by_id) {
+                            sel.push(((u64)bits << 32) | (po[r] + lp * P + row));
+                        } else if (bits == tau) {
+                            sel.push((u64)ar.ids[local + row] ^ 0x8000000000000000ull); // order of signed ids
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
 __global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, MultiArgs h, uint32_t cap)
 {
     // LDS sized by K, not by the largest K the library takes: small k leaves room for every
@@ -307,6 +376,7 @@ __global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, 
     extern __shared__ __align__(16) unsigned char s_dyn[];
     u64 *keys = reinterpret_cast<u64 *>(s_dyn);                  // [cap]
     int64_t *s_id = reinterpret_cast<int64_t *>(keys + cap);     // [k]
+    char *s_q = reinterpret_cast<char *>(s_id + ((a.k + 1) & ~1)); // [2][row_bytes + kQPadBytes], used when rescoring
     __shared__ uint32_t s_cnt;
     __shared__ long long s_red[kSelThreads / 64];
     __shared__ uint32_t s_redpos[kSelThreads / 64];
@@ -314,18 +384,25 @@ __global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, 
     __shared__ uint32_t s_pickpos;
     const uint32_t q = blockIdx.x;
     const int k = a.k;
+    const int qstride = a.row_bytes + kQPadBytes;
     Selector sel;
     sel.init(keys, &s_cnt, a.K, cap);
     const uint32_t cnt_q = a.qcnt[q];
-    if (threadIdx.x == 0) atomicAdd(&h.ix[0]->stats[3], (unsigned long long)cnt_q);
-    uint32_t n;
-    if (cnt_q <= (uint32_t)a.chunk) {
-        // few emitted candidates: select straight from the query's region
-        const u64 *v = a.keys + a.qoff[q];
+    const bool overflow = cnt_q > a.ecap; // the region lost candidates: select by rescoring the query's rows
+    if (threadIdx.x == 0) {
+        atomicAdd(&h.ix[0]->stats[3], (unsigned long long)cnt_q);
+        if (overflow) atomicAdd(&h.ix[0]->stats[4], 1ull);
+        atomicMax(&h.ix[0]->stats[5], (unsigned long long)cnt_q);
+    }
+    const size_t region = (size_t)q * a.ecap;
+    if (!overflow) {
+        const u64 *v = a.keys + region;
         // short ranges go one key per thread and round, so the buffer that gets sorted stays small
         const uint32_t per = cnt_q <= 8192u ? 1u : (uint32_t)kSelVec;
         const uint32_t round = kSelThreads * per;
-        for (uint32_t r = cnt_q; r > 0;) { // latest (best) keys first, see select_partial_kernel
+        // keys were emitted under a gate that tightened over time, so the latest are the best:
+        // reading the region backwards sets a tight selection threshold at once
+        for (uint32_t r = cnt_q; r > 0;) {
             const uint32_t lo = r > round ? r - round : 0u;
             sel.reserve(round);
             const uint32_t p = lo + threadIdx.x * per;
@@ -333,12 +410,19 @@ __global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, 
                 if (p + j < r) sel.push(v[p + j]);
             r = lo;
         }
-        sel.flush();
-        n = s_cnt;
     } else {
-        const int used = (int)((cnt_q + (uint32_t)a.chunk - 1) / (uint32_t)a.chunk);
-        n = merge_partials(sel, a.partial + (size_t)q * a.nchunks * a.K, used, a.K);
+        // the query row (its padding zeroed), then a row of zeros
+        for (int i = threadIdx.x; i < 2 * qstride / 16; i += blockDim.x) {
+            u32x4 w = {0u, 0u, 0u, 0u};
+            if (i < a.row_bytes / 16) w = *reinterpret_cast<const u32x4 *>(a.qs + (size_t)q * a.row_bytes + (size_t)i * 16);
+            *reinterpret_cast<u32x4 *>(s_q + (size_t)i * 16) = w;
+        }
+        __syncthreads();
+        if (a.storage == PK_F16) rescore_query<PK_F16>(a, h, q, s_q, qstride, sel, false, 0u);
+        else rescore_query<PK_F32>(a, h, q, s_q, qstride, sel, false, 0u);
     }
+    sel.flush();
+    const uint32_t n = s_cnt;
 
     // entries carrying the padding value are not candidates
     const uint32_t worst = kWorstBits;
@@ -353,12 +437,31 @@ __global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, 
 
     // Equal values must come in ascending id order.  If the tie group of the k-th value
     // reaches past position k, its members inside the top k are the lowest ids of the
-    // whole group, which may include candidates no partial list kept: rescan for them.
+    // whole group, which may include candidates the selection above did not keep: look again.
     if (n_valid > (uint32_t)k && (uint32_t)(keys[k - 1] >> 32) == (uint32_t)(keys[k] >> 32)) {
         const uint32_t tau = (uint32_t)(keys[k - 1] >> 32);
         uint32_t nb = 0;
         while (nb < (uint32_t)k && (uint32_t)(keys[nb] >> 32) < tau) ++nb;
-        const uint32_t base = a.qoff[q], total = a.qcnt[q];
+        if (overflow) {
+            // the kept keys better than the tie value wait in the query's (unusable) region while
+            // the selector collects the lowest ids of the tie group
+            u64 *spill = a.spill + region;
+            __syncthreads();
+            for (uint32_t i = threadIdx.x; i < nb; i += blockDim.x) spill[i] = keys[i];
+            __syncthreads();
+            sel.init(keys, &s_cnt, (int)((uint32_t)k - nb), cap);
+            if (a.storage == PK_F16) rescore_query<PK_F16>(a, h, q, s_q, qstride, sel, true, tau);
+            else rescore_query<PK_F32>(a, h, q, s_q, qstride, sel, true, tau);
+            sel.flush();
+            for (uint32_t t = nb + threadIdx.x; t < (uint32_t)k; t += blockDim.x)
+                s_id[t] = (int64_t)(keys[t - nb] ^ 0x8000000000000000ull);
+            __syncthreads();
+            for (uint32_t t = threadIdx.x; t < (uint32_t)k; t += blockDim.x)
+                keys[t] = t < nb ? spill[t] : (((u64)tau << 32) | t); // the low word is no longer used
+            __syncthreads();
+        } else {
+        const uint32_t total = cnt_q;
+        const u64 *rk = a.keys + region;
         // Members are taken in (id, position) order: several rows may carry one id, and each
         // of them is a candidate of its own.
         long long last_id = 0;
@@ -368,7 +471,7 @@ __global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, 
             long long best = INT64_MAX;
             uint32_t best_pos = 0xffffffffu;
             for (uint32_t p = threadIdx.x; p < total; p += blockDim.x) {
-                const u64 key = a.keys[base + p];
+                const u64 key = rk[p];
                 if ((uint32_t)(key >> 32) == tau) {
                     const uint32_t pos = (uint32_t)key;
                     const long long id = resolve_id(a, h, q, pos);
@@ -410,6 +513,7 @@ __global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, 
             last_pos = s_pickpos;
             have_last = true;
             __syncthreads();
+        }
         }
     }
 
@@ -499,8 +603,11 @@ hipError_t launch_select_probes(const unsigned long long *partial, int nchunks, 
 hipError_t launch_select_final(const FinalArgs &a, const MultiArgs &h, int64_t nq, hipStream_t s)
 {
     if (nq <= 0) return hipSuccess;
+    if (a.row_bytes <= 0 || a.row_bytes % kIterBytes != 0 || a.ecap < (uint32_t)a.K) return hipErrorInvalidValue;
     const uint32_t cap = final_cap(a.K);
-    const size_t lds = (size_t)cap * sizeof(u64) + (size_t)a.k * sizeof(int64_t);
+    // keys, ids, and the query row + a row of zeros for a query that has to be rescored
+    const size_t lds = (size_t)cap * sizeof(u64) + (size_t)((a.k + 1) & ~1) * sizeof(int64_t) +
+                       (size_t)2 * (a.row_bytes + kQPadBytes);
     hipLaunchKernelGGL(select_final_kernel, dim3((uint32_t)nq), dim3(kSelThreads), lds, s, a, h, cap);
     return hipGetLastError();
 }

@@ -103,13 +103,41 @@ hipError_t launch_prep_coarse(const float *q, int64_t nq, int d, int row_bytes, 
 // ---------------------------------------------------------------- list work list
 
 // per query: count the pairs per list, lay the query's candidate range out probe by probe;
-// and the tiles of the query's threshold sample: the first sm.sp pages of its first probed list
+// and the tiles of the query's threshold sample: the first sm.sp pages of that range (the
+// pages of its first probed list, then of its second, ...), so that a query whose best list is
+// short still draws its threshold from at least k rows whenever it has that many candidates
 __global__ __launch_bounds__(256) void wl_count_kernel(WorklistArgs a, SampleArgs sm, MultiArgs m)
 {
-    __shared__ uint32_t s_len[PK_MAX_NPROBE];
+    __shared__ uint32_t s_len[PK_MAX_NPROBE];    // rows of each probed list
+    __shared__ uint32_t s_pg0[PK_MAX_NPROBE + 1]; // pages of the probed lists before each one
     const uint32_t q = blockIdx.x;
     const uint32_t ag = a.qagent[q];
     const DevIndex &ix = *m.ix[ag];
+    const uint32_t P = (uint32_t)ix.P;
+    for (int r = threadIdx.x; r < a.nprobe; r += blockDim.x) {
+        const uint32_t l = (uint32_t)a.probes[(size_t)q * a.nprobe + r];
+        uint32_t len = 0;
+        if (l < (uint32_t)ix.nlist) {
+            atomicAdd(&a.lcnt[(size_t)ag * a.nlist_max + l], 1u);
+            len = ix.list_len[l];
+        }
+        s_len[r] = len;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t acc = 0, pages = 0;
+        uint32_t *po = a.pair_off + (size_t)q * (a.nprobe + 1);
+        for (int r = 0; r < a.nprobe; ++r) {
+            po[r] = acc;
+            s_pg0[r] = pages;
+            acc += (s_len[r] + 15u) & ~15u; // segments are padded to the 16-row MFMA tile
+            pages += (s_len[r] + P - 1) / P;
+        }
+        po[a.nprobe] = acc;
+        s_pg0[a.nprobe] = pages;
+        a.ccnt[q] = 0;
+        atomicAdd(&m.ix[0]->stats[1], (unsigned long long)acc);
+    }
     {
         const float worst = sm.metric == PK_METRIC_IP ? -INFINITY : INFINITY;
         float *v = sm.vals + (size_t)q * sm.span;
@@ -125,60 +153,38 @@ __global__ __launch_bounds__(256) void wl_count_kernel(WorklistArgs a, SampleArg
                 sm.scalars[2] = g < 1 ? 1 : (g > 8 ? 8 : g);
             }
         }
-        const uint32_t l = (uint32_t)sm.probes[(size_t)q * sm.nprobe];
-        const uint32_t P = (uint32_t)ix.P;
-        for (uint32_t p = threadIdx.x; p < (uint32_t)sm.sp; p += blockDim.x) {
-            Tile tl;
-            tl.x = ix.arenas[0].vec;
-            tl.xn = ix.arenas[0].norm;
-            tl.row0 = p * P;
-            tl.qbeg = q;
-            tl.nrows = 0;
-            tl.qcnt = 1;
-            tl.pad = 0;
-            if (l < (uint32_t)ix.nlist) {
-                const uint32_t len = ix.list_len[l];
-                if (p * P < len) {
-                    const uint32_t pg = phys_page(ix, l, p);
-                    const Arena &ar = arena_of(ix, pg);
-                    const size_t local = pg - ar.first_page;
-                    tl.x = ar.vec + local * P * (size_t)ix.row_bytes;
-                    tl.xn = ar.norm + local * P;
-                    const uint32_t left = len - p * P;
-                    tl.nrows = (uint16_t)(left < P ? left : P);
-                }
-            }
-            sm.tiles[(size_t)q * sm.sp + p] = tl;
-        }
-    }
-    for (int r = threadIdx.x; r < a.nprobe; r += blockDim.x) {
-        const uint32_t l = (uint32_t)a.probes[(size_t)q * a.nprobe + r];
-        uint32_t len = 0;
-        if (l < (uint32_t)ix.nlist) {
-            atomicAdd(&a.lcnt[(size_t)ag * a.nlist_max + l], 1u);
-            len = (ix.list_len[l] + 15u) & ~15u; // segments are padded to the 16-row MFMA tile
-        }
-        s_len[r] = len;
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t acc = 0;
-        uint32_t *po = a.pair_off + (size_t)q * (a.nprobe + 1);
-        for (int r = 0; r < a.nprobe; ++r) {
-            po[r] = acc;
-            acc += s_len[r];
+    for (uint32_t p = threadIdx.x; p < (uint32_t)sm.sp; p += blockDim.x) {
+        Tile tl;
+        tl.x = ix.arenas[0].vec;
+        tl.xn = ix.arenas[0].norm;
+        tl.row0 = p * P; // position inside the sample, not inside a list
+        tl.qbeg = q;
+        tl.nrows = 0;
+        tl.qcnt = 1;
+        tl.pad = 0;
+        if (p < s_pg0[a.nprobe]) {
+            int r = 0;
+            while (s_pg0[r + 1] <= p) ++r; // the probed list that holds page p of the range
+            const uint32_t l = (uint32_t)a.probes[(size_t)q * a.nprobe + r];
+            const uint32_t lp = p - s_pg0[r];
+            const uint32_t pg = phys_page(ix, l, lp);
+            const Arena &ar = arena_of(ix, pg);
+            const size_t local = pg - ar.first_page;
+            tl.x = ar.vec + local * P * (size_t)ix.row_bytes;
+            tl.xn = ar.norm + local * P;
+            const uint32_t left = s_len[r] - lp * P;
+            tl.nrows = (uint16_t)(left < P ? left : P);
         }
-        po[a.nprobe] = acc;
-        a.qtot[q] = acc;
-        a.ccnt[q] = 0;
+        sm.tiles[(size_t)q * sm.sp + p] = tl;
     }
 }
 
-// one workgroup: offsets of the queries' candidate ranges, of the lists' slot ranges and tile ranges
+// one workgroup: offsets of the lists' slot ranges and tile ranges
 __global__ __launch_bounds__(1024) void wl_scan_kernel(WorklistArgs a, MultiArgs m)
 {
     __shared__ uint32_t s_wave[17];
-    const uint32_t total = block_exscan(a.qtot, a.qoff, (uint32_t)a.nq, s_wave);
     const uint32_t nl = (uint32_t)a.n_handles * (uint32_t)a.nlist_max;
     block_exscan(a.lcnt, a.lstart, nl, s_wave);
     // tiles per list: regular lists -> ltile, hot lists -> lhtile (counts first, then their scans in place)
@@ -211,7 +217,7 @@ __global__ __launch_bounds__(1024) void wl_scan_kernel(WorklistArgs a, MultiArgs
         const uint32_t ntiles = none ? 0u : block_exscan(lt, lt, nl, s_wave);
         if (threadIdx.x == 0) {
             uint32_t nt = ntiles;
-            if (ntiles > a.tile_cap || total > a.cand_cap) {
+            if (ntiles > a.tile_cap) {
                 // cannot happen while the host bounds hold; refuse to scan rather than overrun
                 nt = 0;
                 atomicOr(&m.ix[0]->ctr[1], (uint32_t)kErrWorklist);
@@ -223,10 +229,6 @@ __global__ __launch_bounds__(1024) void wl_scan_kernel(WorklistArgs a, MultiArgs
             // consecutive tiles of a batch, so its batches are cut coarser
             uint32_t g = hot && a.hot_rows ? nt / (uint32_t)(a.scan_grid_hot * 4) : nt / (uint32_t)(a.scan_grid * a.grab_div);
             sc[2] = g < 1 ? 1 : (g > 8 ? 8 : g);
-            if (!hot) {
-                sc[3] = total;
-                atomicAdd(&m.ix[0]->stats[1], (unsigned long long)total);
-            }
             if (nt) atomicAdd(&m.ix[0]->stats[2], (unsigned long long)nt);
         }
         __syncthreads();
@@ -247,7 +249,7 @@ __device__ __forceinline__ void wl_slots_block(const WorklistArgs &a, const Mult
     const size_t gl = (size_t)ag * a.nlist_max + (uint32_t)a.probes[i];
     const uint32_t slot = a.lstart[gl] + atomicAdd(&a.lfill[gl], 1u);
     a.slot_query[slot] = q;
-    a.slot_out[slot] = a.qoff[q] + a.pair_off[(size_t)q * (a.nprobe + 1) + r];
+    a.slot_out[slot] = a.pair_off[(size_t)q * (a.nprobe + 1) + r];
 }
 
 // tiles: one workgroup per list; tile order inside a list is [query group][page], so that

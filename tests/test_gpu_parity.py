@@ -790,9 +790,126 @@ def test_search_replays_from_a_hip_graph(gpu_device):
             p.close()
 
 
+def test_reserved_workspace_never_grows_and_capture_refuses_growth(gpu_device):
+    """Section 5: operations must not block the caller.  After one pk_workspace_reserve a config-5
+    style stream of {insert 1; search 16} (and a batch insert, and a larger search within the
+    limits) never reallocates the workspace; without the reservation the first call grows it; a
+    call that would have to grow it while its stream is capturing is refused."""
+    cfg = W.scaled(W.C5, n=30000, d=256, ncomp=64, nlist=64, nprobe=12)
+    p, _ = make_pair(cfg, insert_reserve=5000)
+    try:
+        h = p.gpu.handle
+        assert p.gpu.stats().workspace_bytes == 0  # the build's scratch is gone
+        B.pk_workspace_reserve([h], 64, 20, 12, inserts_ahead=3000)
+        st = p.gpu.stats()
+        assert st.workspace_grows == 1 and 0 < st.workspace_bytes < 64 << 20
+        say("reserved stream")
+        new = W.inserts(cfg, 0, 600)
+        q = W.queries(cfg, 0, 16)
+        lists = []
+        for r in range(600):
+            lists.append(p.gpu.insert(dev(new[r:r + 1]), want_lists=True))
+            if r % 40 == 0:
+                p.gpu.search(dev(q), 10, 12)
+        lists.append(p.gpu.insert(dev(W.inserts(cfg, 1, 64)), want_lists=True))
+        p.gpu.search(dev(W.queries(cfg, 1, 64)), 20, 12)
+        p.gpu.coarse(dev(q), 12)
+        st = p.gpu.stats()
+        assert st.workspace_grows == 1 and st.device_error == 0 and st.n_inserted == 664
+        # the oracle agrees after the stream (the inserts checked and mirrored in one go)
+        p.accept_inserted(np.concatenate([new, W.inserts(cfg, 1, 64)]), torch.cat(lists).cpu().numpy(),
+                          where="reserved stream")
+        p.check_scan(q, 10, p.orc.coarse(q, 12), where="after the reserved stream")
+        # beyond the limits the workspace grows (eagerly) ...
+        p.gpu.search(dev(W.queries(cfg, 2, 256)), 20, 12)
+        assert p.gpu.stats().workspace_grows == 2
+        # ... but not under capture: the call is refused and nothing is recorded
+        big = dev(W.queries(cfg, 3, 2048))
+        ids = torch.empty((2048, 20), dtype=torch.int64, device="cuda")
+        dist = torch.empty((2048, 20), dtype=torch.float32, device="cuda")
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize()
+        refused = None
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                try:
+                    B.pk_search(h, big, 20, 12, ids, dist)
+                except B.PancakeError as e:
+                    refused = e.status
+        torch.cuda.synchronize()
+        assert refused == B.PK_ERR_WORKSPACE
+        assert p.gpu.stats().workspace_grows == 2
+    finally:
+        p.close()
+
+
+def test_overflowing_emission_regions_are_rescored(gpu_device):
+    """A query that emits more candidates than its region holds is selected by rescoring its rows.
+    Forced with a tiny region (every query overflows): rows must equal the default path's bit for
+    bit, multi-handle and level calls included, and match the oracle."""
+    cfg = W.scaled(W.C1, n=9000)
+    for storage, metric in ((F32, IP), (F16, L2), (F32, L2)):
+        p, _ = make_pair(cfg, metric=metric, storage=storage, insert_reserve=512)
+        try:
+            p.insert_both(W.inserts(cfg, 0, 200), where="overflow setup")
+            q = W.queries(cfg, 30, 40)
+            for k, nprobe in ((10, 8), (1, 3), (100, 16)):
+                want_i, want_v = p.gpu.search(dev(q), k, nprobe)
+                B.pk_profile_begin(p.gpu.handle)
+                B.pk_index_set_emit_cap(p.gpu.handle, 16)
+                say(f"rescoring storage={storage} metric={metric} k={k} nprobe={nprobe}")
+                got_i, got_v = p.gpu.search(dev(q), k, nprobe)
+                pr = B.pk_profile_end(p.gpu.handle)
+                B.pk_index_set_emit_cap(p.gpu.handle, 0)
+                if k >= 10:  # k = 1 draws so tight a threshold that 16 entries can be enough
+                    assert pr.overflowed > 0 and pr.max_emitted > 16
+                assert torch.equal(got_i, want_i) and torch.equal(got_v, want_v)
+            B.pk_index_set_emit_cap(p.gpu.handle, 16)
+            p.check_search(q, 10, 8, where="rescored rows against the oracle")
+            B.pk_index_set_emit_cap(p.gpu.handle, 0)
+            assert p.gpu.stats().device_error == 0
+        finally:
+            p.close()
+
+
+def test_tie_group_larger_than_the_emission_region(gpu_device):
+    """3000 exact copies of one vector (scrambled ids, some ids carried twice) in one list: every copy
+    passes any threshold, the region (2048 entries for k = 10) overflows by itself, and the k lowest
+    ids of the tie group must come back, as in the oracle's sort."""
+    rng = np.random.default_rng(26)
+    n, d = 12000, 64
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    x /= np.linalg.norm(x, axis=1, keepdims=True)
+    dup = rng.permutation(n)[:3000]
+    x[dup] = x[dup[0]]
+    ids = rng.permutation(n).astype(np.int64) + 50
+    ids[dup[1]] = ids[dup[2]] = 7   # one id carried by two members of the group
+    cent = x[rng.permutation(n)[:8]].copy()
+    q = np.stack([x[dup[0]], x[5], x[dup[0]] * 0.5])
+    for metric in (IP, L2):
+        p = Pair(x, cent, metric, F32, ids=ids)
+        try:
+            for k in (1, 10, 64):
+                say(f"tie group metric={metric} k={k}")
+                B.pk_profile_begin(p.gpu.handle)
+                gi, gv = p.gpu.search(dev(q), k, 8)
+                pr = B.pk_profile_end(p.gpu.handle)
+                if k <= 10:  # region of 2048 entries; for k = 64 it has 4096 and holds the whole group
+                    assert pr.overflowed >= 2, pr.overflowed
+                gi, gv = gi.cpu().numpy(), gv.cpu().numpy()
+                oi, ov = p.orc.search(q, k, 8)
+                want = sorted(ids[dup].tolist())[:k]
+                assert gi[0].tolist() == want and gi[2].tolist() == want
+                assert np.array_equal(gi, oi[:, :k])
+                np.testing.assert_allclose(gv, ov[:, :k], rtol=1e-4, atol=2e-6)
+        finally:
+            p.close()
+
+
 def test_large_k_no_threshold_and_chunked_selection(gpu_device):
-    """k larger than the first probed list: no threshold can be drawn, every candidate is emitted,
-    and the per-query selection runs over several chunks (> 32768 candidates)."""
+    """k larger than the first probed list: the threshold sample runs on into the next probed lists;
+    with k = 1000 a query still emits more than its region holds (32768 entries) and is rescored."""
     cfg = W.scaled(W.C1, n=45000)
     p, _ = make_pair(cfg, metric=L2)
     try:

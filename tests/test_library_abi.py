@@ -54,6 +54,7 @@ def test_host_side_argument_checks_without_gpu(lib):
     assert lib.pk_index_build(C.byref(cfg), null, null, null, 0, null, 0, null, C.byref(out)) == B.PK_ERR_INVALID_ARG
     assert lib.pk_search(null, null, 1, 1, 1, null, null, null) == B.PK_ERR_BAD_HANDLE
     assert lib.pk_search_noalloc(null, null, 1, 1, 1, null, null, null) == B.PK_ERR_BAD_HANDLE
+    assert lib.pk_index_set_emit_cap(null, 0) == B.PK_ERR_BAD_HANDLE
     assert lib.pk_search_noalloc_bytes(null, 1, 1, 1) == 0
     assert lib.pk_insert(null, null, null, 1, null, null) == B.PK_ERR_BAD_HANDLE
     assert lib.pk_coarse(null, null, 1, 1, null, null) == B.PK_ERR_BAD_HANDLE
@@ -71,6 +72,8 @@ def test_host_side_argument_checks_without_gpu(lib):
     offs = (C.c_int64 * 2)(0, 1)
     assert lib.pk_search_multi(hs, 1, offs, null, 1, 1, null, null, null) == B.PK_ERR_BAD_HANDLE
     assert lib.pk_search_multi(hs, 0, offs, null, 1, 1, null, null, null) == B.PK_ERR_INVALID_ARG
+    assert lib.pk_workspace_reserve(hs, 1, 1, 1, 1, 0, null) == B.PK_ERR_BAD_HANDLE
+    assert lib.pk_workspace_reserve(hs, 0, 1, 1, 1, 0, null) == B.PK_ERR_INVALID_ARG
     assert lib.pk_search_union(hs, 1, null, 1, 1, 1, null, null, null, null) == B.PK_ERR_BAD_HANDLE
     assert lib.pk_insert_multi(hs, 1, offs, null, null, null, null) == B.PK_ERR_BAD_HANDLE
     assert lib.pk_search_union(hs, 0, null, 1, 1, 1, null, null, null, null) == B.PK_ERR_INVALID_ARG
