@@ -366,7 +366,7 @@ int pk_list_lengths(pk_index *index, int64_t *out_len, void *stream);
  * sequences are recorded) and the device adds up what the work lists contained.
  *   coarse_ms   Section 2.2 coarse search: centroid scoring + top-nprobe
  *   worklist_ms grouping of (query, list) pairs into page tiles
- *   scan_ms     Section 2.2 fine search: the list-scan kernel alone
+ *   scan_ms     Section 2.2 fine search: the list-scan kernels alone (both launches)
  *   select_ms   per-query top-k over the scored candidates (Section 4.4 merge)
  * scanned_rows counts each probed list once per launch sequence (the rows the scan must
  * read from memory); candidates counts (query, vector) pairs scored, emitted those that
@@ -379,6 +379,7 @@ typedef struct {
     int64_t scanned_rows, candidates, tiles, emitted; /* sums over all sequences          */
     int64_t overflowed;  /* queries whose emission region overflowed (selected by rescoring) */
     int64_t max_emitted; /* most candidates a single query emitted                          */
+    float scan_hot_ms;   /* the part of scan_ms spent in the launch for lists probed by many queries */
 } pk_profile;
 int pk_profile_begin(pk_index *index, void *stream);
 int pk_profile_end(pk_index *index, pk_profile *out, void *stream);

@@ -44,7 +44,7 @@ class pk_profile(C.Structure):
     _fields_ = [("launches", C.c_int32), ("coarse_ms", C.c_float), ("worklist_ms", C.c_float),
                 ("scan_ms", C.c_float), ("select_ms", C.c_float), ("scanned_rows", C.c_int64),
                 ("candidates", C.c_int64), ("tiles", C.c_int64), ("emitted", C.c_int64),
-                ("overflowed", C.c_int64), ("max_emitted", C.c_int64)]
+                ("overflowed", C.c_int64), ("max_emitted", C.c_int64), ("scan_hot_ms", C.c_float)]
 
 
 class PancakeError(RuntimeError):

@@ -102,7 +102,7 @@ namespace {
 
 bool live(const pk_index *ix) { return ix && ix->magic == kMagic; }
 
-constexpr size_t kProfEvents = 5;
+constexpr size_t kProfEvents = 6;
 constexpr size_t kProfMaxLaunches = 1024;
 
 // records the next stage boundary of the current launch sequence, if timing is on
@@ -191,7 +191,7 @@ struct Plan {
     int nprobe, k, nh;
     int mq_f, mq_h, grid_f, grid_h, grid_s, cchunks, K, nlist_max, sp;
     uint32_t hot_from;
-    bool hot_rs; // the hot class is scored by the rows-stationary kernel (tiles of kRsRows rows x all slots of a list)
+    bool hot_rs; // the hot class is scored by the rows-in-registers kernel (tiles of kRrTileRows rows x up to kRrSlots slots)
     uint32_t stride, ecap, tile_cap, span;
     bool need_coarse, need_fine, f16;
     // buffers
@@ -268,12 +268,26 @@ struct Tunables {
     int densesel; // PK_TUNE_DENSESEL: register top-nprobe selection of the coarse scores (1) or chunked (0)
     int grabdiv;  // PK_TUNE_GRABDIV: tiles per claimed batch = tiles / (grid * this), at most 8
     int hist;     // PK_TUNE_HIST: emission gate tightened by the bucket histogram (1) or sample threshold only (0)
-    int rs_from;  // PK_TUNE_RS_FROM: lists probed by more queries than this go to the rows-stationary kernel (0: none)
+    int rs_from;  // PK_TUNE_RS_FROM: lists probed by more queries than this go to the rows-stationary kernel
+                  // (0: lists with more queries than one group of the regular kernel; -1: none)
+    int rs_nq;    // PK_TUNE_RS_NQ: fewest queries of a batch for which the rows-stationary class exists
+    int hot_grab; // PK_TUNE_HOT_GRAB: tiles per claim of the rows-stationary kernels
 };
+
+#ifdef PK_DEV_TUNABLES
+#define PK_TUNABLES_STORAGE static thread_local
+#else
+#define PK_TUNABLES_STORAGE static const
+#endif
 
 const Tunables &tunables()
 {
-    static const Tunables t = [] {
+#ifdef PK_DEV_TUNABLES
+    PK_TUNABLES_STORAGE Tunables t;
+    t = [] { // read on every call, so one process can sweep
+#else
+    PK_TUNABLES_STORAGE Tunables t = [] {
+#endif
         auto env = [](const char *name, int dflt) {
 #ifdef PK_DEV_TUNABLES
             const char *v = getenv(name);
@@ -286,7 +300,7 @@ const Tunables &tunables()
         return Tunables{env("PK_TUNE_WGS", 4),       env("PK_TUNE_MQ", 0),        env("PK_TUNE_MQH", 64),
                         env("PK_TUNE_KS", 1),        env("PK_TUNE_SP_MAX", 16),   env("PK_TUNE_GEMM_WGS", 128),
                         env("PK_TUNE_DENSESEL", 1),  env("PK_TUNE_GRABDIV", 8),   env("PK_TUNE_HIST", 1),
-                        env("PK_TUNE_RS_FROM", 256)};
+                        env("PK_TUNE_RS_FROM", 0),   env("PK_TUNE_RS_NQ", 512),   env("PK_TUNE_HOT_GRAB", 1)};
     }();
     return t;
 }
@@ -361,16 +375,17 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
         if (ks == 2 || (ks == 1 && wide)) p.hot_from = 0;
         else if (ks == 3) p.hot_from = (uint32_t)p.mq_f;
         else p.hot_from = 0xffffffffu;
-        // Large batches over narrow rows: a list probed by more than rs_from queries is scored with its
-        // rows stationary in LDS, all its queries streaming past them, instead of once per query group.
-        if (p.hot_from == 0xffffffffu && tunables().rs_from > 0 && nq >= 512 && own->row_bytes <= 1536 &&
-            own->P % kRsRows == 0 && scan_rs_lds_bytes(own->row_bytes) <= own->lds_limit) {
+        // Large batches over narrow rows: a list probed by more queries than one group holds is scored
+        // with its rows stationary in registers, all its queries streaming past them, instead of once
+        // per query group (pages must split into tiles of kRrTileRows rows).
+        if (p.hot_from == 0xffffffffu && tunables().rs_from >= 0 && nq >= tunables().rs_nq && own->row_bytes <= 1536 &&
+            own->P % kRrTileRows == 0 && scan_rr_lds_bytes() <= own->lds_limit) {
             bool same = true; // one tile geometry for all handles of the call
             for (int a = 1; a < nh; ++a) same = same && hs[a]->P == own->P;
             if (same) {
                 p.hot_rs = true;
-                p.hot_from = (uint32_t)tunables().rs_from;
-                p.mq_h = kRsSlots;
+                p.hot_from = tunables().rs_from > 0 ? (uint32_t)tunables().rs_from : (uint32_t)p.mq_f;
+                p.mq_h = kRrSlots;
             }
         }
         if (p.hot_from == 0) {
@@ -388,7 +403,7 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
     uint64_t tiles = 0, wmax = 0;
     int nlist_hi = 0, pad_hi = 0;
     const int mq_least = worst ? 16 : std::min(p.mq_f, p.mq_h);
-    const bool rs_tiles = worst ? (own->row_bytes <= 1536 && own->P % kRsRows == 0) : p.hot_rs;
+    const bool rs_tiles = worst ? (own->row_bytes <= 1536 && own->P % kRrTileRows == 0) : p.hot_rs;
     for (int a = 0; a < nh; ++a) {
         const pk_index *ix = hs[a];
         const uint64_t nqa = worst ? (uint64_t)nq : qlo[a + 1] - qlo[a];
@@ -401,8 +416,9 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
         const uint64_t pp = w / ix->P + nprobe;
         const uint64_t pages = std::min<uint64_t>(pages_used_ub(ix, ahead), nqa * pp);
         tiles += pages + nqa * pp / mq_least + 1;
-        // tiles of the rows-stationary kernel are parts of a page: P / kRsRows times the pages
-        if (rs_tiles) tiles += (uint64_t)(ix->P / kRsRows - 1) * pages;
+        // tiles of the rows-in-registers kernel are parts of a page (P / kRrTileRows times the pages), and a
+        // list probed by more than kRrSlots queries has one tile per group of that many
+        if (rs_tiles) tiles += (uint64_t)(ix->P / kRrTileRows) * pages * ((uint64_t)(nqa + kRrSlots - 1) / kRrSlots);
     }
     if (tiles > 0xfffffff0ull) return PK_ERR_UNSUPPORTED;
     {
@@ -559,10 +575,11 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
     w.mq = p.mq_f;
     w.mq_hot = p.mq_h;
     w.hot_from = p.hot_from;
-    w.hot_rows = p.hot_rs ? kRsRows : 0;
+    w.hot_rows = p.hot_rs ? kRrTileRows : 0;
     w.scan_grid = p.grid_f;
     w.scan_grid_hot = p.grid_h;
     w.grab_div = tunables().grabdiv;
+    w.hot_grab = tunables().hot_grab;
     w.lcnt = p.lcnt;
     w.lstart = p.lstart;
     w.lfill = p.lfill;
@@ -623,6 +640,7 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
     sa.storage = own->cfg.storage;
     sa.mq = p.mq_f;
     if (p.hot_from > 0) PK_HIP(launch_scan(sa, p.grid_f, s));
+    if (timed) PK_TRY(mark(own, s));
     if (p.hot_from != 0xffffffffu) {
         sa.tiles = p.tiles_hot;
         sa.ntiles = p.scalars + 12;
@@ -631,7 +649,7 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
         sa.mq = p.mq_h;
         if (p.hot_rs) {
             sa.use_hist = 0; // the regular lists' scan has published its limits; this one only reads them
-            PK_HIP(launch_scan_rs(sa, p.grid_h, s));
+            PK_HIP(launch_scan_rr(sa, p.grid_h, s));
         } else {
             PK_HIP(launch_scan_ks(sa, p.grid_h, s));
         }
@@ -1842,13 +1860,14 @@ int pk_profile_end(pk_index *ix, pk_profile *out, void *stream)
     std::memset(out, 0, sizeof(*out));
     const size_t n = ix->prof_used / kProfEvents;
     for (size_t i = 0; i < n; ++i) {
-        float ms[4];
-        for (int j = 0; j < 4; ++j)
+        float ms[5];
+        for (int j = 0; j < 5; ++j)
             PK_HIP(hipEventElapsedTime(&ms[j], ix->prof_ev[i * kProfEvents + j], ix->prof_ev[i * kProfEvents + j + 1]));
         out->coarse_ms += ms[0];
         out->worklist_ms += ms[1];
-        out->scan_ms += ms[2];
-        out->select_ms += ms[3];
+        out->scan_ms += ms[2] + ms[3];
+        out->scan_hot_ms += ms[3];
+        out->select_ms += ms[4];
     }
     out->launches = (int32_t)n;
     out->scanned_rows = (int64_t)st[0];

@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -12,8 +13,8 @@ namespace pk {
 // ------------------------------------------------------------------ constants
 constexpr int kWave = 64;
 constexpr int kScanThreads = 256;     // 4 waves per workgroup in the scan kernel
-constexpr int kRsRows = 64;           // rows per tile of the rows-stationary scan kernel
-constexpr int kRsSlots = 1024;        // most query slots per tile of that kernel
+constexpr int kRrTileRows = 128;      // rows per tile of the rows-in-registers scan kernel
+constexpr int kRrSlots = 512;         // most query slots per tile of that kernel
 constexpr int kRowBlock = 32;         // rows one wave scores per pass (two 16-wide MFMA tiles)
 constexpr int kIterBytes = 256;       // bytes of one row consumed per inner iteration
 constexpr int kQPadBytes = 16;        // LDS row padding of the query tile (bank spread)
@@ -232,11 +233,93 @@ struct ScanArgs {
 };
 hipError_t launch_scan(const ScanArgs &a, int grid, hipStream_t s);
 hipError_t launch_scan_ks(const ScanArgs &a, int grid, hipStream_t s);
-hipError_t launch_scan_rs(const ScanArgs &a, int grid, hipStream_t s);
-int scan_rs_lds_bytes(int row_bytes);
+hipError_t launch_scan_rr(const ScanArgs &a, int grid, hipStream_t s);
+int scan_rr_lds_bytes();
 int scan_lds_bytes(int row_bytes, int mq);
 int scan_ks_lds_bytes(int mq);
 int scan_max_mq(int row_bytes, int storage, int lds_limit);
+
+// Tile schedule shared by the list-scan kernels.  The first tile of every workgroup is fixed (tile b for
+// workgroup b); later batches come from one counter, so uneven tiles still balance while
+// the launch does not start with a burst of atomics.  A batch is `grab` tiles; the first batch
+// is a single tile so that the emission gates get their first refresh early.  The request for the next
+// batch is issued when a batch starts and collected when it ends, and the descriptor of the
+// next tile is fetched while the current tile is scored.  Every workgroup stops the first
+// time it is handed a batch past the end.
+struct Sched {
+    uint32_t t, end, ntiles, grab;
+    int parity;
+    bool fresh; // t is the first tile of a batch
+    __device__ __forceinline__ void start(uint32_t nt, uint32_t g)
+    {
+        ntiles = nt;
+        grab = g;
+        t = blockIdx.x;
+        end = t + 1 < nt ? t + 1 : nt;
+        parity = 0;
+        fresh = true;
+    }
+    // one thread asks for the batch after the current one (s_misc[2*parity], [2*parity+1] = start, size)
+    __device__ __forceinline__ void request(const ScanArgs &a, uint32_t *s_misc, uint32_t asker = 0u) const
+    {
+        if (threadIdx.x == asker && gridDim.x < ntiles) {
+            // One atomic per batch and no other access to the counter: every workgroup of the
+            // grid claims from this one address, and a second access per claim (a load, to
+            // size the batch by what is left) measurably slows the whole scan.
+            const uint32_t want = grab;
+            s_misc[2 * parity] = gridDim.x + atomicAdd(a.tile_ctr, want);
+            s_misc[2 * parity + 1] = want;
+        }
+    }
+    // index of the tile after t; at the end of a batch this collects the requested batch (block-wide)
+    __device__ __forceinline__ uint32_t peek(const uint32_t *s_misc, uint32_t &next_end, bool &next_fresh) const
+    {
+        if (t + 1 < end) {
+            next_end = end;
+            next_fresh = false;
+            return t + 1;
+        }
+        next_fresh = true;
+        if (gridDim.x >= ntiles) {
+            next_end = ntiles;
+            return ntiles;
+        }
+        __syncthreads();
+        const uint32_t st = s_misc[2 * parity], sz = s_misc[2 * parity + 1];
+        next_end = st + sz < ntiles ? st + sz : ntiles;
+        return st;
+    }
+};
+
+
+// Dynamic LDS beyond 64 KB has to be allowed per kernel and device.  Every scan kernel is cleared
+// once per device for the most a workgroup can have, so the value never depends on the call
+// that happens to come first and threads serving different handles cannot undo each other.
+constexpr int kMaxDevices = 64;
+struct LdsCleared {
+    std::atomic<int> on[kMaxDevices];
+};
+
+template <typename K>
+inline hipError_t launch_with_lds(K kernel, LdsCleared &c, int lds, const ScanArgs &a, int grid, int threads, hipStream_t s)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const bool tracked = dev >= 0 && dev < kMaxDevices;
+    if (!tracked || c.on[dev].load(std::memory_order_acquire) == 0) {
+        int most = 0;
+        e = hipDeviceGetAttribute(&most, hipDeviceAttributeMaxSharedMemoryPerBlock, dev);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, most);
+        if (e != hipSuccess) return e;
+        if (tracked) c.on[dev].store(1, std::memory_order_release);
+    }
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(threads), lds, s, a);
+    return hipGetLastError();
+}
+
+
 
 struct SelectArgs {
     const float *vals;            // candidate values, or NULL when keys are given
@@ -328,7 +411,7 @@ struct WorklistArgs {
     const int32_t *probes;     // [nq][nprobe]; entries outside [0, nlist) are ignored
     const uint16_t *qagent;    // [nq]
     int64_t nq;
-    int nprobe, n_handles, nlist_max, scan_grid, scan_grid_hot, grab_div;
+    int nprobe, n_handles, nlist_max, scan_grid, scan_grid_hot, grab_div, hot_grab;
     int mq;                    // slots per group of a regular tile
     int mq_hot;                // slots per group of a hot tile
     int hot_rows;              // rows per hot tile: 0 = a page; else a divisor of the page size (rows-stationary kernel)

@@ -24,8 +24,6 @@
 //                   too wide for the first kernel to keep several workgroups per CU.
 // centroid_scores_kernel is the coarse step for small query segments (the same operand
 // layout, no LDS staging); large segments go through the GEMM in pk_gemm.hip.
-#include <atomic>
-
 #include "pk_internal.h"
 
 namespace pk {
@@ -213,58 +211,6 @@ __device__ __forceinline__ void finish_block(const ScanArgs &a, const Slots &s, 
         }
     }
 }
-
-// Schedule shared by both kernels.  The first tile of every workgroup is fixed (tile b for
-// workgroup b); later batches come from one counter, so uneven tiles still balance while
-// the launch does not start with a burst of atomics.  A batch is `grab` tiles; the first batch
-// is a single tile so that the emission gates get their first refresh early.  The request for the next
-// batch is issued when a batch starts and collected when it ends, and the descriptor of the
-// next tile is fetched while the current tile is scored.  Every workgroup stops the first
-// time it is handed a batch past the end.
-struct Sched {
-    uint32_t t, end, ntiles, grab;
-    int parity;
-    bool fresh; // t is the first tile of a batch
-    __device__ __forceinline__ void start(uint32_t nt, uint32_t g)
-    {
-        ntiles = nt;
-        grab = g;
-        t = blockIdx.x;
-        end = t + 1 < nt ? t + 1 : nt;
-        parity = 0;
-        fresh = true;
-    }
-    // thread 0 asks for the batch after the current one (s_misc[2*parity], [2*parity+1] = start, size)
-    __device__ __forceinline__ void request(const ScanArgs &a, uint32_t *s_misc) const
-    {
-        if (threadIdx.x == 0 && gridDim.x < ntiles) {
-            // One atomic per batch and no other access to the counter: every workgroup of the
-            // grid claims from this one address, and a second access per claim (a load, to
-            // size the batch by what is left) measurably slows the whole scan.
-            const uint32_t want = grab;
-            s_misc[2 * parity] = gridDim.x + atomicAdd(a.tile_ctr, want);
-            s_misc[2 * parity + 1] = want;
-        }
-    }
-    // index of the tile after t; at the end of a batch this collects the requested batch (block-wide)
-    __device__ __forceinline__ uint32_t peek(const uint32_t *s_misc, uint32_t &next_end, bool &next_fresh) const
-    {
-        if (t + 1 < end) {
-            next_end = end;
-            next_fresh = false;
-            return t + 1;
-        }
-        next_fresh = true;
-        if (gridDim.x >= ntiles) {
-            next_end = ntiles;
-            return ntiles;
-        }
-        __syncthreads();
-        const uint32_t st = s_misc[2 * parity], sz = s_misc[2 * parity + 1];
-        next_end = st + sz < ntiles ? st + sz : ntiles;
-        return st;
-    }
-};
 
 // ------------------------------------------------------------------ whole-group kernel
 
@@ -549,214 +495,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 8))) voi
     }
 }
 
-// ------------------------------------------------------------------ rows-stationary kernel
-
-// Lists probed by hundreds of the batch's queries.  Scored group by group with the kernels
-// above, such a list is read once per group; here the roles are swapped.  A tile is kRsRows
-// rows of one page against ALL slots of the list (up to kRsSlots): the rows are staged once,
-// coalesced, into LDS and stay there; the 8 waves then each take every 8th group of 32
-// slots and stream those queries' operands straight from global memory (the query rows of
-// a hot list are a few hundred KB that every workgroup reads: L2 traffic, not HBM), one
-// 256-byte slice ahead of the MFMAs.  The rows of the next tile are fetched into registers
-// meanwhile.  Per (row, query) the same MFMAs run in the same order as in scan_kernel, so
-// the values are bit-identical and the thresholds of the sample apply.  This launch runs
-// after the regular lists' scan: it reads the bucket limits that scan has published and does
-// not maintain the histogram any further.
-constexpr int kRsStage = kRsRows * 1536 / 16 / 512; // 16-byte pieces of a tile each thread moves, at the widest row
-
-template <int STORAGE>
-__global__ __launch_bounds__(512) void scan_rs_kernel(ScanArgs a)
-{
-    extern __shared__ __align__(16) char smem[];
-    constexpr int MT = 2;
-    const int row_bytes = a.row_bytes;
-    const int xstride = row_bytes + kQPadBytes;
-    char *xrows = smem; // [kRsRows][xstride]
-    Slots s;
-    s.carve(smem + (size_t)kRsRows * xstride, kRsSlots);
-    uint32_t *s_misc = s.bmax + kRsSlots; // keep scan_rs_lds_bytes in step
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int ln = lane & 15, lg = lane >> 4;
-    const int nit = row_bytes / kIterBytes;
-    const int pieces_per_row = row_bytes / 16;
-    const int per_thread = kRsRows * pieces_per_row / 512; // row_bytes / 128, at most kRsStage
-    const gbytes qs = in_global(a.qs);
-    uint32_t cur_qbeg = 0xffffffffu, cur_qcnt = 0;
-
-    Sched sc;
-    sc.start(*a.ntiles, *a.batch);
-    if (sc.t >= sc.ntiles) return;
-    Tile cur = a.tiles[sc.t];
-    // the rows of a tile are contiguous in the page: piece i of the tile is 16 bytes at x + 16 i
-    u32x4 pre[kRsStage];
-#define PK_PREFETCH(tile)                                                                         \
-    {                                                                                             \
-        const gbytes px = in_global((tile).x);                                                    \
-        _Pragma("unroll") for (int j = 0; j < kRsStage; ++j)                                      \
-        {                                                                                         \
-            if (j < per_thread) pre[j] = *reinterpret_cast<gvec4>(px + (size_t)(j * 512 + tid) * 16); \
-        }                                                                                         \
-    }
-    PK_PREFETCH(cur)
-    while (sc.t < sc.ntiles) {
-        const gfloats txn = in_global(cur.xn);
-        const uint32_t row0 = cur.row0;
-        const uint32_t qbeg = __builtin_amdgcn_readfirstlane(cur.qbeg);
-        const uint32_t qcnt = __builtin_amdgcn_readfirstlane((uint32_t)cur.qcnt);
-        const int nrows = __builtin_amdgcn_readfirstlane((int)cur.nrows);
-        if (sc.fresh) sc.request(a, s_misc);
-        uint32_t next_end;
-        bool next_fresh;
-        const uint32_t tn = sc.peek(s_misc, next_end, next_fresh);
-        const Tile nxt = a.tiles[tn < sc.ntiles ? tn : sc.ntiles - 1];
-
-        __syncthreads(); // every wave is done with the previous tile's rows and slot arrays
-#pragma unroll
-        for (int j = 0; j < kRsStage; ++j) {
-            if (j < per_thread) {
-                const int idx = j * 512 + tid, row = idx / pieces_per_row, col = idx - row * pieces_per_row;
-                *reinterpret_cast<u32x4 *>(xrows + (size_t)row * xstride + col * 16) = pre[j];
-            }
-        }
-        if (qbeg != cur_qbeg || qcnt != cur_qcnt) {
-            for (uint32_t m = tid; m < qcnt; m += 512) {
-                const uint32_t q = a.slot_query[qbeg + m];
-                const uint32_t base = q * a.ecap;
-                s.out[m] = a.slot_out[qbeg + m]; // position of the pair inside the query's candidate range
-                s.qn[m] = a.qnorm[q];
-                s.q[m] = q;
-                s.base[m] = base;
-                s.thr[m] = a.tau[q];
-                s.lo[m] = a.tlo[q];
-                s.inv[m] = a.tinv[q];
-                s.bmax[m] = __hip_atomic_load(a.tcur + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-            cur_qbeg = qbeg;
-            cur_qcnt = qcnt;
-        }
-        __syncthreads();
-        if (tn < sc.ntiles) PK_PREFETCH(nxt) // on its way while this tile is scored
-
-        const int groups = (int)((qcnt + 31u) >> 5);
-        // The first slice of a group's query operands is requested before the epilogue of the
-        // group before it (both register buffers are free by then), so its latency hides there.
-        gbytes qp[MT];
-        bool qlive[MT];
-        u32x4 qa[MT][4], qb[MT][4];
-#define PK_QLOAD(buf, it)                                                                         \
-    _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                             \
-    {                                                                                             \
-        _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4)                                          \
-        {                                                                                         \
-            buf[mt][s4] = u32x4{0u, 0u, 0u, 0u};                                                  \
-            if (qlive[mt]) buf[mt][s4] = *reinterpret_cast<gvec4>(qp[mt] + (size_t)(it) * kIterBytes + s4 * 64); \
-        }                                                                                         \
-    }
-#define PK_QGROUP(g)                                                                              \
-    {                                                                                             \
-        const uint32_t left = qcnt - (uint32_t)(g) * 32u;                                         \
-        _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                         \
-        {                                                                                         \
-            const uint32_t m = (uint32_t)(mt * 16 + ln);                                          \
-            qlive[mt] = m < left; /* slots past the group's last contribute zeros */              \
-            qp[mt] = qs + (size_t)(qlive[mt] ? s.q[(uint32_t)(g) * 32u + m] : 0u) * row_bytes + lg * 16; \
-        }                                                                                         \
-        PK_QLOAD(qa, 0)                                                                           \
-    }
-        if (wave < groups) PK_QGROUP(wave)
-        for (int g = wave; g < groups; g += 8) {
-            const uint32_t s0 = (uint32_t)g * 32u;
-            const uint32_t gq = qcnt - s0 < 32u ? qcnt - s0 : 32u; // slots of this group
-            const int mt_used = (int)((gq + 15u) >> 4);
-            f32x4 acc[2][MT][2]; // [half of the tile's rows][slot tile][row tile of the half]
-#pragma unroll
-            for (int h = 0; h < 2; ++h)
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    acc[h][mt][0] = f32x4{0.f, 0.f, 0.f, 0.f};
-                    acc[h][mt][1] = f32x4{0.f, 0.f, 0.f, 0.f};
-                }
-#define PK_COMPUTE(buf, it)                                                                       \
-    {                                                                                             \
-        const char *xb = xrows + (size_t)ln * xstride + (size_t)(it) * kIterBytes + lg * 16;      \
-        _Pragma("unroll") for (int s4 = 0; s4 < 4; ++s4)                                          \
-        {                                                                                         \
-            u32x4 xv[4];                                                                          \
-            _Pragma("unroll") for (int nt = 0; nt < 4; ++nt)                                      \
-                xv[nt] = *reinterpret_cast<const u32x4 *>(xb + (size_t)nt * 16 * xstride + s4 * 64); \
-            _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                     \
-            {                                                                                     \
-                if (mt < mt_used) {                                                               \
-                    _Pragma("unroll") for (int nt = 0; nt < 4; ++nt)                              \
-                        mfma_step<STORAGE>(acc[nt >> 1][mt][nt & 1], buf[mt][s4], xv[nt]);        \
-                }                                                                                 \
-            }                                                                                     \
-        }                                                                                         \
-    }
-            for (int it = 0; it < nit; it += 2) {
-                if (it + 1 < nit) { PK_QLOAD(qb, it + 1) }
-                PK_COMPUTE(qa, it)
-                if (it + 2 < nit) { PK_QLOAD(qa, it + 2) }
-                if (it + 1 < nit) { PK_COMPUTE(qb, it + 1) }
-            }
-#undef PK_COMPUTE
-            if (g + 8 < groups) PK_QGROUP(g + 8)
-            Slots sg = s; // the group's slots are 0 .. gq-1 to the epilogue
-            sg.out += s0;
-            sg.qn += s0;
-            sg.thr += s0;
-            sg.q += s0;
-            sg.base += s0;
-            sg.lo += s0;
-            sg.inv += s0;
-            sg.bmax += s0;
-            // Epilogue.  This kernel is not waiting for memory most of the time, so the gate test is
-            // kept off LDS: the lane's 8 slots' thresholds (and norms) sit in registers, and only a
-            // value that some lane of the wave passes goes on to the emission path.
-            uint32_t thr_r[MT][4];
-            float qn_r[MT][4];
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int m = mt * 16 + lg * 4 + i;
-                    thr_r[mt][i] = sg.thr[m];
-                    qn_r[mt][i] = sg.qn[m];
-                }
-#pragma unroll
-            for (int nt = 0; nt < 4; ++nt) {
-                if (nt * 16 >= nrows) break; // wave-uniform
-                const int row = nt * 16 + ln;
-                const bool live = row < nrows;
-                float xn = 0.f;
-                if (a.metric == PK_METRIC_L2 && live) xn = txn[row];
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    if (mt >= mt_used) break; // wave-uniform
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        float v = acc[nt >> 1][mt][nt & 1][i];
-                        if (a.metric == PK_METRIC_L2) v = l2_from_dot(xn, v, qn_r[mt][i]);
-                        const uint32_t bits = order_bits(v, a.metric);
-                        const bool pass = live && (uint32_t)(mt * 16 + lg * 4 + i) < gq && bits <= thr_r[mt][i];
-                        if (__ballot(pass) == 0ull) continue;
-                        emit_survivors(a, sg, v, bits, pass, mt * 16 + lg * 4 + i, row0 + (uint32_t)row, ln, lg);
-                    }
-                }
-            }
-        }
-#undef PK_QLOAD
-#undef PK_QGROUP
-        sc.t = tn;
-        sc.end = next_end;
-        if (next_fresh) sc.parity ^= 1;
-        sc.fresh = next_fresh;
-        cur = nxt;
-    }
-#undef PK_PREFETCH
-}
-
 // ------------------------------------------------------------------ centroid scoring, small batches
 
 // Coarse step (Section 2.2) for query segments too small to fill the GEMM's 128 x 128
@@ -893,33 +631,6 @@ int scan_max_mq(int row_bytes, int storage, int lds_limit)
     return best;
 }
 
-// Dynamic LDS beyond 64 KB has to be allowed per kernel and device.  Every scan kernel is cleared
-// once per device for the most a workgroup can have, so the value never depends on the call
-// that happens to come first and threads serving different handles cannot undo each other.
-constexpr int kMaxDevices = 64;
-struct LdsCleared {
-    std::atomic<int> on[kMaxDevices];
-};
-
-template <typename K>
-static hipError_t launch_with_lds(K kernel, LdsCleared &c, int lds, const ScanArgs &a, int grid, int threads, hipStream_t s)
-{
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return e;
-    const bool tracked = dev >= 0 && dev < kMaxDevices;
-    if (!tracked || c.on[dev].load(std::memory_order_acquire) == 0) {
-        int most = 0;
-        e = hipDeviceGetAttribute(&most, hipDeviceAttributeMaxSharedMemoryPerBlock, dev);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, most);
-        if (e != hipSuccess) return e;
-        if (tracked) c.on[dev].store(1, std::memory_order_release);
-    }
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(threads), lds, s, a);
-    return hipGetLastError();
-}
-
 template <int STORAGE, int MT, int WAVES, bool GATED>
 static hipError_t launch_one(const ScanArgs &a, int grid, hipStream_t s)
 {
@@ -965,23 +676,6 @@ hipError_t launch_scan(const ScanArgs &a, int grid, hipStream_t s)
     const bool gated = a.tau != nullptr;
     if (a.storage == PK_F16) return gated ? launch_mt<PK_F16, 4, true>(a, grid, s) : launch_mt<PK_F16, 4, false>(a, grid, s);
     return gated ? launch_mt<PK_F32, 4, true>(a, grid, s) : launch_mt<PK_F32, 4, false>(a, grid, s);
-}
-
-int scan_rs_lds_bytes(int row_bytes)
-{
-    return kRsRows * (row_bytes + kQPadBytes) + kRsSlots * kScanSlotWords * 4 + 16; // rows + per-slot arrays + scratch
-}
-
-// the rows-stationary kernel (gated fine search; tiles of kRsRows rows x up to kRsSlots slots; rows of at most 1536 bytes)
-hipError_t launch_scan_rs(const ScanArgs &a, int grid, hipStream_t s)
-{
-    if (a.row_bytes <= 0 || a.row_bytes % kIterBytes != 0 || a.row_bytes > 1536 || a.tau == nullptr || a.mq != kRsSlots ||
-        a.use_hist != 0)
-        return hipErrorInvalidValue;
-    static LdsCleared cleared_h, cleared_f;
-    if (a.storage == PK_F16)
-        return launch_with_lds(&scan_rs_kernel<PK_F16>, cleared_h, scan_rs_lds_bytes(a.row_bytes), a, grid, 512, s);
-    return launch_with_lds(&scan_rs_kernel<PK_F32>, cleared_f, scan_rs_lds_bytes(a.row_bytes), a, grid, 512, s);
 }
 
 // the sliced-query kernel (gated fine search only; fp32 rows are held to 32 slots)

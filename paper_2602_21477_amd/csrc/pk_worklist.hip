@@ -225,10 +225,11 @@ __global__ __launch_bounds__(1024) void wl_scan_kernel(WorklistArgs a, MultiArgs
             uint32_t *sc = hot ? a.scalars_hot : a.scalars;
             sc[0] = nt;
             sc[1] = 0;
-            // tiles per claimed batch; the rows-stationary kernel keeps a list's slot arrays across the
-            // consecutive tiles of a batch, so its batches are cut coarser
-            uint32_t g = hot && a.hot_rows ? nt / (uint32_t)(a.scan_grid_hot * 4) : nt / (uint32_t)(a.scan_grid * a.grab_div);
-            sc[2] = g < 1 ? 1 : (g > 8 ? 8 : g);
+            // tiles per claimed batch
+            uint32_t g = nt / (uint32_t)(a.scan_grid * a.grab_div);
+            g = g < 1 ? 1 : (g > 8 ? 8 : g);
+            // a rows-stationary tile is long (all slots of its list) and tiles differ tenfold: one per claim
+            sc[2] = hot && a.hot_rows ? (uint32_t)a.hot_grab : g;
             if (nt) atomicAdd(&m.ix[0]->stats[2], (unsigned long long)nt);
         }
         __syncthreads();
