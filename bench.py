@@ -33,16 +33,40 @@ HBM_PEAK_GBS = 8000.0  # MI355X datasheet HBM3E bandwidth
 METRIC_NAME = "search queries/sec at recall@10>=0.9 (1 GPU); list-scan HBM GB/s vs peak"
 
 
+MEASURED_STREAM_GBS = 6000.0  # what a bare copy of the scan's load pattern reads on this chip (profiles/scan_kernel_c4_ip.md, section 3)
+MEASURED_STREAM_SOURCE = "profiles/scan_kernel_c4_ip.md section 3 (scan load pattern, random data, 6.0-6.3 TB/s)"
+
+
+def kernel_sources_sha():
+    """Hash of the library's sources: a profile's counter figures only describe the kernels they were taken from."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2602_21477_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
 def profiled_traffic(workload, metric):
     """HBM bytes per scan launch from the committed rocprofv3 counter summary (FETCH_SIZE + WRITE_SIZE,
-    calibrated against a plain copy), if there is one for this workload variant."""
+    calibrated against a plain copy), if there is one for this workload variant AND it was taken from
+    the kernels as they are now (the summary records the hash of the sources it was taken from).
+    Returns (bytes or None, source description)."""
     import re
-    path = os.path.join(ROOT, "profiles", f"scan_kernel_{workload}_{metric}.md")
+    rel = os.path.join("profiles", f"scan_kernel_{workload}_{metric}.md")
     try:
-        m = re.search(r"^traffic_bytes_per_launch:\s*(\d+)", open(path).read(), re.M)
-        return float(m.group(1)) if m else None
+        text = open(os.path.join(ROOT, rel)).read()
     except OSError:
-        return None
+        return None, f"{rel}: no such summary"
+    m = re.search(r"^traffic_bytes_per_launch:\s*(\d+)", text, re.M)
+    k = re.search(r"^kernel_sources_sha:\s*([0-9a-f]+)", text, re.M)
+    if not m:
+        return None, f"{rel}: no traffic figure"
+    if not k or k.group(1) != kernel_sources_sha():
+        return None, f"{rel}: taken from other kernel sources ({k.group(1) if k else 'unrecorded'}), now {kernel_sources_sha()}"
+    return float(m.group(1)), f"{rel} (kernel sources {k.group(1)})"
 
 
 def log(msg):
@@ -120,6 +144,7 @@ class Scenario:
                     self.ins_sizes.append(W.insert_batch_sizes(cfg, steps_total, agent=a))
         self.ins_pos = [0] * na
         self.step_no = 0
+        self.reserved = None
         torch.cuda.synchronize()
 
     @property
@@ -151,6 +176,14 @@ class Scenario:
             self._insert(0, self.insert_m)
         self.step_no += 1
 
+    def reserve(self, steps):
+        """One workspace reservation for everything the run will call (Section 5: no operation blocks the caller)."""
+        cfg = self.cfg
+        ahead = max(self.insert_m, 16) * steps + 1024
+        nq = max(self.queries_per_step(), 64)
+        self.B.pk_workspace_reserve([ix.handle for ix in self.indexes], nq, max(cfg.k, 10), cfg.nprobe, ahead)
+        self.reserved = {"nq_max": nq, "k_max": max(cfg.k, 10), "nprobe_max": cfg.nprobe, "inserts_ahead": ahead}
+
     def queries_per_step(self):
         return self.cfg.nq * len(self.indexes)
 
@@ -170,8 +203,9 @@ class Scenario:
         """recall@10 of the GPU search against the oracle's exact search on a few queries of agent 0
         (base rows only: called before the timed steps insert anything)."""
         import oracle
-        q = self.q_host[0][:nsample]
-        ids, _ = self.indexes[0].search(self.q[0][:nsample].contiguous(), max(10, self.cfg.k), self.cfg.nprobe)
+        nq0 = self.cfg.nq  # agent 0's queries lead every batch
+        q = np.concatenate([b[:nq0] for b in self.q_host])[:nsample]
+        ids, _ = self.indexes[0].search(self.torch.from_numpy(q).cuda(), max(10, self.cfg.k), self.cfg.nprobe)
         bi, _ = oracle.bruteforce(self.datas[0].x, q, 10, self.cfg.metric)
         got = ids.cpu().numpy()
         return float(np.mean([len(set(a[:10].tolist()) & set(b.tolist())) / 10.0 for a, b in zip(got, bi)]))
@@ -209,10 +243,85 @@ class Scenario:
         dt = time.time() - t0
         scanned = float(np.sort(ix.list_lengths())[::-1][:cfg.nprobe].sum())
         return {"value": done / dt, "unit": "queries/s", "cores": oracle.num_threads(), "kind": "oracle",
+                "omp_max_threads": oracle.num_threads(), "affinity_cpus": len(os.sched_getaffinity(0)),
+                "os_cpu_count": os.cpu_count(),
                 "sample": f"{done} queries (nprobe={cfg.nprobe}, k={cfg.k}) on an oracle index over the first "
                           f"{n_s} rows with {nlist_s} lists (1/{f} of the workload, same list length, so the same "
                           f"vectors scanned per query; <= {scanned:.0f} per query); oracle build {build_s:.1f}s not "
                           f"included"}
+
+    def stream(self, rounds, window):
+        """Config 5 as the paper's One-Search-One-Insert pattern (Section 6.1): `rounds` rounds of {insert one
+        vector; search one batch}, every insert a call of its own, so that the lists' delta-page tables
+        grow one vector at a time over the whole stream.  Timed: three windows of `window` rounds at the
+        start, the middle and the end, every round of a window with its search; between the windows every
+        insert still happens and every 64th round searches (what is skipped there is only the waiting for
+        searches nobody times).  After each window 64 more rounds run with the library's stage events on."""
+        torch, B, W, cfg = self.torch, self.B, self.W, self.cfg
+        ix = self.indexes[0]
+        t0 = time.time()
+        nb = (rounds + 255) // 256
+        rows = np.concatenate([W.inserts(cfg, 1000 + b, 256) for b in range(nb)])[:rounds]
+        dev_rows = torch.from_numpy(rows).cuda()
+        log(f"{rounds} insert vectors generated in {time.time() - t0:.1f}s")
+        B.pk_workspace_reserve([ix.handle], max(cfg.nq, 64), max(cfg.k, 10), cfg.nprobe, rounds + 1024)
+        grows0 = ix.stats().workspace_grows
+        starts = sorted({0, max(0, rounds // 2 - window // 2), max(0, rounds - window - 64)})
+        windows, r, nsearch = [], 0, 0
+
+        last_say = [time.time()]
+
+        def one_round(search):
+            nonlocal r, nsearch
+            if time.time() - last_say[0] > 20:
+                log(f"stream: round {r} of {rounds}")
+                last_say[0] = time.time()
+            B.pk_insert(ix.handle, dev_rows[r:r + 1])
+            if search:
+                B.pk_search(ix.handle, self.q[r % self.N_QUERY_BATCHES], cfg.k, cfg.nprobe, self.out_ids, self.out_dist)
+                nsearch += 1
+            r += 1
+
+        for w0 in starts:
+            while r < w0:
+                one_round(r % 64 == 0)
+            n = min(window, rounds - r)
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            ev[0].record()
+            for i in range(n):
+                one_round(True)
+                ev[i + 1].record()
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            per = [ev[i].elapsed_time(ev[i + 1]) for i in range(n)]
+            B.pk_profile_begin(ix.handle)
+            for _ in range(min(64, rounds - r)):
+                one_round(True)
+            pr = B.pk_profile_end(ix.handle)
+            m = max(pr.launches, 1)
+            scan_ms = pr.scan_ms / m
+            alg = pr.scanned_rows / m * self.row_bytes()
+            st = ix.stats()
+            windows.append({"first_round": w0, "rounds": n, "ms_per_round": dt / n * 1e3, "round_ms": percentiles(per),
+                            "queries_per_s": cfg.nq * n / dt, "inserted_so_far": int(st.n_inserted),
+                            "pages_used": int(st.pages_used), "max_list_len": int(st.max_list_len),
+                            "scan_ms": scan_ms, "scan_GBps": alg / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else 0.0,
+                            "scan_frac_of_peak": alg / (scan_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if scan_ms > 0 else 0.0,
+                            "algorithmic_bytes_per_search": alg,
+                            "stages_ms": {"coarse": pr.coarse_ms / m, "sample_and_worklist": pr.worklist_ms / m,
+                                          "scan": scan_ms, "select": pr.select_ms / m}})
+            log(f"window at round {w0}: {windows[-1]['ms_per_round']:.3f} ms/round, scan {scan_ms:.3f} ms = "
+                f"{windows[-1]['scan_GBps']:.0f} GB/s, {st.n_inserted} inserted, {st.pages_used} pages")
+        while r < rounds:
+            one_round(r % 64 == 0)
+        torch.cuda.synchronize()
+        self.check_errors()
+        st = ix.stats()
+        return {"rounds": rounds, "single_vector_insert_calls": rounds, "searches": nsearch, "windows": windows,
+                "inserted": int(st.n_inserted), "workspace_bytes": int(st.workspace_bytes),
+                "workspace_grows_after_the_reservation": int(st.workspace_grows - grows0)}
 
     def maintenance(self, extra_inserts, steps=20):
         """Grow agent 0's lists by `extra_inserts` vectors (batches of 1024: delta pages open all over the
@@ -464,19 +573,38 @@ class Scenario:
         self.torch.cuda.empty_cache()
 
 
+def percentiles(ms):
+    a = np.sort(np.asarray(ms, dtype=np.float64))
+    return {"median": float(np.median(a)), "p10": float(np.percentile(a, 10)), "p90": float(np.percentile(a, 90)),
+            "min": float(a[0]), "max": float(a[-1])}
+
+
+def timed_steps(sc, steps):
+    """K steps: wall clock around all of them (the headline rate) and one HIP event pair per step on the
+    stream the library enqueues on (torch's current stream), for the spread."""
+    import torch
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev[0].record()
+    for i in range(steps):
+        sc.step()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    return dt, [ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]
+
+
 def measure(sc, steps, warmup, recall_queries):
     """Warm-up, K timed steps, the same K steps again with stage events; returns the result dict."""
     import torch
     B = sc.B
     rec = sc.recall(recall_queries) if recall_queries else None
+    sc.reserve(warmup + 2 * steps + 8)
     for _ in range(warmup):
         sc.step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        sc.step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    grows0 = sc.indexes[0].stats().workspace_grows
+    dt, per_step = timed_steps(sc, steps)
     qps = sc.queries_per_step() * steps / dt
     # stage timing: HIP events recorded by the library on the search's own stream
     B.pk_profile_begin(sc.handle)
@@ -484,22 +612,33 @@ def measure(sc, steps, warmup, recall_queries):
         sc.step()
     pr = B.pk_profile_end(sc.handle)
     sc.check_errors()
+    st = sc.indexes[0].stats()
     n = max(pr.launches, 1)
     scan_ms = pr.scan_ms / n
     alg_bytes = pr.scanned_rows / n * sc.row_bytes()
     achieved = alg_bytes / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else 0.0
     res = {
-        "qps": qps, "ms_per_step": dt / steps * 1e3, "recall_at_10": rec,
+        "qps": qps, "ms_per_step": dt / steps * 1e3, "step_ms": percentiles(per_step), "recall_at_10": rec,
+        "recall_queries": recall_queries,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "pk::scan_kernel (gated list scan)",
-                     "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": scan_ms},
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "traffic_source": None,
+                     "measured_stream": MEASURED_STREAM_GBS, "frac_of_measured_stream": achieved / MEASURED_STREAM_GBS,
+                     "measured_stream_source": MEASURED_STREAM_SOURCE,
+                     "kernel": "pk::scan_kernel + pk::scan_rr_kernel (gated list scan)",
+                     "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": scan_ms,
+                     "kernel_ms_lists_probed_by_many_queries": pr.scan_hot_ms / n},
         "stages_ms": {"coarse": pr.coarse_ms / n, "sample_and_worklist": pr.worklist_ms / n, "scan": scan_ms,
                       "select": pr.select_ms / n},
         "per_search": {"tiles": pr.tiles / n, "candidates": pr.candidates / n, "emitted": pr.emitted / n,
-                       "scanned_rows": pr.scanned_rows / n},
+                       "scanned_rows": pr.scanned_rows / n, "max_emitted_by_one_query": pr.max_emitted,
+                       "queries_rescored_after_overflow": pr.overflowed},
+        "workspace": {"bytes": int(st.workspace_bytes), "grows_during_timed_steps": int(st.workspace_grows - grows0),
+                      "reserved_for": sc.reserved},
     }
-    log(f"{qps:.0f} queries/s, {res['ms_per_step']:.3f} ms/step, scan {scan_ms:.3f} ms = {achieved:.0f} GB/s "
-        f"({achieved / HBM_PEAK_GBS:.3f} of peak), recall@10 {rec}, stages {res['stages_ms']}")
+    log(f"{qps:.0f} queries/s, {res['ms_per_step']:.3f} ms/step (median {res['step_ms']['median']:.3f}, p10 "
+        f"{res['step_ms']['p10']:.3f}, p90 {res['step_ms']['p90']:.3f}), scan {scan_ms:.3f} ms = {achieved:.0f} GB/s "
+        f"({achieved / HBM_PEAK_GBS:.3f} of peak), recall@10 {rec}, stages {res['stages_ms']}, workspace "
+        f"{st.workspace_bytes / 2**20:.1f} MiB")
     return res
 
 
@@ -524,10 +663,15 @@ def run(args):
     xd = datas[0].upload() if len(metrics) > 1 else None  # shared by the variants' builds
 
     results = {}
+    stream = None
     for metric in metrics:
         cfg = W.scaled(base, metric=metric)
-        sc = Scenario(cfg, datas, steps_total, xd=xd)
+        full_stream = name == "c5" and args.c5_rounds > 0
+        sc = Scenario(cfg, datas, steps_total, xd=xd,
+                      reserve=(args.c5_rounds + steps_total + 4096) if full_stream else None)
         res = measure(sc, args.steps, args.warmup, 0 if args.no_recall else args.recall_queries)
+        if full_stream:
+            stream = sc.stream(args.c5_rounds, args.c5_window)
         res["n"] = sc.n_total()
         results["ip" if metric == W.METRIC_IP else "l2"] = (res, sc, cfg)
         if metric != metrics[-1]:
@@ -543,13 +687,30 @@ def run(args):
         "config": {"workload": base.name, "n": res["n"], "d": cfg.d, "nlist": cfg.nlist, "nprobe": cfg.nprobe,
                    "k": cfg.k, "agents": len(datas), "queries_per_step": sc.queries_per_step(),
                    "inserts_per_step": sc.insert_m, "metric": head},
-        "roofline": res["roofline"], "stages_ms": res["stages_ms"], "per_search": res["per_search"],
-        "recall_at_10": res["recall_at_10"],
+        "step_ms": res["step_ms"], "roofline": res["roofline"], "stages_ms": res["stages_ms"],
+        "per_search": res["per_search"], "workspace": res["workspace"], "recall_at_10": res["recall_at_10"],
+        "recall_queries": res["recall_queries"], "kernel_sources_sha": kernel_sources_sha(),
     }
     for m, r in results.items():
-        r[0]["roofline"]["traffic"] = profiled_traffic(base.name.split("_")[0], m)
+        r[0]["roofline"]["traffic"], r[0]["roofline"]["traffic_source"] = profiled_traffic(base.name.split("_")[0], m)
     if len(results) > 1:
         out["variants"] = {m: {k: v for k, v in r[0].items()} for m, r in results.items()}
+    if stream is not None:
+        # the headline of the skewed dynamic config is the 1:1 stream itself: all rounds of the three windows
+        ws = stream["windows"]
+        tot_rounds = sum(w["rounds"] for w in ws)
+        tot_ms = sum(w["rounds"] * w["ms_per_round"] for w in ws)
+        out["value"] = cfg.nq * tot_rounds / (tot_ms * 1e-3)
+        out["ms_per_step"] = tot_ms / tot_rounds
+        out["steps"] = tot_rounds
+        last = ws[-1]
+        out["roofline"].update({"achieved": last["scan_GBps"], "frac": last["scan_frac_of_peak"],
+                                "frac_of_measured_stream": last["scan_GBps"] / MEASURED_STREAM_GBS,
+                                "algorithmic_bytes_per_launch": last["algorithmic_bytes_per_search"],
+                                "kernel_ms": last["scan_ms"], "window": "last"})
+        out["stream"] = stream
+        out["short_run_before_the_stream"] = {"qps": res["qps"], "ms_per_step": res["ms_per_step"],
+                                              "step_ms": res["step_ms"], "stages_ms": res["stages_ms"]}
     if not args.no_cpu_baseline:
         # the headline scenario is the last one still open only if it ran last; rebuild nothing: the
         # baseline needs host data only
@@ -579,7 +740,7 @@ def main():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4", "c4l2", "c4ip", "c5"])
-    ap.add_argument("--recall-queries", type=int, default=8)
+    ap.add_argument("--recall-queries", type=int, default=64)
     ap.add_argument("--no-recall", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
@@ -595,6 +756,10 @@ def main():
     ap.add_argument("--maintenance", type=int, default=0, metavar="N",
                     help="after the timed steps: insert N more vectors, compact the index into a fresh arena "
                          "(pk_index_compact) and report the cost (extra field, the headline is unchanged)")
+    ap.add_argument("--c5-rounds", type=int, default=200000,
+                    help="workload c5: rounds of the 1:1 insert/search stream (Section 6.1 One-Search-One-Insert); "
+                         "0 = only the short run of --steps steps")
+    ap.add_argument("--c5-window", type=int, default=2000, help="workload c5: rounds per timed window (start, middle, end)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="counter calibration only: four plain 1 GiB device-to-device copies (a copy kernel of known "
                          "size for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE), then exit")

@@ -193,6 +193,7 @@ struct Plan {
     uint32_t hot_from;
     bool hot_rs; // the hot class is scored by the rows-in-registers kernel (tiles of kRrTileRows rows x up to kRrSlots slots)
     uint32_t stride, ecap, tile_cap, span;
+    uint64_t cbuf_entries; // entries of all emission regions together
     bool need_coarse, need_fine, f16;
     // buffers
     char *qs32, *qs;
@@ -250,7 +251,7 @@ void carve(Plan &p, char *base, const pk_index *own)
         p.sslot_o = c.take<uint32_t>(nq);
         p.stiles = c.take<Tile>(nq * p.sp + 1);
         p.svals = c.take<float>(nq * p.span + 16);
-        p.cbuf = c.take<unsigned long long>(nq * p.ecap + 16);
+        p.cbuf = c.take<unsigned long long>((size_t)p.cbuf_entries + 16);
     }
     p.bytes = round_up(c.off, 256);
 }
@@ -324,13 +325,19 @@ uint32_t pow2_at_least(uint64_t v)
 }
 
 // Entries of one query's emission region.  The gate (sample threshold + running histogram)
-// lets a few times k candidates through, so a few dozen times k with a floor is ample; a query
-// that emits more is selected by rescoring its rows (select_final_kernel), so the size is a
-// matter of speed, not of correctness.  If every candidate a query can have fits, nothing can
-// overflow and the region is just that large.
-uint32_t emit_cap_for(const pk_index *own, int K, uint64_t wmax)
+// lets a few times k candidates through on evenly sized lists, so a few dozen times k with a
+// floor is ample there; a query whose best list is very long lets more through before the
+// histogram has tightened (its threshold is a quantile of the sample, and that quantile of a
+// 400 000-row list is thousands of rows), so a batch of few queries gets regions of up to
+// 32768 entries: all regions of a call together stay near 32 MB.  A query that emits more than
+// its region holds is selected by rescoring its rows (select_final_kernel), one workgroup for
+// the whole query: the size is a matter of speed, not of correctness.  If every candidate a
+// query can have fits, nothing can overflow and the region is just that large.
+uint32_t emit_cap_for(const pk_index *own, int K, uint64_t wmax, int64_t nq)
 {
     uint64_t e = std::min<uint64_t>(std::max<uint64_t>(pow2_at_least(32ull * (uint64_t)K), 2048), 32768);
+    const uint64_t roomy = (4ull << 20) / (uint64_t)std::max<int64_t>(nq, 1); // entries per query at 32 MB in all
+    e = std::max(e, std::min<uint64_t>(32768, roomy / 1024 * 1024));
     if (own->emit_cap > 0) e = (uint64_t)own->emit_cap;
     e = std::min<uint64_t>(e, round_up(wmax, 16));
     return (uint32_t)std::max<uint64_t>(e, round_up((uint64_t)K, 16));
@@ -440,7 +447,10 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
     p.nlist_max = nlist_hi;
     p.stride = (uint32_t)pad_hi;
     p.cchunks = (nlist_hi + kSelChunk - 1) / kSelChunk;
-    p.ecap = emit_cap_for(own, p.K, wmax);
+    p.ecap = emit_cap_for(own, p.K, wmax, nq);
+    p.cbuf_entries = (uint64_t)nq * p.ecap;
+    // a smaller batch has larger regions: none needs more in all than this
+    if (worst) p.cbuf_entries = std::max<uint64_t>(p.cbuf_entries, std::min<uint64_t>(32768ull * (uint64_t)nq, 4ull << 20));
     p.tile_cap = (uint32_t)tiles;
     carve(p, nullptr, own);
     return PK_OK;
@@ -700,7 +710,7 @@ int search_impl(pk_index *const *hs, int nh, const int64_t *q_offsets, const flo
     // queries per launch sequence: the emission regions of one sequence stay within kRegionBytes
     uint64_t wmax = 1;
     for (int a = 0; a < nh; ++a) wmax = std::max(wmax, wq_ub(hs[a], nprobe));
-    const uint64_t per_query = (uint64_t)emit_cap_for(own, k + 1, wmax) * sizeof(unsigned long long);
+    const uint64_t per_query = (uint64_t)emit_cap_for(own, k + 1, wmax, 32768) * sizeof(unsigned long long);
     const int64_t step = std::max<int64_t>(1, std::min<int64_t>(32768, (int64_t)(kRegionBytes / per_query)));
     std::vector<uint32_t> qlo(nh + 1);
     for (int64_t q0 = 0; q0 < nq_all; q0 += step) {
