@@ -43,10 +43,24 @@ def full_batch_search(sc):
     return sc.out_ids.cpu().numpy(), sc.out_dist.cpu().numpy()
 
 
-def spot_check(sc, ids_all, val_all, agent, rows, extra=None, kprime=None):
-    """rows: query rows (inside the agent's segment) to verify.  extra: (ids, vectors) inserted so far."""
+WORST = {}  # largest observed error relative to the tolerance scale, per check (printed, and quoted in the design doc)
+
+
+def note(tag, err):
+    WORST[tag] = max(WORST.get(tag, 0.0), float(err))
+
+
+def spot_check(sc, ids_all, val_all, agent, rows, extra=None, kprime=None, loose_rows=3, tag=""):
+    """rows: query rows (inside the agent's segment) to verify.  extra: (ids, vectors) inserted so far.
+
+    fp32 storage: every sampled row goes through the benchmark spec's rule (1e-4).  fp16 storage: the
+    the benchmark spec's rule (1e-2 against the oracle fed the fp32 query) leaves near-tie runs a thousand
+    long, so it pins values but hardly any id; therefore every sampled row is ALSO checked against the
+    oracle fed the query rounded to fp16 (what the kernel multiplies), at 1e-4: that pins the ids.
+    The looser rule itself is then run on the first `loose_rows` sampled rows."""
     cfg, dat = sc.cfg, sc.datas[agent]
     tol = TOL[cfg.storage]
+    f16 = cfg.storage == B.PK_F16
     lo = sc.q_offsets[agent]
     q = sc.q_host[0][lo:lo + cfg.nq][rows]
     gi, gv = ids_all[lo:lo + cfg.nq][rows], val_all[lo:lo + cfg.nq][rows]
@@ -57,6 +71,10 @@ def spot_check(sc, ids_all, val_all, agent, rows, extra=None, kprime=None):
     xn2 = 1.0 + 1e-3  # rows are unit vectors (up to fp16 rounding)
     qn2 = (q.astype(np.float64) ** 2).sum(1)
     cn2 = float((dat.cent.astype(np.float64) ** 2).sum(1).max())
+    q16 = q.astype(np.float16).astype(np.float32) if f16 else q
+
+    def scale(i):
+        return float(np.sqrt(qn2[i] * xn2) if cfg.metric == W.METRIC_IP else qn2[i] + xn2)
 
     # 1. probe lists
     gp = sc.indexes[agent].coarse(torch.from_numpy(q).cuda(), cfg.nprobe).cpu().numpy()
@@ -73,23 +91,50 @@ def spot_check(sc, ids_all, val_all, agent, rows, extra=None, kprime=None):
         assert len(set(ids.tolist())) == len(ids)
         vecs = x_all[[int(t) if t < dat.n else row_of[int(t)] for t in ids]]
         ov = oracle.pair_values(np.repeat(q[i:i + 1], len(ids), 0), vecs, cfg.metric)
-        s = np.sqrt(qn2[i] * xn2) if cfg.metric == W.METRIC_IP else qn2[i] + xn2
-        assert np.all(np.abs(gv[i] - ov) <= tol * np.maximum(np.abs(ov), s)), f"value mismatch, query {rows[i]}"
+        err = np.abs(gv[i] - ov) / np.maximum(np.abs(ov), scale(i))
+        note(f"{tag} values vs oracle (tolerance {tol})", err.max())
+        assert np.all(err <= tol), f"value mismatch, query {rows[i]}"
+        if f16:
+            ov16 = oracle.pair_values(np.repeat(q16[i:i + 1], len(ids), 0), vecs, cfg.metric)
+            err16 = np.abs(gv[i] - ov16) / np.maximum(np.abs(ov16), scale(i))
+            note(f"{tag} values vs oracle fed the fp16-rounded query (tolerance 1e-4)", err16.max())
+            assert np.all(err16 <= 1e-4), f"value mismatch against the rounded query, query {rows[i]}"
         d = np.diff(gv[i])
         assert np.all(d <= 0) if cfg.metric == W.METRIC_IP else np.all(d >= 0)
 
     # 3. exact search, restricted to the probed lists
     kprime = kprime or max(4 * cfg.k, 256)
-    bi, bv = oracle.bruteforce(x_all, q, kprime, cfg.metric, ids=id_all)
-    assert recall_at(gi, bi, 10) >= 0.9
-    for i in range(len(q)):
-        vec_rows = [int(t) if t < dat.n else row_of[int(t)] for t in bi[i]]
-        lists = orc.assign(x_all[vec_rows])
-        keep = np.isin(lists, gp[i])
-        ei, ev = bi[i][keep], bv[i][keep]
-        assert len(ei) >= cfg.k, "raise kprime"
-        s = np.sqrt(qn2[i] * xn2) if cfg.metric == W.METRIC_IP else qn2[i] + xn2
-        check_row(gi[i], gv[i], ei, ev, cfg.k, tol, float(s), cfg.metric, where=f"agent {agent} query {rows[i]}")
+
+    def against_exact(qq, which, tol_ids):
+        bi, bv = oracle.bruteforce(x_all, qq[which], kprime, cfg.metric, ids=id_all)
+        for j, i in enumerate(which):
+            vec_rows = [int(t) if t < dat.n else row_of[int(t)] for t in bi[j]]
+            lists = orc.assign(x_all[vec_rows])
+            keep = np.isin(lists, gp[i])
+            ei, ev = bi[j][keep], bv[j][keep]
+            assert len(ei) >= cfg.k, "raise kprime"
+            check_row(gi[i], gv[i], ei, ev, cfg.k, tol_ids, scale(i), cfg.metric, where=f"agent {agent} query {rows[i]}")
+        return bi
+
+    everything = list(range(len(q)))
+    if f16:
+        against_exact(q16, everything, 1e-4)           # pins the ids
+        bi = against_exact(q, everything[:loose_rows], tol)  # the benchmark spec's own rule
+        assert recall_at(gi[:loose_rows], bi, 10) >= 0.9
+    else:
+        bi = against_exact(q, everything, tol)
+        assert recall_at(gi, bi, 10) >= 0.9
+
+
+def spread(nq, count):
+    """`count` query rows spread evenly over a batch of nq, first and last included."""
+    return sorted(set(np.linspace(0, nq - 1, min(count, nq)).round().astype(int).tolist()))
+
+
+def report(tag):
+    for k in sorted(WORST):
+        if k.startswith(tag):
+            say(f"WORST {k}: {WORST[k]:.3e}")
 
 
 def check_lists(sc):
@@ -105,7 +150,7 @@ def test_config2_single_agent_full_size(gpu_device):
     try:
         ids, val = full_batch_search(sc)
         say("c2: spot check before inserts")
-        spot_check(sc, ids, val, 0, [0, 21, 63])
+        spot_check(sc, ids, val, 0, spread(cfg.nq, 32), tag="c2")
         new_ids, new_x = [], []
         for r in range(40):  # the config's interleave: search 64, insert 8
             lo = sc.ins_pos[0]
@@ -114,9 +159,10 @@ def test_config2_single_agent_full_size(gpu_device):
             sc.step()
         ids, val = full_batch_search(sc)
         say("c2: spot check after 40 insert batches")
-        spot_check(sc, ids, val, 0, [5, 40], extra=(np.concatenate(new_ids), np.concatenate(new_x)))
+        spot_check(sc, ids, val, 0, spread(cfg.nq, 16), extra=(np.concatenate(new_ids), np.concatenate(new_x)), tag="c2")
         check_lists(sc)
         assert sc.indexes[0].stats().n_total == cfg.n + 320
+        report("c2")
     finally:
         sc.close()
 
@@ -129,9 +175,9 @@ def test_config3_multi_agent_full_size(gpu_device):
     sc = bench.Scenario(cfg, datas, steps_total=16)
     try:
         ids, val = full_batch_search(sc)
-        for a in (0, 7, 15):
+        for a in range(cfg.n_agents):  # two rows of every agent's segment: 32 in all
             say(f"c3: spot check agent {a}")
-            spot_check(sc, ids, val, a, [1, 30])
+            spot_check(sc, ids, val, a, [(3 * a + 1) % cfg.nq, (5 * a + 17) % cfg.nq], tag="c3")
         # one segmented launch == per-handle launches, bit for bit
         for a in (3, 12):
             lo = sc.q_offsets[a]
@@ -141,6 +187,7 @@ def test_config3_multi_agent_full_size(gpu_device):
         for _ in range(4):
             sc.step()  # inserts of 1..16 vectors per agent between launches
         check_lists(sc)
+        report("c3")
     finally:
         sc.close()
 
@@ -150,10 +197,17 @@ def test_config4_large_static_full_size(gpu_device, c4_data, metric):
     cfg = W.scaled(W.C4, metric=metric)
     sc = bench.Scenario(cfg, [c4_data[0]], steps_total=8, xd=c4_data[1])
     try:
+        B.pk_profile_begin(sc.handle)
         ids, val = full_batch_search(sc)
-        say(f"c4 metric={metric}: spot check")
-        spot_check(sc, ids, val, 0, [0, 511, 1023], kprime=2000)
+        pr = B.pk_profile_end(sc.handle)
+        if metric == W.METRIC_L2:  # its probes concentrate: the lists probed by hundreds of queries have their own kernel
+            assert pr.scan_hot_ms > 0.05, "the rows-in-registers kernel should have run"
+        assert pr.overflowed == 0
+        say(f"c4 metric={metric}: spot check of 32 rows (scan {pr.scan_ms:.3f} ms, of which {pr.scan_hot_ms:.3f} ms "
+            f"for lists probed by many queries; most candidates one query emitted: {pr.max_emitted})")
+        spot_check(sc, ids, val, 0, spread(cfg.nq, 32), kprime=2000, tag=f"c4-{'l2' if metric == W.METRIC_L2 else 'ip'}")
         check_lists(sc)
+        report("c4")
     finally:
         sc.close()
 
@@ -168,41 +222,50 @@ def c4_data(gpu_device):
 
 
 def test_config5_skewed_dynamic_full_size(gpu_device):
-    """2 M x 1536 with Zipf list sizes; the 200 000 single inserts of the config are applied as
-    400 timed-style rounds {insert 1; search 16} plus bulk batches for the rest, so that lists
-    grow by many delta pages; searches are spot-checked before, in between and after."""
+    """2 M x 1536 with Zipf list sizes, and the config's stream as the paper's One-Search-One-Insert
+    pattern (Section 6.1) at full length: 200 000 rounds of {insert ONE vector; search 16}, every insert
+    a call of its own, so the delta-page tables of the largest lists grow one vector at a time.  Outside
+    the three checked stretches only every 500th round searches (an unchecked search is only waiting);
+    32 rows are checked against the oracle in all: before, in the middle of and after the stream."""
     cfg = W.C5
-    sc = bench.Scenario(cfg, [bench.Data(cfg)], steps_total=512, reserve=210_000)
+    rounds = 200_000
+    sc = bench.Scenario(cfg, [bench.Data(cfg)], steps_total=8, reserve=rounds + 4096)
     try:
-        lens = sc.indexes[0].list_lengths()
+        ix = sc.indexes[0]
+        lens = ix.list_lengths()
+        pages0 = ix.stats().pages_used
         assert lens.max() > 50 * np.median(lens), "list sizes should be heavily skewed"
         ids, val = full_batch_search(sc)
         say("c5: spot check before inserts")
-        spot_check(sc, ids, val, 0, [0, 9])
-        new_x = []
-        for r in range(400):
-            new_x.append(sc.ins[0][sc.ins_pos[0]:sc.ins_pos[0] + 1].cpu().numpy())
-            sc.step()
-        done = 400
-        bulk = []
-        for b in range(49):  # 49 x 4096 = 200 704 more, from the same insert stream recipe
-            xb = np.concatenate([W.inserts(cfg, 10_000 + 16 * b + j, 256) for j in range(16)])
-            bulk.append(xb)
-            B.pk_insert(sc.handle, torch.from_numpy(xb).cuda())
-            if b == 20:
+        spot_check(sc, ids, val, 0, spread(cfg.nq, 8), tag="c5")
+        rows = np.concatenate([W.inserts(cfg, 1000 + b, 256) for b in range((rounds + 255) // 256)])[:rounds]
+        dev_rows = torch.from_numpy(rows).cuda()
+        B.pk_workspace_reserve([sc.handle], 64, cfg.k, cfg.nprobe, rounds + 1024)
+        grows = ix.stats().workspace_grows
+        for r in range(rounds):
+            B.pk_insert(sc.handle, dev_rows[r:r + 1])
+            if r % 500 == 0 or r > rounds - 64:
+                B.pk_search(sc.handle, sc.q[r % sc.N_QUERY_BATCHES], cfg.k, cfg.nprobe, sc.out_ids, sc.out_dist)
+            if r % 20000 == 0:
+                say(f"c5: round {r}")
+            if r + 1 == rounds // 2:
                 ids, val = full_batch_search(sc)
-                say("c5: spot check in the middle of the insert stream")
-                xs = np.concatenate(new_x + bulk)
-                spot_check(sc, ids, val, 0, [3], extra=(np.arange(cfg.n, cfg.n + len(xs)), xs))
+                say("c5: spot check in the middle of the stream")
+                spot_check(sc, ids, val, 0, spread(cfg.nq, 8), extra=(np.arange(cfg.n, cfg.n + r + 1), rows[:r + 1]), tag="c5")
         ids, val = full_batch_search(sc)
-        xs = np.concatenate(new_x + bulk)
-        say("c5: spot check after the insert stream")
-        spot_check(sc, ids, val, 0, [1, 15], extra=(np.arange(cfg.n, cfg.n + len(xs)), xs))
-        st = sc.indexes[0].stats()
-        assert st.n_total == cfg.n + len(xs) and st.n_inserted == len(xs) >= 200_000 and st.device_error == 0
-        lens2 = sc.indexes[0].list_lengths()
+        say("c5: spot check after the stream")
+        spot_check(sc, ids, val, 0, list(range(cfg.nq)), extra=(np.arange(cfg.n, cfg.n + rounds), rows), tag="c5")
+        st = ix.stats()
+        assert st.n_total == cfg.n + rounds and st.n_inserted == rounds and st.device_error == 0
+        assert st.workspace_grows == grows, "the reserved workspace grew during the stream"
+        lens2 = ix.list_lengths()
         assert int(lens2.sum()) == st.n_total
+        # single inserts fill a list's last page before opening the next: no page is wasted
+        P = 128
+        assert st.pages_used == pages0 + int(np.sum((lens2 + P - 1) // P - (lens + P - 1) // P))
+        assert st.pages_used - pages0 > 1000, "the stream should have opened well over a thousand delta pages"
         grown = np.argsort(lens2 - lens)[::-1][:102]
         assert set(grown.tolist()) <= set(np.argsort(lens)[::-1][:160].tolist()), "inserts go to the largest lists"
+        report("c5")
     finally:
         sc.close()
