@@ -16,6 +16,7 @@ namespace {
 constexpr uint64_t kMagic = 0x70616e63616b6531ull;
 constexpr uint64_t kRegionBytes = 256ull << 20; // emission regions of one launch sequence (all queries together)
 constexpr int kBuildChunk = 16384;          // vectors assigned per coarse pass during the build
+constexpr int kInsertFast = 1024;           // most vectors of an insert call that takes the two-launch path
 
 #define PK_HIP(expr)                                   \
     do {                                               \
@@ -92,6 +93,9 @@ struct pk_index {
     char *ubuf;
     size_t ubuf_bytes;
     int lds_limit, num_cu;
+    // small inserts: top-1 keys of the batch (kept at ~0 between calls) and the slots the batch got
+    unsigned long long *ins_best; // DEVICE [kInsertFast]
+    uint32_t *ins_slots;          // DEVICE [kInsertFast]
     // stage timing (pk_profile_begin .. pk_profile_end)
     bool prof_on;
     std::vector<hipEvent_t> prof_ev; // 5 events per recorded launch sequence
@@ -195,6 +199,7 @@ struct Plan {
     uint32_t stride, ecap, tile_cap, span;
     uint64_t cbuf_entries; // entries of all emission regions together
     bool need_coarse, need_fine, f16;
+    bool raw_queries; // the coarse step reads the caller's query rows directly (no preparation launch)
     // buffers
     char *qs32, *qs;
     float *qn32, *qn, *S, *svals, *tlo, *tinv;
@@ -316,6 +321,8 @@ int grid_for(const pk_index *ix, int row_bytes, int mq)
     per_cu = std::max(1, std::min(per_cu, tunables().wgs));
     return ix->num_cu * per_cu;
 }
+
+bool coarse_by_gemm(uint32_t nqa, const pk_index *ix);
 
 uint32_t pow2_at_least(uint64_t v)
 {
@@ -447,6 +454,11 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
     p.nlist_max = nlist_hi;
     p.stride = (uint32_t)pad_hi;
     p.cchunks = (nlist_hi + kSelChunk - 1) / kSelChunk;
+    // Inner product over rows that need no padding: the coarse step can read the caller's queries as they
+    // are (no norms, no zero fill), unless a segment is large enough for the GEMM, which wants the prepared copy.
+    p.raw_queries = need_coarse && !worst && own->cfg.metric == PK_METRIC_IP && own->cfg.d * 4 == own->rb32;
+    for (int a = 0; a < nh && p.raw_queries; ++a)
+        if (coarse_by_gemm(qlo[a + 1] - qlo[a], hs[a])) p.raw_queries = false;
     p.ecap = emit_cap_for(own, p.K, wmax, nq);
     p.cbuf_entries = (uint64_t)nq * p.ecap;
     // a smaller batch has larger regions: none needs more in all than this
@@ -486,11 +498,18 @@ int run_coarse(const Plan &p, const MultiArgs &m, pk_index *const *hs, const flo
     qm.qagent = p.qagent;
     qm.clear = p.need_fine ? p.lcnt : nullptr;
     qm.nclear = p.need_fine ? (uint32_t)p.nh * (uint32_t)p.nlist_max : 0u;
-    PK_HIP(launch_prep_coarse(q, p.nq, own->cfg.d, own->rb32, p.qs32, p.qn32, qm, m, s));
     // small segments: one launch of the centroid kernel for all of them
     CentroidArgs ca{};
-    ca.qs = p.qs32;
-    ca.qnorm = p.qn32;
+    if (p.raw_queries) {
+        // the caller's rows are usable as they are and no norms are needed: the centroid kernel does the bookkeeping
+        ca.qs = reinterpret_cast<const char *>(q);
+        ca.qnorm = nullptr;
+        ca.meta = qm;
+    } else {
+        PK_HIP(launch_prep_coarse(q, p.nq, own->cfg.d, own->rb32, p.qs32, p.qn32, qm, m, s));
+        ca.qs = p.qs32;
+        ca.qnorm = p.qn32;
+    }
     ca.out = p.S;
     ca.stride = p.stride;
     ca.row_bytes = own->rb32;
@@ -729,6 +748,10 @@ int search_impl(pk_index *const *hs, int nh, const int64_t *q_offsets, const flo
         MultiArgs m;
         fill_multi(m, hs, nh, qlo.data());
         const float *q = queries + (size_t)q0 * d;
+        if (p.raw_queries) { // the fine step reads the same rows (fp16 indexes convert their own copy)
+            p.qs32 = const_cast<char *>(reinterpret_cast<const char *>(q));
+            if (!p.f16) p.qs = p.qs32;
+        }
         const bool timed = mode == kFull && own->prof_on && !fixed_ws; // stage timing creates events
         if (timed) PK_TRY(mark(own, s));
         if (mode == kForced) {
@@ -888,6 +911,7 @@ void destroy(pk_index *ix)
     if (!ix) return;
     if (ix->ws) (void)hipFree(ix->ws);
     if (ix->ubuf) (void)hipFree(ix->ubuf);
+    if (ix->ins_best) (void)hipFree(ix->ins_best);
     if (ix->pin_pages) (void)hipHostFree(ix->pin_pages);
     if (ix->ev) (void)hipEventDestroy(ix->ev);
     for (hipEvent_t e : ix->prof_ev) (void)hipEventDestroy(e);
@@ -948,6 +972,47 @@ int insert_batch(pk_index *const *hs, int nh, const uint32_t *qlo, const float *
 {
     pk_index *own = hs[0];
     const int64_t m = qlo[nh];
+    bool few = forced == nullptr && m <= kInsertFast; // every handle's share small enough for the fused append
+    for (int a = 0; a < nh && few; ++a)
+        few = qlo[a + 1] - qlo[a] <= (uint32_t)kFusedAppend && !coarse_by_gemm(qlo[a + 1] - qlo[a], hs[a]);
+    if (few) {
+        // Two launches (three when the rows need preparing), no workspace: the centroid kernel keeps each
+        // vector's best (score, list) by atomicMin in the handle's own small buffer, and the kernel that
+        // reserves the slots and writes the rows reads the lists from there and resets the words.
+        const bool raw = own->cfg.metric == PK_METRIC_IP && own->cfg.d * 4 == own->rb32;
+        MultiArgs mm;
+        fill_multi(mm, hs, nh, qlo);
+        CentroidArgs ca{};
+        ca.qs = reinterpret_cast<const char *>(x);
+        if (!raw) {
+            // prepared rows and norms: the head of the workspace (nothing else of a plan is needed)
+            const size_t rows = round_up((size_t)m * own->rb32, 256);
+            PK_TRY(ensure_ws(own, rows + round_up((size_t)m * 4, 256), s));
+            PK_HIP(launch_prep_queries(x, m, own->cfg.d, PK_F32, own->rb32, own->ws, reinterpret_cast<float *>(own->ws + rows), s));
+            ca.qs = own->ws;
+            ca.qnorm = reinterpret_cast<float *>(own->ws + rows);
+        }
+        ca.row_bytes = own->rb32;
+        ca.metric = own->cfg.metric;
+        ca.best = own->ins_best;
+        uint32_t longest = 0;
+        for (int a = 0; a < nh; ++a) longest = std::max(longest, qlo[a + 1] - qlo[a]);
+        ca.chunk = (int)std::min<uint32_t>(64, (longest + 15) / 16 * 16);
+        uint64_t wgs = 0;
+        for (int a = 0; a < nh; ++a) {
+            const uint32_t ma = qlo[a + 1] - qlo[a];
+            ca.blk[a] = (uint32_t)wgs;
+            if (ma > 0) wgs += (uint64_t)((ma + ca.chunk - 1) / ca.chunk) * (uint64_t)(hs[a]->nlist_pad / 16);
+        }
+        if (wgs > 0x7fffffffull) return PK_ERR_UNSUPPORTED;
+        ca.blk[nh] = (uint32_t)wgs;
+        PK_HIP(launch_centroid_scores(ca, mm, s));
+        AppendIds idc{};
+        for (int a = 0; a < nh; ++a) idc.id0[a] = hs[a]->next_id;
+        PK_HIP(launch_reserve_append(mm, idc, x, ids, nullptr, own->ins_best, own->ins_slots, assigned_out, s));
+        for (int a = 0; a < nh; ++a) PK_TRY(note_inserted(hs[a], (int64_t)(qlo[a + 1] - qlo[a]), s));
+        return PK_OK;
+    }
     Plan p;
     PK_TRY(make_plan(p, hs, nh, qlo, m, 1, 1, forced == nullptr, false));
     const size_t extra = round_up(p.bytes, 256);
@@ -966,7 +1031,7 @@ int insert_batch(pk_index *const *hs, int nh, const uint32_t *qlo, const float *
     bool small = true;
     for (int a = 0; a < nh; ++a) small = small && qlo[a + 1] - qlo[a] <= (uint32_t)kFusedAppend;
     if (small) {
-        PK_HIP(launch_reserve_append(mm, idc, x, ids, assign, slots, assigned_out, s));
+        PK_HIP(launch_reserve_append(mm, idc, x, ids, assign, nullptr, slots, assigned_out, s));
     } else {
         PK_HIP(launch_reserve(mm, assign, slots, assigned_out, s));
         PK_HIP(launch_append(mm, idc, x, ids, assign, slots, s));
@@ -1055,6 +1120,10 @@ int pk_index_build(const pk_config *cfg, const float *centroids, const float *ve
     if (hipHostMalloc(reinterpret_cast<void **>(&ix->pin_pages), 64, hipHostMallocDefault) != hipSuccess)
         return fail(PK_ERR_HIP);
     if (hipEventCreateWithFlags(&ix->ev, hipEventDisableTiming) != hipSuccess) return fail(PK_ERR_HIP);
+    if (hipMalloc(reinterpret_cast<void **>(&ix->ins_best), (size_t)kInsertFast * 12) != hipSuccess) return fail(PK_ERR_NOMEM);
+    ix->ins_slots = reinterpret_cast<uint32_t *>(ix->ins_best + kInsertFast);
+    if (launch_fill_u32(reinterpret_cast<uint32_t *>(ix->ins_best), 0xffffffffu, (size_t)kInsertFast * 2, s) != hipSuccess)
+        return fail(PK_ERR_HIP);
     {
         // set-up for pk_search_noalloc: resolve this device's copy of its workspace array now, so
         // that the call itself finds the address ready (a failure here is reported by that call)

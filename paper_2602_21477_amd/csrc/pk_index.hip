@@ -112,9 +112,9 @@ hipError_t launch_scatter_build(const DevIndex *ix, const float *x, const int64_
 // take the whole batch, nothing is changed, every slot is 0xffffffff and the sticky error
 // flag is set.  Small batches (x given): the workgroup's 16 waves also write the rows
 // (step 3), which saves the launch that would otherwise follow.
-__global__ __launch_bounds__(1024) void reserve_kernel(MultiArgs ma, const int32_t *assign, uint32_t *slots,
-                                                       int32_t *assigned_out, AppendIds idc, const float *x,
-                                                       const int64_t *ids)
+__global__ __launch_bounds__(1024) void reserve_kernel(MultiArgs ma, const int32_t *assign, unsigned long long *best,
+                                                       uint32_t *slots, int32_t *assigned_out, AppendIds idc,
+                                                       const float *x, const int64_t *ids)
 {
     __shared__ int32_t s_l[1024];
     __shared__ uint32_t s_slot[1024];
@@ -124,7 +124,7 @@ __global__ __launch_bounds__(1024) void reserve_kernel(MultiArgs ma, const int32
     const uint32_t row0 = ma.qlo[blockIdx.x];
     const int m = (int)(ma.qlo[blockIdx.x + 1] - row0);
     if (m == 0) return;
-    assign += row0;
+    if (assign) assign += row0;
     slots += row0;
     if (assigned_out) assigned_out += row0;
     const int i = threadIdx.x;
@@ -134,7 +134,12 @@ __global__ __launch_bounds__(1024) void reserve_kernel(MultiArgs ma, const int32
     }
     int32_t l = -1;
     if (i < m) {
-        l = assign[i];
+        if (assign) {
+            l = assign[i];
+        } else { // the top-1 key the centroid kernel left; reset for the next insert
+            l = (int32_t)(uint32_t)best[row0 + i];
+            best[row0 + i] = ~0ull;
+        }
         if (l < 0 || l >= ix.nlist) l = -1;
     }
     s_l[i] = l;
@@ -196,20 +201,21 @@ hipError_t launch_reserve(const MultiArgs &ma, const int32_t *assign, uint32_t *
     if (ma.n <= 0 || ma.qlo[ma.n] == 0) return hipSuccess;
     for (int a = 0; a < ma.n; ++a)
         if (ma.qlo[a + 1] - ma.qlo[a] > 1024u) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(reserve_kernel, dim3(ma.n), dim3(1024), 0, s, ma, assign, slots, assigned_out, AppendIds{}, nullptr,
-                       nullptr);
+    hipLaunchKernelGGL(reserve_kernel, dim3(ma.n), dim3(1024), 0, s, ma, assign, nullptr, slots, assigned_out, AppendIds{},
+                       nullptr, nullptr);
     return hipGetLastError();
 }
 
 // steps 2 and 3 in one launch, for batches of at most kFusedAppend vectors per handle
 hipError_t launch_reserve_append(const MultiArgs &ma, const AppendIds &idc, const float *x, const int64_t *ids,
-                                 const int32_t *assign, uint32_t *slots, int32_t *assigned_out, hipStream_t s)
+                                 const int32_t *assign, unsigned long long *best, uint32_t *slots, int32_t *assigned_out,
+                                 hipStream_t s)
 {
     if (ma.n <= 0 || ma.qlo[ma.n] == 0) return hipSuccess;
-    if (!x) return hipErrorInvalidValue;
+    if (!x || (!assign && !best)) return hipErrorInvalidValue;
     for (int a = 0; a < ma.n; ++a)
         if (ma.qlo[a + 1] - ma.qlo[a] > (uint32_t)kFusedAppend) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(reserve_kernel, dim3(ma.n), dim3(1024), 0, s, ma, assign, slots, assigned_out, idc, x, ids);
+    hipLaunchKernelGGL(reserve_kernel, dim3(ma.n), dim3(1024), 0, s, ma, assign, best, slots, assigned_out, idc, x, ids);
     return hipGetLastError();
 }
 

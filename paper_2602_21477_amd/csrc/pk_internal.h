@@ -374,6 +374,13 @@ struct CentroidArgs {
     int row_bytes, metric;
     int chunk;           // queries per workgroup: 16, 32, 48 or 64
     uint32_t blk[PK_MAX_HANDLES + 1]; // first workgroup of handle a, [n] = all; a handle scored elsewhere owns none
+    // Optional extras that save a launch each on small batches:
+    //   meta.cand_off != null: this kernel also does the per-query bookkeeping of the coarse step and clears
+    //   the words in meta.clear (qs then are the caller's own rows: no padding needed, no norms for inner product);
+    //   best != null: instead of writing scores, every query keeps its best (score key << 32 | list) by
+    //   atomicMin (top-1 assignment of inserts; best[] must hold ~0 on entry).
+    QueryMeta meta;
+    unsigned long long *best;
 };
 hipError_t launch_centroid_scores(const CentroidArgs &a, const MultiArgs &m, hipStream_t s);
 
@@ -506,7 +513,9 @@ struct AppendIds {
 hipError_t launch_reserve(const MultiArgs &ma, const int32_t *assign, uint32_t *slots, int32_t *assigned_out, hipStream_t s);
 hipError_t launch_append(const MultiArgs &ma, const AppendIds &idc, const float *x, const int64_t *ids,
                          const int32_t *assign, const uint32_t *slots, hipStream_t s);
+// assign == null: the lists are the low words of best[] (left by the centroid kernel), which is reset to ~0
 hipError_t launch_reserve_append(const MultiArgs &ma, const AppendIds &idc, const float *x, const int64_t *ids,
-                                 const int32_t *assign, uint32_t *slots, int32_t *assigned_out, hipStream_t s);
+                                 const int32_t *assign, unsigned long long *best, uint32_t *slots, int32_t *assigned_out,
+                                 hipStream_t s);
 
 } // namespace pk

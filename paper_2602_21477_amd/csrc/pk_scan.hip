@@ -524,6 +524,16 @@ __global__ __launch_bounds__(256) void centroid_scores_kernel(CentroidArgs a, Mu
     const int nit = row_bytes / kIterBytes;
     const int per = (nit + 3) / 4;
     const int it0 = wave * per, it1 = it0 + per < nit ? it0 + per : nit;
+    if (a.meta.cand_off) {
+        // bookkeeping of the coarse step (otherwise done while the queries are prepared)
+        for (uint32_t i = blockIdx.x * blockDim.x + tid; i < a.meta.nclear; i += gridDim.x * blockDim.x) a.meta.clear[i] = 0u;
+        if (cb == 0 && (uint32_t)tid < qcnt) {
+            const uint32_t t = q0 + (uint32_t)tid;
+            a.meta.cand_off[t] = t * a.meta.stride;
+            a.meta.cand_cnt[t] = (uint32_t)ix.nlist;
+            a.meta.qagent[t] = (uint16_t)h;
+        }
+    }
 
     const char *xp = reinterpret_cast<const char *>(ix.cent) + (size_t)(cb * 16u + ln) * row_bytes + lg * 16;
     const char *qp[MT];
@@ -579,7 +589,27 @@ __global__ __launch_bounds__(256) void centroid_scores_kernel(CentroidArgs a, Mu
         if (slot >= qcnt || c >= (uint32_t)ix.nlist) continue;
         float v = (s_red[0][mt][i][lane] + s_red[1][mt][i][lane]) + (s_red[2][mt][i][lane] + s_red[3][mt][i][lane]);
         if (a.metric == PK_METRIC_L2) v = fmaxf(cn - 2.f * v + a.qnorm[q0 + slot], 0.f);
-        a.out[(size_t)(q0 + slot) * a.stride + c] = v;
+        if (!a.best) a.out[(size_t)(q0 + slot) * a.stride + c] = v;
+    }
+    if (a.best) {
+        // top-1: the 16 lanes of a group hold 16 centroids of one query; the best of them goes to the
+        // query's word (ties to the lower list number: the key's low word)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const uint32_t slot = (uint32_t)(mt * 16 + lg * 4 + i);
+            unsigned long long key = ~0ull;
+            if (slot < qcnt && c < (uint32_t)ix.nlist) {
+                float v = (s_red[0][mt][i][lane] + s_red[1][mt][i][lane]) + (s_red[2][mt][i][lane] + s_red[3][mt][i][lane]);
+                if (a.metric == PK_METRIC_L2) v = fmaxf(cn - 2.f * v + a.qnorm[q0 + slot], 0.f);
+                key = ((unsigned long long)order_bits(v, a.metric) << 32) | c;
+            }
+#pragma unroll
+            for (int off = 1; off < 16; off <<= 1) {
+                const unsigned long long o = __shfl_xor(key, off);
+                key = o < key ? o : key;
+            }
+            if (ln == 0 && slot < qcnt && key != ~0ull) atomicMin(a.best + q0 + slot, key);
+        }
     }
 }
 

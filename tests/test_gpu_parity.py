@@ -875,8 +875,9 @@ def test_overflowing_emission_regions_are_rescored(gpu_device):
 
 def test_tie_group_larger_than_the_emission_region(gpu_device):
     """3000 exact copies of one vector (scrambled ids, some ids carried twice) in one list: every copy
-    passes any threshold, the region (2048 entries for k = 10) overflows by itself, and the k lowest
-    ids of the tie group must come back, as in the oracle's sort."""
+    passes any threshold, a region of 2048 entries (what a large batch gets for k = 10; set by hand here,
+    a batch of three queries would get more) overflows by itself, and the k lowest ids of the tie group
+    must come back, as in the oracle's sort."""
     rng = np.random.default_rng(26)
     n, d = 12000, 64
     x = rng.standard_normal((n, d)).astype(np.float32)
@@ -889,14 +890,14 @@ def test_tie_group_larger_than_the_emission_region(gpu_device):
     q = np.stack([x[dup[0]], x[5], x[dup[0]] * 0.5])
     for metric in (IP, L2):
         p = Pair(x, cent, metric, F32, ids=ids)
+        B.pk_index_set_emit_cap(p.gpu.handle, 2048)
         try:
             for k in (1, 10, 64):
                 say(f"tie group metric={metric} k={k}")
                 B.pk_profile_begin(p.gpu.handle)
                 gi, gv = p.gpu.search(dev(q), k, 8)
                 pr = B.pk_profile_end(p.gpu.handle)
-                if k <= 10:  # region of 2048 entries; for k = 64 it has 4096 and holds the whole group
-                    assert pr.overflowed >= 2, pr.overflowed
+                assert pr.overflowed >= 2, pr.overflowed
                 gi, gv = gi.cpu().numpy(), gv.cpu().numpy()
                 oi, ov = p.orc.search(q, k, 8)
                 want = sorted(ids[dup].tolist())[:k]
