@@ -200,6 +200,7 @@ struct Plan {
     uint64_t cbuf_entries; // entries of all emission regions together
     bool need_coarse, need_fine, f16;
     bool raw_queries; // the coarse step reads the caller's query rows directly (no preparation launch)
+    bool wl_small;    // the second half of the work list is small enough for one workgroup (rides in the threshold launch)
     // buffers
     char *qs32, *qs;
     float *qn32, *qn, *S, *svals, *tlo, *tinv;
@@ -236,9 +237,9 @@ void carve(Plan &p, char *base, const pk_index *own)
     }
     if (p.need_fine) {
         const size_t nl = (size_t)p.nh * p.nlist_max;
-        p.lcnt = c.take<uint32_t>(nl);
+        p.lcnt = c.take<uint32_t>(2 * nl); // pair counters, then the fill marks: cleared together
+        p.lfill = p.lcnt ? p.lcnt + nl : nullptr;
         p.lstart = c.take<uint32_t>(nl);
-        p.lfill = c.take<uint32_t>(nl);
         p.ltile = c.take<uint32_t>(nl);
         p.lhtile = c.take<uint32_t>(nl);
         p.pair_off = c.take<uint32_t>(nq * (p.nprobe + 1));
@@ -459,6 +460,8 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
     p.raw_queries = need_coarse && !worst && own->cfg.metric == PK_METRIC_IP && own->cfg.d * 4 == own->rb32;
     for (int a = 0; a < nh && p.raw_queries; ++a)
         if (coarse_by_gemm(qlo[a + 1] - qlo[a], hs[a])) p.raw_queries = false;
+    // few lists, pairs and tiles: the threshold kernel's workgroups lay out slots and tiles as well (see wl_spread)
+    p.wl_small = (uint64_t)nh * (uint64_t)nlist_hi <= kWlSmallLists && (uint64_t)nq * (uint64_t)nprobe <= 16384 && tiles <= 65536;
     p.ecap = emit_cap_for(own, p.K, wmax, nq);
     p.cbuf_entries = (uint64_t)nq * p.ecap;
     // a smaller batch has larger regions: none needs more in all than this
@@ -487,9 +490,67 @@ void fill_multi(MultiArgs &m, pk_index *const *hs, int nh, const uint32_t *qlo)
     m.qlo[nh] = qlo[nh];
 }
 
-// Coarse search of one batch: probes[nq][nprobe] in the plan's workspace.
-int run_coarse(const Plan &p, const MultiArgs &m, pk_index *const *hs, const float *q, hipStream_t s)
+// Arguments of the work-list construction and of the threshold sample of one launch sequence.
+void fill_worklist_args(const Plan &p, const pk_index *own, WorklistArgs &w, SampleArgs &sm)
 {
+    // threshold sampling: k-th best of the first pages of each query's first probed list
+    sm = SampleArgs{};
+    sm.probes = p.probes;
+    sm.qagent = p.qagent;
+    sm.nq = p.nq;
+    sm.nprobe = p.nprobe;
+    sm.sp = p.sp;
+    sm.k = p.k;
+    sm.metric = own->cfg.metric;
+    sm.scan_grid = p.grid_s;
+    sm.span = p.span;
+    sm.tiles = p.stiles;
+    sm.slot_query = p.sslot_q;
+    sm.slot_out = p.sslot_o;
+    sm.vals = p.svals;
+    sm.scalars = p.scalars + 8;
+    sm.tau = p.tau;
+    sm.tlo = p.tlo;
+    sm.tinv = p.tinv;
+    sm.tcur = p.tcur;
+    sm.hist = p.hist;
+    w = WorklistArgs{};
+    w.probes = p.probes;
+    w.qagent = p.qagent;
+    w.nq = p.nq;
+    w.nprobe = p.nprobe;
+    w.n_handles = p.nh;
+    w.nlist_max = p.nlist_max;
+    w.mq = p.mq_f;
+    w.mq_hot = p.mq_h;
+    w.hot_from = p.hot_from;
+    w.hot_rows = p.hot_rs ? kRrTileRows : 0;
+    w.scan_grid = p.grid_f;
+    w.scan_grid_hot = p.grid_h;
+    w.grab_div = tunables().grabdiv;
+    w.hot_grab = tunables().hot_grab;
+    w.lcnt = p.lcnt;
+    w.lstart = p.lstart;
+    w.lfill = p.lfill;
+    w.ltile = p.ltile;
+    w.lhtile = p.lhtile;
+    w.pair_off = p.pair_off;
+    w.ccnt = p.ccnt;
+    w.slot_query = p.slot_q;
+    w.slot_out = p.slot_o;
+    w.tiles = p.tiles;
+    w.tiles_hot = p.tiles_hot;
+    w.tile_cap = p.tile_cap;
+    w.scalars = p.scalars + 4;
+    w.scalars_hot = p.scalars + 12;
+    w.lcnt_cleared = p.need_coarse;
+}
+
+// Coarse search of one batch: probes[nq][nprobe] in the plan's workspace.
+// counted (optional): set when the selection also did the first half of the work-list construction for the fine step.
+int run_coarse(const Plan &p, const MultiArgs &m, pk_index *const *hs, const float *q, hipStream_t s, bool *counted = nullptr)
+{
+    if (counted) *counted = false;
     const pk_index *own = hs[0];
     QueryMeta qm{};
     qm.stride = p.stride;
@@ -497,7 +558,7 @@ int run_coarse(const Plan &p, const MultiArgs &m, pk_index *const *hs, const flo
     qm.cand_cnt = p.cand_cnt;
     qm.qagent = p.qagent;
     qm.clear = p.need_fine ? p.lcnt : nullptr;
-    qm.nclear = p.need_fine ? (uint32_t)p.nh * (uint32_t)p.nlist_max : 0u;
+    qm.nclear = p.need_fine ? 2u * (uint32_t)p.nh * (uint32_t)p.nlist_max : 0u; // and the fill marks behind them
     // small segments: one launch of the centroid kernel for all of them
     CentroidArgs ca{};
     if (p.raw_queries) {
@@ -550,6 +611,16 @@ int run_coarse(const Plan &p, const MultiArgs &m, pk_index *const *hs, const flo
         PK_HIP(launch_gemm_scores(g, s));
     }
     if (p.nlist_max <= kDenseSelectMax && tunables().densesel) {
+        if (counted && p.need_fine) {
+            // the selection's workgroups go on to count their queries' pairs and lay out the sample
+            WorklistArgs w;
+            SampleArgs sm;
+            fill_worklist_args(p, own, w, sm);
+            PK_HIP(launch_select_dense(p.S, p.cand_off, p.cand_cnt, (uint32_t)p.nlist_max, own->cfg.metric, p.nprobe, p.nq,
+                                       p.probes, s, &w, &sm, &m));
+            *counted = true;
+            return PK_OK;
+        }
         PK_HIP(launch_select_dense(p.S, p.cand_off, p.cand_cnt, (uint32_t)p.nlist_max, own->cfg.metric, p.nprobe, p.nq,
                                    p.probes, s));
         return PK_OK;
@@ -570,61 +641,13 @@ int run_coarse(const Plan &p, const MultiArgs &m, pk_index *const *hs, const flo
 
 // Fine search of one batch over p.probes.
 int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, int64_t *out_ids, float *out_dist,
-             hipStream_t s, bool timed)
+             hipStream_t s, bool timed, bool counted)
 {
     if (p.f16) PK_HIP(launch_prep_queries(q, p.nq, own->cfg.d, PK_F16, own->row_bytes, p.qs, p.qn, s));
-    // threshold sampling: k-th best of the first pages of each query's first probed list
-    SampleArgs sm{};
-    sm.probes = p.probes;
-    sm.qagent = p.qagent;
-    sm.nq = p.nq;
-    sm.nprobe = p.nprobe;
-    sm.sp = p.sp;
-    sm.k = p.k;
-    sm.metric = own->cfg.metric;
-    sm.scan_grid = p.grid_s;
-    sm.span = p.span;
-    sm.tiles = p.stiles;
-    sm.slot_query = p.sslot_q;
-    sm.slot_out = p.sslot_o;
-    sm.vals = p.svals;
-    sm.scalars = p.scalars + 8;
-    sm.tau = p.tau;
-    sm.tlo = p.tlo;
-    sm.tinv = p.tinv;
-    sm.tcur = p.tcur;
-    sm.hist = p.hist;
-    WorklistArgs w{};
-    w.probes = p.probes;
-    w.qagent = p.qagent;
-    w.nq = p.nq;
-    w.nprobe = p.nprobe;
-    w.n_handles = p.nh;
-    w.nlist_max = p.nlist_max;
-    w.mq = p.mq_f;
-    w.mq_hot = p.mq_h;
-    w.hot_from = p.hot_from;
-    w.hot_rows = p.hot_rs ? kRrTileRows : 0;
-    w.scan_grid = p.grid_f;
-    w.scan_grid_hot = p.grid_h;
-    w.grab_div = tunables().grabdiv;
-    w.hot_grab = tunables().hot_grab;
-    w.lcnt = p.lcnt;
-    w.lstart = p.lstart;
-    w.lfill = p.lfill;
-    w.ltile = p.ltile;
-    w.lhtile = p.lhtile;
-    w.pair_off = p.pair_off;
-    w.ccnt = p.ccnt;
-    w.slot_query = p.slot_q;
-    w.slot_out = p.slot_o;
-    w.tiles = p.tiles;
-    w.tiles_hot = p.tiles_hot;
-    w.tile_cap = p.tile_cap;
-    w.scalars = p.scalars + 4;
-    w.scalars_hot = p.scalars + 12;
-    w.lcnt_cleared = p.need_coarse;
-    PK_HIP(launch_worklist_count(w, sm, m, s));
+    WorklistArgs w;
+    SampleArgs sm;
+    fill_worklist_args(p, own, w, sm);
+    if (!counted) PK_HIP(launch_worklist_count(w, sm, m, s));
     ScanArgs ss{};
     ss.tiles = p.stiles;
     ss.ntiles = p.scalars + 8;
@@ -640,9 +663,12 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
     ss.storage = own->cfg.storage;
     ss.mq = kSampleSlots;
     PK_HIP(launch_scan(ss, p.grid_s, s));
-    PK_HIP(launch_tau(sm, s));
-
-    PK_HIP(launch_worklist_tiles(w, m, s));
+    if (p.wl_small) {
+        PK_HIP(launch_tau(sm, s, &w, &m)); // its workgroups also lay out the slots and tiles of the work list
+    } else {
+        PK_HIP(launch_tau(sm, s));
+        PK_HIP(launch_worklist_tiles(w, m, s));
+    }
     if (timed) PK_TRY(mark(own, s));
     ScanArgs sa{};
     sa.tiles = p.tiles;
@@ -658,7 +684,9 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
     sa.tlo = p.tlo;
     sa.tinv = p.tinv;
     sa.tcur = p.tcur;
-    sa.use_hist = tunables().hist;
+    // The running per-query histogram tightens the gate while a query's tiles follow one another; when every
+    // tile of the call runs at once (at most one per workgroup of the grid) it can only cost time.
+    sa.use_hist = tunables().hist && p.tile_cap > (uint32_t)p.grid_f;
     sa.hist = p.hist;
     sa.k = p.k;
     sa.ecap = p.ecap;
@@ -754,18 +782,19 @@ int search_impl(pk_index *const *hs, int nh, const int64_t *q_offsets, const flo
         }
         const bool timed = mode == kFull && own->prof_on && !fixed_ws; // stage timing creates events
         if (timed) PK_TRY(mark(own, s));
+        bool counted = false;
         if (mode == kForced) {
             PK_TRY(set_single_agent(p, s));
             PK_HIP(launch_copy_i32(forced + (size_t)q0 * nprobe, p.probes, nq * nprobe, s));
             if (!p.f16) PK_HIP(launch_prep_queries(q, nq, d, PK_F32, own->rb32, p.qs32, p.qn32, s));
         } else {
-            PK_TRY(run_coarse(p, m, hs, q, s));
+            PK_TRY(run_coarse(p, m, hs, q, s, &counted));
         }
         if (timed) PK_TRY(mark(own, s));
         if (mode == kCoarseOnly) {
             PK_HIP(launch_copy_i32(p.probes, out_probes + (size_t)q0 * nprobe, nq * nprobe, s));
         } else {
-            PK_TRY(run_fine(p, m, own, q, out_ids + (size_t)q0 * k, out_dist + (size_t)q0 * k, s, timed));
+            PK_TRY(run_fine(p, m, own, q, out_ids + (size_t)q0 * k, out_dist + (size_t)q0 * k, s, timed, counted));
         }
     }
     return PK_OK;

@@ -8,6 +8,24 @@
 
 #include "pancake.h"
 
+// Development builds (-DPK_DEV_TIMING) record the wall clock of workgroup 0's first thread at marked
+// points of a kernel; a release build holds none of this.
+#ifdef PK_DEV_TIMING
+#define PK_DEV_MARKS(name)                                                                      \
+    static __device__ unsigned long long name##_marks[64];                                      \
+    extern "C" int pk_dev_##name##_marks(unsigned long long *out)                              \
+    {                                                                                           \
+        return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(name##_marks), sizeof(name##_marks));   \
+    }
+#define PK_MARK(name, i)                                                                        \
+    do {                                                                                        \
+        if (blockIdx.x == 0 && threadIdx.x == 0) name##_marks[i] = wall_clock64();              \
+    } while (0)
+#else
+#define PK_DEV_MARKS(name)
+#define PK_MARK(name, i) do { } while (0)
+#endif
+
 namespace pk {
 
 // ------------------------------------------------------------------ constants
@@ -331,9 +349,9 @@ struct SelectArgs {
     unsigned long long *partial;  // [nq][nchunks][K]
 };
 hipError_t launch_select_partial(const SelectArgs &a, int64_t nq, hipStream_t s);
+constexpr uint32_t kWlSmallLists = 2048; // most lists (all handles of a call) whose work list is laid out inside another kernel's launch
 constexpr int kDenseSelectMax = 8192; // longest score row the register-resident selection takes
-hipError_t launch_select_dense(const float *vals, const uint32_t *qoff, const uint32_t *qcnt, uint32_t max_cnt, int metric,
-                               int K, int64_t nq, int32_t *probes, hipStream_t s);
+
 hipError_t launch_select_probes(const unsigned long long *partial, int nchunks, int K, int nprobe, int64_t nq,
                                 int32_t *probes, hipStream_t s);
 
@@ -455,7 +473,12 @@ struct SampleArgs {
 };
 hipError_t launch_worklist_count(const WorklistArgs &a, const SampleArgs &sm, const MultiArgs &m, hipStream_t s);
 hipError_t launch_worklist_tiles(const WorklistArgs &a, const MultiArgs &m, hipStream_t s);
-hipError_t launch_tau(const SampleArgs &a, hipStream_t s);
+// wa / ma given (small batches): the launch also builds the second half of the work list (launch_worklist_tiles is not needed)
+hipError_t launch_tau(const SampleArgs &a, hipStream_t s, const WorklistArgs *wa = nullptr, const MultiArgs *ma = nullptr);
+// wa / sm / ma given: the selection's workgroups also do launch_worklist_count's work for their queries
+hipError_t launch_select_dense(const float *vals, const uint32_t *qoff, const uint32_t *qcnt, uint32_t max_cnt, int metric,
+                               int K, int64_t nq, int32_t *probes, hipStream_t s, const WorklistArgs *wa = nullptr,
+                               const SampleArgs *sm = nullptr, const MultiArgs *ma = nullptr);
 
 // dense coarse scoring on the matrix cores (large query batches, build)
 struct GemmArgs {

@@ -25,6 +25,7 @@
 // centroid_scores_kernel is the coarse step for small query segments (the same operand
 // layout, no LDS staging); large segments go through the GEMM in pk_gemm.hip.
 #include "pk_internal.h"
+PK_DEV_MARKS(scan)
 
 namespace pk {
 
@@ -136,40 +137,113 @@ __device__ __forceinline__ void refresh_slot(const ScanArgs &a, const Slots &s, 
     }
 }
 
-// Gated emission, the part after the threshold test: some lane of the wave holds a value
-// that passed its slot's sample threshold (pass).  The 16 lanes of a group share slot m;
-// position = the row's position in its list.  Wave-uniform call.
-__device__ __forceinline__ void emit_survivors(const ScanArgs &a, const Slots &s, float v, uint32_t bits, bool pass, int m,
-                                               uint32_t position, int ln, int lg)
+// Gated emission of one 32-row block.  The lane holds, for each of its 4 * MT slots m, the values of
+// rows r0 (nt = 0) and r0 + 16 (nt = 1); the 16 lanes of a group share slot m.  Room in the query's
+// region is reserved with one atomic per slot and group; all of a block's reservations are issued
+// before the first answer is used, so a block pays one round trip to the counters, not one per slot.
+template <int MT>
+__device__ __forceinline__ void emit_block(const ScanArgs &a, const Slots &s, f32x4 (&acc)[MT][2], int rb, int ln, int lg,
+                                           int nrows, uint32_t qcnt, uint32_t row0, gfloats txn)
 {
-    uint32_t b = 0;
-    if (pass) {
-        b = bucket_of(v, s.lo[m], s.inv[m], a.metric);
-        pass = b <= s.bmax[m];
+    constexpr int MQ = MT * 16;
+    const int r0 = rb * kRowBlock + ln, r1 = r0 + 16;
+    const bool live0 = r0 < nrows, live1 = r1 < nrows;
+    float xn0 = 0.f, xn1 = 0.f;
+    if (a.metric == PK_METRIC_L2) {
+        if (live0) xn0 = txn[r0];
+        if (live1) xn1 = txn[r1];
     }
-    const unsigned long long mask = __ballot(pass);
-    const uint32_t gmask = (uint32_t)(mask >> (lg * 16)) & 0xffffu;
-    if (gmask) {
-        // one aggregated atomic per group reserves room in the query's region
-        const int leader = __ffs(gmask) - 1;
-        uint32_t base = 0;
-        if (ln == leader) base = atomicAdd(&a.ccnt[s.q[m]], (uint32_t)__popc(gmask));
-        base = __shfl(base, lg * 16 + leader);
-        if (pass) {
-            // a region that is full keeps counting (the selection then rescores the query) but stores nothing
-            const uint32_t at = base + __popc(gmask & ((1u << ln) - 1u));
-            if (at < a.ecap) a.cbuf[(size_t)s.base[m] + at] = ((unsigned long long)bits << 32) | (s.out[m] + position);
+    auto value = [&](int mt, int nt, int i) {
+        float v = acc[mt][nt][i];
+        if (a.metric == PK_METRIC_L2) v = l2_from_dot(nt ? xn1 : xn0, v, s.qn[(mt * 16 + lg * 4 + i) & (MQ - 1)]);
+        return v;
+    };
+    // survivors are rare: one ballot decides whether the wave goes on to emit
+    uint32_t cand = 0; // bit 2 * (mt * 4 + i) + nt
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        if ((uint32_t)(mt * 16) >= qcnt) break; // wave-uniform
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int m = mt * 16 + lg * 4 + i;
+            const bool on = (uint32_t)m < qcnt;
+            const uint32_t thr = s.thr[m];
+            const bool p0 = live0 && on && order_bits(value(mt, 0, i), a.metric) <= thr;
+            const bool p1 = live1 && on && order_bits(value(mt, 1, i), a.metric) <= thr;
+            cand |= ((uint32_t)p0 | ((uint32_t)p1 << 1)) << (2 * (mt * 4 + i));
         }
-        if (a.use_hist) {
-            // count the emitted candidates per bucket; one atomic for the group
-            // when its candidates share a bucket (the usual case)
-            const uint32_t b0 = __shfl(b, lg * 16 + leader);
-            const uint32_t odd = (uint32_t)(__ballot(pass && b != b0) >> (lg * 16)) & 0xffffu;
-            uint32_t *hq = a.hist + (size_t)s.q[m] * kHistBins;
-            if (odd == 0u) {
-                if (ln == leader) atomicAdd(hq + b0, (uint32_t)__popc(gmask));
-            } else if (pass) {
-                atomicAdd(hq + b, 1u);
+    }
+    if (__ballot(cand != 0u) == 0ull) return; // the usual case: nothing survives
+
+    uint32_t base[MT * 4], groups[MT * 4]; // answer of the reservation; the group's survivors (nt = 0 low half)
+    uint32_t any = 0;                      // wave-uniform: slots j with a survivor somewhere in the wave
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int j = mt * 4 + i, m = mt * 16 + lg * 4 + i;
+            base[j] = 0;
+            groups[j] = 0;
+            if (__ballot(((cand >> (2 * j)) & 3u) != 0u) == 0ull) continue;
+            bool p[2];
+            uint32_t b[2] = {0u, 0u};
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) {
+                p[nt] = ((cand >> (2 * j + nt)) & 1u) != 0u;
+                if (p[nt]) { // the bucket limit tightens while the scan runs
+                    b[nt] = bucket_of(value(mt, nt, i), s.lo[m], s.inv[m], a.metric);
+                    p[nt] = b[nt] <= s.bmax[m];
+                }
+            }
+            const uint32_t g0 = (uint32_t)(__ballot(p[0]) >> (lg * 16)) & 0xffffu;
+            const uint32_t g1 = (uint32_t)(__ballot(p[1]) >> (lg * 16)) & 0xffffu;
+            groups[j] = g0 | (g1 << 16);
+            if (__ballot(groups[j] != 0u) == 0ull) continue;
+            any |= 1u << j;
+            if (groups[j] != 0u) {
+                if (ln == 0) base[j] = atomicAdd(&a.ccnt[s.q[m]], (uint32_t)__popc(groups[j]));
+                if (a.use_hist) {
+                    // count the emitted candidates per bucket; one atomic for the group's rows of one
+                    // half when they share a bucket (the usual case)
+                    uint32_t *hq = a.hist + (size_t)s.q[m] * kHistBins;
+#pragma unroll
+                    for (int nt = 0; nt < 2; ++nt) {
+                        const uint32_t g = nt ? g1 : g0;
+                        if (g == 0u) continue; // uniform over the group
+                        const int leader = __ffs(g) - 1;
+                        const uint32_t b0 = __shfl(b[nt], lg * 16 + leader);
+                        const uint32_t odd = (uint32_t)(__ballot(p[nt] && b[nt] != b0) >> (lg * 16)) & 0xffffu;
+                        if (odd == 0u) {
+                            if (ln == leader) atomicAdd(hq + b0, (uint32_t)__popc(g));
+                        } else if (p[nt]) {
+                            atomicAdd(hq + b[nt], 1u);
+                        }
+                    }
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int j = mt * 4 + i, m = mt * 16 + lg * 4 + i;
+            if (((any >> j) & 1u) == 0u) continue; // wave-uniform
+            const uint32_t first = __shfl(base[j], lg * 16);
+            const uint32_t g0 = groups[j] & 0xffffu, g1 = groups[j] >> 16;
+            const uint32_t below = (1u << ln) - 1u;
+            // a region that is full keeps counting (the selection then rescores the query) but stores nothing
+            if ((g0 >> ln) & 1u) {
+                const uint32_t at = first + __popc(g0 & below);
+                if (at < a.ecap)
+                    a.cbuf[(size_t)s.base[m] + at] = ((unsigned long long)order_bits(value(mt, 0, i), a.metric) << 32) |
+                                                     (s.out[m] + row0 + (uint32_t)r0);
+            }
+            if ((g1 >> ln) & 1u) {
+                const uint32_t at = first + __popc(g0) + __popc(g1 & below);
+                if (at < a.ecap)
+                    a.cbuf[(size_t)s.base[m] + at] = ((unsigned long long)order_bits(value(mt, 1, i), a.metric) << 32) |
+                                                     (s.out[m] + row0 + (uint32_t)r1);
             }
         }
     }
@@ -181,31 +255,27 @@ template <int MT, bool GATED>
 __device__ __forceinline__ void finish_block(const ScanArgs &a, const Slots &s, f32x4 (&acc)[MT][2], int rb, int ln, int lg,
                                              int nrows, uint32_t qcnt, uint32_t row0, gfloats txn)
 {
-    constexpr int MQ = MT * 16;
-    const float worst = a.metric == PK_METRIC_IP ? -INFINITY : INFINITY;
-    const int nrows_pad = (nrows + 15) & ~15;
+    if constexpr (GATED) {
+        emit_block<MT>(a, s, acc, rb, ln, lg, nrows, qcnt, row0, txn);
+    } else {
+        constexpr int MQ = MT * 16;
+        const float worst = a.metric == PK_METRIC_IP ? -INFINITY : INFINITY;
+        const int nrows_pad = (nrows + 15) & ~15;
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
-        const int row = rb * kRowBlock + nt * 16 + ln;
-        const bool live = row < nrows;
-        float xn = 0.f;
-        if (a.metric == PK_METRIC_L2 && live) xn = txn[row];
+        for (int nt = 0; nt < 2; ++nt) {
+            const int row = rb * kRowBlock + nt * 16 + ln;
+            const bool live = row < nrows;
+            float xn = 0.f;
+            if (a.metric == PK_METRIC_L2 && live) xn = txn[row];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            if ((uint32_t)(mt * 16) >= qcnt) break; // wave-uniform
+            for (int mt = 0; mt < MT; ++mt) {
+                if ((uint32_t)(mt * 16) >= qcnt) break; // wave-uniform
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int m = mt * 16 + lg * 4 + i;
-                float v = acc[mt][nt][i];
-                if (a.metric == PK_METRIC_L2) v = l2_from_dot(xn, v, s.qn[m & (MQ - 1)]);
-                if constexpr (!GATED) {
+                for (int i = 0; i < 4; ++i) {
+                    const int m = mt * 16 + lg * 4 + i;
+                    float v = acc[mt][nt][i];
+                    if (a.metric == PK_METRIC_L2) v = l2_from_dot(xn, v, s.qn[m & (MQ - 1)]);
                     if ((uint32_t)m < qcnt && row < nrows_pad) a.out[(size_t)s.out[m] + row0 + row] = live ? v : worst;
-                } else {
-                    // survivors are rare: one ballot decides whether the wave goes on to emit
-                    const uint32_t bits = order_bits(v, a.metric);
-                    const bool pass = live && (uint32_t)m < qcnt && bits <= s.thr[m];
-                    if (__ballot(pass) == 0ull) continue; // the usual case: nothing survives
-                    emit_survivors(a, s, v, bits, pass, m, row0 + (uint32_t)row, ln, lg);
                 }
             }
         }
@@ -241,6 +311,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(3, 8
     uint32_t cur_qbeg = 0xffffffffu, cur_qcnt = 0;
     const char *qbase = qtile + (size_t)(ln < qrows ? ln : qrows) * qstride + lg * 16;
 
+    PK_MARK(scan, GATED ? 0 : 8);
     Sched sc;
     sc.start(*a.ntiles, *a.batch);
     if (sc.t >= sc.ntiles) return;
@@ -249,6 +320,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(3, 8
         const gbytes tx = in_global(cur.x);
         const gfloats txn = in_global(cur.xn);
         const uint32_t row0 = cur.row0;
+        PK_MARK(scan, GATED ? 1 : 9);
         const uint32_t qbeg = __builtin_amdgcn_readfirstlane(cur.qbeg);
         const uint32_t qcnt = __builtin_amdgcn_readfirstlane((uint32_t)cur.qcnt);
         const int nrows = __builtin_amdgcn_readfirstlane((int)cur.nrows);
@@ -295,13 +367,30 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(3, 8
         if (qbeg != cur_qbeg || qcnt != cur_qcnt) {
             __syncthreads(); // everyone is done with the previous query group
             const int mrows = qrows < MQ ? qheld : (int)((qcnt + 15u) & ~15u); // rows past the group's last: zeros
-            for (int idx = tid; idx < mrows * chunks_per_row; idx += WAVES * 64) {
-                const int m = idx / chunks_per_row, c = idx - m * chunks_per_row;
-                u32x4 v = {0u, 0u, 0u, 0u};
-                if ((uint32_t)m < qcnt)
-                    v = *reinterpret_cast<const u32x4 *>(a.qs + (size_t)a.slot_query[qbeg + m] * row_bytes +
-                                                         (size_t)c * 16);
-                *reinterpret_cast<u32x4 *>(qtile + (size_t)m * qstride + (size_t)c * 16) = v;
+            // four pieces per thread at a time: their slot numbers first, then the four row pieces, so that
+            // a round costs two trips to memory however many pieces it moves
+            const int total = mrows * chunks_per_row;
+            for (int idx0 = tid; idx0 < total; idx0 += 4 * WAVES * 64) {
+                int mm[4], cc[4];
+                uint32_t sq[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int idx = idx0 + u * WAVES * 64;
+                    mm[u] = idx / chunks_per_row;
+                    cc[u] = idx - mm[u] * chunks_per_row;
+                    sq[u] = idx < total && (uint32_t)mm[u] < qcnt ? a.slot_query[qbeg + mm[u]] : 0xffffffffu;
+                }
+                u32x4 v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    v[u] = u32x4{0u, 0u, 0u, 0u};
+                    if (sq[u] != 0xffffffffu)
+                        v[u] = *reinterpret_cast<const u32x4 *>(a.qs + (size_t)sq[u] * row_bytes + (size_t)cc[u] * 16);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (idx0 + u * WAVES * 64 < total)
+                        *reinterpret_cast<u32x4 *>(qtile + (size_t)mm[u] * qstride + (size_t)cc[u] * 16) = v[u];
             }
             load_slots<MQ, GATED>(a, s, tid, qbeg, qcnt);
             __syncthreads();
@@ -312,6 +401,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(3, 8
             __syncthreads();
         }
         const int mt_used = (int)((qcnt + 15u) >> 4);
+        PK_MARK(scan, GATED ? 2 : 10);
 
         for (; rb * kRowBlock < nrows; rb += WAVES) {
             f32x4 acc[MT][2];
@@ -331,7 +421,9 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(3, 8
                 if (it + 2 < nit) { PK_LOAD(xa, it + 2) }
                 if (it + 1 < nit) { PK_COMPUTE(xb, it + 1) }
             }
+            PK_MARK(scan, GATED ? 3 : 11);
             finish_block<MT, GATED>(a, s, acc, rb, ln, lg, nrows, qcnt, row0, txn);
+            PK_MARK(scan, GATED ? 4 : 12);
         }
 #undef PK_ROWS
 #undef PK_LOAD
@@ -524,17 +616,6 @@ __global__ __launch_bounds__(256) void centroid_scores_kernel(CentroidArgs a, Mu
     const int nit = row_bytes / kIterBytes;
     const int per = (nit + 3) / 4;
     const int it0 = wave * per, it1 = it0 + per < nit ? it0 + per : nit;
-    if (a.meta.cand_off) {
-        // bookkeeping of the coarse step (otherwise done while the queries are prepared)
-        for (uint32_t i = blockIdx.x * blockDim.x + tid; i < a.meta.nclear; i += gridDim.x * blockDim.x) a.meta.clear[i] = 0u;
-        if (cb == 0 && (uint32_t)tid < qcnt) {
-            const uint32_t t = q0 + (uint32_t)tid;
-            a.meta.cand_off[t] = t * a.meta.stride;
-            a.meta.cand_cnt[t] = (uint32_t)ix.nlist;
-            a.meta.qagent[t] = (uint16_t)h;
-        }
-    }
-
     const char *xp = reinterpret_cast<const char *>(ix.cent) + (size_t)(cb * 16u + ln) * row_bytes + lg * 16;
     const char *qp[MT];
 #pragma unroll
@@ -609,6 +690,17 @@ __global__ __launch_bounds__(256) void centroid_scores_kernel(CentroidArgs a, Mu
                 key = o < key ? o : key;
             }
             if (ln == 0 && slot < qcnt && key != ~0ull) atomicMin(a.best + q0 + slot, key);
+        }
+    }
+    if (a.meta.cand_off) {
+        // bookkeeping of the coarse step (otherwise done while the queries are prepared); last, so that no
+        // load of this kernel queues behind these stores
+        for (uint32_t i = blockIdx.x * blockDim.x + tid; i < a.meta.nclear; i += gridDim.x * blockDim.x) a.meta.clear[i] = 0u;
+        if (cb == 0 && (uint32_t)tid < qcnt) {
+            const uint32_t t = q0 + (uint32_t)tid;
+            a.meta.cand_off[t] = t * a.meta.stride;
+            a.meta.cand_cnt[t] = (uint32_t)ix.nlist;
+            a.meta.qagent[t] = (uint16_t)h;
         }
     }
 }

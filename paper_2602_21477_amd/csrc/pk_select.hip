@@ -9,11 +9,18 @@
 // and the selection is deterministic.  A workgroup streams candidates, keeps those that
 // beat the current K-th key in an LDS buffer, and re-sorts the buffer (bitonic network)
 // only when it runs full, so almost all candidates cost one compare.
+#include <algorithm>
+#include <type_traits>
+
 #include "pk_internal.h"
+PK_DEV_MARKS(sel)
+#define PK_WL_MARK(i) PK_MARK(sel, i)
+#include "pk_worklist_dev.h"
 
 namespace pk {
 
 typedef unsigned long long u64;
+typedef unsigned long long u64x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ uint32_t next_pow2(uint32_t n)
 {
@@ -170,6 +177,57 @@ __global__ __launch_bounds__(kSelThreads) void select_probes_kernel(const u64 *p
 }
 
 
+// The K-th smallest (K counts from 1) of the keys that the 256 threads of a workgroup hold in registers
+// (key[j] takes part if live[j]; K is at most the number of live keys), found digit by digit: four
+// 8-bit passes over LDS histograms with one barrier each; every wave works out each digit for itself.
+// hist: LDS [4][256], need not be initialised.  Returns that key; of the `ties` keys equal to it, `left`
+// belong to the K smallest.
+template <int VPT>
+__device__ __forceinline__ uint32_t radix_kth(const uint32_t (&key)[VPT], const bool (&live)[VPT], uint32_t K,
+                                              uint32_t (*hist)[256], uint32_t &left, uint32_t &ties)
+{
+    const uint32_t tid = threadIdx.x, lane = tid & 63;
+#pragma unroll
+    for (int pass = 0; pass < 4; ++pass) hist[pass][tid] = 0;
+    __syncthreads();
+    uint32_t prefix = 0, krem = K, tie = 0;
+    for (int pass = 0; pass < 4; ++pass) {
+        const int shift = 24 - 8 * pass;
+        const uint32_t himask = pass == 0 ? 0u : 0xffffffffu << (shift + 8);
+#pragma unroll
+        for (int j = 0; j < VPT; ++j)
+            if (live[j] && (key[j] & himask) == prefix) atomicAdd(&hist[pass][(key[j] >> shift) & 255u], 1u);
+        __syncthreads();
+        // which digit holds the krem-th smallest of the keys that share the prefix (a lane takes four
+        // neighbouring digits)
+        const u32x4 c4 = *reinterpret_cast<const u32x4 *>(&hist[pass][lane * 4]);
+        const uint32_t t = c4[0] + c4[1] + c4[2] + c4[3];
+        uint32_t incl = t;
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t y = __shfl_up(incl, off);
+            if (lane >= (uint32_t)off) incl += y;
+        }
+        uint32_t run = incl - t, digit = 0, rem = 0, cnt = 0;
+        const bool here = run < krem && krem <= incl;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (run < krem && krem <= run + c4[e]) {
+                digit = lane * 4 + e;
+                rem = krem - run;
+                cnt = c4[e];
+            }
+            run += c4[e];
+        }
+        const int src = __ffsll((unsigned long long)__ballot(here)) - 1; // K <= live keys: some lane has it
+        prefix |= (uint32_t)__shfl(digit, src) << shift;
+        krem = __shfl(rem, src);
+        tie = __shfl(cnt, src);
+    }
+    left = krem;
+    ties = tie;
+    return prefix;
+}
+
 // ---------------------------------------------------------------- dense rows (coarse search)
 
 // Best K of a row of n <= 256 * VPT scores (Section 2.2: the top-nprobe clusters), for the
@@ -178,58 +236,40 @@ __global__ __launch_bounds__(kSelThreads) void select_probes_kernel(const u64 *p
 // radix passes over a 256-bin LDS histogram), then the keys below it and as many of the keys
 // equal to it as are needed, lowest positions first, are collected and sorted.  Positions
 // are list numbers, so ties go to the lower list number.
-template <int VPT>
+// COUNT: the workgroup goes on to do its query's share of the work-list construction (pairs per list,
+// candidate layout, sample tiles), which saves the launch that would otherwise follow the selection.
+template <int VPT, bool COUNT>
 __global__ __launch_bounds__(256) void select_dense_kernel(const float *vals, const uint32_t *qoff, const uint32_t *qcnt,
-                                                           int metric, int K, int32_t *probes)
+                                                           int metric, int K, int32_t *probes, WorklistArgs wa,
+                                                           SampleArgs sm, MultiArgs ma)
 {
-    __shared__ uint32_t hist[256];
+    __shared__ __align__(16) uint32_t hist[4][256]; // one histogram per radix pass: zeroed once
     __shared__ uint32_t s_w[4];
-    __shared__ uint32_t s_digit, s_krem, s_ties, s_n;
-    __shared__ u64 sel[PK_MAX_NPROBE];
+    __shared__ uint32_t s_n;
+    __shared__ __align__(16) u64 sel[PK_MAX_NPROBE + 2];
+    __shared__ int32_t s_probe[COUNT ? PK_MAX_NPROBE : 1];
+    __shared__ std::conditional_t<COUNT, WlCountLds, uint32_t> s_wl;
+    PK_MARK(sel, 0);
     const uint32_t q = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t n = qcnt[q];
     const float *v = vals + qoff[q];
+    WlIndexView view{};
+    if constexpr (COUNT) view = wl_index_view(wa, ma, q); // these loads are over by the time the count needs them
     uint32_t key[VPT];
 #pragma unroll
     for (int j = 0; j < VPT; ++j) {
         const uint32_t p = tid + 256u * j;
         key[j] = p < n ? order_bits(v[p], metric) : 0xffffffffu;
     }
-    uint32_t prefix = 0, krem = (uint32_t)K;
-    for (int pass = 0; pass < 4; ++pass) {
-        const int shift = 24 - 8 * pass;
-        const uint32_t himask = pass == 0 ? 0u : 0xffffffffu << (shift + 8);
-        hist[tid] = 0;
-        if (tid == 0) s_n = 0;
-        __syncthreads();
+    if (tid == 0) s_n = 0;
+    bool live[VPT];
 #pragma unroll
-        for (int j = 0; j < VPT; ++j)
-            if (tid + 256u * j < n && (key[j] & himask) == prefix) atomicAdd(&hist[(key[j] >> shift) & 255u], 1u);
-        __syncthreads();
-        // which digit holds the krem-th smallest of the keys that share the prefix
-        const uint32_t c = hist[tid];
-        uint32_t incl = c;
-        for (int off = 1; off < 64; off <<= 1) {
-            const uint32_t y = __shfl_up(incl, off);
-            if (lane >= (uint32_t)off) incl += y;
-        }
-        if (lane == 63) s_w[wave] = incl;
-        __syncthreads();
-        uint32_t before = 0;
-        for (uint32_t w = 0; w < wave; ++w) before += s_w[w];
-        incl += before;
-        if (incl - c < krem && krem <= incl) {
-            s_digit = tid;
-            s_krem = krem - (incl - c);
-            s_ties = c;
-        }
-        __syncthreads();
-        prefix |= s_digit << shift;
-        krem = s_krem;
-        __syncthreads();
-    }
-    // prefix is the K-th smallest key; krem of the s_ties keys equal to it are needed
-    const uint32_t ties = s_ties;
+    for (int j = 0; j < VPT; ++j) live[j] = tid + 256u * j < n;
+    PK_MARK(sel, 1);
+    uint32_t krem, ties;
+    const uint32_t prefix = radix_kth<VPT>(key, live, (uint32_t)K, hist, krem, ties);
+    PK_MARK(sel, 2);
+    // prefix is the K-th smallest key; krem of the `ties` keys equal to it are needed
 #pragma unroll
     for (int j = 0; j < VPT; ++j) {
         const uint32_t p = tid + 256u * j;
@@ -252,23 +292,66 @@ __global__ __launch_bounds__(256) void select_dense_kernel(const float *vals, co
             __syncthreads();
         }
     }
+    if (tid < 2) sel[K + tid] = kMaxKey; // padding: the rank count reads pairs
     __syncthreads();
-    const uint32_t np2 = next_pow2((uint32_t)K);
-    for (uint32_t i = (uint32_t)K + tid; i < np2; i += 256) sel[i] = kMaxKey;
-    __syncthreads();
-    bitonic_sort(sel, np2);
-    for (uint32_t r = tid; r < (uint32_t)K; r += 256) probes[(size_t)q * K + r] = (int32_t)(uint32_t)sel[r];
+    PK_MARK(sel, 3);
+    if (K <= 256) {
+        // rank of each selected key among the K of them (keys are unique): its place in the probe list
+        if (tid < (uint32_t)K) {
+            const u64 mine = sel[tid];
+            uint32_t rank = 0;
+            for (int o = 0; o < K; o += 2) {
+                const u64x2 w = *reinterpret_cast<const u64x2 *>(sel + o);
+                rank += (w[0] < mine ? 1u : 0u) + (w[1] < mine ? 1u : 0u);
+            }
+            if constexpr (COUNT) s_probe[rank] = (int32_t)(uint32_t)mine; // the count stores the list, after its loads
+            else probes[(size_t)q * K + rank] = (int32_t)(uint32_t)mine;
+        }
+    } else {
+        const uint32_t np2 = next_pow2((uint32_t)K);
+        for (uint32_t i = (uint32_t)K + tid; i < np2; i += 256) sel[i] = kMaxKey;
+        __syncthreads();
+        bitonic_sort(sel, np2);
+        for (uint32_t r = tid; r < (uint32_t)K; r += 256) {
+            if constexpr (COUNT) s_probe[r] = (int32_t)(uint32_t)sel[r];
+            else probes[(size_t)q * K + r] = (int32_t)(uint32_t)sel[r];
+        }
+    }
+    PK_MARK(sel, 4);
+    if constexpr (COUNT) {
+        __syncthreads(); // the probe list is in s_probe
+        wl_count_query(wa, sm, ma, q, s_wl, s_probe, probes + (size_t)q * K, view);
+        PK_MARK(sel, 7);
+    }
 }
 
 hipError_t launch_select_dense(const float *vals, const uint32_t *qoff, const uint32_t *qcnt, uint32_t max_cnt, int metric,
-                               int K, int64_t nq, int32_t *probes, hipStream_t s)
+                               int K, int64_t nq, int32_t *probes, hipStream_t s, const WorklistArgs *wa, const SampleArgs *sm,
+                               const MultiArgs *ma)
 {
     if (nq <= 0) return hipSuccess;
     if (max_cnt > (uint32_t)kDenseSelectMax || K > PK_MAX_NPROBE) return hipErrorInvalidValue;
     const dim3 g((uint32_t)nq), b(256);
-    if (max_cnt <= 1024) hipLaunchKernelGGL(select_dense_kernel<4>, g, b, 0, s, vals, qoff, qcnt, metric, K, probes);
-    else if (max_cnt <= 4096) hipLaunchKernelGGL(select_dense_kernel<16>, g, b, 0, s, vals, qoff, qcnt, metric, K, probes);
-    else hipLaunchKernelGGL(select_dense_kernel<32>, g, b, 0, s, vals, qoff, qcnt, metric, K, probes);
+    if (wa) {
+        if (!sm || !ma || wa->nprobe != K) return hipErrorInvalidValue;
+        if (max_cnt <= 1024)
+            hipLaunchKernelGGL((select_dense_kernel<4, true>), g, b, 0, s, vals, qoff, qcnt, metric, K, probes, *wa, *sm, *ma);
+        else if (max_cnt <= 4096)
+            hipLaunchKernelGGL((select_dense_kernel<16, true>), g, b, 0, s, vals, qoff, qcnt, metric, K, probes, *wa, *sm, *ma);
+        else
+            hipLaunchKernelGGL((select_dense_kernel<32, true>), g, b, 0, s, vals, qoff, qcnt, metric, K, probes, *wa, *sm, *ma);
+        return hipGetLastError();
+    }
+    const WorklistArgs w0{};
+    const SampleArgs s0{};
+    MultiArgs m0;
+    m0.n = 0;
+    if (max_cnt <= 1024)
+        hipLaunchKernelGGL((select_dense_kernel<4, false>), g, b, 0, s, vals, qoff, qcnt, metric, K, probes, w0, s0, m0);
+    else if (max_cnt <= 4096)
+        hipLaunchKernelGGL((select_dense_kernel<16, false>), g, b, 0, s, vals, qoff, qcnt, metric, K, probes, w0, s0, m0);
+    else
+        hipLaunchKernelGGL((select_dense_kernel<32, false>), g, b, 0, s, vals, qoff, qcnt, metric, K, probes, w0, s0, m0);
     return hipGetLastError();
 }
 
@@ -285,6 +368,25 @@ __device__ int64_t resolve_id(const FinalArgs &a, const MultiArgs &h, uint32_t q
     const uint32_t row = pos - po[lo];
     const uint32_t list = (uint32_t)a.probes[(size_t)q * a.nprobe + lo];
     const DevIndex &ix = *h.ix[a.qagent[q]];
+    const uint32_t lp = row / (uint32_t)ix.P;
+    const uint32_t pg = phys_page(ix, list, lp);
+    const Arena &ar = arena_of(ix, pg);
+    return ar.ids[(size_t)(pg - ar.first_page) * ix.P + (row - lp * ix.P)];
+}
+
+constexpr uint32_t kFinalRankMax = 256; // emitted keys up to this many are ranked by counting instead of sorted
+
+// the same with the query's rows of pair_off and probes in LDS
+__device__ int64_t resolve_id_lds(const FinalArgs &a, const DevIndex &ix, uint32_t pos, const uint32_t *po, const uint32_t *pr)
+{
+    int lo = 0, hi = a.nprobe - 1;
+    while (lo < hi) { // largest r with po[r] <= pos
+        const int mid = (lo + hi + 1) >> 1;
+        if (po[mid] <= pos) lo = mid;
+        else hi = mid - 1;
+    }
+    const uint32_t row = pos - po[lo];
+    const uint32_t list = pr[lo];
     const uint32_t lp = row / (uint32_t)ix.P;
     const uint32_t pg = phys_page(ix, list, lp);
     const Arena &ar = arena_of(ix, pg);
@@ -369,14 +471,17 @@ __device__ void rescore_query(const FinalArgs &a, const MultiArgs &h, uint32_t q
     }
 }
 
-__global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, MultiArgs h, uint32_t cap)
+__global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, MultiArgs h, uint32_t cap, uint32_t qbytes)
 {
     // LDS sized by K, not by the largest K the library takes: small k leaves room for every
     // query's workgroup to be resident at once
     extern __shared__ __align__(16) unsigned char s_dyn[];
     u64 *keys = reinterpret_cast<u64 *>(s_dyn);                  // [cap]
     int64_t *s_id = reinterpret_cast<int64_t *>(keys + cap);     // [k]
-    char *s_q = reinterpret_cast<char *>(s_id + ((a.k + 1) & ~1)); // [2][row_bytes + kQPadBytes], used when rescoring
+    // [2][row_bytes + kQPadBytes] when rescoring; the emitted keys (kFinalRankMax + 2 of them) when they are few
+    char *s_q = reinterpret_cast<char *>(s_id + ((a.k + 1) & ~1));
+    uint32_t *s_po = reinterpret_cast<uint32_t *>(s_q + qbytes); // [nprobe + 1] the query's row of pair_off
+    uint32_t *s_pr = s_po + a.nprobe + 1;                        // [nprobe] its probe list
     __shared__ uint32_t s_cnt;
     __shared__ long long s_red[kSelThreads / 64];
     __shared__ uint32_t s_redpos[kSelThreads / 64];
@@ -385,17 +490,59 @@ __global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, 
     const uint32_t q = blockIdx.x;
     const int k = a.k;
     const int qstride = a.row_bytes + kQPadBytes;
+    PK_MARK(sel, 32);
+    const size_t region = (size_t)q * a.ecap;
+    // everything the usual path reads from global memory is requested at once: the count, the thread's key
+    // of a short region (the entry exists whatever the count; it is used only if it is below it), the
+    // query's rows of the candidate layout, its index
+    const uint32_t cnt_q = a.qcnt[q];
+    const u64 early = threadIdx.x < a.ecap ? a.keys[region + threadIdx.x] : kMaxKey;
+    for (int r = threadIdx.x; r <= a.nprobe; r += blockDim.x) {
+        s_po[r] = a.pair_off[(size_t)q * (a.nprobe + 1) + r];
+        if (r < a.nprobe) s_pr[r] = (uint32_t)a.probes[(size_t)q * a.nprobe + r];
+    }
+    const DevIndex &qix = *h.ix[a.qagent[q]];
+    // Running sums of the call (candidates met, candidates emitted, most emitted by one query, queries whose
+    // region overflowed): workgroup 0 adds up every query's numbers, so that they cost four atomics per call
+    // and not several per query on the same words.
+    unsigned long long st_cand = 0, st_emit = 0;
+    uint32_t st_max = 0, st_over = 0;
+    if (blockIdx.x == 0) {
+        for (uint32_t t = threadIdx.x; t < gridDim.x; t += blockDim.x) {
+            const uint32_t c = a.qcnt[t];
+            st_cand += a.pair_off[(size_t)t * (a.nprobe + 1) + a.nprobe];
+            st_emit += c;
+            st_max = c > st_max ? c : st_max;
+            st_over += c > a.ecap ? 1u : 0u;
+        }
+    }
     Selector sel;
     sel.init(keys, &s_cnt, a.K, cap);
-    const uint32_t cnt_q = a.qcnt[q];
     const bool overflow = cnt_q > a.ecap; // the region lost candidates: select by rescoring the query's rows
-    if (threadIdx.x == 0) {
-        atomicAdd(&h.ix[0]->stats[3], (unsigned long long)cnt_q);
-        if (overflow) atomicAdd(&h.ix[0]->stats[4], 1ull);
-        atomicMax(&h.ix[0]->stats[5], (unsigned long long)cnt_q);
-    }
-    const size_t region = (size_t)q * a.ecap;
-    if (!overflow) {
+    if (cnt_q <= kFinalRankMax && !overflow) {
+        // few keys: each one's rank by counting the smaller ones (keys are unique); no sorting network, one barrier
+        u64 *s_in = reinterpret_cast<u64 *>(s_q);
+        static_assert(kFinalRankMax == (uint32_t)kSelThreads, "one key per thread");
+        constexpr int KPT = 1;
+        u64 mine[KPT];
+        mine[0] = threadIdx.x < cnt_q ? early : kMaxKey;
+        if (threadIdx.x < cnt_q) s_in[threadIdx.x] = mine[0];
+        if (threadIdx.x < 2) s_in[cnt_q + threadIdx.x] = kMaxKey; // padding: the keys are read in pairs
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < KPT; ++j) {
+            const uint32_t p = threadIdx.x + (uint32_t)kSelThreads * j;
+            if (p >= cnt_q) continue;
+            uint32_t rank = 0;
+            for (uint32_t o = 0; o < cnt_q; o += 2) {
+                const u64x2 w = *reinterpret_cast<const u64x2 *>(s_in + o);
+                rank += (w[0] < mine[j] ? 1u : 0u) + (w[1] < mine[j] ? 1u : 0u);
+            }
+            if (rank < (uint32_t)a.K) keys[rank] = mine[j];
+        }
+        if (threadIdx.x == 0) s_cnt = cnt_q < (uint32_t)a.K ? cnt_q : (uint32_t)a.K;
+        __syncthreads();
+    } else if (!overflow) {
         const u64 *v = a.keys + region;
         // short ranges go one key per thread and round, so the buffer that gets sorted stays small
         const uint32_t per = cnt_q <= 8192u ? 1u : (uint32_t)kSelVec;
@@ -421,7 +568,8 @@ __global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, 
         if (a.storage == PK_F16) rescore_query<PK_F16>(a, h, q, s_q, qstride, sel, false, 0u);
         else rescore_query<PK_F32>(a, h, q, s_q, qstride, sel, false, 0u);
     }
-    sel.flush();
+    PK_MARK(sel, 33);
+    if (cnt_q > kFinalRankMax || overflow) sel.flush();
     const uint32_t n = s_cnt;
 
     // entries carrying the padding value are not candidates
@@ -432,8 +580,9 @@ __global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, 
         ++n_valid;
     }
     const uint32_t kk = n_valid < (uint32_t)k ? n_valid : (uint32_t)k;
-    for (uint32_t i = threadIdx.x; i < kk; i += blockDim.x) s_id[i] = resolve_id(a, h, q, (uint32_t)keys[i]);
+    for (uint32_t i = threadIdx.x; i < kk; i += blockDim.x) s_id[i] = resolve_id_lds(a, qix, (uint32_t)keys[i], s_po, s_pr);
     __syncthreads();
+    PK_MARK(sel, 34);
 
     // Equal values must come in ascending id order.  If the tie group of the k-th value
     // reaches past position k, its members inside the top k are the lowest ids of the
@@ -517,6 +666,7 @@ __global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, 
         }
     }
 
+    PK_MARK(sel, 35);
     // final order: (value key, id) ascending; rows that carry the same id with the same value
     // keep their order in keys[], so ranks are unique
     for (uint32_t i = threadIdx.x; i < (uint32_t)k; i += blockDim.x) {
@@ -535,39 +685,152 @@ __global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, 
             a.out_dist[(size_t)q * k + i] = a.metric == PK_METRIC_IP ? -INFINITY : INFINITY;
         }
     }
+    if (blockIdx.x == 0) { // last: no load above queues behind these atomics
+        for (int off = 32; off > 0; off >>= 1) {
+            st_cand += __shfl_xor(st_cand, off);
+            st_emit += __shfl_xor(st_emit, off);
+            const uint32_t o = __shfl_xor(st_max, off);
+            st_max = o > st_max ? o : st_max;
+            st_over += __shfl_xor(st_over, off);
+        }
+        __syncthreads(); // keys[] is no longer read
+        if ((threadIdx.x & 63) == 0) {
+            u64 *w = keys + 4 * (threadIdx.x >> 6);
+            w[0] = st_cand;
+            w[1] = st_emit;
+            w[2] = st_max;
+            w[3] = st_over;
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            u64 cand = 0, emit = 0, mx = 0, over = 0;
+            for (int w = 0; w < kSelThreads / 64; ++w) {
+                cand += keys[4 * w];
+                emit += keys[4 * w + 1];
+                mx = keys[4 * w + 2] > mx ? keys[4 * w + 2] : mx;
+                over += keys[4 * w + 3];
+            }
+            unsigned long long *st = h.ix[0]->stats;
+            atomicAdd(&st[1], cand);
+            atomicAdd(&st[3], emit);
+            if (over) atomicAdd(&st[4], over);
+            atomicMax(&st[5], mx);
+        }
+    }
 }
 
 // k-th best of each query's sample -> threshold key; fewer than k real samples: no threshold
-__global__ __launch_bounds__(kSelThreads) void tau_kernel(SampleArgs a)
+// WL: the workgroups then lay out the second half of the work list between them (offsets, slots, tiles:
+// small batches only), so that no launch of its own is needed for it.
+// Threshold of one query from a sample held in registers (up to 256 * VPT values): the k-th best by radix
+// selection, the best and the worst real value and their number by reduction.  s_red: LDS [12].
+// after_loads: called once the sample's loads are on their way (the caller's own read-ahead goes there).
+template <int VPT, typename F>
+__device__ __forceinline__ void tau_by_radix(const SampleArgs &a, const float *v, uint32_t (*hist)[256], uint32_t *s_red,
+                                             uint32_t &cnt, uint32_t &first, uint32_t &kth, uint32_t &last, F after_loads)
 {
-    __shared__ u64 keys[kSelCap];
-    __shared__ uint32_t s_cnt;
-    const uint32_t q = blockIdx.x;
-    Selector sel;
-    sel.init(keys, &s_cnt, a.k);
-    const float *v = a.vals + (size_t)q * a.span;
-    constexpr uint32_t kRound = kSelThreads * kSelVec;
-    for (uint32_t r = 0; r < a.span; r += kRound) {
-        sel.reserve(kRound);
-        const uint32_t p = r + threadIdx.x * kSelVec;
-        if (p < a.span) {
-            const f32x4 x = *reinterpret_cast<const f32x4 *>(v + p);
+    const uint32_t tid = threadIdx.x;
+    uint32_t key[VPT];
+    bool live[VPT];
+    float raw[VPT];
 #pragma unroll
-            for (int j = 0; j < kSelVec; ++j) {
-                const uint32_t b = order_bits(x[j], a.metric);
-                if (b < kWorstBits) sel.push(((u64)b << 32) | (p + j));
-            }
+    for (int j = 0; j < VPT; ++j) {
+        const uint32_t p = tid + (uint32_t)kSelThreads * j;
+        live[j] = p < a.span;
+        raw[j] = live[j] ? v[p] : 0.f;
+    }
+    after_loads();
+    uint32_t mn = 0xffffffffu, mx = 0u, real = 0u;
+#pragma unroll
+    for (int j = 0; j < VPT; ++j) {
+        key[j] = live[j] ? order_bits(raw[j], a.metric) : 0xffffffffu;
+        if (live[j] && key[j] < kWorstBits) { // padding of the sample takes part in the ranking (last) but is no value
+            mn = key[j] < mn ? key[j] : mn;
+            mx = key[j] > mx ? key[j] : mx;
+            ++real;
         }
     }
-    sel.flush();
+    for (int off = 32; off > 0; off >>= 1) {
+        const uint32_t a0 = __shfl_xor(mn, off), a1 = __shfl_xor(mx, off);
+        mn = a0 < mn ? a0 : mn;
+        mx = a1 > mx ? a1 : mx;
+        real += __shfl_xor(real, off);
+    }
+    if ((tid & 63) == 0) {
+        s_red[tid >> 6] = mn;
+        s_red[4 + (tid >> 6)] = mx;
+        s_red[8 + (tid >> 6)] = real;
+    }
+    uint32_t left, ties;
+    kth = radix_kth<VPT>(key, live, (uint32_t)a.k, hist, left, ties); // its barriers publish s_red
+    first = min(min(s_red[0], s_red[1]), min(s_red[2], s_red[3]));
+    last = max(max(s_red[4], s_red[5]), max(s_red[6], s_red[7]));
+    cnt = s_red[8] + s_red[9] + s_red[10] + s_red[11];
+}
+
+// k-th best of each query's sample -> threshold key; fewer than k real samples: no threshold
+// WL: the workgroups then lay out the second half of the work list between them (offsets, slots, tiles:
+// small batches only), so that no launch of its own is needed for it.
+template <bool WL>
+__global__ __launch_bounds__(kSelThreads) void tau_kernel(SampleArgs a, WorklistArgs wa, MultiArgs ma)
+{
+    __shared__ __align__(16) u64 keys[kSelCap];
+    __shared__ uint32_t s_cnt;
+    __shared__ uint32_t s_wave[17];
+    const uint32_t q = blockIdx.x;
+    PK_MARK(sel, 16);
+    WlPrefetch pre;
+    auto read_ahead = [&]() {
+        if constexpr (WL) wl_spread_prefetch(wa, ma, q, pre); // in flight while the threshold is worked out
+    };
+    const float *v = a.vals + (size_t)q * a.span;
+    uint32_t cnt = 0;                      // real samples (or k, if there are more)
+    uint32_t first = 0, kth = 0, last = 0; // value keys: best, k-th best, worst real sample
+    uint32_t(*hist)[256] = reinterpret_cast<uint32_t(*)[256]>(keys);
+    if (a.span <= 4u * kSelThreads) {
+        tau_by_radix<4>(a, v, hist, s_wave, cnt, first, kth, last, read_ahead);
+    } else if (a.span <= 16u * kSelThreads) {
+        tau_by_radix<16>(a, v, hist, s_wave, cnt, first, kth, last, read_ahead);
+    } else {
+        read_ahead();
+        Selector sel;
+        sel.init(keys, &s_cnt, a.k);
+        constexpr uint32_t kRound = kSelThreads * kSelVec;
+        for (uint32_t r = 0; r < a.span; r += kRound) {
+            sel.reserve(kRound);
+            const uint32_t p = r + threadIdx.x * kSelVec;
+            if (p < a.span) {
+                const f32x4 x = *reinterpret_cast<const f32x4 *>(v + p);
+#pragma unroll
+                for (int j = 0; j < kSelVec; ++j) {
+                    const uint32_t b = order_bits(x[j], a.metric);
+                    if (b < kWorstBits) sel.push(((u64)b << 32) | (p + j));
+                }
+            }
+        }
+        sel.flush();
+        cnt = s_cnt; // at most k are kept
+        if (cnt > 0) {
+            first = (uint32_t)(keys[0] >> 32);
+            last = (uint32_t)(keys[cnt - 1] >> 32);
+            kth = last;
+        }
+    }
+    PK_MARK(sel, 18);
+    if constexpr (WL) {
+        __syncthreads(); // the key buffer is free
+        wl_spread(wa, ma, reinterpret_cast<uint32_t *>(keys), s_wave, q, pre);
+        PK_MARK(sel, 24);
+    }
+    // the kernel's own results last: no load above queues behind these stores
     if (threadIdx.x == 0) {
-        const bool full = s_cnt >= (uint32_t)a.k;
-        a.tau[q] = full ? (uint32_t)(keys[a.k - 1] >> 32) : 0xffffffffu;
+        const bool full = cnt >= (uint32_t)a.k;
+        a.tau[q] = full ? kth : 0xffffffffu;
         a.tcur[q] = (uint32_t)kHistBins - 1u;
         float lo = 0.f, inv = 0.f;
-        if (s_cnt > 0) {
-            lo = value_of((uint32_t)(keys[0] >> 32), a.metric);
-            const float far = value_of((uint32_t)(keys[(full ? (uint32_t)a.k : s_cnt) - 1] >> 32), a.metric);
+        if (cnt > 0) {
+            lo = value_of(first, a.metric);
+            const float far = value_of(full ? kth : last, a.metric);
             const float range = fabsf(far - lo);
             if (range > 0.f && range < INFINITY) inv = ((float)kHistBins - 1.001f) / range;
         }
@@ -577,10 +840,20 @@ __global__ __launch_bounds__(kSelThreads) void tau_kernel(SampleArgs a)
     if (threadIdx.x < kHistBins) a.hist[(size_t)q * kHistBins + threadIdx.x] = 0u;
 }
 
-hipError_t launch_tau(const SampleArgs &a, hipStream_t s)
+hipError_t launch_tau(const SampleArgs &a, hipStream_t s, const WorklistArgs *wa, const MultiArgs *ma)
 {
     if (a.nq <= 0) return hipSuccess;
-    hipLaunchKernelGGL(tau_kernel, dim3((uint32_t)a.nq), dim3(kSelThreads), 0, s, a);
+    if (a.span % 4 != 0) return hipErrorInvalidValue;
+    if (wa) {
+        static_assert(2 * kSelCap >= 3 * ((int)kWlSmallLists + 1), "the work-list layout borrows the key buffer");
+        static_assert(kSelThreads * 8 >= (int)kWlSmallLists, "one round of the list scan covers every list");
+        if (!ma || (uint64_t)wa->n_handles * (uint64_t)wa->nlist_max > kWlSmallLists) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(tau_kernel<true>, dim3((uint32_t)a.nq), dim3(kSelThreads), 0, s, a, *wa, *ma);
+        return hipGetLastError();
+    }
+    MultiArgs m0;
+    m0.n = 0;
+    hipLaunchKernelGGL(tau_kernel<false>, dim3((uint32_t)a.nq), dim3(kSelThreads), 0, s, a, WorklistArgs{}, m0);
     return hipGetLastError();
 }
 
@@ -606,9 +879,11 @@ hipError_t launch_select_final(const FinalArgs &a, const MultiArgs &h, int64_t n
     if (a.row_bytes <= 0 || a.row_bytes % kIterBytes != 0 || a.ecap < (uint32_t)a.K) return hipErrorInvalidValue;
     const uint32_t cap = final_cap(a.K);
     // keys, ids, and the query row + a row of zeros for a query that has to be rescored
-    const size_t lds = (size_t)cap * sizeof(u64) + (size_t)((a.k + 1) & ~1) * sizeof(int64_t) +
-                       (size_t)2 * (a.row_bytes + kQPadBytes);
-    hipLaunchKernelGGL(select_final_kernel, dim3((uint32_t)nq), dim3(kSelThreads), lds, s, a, h, cap);
+    const size_t qbytes = std::max((size_t)2 * (a.row_bytes + kQPadBytes), (size_t)(kFinalRankMax + 2) * sizeof(u64));
+    // ..., and the query's rows of the candidate layout
+    const size_t lds = (size_t)cap * sizeof(u64) + (size_t)((a.k + 1) & ~1) * sizeof(int64_t) + qbytes +
+                       (size_t)(2 * a.nprobe + 1) * sizeof(uint32_t);
+    hipLaunchKernelGGL(select_final_kernel, dim3((uint32_t)nq), dim3(kSelThreads), lds, s, a, h, cap, (uint32_t)qbytes);
     return hipGetLastError();
 }
 

@@ -10,10 +10,9 @@
 #include <algorithm>
 
 #include "pk_internal.h"
+#include "pk_worklist_dev.h"
 
 namespace pk {
-
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // ---------------------------------------------------------------- small utilities
 
@@ -102,203 +101,31 @@ hipError_t launch_prep_coarse(const float *q, int64_t nq, int d, int row_bytes, 
 
 // ---------------------------------------------------------------- list work list
 
-// per query: count the pairs per list, lay the query's candidate range out probe by probe;
-// and the tiles of the query's threshold sample: the first sm.sp pages of that range (the
-// pages of its first probed list, then of its second, ...), so that a query whose best list is
-// short still draws its threshold from at least k rows whenever it has that many candidates
+// per query: pairs per list, candidate layout, tiles of the threshold sample
 __global__ __launch_bounds__(256) void wl_count_kernel(WorklistArgs a, SampleArgs sm, MultiArgs m)
 {
-    __shared__ uint32_t s_len[PK_MAX_NPROBE];    // rows of each probed list
-    __shared__ uint32_t s_pg0[PK_MAX_NPROBE + 1]; // pages of the probed lists before each one
-    const uint32_t q = blockIdx.x;
-    const uint32_t ag = a.qagent[q];
-    const DevIndex &ix = *m.ix[ag];
-    const uint32_t P = (uint32_t)ix.P;
-    for (int r = threadIdx.x; r < a.nprobe; r += blockDim.x) {
-        const uint32_t l = (uint32_t)a.probes[(size_t)q * a.nprobe + r];
-        uint32_t len = 0;
-        if (l < (uint32_t)ix.nlist) {
-            atomicAdd(&a.lcnt[(size_t)ag * a.nlist_max + l], 1u);
-            len = ix.list_len[l];
-        }
-        s_len[r] = len;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t acc = 0, pages = 0;
-        uint32_t *po = a.pair_off + (size_t)q * (a.nprobe + 1);
-        for (int r = 0; r < a.nprobe; ++r) {
-            po[r] = acc;
-            s_pg0[r] = pages;
-            acc += (s_len[r] + 15u) & ~15u; // segments are padded to the 16-row MFMA tile
-            pages += (s_len[r] + P - 1) / P;
-        }
-        po[a.nprobe] = acc;
-        s_pg0[a.nprobe] = pages;
-        a.ccnt[q] = 0;
-        atomicAdd(&m.ix[0]->stats[1], (unsigned long long)acc);
-    }
-    {
-        const float worst = sm.metric == PK_METRIC_IP ? -INFINITY : INFINITY;
-        float *v = sm.vals + (size_t)q * sm.span;
-        for (uint32_t i = threadIdx.x; i < sm.span; i += blockDim.x) v[i] = worst;
-        if (threadIdx.x == 0) {
-            sm.slot_query[q] = q;
-            sm.slot_out[q] = q * sm.span;
-            if (q == 0) {
-                const uint32_t ntiles = (uint32_t)sm.nq * (uint32_t)sm.sp;
-                sm.scalars[0] = ntiles;
-                sm.scalars[1] = 0;
-                const uint32_t g = ntiles / (uint32_t)(sm.scan_grid * 4);
-                sm.scalars[2] = g < 1 ? 1 : (g > 8 ? 8 : g);
-            }
-        }
-    }
-    __syncthreads();
-    for (uint32_t p = threadIdx.x; p < (uint32_t)sm.sp; p += blockDim.x) {
-        Tile tl;
-        tl.x = ix.arenas[0].vec;
-        tl.xn = ix.arenas[0].norm;
-        tl.row0 = p * P; // position inside the sample, not inside a list
-        tl.qbeg = q;
-        tl.nrows = 0;
-        tl.qcnt = 1;
-        tl.pad = 0;
-        if (p < s_pg0[a.nprobe]) {
-            int r = 0;
-            while (s_pg0[r + 1] <= p) ++r; // the probed list that holds page p of the range
-            const uint32_t l = (uint32_t)a.probes[(size_t)q * a.nprobe + r];
-            const uint32_t lp = p - s_pg0[r];
-            const uint32_t pg = phys_page(ix, l, lp);
-            const Arena &ar = arena_of(ix, pg);
-            const size_t local = pg - ar.first_page;
-            tl.x = ar.vec + local * P * (size_t)ix.row_bytes;
-            tl.xn = ar.norm + local * P;
-            const uint32_t left = s_len[r] - lp * P;
-            tl.nrows = (uint16_t)(left < P ? left : P);
-        }
-        sm.tiles[(size_t)q * sm.sp + p] = tl;
-    }
+    __shared__ WlCountLds s;
+    wl_count_query(a, sm, m, blockIdx.x, s, a.probes + (size_t)blockIdx.x * a.nprobe, nullptr, wl_index_view(a, m, blockIdx.x));
 }
 
 // one workgroup: offsets of the lists' slot ranges and tile ranges
 __global__ __launch_bounds__(1024) void wl_scan_kernel(WorklistArgs a, MultiArgs m)
 {
     __shared__ uint32_t s_wave[17];
-    const uint32_t nl = (uint32_t)a.n_handles * (uint32_t)a.nlist_max;
-    block_exscan(a.lcnt, a.lstart, nl, s_wave);
-    // tiles per list: regular lists -> ltile, hot lists -> lhtile (counts first, then their scans in place)
-    unsigned long long rows = 0;
-    for (uint32_t gl = threadIdx.x; gl < nl; gl += blockDim.x) {
-        const uint32_t h = gl / (uint32_t)a.nlist_max, l = gl - h * (uint32_t)a.nlist_max;
-        uint32_t nt_reg = 0, nt_hot = 0;
-        const uint32_t c = a.lcnt[gl];
-        if (c > 0) {
-            const DevIndex &ix = *m.ix[h];
-            const uint32_t len = ix.list_len[l];
-            const uint32_t pages = (len + (uint32_t)ix.P - 1) / (uint32_t)ix.P;
-            if (c > a.hot_from) {
-                // hot tiles of the rows-stationary kernel cover hot_rows rows, not a page
-                const uint32_t units = a.hot_rows ? (len + (uint32_t)a.hot_rows - 1) / (uint32_t)a.hot_rows : pages;
-                nt_hot = units * ((c + (uint32_t)a.mq_hot - 1) / (uint32_t)a.mq_hot);
-            } else {
-                nt_reg = pages * ((c + (uint32_t)a.mq - 1) / (uint32_t)a.mq);
-            }
-            rows += len;
-        }
-        a.ltile[gl] = nt_reg;
-        a.lhtile[gl] = nt_hot;
-    }
-    __syncthreads();
-    for (int hot = 0; hot < 2; ++hot) {
-        // a class no list can fall into (no hot class at all, or every list hot) needs no scan
-        const bool none = hot ? a.hot_from == 0xffffffffu : a.hot_from == 0u;
-        uint32_t *lt = hot ? a.lhtile : a.ltile;
-        const uint32_t ntiles = none ? 0u : block_exscan(lt, lt, nl, s_wave);
-        if (threadIdx.x == 0) {
-            uint32_t nt = ntiles;
-            if (ntiles > a.tile_cap) {
-                // cannot happen while the host bounds hold; refuse to scan rather than overrun
-                nt = 0;
-                atomicOr(&m.ix[0]->ctr[1], (uint32_t)kErrWorklist);
-            }
-            uint32_t *sc = hot ? a.scalars_hot : a.scalars;
-            sc[0] = nt;
-            sc[1] = 0;
-            // tiles per claimed batch
-            uint32_t g = nt / (uint32_t)(a.scan_grid * a.grab_div);
-            g = g < 1 ? 1 : (g > 8 ? 8 : g);
-            // a rows-stationary tile is long (all slots of its list) and tiles differ tenfold: one per claim
-            sc[2] = hot && a.hot_rows ? (uint32_t)a.hot_grab : g;
-            if (nt) atomicAdd(&m.ix[0]->stats[2], (unsigned long long)nt);
-        }
-        __syncthreads();
-    }
-    if (rows) atomicAdd(&m.ix[0]->stats[0], rows);
-    __syncthreads();
-    for (uint32_t gl = threadIdx.x; gl < nl; gl += blockDim.x) a.lfill[gl] = 0;
-}
-
-// slots: every (query, probe) pair takes the next free slot of its list (one thread per pair)
-__device__ __forceinline__ void wl_slots_block(const WorklistArgs &a, const MultiArgs &m, uint32_t block)
-{
-    const size_t i = (size_t)block * blockDim.x + threadIdx.x;
-    if (i >= (size_t)a.nq * a.nprobe) return;
-    const uint32_t q = (uint32_t)(i / a.nprobe), r = (uint32_t)(i - (size_t)q * a.nprobe);
-    const uint32_t ag = a.qagent[q];
-    if ((uint32_t)a.probes[i] >= (uint32_t)m.ix[ag]->nlist) return;
-    const size_t gl = (size_t)ag * a.nlist_max + (uint32_t)a.probes[i];
-    const uint32_t slot = a.lstart[gl] + atomicAdd(&a.lfill[gl], 1u);
-    a.slot_query[slot] = q;
-    a.slot_out[slot] = a.pair_off[(size_t)q * (a.nprobe + 1) + r];
-}
-
-// tiles: one workgroup per list; tile order inside a list is [query group][page], so that
-// neighbouring tiles share their query group
-__device__ __forceinline__ void wl_tiles_block(const WorklistArgs &a, const MultiArgs &m, uint32_t gl)
-{
-    const uint32_t c = a.lcnt[gl];
-    if (c == 0) return;
-    const bool hot = c > a.hot_from;
-    if ((hot ? a.scalars_hot[0] : a.scalars[0]) == 0) return; // overflow guard tripped
-    const uint32_t h = gl / (uint32_t)a.nlist_max, l = gl - h * (uint32_t)a.nlist_max;
-    const DevIndex &ix = *m.ix[h];
-    const uint32_t len = ix.list_len[l];
-    const uint32_t P = (uint32_t)ix.P;
-    const uint32_t pages = (len + P - 1) / P;
-    const uint32_t mq = hot ? (uint32_t)a.mq_hot : (uint32_t)a.mq;
-    const uint32_t groups = (c + mq - 1) / mq;
-    Tile *out = (hot ? a.tiles_hot : a.tiles) + (hot ? a.lhtile[gl] : a.ltile[gl]);
-    // rows per tile: a page, or (hot tiles of the rows-stationary kernel) a fixed part of one
-    const uint32_t R = hot && a.hot_rows ? (uint32_t)a.hot_rows : P;
-    const uint32_t units = hot && a.hot_rows ? (len + R - 1) / R : pages;
-    for (uint32_t j = threadIdx.x; j < units * groups; j += blockDim.x) {
-        const uint32_t g = j / units, u = j - g * units;
-        const uint32_t first = u * R;          // position of the tile's first row in the list
-        const uint32_t p = first / P, in_page = first - p * P;
-        const uint32_t pg = phys_page(ix, l, p);
-        const Arena &ar = arena_of(ix, pg);
-        const size_t local = (size_t)(pg - ar.first_page) * P + in_page;
-        Tile tl;
-        tl.x = ar.vec + local * (size_t)ix.row_bytes;
-        tl.xn = ar.norm + local;
-        tl.row0 = first;
-        tl.qbeg = a.lstart[gl] + g * mq;
-        const uint32_t left = len - first;
-        tl.nrows = (uint16_t)(left < R ? left : R);
-        const uint32_t ql = c - g * mq;
-        tl.qcnt = (uint16_t)(ql < mq ? ql : mq);
-        tl.pad = 0;
-        out[j] = tl;
-    }
+    wl_scan_body(a, m, s_wave);
 }
 
 // Slots and tiles both need only the offsets wl_scan wrote, not each other: one launch, the
-// first slot_blocks workgroups place the pairs, the others write one list's tiles each.
+// first slot_blocks workgroups place the pairs (one thread per pair), the others write one
+// list's tiles each.
 __global__ __launch_bounds__(256) void wl_slots_tiles_kernel(WorklistArgs a, MultiArgs m, uint32_t slot_blocks)
 {
-    if (blockIdx.x < slot_blocks) wl_slots_block(a, m, blockIdx.x);
-    else wl_tiles_block(a, m, blockIdx.x - slot_blocks);
+    if (blockIdx.x < slot_blocks) {
+        const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+        if (i < (size_t)a.nq * a.nprobe) wl_slot_of_pair(a, m, i, a.lstart);
+    } else {
+        wl_tiles_of_list(a, m, blockIdx.x - slot_blocks);
+    }
 }
 
 
@@ -307,7 +134,8 @@ __global__ __launch_bounds__(256) void wl_slots_tiles_kernel(WorklistArgs a, Mul
 hipError_t launch_worklist_count(const WorklistArgs &a, const SampleArgs &sm, const MultiArgs &m, hipStream_t s)
 {
     if (!a.lcnt_cleared) {
-        const hipError_t e = launch_fill_u32(a.lcnt, 0u, (size_t)a.n_handles * (size_t)a.nlist_max, s);
+        // the pair counters and, behind them, the fill marks
+        const hipError_t e = launch_fill_u32(a.lcnt, 0u, (size_t)2 * (size_t)a.n_handles * (size_t)a.nlist_max, s);
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(wl_count_kernel, dim3((uint32_t)a.nq), dim3(256), 0, s, a, sm, m);

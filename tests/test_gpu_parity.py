@@ -790,6 +790,38 @@ def test_search_replays_from_a_hip_graph(gpu_device):
             p.close()
 
 
+def test_small_batches_take_fewer_launches_and_give_the_same_results(gpu_device):
+    """Batches of few queries build their work list inside the coarse selection and the threshold kernel
+    (no launches of its own), and a few single inserts are assigned by the centroid kernel itself.  Which
+    launch sequence a query goes through must not show in its result: the rows of a small call are
+    bit-identical to the same queries' rows in a batch large enough for the separate work-list kernels (and,
+    with 512 queries or more, the rows-in-registers kernel for the lists many queries probe); single inserts
+    and inserts of a few vectors land in the lists the oracle's rule picks."""
+    cfg = W.scaled(W.C1, n=24000, nlist=96)
+    for storage, metric in ((F32, IP), (F32, L2), (F16, L2)):
+        p, _ = make_pair(cfg, metric=metric, storage=storage)
+        try:
+            k, nprobe, big = 10, 24, 1024  # 1024 x 24 pairs: beyond what the fused path takes
+            q = np.concatenate([W.queries(cfg, 30 + b, 256) for b in range(big // 256)])
+            say(f"large batch storage={storage} metric={metric}")
+            bi, bv = p.gpu.search(dev(q), k, nprobe)
+            bi, bv = bi.cpu().numpy(), bv.cpu().numpy()
+            p.check_search(q[:64], k, nprobe, where="64 queries on their own")
+            for lo, cnt in ((0, 1), (5, 16), (100, 48), (900, 64)):
+                say(f"small batch [{lo}, {lo + cnt})")
+                si, sv = p.gpu.search(dev(q[lo:lo + cnt]), k, nprobe)
+                assert np.array_equal(si.cpu().numpy(), bi[lo:lo + cnt]), f"ids of queries {lo}..{lo + cnt} differ"
+                assert np.array_equal(sv.cpu().numpy(), bv[lo:lo + cnt]), f"values of queries {lo}..{lo + cnt} differ"
+            new = W.inserts(cfg, 3, 40)
+            say("single inserts")
+            for r in range(8):
+                p.insert_both(new[r:r + 1], where=f"single insert {r}")
+            p.insert_both(new[8:40], where="insert of 32")
+            p.check_search(q[:32], k, nprobe, where="after the inserts")
+        finally:
+            p.close()
+
+
 def test_reserved_workspace_never_grows_and_capture_refuses_growth(gpu_device):
     """Section 5: operations must not block the caller.  After one pk_workspace_reserve a config-5
     style stream of {insert 1; search 16} (and a batch insert, and a larger search within the
