@@ -139,8 +139,8 @@ __device__ __forceinline__ void refresh_slot(const ScanArgs &a, const Slots &s, 
 
 // Gated emission of one 32-row block.  The lane holds, for each of its 4 * MT slots m, the values of
 // rows r0 (nt = 0) and r0 + 16 (nt = 1); the 16 lanes of a group share slot m.  Room in the query's
-// region is reserved with one atomic per slot and group; all of a block's reservations are issued
-// before the first answer is used, so a block pays one round trip to the counters, not one per slot.
+// region is reserved with one atomic per slot and group; the reservations of sixteen slots are issued
+// before the first answer is used, so they cost one round trip to the counters, not one per slot.
 template <int MT>
 __device__ __forceinline__ void emit_block(const ScanArgs &a, const Slots &s, f32x4 (&acc)[MT][2], int rb, int ln, int lg,
                                            int nrows, uint32_t qcnt, uint32_t row0, gfloats txn)
@@ -175,15 +175,16 @@ __device__ __forceinline__ void emit_block(const ScanArgs &a, const Slots &s, f3
     }
     if (__ballot(cand != 0u) == 0ull) return; // the usual case: nothing survives
 
-    uint32_t base[MT * 4], groups[MT * 4]; // answer of the reservation; the group's survivors (nt = 0 low half)
-    uint32_t any = 0;                      // wave-uniform: slots j with a survivor somewhere in the wave
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
+        if (__ballot(((cand >> (8 * mt)) & 0xffu) != 0u) == 0ull) continue; // wave-uniform
+        uint32_t base[4], groups[4]; // answer of the reservation; the group's survivors (nt = 0 in the low half)
+        uint32_t any = 0;            // wave-uniform: slots i with a survivor somewhere in the wave
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int j = mt * 4 + i, m = mt * 16 + lg * 4 + i;
-            base[j] = 0;
-            groups[j] = 0;
+            base[i] = 0;
+            groups[i] = 0;
             if (__ballot(((cand >> (2 * j)) & 3u) != 0u) == 0ull) continue;
             bool p[2];
             uint32_t b[2] = {0u, 0u};
@@ -197,11 +198,11 @@ __device__ __forceinline__ void emit_block(const ScanArgs &a, const Slots &s, f3
             }
             const uint32_t g0 = (uint32_t)(__ballot(p[0]) >> (lg * 16)) & 0xffffu;
             const uint32_t g1 = (uint32_t)(__ballot(p[1]) >> (lg * 16)) & 0xffffu;
-            groups[j] = g0 | (g1 << 16);
-            if (__ballot(groups[j] != 0u) == 0ull) continue;
-            any |= 1u << j;
-            if (groups[j] != 0u) {
-                if (ln == 0) base[j] = atomicAdd(&a.ccnt[s.q[m]], (uint32_t)__popc(groups[j]));
+            groups[i] = g0 | (g1 << 16);
+            if (__ballot(groups[i] != 0u) == 0ull) continue;
+            any |= 1u << i;
+            if (groups[i] != 0u) {
+                if (ln == 0) base[i] = atomicAdd(&a.ccnt[s.q[m]], (uint32_t)__popc(groups[i]));
                 if (a.use_hist) {
                     // count the emitted candidates per bucket; one atomic for the group's rows of one
                     // half when they share a bucket (the usual case)
@@ -222,15 +223,12 @@ __device__ __forceinline__ void emit_block(const ScanArgs &a, const Slots &s, f3
                 }
             }
         }
-    }
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int j = mt * 4 + i, m = mt * 16 + lg * 4 + i;
-            if (((any >> j) & 1u) == 0u) continue; // wave-uniform
-            const uint32_t first = __shfl(base[j], lg * 16);
-            const uint32_t g0 = groups[j] & 0xffffu, g1 = groups[j] >> 16;
+            const int m = mt * 16 + lg * 4 + i;
+            if (((any >> i) & 1u) == 0u) continue; // wave-uniform
+            const uint32_t first = __shfl(base[i], lg * 16);
+            const uint32_t g0 = groups[i] & 0xffffu, g1 = groups[i] >> 16;
             const uint32_t below = (1u << ln) - 1u;
             // a region that is full keeps counting (the selection then rescores the query) but stores nothing
             if ((g0 >> ln) & 1u) {
@@ -367,30 +365,22 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(3, 8
         if (qbeg != cur_qbeg || qcnt != cur_qcnt) {
             __syncthreads(); // everyone is done with the previous query group
             const int mrows = qrows < MQ ? qheld : (int)((qcnt + 15u) & ~15u); // rows past the group's last: zeros
-            // four pieces per thread at a time: their slot numbers first, then the four row pieces, so that
-            // a round costs two trips to memory however many pieces it moves
+            // two pieces per thread at a time: their slot numbers first, then the row pieces, so that a
+            // round costs two trips to memory, not four
             const int total = mrows * chunks_per_row;
-            for (int idx0 = tid; idx0 < total; idx0 += 4 * WAVES * 64) {
-                int mm[4], cc[4];
-                uint32_t sq[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int idx = idx0 + u * WAVES * 64;
-                    mm[u] = idx / chunks_per_row;
-                    cc[u] = idx - mm[u] * chunks_per_row;
-                    sq[u] = idx < total && (uint32_t)mm[u] < qcnt ? a.slot_query[qbeg + mm[u]] : 0xffffffffu;
-                }
-                u32x4 v[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    v[u] = u32x4{0u, 0u, 0u, 0u};
-                    if (sq[u] != 0xffffffffu)
-                        v[u] = *reinterpret_cast<const u32x4 *>(a.qs + (size_t)sq[u] * row_bytes + (size_t)cc[u] * 16);
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    if (idx0 + u * WAVES * 64 < total)
-                        *reinterpret_cast<u32x4 *>(qtile + (size_t)mm[u] * qstride + (size_t)cc[u] * 16) = v[u];
+            for (int idx0 = tid; idx0 < total; idx0 += 2 * WAVES * 64) {
+                const int idx1 = idx0 + WAVES * 64;
+                const int m0 = idx0 / chunks_per_row, m1 = idx1 / chunks_per_row;
+                const uint32_t sq0 = (uint32_t)m0 < qcnt ? a.slot_query[qbeg + m0] : 0xffffffffu;
+                const uint32_t sq1 = idx1 < total && (uint32_t)m1 < qcnt ? a.slot_query[qbeg + m1] : 0xffffffffu;
+                u32x4 v0 = {0u, 0u, 0u, 0u}, v1 = {0u, 0u, 0u, 0u};
+                if (sq0 != 0xffffffffu)
+                    v0 = *reinterpret_cast<const u32x4 *>(a.qs + (size_t)sq0 * row_bytes + (size_t)(idx0 - m0 * chunks_per_row) * 16);
+                if (sq1 != 0xffffffffu)
+                    v1 = *reinterpret_cast<const u32x4 *>(a.qs + (size_t)sq1 * row_bytes + (size_t)(idx1 - m1 * chunks_per_row) * 16);
+                *reinterpret_cast<u32x4 *>(qtile + (size_t)m0 * qstride + (size_t)(idx0 - m0 * chunks_per_row) * 16) = v0;
+                if (idx1 < total)
+                    *reinterpret_cast<u32x4 *>(qtile + (size_t)m1 * qstride + (size_t)(idx1 - m1 * chunks_per_row) * 16) = v1;
             }
             load_slots<MQ, GATED>(a, s, tid, qbeg, qcnt);
             __syncthreads();
