@@ -1280,19 +1280,42 @@ int pk_delete(pk_index *ix, const int64_t *ids, int64_t m, int64_t *n_removed, v
     if (n_removed) *n_removed = 0;
     if (m == 0) return PK_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const size_t need = round_up((size_t)kDeleteChunk * sizeof(int64_t), 256) + 256;
-    PK_TRY(ensure_ws(ix, need, s));
-    int64_t *sorted = reinterpret_cast<int64_t *>(ix->ws);
-    unsigned long long *counter =
-        reinterpret_cast<unsigned long long *>(ix->ws + round_up((size_t)kDeleteChunk * sizeof(int64_t), 256));
-    PK_HIP(launch_fill_u32(reinterpret_cast<uint32_t *>(counter), 0u, 2, s));
-    for (int64_t i0 = 0; i0 < m; i0 += kDeleteChunk) {
-        const int mc = (int)std::min<int64_t>(kDeleteChunk, m - i0);
-        PK_HIP(launch_delete(ix->dev, ix->cfg.nlist, ids + i0, mc, sorted, counter, s));
-    }
+    Carver c{nullptr, 0};
+    DeleteArgs da{};
+    auto lay = [&](Carver &cv) {
+        da.sorted = cv.take<int64_t>(kDeleteChunk);
+        da.unit_start = cv.take<uint32_t>((size_t)ix->cfg.nlist + 1);
+        da.hits = cv.take<unsigned long long>(kDeleteChunk);
+        da.hit_len0 = cv.take<uint32_t>(kDeleteChunk);
+        da.hit_seg0 = cv.take<uint32_t>(kDeleteChunk);
+        da.hit_cnt = cv.take<uint32_t>(kDeleteChunk);
+        da.scal = cv.take<uint32_t>(4);
+        da.removed = cv.take<unsigned long long>(1);
+    };
+    lay(c);
+    PK_TRY(ensure_ws(ix, c.off + 256, s));
+    c = Carver{ix->ws, 0};
+    lay(c);
+    da.ix = ix->dev;
+    da.nlist = ix->cfg.nlist;
+    da.grid = ix->num_cu * 8;
+    PK_HIP(launch_fill_u32(da.scal, 0u, 4, s));
+    PK_HIP(launch_fill_u32(reinterpret_cast<uint32_t *>(da.removed), 0u, 2, s));
     unsigned long long removed = 0;
-    PK_HIP(hipMemcpyAsync(&removed, counter, sizeof(removed), hipMemcpyDeviceToHost, s));
-    PK_HIP(hipStreamSynchronize(s));
+    for (int pass = 0; pass < 1 << 20; ++pass) {
+        for (int64_t i0 = 0; i0 < m; i0 += kDeleteChunk) {
+            da.ids = ids + i0;
+            da.m = (int)std::min<int64_t>(kDeleteChunk, m - i0);
+            PK_HIP(launch_delete(da, s));
+        }
+        // more rows carried the ids than one pass takes (several rows under one id): go again
+        uint32_t again = 0;
+        PK_HIP(hipMemcpyAsync(&removed, da.removed, sizeof(removed), hipMemcpyDeviceToHost, s));
+        PK_HIP(hipMemcpyAsync(&again, da.scal + 2, sizeof(again), hipMemcpyDeviceToHost, s));
+        PK_HIP(hipStreamSynchronize(s));
+        if (!again) break;
+        PK_HIP(launch_fill_u32(da.scal + 2, 0u, 1, s));
+    }
     ix->n_total -= (int64_t)removed;
     if (n_removed) *n_removed = (int64_t)removed;
     return PK_OK;

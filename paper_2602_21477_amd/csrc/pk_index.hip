@@ -257,16 +257,25 @@ __device__ __forceinline__ const Arena &locate(const DevIndex &ix, uint32_t l, u
     return ar;
 }
 
-// sorts the ids to delete (at most kDeleteChunk) so that the list kernel can search them
-__global__ __launch_bounds__(1024) void delete_sort_kernel(const int64_t *ids, int m, int64_t *sorted)
+// Deleting by id (Section 5's interface: delete, and update as delete + insert) in four launches, every
+// one of them parallel over what it works on, so that a list of 400 000 rows costs what its share of the
+// index's rows costs:
+//   prepare  one workgroup: sorts the ids; cuts every list into units of kDeleteUnit rows (prefix sum)
+//   find     many workgroups: every row's id is looked up among the sorted ids (held in LDS); the rows
+//            to go are noted as (list, position)
+//   plan     one workgroup: sorts the noted rows (so a list's rows are neighbours, by position), notes
+//            for each where its list's rows start and how long the list was, and shortens the lists
+//   move     a list that loses c rows keeps its first len - c positions: the rows to go among them are
+//            holes, and as many rows beyond them stay; the i-th row that stays fills the i-th hole.
+//            Every move reads and writes rows no other move touches, so they all run at once.
+// Lists are unordered sets: no tombstones, nothing for the scan to skip.  The pages a list no longer
+// reaches stay its own for later inserts.
+
+__device__ __forceinline__ void sort_keys_lds(unsigned long long *s_keys, int n2)
 {
-    __shared__ unsigned long long s_keys[kDeleteChunk];
-    for (int i = threadIdx.x; i < kDeleteChunk; i += blockDim.x)
-        s_keys[i] = i < m ? (unsigned long long)ids[i] ^ 0x8000000000000000ull : ~0ull; // order of signed values
-    __syncthreads();
-    for (int k = 2; k <= kDeleteChunk; k <<= 1)
+    for (int k = 2; k <= n2; k <<= 1)
         for (int j = k >> 1; j > 0; j >>= 1) {
-            for (int i = threadIdx.x; i < kDeleteChunk; i += blockDim.x) {
+            for (int i = threadIdx.x; i < n2; i += blockDim.x) {
                 const int p = i ^ j;
                 if (p > i) {
                     const unsigned long long a = s_keys[i], b = s_keys[p];
@@ -278,85 +287,171 @@ __global__ __launch_bounds__(1024) void delete_sort_kernel(const int64_t *ids, i
             }
             __syncthreads();
         }
-    for (int i = threadIdx.x; i < m; i += blockDim.x) sorted[i] = (int64_t)(s_keys[i] ^ 0x8000000000000000ull);
 }
 
-// One workgroup per list.  Positions are examined from the end of the list downwards; a row
-// whose id is to go is overwritten by the list's last row (already examined, so it stays)
-// and the list shrinks by one: lists are unordered sets, no tombstones, nothing for the scan
-// to skip.  The pages the list no longer reaches stay its own for later inserts.
-__global__ __launch_bounds__(256) void delete_kernel(const DevIndex *ixp, const int64_t *sorted, int m,
-                                                     unsigned long long *removed)
+// first index in keys[0, n) whose key is not below `key`
+__device__ __forceinline__ uint32_t lower_bound_u64(const unsigned long long *keys, uint32_t n, unsigned long long key)
 {
-    __shared__ uint32_t s_hit[256];
-    __shared__ uint32_t s_nhit;
-    const DevIndex &ix = *ixp;
-    const uint32_t l = blockIdx.x;
-    const uint32_t len0 = ix.list_len[l];
-    if (len0 == 0) return;
-    uint32_t len = len0;
-    const int row_bytes = ix.row_bytes;
-    for (int64_t base = (int64_t)((len0 - 1) / 256u) * 256; base >= 0; base -= 256) {
-        if (threadIdx.x == 0) s_nhit = 0;
-        __syncthreads();
-        // descending positions inside the chunk: thread 0 takes the highest
-        const uint32_t pos = (uint32_t)base + 255u - threadIdx.x;
-        bool hit = false;
-        if (pos < len0) {
+    uint32_t lo = 0, hi = n;
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (keys[mid] < key) lo = mid + 1;
+        else hi = mid;
+    }
+    return lo;
+}
+
+__global__ __launch_bounds__(1024) void delete_prepare_kernel(DeleteArgs a)
+{
+    __shared__ unsigned long long s_keys[kDeleteChunk];
+    __shared__ uint32_t s_wave[17];
+    int n2 = 2;
+    while (n2 < a.m) n2 <<= 1;
+    for (int i = threadIdx.x; i < n2; i += blockDim.x)
+        s_keys[i] = i < a.m ? (unsigned long long)a.ids[i] ^ 0x8000000000000000ull : ~0ull; // order of signed values
+    __syncthreads();
+    sort_keys_lds(s_keys, n2);
+    for (int i = threadIdx.x; i < a.m; i += blockDim.x) a.sorted[i] = (int64_t)(s_keys[i] ^ 0x8000000000000000ull);
+    const DevIndex &ix = *a.ix;
+    for (int l = threadIdx.x; l < a.nlist; l += blockDim.x) a.unit_start[l] = (ix.list_len[l] + kDeleteUnit - 1) / kDeleteUnit;
+    __syncthreads();
+    const uint32_t units = block_exscan(a.unit_start, a.unit_start, (uint32_t)a.nlist, s_wave);
+    if (threadIdx.x == 0) {
+        a.unit_start[a.nlist] = units;
+        a.scal[0] = 0;
+        a.scal[1] = units;
+    }
+}
+
+__global__ __launch_bounds__(256) void delete_find_kernel(DeleteArgs a)
+{
+    __shared__ int64_t s_ids[kDeleteChunk];
+    const DevIndex &ix = *a.ix;
+    for (int i = threadIdx.x; i < a.m; i += blockDim.x) s_ids[i] = a.sorted[i];
+    __syncthreads();
+    const uint32_t units = a.scal[1];
+    for (uint32_t u = blockIdx.x; u < units; u += gridDim.x) {
+        uint32_t lo = 0, hi = (uint32_t)a.nlist - 1; // the last list whose units start at or before u
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi + 1) >> 1;
+            if (a.unit_start[mid] <= u) lo = mid;
+            else hi = mid - 1;
+        }
+        const uint32_t l = lo, len = ix.list_len[l];
+        const uint32_t base = (u - a.unit_start[l]) * (uint32_t)kDeleteUnit;
+#pragma unroll
+        for (int j = 0; j < kDeleteUnit / 256; ++j) {
+            const uint32_t pos = base + (uint32_t)j * 256u + threadIdx.x;
+            if (pos >= len) continue;
             size_t local;
             const Arena &ar = locate(ix, l, pos, local);
             const int64_t id = ar.ids[local];
-            int lo = 0, hi = m;
-            while (lo < hi) {
-                const int mid = (lo + hi) / 2;
-                if (sorted[mid] < id) lo = mid + 1;
-                else hi = mid;
+            int b = 0, e = a.m;
+            while (b < e) {
+                const int mid = (b + e) >> 1;
+                if (s_ids[mid] < id) b = mid + 1;
+                else e = mid;
             }
-            hit = lo < m && sorted[lo] == id;
-        }
-        // hits in descending position order: wave by wave, lane by lane
-        for (int w = 0; w < 4; ++w) {
-            if ((int)(threadIdx.x >> 6) == w) {
-                const unsigned long long mask = __ballot(hit);
-                const uint32_t before = (uint32_t)__popcll(mask & ((1ull << (threadIdx.x & 63)) - 1ull));
-                if (hit) s_hit[s_nhit + before] = pos;
-                __builtin_amdgcn_wave_barrier();
-                if ((threadIdx.x & 63) == 0) s_nhit += (uint32_t)__popcll(mask);
+            if (b < a.m && s_ids[b] == id) {
+                const uint32_t at = atomicAdd(&a.scal[0], 1u);
+                if (at < (uint32_t)kDeleteChunk) a.hits[at] = ((unsigned long long)l << 32) | pos;
             }
-            __syncthreads();
         }
-        const uint32_t nhit = s_nhit;
-        for (uint32_t h = 0; h < nhit; ++h) {
-            const uint32_t p = s_hit[h], last = len - 1;
-            if (p != last) {
-                size_t ls, ld;
-                const Arena &as = locate(ix, l, last, ls);
-                const Arena &ad = locate(ix, l, p, ld);
-                const uint4 *src = reinterpret_cast<const uint4 *>(as.vec + ls * (size_t)row_bytes);
-                uint4 *dst = reinterpret_cast<uint4 *>(ad.vec + ld * (size_t)row_bytes);
-                for (int i = threadIdx.x; i < row_bytes / 16; i += blockDim.x) dst[i] = src[i];
-                if (threadIdx.x == 0) {
-                    ad.norm[ld] = as.norm[ls];
-                    ad.ids[ld] = as.ids[ls];
-                }
-            }
-            len -= 1;
-            __syncthreads(); // the moved row may be the source of the next move
-        }
-    }
-    if (threadIdx.x == 0 && len != len0) {
-        ix.list_len[l] = len;
-        atomicAdd(removed, (unsigned long long)(len0 - len));
     }
 }
 
-hipError_t launch_delete(const DevIndex *ix, int nlist, const int64_t *ids, int m, int64_t *sorted,
-                         unsigned long long *removed, hipStream_t s)
+__global__ __launch_bounds__(1024) void delete_plan_kernel(DeleteArgs a)
 {
-    if (m <= 0) return hipSuccess;
-    if (m > kDeleteChunk) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(delete_sort_kernel, dim3(1), dim3(1024), 0, s, ids, m, sorted);
-    hipLaunchKernelGGL(delete_kernel, dim3(nlist), dim3(256), 0, s, ix, sorted, m, removed);
+    __shared__ unsigned long long s_keys[kDeleteChunk];
+    const DevIndex &ix = *a.ix;
+    const uint32_t found = a.scal[0];
+    const uint32_t nh = found < (uint32_t)kDeleteChunk ? found : (uint32_t)kDeleteChunk;
+    if (nh == 0) return;
+    int n2 = 2;
+    while ((uint32_t)n2 < nh) n2 <<= 1;
+    for (int i = threadIdx.x; i < n2; i += blockDim.x) s_keys[i] = (uint32_t)i < nh ? a.hits[i] : ~0ull;
+    __syncthreads();
+    sort_keys_lds(s_keys, n2);
+    for (uint32_t g = threadIdx.x; g < nh; g += blockDim.x) {
+        const unsigned long long key = s_keys[g];
+        const uint32_t l = (uint32_t)(key >> 32);
+        const uint32_t seg0 = lower_bound_u64(s_keys, nh, (unsigned long long)l << 32);
+        const uint32_t seg1 = lower_bound_u64(s_keys, nh, ((unsigned long long)l + 1ull) << 32);
+        a.hits[g] = key;
+        a.hit_seg0[g] = seg0;
+        a.hit_cnt[g] = seg1 - seg0;
+        a.hit_len0[g] = ix.list_len[l];
+    }
+    __syncthreads(); // every list length has been read (and stored with the hits) before any is changed
+    for (uint32_t g = threadIdx.x; g < nh; g += blockDim.x) {
+        const uint32_t l = (uint32_t)(s_keys[g] >> 32);
+        if (g == 0 || (uint32_t)(s_keys[g - 1] >> 32) != l) {
+            const uint32_t seg1 = lower_bound_u64(s_keys, nh, ((unsigned long long)l + 1ull) << 32);
+            ix.list_len[l] -= seg1 - g;
+        }
+    }
+    if (threadIdx.x == 0) {
+        atomicAdd(a.removed, (unsigned long long)nh);
+        if (found > nh) a.scal[2] = 1u;
+    }
+}
+
+__global__ __launch_bounds__(256) void delete_move_kernel(DeleteArgs a)
+{
+    __shared__ unsigned long long s_keys[kDeleteChunk];
+    __shared__ uint32_t s_list[256], s_src[256], s_dst[256];
+    __shared__ uint32_t s_n;
+    const DevIndex &ix = *a.ix;
+    const uint32_t found = a.scal[0];
+    const uint32_t nh = found < (uint32_t)kDeleteChunk ? found : (uint32_t)kDeleteChunk;
+    if (blockIdx.x * 256u >= nh) return;
+    for (uint32_t i = threadIdx.x; i < nh; i += blockDim.x) s_keys[i] = a.hits[i];
+    if (threadIdx.x == 0) s_n = 0;
+    __syncthreads();
+    const uint32_t g = blockIdx.x * 256u + threadIdx.x;
+    if (g < nh) {
+        // this thread looks at one position beyond the list's new end: position number t of the c there are
+        const uint32_t l = (uint32_t)(s_keys[g] >> 32);
+        const uint32_t seg0 = a.hit_seg0[g], c = a.hit_cnt[g], newlen = a.hit_len0[g] - c;
+        const unsigned long long *seg = s_keys + seg0;
+        const uint32_t t = g - seg0, p = newlen + t;
+        const unsigned long long lkey = (unsigned long long)l << 32;
+        const uint32_t holes = lower_bound_u64(seg, c, lkey | newlen); // rows to go among the positions that stay
+        const uint32_t idx = lower_bound_u64(seg, c, lkey | p);
+        if (!(idx < c && seg[idx] == (lkey | p))) {
+            // the row stays: it is number t - (rows to go beyond the new end and before it) of those that do
+            const uint32_t i = t - (idx - holes);
+            const uint32_t at = atomicAdd(&s_n, 1u);
+            s_list[at] = l;
+            s_src[at] = p;
+            s_dst[at] = (uint32_t)seg[i];
+        }
+    }
+    __syncthreads();
+    const uint32_t moves = s_n;
+    const int row_bytes = ix.row_bytes, lane = threadIdx.x & 63;
+    for (uint32_t mv = threadIdx.x >> 6; mv < moves; mv += 4) { // a wave per move
+        size_t ls, ld;
+        const Arena &as = locate(ix, s_list[mv], s_src[mv], ls);
+        const Arena &ad = locate(ix, s_list[mv], s_dst[mv], ld);
+        const uint4 *src = reinterpret_cast<const uint4 *>(as.vec + ls * (size_t)row_bytes);
+        uint4 *dst = reinterpret_cast<uint4 *>(ad.vec + ld * (size_t)row_bytes);
+        for (int i = lane; i < row_bytes / 16; i += 64) dst[i] = src[i];
+        if (lane == 0) {
+            ad.norm[ld] = as.norm[ls];
+            ad.ids[ld] = as.ids[ls];
+        }
+    }
+}
+
+hipError_t launch_delete(const DeleteArgs &a, hipStream_t s)
+{
+    if (a.m <= 0) return hipSuccess;
+    if (a.m > kDeleteChunk || a.nlist < 1 || a.grid < 1) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(delete_prepare_kernel, dim3(1), dim3(1024), 0, s, a);
+    hipLaunchKernelGGL(delete_find_kernel, dim3(a.grid), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(delete_plan_kernel, dim3(1), dim3(1024), 0, s, a);
+    hipLaunchKernelGGL(delete_move_kernel, dim3(kDeleteChunk / 256), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 

@@ -498,11 +498,25 @@ hipError_t launch_scatter_build(const DevIndex *ix, const float *x, const int64_
                                 int64_t n, int64_t id0, uint32_t *fill, hipStream_t s);
 hipError_t launch_store_centroids(const float *c, int nlist, int d, int dpad32, int nlist_pad, int metric,
                                   float *cent, float *cnorm, hipStream_t s);
-// removes the rows whose id is among ids[0..m), m <= kDeleteChunk (sorted: scratch of kDeleteChunk ids;
-// removed: device counter that receives the number of rows removed, added to)
+// Removes the rows whose id is among ids[0..m), m <= kDeleteChunk.  One pass removes at most kDeleteChunk
+// rows; if more rows carry the ids (several rows under one id), the sticky flag says so and the caller
+// runs the pass again.
 constexpr int kDeleteChunk = 4096;
-hipError_t launch_delete(const DevIndex *ix, int nlist, const int64_t *ids, int m, int64_t *sorted,
-                         unsigned long long *removed, hipStream_t s);
+constexpr int kDeleteUnit = 1024; // rows of one list that a workgroup examines at a time
+struct DeleteArgs {
+    const DevIndex *ix;
+    int nlist, m, grid;        // grid: workgroups of the search over the rows
+    const int64_t *ids;        // [m]
+    int64_t *sorted;           // scratch [kDeleteChunk]
+    uint32_t *unit_start;      // scratch [nlist + 1]: units of the lists before each one
+    unsigned long long *hits;  // scratch [kDeleteChunk]: (list << 32) | position of the rows to go
+    uint32_t *hit_len0;        // scratch [kDeleteChunk]: per hit, its list's length before the pass,
+    uint32_t *hit_seg0;        //   where the list's hits start in the sorted hits,
+    uint32_t *hit_cnt;         //   and how many they are
+    uint32_t *scal;            // [0] rows found in this pass, [1] units, [2] sticky: a pass found more than it could take
+    unsigned long long *removed; // device counter, added to
+};
+hipError_t launch_delete(const DeleteArgs &a, hipStream_t s);
 // copies every list into the contiguous extents of `dst` (dst's tables are already in place)
 // (skip: optional [dst nlist] flags of lists the caller fills itself; lists beyond src's are skipped too)
 hipError_t launch_compact_pages(const DevIndex *src, const DevIndex *dst, uint32_t new_pages, const uint8_t *skip,

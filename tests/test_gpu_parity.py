@@ -501,6 +501,52 @@ def test_delete_update_and_page_reuse(gpu_device, storage, metric):
         p.close()
 
 
+def test_delete_from_a_very_long_list(gpu_device):
+    """Deleting is parallel over the rows, not over the lists: 4096 ids out of a list of more than
+    400 000 rows (most of them at its tail, so that rows to go and rows that stay meet beyond the list's
+    new end), twice in a row, then ids that several rows carry (more rows than one pass takes).  List
+    lengths and counts follow the oracle, searches over the shrunken list match it, and the call takes
+    milliseconds, not the seconds a walk along the list would."""
+    import time
+    rng = np.random.default_rng(11)
+    d, nlist, n_big, n_rest = 32, 8, 420000, 30000
+    cent = rng.standard_normal((nlist, d)).astype(np.float32) * 4
+    x = np.concatenate([cent[0] + 0.3 * rng.standard_normal((n_big, d)).astype(np.float32),
+                        cent[rng.integers(1, nlist, n_rest)] + 0.3 * rng.standard_normal((n_rest, d)).astype(np.float32)])
+    ids = np.arange(len(x), dtype=np.int64) * 3 + 1
+    ids[200000:205000] = 77  # 5000 rows under one id
+    p = Pair(x, cent, L2, F32, ids=ids, insert_reserve=1000)
+    try:
+        assert p.orc.list_lengths()[0] >= 400000
+        q = (cent[0] + 0.3 * rng.standard_normal((32, d))).astype(np.float32)
+        tail = ids[n_big - 3000:n_big]  # the list's last rows in build order
+        free = np.concatenate([np.arange(0, 200000), np.arange(205000, n_big - 3000)])  # not the shared id, not the tail
+        gone = np.concatenate([tail[::2], ids[rng.choice(free, 4096 - 1500, replace=False)]])
+        for rep in range(2):
+            say(f"delete of {len(gone)} ids, call {rep}")
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            n_g = p.gpu.delete(dev(gone))
+            ms = (time.perf_counter() - t0) * 1e3
+            n_o = p.orc.delete(gone)
+            print(f"[delete] {len(gone)} ids, {n_g} rows removed from a {int(p.orc.list_lengths()[0]) + n_g}-row list "
+                  f"in {ms:.2f} ms", flush=True)
+            assert n_g == n_o and (n_g > 4000 if rep == 0 else n_g == 0)
+            assert ms < 50, f"delete took {ms:.1f} ms"
+            assert np.array_equal(p.gpu.list_lengths(), p.orc.list_lengths())
+        p.check_search(q, 10, 2, where="after the delete")
+        say("delete of an id that 5000 rows carry")
+        assert p.gpu.delete(dev(np.array([77, ids[5]]))) == p.orc.delete(np.array([77, ids[5]])) == 5001
+        assert np.array_equal(p.gpu.list_lengths(), p.orc.list_lengths())
+        st = p.gpu.stats()
+        assert st.n_total == p.orc.ntotal and st.device_error == 0
+        p.check_search(q, 10, 2, where="after the second delete")
+        full = np.tile(np.arange(nlist, dtype=np.int32), (len(q), 1))
+        p.check_scan(q, 20, full, where="all lists after the deletes")
+    finally:
+        p.close()
+
+
 @pytest.mark.parametrize("storage,metric", [(F32, L2), (F16, IP)])
 def test_ivf_split(gpu_device, storage, metric):
     """Lists over the threshold are split by a 2-means on the device.  Against the oracle's own split:
