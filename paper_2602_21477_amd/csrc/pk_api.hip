@@ -1402,7 +1402,6 @@ struct SplitJob {
     int list;              // the list (keeps side 0); the new list is nlist_old + (position of the job)
     uint32_t len, len_new; // members before the split, members that move to the new list
     int32_t *side;         // DEVICE [len] 0 / 1
-    float *cent2;          // DEVICE [2][d] the two centroids
 };
 
 // Moves the index into `arena`, every list in one contiguous extent.  threshold > 0: lists
@@ -1438,57 +1437,70 @@ int relayout(pk_index *ix, void *arena, size_t arena_bytes, int64_t threshold, i
         release();
         return code;
     };
+    SplitArgs sp{};
+    uint32_t *slots_all = nullptr;       // DEVICE scratch of the scatter, one part per job
+    std::vector<uint32_t> job_row0;      // members of the jobs before each one
     if (threshold > 0) {
-        uint32_t longest = 0;
-        for (int l = 0; l < nlist0; ++l)
-            if ((int64_t)len[l] > threshold) longest = std::max(longest, len[l]);
-        float *rows = nullptr;
-        int64_t *ids = nullptr;
-        if (longest > 0) {
-            if (hipMalloc(reinterpret_cast<void **>(&rows), (size_t)longest * d * sizeof(float)) != hipSuccess)
-                return fail(PK_ERR_NOMEM);
-            owned.push_back(rows);
-            if (hipMalloc(reinterpret_cast<void **>(&ids), (size_t)longest * sizeof(int64_t)) != hipSuccess)
-                return fail(PK_ERR_NOMEM);
-            owned.push_back(ids);
-        }
-        std::vector<int64_t> hid;
-        std::vector<int32_t> hside;
+        std::vector<uint32_t> jl, jn, ju;
+        uint64_t rows = 0, units = 0;
         for (int l = 0; l < nlist0; ++l) {
             if ((int64_t)len[l] <= threshold) continue;
             if (nlist0 + (int)jobs.size() + 1 > 0x3fffffff) return fail(PK_ERR_UNSUPPORTED);
             SplitJob j{};
             j.list = l;
             j.len = len[l];
-            if (hipMalloc(reinterpret_cast<void **>(&j.side), (size_t)j.len * sizeof(int32_t)) != hipSuccess)
-                return fail(PK_ERR_NOMEM);
-            owned.push_back(j.side);
-            if (hipMalloc(reinterpret_cast<void **>(&j.cent2), (size_t)2 * d * sizeof(float)) != hipSuccess)
-                return fail(PK_ERR_NOMEM);
-            owned.push_back(j.cent2);
-            if (launch_gather_list(ix->dev, (uint32_t)l, j.len, rows, ids, s) != hipSuccess) return fail(PK_ERR_HIP);
-            // initial centroids: the member with the smallest id and the member with the largest id
-            hid.resize(j.len);
-            if (hipMemcpyAsync(hid.data(), ids, (size_t)j.len * sizeof(int64_t), hipMemcpyDeviceToHost, s) != hipSuccess ||
-                hipStreamSynchronize(s) != hipSuccess)
-                return fail(PK_ERR_HIP);
-            size_t lo = 0, hi = 0;
-            for (size_t r = 1; r < hid.size(); ++r) {
-                if (hid[r] < hid[lo]) lo = r;
-                if (hid[r] > hid[hi]) hi = r;
-            }
-            if (hipMemcpyAsync(j.cent2, rows + lo * d, (size_t)d * sizeof(float), hipMemcpyDeviceToDevice, s) != hipSuccess ||
-                hipMemcpyAsync(j.cent2 + d, rows + hi * d, (size_t)d * sizeof(float), hipMemcpyDeviceToDevice, s) != hipSuccess)
-                return fail(PK_ERR_HIP);
-            const int rc = pk_kmeans(rows, j.len, d, 2, iters, j.cent2, j.side, nullptr, s);
-            if (rc != PK_OK) return fail(rc);
-            hside.resize(j.len);
-            if (hipMemcpy(hside.data(), j.side, (size_t)j.len * sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess)
-                return fail(PK_ERR_HIP);
-            uint32_t ones = 0;
-            for (int32_t v : hside) ones += v != 0;
-            j.len_new = ones;
             jobs.push_back(j);
+            jl.push_back((uint32_t)l);
+            jn.push_back(len[l]);
+            ju.push_back((uint32_t)units);
+            job_row0.push_back((uint32_t)rows);
+            rows += len[l];
+            units += (len[l] + kSplitUnit - 1) / kSplitUnit;
+        }
+        const size_t nj = jobs.size();
+        if (nj > 0) {
+            if (rows > 0xfffffff0ull || units > 0x7fffffffull) return fail(PK_ERR_UNSUPPORTED);
+            ju.push_back((uint32_t)units);
+            // one block of scratch for every job: tables, centroids, sums, counts, sides, scatter slots
+            Carver cv{nullptr, 0};
+            auto lay = [&](Carver &c) {
+                sp.job_list = c.take<uint32_t>(nj);
+                sp.job_len = c.take<uint32_t>(nj);
+                sp.job_unit0 = c.take<uint32_t>(nj + 1);
+                sp.job_row0 = c.take<uint32_t>(nj);
+                sp.cent = c.take<double>(nj * 2 * d);
+                sp.sum = c.take<double>(nj * 2 * d);
+                sp.cnt = c.take<unsigned long long>(nj * 2);
+                sp.cnt_out = c.take<unsigned long long>(nj * 2);
+                sp.side = c.take<int32_t>(rows);
+                slots_all = c.take<uint32_t>(rows);
+            };
+            lay(cv);
+            char *block = nullptr;
+            if (hipMalloc(reinterpret_cast<void **>(&block), cv.off + 256) != hipSuccess) return fail(PK_ERR_NOMEM);
+            owned.push_back(block);
+            cv = Carver{block, 0};
+            lay(cv);
+            sp.ix = ix->dev;
+            sp.njobs = (int)nj;
+            auto up = [&](const uint32_t *dst, const std::vector<uint32_t> &v) {
+                return hipMemcpyAsync(const_cast<uint32_t *>(dst), v.data(), v.size() * 4, hipMemcpyHostToDevice, s);
+            };
+            if (up(sp.job_list, jl) != hipSuccess || up(sp.job_len, jn) != hipSuccess || up(sp.job_unit0, ju) != hipSuccess ||
+                up(sp.job_row0, job_row0) != hipSuccess)
+                return fail(PK_ERR_HIP);
+            if (launch_split_init(sp, s) != hipSuccess) return fail(PK_ERR_HIP);
+            for (int it = 0; it < iters; ++it)
+                if (launch_split_iterate(sp, (uint32_t)units, d, s) != hipSuccess) return fail(PK_ERR_HIP);
+            std::vector<unsigned long long> cnt(nj * 2);
+            if (hipMemcpyAsync(cnt.data(), sp.cnt_out, cnt.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost, s) !=
+                    hipSuccess ||
+                hipStreamSynchronize(s) != hipSuccess) // also keeps the uploaded tables alive until they are read
+                return fail(PK_ERR_HIP);
+            for (size_t t = 0; t < nj; ++t) {
+                jobs[t].len_new = (uint32_t)cnt[2 * t + 1];
+                jobs[t].side = sp.side + job_row0[t];
+            }
         }
     }
     const int ns = (int)jobs.size(), nlist1 = nlist0 + ns;
@@ -1536,12 +1548,7 @@ int relayout(pk_index *ix, void *arena, size_t arena_bytes, int64_t threshold, i
             owned.push_back(dense);
             PK_HIP(hipMemcpy2DAsync(dense, (size_t)d * sizeof(float), O.cent, (size_t)ix->dpad32 * sizeof(float),
                                     (size_t)d * sizeof(float), (size_t)nlist0, hipMemcpyDeviceToDevice, s));
-            for (int t = 0; t < ns; ++t) {
-                PK_HIP(hipMemcpyAsync(dense + (size_t)jobs[t].list * d, jobs[t].cent2, (size_t)d * sizeof(float),
-                                      hipMemcpyDeviceToDevice, s));
-                PK_HIP(hipMemcpyAsync(dense + (size_t)(nlist0 + t) * d, jobs[t].cent2 + d, (size_t)d * sizeof(float),
-                                      hipMemcpyDeviceToDevice, s));
-            }
+            PK_HIP(launch_split_centroids(sp, nlist0, dense, s));
             PK_HIP(launch_store_centroids(dense, nlist1, d, x.dpad32, x.nlist_pad, cfg.metric, cent, cnorm, s));
         }
         PK_HIP(hipMemcpyAsync(N.list_len, nlen.data(), nlen.size() * 4, hipMemcpyHostToDevice, s));
@@ -1562,16 +1569,9 @@ int relayout(pk_index *ix, void *arena, size_t arena_bytes, int64_t threshold, i
             PK_HIP(hipMemcpyAsync(dskip, skip.data(), skip.size(), hipMemcpyHostToDevice, s));
         }
         PK_HIP(launch_compact_pages(ix->dev, ndev, (uint32_t)used, dskip, s));
-        for (int t = 0; t < ns; ++t) {
-            uint32_t *slot = nullptr;
-            if (hipMalloc(reinterpret_cast<void **>(&slot), (size_t)jobs[t].len * sizeof(uint32_t)) != hipSuccess) {
-                (void)hipGetLastError();
-                return PK_ERR_NOMEM;
-            }
-            owned.push_back(slot);
-            PK_HIP(launch_split_list(ix->dev, ndev, (uint32_t)jobs[t].list, (uint32_t)(nlist0 + t), jobs[t].side, slot,
-                                     jobs[t].len, s));
-        }
+        for (int t = 0; t < ns; ++t)
+            PK_HIP(launch_split_list(ix->dev, ndev, (uint32_t)jobs[t].list, (uint32_t)(nlist0 + t), jobs[t].side,
+                                     slots_all + job_row0[(size_t)t], jobs[t].len, s));
         PK_HIP(hipStreamSynchronize(s)); // the old arenas are out of use from here on
         return PK_OK;
     };

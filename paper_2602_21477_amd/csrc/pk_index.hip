@@ -537,6 +537,226 @@ hipError_t launch_gather_list(const DevIndex *ix, uint32_t l, uint32_t len, floa
     return hipGetLastError();
 }
 
+// ---- 2-means of the lists to split
+
+// stored row -> element i as fp32
+__device__ __forceinline__ float row_element(const char *row, int storage, int i)
+{
+    return storage == PK_F16 ? (float)reinterpret_cast<const _Float16 *>(row)[i] : reinterpret_cast<const float *>(row)[i];
+}
+
+// one workgroup per job: the members with the smallest and the largest id become the first centroids
+__global__ __launch_bounds__(1024) void split_init_kernel(SplitArgs a)
+{
+    __shared__ long long s_id[2][16];
+    __shared__ uint32_t s_pos[2][16];
+    const DevIndex &ix = *a.ix;
+    const uint32_t j = blockIdx.x, l = a.job_list[j], len = a.job_len[j];
+    long long lo_id = INT64_MAX, hi_id = INT64_MIN;
+    uint32_t lo_pos = 0xffffffffu, hi_pos = 0xffffffffu;
+    for (uint32_t r = threadIdx.x; r < len; r += blockDim.x) {
+        size_t local;
+        const Arena &ar = locate(ix, l, r, local);
+        const long long id = ar.ids[local];
+        if (id < lo_id || (id == lo_id && r < lo_pos)) {
+            lo_id = id;
+            lo_pos = r;
+        }
+        if (id > hi_id || (id == hi_id && r < hi_pos)) {
+            hi_id = id;
+            hi_pos = r;
+        }
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        const long long oi = __shfl_xor(lo_id, off), pi = __shfl_xor(hi_id, off);
+        const uint32_t op = __shfl_xor(lo_pos, off), pp = __shfl_xor(hi_pos, off);
+        if (oi < lo_id || (oi == lo_id && op < lo_pos)) {
+            lo_id = oi;
+            lo_pos = op;
+        }
+        if (pi > hi_id || (pi == hi_id && pp < hi_pos)) {
+            hi_id = pi;
+            hi_pos = pp;
+        }
+    }
+    if ((threadIdx.x & 63) == 0) {
+        s_id[0][threadIdx.x >> 6] = lo_id;
+        s_pos[0][threadIdx.x >> 6] = lo_pos;
+        s_id[1][threadIdx.x >> 6] = hi_id;
+        s_pos[1][threadIdx.x >> 6] = hi_pos;
+    }
+    __syncthreads();
+    for (int w = 0; w < (int)(blockDim.x >> 6); ++w) { // every thread folds the waves' results the same way
+        if (s_id[0][w] < lo_id || (s_id[0][w] == lo_id && s_pos[0][w] < lo_pos)) {
+            lo_id = s_id[0][w];
+            lo_pos = s_pos[0][w];
+        }
+        if (s_id[1][w] > hi_id || (s_id[1][w] == hi_id && s_pos[1][w] < hi_pos)) {
+            hi_id = s_id[1][w];
+            hi_pos = s_pos[1][w];
+        }
+    }
+    const int d = ix.d;
+    for (int side = 0; side < 2; ++side) {
+        size_t local;
+        const Arena &ar = locate(ix, l, side ? hi_pos : lo_pos, local);
+        const char *row = ar.vec + local * (size_t)ix.row_bytes;
+        for (int i = threadIdx.x; i < d; i += blockDim.x) {
+            a.cent[((size_t)j * 2 + side) * d + i] = (double)row_element(row, ix.storage, i);
+            a.sum[((size_t)j * 2 + side) * d + i] = 0.0;
+        }
+    }
+    if (threadIdx.x < 2) a.cnt[(size_t)j * 2 + threadIdx.x] = 0ull;
+}
+
+// One workgroup per unit of kSplitUnit members of one job; a wave takes a quarter of them, row by row:
+// the lanes share the row's elements, the two squared distances are reduced over the wave (fp32), and the
+// row is added to the wave's running sum of its side.  The four waves' sums meet in LDS and go to the
+// job's sums as one fp64 atomic per element and unit.
+constexpr int kSplitEl = (PK_MAX_DIM + 63) / 64; // elements of a row per lane
+__global__ __launch_bounds__(256) void split_assign_kernel(SplitArgs a)
+{
+    extern __shared__ __align__(16) float s_split[]; // [2][d] centroids, then [4][2][d] the waves' sums
+    __shared__ uint32_t s_ones[4];
+    const DevIndex &ix = *a.ix;
+    const int d = ix.d, storage = ix.storage, row_bytes = ix.row_bytes;
+    const uint32_t P = (uint32_t)ix.P;
+    uint32_t lo = 0, hi = (uint32_t)a.njobs - 1; // the job this unit belongs to
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi + 1) >> 1;
+        if (a.job_unit0[mid] <= blockIdx.x) lo = mid;
+        else hi = mid - 1;
+    }
+    const uint32_t j = lo, l = a.job_list[j], len = a.job_len[j];
+    const uint32_t first = (blockIdx.x - a.job_unit0[j]) * (uint32_t)kSplitUnit;
+    float *s_c = s_split, *s_sum = s_split + 2 * d;
+    for (int i = threadIdx.x; i < 2 * d; i += blockDim.x) s_c[i] = (float)a.cent[(size_t)j * 2 * d + i];
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float c0[kSplitEl], c1[kSplitEl], acc0[kSplitEl], acc1[kSplitEl];
+#pragma unroll
+    for (int e = 0; e < kSplitEl; ++e) {
+        const int i = lane + 64 * e;
+        c0[e] = i < d ? s_c[i] : 0.f;
+        c1[e] = i < d ? s_c[d + i] : 0.f;
+        acc0[e] = acc1[e] = 0.f;
+    }
+    uint32_t ones = 0;
+    const uint32_t r0 = first + (uint32_t)wave * (kSplitUnit / 4);
+    const uint32_t r1 = min(r0 + (uint32_t)(kSplitUnit / 4), len);
+    for (uint32_t r = r0; r < r1;) {
+        // the rows of one page are neighbours in memory
+        const uint32_t lp = r / P, in_page = r - lp * P;
+        const uint32_t pg = phys_page(ix, l, lp);
+        const Arena &ar = arena_of(ix, pg);
+        const char *page = ar.vec + ((size_t)(pg - ar.first_page) * P) * (size_t)row_bytes;
+        const uint32_t n = min(P - in_page, r1 - r);
+        for (uint32_t t = 0; t < n; ++t) {
+            const char *row = page + (size_t)(in_page + t) * row_bytes;
+            float x[kSplitEl], s0 = 0.f, s1 = 0.f;
+#pragma unroll
+            for (int e = 0; e < kSplitEl; ++e) {
+                const int i = lane + 64 * e;
+                x[e] = i < d ? row_element(row, storage, i) : 0.f;
+            }
+#pragma unroll
+            for (int e = 0; e < kSplitEl; ++e) {
+                const float u0 = x[e] - c0[e], u1 = x[e] - c1[e];
+                s0 += u0 * u0;
+                s1 += u1 * u1;
+            }
+            for (int off = 32; off > 0; off >>= 1) {
+                s0 += __shfl_xor(s0, off);
+                s1 += __shfl_xor(s1, off);
+            }
+            const bool second = s1 < s0; // the same in every lane
+            if (second) {
+#pragma unroll
+                for (int e = 0; e < kSplitEl; ++e) acc1[e] += x[e];
+                ++ones;
+            } else {
+#pragma unroll
+                for (int e = 0; e < kSplitEl; ++e) acc0[e] += x[e];
+            }
+            if (lane == 0) a.side[(size_t)a.job_row0[j] + r + t] = second ? 1 : 0;
+        }
+        r += n;
+    }
+#pragma unroll
+    for (int e = 0; e < kSplitEl; ++e) {
+        const int i = lane + 64 * e;
+        if (i < d) {
+            s_sum[((size_t)wave * 2 + 0) * d + i] = acc0[e];
+            s_sum[((size_t)wave * 2 + 1) * d + i] = acc1[e];
+        }
+    }
+    if (lane == 0) s_ones[wave] = ones;
+    __syncthreads();
+    for (int i = threadIdx.x; i < 2 * d; i += blockDim.x) {
+        const double v = ((double)s_sum[i] + (double)s_sum[2 * d + i]) + ((double)s_sum[4 * d + i] + (double)s_sum[6 * d + i]);
+        if (v != 0.0) atomicAdd(&a.sum[(size_t)j * 2 * d + i], v);
+    }
+    if (threadIdx.x == 0) {
+        const uint32_t rows = first < len ? min((uint32_t)kSplitUnit, len - first) : 0u;
+        const uint32_t n1 = s_ones[0] + s_ones[1] + s_ones[2] + s_ones[3];
+        if (rows - n1) atomicAdd(&a.cnt[(size_t)j * 2], (unsigned long long)(rows - n1));
+        if (n1) atomicAdd(&a.cnt[(size_t)j * 2 + 1], (unsigned long long)n1);
+    }
+}
+
+// one workgroup per job: centroids to the means of their members; sums and counts back to zero
+__global__ __launch_bounds__(256) void split_update_kernel(SplitArgs a)
+{
+    const uint32_t j = blockIdx.x;
+    const int d = a.ix->d;
+    const unsigned long long n0 = a.cnt[(size_t)j * 2], n1 = a.cnt[(size_t)j * 2 + 1];
+    for (int i = threadIdx.x; i < 2 * d; i += blockDim.x) {
+        const unsigned long long n = i < d ? n0 : n1;
+        const size_t at = (size_t)j * 2 * d + i;
+        if (n > 0) a.cent[at] = a.sum[at] / (double)n;
+        a.sum[at] = 0.0;
+    }
+    __syncthreads(); // every thread has read the counts
+    if (threadIdx.x < 2) {
+        a.cnt_out[(size_t)j * 2 + threadIdx.x] = threadIdx.x ? n1 : n0;
+        a.cnt[(size_t)j * 2 + threadIdx.x] = 0ull;
+    }
+}
+
+__global__ __launch_bounds__(256) void split_centroids_kernel(SplitArgs a, int nlist0, float *dense)
+{
+    const uint32_t j = blockIdx.x;
+    const int d = a.ix->d;
+    for (int i = threadIdx.x; i < d; i += blockDim.x) {
+        dense[(size_t)a.job_list[j] * d + i] = (float)a.cent[(size_t)j * 2 * d + i];
+        dense[(size_t)(nlist0 + j) * d + i] = (float)a.cent[((size_t)j * 2 + 1) * d + i];
+    }
+}
+
+hipError_t launch_split_init(const SplitArgs &a, hipStream_t s)
+{
+    if (a.njobs <= 0) return hipSuccess;
+    hipLaunchKernelGGL(split_init_kernel, dim3(a.njobs), dim3(1024), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_split_iterate(const SplitArgs &a, uint32_t total_units, int d, hipStream_t s)
+{
+    if (a.njobs <= 0 || total_units == 0) return hipSuccess;
+    if (d > PK_MAX_DIM) return hipErrorInvalidValue;
+    const size_t lds = (size_t)10 * d * sizeof(float); // at most 60 KB
+    hipLaunchKernelGGL(split_assign_kernel, dim3(total_units), dim3(256), lds, s, a);
+    hipLaunchKernelGGL(split_update_kernel, dim3(a.njobs), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_split_centroids(const SplitArgs &a, int nlist0, float *dense, hipStream_t s)
+{
+    if (a.njobs <= 0) return hipSuccess;
+    hipLaunchKernelGGL(split_centroids_kernel, dim3(a.njobs), dim3(256), 0, s, a, nlist0, dense);
+    return hipGetLastError();
+}
+
 // Stable partition of a list by side[r] in {0, 1}: slot[r] = number of earlier members on the
 // same side (one workgroup walks the list)
 __global__ __launch_bounds__(1024) void split_slots_kernel(const int32_t *side, uint32_t len, uint32_t *slot)

@@ -523,6 +523,29 @@ hipError_t launch_compact_pages(const DevIndex *src, const DevIndex *dst, uint32
                                 hipStream_t s);
 // the first min(len, length of list l) members of list l as dense fp32 rows [.][d] and / or their ids
 hipError_t launch_gather_list(const DevIndex *ix, uint32_t l, uint32_t len, float *rows, int64_t *ids, hipStream_t s);
+// 2-means of every list to split, all lists in the same launches, straight from the lists' pages
+// (Section 4.4: a light k-means on the device decides the split).  Job j splits list job_list[j].
+constexpr int kSplitUnit = 1024; // rows of one list that a workgroup assigns at a time
+struct SplitArgs {
+    const DevIndex *ix;
+    int njobs;
+    const uint32_t *job_list;  // [njobs]
+    const uint32_t *job_len;   // [njobs] members
+    const uint32_t *job_unit0; // [njobs + 1] units of the jobs before each one
+    const uint32_t *job_row0;  // [njobs] members of the jobs before each one: where the job's part of side[] starts
+    double *cent;              // [njobs][2][d] the two centroids
+    double *sum;               // [njobs][2][d] sums of the members of each side (zero between the launches)
+    unsigned long long *cnt;   // [njobs][2] members of each side (zero between the launches)
+    unsigned long long *cnt_out; // [njobs][2] the counts of the last assignment
+    int32_t *side;             // [sum of job_len] 0 / 1 per member, by position in its list
+};
+// first centroids: the member with the smallest id and the member with the largest id
+hipError_t launch_split_init(const SplitArgs &a, hipStream_t s);
+// one Lloyd iteration: every member to the nearer centroid (ties to the first), then the centroids to the
+// means of their members (a centroid without members stays)
+hipError_t launch_split_iterate(const SplitArgs &a, uint32_t total_units, int d, hipStream_t s);
+// the jobs' centroids into a dense fp32 table [.][d]: row job_list[j] and row nlist0 + j
+hipError_t launch_split_centroids(const SplitArgs &a, int nlist0, float *dense, hipStream_t s);
 // list l of src split by side[r]: side 0 stays list l of dst, side 1 becomes list lnew of dst (slot: scratch [len])
 hipError_t launch_split_list(const DevIndex *src, const DevIndex *dst, uint32_t l, uint32_t lnew, const int32_t *side,
                              uint32_t *slot, uint32_t len, hipStream_t s);
