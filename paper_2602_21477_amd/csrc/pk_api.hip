@@ -439,7 +439,7 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
     {
         // Sample pages per query.  A larger sample gives a tighter threshold and a finer bucket
         // scale, hence fewer emitted candidates; it costs one tile per query and page.  Wanted:
-        // the k-th best of the sample at most its 30 % quantile (large k); and, for batches of
+        // the k-th best of the sample at most its 40 % quantile (large k); and, for batches of
         // few queries, whose emitted candidates all meet at a handful of counters and
         // serialise there, a sample of 0.5 % of the most rows a query can meet (long lists).
         // Spent: at most 3 % of the scan's tiles, and sp_max pages.
@@ -451,6 +451,7 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
         if (worst) more = (uint64_t)tunables().sp_max;
         p.sp = std::max(p.sp, (int)more);
     }
+    p.sp = std::min(p.sp, kMaxSamplePages); // (a sample of fewer than k rows gives no threshold: slower, not wrong)
     p.span = (uint32_t)(p.sp * own->P);
     p.nlist_max = nlist_hi;
     p.stride = (uint32_t)pad_hi;

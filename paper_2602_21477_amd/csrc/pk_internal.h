@@ -349,6 +349,7 @@ struct SelectArgs {
     unsigned long long *partial;  // [nq][nchunks][K]
 };
 hipError_t launch_select_partial(const SelectArgs &a, int64_t nq, hipStream_t s);
+constexpr int kMaxSamplePages = 64;      // most pages of one query's threshold sample
 constexpr uint32_t kWlSmallLists = 2048; // most lists (all handles of a call) whose work list is laid out inside another kernel's launch
 constexpr int kDenseSelectMax = 8192; // longest score row the register-resident selection takes
 

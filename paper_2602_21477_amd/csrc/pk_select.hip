@@ -374,7 +374,6 @@ __device__ int64_t resolve_id(const FinalArgs &a, const MultiArgs &h, uint32_t q
     return ar.ids[(size_t)(pg - ar.first_page) * ix.P + (row - lp * ix.P)];
 }
 
-constexpr uint32_t kFinalRankMax = 256; // emitted keys up to this many are ranked by counting instead of sorted
 
 // the same with the query's rows of pair_off and probes in LDS
 __device__ int64_t resolve_id_lds(const FinalArgs &a, const DevIndex &ix, uint32_t pos, const uint32_t *po, const uint32_t *pr)
@@ -471,6 +470,72 @@ __device__ void rescore_query(const FinalArgs &a, const MultiArgs &h, uint32_t q
     }
 }
 
+// Best K of the cnt_q <= 256 * VPT keys of a query's region, held in registers: the K-th smallest value by
+// radix selection; among the keys with that value, if not all of them are needed, the lowest positions by a
+// second selection over the low words.  The kept keys end up sorted in keys[0, min(K, cnt_q)); *s_cnt is
+// their number.  early: key number threadIdx.x of the region, already loaded.  hist: LDS [4][256].
+template <int VPT>
+__device__ __forceinline__ void final_by_radix(const u64 *v, uint32_t cnt_q, uint32_t K, u64 early, uint32_t (*hist)[256],
+                                               u64 *keys, uint32_t *s_cnt)
+{
+    const uint32_t tid = threadIdx.x;
+    u64 k64[VPT];
+    uint32_t hi[VPT];
+    bool live[VPT];
+#pragma unroll
+    for (int j = 0; j < VPT; ++j) {
+        const uint32_t p = tid + (uint32_t)kSelThreads * j;
+        live[j] = p < cnt_q;
+        k64[j] = live[j] ? (j == 0 ? early : v[p]) : kMaxKey;
+        hi[j] = (uint32_t)(k64[j] >> 32);
+    }
+    if (tid == 0) *s_cnt = 0;
+    uint32_t prefix = 0xffffffffu, lo_max = 0xffffffffu; // everything is kept
+    if (cnt_q > K) {
+        uint32_t left, ties;
+        prefix = radix_kth<VPT>(hi, live, K, hist, left, ties);
+        if (ties != left) { // block-uniform: only the `left` lowest positions of the boundary value are kept
+            uint32_t lo[VPT];
+            bool tl[VPT];
+#pragma unroll
+            for (int j = 0; j < VPT; ++j) {
+                lo[j] = (uint32_t)k64[j];
+                tl[j] = live[j] && hi[j] == prefix;
+            }
+            __syncthreads(); // the histograms are read no more
+            uint32_t l2, t2;
+            lo_max = radix_kth<VPT>(lo, tl, left, hist, l2, t2);
+        }
+    } else {
+        __syncthreads();
+    }
+#pragma unroll
+    for (int j = 0; j < VPT; ++j)
+        if (live[j] && (hi[j] < prefix || (hi[j] == prefix && (uint32_t)k64[j] <= lo_max))) keys[atomicAdd(s_cnt, 1u)] = k64[j];
+    __syncthreads();
+    const uint32_t n = *s_cnt;
+    if (n <= (uint32_t)kSelThreads) {
+        // order by counting: the rank of a key is the number of smaller ones (keys are unique)
+        if (tid < 2) keys[n + tid] = kMaxKey; // padding: the keys are read in pairs
+        __syncthreads();
+        const u64 mine = tid < n ? keys[tid] : kMaxKey;
+        uint32_t rank = 0;
+        if (tid < n)
+            for (uint32_t o = 0; o < n; o += 2) {
+                const u64x2 w = *reinterpret_cast<const u64x2 *>(keys + o);
+                rank += (w[0] < mine ? 1u : 0u) + (w[1] < mine ? 1u : 0u);
+            }
+        __syncthreads();
+        if (tid < n) keys[rank] = mine;
+        __syncthreads();
+    } else {
+        const uint32_t np2 = next_pow2(n);
+        for (uint32_t i = n + tid; i < np2; i += blockDim.x) keys[i] = kMaxKey;
+        __syncthreads();
+        bitonic_sort(keys, np2);
+    }
+}
+
 __global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, MultiArgs h, uint32_t cap, uint32_t qbytes)
 {
     // LDS sized by K, not by the largest K the library takes: small k leaves room for every
@@ -478,7 +543,7 @@ __global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, 
     extern __shared__ __align__(16) unsigned char s_dyn[];
     u64 *keys = reinterpret_cast<u64 *>(s_dyn);                  // [cap]
     int64_t *s_id = reinterpret_cast<int64_t *>(keys + cap);     // [k]
-    // [2][row_bytes + kQPadBytes] when rescoring; the emitted keys (kFinalRankMax + 2 of them) when they are few
+    // [2][row_bytes + kQPadBytes] when rescoring; the histograms of the radix selection otherwise
     char *s_q = reinterpret_cast<char *>(s_id + ((a.k + 1) & ~1));
     uint32_t *s_po = reinterpret_cast<uint32_t *>(s_q + qbytes); // [nprobe + 1] the query's row of pair_off
     uint32_t *s_pr = s_po + a.nprobe + 1;                        // [nprobe] its probe list
@@ -519,29 +584,13 @@ __global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, 
     Selector sel;
     sel.init(keys, &s_cnt, a.K, cap);
     const bool overflow = cnt_q > a.ecap; // the region lost candidates: select by rescoring the query's rows
-    if (cnt_q <= kFinalRankMax && !overflow) {
-        // few keys: each one's rank by counting the smaller ones (keys are unique); no sorting network, one barrier
-        u64 *s_in = reinterpret_cast<u64 *>(s_q);
-        static_assert(kFinalRankMax == (uint32_t)kSelThreads, "one key per thread");
-        constexpr int KPT = 1;
-        u64 mine[KPT];
-        mine[0] = threadIdx.x < cnt_q ? early : kMaxKey;
-        if (threadIdx.x < cnt_q) s_in[threadIdx.x] = mine[0];
-        if (threadIdx.x < 2) s_in[cnt_q + threadIdx.x] = kMaxKey; // padding: the keys are read in pairs
-        __syncthreads();
-#pragma unroll
-        for (int j = 0; j < KPT; ++j) {
-            const uint32_t p = threadIdx.x + (uint32_t)kSelThreads * j;
-            if (p >= cnt_q) continue;
-            uint32_t rank = 0;
-            for (uint32_t o = 0; o < cnt_q; o += 2) {
-                const u64x2 w = *reinterpret_cast<const u64x2 *>(s_in + o);
-                rank += (w[0] < mine[j] ? 1u : 0u) + (w[1] < mine[j] ? 1u : 0u);
-            }
-            if (rank < (uint32_t)a.K) keys[rank] = mine[j];
-        }
-        if (threadIdx.x == 0) s_cnt = cnt_q < (uint32_t)a.K ? cnt_q : (uint32_t)a.K;
-        __syncthreads();
+    const bool in_registers = cnt_q <= 16u * kSelThreads && !overflow;
+    if (in_registers) {
+        uint32_t(*hist)[256] = reinterpret_cast<uint32_t(*)[256]>(s_q);
+        const u64 *v = a.keys + region;
+        if (cnt_q <= (uint32_t)kSelThreads) final_by_radix<1>(v, cnt_q, (uint32_t)a.K, early, hist, keys, &s_cnt);
+        else if (cnt_q <= 4u * kSelThreads) final_by_radix<4>(v, cnt_q, (uint32_t)a.K, early, hist, keys, &s_cnt);
+        else final_by_radix<16>(v, cnt_q, (uint32_t)a.K, early, hist, keys, &s_cnt);
     } else if (!overflow) {
         const u64 *v = a.keys + region;
         // short ranges go one key per thread and round, so the buffer that gets sorted stays small
@@ -569,7 +618,7 @@ __global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, 
         else rescore_query<PK_F32>(a, h, q, s_q, qstride, sel, false, 0u);
     }
     PK_MARK(sel, 33);
-    if (cnt_q > kFinalRankMax || overflow) sel.flush();
+    if (!in_registers) sel.flush();
     const uint32_t n = s_cnt;
 
     // entries carrying the padding value are not candidates
@@ -879,7 +928,7 @@ hipError_t launch_select_final(const FinalArgs &a, const MultiArgs &h, int64_t n
     if (a.row_bytes <= 0 || a.row_bytes % kIterBytes != 0 || a.ecap < (uint32_t)a.K) return hipErrorInvalidValue;
     const uint32_t cap = final_cap(a.K);
     // keys, ids, and the query row + a row of zeros for a query that has to be rescored
-    const size_t qbytes = std::max((size_t)2 * (a.row_bytes + kQPadBytes), (size_t)(kFinalRankMax + 2) * sizeof(u64));
+    const size_t qbytes = std::max((size_t)2 * (a.row_bytes + kQPadBytes), (size_t)4 * 256 * sizeof(uint32_t));
     // ..., and the query's rows of the candidate layout
     const size_t lds = (size_t)cap * sizeof(u64) + (size_t)((a.k + 1) & ~1) * sizeof(int64_t) + qbytes +
                        (size_t)(2 * a.nprobe + 1) * sizeof(uint32_t);

@@ -13,10 +13,9 @@
 namespace pk {
 
 // Work of one query: count the pairs per list, lay the query's candidate range out probe by
-// probe; and the tiles of the query's threshold sample: the first sm.sp pages of that range
-// (the pages of its first probed list, then of its second, ...), so that a query whose best
-// list is short still draws its threshold from at least k rows whenever it has that many
-// candidates.  Called by every thread of a workgroup.  probes_q: the query's probe list (global
+// probe; and the tiles of the query's threshold sample: sm.sp pages of its nearest lists, full
+// pages before partly filled ones, so that a query whose best lists are short still draws its
+// threshold from at least k rows whenever longer lists follow.  Called by every thread of a workgroup.  probes_q: the query's probe list (global
 // memory or, straight from the selection, LDS); probes_out: where to store it, or null.
 // v: the query's index, read ahead of the caller's own work so that the chain of dependent loads is
 // over by now.  Everything is read before anything is written: a load queues behind the stores and
@@ -43,7 +42,9 @@ struct WlCountLds {
     uint32_t mp[PK_MAX_NPROBE];      // pages of its build-time extent
     uint32_t mb[PK_MAX_NPROBE];      // first page of that extent
     uint32_t po[PK_MAX_NPROBE + 1];  // candidates of the probed lists before each one
-    uint32_t pg0[PK_MAX_NPROBE + 1]; // pages of the probed lists before each one
+    uint16_t sr[kMaxSamplePages];    // the sample's pages: which probed list,
+    uint32_t slp[kMaxSamplePages];   //   and which of its pages
+    uint32_t ns;                     // how many there are
 };
 __device__ __forceinline__ void wl_count_query(const WorklistArgs &a, const SampleArgs &sm, const MultiArgs &m, uint32_t q,
                                                WlCountLds &s, const int32_t *probes_q, int32_t *probes_out,
@@ -61,15 +62,28 @@ __device__ __forceinline__ void wl_count_query(const WorklistArgs &a, const Samp
     __syncthreads();
     PK_WL_MARK(5);
     if (threadIdx.x == 0) {
-        uint32_t acc = 0, pages = 0;
+        uint32_t acc = 0;
         for (int r = 0; r < a.nprobe; ++r) {
             s.po[r] = acc;
-            s.pg0[r] = pages;
             acc += (s.len[r] + 15u) & ~15u; // segments are padded to the 16-row MFMA tile
-            pages += (s.len[r] + P - 1) / P;
         }
         s.po[a.nprobe] = acc;
-        s.pg0[a.nprobe] = pages;
+        // The sample's pages: full pages first, nearest lists first, then the lists' last, partly filled
+        // pages: short lists at the head of the probe list cannot leave the sample with fewer than k
+        // rows (and the query without a threshold) while longer lists follow.
+        const uint32_t want = (uint32_t)sm.sp;
+        uint32_t ns = 0;
+        for (int r = 0; r < a.nprobe && ns < want; ++r)
+            for (uint32_t lp = 0; lp < s.len[r] / P && ns < want; ++lp) {
+                s.sr[ns] = (uint16_t)r;
+                s.slp[ns++] = lp;
+            }
+        for (int r = 0; r < a.nprobe && ns < want; ++r)
+            if (s.len[r] % P) {
+                s.sr[ns] = (uint16_t)r;
+                s.slp[ns++] = s.len[r] / P;
+            }
+        s.ns = ns;
     }
     __syncthreads();
     PK_WL_MARK(6);
@@ -82,11 +96,10 @@ __device__ __forceinline__ void wl_count_query(const WorklistArgs &a, const Samp
         tl.nrows = 0;
         tl.qcnt = 1;
         tl.pad = 0;
-        if (p < s.pg0[a.nprobe]) {
-            int r = 0;
-            while (s.pg0[r + 1] <= p) ++r; // the probed list that holds page p of the range
+        if (p < s.ns) {
+            const int r = s.sr[p];
             const uint32_t l = (uint32_t)probes_q[r];
-            const uint32_t lp = p - s.pg0[r];
+            const uint32_t lp = s.slp[p];
             const uint32_t pg = lp < s.mp[r] ? s.mb[r] + lp : ix.dtab[(size_t)l * ix.max_dp + (lp - s.mp[r])];
             const Arena &ar = arena_of(ix, pg);
             const size_t local = pg - ar.first_page;
