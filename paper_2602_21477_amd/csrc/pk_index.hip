@@ -62,16 +62,27 @@ __device__ void write_row(const DevIndex &ix, uint32_t l, uint32_t slot, const f
     const int lane = threadIdx.x & 63;
     const int n_el = ix.storage == PK_F16 ? ix.row_bytes / 2 : ix.row_bytes / 4;
     float acc = 0.f;
-    for (int i = lane; i < n_el; i += 64) {
-        float v = i < ix.d ? src[i] : 0.f;
-        if (ix.storage == PK_F16) {
-            const _Float16 h = (_Float16)v;
-            reinterpret_cast<_Float16 *>(dst)[i] = h;
-            v = (float)h;
-        } else {
-            reinterpret_cast<float *>(dst)[i] = v;
+    constexpr int kBatch = 8; // elements read before the first of them is written: a load queues behind earlier stores
+    for (int i0 = lane; i0 < n_el; i0 += 64 * kBatch) {
+        float v[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int i = i0 + 64 * u;
+            v[u] = i < ix.d ? src[i] : 0.f;
         }
-        acc += v * v;
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int i = i0 + 64 * u;
+            if (i >= n_el) continue;
+            if (ix.storage == PK_F16) {
+                const _Float16 h = (_Float16)v[u];
+                reinterpret_cast<_Float16 *>(dst)[i] = h;
+                v[u] = (float)h;
+            } else {
+                reinterpret_cast<float *>(dst)[i] = v[u];
+            }
+            acc += v[u] * v[u];
+        }
     }
     for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
     if (lane == 0) {
@@ -136,9 +147,8 @@ __global__ __launch_bounds__(1024) void reserve_kernel(MultiArgs ma, const int32
     if (i < m) {
         if (assign) {
             l = assign[i];
-        } else { // the top-1 key the centroid kernel left; reset for the next insert
+        } else { // the top-1 key the centroid kernel left (reset for the next insert on the way out)
             l = (int32_t)(uint32_t)best[row0 + i];
-            best[row0 + i] = ~0ull;
         }
         if (l < 0 || l >= ix.nlist) l = -1;
     }
@@ -185,7 +195,10 @@ __global__ __launch_bounds__(1024) void reserve_kernel(MultiArgs ma, const int32
         slots[i] = ok ? slot : 0xffffffffu;
         if (assigned_out) assigned_out[i] = l;
     }
-    if (!x) return;
+    if (!x) {
+        if (best && !assign && i < m) best[row0 + i] = ~0ull;
+        return;
+    }
     s_slot[i] = ok ? slot : 0xffffffffu;
     __syncthreads(); // slots, and the page table entries just written, are visible to the whole workgroup
     for (int r = i >> 6; r < m; r += 16) {
@@ -194,6 +207,7 @@ __global__ __launch_bounds__(1024) void reserve_kernel(MultiArgs ma, const int32
         write_row(ix, (uint32_t)s_l[r], s_slot[r], x + (size_t)row * ix.d,
                   ids ? ids[row] : idc.id0[blockIdx.x] + (int64_t)r);
     }
+    if (best && !assign && i < m) best[row0 + i] = ~0ull;
 }
 
 hipError_t launch_reserve(const MultiArgs &ma, const int32_t *assign, uint32_t *slots, int32_t *assigned_out, hipStream_t s)

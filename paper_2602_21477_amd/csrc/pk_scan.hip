@@ -586,10 +586,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 8))) voi
 // contraction index, so each wave streams a quarter of every row (centroids and queries
 // alike come straight from global memory / L2 in MFMA operand layout, no LDS staging), and
 // the four partial accumulators meet in LDS.  Output: out[query * stride + centroid].
-template <int MT>
-__global__ __launch_bounds__(256) void centroid_scores_kernel(CentroidArgs a, MultiArgs m)
+template <int MT, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void centroid_scores_kernel(CentroidArgs a, MultiArgs m)
 {
-    __shared__ float s_red[4][MT][4][64];
+    __shared__ float s_red[WAVES][MT][4][64];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int ln = lane & 15, lg = lane >> 4;
     int h = 0;
@@ -604,7 +604,7 @@ __global__ __launch_bounds__(256) void centroid_scores_kernel(CentroidArgs a, Mu
     const int mt_used = (int)((qcnt + 15u) >> 4);
     const int row_bytes = a.row_bytes;
     const int nit = row_bytes / kIterBytes;
-    const int per = (nit + 3) / 4;
+    const int per = (nit + WAVES - 1) / WAVES;
     const int it0 = wave * per, it1 = it0 + per < nit ? it0 + per : nit;
     const char *xp = reinterpret_cast<const char *>(ix.cent) + (size_t)(cb * 16u + ln) * row_bytes + lg * 16;
     const char *qp[MT];
@@ -650,7 +650,14 @@ __global__ __launch_bounds__(256) void centroid_scores_kernel(CentroidArgs a, Mu
 #pragma unroll
         for (int i = 0; i < 4; ++i) s_red[wave][mt][i][lane] = acc[mt][i];
     __syncthreads();
-    const int i = wave; // after the barrier wave w adds up element i = w of every lane
+    const int i = wave & 3; // after the barrier wave w < 4 adds up element i = w of every lane
+    auto partial_sum = [&](int mt) {
+        float v = (s_red[0][mt][i][lane] + s_red[1][mt][i][lane]) + (s_red[2][mt][i][lane] + s_red[3][mt][i][lane]);
+        if constexpr (WAVES == 8)
+            v += (s_red[4][mt][i][lane] + s_red[5][mt][i][lane]) + (s_red[6][mt][i][lane] + s_red[7][mt][i][lane]);
+        return v;
+    };
+    if (wave < 4) {
     const uint32_t c = cb * 16u + (uint32_t)ln;
     float cn = 0.f;
     if (a.metric == PK_METRIC_L2 && c < (uint32_t)ix.nlist) cn = ix.cnorm[c];
@@ -658,7 +665,7 @@ __global__ __launch_bounds__(256) void centroid_scores_kernel(CentroidArgs a, Mu
     for (int mt = 0; mt < MT; ++mt) {
         const uint32_t slot = (uint32_t)(mt * 16 + lg * 4 + i);
         if (slot >= qcnt || c >= (uint32_t)ix.nlist) continue;
-        float v = (s_red[0][mt][i][lane] + s_red[1][mt][i][lane]) + (s_red[2][mt][i][lane] + s_red[3][mt][i][lane]);
+        float v = partial_sum(mt);
         if (a.metric == PK_METRIC_L2) v = fmaxf(cn - 2.f * v + a.qnorm[q0 + slot], 0.f);
         if (!a.best) a.out[(size_t)(q0 + slot) * a.stride + c] = v;
     }
@@ -670,7 +677,7 @@ __global__ __launch_bounds__(256) void centroid_scores_kernel(CentroidArgs a, Mu
             const uint32_t slot = (uint32_t)(mt * 16 + lg * 4 + i);
             unsigned long long key = ~0ull;
             if (slot < qcnt && c < (uint32_t)ix.nlist) {
-                float v = (s_red[0][mt][i][lane] + s_red[1][mt][i][lane]) + (s_red[2][mt][i][lane] + s_red[3][mt][i][lane]);
+                float v = partial_sum(mt);
                 if (a.metric == PK_METRIC_L2) v = fmaxf(cn - 2.f * v + a.qnorm[q0 + slot], 0.f);
                 key = ((unsigned long long)order_bits(v, a.metric) << 32) | c;
             }
@@ -682,6 +689,7 @@ __global__ __launch_bounds__(256) void centroid_scores_kernel(CentroidArgs a, Mu
             if (ln == 0 && slot < qcnt && key != ~0ull) atomicMin(a.best + q0 + slot, key);
         }
     }
+    } // wave < 4
     if (a.meta.cand_off) {
         // bookkeeping of the coarse step (otherwise done while the queries are prepared); last, so that no
         // load of this kernel queues behind these stores
@@ -700,11 +708,16 @@ __global__ __launch_bounds__(256) void centroid_scores_kernel(CentroidArgs a, Mu
 template <int MT>
 static hipError_t launch_centroid_mt(const CentroidArgs &a, const MultiArgs &m, hipStream_t s)
 {
-    hipLaunchKernelGGL(centroid_scores_kernel<MT>, dim3(a.blk[m.n]), dim3(256), 0, s, a, m);
+    static_assert(MT >= 1, "");
+    if (MT == 1 && a.row_bytes / kIterBytes >= 16) {
+        // one group of queries over long rows: eight waves share the row, so that each has few slices in a row to wait for
+        hipLaunchKernelGGL((centroid_scores_kernel<1, 8>), dim3(a.blk[m.n]), dim3(512), 0, s, a, m);
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL((centroid_scores_kernel<MT, 4>), dim3(a.blk[m.n]), dim3(256), 0, s, a, m);
     return hipGetLastError();
 }
 
-// a.chunk = queries per workgroup (16, 32, 48 or 64); a.blk as filled by the caller for that chunk
 hipError_t launch_centroid_scores(const CentroidArgs &a, const MultiArgs &m, hipStream_t s)
 {
     if (a.row_bytes <= 0 || a.row_bytes % kIterBytes != 0) return hipErrorInvalidValue;
