@@ -55,11 +55,17 @@ def profiled_traffic(workload, metric):
     the kernels as they are now (the summary records the hash of the sources it was taken from).
     Returns (bytes or None, source description)."""
     import re
-    rel = os.path.join("profiles", f"scan_kernel_{workload}_{metric}.md")
-    try:
-        text = open(os.path.join(ROOT, rel)).read()
-    except OSError:
-        return None, f"{rel}: no such summary"
+    text = None
+    # summaries are named for the kernel that scans most of the workload's rows
+    for name in (f"scan_kernel_{workload}_{metric}.md", f"scan_ks_kernel_{workload}.md"):
+        rel = os.path.join("profiles", name)
+        try:
+            text = open(os.path.join(ROOT, rel)).read()
+            break
+        except OSError:
+            continue
+    if text is None:
+        return None, f"profiles/: no summary for {workload} ({metric})"
     m = re.search(r"^traffic_bytes_per_launch:\s*(\d+)", text, re.M)
     k = re.search(r"^kernel_sources_sha:\s*([0-9a-f]+)", text, re.M)
     if not m:
