@@ -96,9 +96,16 @@ struct pk_index {
     // small inserts: top-1 keys of the batch (kept at ~0 between calls) and the slots the batch got
     unsigned long long *ins_best; // DEVICE [kInsertFast]
     uint32_t *ins_slots;          // DEVICE [kInsertFast]
+    // second stream of a search whose lists fall into two tile classes: the kernel for the lists many
+    // queries probe is bound by the matrix cores and runs on some of the CUs while the HBM-bound scan of
+    // the other lists has the rest (fork and join by events; default priority)
+    hipStream_t side;
+    hipEvent_t ev_fork, ev_join;
     // stage timing (pk_profile_begin .. pk_profile_end)
     bool prof_on;
-    std::vector<hipEvent_t> prof_ev; // 5 events per recorded launch sequence
+    std::vector<hipEvent_t> prof_ev; // 6 events per recorded launch sequence
+    std::vector<uint8_t> prof_beside; // per sequence: the two scan kernels ran side by side (the fourth event then
+                                      // follows the kernel of the lists many queries probe, not the regular scan)
     size_t prof_used;
 };
 
@@ -279,6 +286,8 @@ struct Tunables {
                   // (0: lists with more queries than one group of the regular kernel; -1: none)
     int rs_nq;    // PK_TUNE_RS_NQ: fewest queries of a batch for which the rows-stationary class exists
     int hot_grab; // PK_TUNE_HOT_GRAB: tiles per claim of the rows-stationary kernels
+    int hot_cus;  // PK_TUNE_HOT_CUS: CUs given to the rows-in-registers kernel while it runs beside the regular
+                  // lists' scan (0: one after the other on the caller's stream)
 };
 
 #ifdef PK_DEV_TUNABLES
@@ -307,7 +316,8 @@ const Tunables &tunables()
         return Tunables{env("PK_TUNE_WGS", 4),       env("PK_TUNE_MQ", 0),        env("PK_TUNE_MQH", 64),
                         env("PK_TUNE_KS", 1),        env("PK_TUNE_SP_MAX", 16),   env("PK_TUNE_GEMM_WGS", 128),
                         env("PK_TUNE_DENSESEL", 1),  env("PK_TUNE_GRABDIV", 8),   env("PK_TUNE_HIST", 1),
-                        env("PK_TUNE_RS_FROM", 0),   env("PK_TUNE_RS_NQ", 512),   env("PK_TUNE_HOT_GRAB", 1)};
+                        env("PK_TUNE_RS_FROM", 0),   env("PK_TUNE_RS_NQ", 512),   env("PK_TUNE_HOT_GRAB", 1),
+                        env("PK_TUNE_HOT_CUS", 96)};
     }();
     return t;
 }
@@ -642,7 +652,7 @@ int run_coarse(const Plan &p, const MultiArgs &m, pk_index *const *hs, const flo
 
 // Fine search of one batch over p.probes.
 int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, int64_t *out_ids, float *out_dist,
-             hipStream_t s, bool timed, bool counted)
+             hipStream_t s, bool timed, bool counted, bool fixed)
 {
     if (p.f16) PK_HIP(launch_prep_queries(q, p.nq, own->cfg.d, PK_F16, own->row_bytes, p.qs, p.qn, s));
     WorklistArgs w;
@@ -697,22 +707,50 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
     sa.metric = own->cfg.metric;
     sa.storage = own->cfg.storage;
     sa.mq = p.mq_f;
-    if (p.hot_from > 0) PK_HIP(launch_scan(sa, p.grid_f, s));
-    if (timed) PK_TRY(mark(own, s));
-    if (p.hot_from != 0xffffffffu) {
-        sa.tiles = p.tiles_hot;
-        sa.ntiles = p.scalars + 12;
-        sa.tile_ctr = p.scalars + 13;
-        sa.batch = p.scalars + 14;
-        sa.mq = p.mq_h;
-        if (p.hot_rs) {
-            sa.use_hist = 0; // the regular lists' scan has published its limits; this one only reads them
-            PK_HIP(launch_scan_rr(sa, p.grid_h, s));
-        } else {
-            PK_HIP(launch_scan_ks(sa, p.grid_h, s));
+    // Two tile classes: the rows-in-registers kernel (matrix cores, little HBM traffic) takes hot_cus CUs while the
+    // regular lists' scan (HBM) runs on the others.  The first goes to the caller's stream, where it starts at once
+    // and has its CUs (it needs whole ones: a wave per SIMD with all its registers) by the time the scan, launched
+    // on the handle's second stream behind an event, brings its workgroups; the caller's stream then waits for the
+    // scan.  The first only reads the bucket limits the scan publishes (whatever they are by then: a looser gate
+    // emits more, never less).  Not under capture, and not for a fixed workspace shared by all handles of the
+    // process: there the two run one after the other.
+    const bool beside = p.hot_rs && p.hot_from > 0 && p.hot_from != 0xffffffffu && tunables().hot_cus > 0 &&
+                        tunables().hot_cus < own->num_cu && own->side && !fixed && !capturing(s);
+    ScanArgs sh = sa;
+    sh.tiles = p.tiles_hot;
+    sh.ntiles = p.scalars + 12;
+    sh.tile_ctr = p.scalars + 13;
+    sh.batch = p.scalars + 14;
+    sh.mq = p.mq_h;
+    if (beside) {
+        sh.use_hist = 0;
+        PK_HIP(hipEventRecord(own->ev_fork, s));
+        PK_HIP(launch_scan_rr(sh, tunables().hot_cus, s));
+        PK_HIP(hipStreamWaitEvent(own->side, own->ev_fork, 0));
+        PK_HIP(launch_scan(sa, p.grid_f, own->side));
+        PK_HIP(hipEventRecord(own->ev_join, own->side));
+        if (timed) {
+            own->prof_beside.push_back(1);
+            PK_TRY(mark(own, s)); // after the kernel of the lists many queries probe
         }
+        PK_HIP(hipStreamWaitEvent(s, own->ev_join, 0));
+        if (timed) PK_TRY(mark(own, s));
+    } else {
+        if (p.hot_from > 0) PK_HIP(launch_scan(sa, p.grid_f, s));
+        if (timed) {
+            own->prof_beside.push_back(0);
+            PK_TRY(mark(own, s)); // after the regular lists' scan
+        }
+        if (p.hot_from != 0xffffffffu) {
+            if (p.hot_rs) {
+                sh.use_hist = 0; // the regular lists' scan has published its limits; this one only reads them
+                PK_HIP(launch_scan_rr(sh, p.grid_h, s));
+            } else {
+                PK_HIP(launch_scan_ks(sh, p.grid_h, s));
+            }
+        }
+        if (timed) PK_TRY(mark(own, s));
     }
-    if (timed) PK_TRY(mark(own, s));
     FinalArgs f{};
     f.K = p.K;
     f.k = p.k;
@@ -795,7 +833,7 @@ int search_impl(pk_index *const *hs, int nh, const int64_t *q_offsets, const flo
         if (mode == kCoarseOnly) {
             PK_HIP(launch_copy_i32(p.probes, out_probes + (size_t)q0 * nprobe, nq * nprobe, s));
         } else {
-            PK_TRY(run_fine(p, m, own, q, out_ids + (size_t)q0 * k, out_dist + (size_t)q0 * k, s, timed, counted));
+            PK_TRY(run_fine(p, m, own, q, out_ids + (size_t)q0 * k, out_dist + (size_t)q0 * k, s, timed, counted, fixed_ws != nullptr));
         }
     }
     return PK_OK;
@@ -944,6 +982,9 @@ void destroy(pk_index *ix)
     if (ix->ins_best) (void)hipFree(ix->ins_best);
     if (ix->pin_pages) (void)hipHostFree(ix->pin_pages);
     if (ix->ev) (void)hipEventDestroy(ix->ev);
+    if (ix->ev_fork) (void)hipEventDestroy(ix->ev_fork);
+    if (ix->ev_join) (void)hipEventDestroy(ix->ev_join);
+    if (ix->side) (void)hipStreamDestroy(ix->side);
     for (hipEvent_t e : ix->prof_ev) (void)hipEventDestroy(e);
     ix->magic = 0;
     delete ix;
@@ -1150,6 +1191,10 @@ int pk_index_build(const pk_config *cfg, const float *centroids, const float *ve
     if (hipHostMalloc(reinterpret_cast<void **>(&ix->pin_pages), 64, hipHostMallocDefault) != hipSuccess)
         return fail(PK_ERR_HIP);
     if (hipEventCreateWithFlags(&ix->ev, hipEventDisableTiming) != hipSuccess) return fail(PK_ERR_HIP);
+    if (hipStreamCreateWithFlags(&ix->side, hipStreamNonBlocking) != hipSuccess ||
+        hipEventCreateWithFlags(&ix->ev_fork, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&ix->ev_join, hipEventDisableTiming) != hipSuccess)
+        return fail(PK_ERR_HIP);
     if (hipMalloc(reinterpret_cast<void **>(&ix->ins_best), (size_t)kInsertFast * 12) != hipSuccess) return fail(PK_ERR_NOMEM);
     ix->ins_slots = reinterpret_cast<uint32_t *>(ix->ins_best + kInsertFast);
     if (launch_fill_u32(reinterpret_cast<uint32_t *>(ix->ins_best), 0xffffffffu, (size_t)kInsertFast * 2, s) != hipSuccess)
@@ -1976,6 +2021,7 @@ int pk_profile_begin(pk_index *ix, void *stream)
     hipStream_t s = static_cast<hipStream_t>(stream);
     PK_HIP(launch_fill_u32(reinterpret_cast<uint32_t *>(ix->host.stats), 0u, 16, s));
     ix->prof_used = 0;
+    ix->prof_beside.clear();
     ix->prof_on = true;
     return PK_OK;
 }
@@ -1998,7 +2044,7 @@ int pk_profile_end(pk_index *ix, pk_profile *out, void *stream)
         out->coarse_ms += ms[0];
         out->worklist_ms += ms[1];
         out->scan_ms += ms[2] + ms[3];
-        out->scan_hot_ms += ms[3];
+        out->scan_hot_ms += i < ix->prof_beside.size() && ix->prof_beside[i] ? ms[2] : ms[3];
         out->select_ms += ms[4];
     }
     out->launches = (int32_t)n;
@@ -2009,6 +2055,7 @@ int pk_profile_end(pk_index *ix, pk_profile *out, void *stream)
     out->overflowed = (int64_t)st[4];
     out->max_emitted = (int64_t)st[5];
     ix->prof_used = 0;
+    ix->prof_beside.clear();
     return PK_OK;
 }
 

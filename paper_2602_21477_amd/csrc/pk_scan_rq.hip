@@ -197,24 +197,35 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                 acc[f][0] = f32x4{0.f, 0.f, 0.f, 0.f};
                 acc[f][1] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
-            // The slot tiles' operands of one 64-byte step are all read before its MFMAs start (the
-            // scheduling barriers pin that order): one wave per SIMD has nobody to hide an LDS round trip per tile.
+            // One wave per SIMD has nobody to hide an LDS round trip, so the operand reads run one
+            // 64-byte step ahead of the MFMAs that use them: a slot tile's operand of the next step is
+            // read right after its two MFMAs of this step have issued (the register is free then), which
+            // gives every read the other seven tiles' MFMAs to arrive in.  The scheduling hints pin that
+            // interleave (two MFMAs, one LDS read); the pipeline drains once per slice, at the barrier
+            // that switches the LDS buffers.
 #define PK_COMPUTE(buf, slice, NF)                                                                \
     {                                                                                             \
         const char *ab = apb + (size_t)(buf) * kRqBlock * kRrAStride;                             \
+        u32x4 qa[NF];                                                                             \
+        _Pragma("unroll") for (int f = 0; f < NF; ++f)                                            \
+            qa[f] = *reinterpret_cast<const u32x4 *>(ab + (size_t)f * 16 * kRrAStride);           \
+        __builtin_amdgcn_sched_barrier(0);                                                        \
         _Pragma("unroll") for (int jj = 0; jj < 4; ++jj)                                          \
         {                                                                                         \
-            u32x4 qa[NF];                                                                         \
-            _Pragma("unroll") for (int f = 0; f < NF; ++f)                                        \
-                qa[f] = *reinterpret_cast<const u32x4 *>(ab + (size_t)f * 16 * kRrAStride + jj * 64); \
-            __builtin_amdgcn_sched_barrier(0);                                                    \
             _Pragma("unroll") for (int f = 0; f < NF; ++f)                                        \
             {                                                                                     \
                 mfma_step<STORAGE>(acc[f][0], qa[f], xb[(slice) * 4 + jj][0]);                    \
                 mfma_step<STORAGE>(acc[f][1], qa[f], xb[(slice) * 4 + jj][1]);                    \
+                if (jj < 3)                                                                       \
+                    qa[f] = *reinterpret_cast<const u32x4 *>(ab + (size_t)f * 16 * kRrAStride + (jj + 1) * 64); \
             }                                                                                     \
-            __builtin_amdgcn_sched_barrier(0);                                                    \
+            _Pragma("unroll") for (int f = 0; f < NF; ++f)                                        \
+            {                                                                                     \
+                __builtin_amdgcn_sched_group_barrier(0x008, STORAGE == PK_F16 ? 2 : 8, 0);        \
+                if (jj < 3) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                    \
+            }                                                                                     \
         }                                                                                         \
+        __builtin_amdgcn_sched_barrier(0);                                                        \
     }
             // (the empty asm statements keep the compiler from sinking the loads below the MFMAs, which
             // would leave them one slice of lead instead of two)
