@@ -92,6 +92,26 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         const Tile nxt = a.tiles[t_next < ntiles ? t_next : ntiles - 1]; // on its way while this tile is scored
         uint32_t claim = ntiles;
         if (tid == 0 && t_next < ntiles) claim = gridDim.x + atomicAdd(a.tile_ctr, 1u); // read when the tile ends
+        // ---- this wave's 32 rows, whole, into registers, requested first of all: they come from HBM, and the
+        // per-slot arrays and the first query slices (L2) are fetched while they are on their way (rows past
+        // the tile's last lie inside the page and hold stale bytes: h = +inf keeps them out)
+        u32x4 xb[NCH][2];
+        float xn[2], h[2];
+        {
+            const gbytes p0 = in_global(cur.x) + (size_t)(wave * 32 + ln) * ROW_BYTES + lg * 16;
+            const gbytes p1 = p0 + (size_t)16 * ROW_BYTES;
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                xb[c][0] = *reinterpret_cast<gvec4>(p0 + c * 64);
+                xb[c][1] = *reinterpret_cast<gvec4>(p1 + c * 64);
+            }
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) {
+                const int row = wave * 32 + nt * 16 + ln;
+                xn[nt] = l2 && row < nrows ? in_global(cur.xn)[row] : 0.f;
+            }
+        }
+        asm volatile("" ::: "memory");
         if (qbeg != cur_qbeg || qcnt != cur_qcnt) {
             // Gate: a value passes iff dot >= h(row) + c(slot), up to rounding, for which both constants
             // are lowered a little so that the test passes a superset (what passes is tested again exactly):
@@ -157,34 +177,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #define PK_STOREA(R, buf)                                                                         \
     _Pragma("unroll") for (int j = 0; j < 8; ++j)                                                 \
         *reinterpret_cast<u32x4 *>(adst + ((size_t)(buf) * kRqBlock + 16 * j) * kRrAStride) = R[j];
-        // The first two query slices are requested BEFORE the rows: a wave's loads return in order, and
-        // the slices (L2) must not queue behind the rows (HBM).  The rows then stream in while the first
-        // slices are scored.
+        // the first two query slices
         PK_SETPTR(0)
         PK_LOADA(R0)
         PK_LOADA(R1)
         asm volatile("" ::: "memory");
-        // ---- this wave's 32 rows, whole, into registers (rows past the tile's last lie inside the
-        // page and hold stale bytes: h = +inf keeps them out)
-        u32x4 xb[NCH][2];
-        float xn[2], h[2];
-        {
-            const gbytes p0 = in_global(cur.x) + (size_t)(wave * 32 + ln) * ROW_BYTES + lg * 16;
-            const gbytes p1 = p0 + (size_t)16 * ROW_BYTES;
-#pragma unroll
-            for (int c = 0; c < NCH; ++c) {
-                xb[c][0] = *reinterpret_cast<gvec4>(p0 + c * 64);
-                xb[c][1] = *reinterpret_cast<gvec4>(p1 + c * 64);
-            }
-#pragma unroll
-            for (int nt = 0; nt < 2; ++nt) {
-                const int row = wave * 32 + nt * 16 + ln;
-                xn[nt] = l2 && row < nrows ? in_global(cur.xn)[row] : 0.f;
-                h[nt] = row < nrows ? xn[nt] * (0.5f - 0x1p-21f) : INFINITY;
-            }
-        }
-        asm volatile("" ::: "memory");
         PK_STOREA(R0, 0)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) h[nt] = wave * 32 + nt * 16 + ln < nrows ? xn[nt] * (0.5f - 0x1p-21f) : INFINITY;
         __syncthreads();
 
         int g = 0; // slices scored so far in this tile: slice g sits in buffer g & 1 (a constant per slice when NIT is even)
