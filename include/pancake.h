@@ -34,6 +34,10 @@
  *     `inserts_ahead` (the graph's tile list bound was taken at capture time).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work
  *     is enqueued on it; outputs are valid once the caller has synchronised the stream.
+ *     (A search of 512 queries or more may run one of its kernels on a stream that the
+ *     handle owns, forked from and joined to the caller's stream by events inside the
+ *     call, at the default priority: to the caller the call stays ordered on `stream`.
+ *     Under graph capture and in pk_search_noalloc everything stays on `stream`.)
  *     Calls on one handle must come from one thread and one stream at a time; an
  *     insert enqueued before a search on the same stream is seen by that search.
  *     pk_index_build, pk_index_stats and pk_list_lengths synchronise the stream.

@@ -690,6 +690,67 @@ def test_hot_lists_rows_stationary_kernel(gpu_device):
         p.close()
 
 
+def test_two_tile_classes_side_by_side_on_two_streams(gpu_device):
+    """A batch of 512 queries or more whose lists fall into both tile classes has the kernel for the lists
+    many queries probe and the scan of the other lists run side by side (the second on a stream of the
+    handle's own, forked from and joined to the caller's by events).  The call must stay stream-ordered for
+    the caller: searches issued back to back on a stream other than the default one, with an insert between
+    them, give bit for bit the rows of the same searches run one at a time between device-wide waits; those
+    match the oracle; and a captured graph (under capture the two kernels run one after the other) replays
+    to the same rows."""
+    cfg = W.scaled(W.C1, n=30000, ncomp=96, nlist=96)
+    p, _ = make_pair(cfg, metric=L2, storage=F16, insert_reserve=4096)
+    try:
+        k, nprobe, nq = 10, 6, 768
+        qs = [dev(W.queries(cfg, 40 + b, nq)) for b in range(3)]
+        new = W.inserts(cfg, 5, 300).astype(np.float16).astype(np.float32)
+        say("one search at a time")
+        alone = []
+        for b in range(3):
+            i, v = p.gpu.search(qs[b], k, nprobe)
+            torch.cuda.synchronize()
+            alone.append((i.cpu().numpy(), v.cpu().numpy()))
+        B.pk_profile_begin(p.gpu.handle)
+        p.gpu.search(qs[0], k, nprobe)
+        pr = B.pk_profile_end(p.gpu.handle)
+        assert pr.scan_hot_ms > 0 and pr.scan_ms >= pr.scan_hot_ms, "the batch has lists of both tile classes"
+        say("back to back on a second stream")
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            outs = [p.gpu.search(qs[b], k, nprobe) for b in (0, 1, 2, 0)]
+            lists = p.gpu.insert(dev(new), want_lists=True)
+            after = p.gpu.search(qs[1], k, nprobe)
+        torch.cuda.synchronize()
+        for n, b in enumerate((0, 1, 2, 0)):
+            assert np.array_equal(outs[n][0].cpu().numpy(), alone[b][0]), f"ids of back-to-back search {n} differ"
+            assert np.array_equal(outs[n][1].cpu().numpy(), alone[b][1]), f"values of back-to-back search {n} differ"
+        p.accept_inserted(new, lists.cpu().numpy(), where="insert between searches")
+        say("after the insert: the oracle's rows, and the search issued right behind the insert")
+        p.check_search(qs[1].cpu().numpy(), k, nprobe, where="after the insert")
+        i2, v2 = p.gpu.search(qs[1], k, nprobe)
+        torch.cuda.synchronize()
+        assert np.array_equal(after[0].cpu().numpy(), i2.cpu().numpy()) and np.array_equal(after[1].cpu().numpy(), v2.cpu().numpy())
+        say("graph capture")
+        ids = torch.empty((nq, k), dtype=torch.int64, device="cuda")
+        dist = torch.empty((nq, k), dtype=torch.float32, device="cuda")
+        graph = torch.cuda.CUDAGraph()
+        cap = torch.cuda.Stream()
+        with torch.cuda.stream(cap):
+            with torch.cuda.graph(graph, stream=cap):
+                B.pk_search(p.gpu.handle, qs[1], k, nprobe, ids, dist)
+        torch.cuda.synchronize()
+        for rep in range(2):
+            ids.fill_(-7)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(ids.cpu().numpy(), i2.cpu().numpy()) and np.array_equal(dist.cpu().numpy(), v2.cpu().numpy())
+        st = p.gpu.stats()
+        assert st.device_error == 0
+    finally:
+        p.close()
+
+
 def test_hot_lists_across_agents_in_one_call(gpu_device):
     """Two agents, hundreds of queries each over few lists, one segmented call: the rows-stationary tiles
     of both indexes share a launch.  Same results as the per-handle calls (which, 400 queries each, stay
