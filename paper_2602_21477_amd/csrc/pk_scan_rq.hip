@@ -74,13 +74,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     char *const adst = abuf + (size_t)srow * kRrAStride + scol;
     const char *const apb = abuf + (size_t)ln * kRrAStride + lg * 16;
 
-    // Tiles: workgroup b starts with tile b; every later tile is claimed from one counter, one tile
-    // per claim (tiles are long and differ tenfold in length), a tile ahead: the claim made while
-    // tile i - 1 runs names tile i + 1, whose descriptor is fetched while tile i runs.
+    // Tiles are handed out in pairs of neighbours (the tiles of a list and slot group follow one another, so the
+    // second of a pair nearly always finds the per-slot arrays of the first in LDS): workgroup b starts with
+    // pair b; every later pair is claimed from one counter (tiles are long and differ tenfold in length, so
+    // no more than two per claim), a pair ahead: the claim made while the last tile of pair i - 1 runs names
+    // pair i + 1, and the descriptor of the next tile is fetched while the current one runs.
     const uint32_t ntiles = *a.ntiles;
-    if (blockIdx.x >= ntiles) return;
+    const uint32_t npairs = (ntiles + 1u) >> 1;
+    if (blockIdx.x >= npairs) return;
     if (tid == 0) s_misc[0] = gridDim.x + atomicAdd(a.tile_ctr, 1u);
-    Tile cur = a.tiles[blockIdx.x];
+    uint32_t pair = blockIdx.x;
+    int half = 0;
+    Tile cur = a.tiles[2u * pair];
     while (true) {
         const uint32_t row0 = cur.row0;
         const uint32_t qbeg = __builtin_amdgcn_readfirstlane(cur.qbeg);
@@ -88,10 +93,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         const int nrows = __builtin_amdgcn_readfirstlane((int)cur.nrows);
 
         __syncthreads(); // every wave is done with the previous tile's slices and slot arrays
-        const uint32_t t_next = __builtin_amdgcn_readfirstlane(s_misc[0]);
+        const uint32_t p_next = __builtin_amdgcn_readfirstlane(s_misc[0]);
+        const bool last_of_pair = half == 1 || 2u * pair + 1u >= ntiles;
+        const bool more = !last_of_pair || p_next < npairs;
+        const uint32_t t_next = last_of_pair ? 2u * p_next : 2u * pair + 1u;
         const Tile nxt = a.tiles[t_next < ntiles ? t_next : ntiles - 1]; // on its way while this tile is scored
-        uint32_t claim = ntiles;
-        if (tid == 0 && t_next < ntiles) claim = gridDim.x + atomicAdd(a.tile_ctr, 1u); // read when the tile ends
+        uint32_t claim = npairs;
+        if (tid == 0 && last_of_pair && p_next < npairs) claim = gridDim.x + atomicAdd(a.tile_ctr, 1u); // read when the pair ends
         // ---- this wave's 32 rows, whole, into registers, requested first of all: they come from HBM, and the
         // per-slot arrays and the first query slices (L2) are fetched while they are on their way (rows past
         // the tile's last lie inside the page and hold stale bytes: h = +inf keeps them out)
@@ -299,9 +307,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #undef PK_SETPTR
 #undef PK_LOADA
 #undef PK_STOREA
-        if (t_next >= ntiles) break;
-        // every wave has read s_misc[0] long ago (barriers since); the next tile's first barrier publishes this
-        if (tid == 0) s_misc[0] = claim;
+        if (!more) break;
+        if (last_of_pair) {
+            // every wave has read s_misc[0] long ago (barriers since); the next tile's first barrier publishes this
+            if (tid == 0) s_misc[0] = claim;
+            pair = p_next;
+            half = 0;
+        } else {
+            half = 1;
+        }
         cur = nxt;
     }
 }
