@@ -288,6 +288,7 @@ struct Tunables {
     int hot_grab; // PK_TUNE_HOT_GRAB: tiles per claim of the rows-stationary kernels
     int hot_cus;  // PK_TUNE_HOT_CUS: CUs given to the rows-in-registers kernel while it runs beside the regular
                   // lists' scan (0: one after the other on the caller's stream)
+    int wl_aside; // PK_TUNE_WL_ASIDE: large batches build the second half of the work list beside the sample scan
 };
 
 #ifdef PK_DEV_TUNABLES
@@ -317,7 +318,7 @@ const Tunables &tunables()
                         env("PK_TUNE_KS", 1),        env("PK_TUNE_SP_MAX", 16),   env("PK_TUNE_GEMM_WGS", 128),
                         env("PK_TUNE_DENSESEL", 1),  env("PK_TUNE_GRABDIV", 8),   env("PK_TUNE_HIST", 1),
                         env("PK_TUNE_RS_FROM", 0),   env("PK_TUNE_RS_NQ", 512),   env("PK_TUNE_HOT_GRAB", 1),
-                        env("PK_TUNE_HOT_CUS", 96)};
+                        env("PK_TUNE_HOT_CUS", 96),  env("PK_TUNE_WL_ASIDE", 1)};
     }();
     return t;
 }
@@ -673,12 +674,24 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
     ss.metric = own->cfg.metric;
     ss.storage = own->cfg.storage;
     ss.mq = kSampleSlots;
+    // Large batches: the second half of the work list (two small, latency-bound kernels) needs the pair counts
+    // only, not the thresholds: it runs on the handle's second stream while the sample is scored (HBM-bound).
+    // (worth the two cross-stream waits only beside a sample of some length: 400 MB are about 80 us)
+    const bool wl_aside = !p.wl_small && tunables().wl_aside && own->side && !fixed && !capturing(s) &&
+                          (uint64_t)p.nq * p.span * (uint64_t)own->row_bytes >= (400ull << 20);
+    if (wl_aside) {
+        PK_HIP(hipEventRecord(own->ev_fork, s));
+        PK_HIP(hipStreamWaitEvent(own->side, own->ev_fork, 0));
+        PK_HIP(launch_worklist_tiles(w, m, own->side));
+        PK_HIP(hipEventRecord(own->ev_join, own->side));
+    }
     PK_HIP(launch_scan(ss, p.grid_s, s));
     if (p.wl_small) {
         PK_HIP(launch_tau(sm, s, &w, &m)); // its workgroups also lay out the slots and tiles of the work list
     } else {
         PK_HIP(launch_tau(sm, s));
-        PK_HIP(launch_worklist_tiles(w, m, s));
+        if (wl_aside) PK_HIP(hipStreamWaitEvent(s, own->ev_join, 0));
+        else PK_HIP(launch_worklist_tiles(w, m, s));
     }
     if (timed) PK_TRY(mark(own, s));
     ScanArgs sa{};
