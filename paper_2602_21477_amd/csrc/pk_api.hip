@@ -203,6 +203,7 @@ struct Plan {
     int mq_f, mq_h, grid_f, grid_h, grid_s, cchunks, K, nlist_max, sp;
     uint32_t hot_from;
     bool hot_rs; // the hot class is scored by the rows-in-registers kernel (tiles of kRrTileRows rows x up to kRrSlots slots)
+    double avg_per_list; // queries per list on average (the largest over the handles of the call)
     uint32_t stride, ecap, tile_cap, span;
     uint64_t cbuf_entries; // entries of all emission regions together
     bool need_coarse, need_fine, f16;
@@ -392,6 +393,7 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
         double avg = 0;
         for (int a = 0; a < nh; ++a)
             avg = std::max(avg, (double)(qlo[a + 1] - qlo[a]) * nprobe / hs[a]->cfg.nlist);
+        p.avg_per_list = avg;
         const int want = avg <= 6 ? 16 : (avg <= 20 ? 32 : 64);
         p.mq_f = std::min(p.mq_f, tunables().mq > 0 ? tunables().mq : want);
         p.mq_h = own->cfg.storage == PK_F16 ? 64 : 32;
@@ -727,8 +729,11 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
     // scan.  The first only reads the bucket limits the scan publishes (whatever they are by then: a looser gate
     // emits more, never less).  Not under capture, and not for a fixed workspace shared by all handles of the
     // process: there the two run one after the other.
+    // Nor when the average list is probed by more queries than a regular tile holds: then most lists are of the
+    // first kernel's class, and it should have the whole chip rather than a part of it beside an idle scan.
     const bool beside = p.hot_rs && p.hot_from > 0 && p.hot_from != 0xffffffffu && tunables().hot_cus > 0 &&
-                        tunables().hot_cus < own->num_cu && own->side && !fixed && !capturing(s);
+                        tunables().hot_cus < own->num_cu && own->side && !fixed && !capturing(s) &&
+                        p.avg_per_list < (double)p.hot_from;
     ScanArgs sh = sa;
     sh.tiles = p.tiles_hot;
     sh.ntiles = p.scalars + 12;
