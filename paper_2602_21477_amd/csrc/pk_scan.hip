@@ -286,7 +286,7 @@ __device__ __forceinline__ void finish_block(const ScanArgs &a, const Slots &s, 
 // GATED = emit only values that pass the per-query gate (fine search) instead of writing
 // every value (coarse search, threshold sampling).
 template <int STORAGE, int MT, int WAVES, bool GATED>
-__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(3, 8))) void scan_kernel(ScanArgs a)
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu((!GATED && MT == 1) ? 2 : 3, 8))) void scan_kernel(ScanArgs a)
 {
     extern __shared__ __align__(16) char smem[];
     constexpr int MQ = MT * 16;
@@ -405,11 +405,41 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(3, 8
                 PK_LOAD(xa, 0)
             }
             preloaded = false;
-            for (int it = 0; it < nit; it += 2) {
-                if (it + 1 < nit) { PK_LOAD(xb, it + 1) }
-                PK_COMPUTE(xa, it)
-                if (it + 2 < nit) { PK_LOAD(xa, it + 2) }
-                if (it + 1 < nit) { PK_COMPUTE(xb, it + 1) }
+            bool scored = false;
+            if constexpr (!GATED && MT == 1) {
+                // The threshold sample: one query per tile, one 32-row block per wave, so a wave's time is its
+                // chain of slices.  Long rows keep three slices in flight ahead of the one being multiplied
+                // (four register buffers; the multiplication order is unchanged, so the values are too).
+                if ((nit & 3) == 0 && nit >= 8) { // wave-uniform
+                    u32x4 xc[2][4], xd[2][4];
+                    PK_LOAD(xb, 1)
+                    PK_LOAD(xc, 2)
+                    int it = 0;
+                    for (; it + 4 < nit; it += 4) {
+                        PK_LOAD(xd, it + 3)
+                        PK_COMPUTE(xa, it)
+                        PK_LOAD(xa, it + 4)
+                        PK_COMPUTE(xb, it + 1)
+                        PK_LOAD(xb, it + 5)
+                        PK_COMPUTE(xc, it + 2)
+                        PK_LOAD(xc, it + 6)
+                        PK_COMPUTE(xd, it + 3)
+                    }
+                    PK_LOAD(xd, it + 3)
+                    PK_COMPUTE(xa, it)
+                    PK_COMPUTE(xb, it + 1)
+                    PK_COMPUTE(xc, it + 2)
+                    PK_COMPUTE(xd, it + 3)
+                    scored = true;
+                }
+            }
+            if (!scored) {
+                for (int it = 0; it < nit; it += 2) {
+                    if (it + 1 < nit) { PK_LOAD(xb, it + 1) }
+                    PK_COMPUTE(xa, it)
+                    if (it + 2 < nit) { PK_LOAD(xa, it + 2) }
+                    if (it + 1 < nit) { PK_COMPUTE(xb, it + 1) }
+                }
             }
             PK_MARK(scan, GATED ? 3 : 11);
             finish_block<MT, GATED>(a, s, acc, rb, ln, lg, nrows, qcnt, row0, txn);
