@@ -21,6 +21,7 @@ LIB = os.path.join(HERE, "libpancake.so")
 SOURCES = ["pk_api.hip", "pk_scan.hip", "pk_scan_rq.hip", "pk_select.hip", "pk_worklist.hip", "pk_index.hip", "pk_gemm.hip",
            "pk_kmeans.hip"]
 HEADERS = [os.path.join(CSRC, "pk_internal.h"), os.path.join(CSRC, "pk_worklist_dev.h"),
+           os.path.join(CSRC, "pk_select_dev.h"),
            os.path.join(ROOT, "include", "pancake.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -290,6 +290,7 @@ struct Tunables {
     int hot_cus;  // PK_TUNE_HOT_CUS: CUs given to the rows-in-registers kernel while it runs beside the regular
                   // lists' scan (0: one after the other on the caller's stream)
     int wl_aside; // PK_TUNE_WL_ASIDE: large batches build the second half of the work list beside the sample scan
+    int fuse_tau; // PK_TUNE_FUSE_TAU: small batches take sample, thresholds and work list in one launch
 };
 
 #ifdef PK_DEV_TUNABLES
@@ -319,7 +320,7 @@ const Tunables &tunables()
                         env("PK_TUNE_KS", 1),        env("PK_TUNE_SP_MAX", 16),   env("PK_TUNE_GEMM_WGS", 128),
                         env("PK_TUNE_DENSESEL", 1),  env("PK_TUNE_GRABDIV", 8),   env("PK_TUNE_HIST", 1),
                         env("PK_TUNE_RS_FROM", 0),   env("PK_TUNE_RS_NQ", 512),   env("PK_TUNE_HOT_GRAB", 1),
-                        env("PK_TUNE_HOT_CUS", 96),  env("PK_TUNE_WL_ASIDE", 1)};
+                        env("PK_TUNE_HOT_CUS", 96),  env("PK_TUNE_WL_ASIDE", 1),  env("PK_TUNE_FUSE_TAU", 1)};
     }();
     return t;
 }
@@ -687,10 +688,14 @@ int run_fine(const Plan &p, const MultiArgs &m, pk_index *own, const float *q, i
         PK_HIP(launch_worklist_tiles(w, m, own->side));
         PK_HIP(hipEventRecord(own->ev_join, own->side));
     }
-    PK_HIP(launch_scan(ss, p.grid_s, s));
-    if (p.wl_small) {
+    if (p.wl_small && p.span <= 16u * (uint32_t)kSelThreads && tunables().fuse_tau) {
+        // small batches: the sample, the thresholds and the slots and tiles of the work list in one launch
+        PK_HIP(launch_sample_tau(ss, sm, w, m, p.grid_s, s));
+    } else if (p.wl_small) {
+        PK_HIP(launch_scan(ss, p.grid_s, s));
         PK_HIP(launch_tau(sm, s, &w, &m)); // its workgroups also lay out the slots and tiles of the work list
     } else {
+        PK_HIP(launch_scan(ss, p.grid_s, s));
         PK_HIP(launch_tau(sm, s));
         if (wl_aside) PK_HIP(hipStreamWaitEvent(s, own->ev_join, 0));
         else PK_HIP(launch_worklist_tiles(w, m, s));

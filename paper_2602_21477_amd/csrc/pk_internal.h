@@ -266,13 +266,16 @@ int scan_max_mq(int row_bytes, int storage, int lds_limit);
 // time it is handed a batch past the end.
 struct Sched {
     uint32_t t, end, ntiles, grab;
+    uint32_t nblk; // workgroups that take tiles (all of the launch, unless its first ones do other work)
     int parity;
     bool fresh; // t is the first tile of a batch
-    __device__ __forceinline__ void start(uint32_t nt, uint32_t g)
+    // bid: this workgroup's number among the nblk that take tiles
+    __device__ __forceinline__ void start(uint32_t nt, uint32_t g, uint32_t bid, uint32_t nb)
     {
         ntiles = nt;
         grab = g;
-        t = blockIdx.x;
+        nblk = nb;
+        t = bid;
         end = t + 1 < nt ? t + 1 : nt;
         parity = 0;
         fresh = true;
@@ -280,12 +283,12 @@ struct Sched {
     // one thread asks for the batch after the current one (s_misc[2*parity], [2*parity+1] = start, size)
     __device__ __forceinline__ void request(const ScanArgs &a, uint32_t *s_misc, uint32_t asker = 0u) const
     {
-        if (threadIdx.x == asker && gridDim.x < ntiles) {
+        if (threadIdx.x == asker && nblk < ntiles) {
             // One atomic per batch and no other access to the counter: every workgroup of the
             // grid claims from this one address, and a second access per claim (a load, to
             // size the batch by what is left) measurably slows the whole scan.
             const uint32_t want = grab;
-            s_misc[2 * parity] = gridDim.x + atomicAdd(a.tile_ctr, want);
+            s_misc[2 * parity] = nblk + atomicAdd(a.tile_ctr, want);
             s_misc[2 * parity + 1] = want;
         }
     }
@@ -298,7 +301,7 @@ struct Sched {
             return t + 1;
         }
         next_fresh = true;
-        if (gridDim.x >= ntiles) {
+        if (nblk >= ntiles) {
             next_end = ntiles;
             return ntiles;
         }
@@ -476,6 +479,10 @@ hipError_t launch_worklist_count(const WorklistArgs &a, const SampleArgs &sm, co
 hipError_t launch_worklist_tiles(const WorklistArgs &a, const MultiArgs &m, hipStream_t s);
 // wa / ma given (small batches): the launch also builds the second half of the work list (launch_worklist_tiles is not needed)
 hipError_t launch_tau(const SampleArgs &a, hipStream_t s, const WorklistArgs *wa = nullptr, const MultiArgs *ma = nullptr);
+// small batches: the sample's tiles, the thresholds and the second half of the work list in one launch (in place of
+// launch_scan over the sample, launch_tau and launch_worklist_tiles); sm.span at most 4096
+hipError_t launch_sample_tau(const ScanArgs &a, const SampleArgs &sm, const WorklistArgs &wa, const MultiArgs &ma, int grid,
+                             hipStream_t s);
 // wa / sm / ma given: the selection's workgroups also do launch_worklist_count's work for their queries
 hipError_t launch_select_dense(const float *vals, const uint32_t *qoff, const uint32_t *qcnt, uint32_t max_cnt, int metric,
                                int K, int64_t nq, int32_t *probes, hipStream_t s, const WorklistArgs *wa = nullptr,

@@ -24,8 +24,16 @@
 //                   too wide for the first kernel to keep several workgroups per CU.
 // centroid_scores_kernel is the coarse step for small query segments (the same operand
 // layout, no LDS staging); large segments go through the GEMM in pk_gemm.hip.
+#include <algorithm>
+
 #include "pk_internal.h"
 PK_DEV_MARKS(scan)
+#include "pk_select_dev.h"
+#include "pk_worklist_dev.h"
+
+#ifndef PK_FUSE_MODE
+#define PK_FUSE_MODE 2
+#endif
 
 namespace pk {
 
@@ -249,7 +257,9 @@ __device__ __forceinline__ void emit_block(const ScanArgs &a, const Slots &s, f3
 
 // Epilogue of one 32-row block: the lane holds rows (rb*32 + nt*16 + ln) for slots
 // mt*16 + lg*4 + i.  Dense mode writes every value; gated mode emits the survivors.
-template <int MT, bool GATED>
+// COHERENT (dense mode): the values are written through to where every CU of the device reads them
+// (another workgroup of the same launch goes on to read them).
+template <int MT, bool GATED, bool COHERENT = false>
 __device__ __forceinline__ void finish_block(const ScanArgs &a, const Slots &s, f32x4 (&acc)[MT][2], int rb, int ln, int lg,
                                              int nrows, uint32_t qcnt, uint32_t row0, gfloats txn)
 {
@@ -273,7 +283,11 @@ __device__ __forceinline__ void finish_block(const ScanArgs &a, const Slots &s, 
                     const int m = mt * 16 + lg * 4 + i;
                     float v = acc[mt][nt][i];
                     if (a.metric == PK_METRIC_L2) v = l2_from_dot(xn, v, s.qn[m & (MQ - 1)]);
-                    if ((uint32_t)m < qcnt && row < nrows_pad) a.out[(size_t)s.out[m] + row0 + row] = live ? v : worst;
+                    if ((uint32_t)m < qcnt && row < nrows_pad) {
+                        float *dst = a.out + (size_t)s.out[m] + row0 + row;
+                        if constexpr (COHERENT) __hip_atomic_store(dst, live ? v : worst, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        else *dst = live ? v : worst;
+                    }
                 }
             }
         }
@@ -285,10 +299,13 @@ __device__ __forceinline__ void finish_block(const ScanArgs &a, const Slots &s, 
 // MT = query tiles of 16 slots held in LDS (MQ = 16*MT); WAVES = waves per workgroup;
 // GATED = emit only values that pass the per-query gate (fine search) instead of writing
 // every value (coarse search, threshold sampling).
-template <int STORAGE, int MT, int WAVES, bool GATED>
-__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu((!GATED && MT == 1) ? 2 : 3, 8))) void scan_kernel(ScanArgs a)
+// FUSED (threshold sample of a small batch; sm, extra_off given): the workgroup that scores the last of a
+// query's sample tiles goes on to work out that query's threshold, so that no launch of its own is needed
+// for it.  bid / nblk: this workgroup's number among those of the launch that take tiles.
+template <int STORAGE, int MT, int WAVES, bool GATED, bool FUSED>
+__device__ __forceinline__ void scan_body(const ScanArgs &a, char *smem, uint32_t bid, uint32_t nblk, const SampleArgs *sm,
+                                          uint32_t extra_off)
 {
-    extern __shared__ __align__(16) char smem[];
     constexpr int MQ = MT * 16;
     const int row_bytes = a.row_bytes;
     const int qstride = row_bytes + kQPadBytes;
@@ -311,7 +328,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu((!GA
 
     PK_MARK(scan, GATED ? 0 : 8);
     Sched sc;
-    sc.start(*a.ntiles, *a.batch);
+    sc.start(*a.ntiles, *a.batch, bid, nblk);
     if (sc.t >= sc.ntiles) return;
     Tile cur = a.tiles[sc.t];
     while (sc.t < sc.ntiles) {
@@ -442,18 +459,79 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu((!GA
                 }
             }
             PK_MARK(scan, GATED ? 3 : 11);
-            finish_block<MT, GATED>(a, s, acc, rb, ln, lg, nrows, qcnt, row0, txn);
+            finish_block<MT, GATED, FUSED && PK_FUSE_MODE == 2>(a, s, acc, rb, ln, lg, nrows, qcnt, row0, txn);
             PK_MARK(scan, GATED ? 4 : 12);
         }
 #undef PK_ROWS
 #undef PK_LOAD
 #undef PK_COMPUTE
+        if constexpr (FUSED) {
+            // A sample tile is one page against one query (slot number = query number), and every query has
+            // sm->sp of them (pages it lacks are empty tiles).  The query's running limit word, unused until its
+            // threshold exists, counts the tiles that are done: each thread makes its values of the tile
+            // visible to the device, the workgroup meets, one thread counts.  Whoever counts the last one
+            // finds every value of the query's sample in place.
+            uint32_t *fx = reinterpret_cast<uint32_t *>(smem + extra_off); // [4][256] histograms, [12] reduction, [1] flag
+#if PK_FUSE_MODE == 2
+            __builtin_amdgcn_s_waitcnt(0x0f70); // vmcnt(0): this thread's written-through values have arrived
+#else
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+#endif
+            __syncthreads();
+            if (tid == 0)
+                fx[4 * 256 + 12] = __hip_atomic_fetch_add(sm->tcur + qbeg, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u ==
+                                           (uint32_t)sm->sp
+                                       ? 1u
+                                       : 0u;
+            __syncthreads();
+            if (fx[4 * 256 + 12]) {
+                // (the sample is read past the CU's and the XCD's caches: tau_by_radix, COHERENT)
+                const float *v = sm->vals + (size_t)qbeg * sm->span;
+                uint32_t cnt = 0, first = 0, kth = 0, last = 0;
+                uint32_t(*hist)[256] = reinterpret_cast<uint32_t(*)[256]>(fx);
+                if (sm->span <= 4u * kSelThreads)
+                    tau_by_radix<4, true>(*sm, v, hist, fx + 4 * 256, cnt, first, kth, last, [] {});
+                else
+                    tau_by_radix<16, true>(*sm, v, hist, fx + 4 * 256, cnt, first, kth, last, [] {});
+                tau_publish(*sm, qbeg, cnt, first, kth, last);
+            }
+        }
         sc.t = tn;
         sc.end = next_end;
         if (next_fresh) sc.parity ^= 1;
         sc.fresh = next_fresh;
         cur = nxt;
     }
+}
+
+template <int STORAGE, int MT, int WAVES, bool GATED>
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu((!GATED && MT == 1) ? 2 : 3, 8))) void scan_kernel(ScanArgs a)
+{
+    extern __shared__ __align__(16) char smem[];
+    scan_body<STORAGE, MT, WAVES, GATED, false>(a, smem, blockIdx.x, gridDim.x, nullptr, 0u);
+}
+
+// The threshold sample of a small batch with everything that hangs on it, in one launch.  The first sm.nq
+// workgroups lay out the second half of the work list (slots and tiles of the fine scan: it needs the
+// pair counts only, which the coarse selection left); the others score the sample tiles, and the one that
+// finishes a query's last tile works out its threshold (scan_body, FUSED).  extra_off: where, in the
+// dynamic LDS, the threshold's histograms lie (behind the scan's own part).
+template <int STORAGE>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 8))) void sample_tau_kernel(ScanArgs a, SampleArgs sm,
+                                                                                                     WorklistArgs wa,
+                                                                                                     MultiArgs ma,
+                                                                                                     uint32_t extra_off)
+{
+    extern __shared__ __align__(16) char smem[]; // (all of the kernel's LDS: the limit set for it counts static LDS in)
+    const uint32_t nq = (uint32_t)sm.nq;
+    if (blockIdx.x < nq) {
+        uint32_t *s_pref = reinterpret_cast<uint32_t *>(smem); // [3][kWlSmallLists + 1], then [12] for the waves' sums
+        WlPrefetch pre;
+        wl_spread_prefetch(wa, ma, blockIdx.x, pre);
+        wl_spread(wa, ma, s_pref, s_pref + 3 * (kWlSmallLists + 1), blockIdx.x, pre);
+        return;
+    }
+    scan_body<STORAGE, 1, 4, false, true>(a, smem, blockIdx.x - nq, gridDim.x - nq, &sm, extra_off);
 }
 
 // ------------------------------------------------------------------ sliced-query kernel
@@ -483,7 +561,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 8))) voi
     const int qm = tid >> 4, qpiece = (tid & 15) * 16; // this thread's slot (mod 16) and piece of a slice
 
     Sched sc;
-    sc.start(*a.ntiles, *a.batch);
+    sc.start(*a.ntiles, *a.batch, blockIdx.x, gridDim.x);
     if (sc.t >= sc.ntiles) return;
     Tile cur = a.tiles[sc.t];
     while (sc.t < sc.ntiles) {
@@ -822,6 +900,43 @@ static hipError_t launch_ks_mt(const ScanArgs &a, int grid, hipStream_t s)
     case 64: return launch_ks_one<STORAGE, 4, GATED>(a, grid, s);
     default: return hipErrorInvalidValue;
     }
+}
+
+// Threshold sample of a small batch: the sample's tiles (a.mq < 16: one query each), every query's threshold and
+// the second half of the work list in one launch.  grid: workgroups for the tiles; sm.nq more are added.
+hipError_t launch_sample_tau(const ScanArgs &a, const SampleArgs &sm, const WorklistArgs &wa, const MultiArgs &ma, int grid,
+                             hipStream_t s)
+{
+    if (a.row_bytes <= 0 || a.row_bytes % kIterBytes != 0 || a.tau != nullptr || a.mq < 1 || a.mq >= 16)
+        return hipErrorInvalidValue;
+    if (sm.nq <= 0 || sm.span % 4 != 0 || sm.span > 16u * kSelThreads) return hipErrorInvalidValue;
+    if ((uint64_t)wa.n_handles * (uint64_t)wa.nlist_max > kWlSmallLists) return hipErrorInvalidValue;
+    const int scan_part = (scan_lds_bytes(a.row_bytes, a.mq) + 15) & ~15;
+    const int tau_part = (4 * 256 + 12 + 4) * 4;               // histograms, reduction, flag
+    const int spread_part = (3 * ((int)kWlSmallLists + 1) + 12) * 4; // the three prefix sums over the lists, the waves' sums
+    const int lds = std::max(scan_part + tau_part, spread_part);
+    const void *fn = a.storage == PK_F16 ? reinterpret_cast<const void *>(&sample_tau_kernel<PK_F16>)
+                                         : reinterpret_cast<const void *>(&sample_tau_kernel<PK_F32>);
+    static LdsCleared cleared[2];
+    LdsCleared &c = cleared[a.storage == PK_F16 ? 1 : 0];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const bool tracked = dev >= 0 && dev < kMaxDevices;
+    if (!tracked || c.on[dev].load(std::memory_order_acquire) == 0) {
+        int most = 0;
+        e = hipDeviceGetAttribute(&most, hipDeviceAttributeMaxSharedMemoryPerBlock, dev);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, most);
+        if (e != hipSuccess) return e;
+        if (tracked) c.on[dev].store(1, std::memory_order_release);
+    }
+    const dim3 g((uint32_t)grid + (uint32_t)sm.nq), b(256);
+    if (a.storage == PK_F16)
+        hipLaunchKernelGGL(sample_tau_kernel<PK_F16>, g, b, lds, s, a, sm, wa, ma, (uint32_t)scan_part);
+    else
+        hipLaunchKernelGGL(sample_tau_kernel<PK_F32>, g, b, lds, s, a, sm, wa, ma, (uint32_t)scan_part);
+    return hipGetLastError();
 }
 
 // whole-group kernel: gated (fine search) when a.tau is set, else every value is written (threshold sampling)

@@ -14,8 +14,9 @@
 //
 // Per (row, query) the same MFMAs run in the same order as in scan_kernel, so the values are
 // bit-identical and the thresholds of the sample apply.  The launch runs after the regular
-// lists' scan: it reads the bucket limits that scan has published and does not maintain the
-// histogram any further.
+// lists' scan or beside it: it reads the bucket limits that scan has published by then (a
+// limit only ever tightens, so an early reading emits more, never less) and does not maintain
+// the histogram itself.
 //
 // The row length is a template parameter (NIT = row bytes / 256): every inner loop has a
 // compile-time trip count and the steady state is straight-line code, which is what lets the

@@ -125,6 +125,7 @@ __device__ __forceinline__ void wl_count_query(const WorklistArgs &a, const Samp
     for (uint32_t i = threadIdx.x; i < sm.span; i += blockDim.x) vals[i] = worst;
     if (threadIdx.x == 0) {
         a.ccnt[q] = 0;
+        sm.tcur[q] = 0; // until the threshold exists: the query's sample tiles that are done (small batches)
         sm.slot_query[q] = q;
         sm.slot_out[q] = q * sm.span;
         if (q == 0) {

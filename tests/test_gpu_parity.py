@@ -929,6 +929,75 @@ def test_small_batches_take_fewer_launches_and_give_the_same_results(gpu_device)
             p.close()
 
 
+def _captured_kernel_launches(call):
+    """Kernel nodes (and all nodes) of the HIP graph that capturing `call` on a stream of its own records.
+    Nothing of the graph is run.  The HIP runtime is the one the process has loaded already (torch's)."""
+    import ctypes as C
+    path = None
+    with open("/proc/self/maps") as f:
+        for line in f:
+            if "libamdhip64" in line:
+                path = line.split()[-1]
+                break
+    assert path, "no HIP runtime in this process"
+    hip = C.CDLL(path)
+    hip.hipStreamBeginCapture.argtypes = [C.c_void_p, C.c_int]
+    hip.hipStreamEndCapture.argtypes = [C.c_void_p, C.POINTER(C.c_void_p)]
+    hip.hipGraphGetNodes.argtypes = [C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_size_t)]
+    hip.hipGraphNodeGetType.argtypes = [C.c_void_p, C.POINTER(C.c_int)]
+    hip.hipGraphDestroy.argtypes = [C.c_void_p]
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    graph = C.c_void_p()
+    with torch.cuda.stream(side):
+        assert hip.hipStreamBeginCapture(side.cuda_stream, 2) == 0  # relaxed mode: other threads are not affected
+        try:
+            call()
+        finally:
+            rc = hip.hipStreamEndCapture(side.cuda_stream, C.byref(graph))
+    assert rc == 0 and graph.value
+    n = C.c_size_t(0)
+    assert hip.hipGraphGetNodes(graph, None, C.byref(n)) == 0
+    nodes = (C.c_void_p * max(1, n.value))()
+    assert hip.hipGraphGetNodes(graph, nodes, C.byref(n)) == 0
+    kernels = 0
+    for i in range(n.value):
+        kind = C.c_int(-1)
+        assert hip.hipGraphNodeGetType(nodes[i], C.byref(kind)) == 0
+        kernels += kind.value == 0  # hipGraphNodeTypeKernel
+    hip.hipGraphDestroy(graph)
+    torch.cuda.synchronize()
+    return kernels, n.value
+
+
+def test_a_small_search_is_five_kernel_launches(gpu_device):
+    """Section 3.3: small batches are bound by launches, not by arithmetic.  A search of up to 64 queries
+    over fp32 rows (inner product) is five kernels: centroid scores, top-nprobe with the pair counts,
+    threshold sample with thresholds and work list, gated scan, final selection; the other storage and
+    metric combinations add the preparation of the queries.  Counted as the kernel nodes of the HIP graph
+    a capture of the call records (the graph is not run; the eager call before it is checked against the
+    oracle, and so is the one after it)."""
+    cfg = W.scaled(W.C1, n=6000)
+    for storage, metric, most in ((F32, IP, 5), (F32, L2, 6), (F16, IP, 6), (F16, L2, 7)):
+        p, _ = make_pair(cfg, metric=metric, storage=storage)
+        try:
+            k, nprobe = 10, 8
+            for nq in (1, 16, 64):
+                q = W.queries(cfg, 40, nq)
+                qbuf = dev(q)
+                ids = torch.empty((nq, k), dtype=torch.int64, device="cuda")
+                dist = torch.empty((nq, k), dtype=torch.float32, device="cuda")
+                p.check_search(q, k, nprobe, where=f"before the capture, {nq} queries")  # also sizes the workspace
+                say(f"capture storage={storage} metric={metric} nq={nq}")
+                kernels, nodes = _captured_kernel_launches(lambda: B.pk_search(p.gpu.handle, qbuf, k, nprobe, ids, dist))
+                say(f"storage={storage} metric={metric} nq={nq}: {kernels} kernel launches ({nodes} graph nodes)")
+                assert kernels == nodes, "a search records kernels only"
+                assert kernels <= most, f"{kernels} launches for {nq} queries (storage {storage}, metric {metric})"
+                p.check_search(q, k, nprobe, where=f"after the capture, {nq} queries")
+        finally:
+            p.close()
+
+
 def test_reserved_workspace_never_grows_and_capture_refuses_growth(gpu_device):
     """Section 5: operations must not block the caller.  After one pk_workspace_reserve a config-5
     style stream of {insert 1; search 16} (and a batch insert, and a larger search within the
