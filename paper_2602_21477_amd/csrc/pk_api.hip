@@ -2,6 +2,7 @@
 // sequences of build, insert and search.  See include/pancake.h for the contract.
 #include <algorithm>
 #include <atomic>
+#include <cmath>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -429,7 +430,7 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
     p.grid_s = grid_for(own, own->row_bytes, kSampleSlots);
     p.K = k + 1;
     p.sp = (k + own->P - 1) / own->P; // sample pages: at least k rows when the first pages are full
-    uint64_t tiles = 0, wmax = 0;
+    uint64_t tiles = 0, wmax = 0, lmax = 0;
     int nlist_hi = 0, pad_hi = 0;
     const int mq_least = worst ? 16 : std::min(p.mq_f, p.mq_h);
     const bool rs_tiles = worst ? (own->row_bytes <= 1536 && own->P % kRrTileRows == 0) : p.hot_rs;
@@ -442,6 +443,7 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
         const uint64_t w = wq_ub(ix, nprobe, ahead);
         if (w > 0xfffffff0ull) return PK_ERR_UNSUPPORTED; // positions inside a query's range are 32-bit
         wmax = std::max(wmax, w);
+        lmax = std::max(lmax, wq_ub(ix, 1)); // the longest list as it may be now
         const uint64_t pp = w / ix->P + nprobe;
         const uint64_t pages = std::min<uint64_t>(pages_used_ub(ix, ahead), nqa * pp);
         tiles += pages + nqa * pp / mq_least + 1;
@@ -453,13 +455,22 @@ int make_plan(Plan &p, pk_index *const *hs, int nh, const uint32_t *qlo, int64_t
     {
         // Sample pages per query.  A larger sample gives a tighter threshold and a finer bucket
         // scale, hence fewer emitted candidates; it costs one tile per query and page.  Wanted:
-        // the k-th best of the sample at most its 40 % quantile (large k); and, for batches of
-        // few queries, whose emitted candidates all meet at a handful of counters and
-        // serialise there, a sample of 0.5 % of the most rows a query can meet (long lists).
+        // the k-th best of the sample at most its 40 % quantile (large k).  And for batches of
+        // few queries, whose emitted candidates all meet at a handful of counters and serialise
+        // there: the query that lands in the longest list emits a share of that list's rows that
+        // falls as 1 / pages, about 1 ns of serialised emission per row of the list at one page
+        // (measured: 60 k entries from a 444 k-row list, 0.45 ms), while a page costs every query
+        // a tile: 0.7 us of latency plus its bytes at 10 TB/s while the tiles fit the chip side by
+        // side.  The sum is least at pages = sqrt(first cost / second).
         // Spent: at most 3 % of the scan's tiles, and sp_max pages.
         const uint64_t afford = tiles * 3u / 100u / (uint64_t)std::max<int64_t>(nq, 1);
         const uint64_t by_quantile = ((uint64_t)p.K * 10 + 3 * own->P - 1) / (3 * own->P);
-        const uint64_t by_size = nq <= 64 ? (wmax / 200 + own->P - 1) / own->P : 0;
+        uint64_t by_size = 0;
+        if (nq <= 64) {
+            const double emit_us = 1.0e-3 * (double)lmax;
+            const double page_us = 0.7 + (double)nq * (double)own->P * (double)own->row_bytes / 1.0e7;
+            by_size = (uint64_t)std::llround(std::sqrt(emit_us / page_us));
+        }
         uint64_t more = std::min(afford, std::max(by_quantile, by_size));
         more = std::min<uint64_t>(more, (uint64_t)tunables().sp_max);
         if (worst) more = (uint64_t)tunables().sp_max;
@@ -559,6 +570,11 @@ void fill_worklist_args(const Plan &p, const pk_index *own, WorklistArgs &w, Sam
     w.scalars = p.scalars + 4;
     w.scalars_hot = p.scalars + 12;
     w.lcnt_cleared = p.need_coarse;
+    if (p.nh == 1) {
+        w.len1 = own->host.list_len;
+        w.P1 = (uint32_t)own->host.P;
+        w.nlist1 = (uint32_t)own->host.nlist;
+    }
 }
 
 // Coarse search of one batch: probes[nq][nprobe] in the plan's workspace.

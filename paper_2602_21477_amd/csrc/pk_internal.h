@@ -21,9 +21,15 @@
     do {                                                                                        \
         if (blockIdx.x == 0 && threadIdx.x == 0) name##_marks[i] = wall_clock64();              \
     } while (0)
+// (mark by the first thread of whichever workgroup `cond` picks)
+#define PK_MARK_IF(name, i, cond)                                                               \
+    do {                                                                                        \
+        if ((cond) && threadIdx.x == 0) name##_marks[i] = wall_clock64();                       \
+    } while (0)
 #else
 #define PK_DEV_MARKS(name)
 #define PK_MARK(name, i) do { } while (0)
+#define PK_MARK_IF(name, i, cond) do { } while (0)
 #endif
 
 namespace pk {
@@ -454,6 +460,10 @@ struct WorklistArgs {
     uint32_t tile_cap;
     uint32_t *scalars;         // [0] ntiles [1] tile counter [2] grab size
     uint32_t *scalars_hot;     // [0] hot tiles [1] tile counter [2] grab size
+    // one handle only: its list lengths, page size and list count, so that the work-list layout of a small batch
+    // reads them without first chasing the handle's descriptor (null / 0 otherwise)
+    const uint32_t *len1;
+    uint32_t P1, nlist1;
 };
 
 // Threshold sampling: the first `sp` pages of each query's first probed list are scored

@@ -28,12 +28,9 @@
 
 #include "pk_internal.h"
 PK_DEV_MARKS(scan)
+#define PK_WL_MARK(i) PK_MARK(scan, i)
 #include "pk_select_dev.h"
 #include "pk_worklist_dev.h"
-
-#ifndef PK_FUSE_MODE
-#define PK_FUSE_MODE 2
-#endif
 
 namespace pk {
 
@@ -261,7 +258,7 @@ __device__ __forceinline__ void emit_block(const ScanArgs &a, const Slots &s, f3
 // (another workgroup of the same launch goes on to read them).
 template <int MT, bool GATED, bool COHERENT = false>
 __device__ __forceinline__ void finish_block(const ScanArgs &a, const Slots &s, f32x4 (&acc)[MT][2], int rb, int ln, int lg,
-                                             int nrows, uint32_t qcnt, uint32_t row0, gfloats txn)
+                                             int nrows, uint32_t qcnt, uint32_t row0, gfloats txn, float *lds_vals = nullptr)
 {
     if constexpr (GATED) {
         emit_block<MT>(a, s, acc, rb, ln, lg, nrows, qcnt, row0, txn);
@@ -285,8 +282,12 @@ __device__ __forceinline__ void finish_block(const ScanArgs &a, const Slots &s, 
                     if (a.metric == PK_METRIC_L2) v = l2_from_dot(xn, v, s.qn[m & (MQ - 1)]);
                     if ((uint32_t)m < qcnt && row < nrows_pad) {
                         float *dst = a.out + (size_t)s.out[m] + row0 + row;
-                        if constexpr (COHERENT) __hip_atomic_store(dst, live ? v : worst, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        else *dst = live ? v : worst;
+                        if constexpr (COHERENT) {
+                            if (lds_vals) lds_vals[row0 + row] = live ? v : worst; // (one slot, one tile: the values' only reader is this workgroup)
+                            else __hip_atomic_store(dst, live ? v : worst, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        } else {
+                            *dst = live ? v : worst;
+                        }
                     }
                 }
             }
@@ -326,16 +327,27 @@ __device__ __forceinline__ void scan_body(const ScanArgs &a, char *smem, uint32_
     uint32_t cur_qbeg = 0xffffffffu, cur_qcnt = 0;
     const char *qbase = qtile + (size_t)(ln < qrows ? ln : qrows) * qstride + lg * 16;
 
-    PK_MARK(scan, GATED ? 0 : 8);
+    PK_MARK_IF(scan, GATED ? 0 : 8, bid == 0);
     Sched sc;
-    sc.start(*a.ntiles, *a.batch, bid, nblk);
+    if constexpr (FUSED) {
+        // the sample has sp tiles for every query (the scalars in memory say the same: no need to wait for them)
+        const uint32_t nt = (uint32_t)sm->nq * (uint32_t)sm->sp;
+        const uint32_t g = nt / (uint32_t)(sm->scan_grid * 4);
+        sc.start(nt, g < 1 ? 1 : (g > 8 ? 8 : g), bid, nblk);
+    } else {
+        sc.start(*a.ntiles, *a.batch, bid, nblk);
+    }
     if (sc.t >= sc.ntiles) return;
+    // FUSED with one tile per query: the tile's values go to the threshold through LDS, not through memory
+    [[maybe_unused]] const bool one = FUSED && sm->sp == 1;
+    [[maybe_unused]] uint32_t *const fx = reinterpret_cast<uint32_t *>(smem + extra_off); // [4][256] histograms, [12] reduction, [4] flag
+    [[maybe_unused]] float *const sv = reinterpret_cast<float *>(fx + 4 * 256 + 16);      // [span] values (one tile per query)
     Tile cur = a.tiles[sc.t];
     while (sc.t < sc.ntiles) {
         const gbytes tx = in_global(cur.x);
         const gfloats txn = in_global(cur.xn);
         const uint32_t row0 = cur.row0;
-        PK_MARK(scan, GATED ? 1 : 9);
+        PK_MARK_IF(scan, GATED ? 1 : 9, bid == 0);
         const uint32_t qbeg = __builtin_amdgcn_readfirstlane(cur.qbeg);
         const uint32_t qcnt = __builtin_amdgcn_readfirstlane((uint32_t)cur.qcnt);
         const int nrows = __builtin_amdgcn_readfirstlane((int)cur.nrows);
@@ -388,8 +400,10 @@ __device__ __forceinline__ void scan_body(const ScanArgs &a, char *smem, uint32_
             for (int idx0 = tid; idx0 < total; idx0 += 2 * WAVES * 64) {
                 const int idx1 = idx0 + WAVES * 64;
                 const int m0 = idx0 / chunks_per_row, m1 = idx1 / chunks_per_row;
-                const uint32_t sq0 = (uint32_t)m0 < qcnt ? a.slot_query[qbeg + m0] : 0xffffffffu;
-                const uint32_t sq1 = idx1 < total && (uint32_t)m1 < qcnt ? a.slot_query[qbeg + m1] : 0xffffffffu;
+                // (the sample's slot numbers are its query numbers)
+                const uint32_t sq0 = (uint32_t)m0 < qcnt ? (FUSED ? qbeg + m0 : a.slot_query[qbeg + m0]) : 0xffffffffu;
+                const uint32_t sq1 =
+                    idx1 < total && (uint32_t)m1 < qcnt ? (FUSED ? qbeg + m1 : a.slot_query[qbeg + m1]) : 0xffffffffu;
                 u32x4 v0 = {0u, 0u, 0u, 0u}, v1 = {0u, 0u, 0u, 0u};
                 if (sq0 != 0xffffffffu)
                     v0 = *reinterpret_cast<const u32x4 *>(a.qs + (size_t)sq0 * row_bytes + (size_t)(idx0 - m0 * chunks_per_row) * 16);
@@ -399,7 +413,15 @@ __device__ __forceinline__ void scan_body(const ScanArgs &a, char *smem, uint32_
                 if (idx1 < total)
                     *reinterpret_cast<u32x4 *>(qtile + (size_t)m1 * qstride + (size_t)(idx1 - m1 * chunks_per_row) * 16) = v1;
             }
-            load_slots<MQ, GATED>(a, s, tid, qbeg, qcnt);
+            if constexpr (FUSED) {
+                if (tid < MQ) {
+                    const bool on = (uint32_t)tid < qcnt;
+                    s.out[tid] = on ? (qbeg + (uint32_t)tid) * sm->span : 0u;
+                    s.qn[tid] = on ? a.qnorm[qbeg + tid] : 0.f;
+                }
+            } else {
+                load_slots<MQ, GATED>(a, s, tid, qbeg, qcnt);
+            }
             __syncthreads();
             cur_qbeg = qbeg;
             cur_qcnt = qcnt;
@@ -408,7 +430,14 @@ __device__ __forceinline__ void scan_body(const ScanArgs &a, char *smem, uint32_
             __syncthreads();
         }
         const int mt_used = (int)((qcnt + 15u) >> 4);
-        PK_MARK(scan, GATED ? 2 : 10);
+        if constexpr (FUSED) {
+            if (one) {
+                const float worst = a.metric == PK_METRIC_IP ? -INFINITY : INFINITY;
+                for (uint32_t i = tid; i < sm->span; i += WAVES * 64) sv[i] = worst;
+                __syncthreads();
+            }
+        }
+        PK_MARK_IF(scan, GATED ? 2 : 10, bid == 0);
 
         for (; rb * kRowBlock < nrows; rb += WAVES) {
             f32x4 acc[MT][2];
@@ -458,9 +487,9 @@ __device__ __forceinline__ void scan_body(const ScanArgs &a, char *smem, uint32_
                     if (it + 1 < nit) { PK_COMPUTE(xb, it + 1) }
                 }
             }
-            PK_MARK(scan, GATED ? 3 : 11);
-            finish_block<MT, GATED, FUSED && PK_FUSE_MODE == 2>(a, s, acc, rb, ln, lg, nrows, qcnt, row0, txn);
-            PK_MARK(scan, GATED ? 4 : 12);
+            PK_MARK_IF(scan, GATED ? 3 : 11, bid == 0);
+            finish_block<MT, GATED, FUSED>(a, s, acc, rb, ln, lg, nrows, qcnt, row0, txn, FUSED && one ? sv : nullptr);
+            PK_MARK_IF(scan, GATED ? 4 : 12, bid == 0);
         }
 #undef PK_ROWS
 #undef PK_LOAD
@@ -471,29 +500,38 @@ __device__ __forceinline__ void scan_body(const ScanArgs &a, char *smem, uint32_
             // threshold exists, counts the tiles that are done: each thread makes its values of the tile
             // visible to the device, the workgroup meets, one thread counts.  Whoever counts the last one
             // finds every value of the query's sample in place.
-            uint32_t *fx = reinterpret_cast<uint32_t *>(smem + extra_off); // [4][256] histograms, [12] reduction, [1] flag
-#if PK_FUSE_MODE == 2
-            __builtin_amdgcn_s_waitcnt(0x0f70); // vmcnt(0): this thread's written-through values have arrived
-#else
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-#endif
-            __syncthreads();
-            if (tid == 0)
-                fx[4 * 256 + 12] = __hip_atomic_fetch_add(sm->tcur + qbeg, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u ==
-                                           (uint32_t)sm->sp
-                                       ? 1u
-                                       : 0u;
-            __syncthreads();
-            if (fx[4 * 256 + 12]) {
-                // (the sample is read past the CU's and the XCD's caches: tau_by_radix, COHERENT)
-                const float *v = sm->vals + (size_t)qbeg * sm->span;
+            bool mine = true; // this workgroup works out the query's threshold
+            if (one) {
+                __syncthreads(); // the tile's values are in LDS
+            } else {
+                __builtin_amdgcn_s_waitcnt(0x0f70); // vmcnt(0): this thread's written-through values have arrived
+                __syncthreads();
+                if (tid == 0)
+                    fx[4 * 256 + 12] =
+                        __hip_atomic_fetch_add(sm->tcur + qbeg, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u ==
+                                (uint32_t)sm->sp
+                            ? 1u
+                            : 0u;
+                __syncthreads();
+                mine = fx[4 * 256 + 12] != 0u;
+            }
+            PK_MARK_IF(scan, 13, bid == 0);
+            if (mine) {
+                PK_MARK_IF(scan, 14, qbeg == 0);
                 uint32_t cnt = 0, first = 0, kth = 0, last = 0;
                 uint32_t(*hist)[256] = reinterpret_cast<uint32_t(*)[256]>(fx);
-                if (sm->span <= 4u * kSelThreads)
-                    tau_by_radix<4, true>(*sm, v, hist, fx + 4 * 256, cnt, first, kth, last, [] {});
-                else
-                    tau_by_radix<16, true>(*sm, v, hist, fx + 4 * 256, cnt, first, kth, last, [] {});
+                if (one) {
+                    tau_by_radix<4, false>(*sm, sv, hist, fx + 4 * 256, cnt, first, kth, last, [] {});
+                } else {
+                    // (the sample is read past the CU's and the XCD's caches)
+                    const float *v = sm->vals + (size_t)qbeg * sm->span;
+                    if (sm->span <= 4u * kSelThreads)
+                        tau_by_radix<4, true>(*sm, v, hist, fx + 4 * 256, cnt, first, kth, last, [] {});
+                    else
+                        tau_by_radix<16, true>(*sm, v, hist, fx + 4 * 256, cnt, first, kth, last, [] {});
+                }
                 tau_publish(*sm, qbeg, cnt, first, kth, last);
+                PK_MARK_IF(scan, 15, qbeg == 0);
             }
         }
         sc.t = tn;
@@ -525,10 +563,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 8))) voi
     extern __shared__ __align__(16) char smem[]; // (all of the kernel's LDS: the limit set for it counts static LDS in)
     const uint32_t nq = (uint32_t)sm.nq;
     if (blockIdx.x < nq) {
+        PK_MARK(scan, 19);
         uint32_t *s_pref = reinterpret_cast<uint32_t *>(smem); // [3][kWlSmallLists + 1], then [12] for the waves' sums
         WlPrefetch pre;
         wl_spread_prefetch(wa, ma, blockIdx.x, pre);
         wl_spread(wa, ma, s_pref, s_pref + 3 * (kWlSmallLists + 1), blockIdx.x, pre);
+        PK_MARK(scan, 23);
         return;
     }
     scan_body<STORAGE, 1, 4, false, true>(a, smem, blockIdx.x - nq, gridDim.x - nq, &sm, extra_off);
@@ -912,7 +952,7 @@ hipError_t launch_sample_tau(const ScanArgs &a, const SampleArgs &sm, const Work
     if (sm.nq <= 0 || sm.span % 4 != 0 || sm.span > 16u * kSelThreads) return hipErrorInvalidValue;
     if ((uint64_t)wa.n_handles * (uint64_t)wa.nlist_max > kWlSmallLists) return hipErrorInvalidValue;
     const int scan_part = (scan_lds_bytes(a.row_bytes, a.mq) + 15) & ~15;
-    const int tau_part = (4 * 256 + 12 + 4) * 4;               // histograms, reduction, flag
+    const int tau_part = (4 * 256 + 16) * 4 + (sm.sp == 1 ? (int)sm.span * 4 : 0); // histograms, reduction, flag; one tile's values
     const int spread_part = (3 * ((int)kWlSmallLists + 1) + 12) * 4; // the three prefix sums over the lists, the waves' sums
     const int lds = std::max(scan_part + tau_part, spread_part);
     const void *fn = a.storage == PK_F16 ? reinterpret_cast<const void *>(&sample_tau_kernel<PK_F16>)

@@ -275,21 +275,36 @@ struct WlPrefetch {
 __device__ __forceinline__ void wl_spread_prefetch(const WorklistArgs &a, const MultiArgs &m, uint32_t q, WlPrefetch &w)
 {
     const uint32_t nl = (uint32_t)a.n_handles * (uint32_t)a.nlist_max;
+    if (a.len1) { // one handle: nothing to look up first
 #pragma unroll
-    for (int j = 0; j < kWlPerThread; ++j) {
-        const uint32_t gl = threadIdx.x * kWlPerThread + j;
-        w.c[j] = w.len[j] = 0;
-        w.P[j] = 1;
-        if (gl < nl) {
-            const uint32_t h = gl / (uint32_t)a.nlist_max, l = gl - h * (uint32_t)a.nlist_max;
-            const DevIndex &ix = *m.ix[h];
-            w.c[j] = a.lcnt[gl];
-            w.P[j] = (uint32_t)ix.P;
-            if (l < (uint32_t)ix.nlist) w.len[j] = ix.list_len[l];
+        for (int j = 0; j < kWlPerThread; ++j) {
+            const uint32_t gl = threadIdx.x * kWlPerThread + j;
+            w.c[j] = w.len[j] = 0;
+            w.P[j] = a.P1;
+            if (gl < nl) {
+                w.c[j] = a.lcnt[gl];
+                if (gl < a.nlist1) w.len[j] = a.len1[gl];
+            }
         }
+        w.ag = 0;
+        w.nlist = a.nlist1;
+    } else {
+#pragma unroll
+        for (int j = 0; j < kWlPerThread; ++j) {
+            const uint32_t gl = threadIdx.x * kWlPerThread + j;
+            w.c[j] = w.len[j] = 0;
+            w.P[j] = 1;
+            if (gl < nl) {
+                const uint32_t h = gl / (uint32_t)a.nlist_max, l = gl - h * (uint32_t)a.nlist_max;
+                const DevIndex &ix = *m.ix[h];
+                w.c[j] = a.lcnt[gl];
+                w.P[j] = (uint32_t)ix.P;
+                if (l < (uint32_t)ix.nlist) w.len[j] = ix.list_len[l];
+            }
+        }
+        w.ag = a.qagent[q];
+        w.nlist = (uint32_t)m.ix[w.ag]->nlist;
     }
-    w.ag = a.qagent[q];
-    w.nlist = (uint32_t)m.ix[w.ag]->nlist;
     w.probe = 0xffffffffu;
     w.pair_off = 0;
     if (threadIdx.x < (uint32_t)a.nprobe) {
