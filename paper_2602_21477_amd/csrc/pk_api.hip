@@ -611,13 +611,21 @@ int run_coarse(const Plan &p, const MultiArgs &m, pk_index *const *hs, const flo
         const uint32_t nqa = m.qlo[a + 1] - m.qlo[a];
         if (!coarse_by_gemm(nqa, hs[a])) longest = std::max(longest, nqa);
     }
+    // Queries per workgroup: as many as one workgroup takes (64) when that still leaves a workgroup for every
+    // CU; fewer otherwise, since the kernel is a chain of dependent slices and a chip half empty gains nothing
+    // from the centroid rows a larger group shares.
     ca.chunk = (int)std::min<uint32_t>(64, (longest + 15) / 16 * 16);
     uint64_t wgs = 0;
-    for (int a = 0; a < m.n; ++a) {
-        const uint32_t nqa = m.qlo[a + 1] - m.qlo[a];
-        ca.blk[a] = (uint32_t)wgs;
-        if (nqa > 0 && !coarse_by_gemm(nqa, hs[a]))
-            wgs += (uint64_t)((nqa + ca.chunk - 1) / ca.chunk) * (uint64_t)(hs[a]->nlist_pad / 16);
+    while (true) {
+        wgs = 0;
+        for (int a = 0; a < m.n; ++a) {
+            const uint32_t nqa = m.qlo[a + 1] - m.qlo[a];
+            ca.blk[a] = (uint32_t)wgs;
+            if (nqa > 0 && !coarse_by_gemm(nqa, hs[a]))
+                wgs += (uint64_t)((nqa + ca.chunk - 1) / ca.chunk) * (uint64_t)(hs[a]->nlist_pad / 16);
+        }
+        if (wgs >= (uint64_t)own->num_cu || ca.chunk <= 16) break;
+        ca.chunk -= 16;
     }
     if (wgs > 0x7fffffffull) return PK_ERR_UNSUPPORTED;
     ca.blk[m.n] = (uint32_t)wgs;
