@@ -929,6 +929,41 @@ def test_small_batches_take_fewer_launches_and_give_the_same_results(gpu_device)
             p.close()
 
 
+def test_small_batch_thresholds_from_one_tile_several_tiles_and_long_samples(gpu_device):
+    """The one-launch sample of small batches has three ways to a query's threshold: one tile per query
+    (values through LDS), several tiles (values through memory, the last workgroup to finish reads them
+    back) with samples of up to 1024 rows, and longer samples (a very long list in a batch of one or two
+    queries asks for many pages).  Each must give the rows the oracle gives, and the rows the same queries
+    get inside a 1024-query batch, whose sample, thresholds and work list come from separate launches."""
+    rng = np.random.default_rng(77)
+    d, nlist = 32, 16
+    cent = rng.standard_normal((nlist, d)).astype(np.float32)
+    # list 3 takes 85 % of the rows: 60 000 of 70 000
+    n = 70000
+    comp = np.where(rng.random(n) < 0.85, 3, rng.integers(0, nlist, n))
+    x = (cent[comp] + 0.35 * rng.standard_normal((n, d))).astype(np.float32)
+    qc = np.where(rng.random(1024) < 0.5, 3, rng.integers(0, nlist, 1024))
+    q = (cent[qc] + 0.35 * rng.standard_normal((1024, d))).astype(np.float32)
+    for storage, metric, page_vecs in ((F32, L2, 128), (F16, IP, 128), (F32, IP, 32)):
+        p = Pair(x, cent, metric, storage, page_vecs=page_vecs)
+        try:
+            assert p.gpu.list_lengths()[3] > 50000
+            for k, nprobe in ((10, 4), (100, 3), (300, 4)):
+                say(f"large batch storage={storage} metric={metric} P={page_vecs} k={k}")
+                bi, bv = p.gpu.search(dev(q), k, nprobe)
+                bi, bv = bi.cpu().numpy(), bv.cpu().numpy()
+                for lo, cnt in ((0, 1), (1, 2), (8, 8), (100, 64)):
+                    say(f"small batch [{lo}, {lo + cnt}) k={k}")
+                    si, sv = p.gpu.search(dev(q[lo:lo + cnt]), k, nprobe)
+                    assert np.array_equal(si.cpu().numpy(), bi[lo:lo + cnt]), f"ids of queries {lo}..{lo + cnt} differ (k={k})"
+                    assert np.array_equal(sv.cpu().numpy(), bv[lo:lo + cnt]), f"values of queries {lo}..{lo + cnt} differ (k={k})"
+                p.check_search(q[:2], k, nprobe, where=f"two queries k={k}")
+                p.check_search(q[100:132], k, nprobe, where=f"32 queries k={k}")
+            assert p.gpu.stats().device_error == 0
+        finally:
+            p.close()
+
+
 def _captured_kernel_launches(call):
     """Kernel nodes (and all nodes) of the HIP graph that capturing `call` on a stream of its own records.
     Nothing of the graph is run.  The HIP runtime is the one the process has loaded already (torch's)."""
