@@ -22,6 +22,9 @@
 //                   buffered), so LDS use is independent of the row length and up to 128
 //                   slots fit: for lists probed by many queries of the batch and for rows
 //                   too wide for the first kernel to keep several workgroups per CU.
+// sample_tau_kernel is scan_kernel's one-query form for the threshold sample of a small batch,
+// with the thresholds and the work-list layout in the same launch (Section 3.3: small
+// batches are bound by launches).
 // centroid_scores_kernel is the coarse step for small query segments (the same operand
 // layout, no LDS staging); large segments go through the GEMM in pk_gemm.hip.
 #include <algorithm>

@@ -718,9 +718,11 @@ __global__ __launch_bounds__(kSelThreads) void select_final_kernel(FinalArgs a, 
     }
 }
 
-// k-th best of each query's sample -> threshold key; fewer than k real samples: no threshold
+// k-th best of each query's sample -> threshold key; fewer than k real samples: no threshold.  For samples
+// scored by a launch of their own (large batches; small ones usually take sample_tau_kernel instead).
 // WL: the workgroups then lay out the second half of the work list between them (offsets, slots, tiles:
-// small batches only), so that no launch of its own is needed for it.
+// small batches whose samples are too long for the one-launch form), so that no launch of its own is
+// needed for it.
 template <bool WL>
 __global__ __launch_bounds__(kSelThreads) void tau_kernel(SampleArgs a, WorklistArgs wa, MultiArgs ma)
 {

@@ -1,7 +1,7 @@
 // Device-side pieces of the work-list construction, shared by the kernels that run them on
 // their own (pk_worklist.hip) and by the kernels that take them along to save launches on
-// small batches (the coarse selection counts the pairs, the threshold kernel's extra
-// workgroup lays out slots and tiles).
+// small batches (the coarse selection counts the pairs; the first workgroups of the launch
+// that scores the threshold sample, or else the threshold kernel's, lay out slots and tiles).
 #pragma once
 
 #include "pk_internal.h"
