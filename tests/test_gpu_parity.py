@@ -944,7 +944,7 @@ def test_small_batch_thresholds_from_one_tile_several_tiles_and_long_samples(gpu
     x = (cent[comp] + 0.35 * rng.standard_normal((n, d))).astype(np.float32)
     qc = np.where(rng.random(1024) < 0.5, 3, rng.integers(0, nlist, 1024))
     q = (cent[qc] + 0.35 * rng.standard_normal((1024, d))).astype(np.float32)
-    for storage, metric, page_vecs in ((F32, L2, 128), (F16, IP, 128), (F32, IP, 32)):
+    for storage, metric, page_vecs in ((F32, L2, 128), (F16, IP, 128), (F32, IP, 32), (F16, L2, 1024)):
         p = Pair(x, cent, metric, storage, page_vecs=page_vecs)
         try:
             assert p.gpu.list_lengths()[3] > 50000
